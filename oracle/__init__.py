@@ -1,0 +1,118 @@
+"""ctypes front end of the CPU oracle (oracle/srigl_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports this module and
+this module never imports the product package.
+
+Every wrapper takes and returns plain numpy arrays; the arithmetic is in the C++
+file, which states, per function, the passage of the paper it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "srigl_oracle.cpp")
+_LIB = os.path.join(_HERE, "libsrigl_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (plain -O2, no vector or thread tuning)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dt):
+    return None if a is None else np.ascontiguousarray(a, dtype=dt)
+
+
+def check_fanin_mask(mask: np.ndarray, K_expected: int = -1) -> dict:
+    mask = _c(mask, np.uint8)
+    n_rows, d_in = mask.shape
+    rep = np.zeros(4, dtype=np.int32)
+    rc = _load().oracle_check_fanin_mask(_p(mask), n_rows, d_in, int(K_expected), _p(rep))
+    return {"K": int(rep[0]), "n_active": int(rep[1]), "n_bad_rows": int(rep[2]),
+            "first_bad_row": int(rep[3]), "status": int(rc)}
+
+
+def check_fanin_idx(idx: np.ndarray, d_in: int) -> dict:
+    idx = _c(idx, np.int32)
+    n_rows, K = idx.shape
+    rep = np.zeros(4, dtype=np.int32)
+    rc = _load().oracle_check_fanin_idx(_p(idx), n_rows, K, int(d_in), _p(rep))
+    return {"K": int(rep[0]), "n_active": int(rep[1]), "n_bad_rows": int(rep[2]),
+            "first_bad_row": int(rep[3]), "status": int(rc)}
+
+
+def condense(W: np.ndarray, mask: np.ndarray, K: int):
+    """W: float32 [d_out, d_in] or uint16 (bf16 bits).  Returns (W_c, idx, active);
+    raises ValueError naming the first row whose count is neither 0 nor K."""
+    assert W.dtype in (np.float32, np.uint16)
+    W = np.ascontiguousarray(W)
+    mask = _c(mask, np.uint8)
+    d_out, d_in = mask.shape
+    assert W.shape == (d_out, d_in)
+    W_c = np.zeros((d_out, K), dtype=W.dtype)
+    idx = np.zeros((d_out, K), dtype=np.int32)
+    active = np.zeros(d_out, dtype=np.int32)
+    n_active = ctypes.c_int32(0)
+    bad = ctypes.c_int32(-1)
+    rc = _load().oracle_condense(_p(W), W.dtype.itemsize, _p(mask), d_out, d_in, int(K), _p(W_c), _p(idx),
+                                 _p(active), ctypes.byref(n_active), ctypes.byref(bad))
+    if rc != 0:
+        raise ValueError("row %d does not hold 0 or %d kept weights" % (bad.value, K))
+    n = n_active.value
+    return W_c[:n].copy(), idx[:n].copy(), active[:n].copy()
+
+
+def fwd(x: np.ndarray, W_c: np.ndarray, idx: np.ndarray, active, bias, d_out: int, want_scale: bool = False):
+    """Alg. 1 + bias + scatter.  x / W_c both float32, or both uint16 (bf16 bits)."""
+    bf16 = x.dtype == np.uint16
+    assert (W_c.dtype == np.uint16) == bf16
+    x = np.ascontiguousarray(x)
+    W_c = np.ascontiguousarray(W_c)
+    idx = _c(idx, np.int32)
+    active = _c(active, np.int32)
+    bias = _c(bias, np.float32)
+    B, d_in = x.shape
+    n_active, K = W_c.shape
+    assert idx.shape == (n_active, K)
+    if active is None:
+        assert n_active == d_out
+    y = np.empty((B, d_out), dtype=np.float32)
+    scale = np.empty((B, d_out), dtype=np.float64) if want_scale else None
+    fn = _load().oracle_fwd_bf16 if bf16 else _load().oracle_fwd_f32
+    fn(_p(x), B, d_in, _p(W_c), _p(idx), _p(active), n_active, K, _p(bias), int(d_out), _p(y), _p(scale))
+    return (y, scale) if want_scale else y
+
+
+def dense_masked_fwd(x: np.ndarray, W: np.ndarray, mask: np.ndarray, bias) -> np.ndarray:
+    x = _c(x, np.float32)
+    W = _c(W, np.float32)
+    mask = _c(mask, np.uint8)
+    bias = _c(bias, np.float32)
+    B, d_in = x.shape
+    d_out = W.shape[0]
+    y = np.empty((B, d_out), dtype=np.float32)
+    _load().oracle_dense_masked_fwd_f32(_p(x), B, d_in, _p(W), _p(mask), _p(bias), d_out, _p(y))
+    return y

@@ -1,0 +1,172 @@
+// CPU oracle for the condensed constant fan-in sparse linear layer.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain-loop statement of what
+// the GPU library must compute.  It shares no code, header, table or helper with
+// the HIP path, and nothing in the product imports it: only tests/, the smoke
+// check and the benchmark's cpu_baseline leg call it.
+//
+// What each function follows (paper: arXiv 2305.02299):
+//   * oracle_dense_masked_fwd_*  -- the definition: the ordinary matrix-vector
+//     product of App. E, first equation, with W replaced by W (.) M, plus bias
+//     (Sec. 4.4 extracts "weights and bias" of the layer).
+//   * oracle_fwd_*               -- Alg. 1 (condensed forward), three nested
+//     loops b, n, k in the paper's order, output[b,n] += x[b, idx[n,k]] * w[n,k].
+//     Readings where Alg. 1 is silent: a bias is added; the output has the full
+//     layer width and the s-th stored neuron writes column active[s]; every
+//     column of a neuron that is not stored (ablated, Sec. 3.1 step 4: all of
+//     its incoming weights are pruned) holds its bias only.
+//   * oracle_condense            -- App. E, last paragraph: two n x k arrays, one
+//     with the values of the non-zeros of W and one with their column indices;
+//     Sec. 4.4: ablated neurons are dropped.  Reading: which entries are
+//     "non-zero" is decided by the mask, not by the value; columns appear in
+//     ascending order; stored neurons appear in ascending order.
+//   * oracle_check_fanin_*       -- the constant fan-in invariant (Fig. 1a, Sec.
+//     3.1): every neuron that is not ablated has exactly k unmasked weights.
+//
+// Floating point: accumulation in double in ascending k, one rounding to float
+// at the end.  Parity status: every function here is pinned by the CPU tests
+// (hand-worked fixture, dense definition by a library matmul, K == d_in special
+// case, one-hot inputs, integer-exact inputs, round trip through the mask).
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+extern "C" {
+
+// report[0]=K, [1]=n_active, [2]=n_bad_rows, [3]=first_bad_row (-1 if none)
+// A row is "bad" when its count of non-zero mask bytes is neither 0 nor K.
+// K_expected < 0: K is the count of the first non-empty row (0 if all rows empty).
+int oracle_check_fanin_mask(const uint8_t* mask, int n_rows, int d_in, int K_expected, int32_t* report) {
+    int K = K_expected;
+    if (K < 0) {
+        K = 0;
+        for (int r = 0; r < n_rows && K == 0; ++r) {
+            int c = 0;
+            for (int j = 0; j < d_in; ++j) c += mask[(size_t)r * d_in + j] != 0;
+            K = c;
+        }
+    }
+    int n_active = 0, n_bad = 0, first_bad = -1;
+    for (int r = 0; r < n_rows; ++r) {
+        int c = 0;
+        for (int j = 0; j < d_in; ++j) c += mask[(size_t)r * d_in + j] != 0;
+        if (c == 0) continue;
+        if (c == K) { ++n_active; continue; }
+        ++n_bad;
+        if (first_bad < 0) first_bad = r;
+    }
+    report[0] = K; report[1] = n_active; report[2] = n_bad; report[3] = first_bad;
+    return n_bad == 0 ? 0 : 2;
+}
+
+// Condensed-form check: every row of idx[n_rows][K] in [0, d_in) and strictly
+// ascending (hence distinct, App. E: j_alpha != j_alpha').
+int oracle_check_fanin_idx(const int32_t* idx, int n_rows, int K, int d_in, int32_t* report) {
+    int n_bad = 0, first_bad = -1;
+    for (int r = 0; r < n_rows; ++r) {
+        bool ok = true;
+        for (int k = 0; k < K; ++k) {
+            int32_t j = idx[(size_t)r * K + k];
+            if (j < 0 || j >= d_in) ok = false;
+            if (k > 0 && j <= idx[(size_t)r * K + k - 1]) ok = false;
+        }
+        if (!ok) { ++n_bad; if (first_bad < 0) first_bad = r; }
+    }
+    report[0] = K; report[1] = n_rows - n_bad; report[2] = n_bad; report[3] = first_bad;
+    return n_bad == 0 ? 0 : 2;
+}
+
+// W: d_out x d_in elements of elem_bytes bytes each (4 = fp32, 2 = bf16), copied bit for bit.
+// Outputs sized for d_out rows.  Returns 0, or 2 if some row count is neither 0 nor K
+// (then *first_bad_row names it and the outputs are not meaningful).
+int oracle_condense(const void* W, int elem_bytes, const uint8_t* mask, int d_out, int d_in, int K,
+                    void* W_c, int32_t* idx, int32_t* active, int32_t* n_active, int32_t* first_bad_row) {
+    const unsigned char* w = static_cast<const unsigned char*>(W);
+    unsigned char* wc = static_cast<unsigned char*>(W_c);
+    int slot = 0;
+    *first_bad_row = -1;
+    for (int r = 0; r < d_out; ++r) {
+        int c = 0;
+        for (int j = 0; j < d_in; ++j) c += mask[(size_t)r * d_in + j] != 0;
+        if (c == 0) continue;                       // ablated neuron: dropped
+        if (c != K) { *first_bad_row = r; *n_active = slot; return 2; }
+        active[slot] = r;
+        int t = 0;
+        for (int j = 0; j < d_in; ++j) {
+            if (mask[(size_t)r * d_in + j] == 0) continue;
+            idx[(size_t)slot * K + t] = j;
+            std::memcpy(wc + ((size_t)slot * K + t) * elem_bytes, w + ((size_t)r * d_in + j) * elem_bytes, elem_bytes);
+            ++t;
+        }
+        ++slot;
+    }
+    *n_active = slot;
+    return 0;
+}
+
+static inline float bf16_to_float(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// Alg. 1 with bias and the active-neuron scatter.  active == NULL means the s-th
+// stored neuron is column s.  bias == NULL means zero bias (Alg. 1 verbatim).
+// scale (optional, B x d_out doubles): |bias| + sum_k |w * x| per output, the size
+// of the terms that were added, against which a relative error is measured.
+static void fwd_generic(const float* xf, const uint16_t* xh, int B, int d_in,
+                        const float* wf, const uint16_t* wh, const int32_t* idx, const int32_t* active,
+                        int n_active, int K, const float* bias, int d_out, float* y, double* scale) {
+    for (int b = 0; b < B; ++b)
+        for (int r = 0; r < d_out; ++r) {
+            float bv = bias ? bias[r] : 0.0f;
+            y[(size_t)b * d_out + r] = bv;
+            if (scale) scale[(size_t)b * d_out + r] = std::fabs((double)bv);
+        }
+    for (int b = 0; b < B; ++b) {
+        for (int n = 0; n < n_active; ++n) {
+            double acc = 0.0, mag = 0.0;
+            for (int k = 0; k < K; ++k) {
+                int32_t source_idx = idx[(size_t)n * K + k];
+                double feature = xf ? (double)xf[(size_t)b * d_in + source_idx]
+                                    : (double)bf16_to_float(xh[(size_t)b * d_in + source_idx]);
+                double w = wf ? (double)wf[(size_t)n * K + k] : (double)bf16_to_float(wh[(size_t)n * K + k]);
+                acc += feature * w;
+                mag += std::fabs(feature * w);
+            }
+            int col = active ? active[n] : n;
+            double bv = bias ? (double)bias[col] : 0.0;
+            y[(size_t)b * d_out + col] = (float)(acc + bv);
+            if (scale) scale[(size_t)b * d_out + col] = mag + std::fabs(bv);
+        }
+    }
+}
+
+void oracle_fwd_f32(const float* x, int B, int d_in, const float* W_c, const int32_t* idx,
+                    const int32_t* active, int n_active, int K, const float* bias, int d_out,
+                    float* y, double* scale) {
+    fwd_generic(x, nullptr, B, d_in, W_c, nullptr, idx, active, n_active, K, bias, d_out, y, scale);
+}
+
+void oracle_fwd_bf16(const uint16_t* x, int B, int d_in, const uint16_t* W_c, const int32_t* idx,
+                     const int32_t* active, int n_active, int K, const float* bias, int d_out,
+                     float* y, double* scale) {
+    fwd_generic(nullptr, x, B, d_in, nullptr, W_c, idx, active, n_active, K, bias, d_out, y, scale);
+}
+
+// The definition: y[b][r] = bias[r] + sum_j M[r][j] W[r][j] x[b][j], all d_in terms visited.
+void oracle_dense_masked_fwd_f32(const float* x, int B, int d_in, const float* W, const uint8_t* mask,
+                                 const float* bias, int d_out, float* y) {
+    for (int b = 0; b < B; ++b)
+        for (int r = 0; r < d_out; ++r) {
+            double acc = 0.0;
+            for (int j = 0; j < d_in; ++j)
+                if (mask[(size_t)r * d_in + j] != 0)
+                    acc += (double)W[(size_t)r * d_in + j] * (double)x[(size_t)b * d_in + j];
+            y[(size_t)b * d_out + r] = (float)(acc + (bias ? (double)bias[r] : 0.0));
+        }
+}
+
+}  // extern "C"

@@ -1,0 +1,260 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests compares the oracle with itself: the expected values come
+from a hand-worked fixture (App. E's definition applied with pencil and paper),
+from numpy's float64 matmul on the dense masked matrix (App. E: the condensed and
+the ordinary product are equal for any matrix), from closed forms (one-hot
+inputs, integer-exact inputs), and from the sampler's own ground truth.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+
+
+def _dense_ref(x, W, mask, bias):
+    """Library routine: float64 matmul of the dense masked matrix (App. E, first equation)."""
+    Wm = W.astype(np.float64) * (mask != 0)
+    y = x.astype(np.float64) @ Wm.T
+    if bias is not None:
+        y = y + bias.astype(np.float64)
+    return y
+
+
+# ----------------------------------------------------------------------------- hand-worked fixture
+def test_handworked_fixture(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "appE_handworked.json")))
+    W = np.array(g["W"], np.float32)
+    mask = np.array(g["mask"], np.uint8)
+    bias = np.array(g["bias"], np.float32)
+    x = np.array(g["x"], np.float32)
+    rep = oracle.check_fanin_mask(mask)
+    assert rep == {"K": 2, "n_active": 3, "n_bad_rows": 0, "first_bad_row": -1, "status": 0}
+    W_c, idx, active = oracle.condense(W, mask, g["K"])
+    assert W_c.tolist() == g["W_c"] and idx.tolist() == g["idx"] and active.tolist() == g["active"]
+    y = oracle.fwd(x, W_c, idx, active, bias, g["d_out"])
+    assert y.tolist() == g["y"]
+    assert oracle.fwd(x, W_c, idx, active, None, g["d_out"]).tolist() == g["y_no_bias"]
+    assert oracle.dense_masked_fwd(x, W, mask, bias).tolist() == g["y"]
+    # compact output (no scatter): the s-th stored neuron is column s
+    yc = oracle.fwd(x, W_c, idx, None, bias[active], 3)
+    assert yc.tolist() == [[r[c] for c in g["active"]] for r in g["y"]]
+
+
+# ----------------------------------------------------------------------------- condense
+@pytest.mark.parametrize("d_in,d_out,K,abl,seed", [(16, 8, 3, 0.25, 1), (768, 96, 77, 0.0, 2), (3072, 40, 307, 0.3, 3),
+                                                   (64, 33, 64, 0.1, 4), (50, 7, 1, 0.0, 5)])
+def test_condense_matches_sampler_ground_truth(d_in, d_out, K, abl, seed):
+    L = si.make_layer(d_in, d_out, K, 2, ablate_frac=abl, seed=seed)
+    W_c, idx, active = oracle.condense(L.W, L.mask, K)
+    assert np.array_equal(idx, L.true_idx)
+    assert np.array_equal(active, L.true_active)
+    assert np.array_equal(W_c.view(np.uint32), si.gather_condensed(L).view(np.uint32))
+    # invariant: exactly K strictly ascending in-range columns per stored neuron
+    assert idx.shape == (L.n_active, K)
+    assert (idx >= 0).all() and (idx < d_in).all()
+    if K > 1:
+        assert (np.diff(idx, axis=1) > 0).all()
+    # round trip: scattering back gives W (.) M bit for bit
+    back = np.zeros_like(L.W)
+    back[active[:, None], idx] = W_c
+    assert np.array_equal(back.view(np.uint32), np.where(L.mask != 0, L.W, np.float32(0)).view(np.uint32))
+
+
+def test_condense_is_mask_driven_and_bit_exact():
+    """A kept weight that is -0.0, +0.0, NaN or inf is copied bit for bit and counts toward K."""
+    L = si.make_layer(32, 6, 4, 1, seed=7)
+    W = L.W.copy()
+    specials = np.array([0x80000000, 0x00000000, 0x7FC00123, 0xFF800000], np.uint32).view(np.float32)
+    W[0, L.true_idx[0]] = specials
+    W_c, idx, active = oracle.condense(W, L.mask, 4)
+    assert np.array_equal(W_c[0].view(np.uint32), specials.view(np.uint32))
+    assert np.array_equal(idx, L.true_idx)
+    # an unmasked non-zero value is ignored
+    assert (L.mask[1] == 0).sum() > 0
+
+
+def test_condense_bf16_bit_copy():
+    L = si.make_layer(64, 10, 9, 1, dtype="bf16", ablate_frac=0.2, seed=8)
+    W_c, idx, active = oracle.condense(L.W_bf16, L.mask, 9)
+    assert W_c.dtype == np.uint16
+    assert np.array_equal(W_c, L.W_bf16[L.true_active[:, None], L.true_idx])
+    assert np.array_equal(idx, L.true_idx) and np.array_equal(active, L.true_active)
+
+
+def test_condense_rejects_wrong_fanin():
+    L = si.make_layer(32, 6, 4, 1, seed=9)
+    m = L.mask.copy()
+    j = int(np.flatnonzero(m[3] == 0)[0])
+    m[3, j] = 1
+    with pytest.raises(ValueError, match="row 3"):
+        oracle.condense(L.W, m, 4)
+
+
+# ----------------------------------------------------------------------------- check_fanin
+def test_check_fanin_accepts_generated_and_flags_single_flip():
+    L = si.make_layer(96, 20, 10, 1, ablate_frac=0.25, seed=11)
+    rep = oracle.check_fanin_mask(L.mask)
+    assert rep == {"K": 10, "n_active": 15, "n_bad_rows": 0, "first_bad_row": -1, "status": 0}
+    assert oracle.check_fanin_mask(L.mask, 10)["status"] == 0
+    for r in (int(L.true_active[2]), int(L.true_active[-1])):
+        for newval, col in ((1, int(np.flatnonzero(L.mask[r] == 0)[0])), (0, int(np.flatnonzero(L.mask[r])[0]))):
+            m = L.mask.copy()
+            m[r, col] = newval
+            rep = oracle.check_fanin_mask(m, 10)
+            assert rep["n_bad_rows"] == 1 and rep["first_bad_row"] == r and rep["status"] == 2
+            assert rep["n_active"] == 14
+    # any non-zero byte counts as kept
+    m = L.mask.copy() * 200
+    assert oracle.check_fanin_mask(m, 10)["status"] == 0
+    # wrong expectation: every stored row is bad
+    rep = oracle.check_fanin_mask(L.mask, 9)
+    assert rep["n_bad_rows"] == 15 and rep["first_bad_row"] == int(L.true_active[0])
+    # all rows ablated
+    z = np.zeros((4, 8), np.uint8)
+    assert oracle.check_fanin_mask(z) == {"K": 0, "n_active": 0, "n_bad_rows": 0, "first_bad_row": -1, "status": 0}
+
+
+def test_check_fanin_idx_mode():
+    L = si.make_layer(96, 20, 10, 1, seed=12)
+    assert oracle.check_fanin_idx(L.true_idx, 96)["status"] == 0
+    bad = L.true_idx.copy()
+    bad[5, 3] = bad[5, 2]                    # duplicate -> not strictly ascending
+    rep = oracle.check_fanin_idx(bad, 96)
+    assert rep["n_bad_rows"] == 1 and rep["first_bad_row"] == 5
+    bad = L.true_idx.copy()
+    bad[7, -1] = 96                          # out of range
+    assert oracle.check_fanin_idx(bad, 96)["first_bad_row"] == 7
+    bad = L.true_idx.copy()
+    bad[0, 0] = -1
+    assert oracle.check_fanin_idx(bad, 96)["first_bad_row"] == 0
+    bad = L.true_idx.copy()
+    bad[9, [1, 2]] = bad[9, [2, 1]]          # swapped -> descending pair
+    assert oracle.check_fanin_idx(bad, 96)["first_bad_row"] == 9
+
+
+# ----------------------------------------------------------------------------- forward
+@pytest.mark.parametrize("d_in,d_out,K,B,abl,seed", [(16, 8, 3, 3, 0.25, 21), (768, 64, 77, 4, 0.0, 22),
+                                                     (3072, 24, 307, 2, 0.3, 23), (40, 9, 40, 5, 0.0, 24)])
+def test_fwd_equals_dense_masked_product(d_in, d_out, K, B, abl, seed):
+    """App. E: the condensed product equals the ordinary product for any matrix."""
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=seed)
+    W_c, idx, active = oracle.condense(L.W, L.mask, K)
+    y = oracle.fwd(L.x, W_c, idx, active, L.bias, d_out)
+    ref = _dense_ref(L.x, L.W, L.mask, L.bias)
+    # float64 sums of <= 3072 terms rounded once to fp32: at most one fp32 ulp apart
+    assert np.array_equal(y, ref.astype(np.float32)) or np.max(np.abs(y - ref) / np.maximum(np.abs(ref), 1e-30)) < 2.0 ** -23
+    yd = oracle.dense_masked_fwd(L.x, L.W, L.mask, L.bias)
+    assert np.max(np.abs(yd.astype(np.float64) - ref)) <= np.max(np.abs(ref)) * 2.0 ** -23
+    # asymmetric in every operand: a transposed or mis-indexed operand cannot pass
+    assert not np.allclose(y, _dense_ref(L.x, L.W, L.mask, None).astype(np.float32))
+
+
+def test_fwd_dense_special_case_K_equals_d_in():
+    """K = d_in with identity indices is an ordinary dense linear layer."""
+    rng = np.random.default_rng(31)
+    B, d_in, d_out = 5, 24, 7
+    W = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    x = rng.standard_normal((B, d_in)).astype(np.float32)
+    bias = rng.standard_normal(d_out).astype(np.float32)
+    idx = np.tile(np.arange(d_in, dtype=np.int32), (d_out, 1))
+    y = oracle.fwd(x, W, idx, None, bias, d_out)
+    ref = x.astype(np.float64) @ W.astype(np.float64).T + bias
+    assert np.max(np.abs(y - ref)) <= np.max(np.abs(ref)) * 2.0 ** -23
+
+
+def test_fwd_ablated_columns_hold_bias_bits():
+    L = si.make_layer(64, 20, 6, 3, ablate_frac=0.4, seed=33)
+    W_c, idx, active = oracle.condense(L.W, L.mask, 6)
+    y = oracle.fwd(L.x, W_c, idx, active, L.bias, 20)
+    ablated = np.setdiff1d(np.arange(20), active)
+    assert len(ablated) == 8
+    for b in range(3):
+        assert np.array_equal(y[b, ablated].view(np.uint32), L.bias[ablated].view(np.uint32))
+    y0 = oracle.fwd(L.x, W_c, idx, active, None, 20)
+    assert (y0[:, ablated] == 0).all()
+
+
+def test_fwd_one_hot_input_reads_single_weight():
+    """x = e_j: y[n] = bias[n] + W[n][j] M[n][j], one rounding."""
+    L = si.make_layer(48, 12, 5, 1, ablate_frac=0.25, seed=34)
+    W_c, idx, active = oracle.condense(L.W, L.mask, 5)
+    for j in (0, 17, 47):
+        x = np.zeros((1, 48), np.float32)
+        x[0, j] = 1.0
+        y = oracle.fwd(x, W_c, idx, active, L.bias, 12)
+        exp = (L.bias.astype(np.float64) + L.W[:, j].astype(np.float64) * (L.mask[:, j] != 0)).astype(np.float32)
+        assert np.array_equal(y[0].view(np.uint32), exp.view(np.uint32))
+
+
+def test_fwd_small_integers_exact():
+    """Integer operands: every partial sum is an integer below 2^24, so the result is exact."""
+    rng = np.random.default_rng(35)
+    B, d_in, d_out, K = 4, 100, 10, 30
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=0.2, seed=35)
+    W = rng.integers(-8, 9, size=(d_out, d_in)).astype(np.float32)
+    x = rng.integers(-8, 9, size=(B, d_in)).astype(np.float32)
+    bias = rng.integers(-8, 9, size=d_out).astype(np.float32)
+    W_c, idx, active = oracle.condense(W, L.mask, K)
+    y = oracle.fwd(x, W_c, idx, active, bias, d_out)
+    exp = x.astype(np.int64) @ (W.astype(np.int64) * L.mask).T + bias.astype(np.int64)
+    assert np.array_equal(y.astype(np.int64), exp) and np.array_equal(y, exp.astype(np.float32))
+
+
+def test_fwd_any_index_order_and_duplicates():
+    """Alg. 1 is a plain sum over k: permuting (w, idx) pairs within a row changes nothing
+    beyond rounding, and a repeated index contributes twice."""
+    L = si.make_layer(64, 8, 7, 3, seed=36)
+    W_c, idx, active = oracle.condense(L.W, L.mask, 7)
+    rng = np.random.default_rng(36)
+    perm = np.stack([rng.permutation(7) for _ in range(8)])
+    Wp = np.take_along_axis(W_c, perm, 1)
+    ip = np.take_along_axis(idx, perm, 1)
+    y = oracle.fwd(L.x, W_c, idx, active, L.bias, 8)
+    yp = oracle.fwd(L.x, Wp, ip, active, L.bias, 8)
+    assert np.max(np.abs(y - yp)) < 1e-6
+    dup_idx = idx.copy()
+    dup_idx[:, 1] = dup_idx[:, 0]
+    yd = oracle.fwd(L.x, W_c, dup_idx, active, None, 8)
+    exp = np.einsum("nk,bnk->bn", W_c.astype(np.float64), L.x.astype(np.float64)[:, dup_idx])
+    assert np.max(np.abs(yd - exp)) < 1e-5
+
+
+def test_fwd_bf16_widens_exactly():
+    L = si.make_layer(128, 16, 13, 3, dtype="bf16", ablate_frac=0.25, seed=37)
+    W_c, idx, active = oracle.condense(L.W_bf16, L.mask, 13)
+    y = oracle.fwd(L.x_bf16, W_c, idx, active, L.bias, 16)
+    ref = _dense_ref(L.x, L.W, L.mask, L.bias)          # L.W / L.x are the exactly widened values
+    assert np.max(np.abs(y - ref)) <= np.max(np.abs(ref)) * 2.0 ** -23
+    # and identical to the fp32 entry point on the widened values
+    y32 = oracle.fwd(L.x, si.bf16_bits_to_f32(W_c), idx, active, L.bias, 16)
+    assert np.array_equal(y, y32)
+
+
+def test_fwd_scale_is_sum_of_term_magnitudes():
+    L = si.make_layer(40, 6, 5, 2, ablate_frac=0.34, seed=38)
+    W_c, idx, active = oracle.condense(L.W, L.mask, 5)
+    y, S = oracle.fwd(L.x, W_c, idx, active, L.bias, 6, want_scale=True)
+    exp = np.abs(L.x.astype(np.float64)) @ (np.abs(L.W.astype(np.float64)) * L.mask).T + np.abs(L.bias.astype(np.float64))
+    assert np.allclose(S, exp, rtol=1e-12, atol=0)
+    assert (S >= np.abs(y) * (1 - 1e-6)).all()
+
+
+def test_fwd_degenerate_shapes():
+    # B = 0
+    L = si.make_layer(16, 4, 3, 0, seed=39)
+    W_c, idx, active = oracle.condense(L.W, L.mask, 3)
+    assert oracle.fwd(L.x, W_c, idx, active, L.bias, 4).shape == (0, 4)
+    # n_active = 0: bias broadcast
+    L = si.make_layer(16, 4, 3, 2, ablate_frac=1.0, seed=40)
+    W_c, idx, active = oracle.condense(L.W, L.mask, 3)
+    assert W_c.shape == (0, 3)
+    y = oracle.fwd(L.x, W_c, idx, active, L.bias, 4)
+    assert np.array_equal(y, np.tile(L.bias, (2, 1)))
+    # K = 0
+    y = oracle.fwd(L.x, np.zeros((4, 0), np.float32), np.zeros((4, 0), np.int32), None, L.bias, 4)
+    assert np.array_equal(y, np.tile(L.bias, (2, 1)))
