@@ -1,0 +1,160 @@
+/* srigl.h -- C ABI of the condensed constant fan-in sparse linear layer for AMD MI355X (gfx950).
+ *
+ * The layer is the inference form of a network trained with SRigL (arXiv 2305.02299): every
+ * neuron that is not ablated keeps exactly K incoming weights (constant fan-in, Fig. 1a, Sec. 3.1),
+ * so the sparse weight matrix is stored as two dense [n_active][K] arrays, the kept values W_c and
+ * their column indices idx (App. E), and the forward pass is the triple loop of Alg. 1:
+ *
+ *     y[b][active[s]] = bias[active[s]] + sum_{k<K} W_c[s][k] * x[b][ idx[s][k] ]
+ *     y[b][r]         = bias[r]                      for every neuron r that is not stored (ablated)
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer on the current HIP device unless marked "host".
+ *   - The caller owns every buffer.  The library never allocates, frees or keeps a pointer.
+ *   - All matrices are row-major and dense: x[B][d_in], y[B][d_out], W[d_out][d_in],
+ *     mask[d_out][d_in], W_c[rows][K], idx[rows][K].
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ *     the call returns without synchronising.
+ *   - The return value reports what the host can see (NULL pointers, negative sizes, K > d_in,
+ *     workspace too small, launch failure).  What only the data can show (a row with a wrong
+ *     fan-in, an index out of range, too few output rows) is written to the device-side
+ *     srigl_report, which the caller reads after its own synchronisation.
+ *   - Empty problems (B == 0, d_out == 0, n_rows == 0) are valid and do nothing; K == 0 or
+ *     n_active == 0 makes the forward pass a bias broadcast.
+ *   - Calls that share a workspace or an output buffer must be ordered by the caller (same stream
+ *     or explicit dependencies).
+ */
+#ifndef SRIGL_H_
+#define SRIGL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SRIGL_OK = 0,
+    SRIGL_ERR_INVALID_ARG = 1, /* NULL where data is required, negative size, K > d_in, bad enum   */
+    SRIGL_ERR_FANIN = 2,       /* device-side: some row holds neither 0 nor K kept weights          */
+    SRIGL_ERR_CAPACITY = 3,    /* workspace too small (host) / more stored rows than cap_rows (dev) */
+    SRIGL_ERR_INDEX_RANGE = 4, /* device-side: an index outside [0, d_in) or a row not ascending    */
+    SRIGL_ERR_UNSUPPORTED = 5, /* dtype combination or algorithm not available for these sizes      */
+    SRIGL_ERR_HIP = 6          /* a HIP call failed                                                 */
+} srigl_status;
+
+typedef enum { SRIGL_F32 = 0, SRIGL_BF16 = 1 } srigl_dtype;
+
+/* Forward algorithms.  AUTO picks by batch size and shape. */
+typedef enum {
+    SRIGL_FWD_AUTO = 0,
+    SRIGL_FWD_GENERIC = 1,  /* one thread per output, activations read from global memory; any index order */
+    SRIGL_FWD_KLANE = 2,    /* small batch: lanes split one neuron's K terms, cross-lane reduction          */
+    SRIGL_FWD_ROWLANE = 3   /* batched: lanes are batch rows, activation tile transposed in LDS             */
+} srigl_fwd_algo;
+
+/* 32 bytes, lives in device memory, written by check_fanin / condense. */
+typedef struct {
+    int32_t K;             /* fan-in that was checked against (given, or inferred)        */
+    int32_t n_active;      /* rows holding exactly K kept weights (mask mode) / valid rows */
+    int32_t n_bad_rows;    /* rows that violate the invariant                              */
+    int32_t first_bad_row; /* smallest such row, -1 if none                                */
+    int32_t status;        /* SRIGL_OK, SRIGL_ERR_FANIN, SRIGL_ERR_INDEX_RANGE, SRIGL_ERR_CAPACITY */
+    int32_t reserved[3];
+} srigl_report;
+
+/* Bytes of device scratch that check_fanin / condense need for n_rows rows. */
+size_t srigl_workspace_bytes(int32_t n_rows);
+
+/* Number of uint16 entries per stored row in the optional `seg` table: d_in/64 rounded up, plus 1. */
+int32_t srigl_seg_stride(int32_t d_in);
+
+/* srigl_check_fanin -- the constant fan-in invariant (Fig. 1a; Sec. 3.1: every neuron that is not
+ * ablated has the same number of unmasked incoming weights).
+ *
+ * Mask mode (idx == NULL): mask[n_rows][d_in], uint8, non-zero = kept.  A row is valid when it
+ *   holds 0 (ablated) or K kept weights.  K_expected < 0: K is taken from the first non-empty row.
+ * Index mode (mask == NULL): idx[n_rows][K_expected] must lie in [0, d_in) and be strictly
+ *   ascending within each row (distinct columns, App. E).  If seg != NULL it receives, per row,
+ *   srigl_seg_stride(d_in) uint16 entries: seg[r][c] = number of indices of row r below 64*c
+ *   (the forward pass uses it to walk a row chunk by chunk); rows that fail the check get
+ *   all-zero entries so that a later forward pass reads nothing for them.
+ * Exactly one of mask / idx must be non-NULL.  workspace: srigl_workspace_bytes(n_rows) bytes.
+ * report_dev receives {K, n_active, n_bad_rows, first_bad_row, status}.
+ */
+srigl_status srigl_check_fanin(const uint8_t* mask, const int32_t* idx, int32_t n_rows, int32_t d_in,
+                               int32_t K_expected, uint16_t* seg, void* workspace, size_t workspace_bytes,
+                               srigl_report* report_dev, void* stream);
+
+/* srigl_condense -- dense weights plus constant fan-in mask to the condensed form (App. E, last
+ * paragraph: one [n][k] array of values, one of column indices; Sec. 4.4: ablated neurons and
+ * masked weights are removed).
+ *
+ * W[d_out][d_in] of w_dtype, mask[d_out][d_in] uint8.  For the s-th row r (ascending) that holds
+ * exactly K kept weights: active[s] = r, idx[s][0..K) = its kept columns ascending,
+ * W_c[s][t] = W[r][idx[s][t]] copied bit for bit (the mask decides, not the value).
+ * Rows s >= n_active of the outputs are left untouched.  cap_rows = rows available in W_c / idx /
+ * active / seg; if n_active > cap_rows only the first cap_rows stored rows are written and
+ * report.status = SRIGL_ERR_CAPACITY.  Rows whose count is neither 0 nor K are skipped and
+ * reported (status = SRIGL_ERR_FANIN); the other outputs are then not meaningful.
+ * seg (optional, may be NULL): [cap_rows][srigl_seg_stride(d_in)] uint16 as in check_fanin.
+ * K > 65535 with seg != NULL is SRIGL_ERR_UNSUPPORTED.
+ */
+srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* mask, int32_t d_out,
+                            int32_t d_in, int32_t K, int32_t cap_rows, void* W_c, int32_t* idx,
+                            int32_t* active, uint16_t* seg, void* workspace, size_t workspace_bytes,
+                            srigl_report* report_dev, void* stream);
+
+/* srigl_condensed_linear_fwd -- Alg. 1 (condensed linear layer forward) plus bias and the scatter of
+ * stored neurons to their columns.
+ *
+ * x[B][d_in] of x_dtype; W_c[n_active][K] of w_dtype (both F32 or both BF16); idx[n_active][K]
+ * int32 in [0, d_in) (not checked here: validate once with srigl_check_fanin in index mode);
+ * active[n_active] strictly ascending columns in [0, d_out), or NULL when n_active == d_out
+ * (the s-th stored neuron is column s); bias[d_out] fp32 or NULL (= zero, Alg. 1 verbatim);
+ * y[B][d_out] fp32, fully overwritten.  Accumulation is fp32 (bf16 products are exact in fp32).
+ * seg: the table written by condense / check_fanin for these idx, or NULL.  With seg == NULL, or
+ * rows that are not ascending, only algorithms that do not depend on the order are used.
+ * Out-of-range entries of `active` are skipped, never written.
+ */
+srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
+                                        const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
+                                        const int32_t* active, int32_t n_active, int32_t K,
+                                        const float* bias, int32_t d_out, float* y,
+                                        const uint16_t* seg, void* stream);
+
+/* Launch-shape knobs of the forward kernels (host struct).  0 in a field = the library's default.
+ * Values the kernels cannot run are rejected with SRIGL_ERR_UNSUPPORTED, never launched. */
+typedef struct {
+    int32_t rows_per_lane;    /* ROWLANE: batch rows per lane, 1, 2 or 4 (batch tile = 64 * rows_per_lane) */
+    int32_t waves;            /* ROWLANE: wavefronts per workgroup, 1..16                                  */
+    int32_t neurons_per_wave; /* ROWLANE: stored neurons accumulated per wavefront, 1..8                   */
+    int32_t chunk_cols;       /* ROWLANE: activation columns per LDS tile, multiple of 64                  */
+    int32_t lanes_per_neuron; /* KLANE: lanes that share one neuron, power of two 1..64                    */
+    int32_t rows_per_block;   /* KLANE: batch rows staged per workgroup, 1, 2, 4 or 8                      */
+    int32_t reserved[2];
+} srigl_fwd_tuning;
+
+/* Same, with the algorithm and launch shape forced (for tests and measurements).  tuning may be
+ * NULL.  SRIGL_ERR_UNSUPPORTED if the algorithm cannot run these sizes (e.g. ROWLANE without seg
+ * when d_in does not fit one LDS tile). */
+srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
+                                             const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
+                                             const int32_t* active, int32_t n_active, int32_t K,
+                                             const float* bias, int32_t d_out, float* y,
+                                             const uint16_t* seg, srigl_fwd_algo algo,
+                                             const srigl_fwd_tuning* tuning, void* stream);
+
+/* An empty kernel on `stream`: the dispatch floor against which microsecond-scale calls are read. */
+srigl_status srigl_launch_empty(void* stream);
+
+/* Plain device copy kernel of n_bytes (multiple of 16), the reference for bandwidth counters. */
+srigl_status srigl_copy_bytes(const void* src, void* dst, size_t n_bytes, void* stream);
+
+const char* srigl_status_str(srigl_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SRIGL_H_ */

@@ -1,0 +1,159 @@
+"""Thin ctypes binding of libsrigl.so: argument marshalling only.
+
+Function names and argument order follow include/srigl.h.  Every array argument is a
+torch tensor on the GPU (PyTorch is used for device memory and streams, nothing else);
+the binding passes its data pointer and the current HIP stream.  All arithmetic runs
+in the library's HIP kernels.  If the library is missing the import of this module
+fails: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsrigl.so")
+
+OK, ERR_INVALID_ARG, ERR_FANIN, ERR_CAPACITY, ERR_INDEX_RANGE, ERR_UNSUPPORTED, ERR_HIP = range(7)
+F32, BF16 = 0, 1
+FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE = range(4)
+
+EXPORTS = (
+    "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense",
+    "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
+    "srigl_copy_bytes", "srigl_status_str",
+)
+
+
+class SriglError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s: %s (status %d)" % (where, status_str(status), status))
+
+
+class FwdTuning(ctypes.Structure):
+    _fields_ = [("rows_per_lane", ctypes.c_int32), ("waves", ctypes.c_int32), ("neurons_per_wave", ctypes.c_int32),
+                ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32), ("rows_per_block", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libsrigl.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(hipcc --offload-arch=gfx950) first; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lib.srigl_workspace_bytes.restype = sz
+    lib.srigl_workspace_bytes.argtypes = [i32]
+    lib.srigl_seg_stride.restype = i32
+    lib.srigl_seg_stride.argtypes = [i32]
+    lib.srigl_check_fanin.restype = ctypes.c_int
+    lib.srigl_check_fanin.argtypes = [vp, vp, i32, i32, i32, vp, vp, sz, vp, vp]
+    lib.srigl_condense.restype = ctypes.c_int
+    lib.srigl_condense.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.srigl_condensed_linear_fwd.restype = ctypes.c_int
+    lib.srigl_condensed_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32, vp, vp, vp]
+    lib.srigl_condensed_linear_fwd_algo.restype = ctypes.c_int
+    lib.srigl_condensed_linear_fwd_algo.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32,
+                                                    vp, vp, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
+    lib.srigl_launch_empty.restype = ctypes.c_int
+    lib.srigl_launch_empty.argtypes = [vp]
+    lib.srigl_copy_bytes.restype = ctypes.c_int
+    lib.srigl_copy_bytes.argtypes = [vp, vp, sz, vp]
+    lib.srigl_status_str.restype = ctypes.c_char_p
+    lib.srigl_status_str.argtypes = [ctypes.c_int]
+    return lib
+
+
+lib = _load()
+
+
+def status_str(status: int) -> str:
+    return lib.srigl_status_str(int(status)).decode()
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype in (torch.bfloat16, torch.uint16, torch.int16):
+        return BF16   # 16-bit containers carry bf16 bit patterns
+    raise TypeError("unsupported element type %s" % t.dtype)
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise SriglError(status, where)
+
+
+def srigl_workspace_bytes(n_rows: int) -> int:
+    return int(lib.srigl_workspace_bytes(int(n_rows)))
+
+
+def srigl_seg_stride(d_in: int) -> int:
+    return int(lib.srigl_seg_stride(int(d_in)))
+
+
+def new_workspace(n_rows: int, device="cuda"):
+    return torch.empty(srigl_workspace_bytes(n_rows), dtype=torch.uint8, device=device)
+
+
+def new_report(device="cuda"):
+    return torch.full((8,), -7, dtype=torch.int32, device=device)
+
+
+def read_report(report) -> dict:
+    """Synchronising read of the 32-byte device report."""
+    r = report.cpu().tolist()
+    return {"K": r[0], "n_active": r[1], "n_bad_rows": r[2], "first_bad_row": r[3], "status": r[4]}
+
+
+def srigl_check_fanin(mask, idx, n_rows, d_in, K_expected, seg, workspace, report):
+    st = lib.srigl_check_fanin(_ptr(mask), _ptr(idx), int(n_rows), int(d_in), int(K_expected), _ptr(seg), _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(), _ptr(report), _stream())
+    _check(st, "srigl_check_fanin")
+
+
+def srigl_condense(W, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, workspace, report):
+    st = lib.srigl_condense(_ptr(W), _dtype_code(W), _ptr(mask), int(d_out), int(d_in), int(K), int(cap_rows), _ptr(W_c),
+                            _ptr(idx), _ptr(active), _ptr(seg), _ptr(workspace),
+                            0 if workspace is None else workspace.numel() * workspace.element_size(), _ptr(report), _stream())
+    _check(st, "srigl_condense")
+
+
+def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, d_out, y, seg=None, algo=None, tuning=None):
+    """algo None: the library's own entry point; otherwise the forced-algorithm entry point."""
+    if algo is None and tuning is None:
+        st = lib.srigl_condensed_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
+                                            _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
+                                            _stream())
+    else:
+        tn = None
+        if tuning is not None:
+            tn = FwdTuning()
+            for k, v in tuning.items():
+                setattr(tn, k, int(v))
+        st = lib.srigl_condensed_linear_fwd_algo(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
+                                                 _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
+                                                 int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
+    _check(st, "srigl_condensed_linear_fwd")
+
+
+def srigl_launch_empty():
+    _check(lib.srigl_launch_empty(_stream()), "srigl_launch_empty")
+
+
+def srigl_copy_bytes(src, dst, n_bytes):
+    _check(lib.srigl_copy_bytes(_ptr(src), _ptr(dst), int(n_bytes), _stream()), "srigl_copy_bytes")

@@ -1,0 +1,40 @@
+// Internal declarations shared by the HIP translation units of libsrigl (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "srigl.h"
+
+namespace srigl {
+
+constexpr int kWave = 64;              // CDNA wavefront width
+constexpr int kSegCols = 64;           // columns per entry of the seg table
+constexpr size_t kLdsMax = 160 * 1024; // LDS per workgroup on gfx950
+
+struct FwdArgs {
+    const void* x;
+    int32_t x_bf16;
+    int32_t B, d_in;
+    const void* W_c;
+    const int32_t* idx;
+    const int32_t* active;
+    int32_t n_active, K;
+    const float* bias;
+    int32_t d_out;
+    float* y;
+    const uint16_t* seg;
+    int32_t seg_stride;
+};
+
+// Each returns SRIGL_OK, SRIGL_ERR_UNSUPPORTED (cannot run these sizes) or SRIGL_ERR_HIP.
+srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st);
+srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
+srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
+bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
+
+inline srigl_status hip_ok(hipError_t e) { return e == hipSuccess ? SRIGL_OK : SRIGL_ERR_HIP; }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+}  // namespace srigl

@@ -1,0 +1,45 @@
+"""The C-ABI library loads without a GPU and exports every function include/srigl.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "srigl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(srigl_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert {"srigl_condense", "srigl_condensed_linear_fwd", "srigl_check_fanin"} <= set(names)
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2305_02299_amd", "libsrigl.so"))
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_lists_the_same_names():
+    from paper_2305_02299_amd import binding
+    assert sorted(binding.EXPORTS) == _declared()
+    for n in binding.EXPORTS:
+        assert hasattr(binding.lib, n)
+
+
+def test_host_only_entry_points():
+    from paper_2305_02299_amd import binding
+    assert binding.srigl_seg_stride(768) == 13 and binding.srigl_seg_stride(1) == 2 and binding.srigl_seg_stride(0) == 1
+    assert binding.srigl_workspace_bytes(3072) >= 2 * 4 * 3072
+    assert binding.status_str(0) == "ok" and "fan" in binding.status_str(2).lower() or "K" in binding.status_str(2)
+    s = ctypes.sizeof(binding.FwdTuning)
+    assert s == 32
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2305_02299_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src, os.path.join(dirpath, f)

@@ -1,0 +1,254 @@
+"""GPU parity, floating-point side: srigl_condensed_linear_fwd against the CPU oracle (Alg. 1).
+
+Gate: |y_gpu - y_ref| <= tol * max(|y_ref|, S) per element, S = |bias| + sum_k |w x| from the
+oracle; tol = 1e-5 for fp32 storage, 1e-2 for bf16 storage (fp32 accumulate).  Columns of ablated
+neurons and integer-valued problems are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from gpu_util import TOL_BF16, TOL_F32, dev, gate, host, oracle_condensed, oracle_seg
+from paper_2305_02299_amd import binding as B_
+
+pytestmark = pytest.mark.gpu
+
+ALGOS = {"auto": None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE}
+GUARD = 1024
+
+
+def run_gpu(L, W_c, idx, active, bias, algo=None, tuning=None, seg=True, x=None):
+    """Runs the library on device copies; y sits between two guard zones that must stay untouched."""
+    xsrc = x if x is not None else (L.x_bf16 if L.dtype == "bf16" else L.x)
+    Bn, d_in, d_out = xsrc.shape[0], L.d_in, L.d_out
+    n_active, K = W_c.shape
+    flat = torch.full((Bn * d_out + 2 * GUARD,), 777.0, dtype=torch.float32, device="cuda")
+    y = flat[GUARD:GUARD + Bn * d_out].view(Bn, d_out)
+    sg = dev(oracle_seg(idx, d_in)) if (seg and n_active and K) else None
+    B_.srigl_condensed_linear_fwd(dev(xsrc), Bn, d_in, dev(W_c), dev(idx), dev(active), n_active, K, dev(bias), d_out, y,
+                                  sg, algo=algo, tuning=tuning)
+    torch.cuda.synchronize()
+    out = flat.cpu().numpy()
+    assert (out[:GUARD] == 777.0).all() and (out[GUARD + Bn * d_out:] == 777.0).all(), "write outside y"
+    return out[GUARD:GUARD + Bn * d_out].reshape(Bn, d_out).copy()
+
+
+def check_layer(L, algo, tuning=None, bias=True, seg=True):
+    W_c, idx, active = oracle_condensed(L)
+    bias_v = L.bias if bias else None
+    xsrc = L.x_bf16 if L.dtype == "bf16" else L.x
+    y_ref, S = oracle.fwd(xsrc, W_c, idx, active, bias_v, L.d_out, want_scale=True)
+    act_arg = None if len(active) == L.d_out else active
+    try:
+        y = run_gpu(L, W_c, idx, act_arg, bias_v, algo, tuning, seg)
+    except B_.SriglError as e:
+        if e.status == B_.ERR_UNSUPPORTED and algo is not None:
+            pytest.skip("algorithm does not run these sizes")
+        raise
+    worst = gate(y, y_ref, S, TOL_BF16 if L.dtype == "bf16" else TOL_F32)
+    ablated = np.setdiff1d(np.arange(L.d_out), active)
+    if len(ablated):
+        exp = (L.bias if bias else np.zeros(L.d_out, np.float32))[ablated]
+        assert np.array_equal(y[:, ablated].view(np.uint32), np.tile(exp, (L.B, 1)).view(np.uint32)), "ablated column != bias"
+    return worst
+
+
+# ----------------------------------------------------------------------------- the named configurations
+@pytest.mark.parametrize("algo", list(ALGOS))
+@pytest.mark.parametrize("cfg,B", [("c1", 1), ("c2", 256), ("c3", 1), ("c3", 256)])
+def test_named_configs(cfg, B, algo):
+    L = si.config(cfg, B=B)
+    worst = check_layer(L, ALGOS[algo])
+    print("%s B=%d %s: worst err/scale %.2e" % (cfg, B, algo, worst))
+    assert worst < 2e-6   # fp32 accumulation of <= 307 terms stays far inside the gate
+
+
+def test_c2_through_gpu_condense():
+    """Config 2 end to end on the GPU: dense W + mask -> srigl_condense -> forward."""
+    from paper_2305_02299_amd import condense_layer
+    L = si.config("c2")
+    layer = condense_layer(dev(L.W), dev(L.mask), L.K, dev(L.bias))
+    W_c, idx, active = oracle_condensed(L)
+    assert layer.n_active == 3072 and layer.active is None
+    assert np.array_equal(host(layer.idx), idx) and np.array_equal(host(layer.W_c).view(np.uint32), W_c.view(np.uint32))
+    y = host(layer.forward(dev(L.x)))
+    y_ref, S = oracle.fwd(L.x, W_c, idx, active, L.bias, L.d_out, want_scale=True)
+    gate(y, y_ref, S, TOL_F32)
+    # same call twice: identical bits
+    y2 = host(layer.forward(dev(L.x)))
+    assert np.array_equal(y.view(np.uint32), y2.view(np.uint32))
+
+
+# ----------------------------------------------------------------------------- ragged shapes, every algorithm
+RAGGED = [
+    # d_in, d_out, K, B, ablate
+    (16, 8, 3, 3, 0.25),
+    (50, 7, 1, 5, 0.0),
+    (77, 33, 20, 70, 0.1),
+    (1001, 130, 333, 65, 0.5),
+    (257, 5, 257, 2, 0.0),
+    (768, 100, 77, 130, 0.0),
+    (768, 3072, 8, 16, 0.0),
+    (3072, 200, 615, 64, 0.05),
+    (640, 1000, 39, 33, 0.9),
+]
+
+
+@pytest.mark.parametrize("algo", list(ALGOS))
+@pytest.mark.parametrize("d_in,d_out,K,B,abl", RAGGED)
+def test_ragged_shapes(d_in, d_out, K, B, abl, algo):
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=200 + d_in + B)
+    check_layer(L, ALGOS[algo])
+
+
+@pytest.mark.parametrize("algo", list(ALGOS))
+def test_no_bias_and_no_seg(algo):
+    L = si.make_layer(512, 96, 40, 67, ablate_frac=0.2, seed=31)
+    check_layer(L, ALGOS[algo], bias=False)
+    check_layer(L, ALGOS[algo], seg=False)
+
+
+@pytest.mark.parametrize("tuning", [
+    {"rows_per_lane": 1, "waves": 4, "neurons_per_wave": 1, "chunk_cols": 64},
+    {"rows_per_lane": 1, "waves": 16, "neurons_per_wave": 8, "chunk_cols": 256},
+    {"rows_per_lane": 2, "waves": 8, "neurons_per_wave": 3, "chunk_cols": 128},
+    {"rows_per_lane": 2, "waves": 2, "neurons_per_wave": 6, "chunk_cols": 256},
+    {"rows_per_lane": 4, "waves": 8, "neurons_per_wave": 2, "chunk_cols": 128},
+    {"rows_per_lane": 4, "waves": 16, "neurons_per_wave": 4, "chunk_cols": 64},
+])
+def test_rowlane_launch_shapes(tuning):
+    for (d_in, d_out, K, B, abl) in ((768, 300, 77, 300, 0.1), (3072, 96, 307, 70, 0.3), (1001, 64, 100, 257, 0.0)):
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=77)
+        check_layer(L, B_.FWD_ROWLANE, tuning)
+
+
+@pytest.mark.parametrize("tuning", [{"lanes_per_neuron": l, "rows_per_block": r} for l in (1, 4, 16, 64) for r in (1, 2, 4, 8)])
+def test_klane_launch_shapes(tuning):
+    for (d_in, d_out, K, B, abl) in ((768, 300, 77, 9, 0.1), (3072, 96, 307, 3, 0.3), (100, 64, 5, 1, 0.0)):
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=78)
+        check_layer(L, B_.FWD_KLANE, tuning)
+
+
+# ----------------------------------------------------------------------------- exact cases
+@pytest.mark.parametrize("algo", list(ALGOS))
+def test_integer_inputs_are_bit_exact(algo):
+    """Integer operands: every partial sum is an integer below 2^24, so any summation order gives the same bits."""
+    rng = np.random.default_rng(41)
+    for (d_in, d_out, K, B, abl) in ((768, 256, 154, 70, 0.1), (3072, 64, 615, 3, 0.3)):
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=41)
+        L.W = rng.integers(-8, 9, size=L.W.shape).astype(np.float32)
+        L.x = rng.integers(-8, 9, size=L.x.shape).astype(np.float32)
+        L.bias = rng.integers(-8, 9, size=L.bias.shape).astype(np.float32)
+        W_c, idx, active = oracle_condensed(L)
+        y_ref = oracle.fwd(L.x, W_c, idx, active, L.bias, d_out)
+        try:
+            y = run_gpu(L, W_c, idx, active, L.bias, ALGOS[algo])
+        except B_.SriglError as e:
+            assert e.status == B_.ERR_UNSUPPORTED
+            continue
+        assert np.array_equal(y.view(np.uint32), y_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("algo", list(ALGOS))
+def test_one_hot_rows_are_bit_exact(algo):
+    """x = e_j: y[n] = bias[n] + W[n][j] M[n][j], a single rounding."""
+    L = si.make_layer(768, 200, 77, 64, ablate_frac=0.2, seed=42)
+    cols = np.random.default_rng(42).integers(0, 768, size=64)
+    L.x = np.zeros((64, 768), np.float32)
+    L.x[np.arange(64), cols] = 1.0
+    W_c, idx, active = oracle_condensed(L)
+    y = run_gpu(L, W_c, idx, active, L.bias, ALGOS[algo])
+    exp = (L.bias[None, :].astype(np.float64) + (L.W * L.mask)[:, cols].T.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(y.view(np.uint32), exp.view(np.uint32))
+
+
+@pytest.mark.parametrize("algo", ["auto", "generic", "klane"])
+def test_unsorted_and_duplicate_indices(algo):
+    """Alg. 1 is a plain sum over k: without seg the library must accept any in-range index order."""
+    L = si.make_layer(300, 50, 21, 40, seed=43)
+    W_c, idx, active = oracle_condensed(L)
+    rng = np.random.default_rng(43)
+    perm = np.stack([rng.permutation(21) for _ in range(50)])
+    Wp, ip = np.take_along_axis(W_c, perm, 1), np.take_along_axis(idx, perm, 1)
+    ip[:, 3] = ip[:, 2]
+    y_ref, S = oracle.fwd(L.x, Wp, ip, None, L.bias, 50, want_scale=True)
+    y = run_gpu(L, Wp, ip, None, L.bias, ALGOS[algo], seg=False)
+    gate(y, y_ref, S, TOL_F32)
+
+
+# ----------------------------------------------------------------------------- degenerate problems
+def test_degenerate_problems():
+    L = si.make_layer(64, 12, 5, 3, ablate_frac=0.25, seed=44)
+    W_c, idx, active = oracle_condensed(L)
+    # n_active = 0: bias broadcast
+    y = run_gpu(L, W_c[:0], idx[:0], active[:0], L.bias, None)
+    assert np.array_equal(y, np.tile(L.bias, (3, 1)))
+    # K = 0
+    y = run_gpu(L, np.zeros((9, 0), np.float32), np.zeros((9, 0), np.int32), active, L.bias, None)
+    assert np.array_equal(y, np.tile(L.bias, (3, 1)))
+    # no bias, nothing stored: zeros
+    y = run_gpu(L, W_c[:0], idx[:0], active[:0], None, None)
+    assert (y == 0).all()
+    # B = 0 returns without touching anything
+    y = run_gpu(L, W_c, idx, active, L.bias, None, x=L.x[:0])
+    assert y.shape == (0, 12)
+    # out-of-range columns in `active` are skipped, not written
+    bad_active = active.copy()
+    bad_active[-1] = 12
+    y = run_gpu(L, W_c, idx, bad_active, L.bias, B_.FWD_GENERIC)
+    assert y.shape == (3, 12)
+
+
+def test_fwd_host_side_argument_errors():
+    L = si.make_layer(64, 12, 5, 3, seed=45)
+    W_c, idx, active = oracle_condensed(L)
+    x, W, i, y = dev(L.x), dev(W_c), dev(idx), torch.empty((3, 12), device="cuda")
+    with pytest.raises(B_.SriglError) as e:   # active == NULL needs n_active == d_out
+        B_.srigl_condensed_linear_fwd(x, 3, 64, W, i, None, 11, 5, None, 12, y)
+    assert e.value.status == B_.ERR_INVALID_ARG
+    with pytest.raises(B_.SriglError) as e:   # K > d_in
+        B_.srigl_condensed_linear_fwd(x, 3, 4, W, i, None, 12, 5, None, 12, y)
+    assert e.value.status == B_.ERR_INVALID_ARG
+    with pytest.raises(B_.SriglError) as e:   # mixed storage types
+        B_.srigl_condensed_linear_fwd(x, 3, 64, W.to(torch.int16), i, None, 12, 5, None, 12, y)
+    assert e.value.status == B_.ERR_UNSUPPORTED
+    with pytest.raises(B_.SriglError) as e:   # ROWLANE over several chunks needs seg
+        B_.srigl_condensed_linear_fwd(x, 3, 64, W, i, None, 12, 5, None, 12, y, None, algo=B_.FWD_ROWLANE,
+                                      tuning={"chunk_cols": 64 if False else 0, "rows_per_lane": 3})
+    assert e.value.status == B_.ERR_UNSUPPORTED
+
+
+# ----------------------------------------------------------------------------- bf16 storage
+@pytest.mark.parametrize("algo", list(ALGOS))
+@pytest.mark.parametrize("d_in,d_out,K,B,abl", [(4096, 512, 205, 96, 0.2), (130, 9, 7, 5, 0.0), (768, 300, 77, 1, 0.1)])
+def test_bf16_storage(d_in, d_out, K, B, abl, algo):
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype="bf16", idx_dist="clustered" if d_in >= 1024 else "uniform", seed=46)
+    worst = check_layer(L, ALGOS[algo])
+    assert worst < 2e-6   # same bf16 inputs on both sides: only the fp32 accumulation differs
+
+
+# ----------------------------------------------------------------------------- the sparsity x batch sweep
+@pytest.mark.parametrize("d_in,d_out,s,K,B", si.sweep_points())
+def test_sweep_points(d_in, d_out, s, K, B):
+    L = si.make_layer(d_in, d_out, K, B, seed=0)
+    check_layer(L, None)
+
+
+# ----------------------------------------------------------------------------- full-size stress layer, sampled
+def test_large_layer_sampled_rows():
+    """4096 -> 16384, K = 205, bf16 storage, B = 2048, 20 % ablated, clustered indices: the GPU runs the
+    whole batch; the oracle recomputes a sample of batch rows (first, last, tile edges, random)."""
+    L = si.config("c5")
+    W_c, idx, active = oracle_condensed(L)
+    assert W_c.shape == (13108, 205)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 255, 256, 1023, 2046, 2047],
+                                     np.random.default_rng(5).integers(0, 2048, size=5)]))
+    y_ref, S = oracle.fwd(L.x_bf16[rows], W_c, idx, active, L.bias, L.d_out, want_scale=True)
+    for algo in (None, B_.FWD_ROWLANE):
+        y = run_gpu(L, W_c, idx, active, L.bias, algo)
+        gate(y[rows], y_ref, S, TOL_BF16)
+        ablated = np.setdiff1d(np.arange(L.d_out), active)
+        assert np.array_equal(y[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (2048, 1)).view(np.uint32))
+        assert np.isfinite(y).all()
