@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the condensed constant fan-in linear forward pass on one MI355X.
+
+A step is one call of srigl_condensed_linear_fwd on the 768 -> 3072, 90 % sparse (K = 77), fp32
+layer at batch 256 (the layer of Sec. 4.4 / App. H-I of arXiv 2305.02299, with a random constant
+fan-in topology standing in for the trained one).  The condensed arrays come from srigl_condense on
+the GPU, which runs (and is timed) once before the loop, as the paper amortises it.
+
+Timing: W warm-up steps, then exactly K steps between two HIP events on the stream the kernels are
+launched on, bracketed by device synchronisation.  The headline ("cold") rotates through enough
+independent copies of every operand that each call streams its operands from HBM rather than from
+L2 / Infinity Cache; the same loop on one fixed set of buffers ("warm") is reported beside it, as
+are batch 1, the dispatch floor of an empty kernel, a dense torch matmul of the same layer, and
+the CPU oracle on the host cores.
+
+Prints one JSON line on stdout (everything else goes to stderr).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VALU_PEAK_TFLOPS = 157.3  # published vector fp32 (packed forms); 78.6 without packed fp32
+CACHE_BYTES = 256 << 20        # Infinity Cache; the cold loop cycles through >= 2x this
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (scaled by the same counters on srigl_copy_bytes); filled in from profiles/, None = not measured.
+MEASURED_TRAFFIC_BYTES = {"c2": None, "c1": None}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(n_active, K, B, d_in, d_out, elem):
+    """Each operand touched once: W_c + idx, x, y, bias, active list."""
+    return n_active * K * (elem + 4) + B * d_in * elem + B * d_out * 4 + d_out * 4 + n_active * 4
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus)
+        sys.exit(2)
+
+    import torch
+
+    import synth_inputs as si
+    from paper_2305_02299_amd import binding as B_
+    from paper_2305_02299_amd import condense_layer
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    algo = {None: None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE}[args.algo]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
+
+    L = si.config(args.workload)                      # B = 256
+    d_in, d_out, K, Bn = L.d_in, L.d_out, L.K, L.B
+    W_d, mask_d, bias_d = dev(L.W), dev(L.mask), dev(L.bias)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def time_loop(fn, steps, warmup):
+        """ms per step of fn(i), HIP events on the launch stream."""
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for i in range(steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    # ---- set-up on the GPU: invariant check + condense (timed, not part of a step) ----
+    ws, rep = B_.new_workspace(d_out), B_.new_report()
+    t_check = time_loop(lambda i: B_.srigl_check_fanin(mask_d, None, d_out, d_in, K, None, ws, rep), 20, 3)
+    assert B_.read_report(rep)["status"] == 0
+    layer = condense_layer(W_d, mask_d, K, bias_d)
+    cW, cI, cA, cS = (torch.empty_like(layer.W_c), torch.empty_like(layer.idx),
+                      torch.empty(d_out, dtype=torch.int32, device="cuda"), torch.empty_like(layer.seg))
+    t_cond = time_loop(lambda i: B_.srigl_condense(W_d, mask_d, d_out, d_in, K, d_out, cW, cI, cA, cS, ws, rep), 20, 3)
+    n_active = layer.n_active
+    log("layer %s: %d -> %d, K=%d, n_active=%d, B=%d; check_fanin %.1f us, condense %.1f us"
+        % (args.workload, d_in, d_out, K, n_active, Bn, t_check * 1e3, t_cond * 1e3))
+
+    # ---- operand copies for the cold loop ----
+    def make_sets(B, n_sets):
+        sets = []
+        xs = dev(L.x[:B])
+        for _ in range(n_sets):
+            sets.append((xs.clone(), layer.W_c.clone(), layer.idx.clone(),
+                         None if layer.active is None else layer.active.clone(), layer.bias.clone(),
+                         None if layer.seg is None else layer.seg.clone(),
+                         torch.empty((B, d_out), dtype=torch.float32, device="cuda")))
+        return sets
+
+    def fwd_on(sets, B):
+        n = len(sets)
+
+        def f(i):
+            x, W_c, idx, act, bias, seg, y = sets[i % n]
+            B_.srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, act, n_active, K, bias, d_out, y, seg, algo=algo)
+        return f
+
+    results = {}
+    for B in (Bn, 1):
+        nbytes = algorithmic_bytes(n_active, K, B, d_in, d_out, 4)
+        n_sets = max(2, -(-2 * CACHE_BYTES // nbytes))
+        sets = make_sets(B, n_sets)
+        f_cold, f_warm = fwd_on(sets, B), fwd_on(sets[:1], B)
+        steps = args.steps
+        reps = [time_loop(f_cold, max(steps // 5, 1), args.warmup) for _ in range(5)]
+        cold = time_loop(f_cold, steps, args.warmup)            # the K timed steps of the contract
+        warm = time_loop(f_warm, steps, args.warmup)
+        # single synchronised call (host launch + kernel + wait)
+        lat = []
+        for i in range(30):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            f_cold(i)
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - t0) * 1e6)
+        flops = 2.0 * B * n_active * K
+        results[B] = {
+            "us_per_call_cold": cold * 1e3, "us_per_call_warm": warm * 1e3,
+            "us_cold_median_of_5": statistics.median(reps) * 1e3, "us_cold_std_of_5": statistics.pstdev(reps) * 1e3,
+            "sync_call_latency_us_median": statistics.median(lat),
+            "algorithmic_bytes": nbytes, "operand_sets": n_sets,
+            "hbm_gbs_cold": nbytes / (cold * 1e-3) / 1e9, "effective_gbs_warm": nbytes / (warm * 1e-3) / 1e9,
+            "gflops_cold": flops / (cold * 1e-3) / 1e9, "gflops_warm": flops / (warm * 1e-3) / 1e9,
+        }
+        results[B]["hbm_roofline_frac_cold"] = results[B]["hbm_gbs_cold"] / HBM_PEAK_GBS
+        log("B=%d: cold %.2f us (median of 5: %.2f +- %.2f), warm %.2f us, %.0f GB/s cold = %.1f%% of 8 TB/s, %.0f GFLOP/s"
+            % (B, cold * 1e3, results[B]["us_cold_median_of_5"], results[B]["us_cold_std_of_5"], warm * 1e3,
+               results[B]["hbm_gbs_cold"], 100 * results[B]["hbm_roofline_frac_cold"], results[B]["gflops_cold"]))
+        del sets
+
+    # ---- context: dispatch floor, copy bandwidth, dense torch matmul ----
+    t_empty = time_loop(lambda i: B_.srigl_launch_empty(), 2000, 100)
+    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    big2 = torch.empty_like(big)
+    t_copy = time_loop(lambda i: B_.srigl_copy_bytes(big, big2, big.numel()), 10, 2)
+    copy_gbs = 2 * big.numel() / (t_copy * 1e-3) / 1e9
+    del big, big2
+    Wm = dev(L.W * L.mask)
+    xd = dev(L.x)
+    t_dense = time_loop(lambda i: torch.nn.functional.linear(xd, Wm, bias_d), 500, 50)
+    log("empty kernel %.2f us/launch, copy kernel %.0f GB/s (read+write), torch dense linear B=%d %.2f us"
+        % (t_empty * 1e3, copy_gbs, Bn, t_dense * 1e3))
+
+    # ---- CPU oracle on the host cores (reported baseline, one thread, never tuned) ----
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        W_c_h, idx_h = layer.W_c.cpu().numpy(), layer.idx.cpu().numpy()
+        act_h = None if layer.active is None else layer.active.cpu().numpy()
+        times = []
+        t_start = time.perf_counter()
+        while len(times) < 5 or (time.perf_counter() - t_start < 10.0 and len(times) < 200):
+            t0 = time.perf_counter()
+            oracle.fwd(L.x, W_c_h, idx_h, act_h, L.bias, d_out)
+            times.append(time.perf_counter() - t0)
+        cpu = {"value": statistics.median(times) * 1e6, "unit": "us/call", "cores": 1, "kind": "oracle",
+               "sample": "the whole %s forward (B=%d), median of %d calls, fp64 accumulate, g++ -O2, 1 thread of %d host cores"
+                         % (args.workload, Bn, len(times), os.cpu_count())}
+        log("CPU oracle: %.0f us/call" % cpu["value"])
+
+    r = results[Bn]
+    out = {
+        "metric": "condensed_linear_fwd_us_per_call", "value": r["us_per_call_cold"], "unit": "us/call",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["us_per_call_cold"] / 1e3,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d->%d fp32, K=%d (90%% sparse), n_active=%d, B=%d, operands rotated through %d copies (HBM-cold)"
+                               % (args.workload, d_in, d_out, K, n_active, Bn, r["operand_sets"]),
+                   "algo": args.algo or "auto"},
+        "roofline": {"bound": "hbm", "achieved": r["hbm_gbs_cold"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": r["hbm_roofline_frac_cold"], "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "algorithmic_bytes": r["algorithmic_bytes"]},
+        "cpu_baseline": cpu,
+        "batch256": r, "batch1": results[1],
+        "gflops_effective": r["gflops_cold"],
+        "valu_frac_of_fp32_peak": r["gflops_cold"] / 1e3 / FP32_VALU_PEAK_TFLOPS,
+        "setup_us": {"check_fanin": t_check * 1e3, "condense": t_cond * 1e3},
+        "context": {"empty_kernel_us": t_empty * 1e3, "copy_kernel_gbs": copy_gbs, "torch_dense_linear_us": t_dense * 1e3,
+                    "paper_speedups": "3.4x/2.5x vs dense/CSR (Xeon W-2145, B=1), 1.7x/13.0x (Titan V, B=256): other hardware"},
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

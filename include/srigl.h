@@ -112,7 +112,7 @@ srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* m
  * x[B][d_in] of x_dtype; W_c[n_active][K] of w_dtype (both F32 or both BF16); idx[n_active][K]
  * int32 in [0, d_in) (not checked here: validate once with srigl_check_fanin in index mode);
  * active[n_active] strictly ascending columns in [0, d_out), or NULL when n_active == d_out
- * (the s-th stored neuron is column s); bias[d_out] fp32 or NULL (= zero, Alg. 1 verbatim);
+ * (the s-th stored neuron is column s) or n_active == 0; bias[d_out] fp32 or NULL (= zero, Alg. 1 verbatim);
  * y[B][d_out] fp32, fully overwritten.  Accumulation is fp32 (bf16 products are exact in fp32).
  * seg: the table written by condense / check_fanin for these idx, or NULL.  With seg == NULL, or
  * rows that are not ascending, only algorithms that do not depend on the order are used.

@@ -54,6 +54,13 @@ __global__ __launch_bounds__(256) void k_fwd_generic(const XT* __restrict__ x, i
     }
 }
 
+// y[b][c] = bias[c] (or 0): the whole forward pass when nothing is stored (n_active == 0 or K == 0).
+__global__ __launch_bounds__(256) void k_bias_broadcast(const float* __restrict__ bias, int B, int d_out, float* __restrict__ y) {
+    const long long total = (long long)B * d_out;
+    for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x)
+        y[t] = bias_at(bias, (int)(t % d_out));
+}
+
 // ------------------------------------------------------------------------------------------------
 // KLANE (small batch, online inference).  A workgroup stages RB rows of x in LDS (fp32, row-major)
 // and walks over stored rows; L lanes (a power of two) share one stored row: lane q takes the terms
@@ -484,7 +491,7 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
     if (B < 0 || d_in < 0 || n_active < 0 || K < 0 || d_out < 0 || K > d_in || n_active > d_out) return SRIGL_ERR_INVALID_ARG;
     if ((x_dtype != SRIGL_F32 && x_dtype != SRIGL_BF16) || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
     if (x_dtype != w_dtype) return SRIGL_ERR_UNSUPPORTED;
-    if (active == nullptr && n_active != d_out) return SRIGL_ERR_INVALID_ARG;
+    if (active == nullptr && n_active != d_out && n_active != 0) return SRIGL_ERR_INVALID_ARG;
     if (B == 0 || d_out == 0) return SRIGL_OK;
     if (y == nullptr) return SRIGL_ERR_INVALID_ARG;
     if (n_active > 0 && K > 0 && (x == nullptr || W_c == nullptr || idx == nullptr)) return SRIGL_ERR_INVALID_ARG;
@@ -493,10 +500,11 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
     a.x = x; a.x_bf16 = (x_dtype == SRIGL_BF16); a.B = B; a.d_in = d_in; a.W_c = W_c; a.idx = idx; a.active = active;
     a.n_active = n_active; a.K = K; a.bias = bias; a.d_out = d_out; a.y = y; a.seg = seg;
     a.seg_stride = srigl_seg_stride(d_in);
-    if (n_active == 0 || K == 0) {
-        // bias broadcast: no stored term is read.  K = 0 keeps every pointer untouched in the kernels.
-        a.K = 0; a.seg = nullptr;
-        return launch_fwd_generic(a, st);
+    if (n_active == 0 || K == 0) {   // nothing is stored: every column holds its bias
+        long long blocks = ((long long)B * d_out + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(k_bias_broadcast, dim3((unsigned)blocks), dim3(256), 0, st, bias, B, d_out, y);
+        return hip_ok(hipGetLastError());
     }
     switch (algo) {
         case SRIGL_FWD_GENERIC: return launch_fwd_generic(a, st);

@@ -214,9 +214,16 @@ def test_fwd_host_side_argument_errors():
     with pytest.raises(B_.SriglError) as e:   # mixed storage types
         B_.srigl_condensed_linear_fwd(x, 3, 64, W.to(torch.int16), i, None, 12, 5, None, 12, y)
     assert e.value.status == B_.ERR_UNSUPPORTED
-    with pytest.raises(B_.SriglError) as e:   # ROWLANE over several chunks needs seg
+    with pytest.raises(B_.SriglError) as e:   # a launch shape the kernels do not have
         B_.srigl_condensed_linear_fwd(x, 3, 64, W, i, None, 12, 5, None, 12, y, None, algo=B_.FWD_ROWLANE,
-                                      tuning={"chunk_cols": 64 if False else 0, "rows_per_lane": 3})
+                                      tuning={"rows_per_lane": 3})
+    assert e.value.status == B_.ERR_UNSUPPORTED
+    # ROWLANE over several LDS chunks needs the seg table
+    L = si.make_layer(3072, 16, 30, 3, seed=45)
+    W_c, idx, active = oracle_condensed(L)
+    with pytest.raises(B_.SriglError) as e:
+        B_.srigl_condensed_linear_fwd(dev(L.x), 3, 3072, dev(W_c), dev(idx), None, 16, 30, None, 16,
+                                      torch.empty((3, 16), device="cuda"), None, algo=B_.FWD_ROWLANE)
     assert e.value.status == B_.ERR_UNSUPPORTED
 
 
