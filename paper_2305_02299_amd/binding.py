@@ -144,7 +144,10 @@ def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, 
         if tuning is not None:
             tn = FwdTuning()
             for k, v in tuning.items():
-                setattr(tn, k, int(v))
+                if k == "dbg":
+                    tn.reserved[0] = int(v)
+                else:
+                    setattr(tn, k, int(v))
         st = lib.srigl_condensed_linear_fwd_algo(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
                                                  _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
                                                  int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
