@@ -35,9 +35,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VALU_PEAK_TFLOPS = 157.3  # published vector fp32 (packed forms); 78.6 without packed fp32
 CACHE_BYTES = 256 << 20        # Infinity Cache; the cold loop cycles through >= 2x this
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script (scaled by the same counters on srigl_copy_bytes); filled in from profiles/, None = not measured.
-MEASURED_TRAFFIC_BYTES = {"c2": None, "c1": None}
+# Bytes per launch between L2 and the fabric (HBM / Infinity Cache) of the forward kernel, from the rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE runs of this script summarised in profiles/fwd_c2_c1_hbm_traffic.md (each counter scaled
+# by what it reads for srigl_copy_bytes on 1 GiB).  Keys: workload and batch.
+MEASURED_TRAFFIC_BYTES = {("c2", 256): 11702308, ("c2", 1): 2094130}
 
 
 def log(*a):
@@ -219,7 +220,7 @@ def main():
                                % (args.workload, d_in, d_out, K, n_active, Bn, r["operand_sets"]),
                    "algo": args.algo or "auto"},
         "roofline": {"bound": "hbm", "achieved": r["hbm_gbs_cold"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": r["hbm_roofline_frac_cold"], "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "frac": r["hbm_roofline_frac_cold"], "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, Bn)),
                      "algorithmic_bytes": r["algorithmic_bytes"]},
         "cpu_baseline": cpu,
         "batch256": r, "batch1": results[1],

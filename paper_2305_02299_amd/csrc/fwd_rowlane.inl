@@ -1,0 +1,446 @@
+// ROWLANE forward kernel and its launchers, included once per element type (one translation unit each,
+// so that the instantiations compile in parallel).
+#pragma once
+#include "srigl_internal.h"
+
+namespace srigl {
+
+#ifdef SRIGL_TIMELINE   // development builds only: per-wavefront cycle stamps at phase boundaries
+static __device__ long long g_timeline[16 * 4096];
+#define SRIGL_STAMP(slot)                                                                                       \
+    if (lane == 0 && blockIdx.x * 16 + wv_id < 4096) g_timeline[(blockIdx.x * 16 + wv_id) * 16 + (slot)] = clock64();
+#else
+#define SRIGL_STAMP(slot)
+#endif
+
+template <typename XT> __device__ __forceinline__ float rl_to_f32(XT v);
+template <> __device__ __forceinline__ float rl_to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float rl_to_f32<uint16_t>(uint16_t v) { return bf16_bits_to_float(v); }
+__device__ __forceinline__ float rl_bias_at(const float* __restrict__ bias, int col) { return bias ? bias[col] : 0.0f; }
+
+// ------------------------------------------------------------------------------------------------
+// ROWLANE (batched).  Lanes are batch rows: a workgroup owns a tile of BT = 64*R batch rows and a
+// group of stored rows, and keeps the activation tile transposed in LDS (xs[column][row], fp32), so
+// that for one term (stored row s, k) the gather x[b][idx[s][k]] of all rows of the tile is one
+// conflict-free LDS read of BT consecutive words.
+//
+// Weights and indices reach the lanes without scalar loads: a wavefront reads 16 consecutive terms
+// of a stored row with one vector load (lane l holds term l mod 16, the four 16-lane DPP rows hold
+// copies) and every multiply-add takes its weight, and every LDS address its index, through the DPP
+// row broadcast (row_newbcast:n) of lane n, which costs no instruction of its own.  Vector loads
+// count on vmcnt only, so they stay in flight across LDS traffic.
+//
+// d_in is walked in chunks of C columns (one LDS buffer).  The global loads of chunk c+1 are issued
+// into registers before the arithmetic of chunk c, written to LDS after it between two barriers.
+// Within a chunk the terms of an ascending row are the contiguous range the seg table gives; lane j
+// of a per-row register holds boundary j, read with v_readlane.  The first KPRE blocks of 16 terms
+// of the next chunk are requested as soon as the registers of the current chunk's blocks are free.
+//
+// Terms run in groups of 8: the LDS reads of group g+1 are issued before the multiply-adds of group
+// g, so that the LDS latency of one group hides behind the arithmetic of the other.
+//
+// LDS: row stride S = BT + 4 words.  The staging pass moves 16 rows x 16 columns per wavefront
+// instruction (global reads of 64 contiguous bytes per row) and the +4 skew spreads its LDS writes
+// over all banks, while reads of consecutive rows stay conflict-free and 16-byte aligned.  Column C
+// is all zeros: terms that pad a group carry weight 0 and point there, so that a non-finite
+// activation in an unrelated column never meets a padded term.
+//
+// Results leave through LDS as well: the accumulators are transposed into an out[row][stored row]
+// tile so that a wavefront stores runs of consecutive columns of one output row.
+// ------------------------------------------------------------------------------------------------
+template <int R> struct RowVec;
+template <> struct RowVec<1> { using type = float; };
+template <> struct RowVec<2> { using type = float2; };
+template <> struct RowVec<4> { using type = float4; };
+
+
+template <typename XT>
+__device__ __forceinline__ void load4(const XT* __restrict__ p, bool vec_ok, int n_valid, float out[4]);
+
+template <>
+__device__ __forceinline__ void load4<float>(const float* __restrict__ p, bool vec_ok, int n_valid, float out[4]) {
+    if (vec_ok && n_valid >= 4) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = (i < n_valid) ? p[i] : 0.0f;
+    }
+}
+
+template <>
+__device__ __forceinline__ void load4<uint16_t>(const uint16_t* __restrict__ p, bool vec_ok, int n_valid, float out[4]) {
+    if (vec_ok && n_valid >= 4) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xffff0000u);
+        out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xffff0000u);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = (i < n_valid) ? bf16_bits_to_float(p[i]) : 0.0f;
+    }
+}
+
+// lane n of each 16-lane row, seen by every lane of that row (folds into the consuming VALU instruction)
+template <int N>
+__device__ __forceinline__ int row_bcast(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + N, 0xf, 0xf, true);
+}
+
+// acc += w[lane n of this row] * x.  The s_nop at the head of every run of 4 covers the two wait states a DPP
+// read needs after a VALU write of `w`; the terms of a group run in order (they chain through acc).
+template <int N>
+__device__ __forceinline__ void fmac_row_bcast(float& acc, float w, float x) {
+    if constexpr (N % 4 == 0)
+        asm("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1" : "+v"(acc) : "v"(w), "v"(x), "n"(N));
+    else
+        asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1" : "+v"(acc) : "v"(w), "v"(x), "n"(N));
+}
+
+template <int R, int N>
+__device__ __forceinline__ void fmac_rows(float (&acc)[R], float wv, const typename RowVec<R>::type& xv) {
+    if constexpr (R == 1) {
+        fmac_row_bcast<N>(acc[0], wv, xv);
+    } else if constexpr (R == 2) {
+        fmac_row_bcast<N>(acc[0], wv, xv.x);
+        fmac_row_bcast<N>(acc[1], wv, xv.y);
+    } else {
+        fmac_row_bcast<N>(acc[0], wv, xv.x);
+        fmac_row_bcast<N>(acc[1], wv, xv.y);
+        fmac_row_bcast<N>(acc[2], wv, xv.z);
+        fmac_row_bcast<N>(acc[3], wv, xv.w);
+    }
+}
+
+// Terms run in groups of GS (8 for R <= 2, 4 for R = 4: 32 data registers per group at most).
+template <int R> struct GroupSize { static constexpr int value = (R == 4) ? 4 : 8; };
+
+// Group Q of a block (terms Q*GS .. Q*GS+GS-1): its LDS reads, and its multiply-adds
+template <int R, int Q, int J = 0>
+__device__ __forceinline__ void group_reads(typename RowVec<R>::type (&xv)[GroupSize<R>::value], int ov, const char* __restrict__ xb) {
+    using V = typename RowVec<R>::type;
+    constexpr int GS = GroupSize<R>::value;
+    if constexpr (J < GS) {
+        xv[J] = *reinterpret_cast<const V*>(xb + row_bcast<Q * GS + J>(ov));
+        group_reads<R, Q, J + 1>(xv, ov, xb);
+    }
+}
+template <int R, int Q, int J = 0>
+__device__ __forceinline__ void group_fmacs(float (&acc)[R], float wv, const typename RowVec<R>::type (&xv)[GroupSize<R>::value]) {
+    constexpr int GS = GroupSize<R>::value;
+    if constexpr (J < GS) {
+        fmac_rows<R, Q * GS + J>(acc, wv, xv[J]);
+        group_fmacs<R, Q, J + 1>(acc, wv, xv);
+    }
+}
+
+// Groups G, G+1, ... of NB blocks held in registers; n = number of real terms (wave-uniform).
+// On entry the reads of group G are in flight in `cur`; every path issues the reads of the next group
+// before the multiply-adds of this one.
+template <int R, int G, int NB>
+__device__ __forceinline__ void pipe_groups(float (&acc)[R], const float (&wv)[NB], const int (&ov)[NB], const char* __restrict__ xb,
+                                            int n, typename RowVec<R>::type (&cur)[GroupSize<R>::value],
+                                            typename RowVec<R>::type (&nxt)[GroupSize<R>::value]) {
+    constexpr int GS = GroupSize<R>::value;
+    constexpr int GPB = kBlock / GS;   // groups per block
+    if constexpr (G + 1 < GPB * NB) {
+        if (n > GS * (G + 1)) {
+            group_reads<R, (G + 1) % GPB>(nxt, ov[(G + 1) / GPB], xb);
+            group_fmacs<R, G % GPB>(acc, wv[G / GPB], cur);
+            pipe_groups<R, G + 1, NB>(acc, wv, ov, xb, n, nxt, cur);
+            return;
+        }
+    }
+    group_fmacs<R, G % GPB>(acc, wv[G / GPB], cur);
+}
+
+// 16 consecutive terms of stored-row data starting at term index t0 (wave-uniform): lane l requests term
+// l mod 16.  The loads are unconditional (the term index is clamped into the arrays) and nothing here
+// consumes their result, so that they stay in flight; finish_terms() turns the raw words into a
+// weight and an LDS byte offset when the block is about to be used.
+template <typename XT>
+__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const int32_t* __restrict__ idx, int t0, int l16, int t_last,
+                                              XT& w_raw, int& i_raw) {
+    const unsigned t = (unsigned)min(t0 + l16, t_last);
+    w_raw = W_c[t];
+    i_raw = idx[t];
+}
+// n_valid (wave-uniform, may be <= 0) of the 16 terms are real; the others become (weight 0, all-zero column).
+template <typename XT>
+__device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, int l16, int off_mul, int off_add, int zero_off,
+                                             float& wv, int& ov) {
+    const bool real = l16 < n_valid;
+    wv = real ? rl_to_f32<XT>(w_raw) : 0.0f;
+    ov = real ? i_raw * off_mul + off_add : zero_off;
+}
+
+template <int R, int NPW, int KPRE, typename XT, bool FAST>
+__global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
+                                                      const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
+                                                      int n_active, int K, const float* __restrict__ bias, int d_out,
+                                                      float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
+                                                      int C, int n_chunks, int n_btiles, int n_groups) {
+    extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
+    constexpr int BT = kWave * R;
+    constexpr int S = BT + 4;
+    constexpr int S4 = S * 4;
+    using V = typename RowVec<R>::type;
+
+    // XCD-aware decode: consecutive workgroup ids go to different XCDs (8 of them), so the id modulo 8
+    // selects the XCD; all batch tiles of one neuron group are given to the same XCD, whose L2 then
+    // holds that group's W_c / idx once.
+    const int wg = blockIdx.x;
+    const int xcd = wg & 7, inx = wg >> 3;
+    const int bt = inx % n_btiles;
+    const int g = (inx / n_btiles) * 8 + xcd;
+    if (g >= n_groups) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int l16 = lane & (kBlock - 1);
+    const int wv_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nw = blockDim.x >> 6;
+    const int NG = nw * NPW;                 // stored rows (slots) per workgroup
+    const int b0 = bt * BT;
+    const int n_slots = active ? n_active + 1 : n_active;
+    const int sg0 = g * NG;                  // first slot of the workgroup
+    const int s0 = sg0 + wv_id * NPW;        // first slot of this wavefront
+    const int zero_off = C * S4;             // byte offset of the all-zero column
+    const int segs_per_chunk = C / kSegCols;
+    const int t_last = n_active * K - 1;     // the host guarantees n_active * K < 2^31
+    SRIGL_STAMP(0)
+
+    // ---- chunk boundaries: lane j of bnd[i] holds the first term of chunk cb + j for slot s0 + i ----
+    int bnd[NPW];
+    int cb = 0;
+#define SRIGL_LOAD_BOUNDS()                                                                                     \
+    _Pragma("unroll") for (int i = 0; i < NPW; ++i) {                                                           \
+        const int s = min(s0 + i, n_active - 1);                                                                \
+        const int j = min(cb + lane, n_chunks);                                                                 \
+        int v = (j == 0) ? 0 : K;                                                                               \
+        if (seg) v = seg[(unsigned)(s * seg_stride + min(j * segs_per_chunk, seg_stride - 1))];                 \
+        bnd[i] = v;                                                                                             \
+    }
+
+    // ---- staging: 16 rows x 16 columns per unit; unit u = wv_id + i * nw -> (row tile, column tile) ----
+    const int dq = lane & 3, db = lane >> 2;             // 4 column quads x 16 rows per wavefront pass
+    const int col_tiles = C >> 4;                         // C is a multiple of 64
+    const int units = (BT / 16) * col_tiles;              // <= kStageUnits * nw (checked by the host)
+    unsigned g_off[kStageUnits];                          // element offset into x of this lane's 4 columns (chunk 0)
+    int l_off[kStageUnits];                               // word offset into the LDS tile
+    int u_col[kStageUnits];                               // first column of the unit (wave-uniform)
+#pragma unroll
+    for (int i = 0; i < kStageUnits; ++i) {
+        const int u = wv_id + i * nw;
+        const int rt = u / col_tiles, ct = u - rt * col_tiles;
+        const int rl = rt * 16 + db;
+        const int f = ct * 16 + dq * 4;
+        // rows past B re-read row B - 1: their lanes compute values that are never stored
+        g_off[i] = (unsigned)(min(b0 + rl, B - 1) * d_in + f);   // the host guarantees B * d_in < 2^31
+        l_off[i] = f * S + rl;
+        u_col[i] = (u < units) ? ct * 16 : 0x40000000;   // units past the tile never pass the column tests below
+    }
+    float st[kStageUnits][4];
+#define SRIGL_STAGE_LOAD(c)                                                                                     \
+    _Pragma("unroll") for (int i = 0; i < kStageUnits; ++i) {                                                   \
+        const int c0_ = (c) * C;                                                                                \
+        if (FAST) {                                                                                             \
+            if (c0_ + u_col[i] < d_in) load4<XT>(x + (g_off[i] + (unsigned)c0_), true, 4, st[i]);               \
+        } else {                                                                                                \
+            st[i][0] = st[i][1] = st[i][2] = st[i][3] = 0.0f;                                                   \
+            const int nv = min(4, d_in - (c0_ + u_col[i] + dq * 4));                                            \
+            if (u_col[i] < C && nv > 0) load4<XT>(x + (g_off[i] + (unsigned)c0_), false, nv, st[i]);            \
+        }                                                                                                       \
+    }
+#define SRIGL_STAGE_STORE()                                                                                     \
+    _Pragma("unroll") for (int i = 0; i < kStageUnits; ++i) {                                                   \
+        if (u_col[i] < C) {                                                                                     \
+            float* d_ = lds + l_off[i];                                                                         \
+            d_[0] = st[i][0]; d_[S] = st[i][1]; d_[2 * S] = st[i][2]; d_[3 * S] = st[i][3];                     \
+        }                                                                                                       \
+    }
+
+    // ---- terms: the first KPRE blocks of every slot for one chunk live in registers ----
+    XT rw[NPW][KPRE];    // raw words as loaded; finished into (weight, offset) right before use
+    int ri[NPW][KPRE];
+#define SRIGL_PRELOAD(i, c)                                                                                     \
+    {                                                                                                           \
+        const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
+        _Pragma("unroll") for (int p = 0; p < KPRE; ++p)                                                        \
+            request_terms<XT>(W_c, idx, (s0 + (i)) * K + k0_ + p * kBlock, l16, t_last, rw[i][p], ri[i][p]);    \
+    }
+
+    float acc[NPW][R];
+#pragma unroll
+    for (int i = 0; i < NPW; ++i)
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[i][r] = 0.0f;
+
+    // Chunk 0 starts at term 0 of every row, so its blocks are requested before the boundaries are known.
+#pragma unroll
+    for (int i = 0; i < NPW; ++i)
+#pragma unroll
+        for (int p = 0; p < KPRE; ++p) request_terms<XT>(W_c, idx, (s0 + i) * K + p * kBlock, l16, t_last, rw[i][p], ri[i][p]);
+    SRIGL_LOAD_BOUNDS()
+    SRIGL_STAGE_LOAD(0)
+    for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
+    SRIGL_STAMP(1)
+    SRIGL_STAGE_STORE()
+    SRIGL_STAMP(2)
+    __syncthreads();
+    SRIGL_STAMP(3)
+
+    const char* xb = reinterpret_cast<const char*>(lds) + lane * (R * 4);
+    for (int c = 0; c < n_chunks; ++c) {
+        const bool more = (c + 1 < n_chunks);
+        if (more) {
+            SRIGL_STAGE_LOAD(c + 1)                       // in flight during the arithmetic below
+        }
+        int k0n[NPW], nn[NPW];
+#pragma unroll
+        for (int i = 0; i < NPW; ++i) {
+            k0n[i] = __builtin_amdgcn_readlane(bnd[i], c - cb);
+            nn[i] = (s0 + i < n_active) ? __builtin_amdgcn_readlane(bnd[i], c - cb + 1) - k0n[i] : 0;
+        }
+        if (more && c + 2 - cb > kWave - 1) { cb = c + 1; SRIGL_LOAD_BOUNDS() }   // boundaries c+1, c+2 stay in the register
+#pragma unroll
+        for (int i = 0; i < NPW; ++i) {
+            const int n_terms = nn[i];
+            V xa[GroupSize<R>::value], xc[GroupSize<R>::value];
+            if (n_terms > 0) {
+                float pw[KPRE];
+                int po[KPRE];
+#pragma unroll
+                for (int p = 0; p < KPRE; ++p)
+                    finish_terms<XT>(rw[i][p], ri[i][p], n_terms - p * kBlock, l16, S4, -c * C * S4, zero_off, pw[p], po[p]);
+                group_reads<R, 0>(xa, po[0], xb);
+                pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, n_terms, xa, xc);
+                // long ranges: the remaining blocks, one at a time, each requested one block ahead
+                if (n_terms > KPRE * kBlock) {
+                    const int row = (s0 + i) * K + k0n[i];
+                    XT wr;
+                    int ir;
+                    request_terms<XT>(W_c, idx, row + KPRE * kBlock, l16, t_last, wr, ir);
+                    for (int kb = KPRE * kBlock; kb < n_terms; kb += kBlock) {
+                        float wc[1];
+                        int oc[1];
+                        finish_terms<XT>(wr, ir, n_terms - kb, l16, S4, -c * C * S4, zero_off, wc[0], oc[0]);
+                        if (kb + kBlock < n_terms) request_terms<XT>(W_c, idx, row + kb + kBlock, l16, t_last, wr, ir);
+                        group_reads<R, 0>(xa, oc[0], xb);
+                        pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, n_terms - kb, xa, xc);
+                    }
+                }
+            }
+            if (more) SRIGL_PRELOAD(i, c + 1)             // this slot's registers are free: request its next chunk
+        }
+        SRIGL_STAMP(4 + 3 * (c < 3 ? c : 2))
+        if (more) {
+            __syncthreads();                              // every wavefront is done reading chunk c
+            SRIGL_STAGE_STORE()
+            SRIGL_STAMP(5 + 3 * (c < 3 ? c : 2))
+            __syncthreads();
+            SRIGL_STAMP(6 + 3 * (c < 3 ? c : 2))
+        }
+    }
+#undef SRIGL_LOAD_BOUNDS
+#undef SRIGL_STAGE_LOAD
+#undef SRIGL_STAGE_STORE
+#undef SRIGL_PRELOAD
+
+    // ---- results: transpose through LDS, then bias + scatter with row-contiguous stores ----
+    __syncthreads();                                       // every wavefront is done reading the x tile
+    const int OS = NG + 1;                                 // odd stride: conflict-free transposed writes
+#pragma unroll
+    for (int i = 0; i < NPW; ++i)
+#pragma unroll
+        for (int r = 0; r < R; ++r) lds[(lane * R + r) * OS + wv_id * NPW + i] = acc[i][r];
+    __syncthreads();
+
+    // lane <-> slot of the workgroup (two slots per lane cover NG <= 128)
+    int colv[2], prevv[2];
+    float biasv[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int i = lane + h * kWave;
+        const int s = sg0 + i;
+        colv[h] = -1;
+        prevv[h] = 0;
+        biasv[h] = 0.0f;
+        if (i < NG && s < n_slots) {
+            int col = s, prev = s - 1;
+            if (active) {
+                col = min((s < n_active) ? active[s] : d_out, d_out);
+                prev = (s > 0) ? active[s - 1] : -1;
+            }
+            prevv[h] = max(prev + 1, 0);                   // first column of the gap in front of this slot
+            colv[h] = col;
+            if (s < n_active && col >= 0 && col < d_out) biasv[h] = rl_bias_at(bias, col);
+        }
+    }
+    SRIGL_STAMP(13)
+    const int n_rows = min(BT, B - b0);
+    for (int row = wv_id; row < n_rows; row += nw) {
+        float* yr = y + (size_t)(b0 + row) * d_out;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int i = lane + h * kWave;
+            const int col = colv[h];
+            if (col < 0) continue;
+            if (active)
+                for (int cc = prevv[h]; cc < col; ++cc) yr[cc] = rl_bias_at(bias, cc);
+            if (sg0 + i < n_active && col < d_out) yr[col] = lds[row * OS + i] + biasv[h];
+        }
+    }
+    SRIGL_STAMP(14)
+}
+
+template <int R, int NPW, int KPRE, typename XT, bool FAST>
+static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
+    auto kern = k_fwd_rowlane<R, NPW, KPRE, XT, FAST>;
+    static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
+    if (p.lds > lds_allowed) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
+            return SRIGL_ERR_HIP;
+        lds_allowed = kLdsMax;
+    }
+    const long long blocks = 8LL * ((p.n_groups + 7) / 8) * p.n_btiles;
+    if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
+                       a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
+                       p.n_groups);
+    return hip_ok(hipGetLastError());
+}
+
+template <int R, int NPW, typename XT>
+static srigl_status launch_rowlane_k(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
+    constexpr int KPRE = rowlane_kpre(NPW);
+    if (p.fast) return launch_rowlane_f<R, NPW, KPRE, XT, true>(a, p, st);
+    if constexpr (R == 1) return launch_rowlane_f<R, NPW, KPRE, XT, false>(a, p, st);
+    return SRIGL_ERR_UNSUPPORTED;   // the planner keeps R = 1 when the fast staging does not apply
+}
+
+template <int R, typename XT>
+static srigl_status launch_rowlane_r(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
+    constexpr int MAXN = rowlane_max_npw(R);
+    switch (p.NPW) {
+        case 1: return launch_rowlane_k<R, 1, XT>(a, p, st);
+        case 2: return launch_rowlane_k<R, 2, XT>(a, p, st);
+        case 3: return launch_rowlane_k<R, 3, XT>(a, p, st);
+        case 4: return launch_rowlane_k<R, 4, XT>(a, p, st);
+        case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, 6, XT>(a, p, st); else break;
+        case 8: if constexpr (MAXN >= 8) return launch_rowlane_k<R, 8, XT>(a, p, st); else break;
+        default: break;
+    }
+    return SRIGL_ERR_UNSUPPORTED;
+}
+
+template <typename XT>
+static srigl_status launch_rowlane_x(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
+    switch (p.R) {
+        case 1: return launch_rowlane_r<1, XT>(a, p, st);
+        case 2: return launch_rowlane_r<2, XT>(a, p, st);
+        case 4: return launch_rowlane_r<4, XT>(a, p, st);
+        default: return SRIGL_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace srigl

@@ -259,3 +259,25 @@ def test_large_layer_sampled_rows():
         ablated = np.setdiff1d(np.arange(L.d_out), active)
         assert np.array_equal(y[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (2048, 1)).view(np.uint32))
         assert np.isfinite(y).all()
+
+
+# ----------------------------------------------------------------------------- non-finite activations stay local
+@pytest.mark.parametrize("algo", list(ALGOS))
+def test_non_finite_activation_only_reaches_its_own_terms(algo):
+    """y[b][n] depends on x[b][j] only for j in idx[n]: an inf / NaN in one column must not touch neurons that do not
+    index that column (padding inside the kernels must never multiply 0 by it)."""
+    L = si.make_layer(768, 200, 77, 70, ablate_frac=0.1, seed=47)
+    W_c, idx, active = oracle_condensed(L)
+    x = L.x.copy()
+    bad_cols = [0, 63, 64, 383, 384, 767]          # tile / chunk edges
+    x[3, bad_cols] = np.inf
+    x[40, bad_cols] = np.nan
+    y = run_gpu(L, W_c, idx, active, L.bias, ALGOS[algo], x=x)
+    y_ref, S = oracle.fwd(x, W_c, idx, active, L.bias, L.d_out, want_scale=True)
+    touches = np.isin(idx, bad_cols).any(axis=1)                     # stored rows that index a bad column
+    clean_cols = active[~touches]
+    assert len(clean_cols) > 50
+    assert np.isfinite(y[:, clean_cols]).all()
+    fin = np.isfinite(y_ref)
+    assert np.array_equal(np.isfinite(y), fin)
+    assert np.max(np.abs(y[fin] - y_ref[fin]) / np.maximum(np.maximum(np.abs(y_ref[fin]), S[fin]), 1e-30)) < TOL_F32
