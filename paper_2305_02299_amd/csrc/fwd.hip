@@ -68,6 +68,21 @@ __global__ __launch_bounds__(256) void k_bias_broadcast(const float* __restrict_
 // k = q, q+L, ... so that a wavefront's loads of W_c and idx are runs of L contiguous words, and the
 // partial sums are combined with a butterfly of cross-lane shuffles.
 // ------------------------------------------------------------------------------------------------
+constexpr int kKlaneTerms = 4;   // terms a lane keeps in flight per request
+
+// Lane q of a group asks for terms kb + q, kb + q + L, ... (kKlaneTerms of them) of stored row s.  The loads are
+// unconditional (term index clamped into the row) and nothing here consumes them, so they all stay in flight.
+template <typename XT>
+__device__ __forceinline__ void klane_request(const XT* __restrict__ W_c, const int32_t* __restrict__ idx, size_t row, int kb, int q,
+                                              int L, int K, XT (&wr)[kKlaneTerms], int (&ir)[kKlaneTerms]) {
+#pragma unroll
+    for (int t = 0; t < kKlaneTerms; ++t) {
+        const size_t e = row + (size_t)min(kb + q + t * L, K - 1);
+        wr[t] = W_c[e];
+        ir[t] = idx[e];
+    }
+}
+
 template <int RB, typename XT>
 __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                    const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
@@ -84,18 +99,15 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
     const int s_begin = blockIdx.x * rows_per_wg;
     const int s_end = min(s_begin + rows_per_wg, n_slots);
 
-    // first terms of the first stored row are requested before the staging barrier
+    // the first terms of the first stored row are requested before the staging barrier
     int s = s_begin + grp;
-    float w0 = 0.0f;
-    int j0 = 0;
-    if (s < min(s_end, n_active) && q < K) {
-        w0 = to_f32<XT>(W_c[(size_t)s * K + q]);
-        j0 = idx[(size_t)s * K + q];
-    }
+    XT wr[kKlaneTerms];
+    int ir[kKlaneTerms];
+    klane_request<XT>(W_c, idx, (size_t)min(s, n_active - 1) * K, 0, q, L, K, wr, ir);
 
     for (int r = 0; r < RB; ++r) {
-        const int b = b0 + r;
-        for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = (b < B) ? to_f32<XT>(x[(size_t)b * d_in + j]) : 0.0f;
+        const int b = min(b0 + r, B - 1);             // rows past B re-read the last row; they are never stored
+        for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = to_f32<XT>(x[(size_t)b * d_in + j]);
     }
     __syncthreads();
 
@@ -104,25 +116,26 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
 #pragma unroll
         for (int r = 0; r < RB; ++r) acc[r] = 0.0f;
         if (s < n_active) {
-            const XT* w = W_c + (size_t)s * K;
-            const int32_t* ix = idx + (size_t)s * K;
-            if (q < K) {
+            const size_t row = (size_t)s * K;
+            for (int kb = 0; kb < K; kb += kKlaneTerms * L) {
+                XT wc[kKlaneTerms];
+                int ic[kKlaneTerms];
 #pragma unroll
-                for (int r = 0; r < RB; ++r) acc[r] = w0 * xs[r * d_in + j0];
-            }
-            for (int k = q + L; k < K; k += L) {
-                const float wv = to_f32<XT>(w[k]);
-                const int j = ix[k];
+                for (int t = 0; t < kKlaneTerms; ++t) { wc[t] = wr[t]; ic[t] = ir[t]; }
+                if (kb + kKlaneTerms * L < K) klane_request<XT>(W_c, idx, row, kb + kKlaneTerms * L, q, L, K, wr, ir);
 #pragma unroll
-                for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + j], acc[r]);
+                for (int t = 0; t < kKlaneTerms; ++t) {
+                    if (kb + q + t * L < K) {
+                        const float wv = to_f32<XT>(wc[t]);
+#pragma unroll
+                        for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + ic[t]], acc[r]);
+                    }
+                }
             }
         }
         // next row's first terms: in flight during the reduction and the stores
         const int sn = s + groups;
-        if (sn < min(s_end, n_active) && q < K) {
-            w0 = to_f32<XT>(W_c[(size_t)sn * K + q]);
-            j0 = idx[(size_t)sn * K + q];
-        }
+        if (sn < min(s_end, n_active)) klane_request<XT>(W_c, idx, (size_t)sn * K, 0, q, L, K, wr, ir);
         for (int off = L >> 1; off > 0; off >>= 1) {
 #pragma unroll
             for (int r = 0; r < RB; ++r) acc[r] += __shfl_xor(acc[r], off, kWave);
@@ -193,7 +206,7 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     if (a.B == 0 || n_slots == 0) return SRIGL_OK;
     // lanes per stored row: enough that a lane has at most ~4 terms, at least 4, at most 64
     int L = t && t->lanes_per_neuron ? t->lanes_per_neuron : 0;
-    if (L == 0) { L = 4; while (L < 64 && L * 4 < a.K) L <<= 1; }
+    if (L == 0) { L = 4; while (L < 64 && L * kKlaneTerms < a.K) L <<= 1; }
     if (L < 1 || L > 64 || (L & (L - 1)) != 0) return SRIGL_ERR_UNSUPPORTED;
     int RB = t && t->rows_per_block ? t->rows_per_block : 0;
     if (RB == 0) { RB = 1; while (RB < 8 && RB < a.B) RB <<= 1; }
