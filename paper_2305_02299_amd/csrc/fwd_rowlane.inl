@@ -240,17 +240,20 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         u_col[i] = (u < units) ? ct * 16 : 0x40000000;   // units past the tile never pass the column tests below
     }
     float st[kStageUnits][4];
-#define SRIGL_STAGE_LOAD(c)                                                                                     \
-    _Pragma("unroll") for (int i = 0; i < kStageUnits; ++i) {                                                   \
+#define SRIGL_STAGE_LOAD_UNITS(c, u_first, u_last)                                                              \
+    _Pragma("unroll") for (int u_ = 0; u_ < kStageUnits; ++u_) {                                                \
         const int c0_ = (c) * C;                                                                                \
-        if (FAST) {                                                                                             \
-            if (c0_ + u_col[i] < d_in) load4<XT>(x + (g_off[i] + (unsigned)c0_), true, 4, st[i]);               \
-        } else {                                                                                                \
-            st[i][0] = st[i][1] = st[i][2] = st[i][3] = 0.0f;                                                   \
-            const int nv = min(4, d_in - (c0_ + u_col[i] + dq * 4));                                            \
-            if (u_col[i] < C && nv > 0) load4<XT>(x + (g_off[i] + (unsigned)c0_), false, nv, st[i]);            \
+        if (u_ >= (u_first) && u_ < (u_last)) {                                                                 \
+            if (FAST) {                                                                                         \
+                if (c0_ + u_col[u_] < d_in) load4<XT>(x + (g_off[u_] + (unsigned)c0_), true, 4, st[u_]);        \
+            } else {                                                                                            \
+                st[u_][0] = st[u_][1] = st[u_][2] = st[u_][3] = 0.0f;                                           \
+                const int nv = min(4, d_in - (c0_ + u_col[u_] + dq * 4));                                       \
+                if (u_col[u_] < C && nv > 0) load4<XT>(x + (g_off[u_] + (unsigned)c0_), false, nv, st[u_]);     \
+            }                                                                                                   \
         }                                                                                                       \
     }
+#define SRIGL_STAGE_LOAD(c) SRIGL_STAGE_LOAD_UNITS(c, 0, kStageUnits)
 #define SRIGL_STAGE_STORE()                                                                                     \
     _Pragma("unroll") for (int i = 0; i < kStageUnits; ++i) {                                                   \
         if (u_col[i] < C) {                                                                                     \
@@ -292,9 +295,6 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     const char* xb = reinterpret_cast<const char*>(lds) + lane * (R * 4);
     for (int c = 0; c < n_chunks; ++c) {
         const bool more = (c + 1 < n_chunks);
-        if (more) {
-            SRIGL_STAGE_LOAD(c + 1)                       // in flight during the arithmetic below
-        }
         int k0n[NPW], nn[NPW];
 #pragma unroll
         for (int i = 0; i < NPW; ++i) {
@@ -304,6 +304,9 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         if (more && c + 2 - cb > kWave - 1) { cb = c + 1; SRIGL_LOAD_BOUNDS() }   // boundaries c+1, c+2 stay in the register
 #pragma unroll
         for (int i = 0; i < NPW; ++i) {
+            // the next chunk's activations: a share of the staging loads goes out before each stored row's arithmetic,
+            // so that the vector-memory queue never takes the whole burst at once
+            if (more) { SRIGL_STAGE_LOAD_UNITS(c + 1, (i * kStageUnits) / NPW, ((i + 1) * kStageUnits) / NPW) }
             const int n_terms = nn[i];
             V xa[GroupSize<R>::value], xc[GroupSize<R>::value];
             if (n_terms > 0) {
@@ -343,6 +346,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     }
 #undef SRIGL_LOAD_BOUNDS
 #undef SRIGL_STAGE_LOAD
+#undef SRIGL_STAGE_LOAD_UNITS
 #undef SRIGL_STAGE_STORE
 #undef SRIGL_PRELOAD
 
