@@ -50,6 +50,85 @@ def algorithmic_bytes(n_active, K, B, d_in, d_out, elem):
     return n_active * K * (elem + 4) + B * d_in * elem + B * d_out * 4 + d_out * 4 + n_active * 4
 
 
+def sweep(args):
+    """--sweep: every named configuration and the sparsity x batch grid, one JSON line per point (cold and warm
+    us/call from a HIP graph of the calls, effective GFLOP/s, algorithmic GB/s, dense torch matmul as context)."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2305_02299_amd import binding as B_
+    from paper_2305_02299_amd import condense_layer
+
+    torch.cuda.set_device(0)
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def time_graph(fn, steps, warmup):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for i in range(warmup):
+                fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            e0, e1 = ev(), ev()
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) / steps
+            best = t if best is None else min(best, t)
+        return best
+
+    points = [("c1", si.config("c1"), 1), ("c2", si.config("c2"), 256), ("c3", si.config("c3", B=1), 1),
+              ("c3", si.config("c3", B=256), 256)]
+    for (d_in, d_out, sp, K, B) in si.sweep_points():
+        points.append(("sweep %d->%d @%d%%" % (d_in, d_out, sp), si.make_layer(d_in, d_out, K, B, seed=0), B))
+    if not args.no_large:
+        points.append(("c5", si.config("c5"), 2048))
+    for label, L, B in points:
+        bf16 = L.dtype == "bf16"
+        Wsrc, xsrc = (L.W_bf16, L.x_bf16) if bf16 else (L.W, L.x)
+        layer = condense_layer(dev(Wsrc), dev(L.mask), L.K, dev(L.bias))
+        elem = 2 if bf16 else 4
+        nbytes = algorithmic_bytes(layer.n_active, L.K, B, L.d_in, L.d_out, elem)
+        n_sets = min(max(2, -(-2 * CACHE_BYTES // nbytes)), 300)
+        xs = dev(xsrc)
+        sets = [(xs.clone(), layer.W_c.clone(), layer.idx.clone(), None if layer.active is None else layer.active.clone(),
+                 layer.bias.clone(), layer.seg.clone(), torch.empty((B, L.d_out), device="cuda")) for _ in range(n_sets)]
+
+        def f_on(ss):
+            def f(i):
+                x, W_c, idx, act, bias, seg, y = ss[i % len(ss)]
+                B_.srigl_condensed_linear_fwd(x, B, L.d_in, W_c, idx, act, layer.n_active, L.K, bias, L.d_out, y, seg)
+            return f
+        steps = max(20, min(400, int(20000 / max(1.0, nbytes / 4e5))))
+        cold = time_graph(f_on(sets), max(steps, n_sets), 10) * 1e3
+        warm = time_graph(f_on(sets[:1]), steps, 10) * 1e3
+        Wm = dev((L.W * L.mask).astype(np.float32))
+        Wd = Wm.to(torch.bfloat16) if bf16 else Wm
+        xd = dev(L.x).to(torch.bfloat16) if bf16 else dev(L.x)
+        dense = time_graph(lambda i: torch.matmul(xd, Wd.t()), min(steps, 100), 5) * 1e3
+        flops = 2.0 * B * layer.n_active * L.K
+        print(json.dumps({"point": label, "d_in": L.d_in, "d_out": L.d_out, "K": L.K, "n_active": layer.n_active, "B": B,
+                          "dtype": L.dtype, "us_cold": round(cold, 2), "us_warm": round(warm, 2),
+                          "gbs_cold": round(nbytes / cold / 1e3, 1), "hbm_frac_cold": round(nbytes / cold / 1e3 / HBM_PEAK_GBS, 4),
+                          "gflops_cold": round(flops / cold / 1e3, 1), "gflops_warm": round(flops / warm / 1e3, 1),
+                          "algorithmic_bytes": nbytes, "torch_dense_matmul_us": round(dense, 2)}), flush=True)
+        del sets, layer
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,10 +137,15 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane"])
+    ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")
+    ap.add_argument("--no-large", action="store_true", help="--sweep without the 4096->16384 bf16 layer")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus)
         sys.exit(2)
+
+    if args.sweep:
+        return sweep(args)
 
     import torch
 
