@@ -127,13 +127,15 @@ srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int3
 /* Launch-shape knobs of the forward kernels (host struct).  0 in a field = the library's default.
  * Values the kernels cannot run are rejected with SRIGL_ERR_UNSUPPORTED, never launched. */
 typedef struct {
-    int32_t rows_per_lane;    /* ROWLANE: batch rows per lane, 1, 2 or 4 (batch tile = 64 * rows_per_lane) */
+    int32_t rows_per_lane;    /* ROWLANE: batch rows per lane, 1 or 2                                       */
     int32_t waves;            /* ROWLANE: wavefronts per workgroup, 1..16                                  */
     int32_t neurons_per_wave; /* ROWLANE: stored neurons accumulated per wavefront, 1..8                   */
     int32_t chunk_cols;       /* ROWLANE: activation columns per LDS tile, multiple of 64                  */
     int32_t lanes_per_neuron; /* KLANE: lanes that share one neuron, power of two 1..64                    */
     int32_t rows_per_block;   /* KLANE: batch rows staged per workgroup, 1, 2, 4 or 8                      */
-    int32_t reserved[2];
+    int32_t term_slices;      /* ROWLANE: 1, 2 or 4 groups of lanes that work on different terms of a stored
+                                 row at once (batch tile = 64 * rows_per_lane / term_slices rows)           */
+    int32_t reserved[1];
 } srigl_fwd_tuning;
 
 /* Same, with the algorithm and launch shape forced (for tests and measurements).  tuning may be

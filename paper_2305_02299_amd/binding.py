@@ -36,7 +36,7 @@ class SriglError(RuntimeError):
 class FwdTuning(ctypes.Structure):
     _fields_ = [("rows_per_lane", ctypes.c_int32), ("waves", ctypes.c_int32), ("neurons_per_wave", ctypes.c_int32),
                 ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32), ("rows_per_block", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 2)]
+                ("term_slices", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
 
 
 def _load() -> ctypes.CDLL:
@@ -144,10 +144,7 @@ def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, 
         if tuning is not None:
             tn = FwdTuning()
             for k, v in tuning.items():
-                if k == "dbg":
-                    tn.reserved[0] = int(v)
-                else:
-                    setattr(tn, k, int(v))
+                setattr(tn, k, int(v))
         st = lib.srigl_condensed_linear_fwd_algo(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
                                                  _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
                                                  int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())

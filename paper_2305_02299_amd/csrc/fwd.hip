@@ -236,12 +236,22 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
         (long long)a.n_active * a.seg_stride >= (1LL << 31)) return p;
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
     p.R = t && t->rows_per_lane ? t->rows_per_lane : 1;
-    if (p.R != 1 && p.R != 2 && p.R != 4) return p;
+    p.H = t && t->term_slices ? t->term_slices : 0;
+    if (p.R != 1 && p.R != 2) return p;
     // fast staging: whole 16-column units, rows aligned for 4-element vector loads
     const size_t xal = (a.x_bf16 ? 2 : 4) * 4;
     p.fast = (a.d_in % 16 == 0) && ((reinterpret_cast<uintptr_t>(a.x) % xal) == 0);
-    if (!p.fast && p.R != 1) return p;
-    const int BT = kWave * p.R, S = BT + 4;
+    if (p.H == 0) {
+        // A workgroup stages (rows per tile) x d_in activations.  For wide inputs and batches of a few tiles the
+        // staging outweighs the arithmetic of the few stored rows a workgroup gets, so the tile gets fewer rows
+        // (more term slices); measured on 768- and 3072-wide layers.  Large batches amortise it: 64-row tiles.
+        p.H = 1;
+        if (p.fast && p.R == 1 && a.B <= 512) p.H = a.d_in <= 1024 ? 1 : (a.d_in <= 2048 ? 2 : 4);
+    }
+    if (p.H != 1 && p.H != 2 && p.H != 4) return p;
+    if (p.H > 1 && p.R != 1) return p;
+    if (!p.fast && (p.R != 1 || p.H != 1)) return p;
+    const int BT = kWave * p.R / p.H, S = BT + 4;
     p.n_btiles = (a.B + BT - 1) / BT;
     const int nw_max = rowlane_max_threads(p.R) / kWave;
     p.NW = t && t->waves ? t->waves : nw_max;

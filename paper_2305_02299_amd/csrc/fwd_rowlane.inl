@@ -153,36 +153,40 @@ __device__ __forceinline__ void pipe_groups(float (&acc)[R], const float (&wv)[N
     group_fmacs<R, G % GPB>(acc, wv[G / GPB], cur);
 }
 
-// 16 consecutive terms of stored-row data starting at term index t0 (wave-uniform): lane l requests term
-// l mod 16.  The loads are unconditional (the term index is clamped into the arrays) and nothing here
-// consumes their result, so that they stay in flight; finish_terms() turns the raw words into a
-// weight and an LDS byte offset when the block is about to be used.
+// One block of terms of stored-row data starting at term index t0 (wave-uniform): the lane at position l16 of
+// slice p requests term t0 + tofs, tofs = H * l16 + p (16 * H consecutive terms per block, one vector load per
+// array).  The loads are unconditional (the term index is clamped into the arrays) and nothing here consumes their
+// result, so that they stay in flight; finish_terms() turns the raw words into a weight and an LDS byte offset
+// when the block is about to be used.
 template <typename XT>
-__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const int32_t* __restrict__ idx, int t0, int l16, int t_last,
+__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const int32_t* __restrict__ idx, int t0, int tofs, int t_last,
                                               XT& w_raw, int& i_raw) {
-    const unsigned t = (unsigned)min(t0 + l16, t_last);
-    w_raw = W_c[t];
-    i_raw = idx[t];
+    // 32-bit unsigned byte offsets from the (wave-uniform) array bases: one address instruction per load
+    const unsigned t = (unsigned)min(t0 + tofs, t_last);
+    w_raw = *reinterpret_cast<const XT*>(reinterpret_cast<const char*>(W_c) + t * (unsigned)sizeof(XT));
+    i_raw = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(idx) + t * 4u);
 }
-// n_valid (wave-uniform, may be <= 0) of the 16 terms are real; the others become (weight 0, all-zero column).
+// n_valid (wave-uniform, may be <= 0) of the block's terms are real; the others become (weight 0, all-zero column).
 template <typename XT>
-__device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, int l16, int off_mul, int off_add, int zero_off,
+__device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, int tofs, int off_mul, int off_add, int zero_off,
                                              float& wv, int& ov) {
-    const bool real = l16 < n_valid;
+    const bool real = tofs < n_valid;
     wv = real ? rl_to_f32<XT>(w_raw) : 0.0f;
     ov = real ? i_raw * off_mul + off_add : zero_off;
 }
 
-template <int R, int NPW, int KPRE, typename XT, bool FAST>
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST>
 __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                       const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
                                                       int C, int n_chunks, int n_btiles, int n_groups) {
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
-    constexpr int BT = kWave * R;
+    constexpr int LR = kWave / H;            // lanes per term slice
+    constexpr int BT = LR * R;               // batch rows per tile
     constexpr int S = BT + 4;
     constexpr int S4 = S * 4;
+    constexpr int TB = kBlock * H;           // terms per block (16 steps of H terms)
     using V = typename RowVec<R>::type;
 
     // XCD-aware decode: consecutive workgroup ids go to different XCDs (8 of them), so the id modulo 8
@@ -196,7 +200,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int l16 = lane & (kBlock - 1);
+    const int rowl = lane & (LR - 1);        // this lane's first row inside the tile is rowl * R
+    const int tofs = H * (lane & (kBlock - 1)) + lane / LR;   // this lane's term inside a block
     const int wv_id = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nw = blockDim.x >> 6;
     const int NG = nw * NPW;                 // stored rows (slots) per workgroup
@@ -269,7 +274,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     {                                                                                                           \
         const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
         _Pragma("unroll") for (int p = 0; p < KPRE; ++p)                                                        \
-            request_terms<XT>(W_c, idx, (s0 + (i)) * K + k0_ + p * kBlock, l16, t_last, rw[i][p], ri[i][p]);    \
+            request_terms<XT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, tofs, t_last, rw[i][p], ri[i][p]);      \
     }
 
     float acc[NPW][R];
@@ -282,7 +287,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
-        for (int p = 0; p < KPRE; ++p) request_terms<XT>(W_c, idx, (s0 + i) * K + p * kBlock, l16, t_last, rw[i][p], ri[i][p]);
+        for (int p = 0; p < KPRE; ++p) request_terms<XT>(W_c, idx, (s0 + i) * K + p * TB, tofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
     SRIGL_STAGE_LOAD(0)
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
@@ -292,7 +297,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     __syncthreads();
     SRIGL_STAMP(3)
 
-    const char* xb = reinterpret_cast<const char*>(lds) + lane * (R * 4);
+    const char* xb = reinterpret_cast<const char*>(lds) + rowl * (R * 4);
     for (int c = 0; c < n_chunks; ++c) {
         const bool more = (c + 1 < n_chunks);
         int k0n[NPW], nn[NPW];
@@ -314,22 +319,22 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 int po[KPRE];
 #pragma unroll
                 for (int p = 0; p < KPRE; ++p)
-                    finish_terms<XT>(rw[i][p], ri[i][p], n_terms - p * kBlock, l16, S4, -c * C * S4, zero_off, pw[p], po[p]);
+                    finish_terms<XT>(rw[i][p], ri[i][p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p]);
                 group_reads<R, 0>(xa, po[0], xb);
-                pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, n_terms, xa, xc);
+                pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, (n_terms + H - 1) / H, xa, xc);
                 // long ranges: the remaining blocks, one at a time, each requested one block ahead
-                if (n_terms > KPRE * kBlock) {
+                if (n_terms > KPRE * TB) {
                     const int row = (s0 + i) * K + k0n[i];
                     XT wr;
                     int ir;
-                    request_terms<XT>(W_c, idx, row + KPRE * kBlock, l16, t_last, wr, ir);
-                    for (int kb = KPRE * kBlock; kb < n_terms; kb += kBlock) {
+                    request_terms<XT>(W_c, idx, row + KPRE * TB, tofs, t_last, wr, ir);
+                    for (int kb = KPRE * TB; kb < n_terms; kb += TB) {
                         float wc[1];
                         int oc[1];
-                        finish_terms<XT>(wr, ir, n_terms - kb, l16, S4, -c * C * S4, zero_off, wc[0], oc[0]);
-                        if (kb + kBlock < n_terms) request_terms<XT>(W_c, idx, row + kb + kBlock, l16, t_last, wr, ir);
+                        finish_terms<XT>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
+                        if (kb + TB < n_terms) request_terms<XT>(W_c, idx, row + kb + TB, tofs, t_last, wr, ir);
                         group_reads<R, 0>(xa, oc[0], xb);
-                        pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, n_terms - kb, xa, xc);
+                        pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, (n_terms - kb + H - 1) / H, xa, xc);
                     }
                 }
             }
@@ -356,7 +361,12 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
-        for (int r = 0; r < R; ++r) lds[(lane * R + r) * OS + wv_id * NPW + i] = acc[i][r];
+        for (int r = 0; r < R; ++r) {
+            float v = acc[i][r];
+            if constexpr (H >= 2) v += __shfl_xor(v, LR, kWave);        // the slices hold partial sums of the same rows
+            if constexpr (H >= 4) v += __shfl_xor(v, 2 * LR, kWave);
+            if (lane < LR) lds[(rowl * R + r) * OS + wv_id * NPW + i] = v;
+        }
     __syncthreads();
 
     // lane <-> slot of the workgroup (two slots per lane cover NG <= 128)
@@ -397,9 +407,9 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     SRIGL_STAMP(14)
 }
 
-template <int R, int NPW, int KPRE, typename XT, bool FAST>
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST>
 static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
-    auto kern = k_fwd_rowlane<R, NPW, KPRE, XT, FAST>;
+    auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST>;
     static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
     if (p.lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
@@ -414,24 +424,23 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
     return hip_ok(hipGetLastError());
 }
 
-template <int R, int NPW, typename XT>
+template <int R, int H, int NPW, typename XT>
 static srigl_status launch_rowlane_k(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     constexpr int KPRE = rowlane_kpre(NPW);
-    if (p.fast) return launch_rowlane_f<R, NPW, KPRE, XT, true>(a, p, st);
-    if constexpr (R == 1) return launch_rowlane_f<R, NPW, KPRE, XT, false>(a, p, st);
-    return SRIGL_ERR_UNSUPPORTED;   // the planner keeps R = 1 when the fast staging does not apply
+    if (p.fast) return launch_rowlane_f<R, H, NPW, KPRE, XT, true>(a, p, st);
+    if constexpr (R == 1 && H == 1) return launch_rowlane_f<R, H, NPW, KPRE, XT, false>(a, p, st);
+    return SRIGL_ERR_UNSUPPORTED;   // the planner keeps R = 1, H = 1 when the fast staging does not apply
 }
 
-template <int R, typename XT>
+template <int R, int H, typename XT>
 static srigl_status launch_rowlane_r(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     constexpr int MAXN = rowlane_max_npw(R);
     switch (p.NPW) {
-        case 1: return launch_rowlane_k<R, 1, XT>(a, p, st);
-        case 2: return launch_rowlane_k<R, 2, XT>(a, p, st);
-        case 3: return launch_rowlane_k<R, 3, XT>(a, p, st);
-        case 4: return launch_rowlane_k<R, 4, XT>(a, p, st);
-        case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, 6, XT>(a, p, st); else break;
-        case 8: if constexpr (MAXN >= 8) return launch_rowlane_k<R, 8, XT>(a, p, st); else break;
+        case 1: return launch_rowlane_k<R, H, 1, XT>(a, p, st);
+        case 2: return launch_rowlane_k<R, H, 2, XT>(a, p, st);
+        case 3: return launch_rowlane_k<R, H, 3, XT>(a, p, st);
+        case 4: return launch_rowlane_k<R, H, 4, XT>(a, p, st);
+        case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, H, 6, XT>(a, p, st); else break;
         default: break;
     }
     return SRIGL_ERR_UNSUPPORTED;
@@ -439,10 +448,11 @@ static srigl_status launch_rowlane_r(const FwdArgs& a, const RowlanePlan& p, hip
 
 template <typename XT>
 static srigl_status launch_rowlane_x(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
-    switch (p.R) {
-        case 1: return launch_rowlane_r<1, XT>(a, p, st);
-        case 2: return launch_rowlane_r<2, XT>(a, p, st);
-        case 4: return launch_rowlane_r<4, XT>(a, p, st);
+    switch (p.R * 10 + p.H) {
+        case 11: return launch_rowlane_r<1, 1, XT>(a, p, st);
+        case 12: return launch_rowlane_r<1, 2, XT>(a, p, st);
+        case 14: return launch_rowlane_r<1, 4, XT>(a, p, st);
+        case 21: return launch_rowlane_r<2, 1, XT>(a, p, st);
         default: return SRIGL_ERR_UNSUPPORTED;
     }
 }

@@ -29,18 +29,16 @@ struct FwdArgs {
 
 // Launch shape of the ROWLANE kernel, decided on the host.
 struct RowlanePlan {
-    int R, NW, NPW, KPRE, C, n_chunks, n_btiles, n_groups;
+    int R, H, NW, NPW, KPRE, C, n_chunks, n_btiles, n_groups;
     size_t lds;
     bool fast;   // x rows allow aligned 4-element loads and d_in is a multiple of 16
     bool ok;
 };
 constexpr int kStageUnits = 8;   // 16x16 staging units a wavefront holds in registers per chunk
 constexpr int kBlock = 16;       // terms per vector load of W_c / idx (one DPP row)
-// workgroup size limit by rows per lane: R = 4 keeps 16 data + 4 accumulator registers per term group and
-// stored row, which needs the 256-register budget of 8 wavefronts
-constexpr int rowlane_max_threads(int R) { return R == 4 ? 512 : 1024; }
+constexpr int rowlane_max_threads(int) { return 1024; }
 // stored rows per wavefront the register budget allows without spilling
-constexpr int rowlane_max_npw(int R) { return R == 1 ? 6 : (R == 2 ? 4 : 8); }
+constexpr int rowlane_max_npw(int R) { return R == 1 ? 6 : 4; }
 // blocks of 16 terms per (stored row, chunk) kept in registers, by stored rows per wavefront
 constexpr int rowlane_kpre(int npw) { return npw <= 3 ? 3 : (npw <= 4 ? 2 : 1); }
 srigl_status launch_rowlane_f32(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);

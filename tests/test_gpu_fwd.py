@@ -35,7 +35,7 @@ def run_gpu(L, W_c, idx, active, bias, algo=None, tuning=None, seg=True, x=None)
     return out[GUARD:GUARD + Bn * d_out].reshape(Bn, d_out).copy()
 
 
-def check_layer(L, algo, tuning=None, bias=True, seg=True):
+def check_layer(L, algo, tuning=None, bias=True, seg=True, unsupported_ok=False):
     W_c, idx, active = oracle_condensed(L)
     bias_v = L.bias if bias else None
     xsrc = L.x_bf16 if L.dtype == "bf16" else L.x
@@ -45,6 +45,8 @@ def check_layer(L, algo, tuning=None, bias=True, seg=True):
         y = run_gpu(L, W_c, idx, act_arg, bias_v, algo, tuning, seg)
     except B_.SriglError as e:
         if e.status == B_.ERR_UNSUPPORTED and algo is not None:
+            if unsupported_ok:
+                return None
             pytest.skip("algorithm does not run these sizes")
         raise
     worst = gate(y, y_ref, S, TOL_BF16 if L.dtype == "bf16" else TOL_F32)
@@ -112,16 +114,21 @@ def test_no_bias_and_no_seg(algo):
 
 @pytest.mark.parametrize("tuning", [
     {"rows_per_lane": 1, "waves": 4, "neurons_per_wave": 1, "chunk_cols": 64},
-    {"rows_per_lane": 1, "waves": 16, "neurons_per_wave": 8, "chunk_cols": 256},
+    {"rows_per_lane": 1, "waves": 16, "neurons_per_wave": 6, "chunk_cols": 256},
     {"rows_per_lane": 2, "waves": 8, "neurons_per_wave": 3, "chunk_cols": 128},
-    {"rows_per_lane": 2, "waves": 2, "neurons_per_wave": 6, "chunk_cols": 256},
-    {"rows_per_lane": 4, "waves": 8, "neurons_per_wave": 2, "chunk_cols": 128},
-    {"rows_per_lane": 4, "waves": 16, "neurons_per_wave": 4, "chunk_cols": 64},
+    {"rows_per_lane": 2, "waves": 16, "neurons_per_wave": 4, "chunk_cols": 256},
+    {"term_slices": 2, "waves": 16, "neurons_per_wave": 3},
+    {"term_slices": 2, "waves": 8, "neurons_per_wave": 6, "chunk_cols": 192},
+    {"term_slices": 4, "waves": 8, "neurons_per_wave": 6},
+    {"term_slices": 4, "waves": 16, "neurons_per_wave": 2, "chunk_cols": 128},
+    {"term_slices": 4, "waves": 2, "neurons_per_wave": 1, "chunk_cols": 64},
 ])
 def test_rowlane_launch_shapes(tuning):
-    for (d_in, d_out, K, B, abl) in ((768, 300, 77, 300, 0.1), (3072, 96, 307, 70, 0.3), (1001, 64, 100, 257, 0.0)):
+    for (d_in, d_out, K, B, abl) in ((768, 300, 77, 300, 0.1), (3072, 96, 307, 70, 0.3), (1001, 64, 100, 257, 0.0),
+                                     (768, 40, 8, 17, 0.0), (1024, 50, 615, 33, 0.2)):
         L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=77)
-        check_layer(L, B_.FWD_ROWLANE, tuning)
+        ran = check_layer(L, B_.FWD_ROWLANE, tuning, unsupported_ok=True)
+        assert ran is not None or d_in % 16 != 0     # only the ragged-width layer may be refused (slow staging: H = R = 1)
 
 
 @pytest.mark.parametrize("tuning", [{"lanes_per_neuron": l, "rows_per_block": r} for l in (1, 4, 16, 64) for r in (1, 2, 4, 8)])
