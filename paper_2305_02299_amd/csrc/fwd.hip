@@ -209,7 +209,7 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     if (L == 0) { L = 4; while (L < 64 && L * kKlaneTerms < a.K) L <<= 1; }
     if (L < 1 || L > 64 || (L & (L - 1)) != 0) return SRIGL_ERR_UNSUPPORTED;
     int RB = t && t->rows_per_block ? t->rows_per_block : 0;
-    if (RB == 0) { RB = 1; while (RB < 8 && RB < a.B) RB <<= 1; }
+    if (RB == 0) RB = a.B > 4 ? 2 : 1;   // measured: one row per workgroup up to batch 4, two beat four and eight above
     while (RB > 1 && (size_t)RB * a.d_in * sizeof(float) > kLdsMax / 2) RB >>= 1;
     if (RB != 1 && RB != 2 && RB != 4 && RB != 8) return SRIGL_ERR_UNSUPPORTED;
     const int log2L = ilog2_floor(L);
@@ -247,6 +247,11 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
         // (more term slices); measured on 768- and 3072-wide layers.  Large batches amortise it: 64-row tiles.
         p.H = 1;
         if (p.fast && p.R == 1 && a.B <= 512) p.H = a.d_in <= 1024 ? 1 : (a.d_in <= 2048 ? 2 : 4);
+        // batches below one 64-row tile: a tile no taller than the batch keeps every lane on real rows
+        if (p.fast && p.R == 1) {
+            const int hb = a.B <= 16 ? 4 : (a.B <= 32 ? 2 : 1);
+            if (hb > p.H) p.H = hb;
+        }
     }
     if (p.H != 1 && p.H != 2 && p.H != 4) return p;
     if (p.H > 1 && p.R != 1) return p;
@@ -351,7 +356,7 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
         case SRIGL_FWD_AUTO: break;
         default: return SRIGL_ERR_INVALID_ARG;
     }
-    if (B >= 32 && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
+    if (B > 16 && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
     srigl_status s = launch_fwd_klane(a, nullptr, st);
     if (s == SRIGL_ERR_UNSUPPORTED) s = launch_fwd_generic(a, st);
     return s;
