@@ -22,10 +22,10 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with g++ (plain -O2, no vector or thread tuning)."""
+    """Compile the oracle with g++ (plain -O2; -fopenmp only serves the all-cores timing companion)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", tmp, _SRC])
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -116,3 +116,18 @@ def dense_masked_fwd(x: np.ndarray, W: np.ndarray, mask: np.ndarray, bias) -> np
     y = np.empty((B, d_out), dtype=np.float32)
     _load().oracle_dense_masked_fwd_f32(_p(x), B, d_in, _p(W), _p(mask), _p(bias), d_out, _p(y))
     return y
+
+
+def fwd_allcores(x, W_c, idx, active, bias, d_out):
+    """Timing companion (fp32 accumulate, OpenMP over batch x neurons): returns (y, threads used)."""
+    x = _c(x, np.float32)
+    W_c = _c(W_c, np.float32)
+    idx = _c(idx, np.int32)
+    active = _c(active, np.int32)
+    bias = _c(bias, np.float32)
+    B, d_in = x.shape
+    n_active, K = W_c.shape
+    y = np.empty((B, d_out), dtype=np.float32)
+    lib = _load()
+    lib.oracle_fwd_f32_allcores(_p(x), B, d_in, _p(W_c), _p(idx), _p(active), n_active, K, _p(bias), int(d_out), _p(y))
+    return y, int(lib.oracle_num_threads())

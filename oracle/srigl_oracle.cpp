@@ -31,6 +31,9 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 extern "C" {
 
@@ -167,6 +170,39 @@ void oracle_dense_masked_fwd_f32(const float* x, int B, int d_in, const float* W
                     acc += (double)W[(size_t)r * d_in + j] * (double)x[(size_t)b * d_in + j];
             y[(size_t)b * d_out + r] = (float)(acc + (bias ? (double)bias[r] : 0.0));
         }
+}
+
+// Timing companion of oracle_fwd_f32 (not used for parity): the same three loops of Alg. 1 with fp32
+// accumulation and the batch x neuron iterations spread over the host cores with OpenMP.  It exists so that
+// the benchmark can say what all host cores do with the plain loops; nothing else is changed or tuned.
+void oracle_fwd_f32_allcores(const float* x, int B, int d_in, const float* W_c, const int32_t* idx,
+                             const int32_t* active, int n_active, int K, const float* bias, int d_out, float* y) {
+#pragma omp parallel for schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int r = 0; r < d_out; ++r) y[(size_t)b * d_out + r] = bias ? bias[r] : 0.0f;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b) {
+        for (int n = 0; n < n_active; ++n) {
+            float acc = 0.0f;
+            for (int k = 0; k < K; ++k) acc += x[(size_t)b * d_in + idx[(size_t)n * K + k]] * W_c[(size_t)n * K + k];
+            const int col = active ? active[n] : n;
+            y[(size_t)b * d_out + col] = acc + (bias ? bias[col] : 0.0f);
+        }
+    }
+}
+
+int oracle_num_threads() {
+#ifdef _OPENMP
+    int n = 1;
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+    return n;
+#else
+    return 1;
+#endif
 }
 
 }  // extern "C"

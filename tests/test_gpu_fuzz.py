@@ -1,0 +1,59 @@
+"""Seeded random shapes through every forward algorithm and through condense, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from gpu_util import TOL_BF16, TOL_F32, dev, gate, host, oracle_condensed, oracle_seg
+from paper_2305_02299_amd import binding as B_
+from paper_2305_02299_amd import condense_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        d_in = int(rng.choice([16 * int(rng.integers(1, 80)), int(rng.integers(1, 1300))]))
+        d_out = int(rng.integers(1, 400))
+        K = int(rng.integers(1, min(d_in, 400) + 1))
+        B = int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 31, 33, 64, 65, 100, 129, 200]))
+        abl = float(rng.choice([0.0, 0.0, 0.1, 0.5, 0.9]))
+        dtype = "bf16" if rng.random() < 0.3 else "f32"
+        out.append((d_in, d_out, K, B, abl, dtype, 1000 + i))
+    return out
+
+
+@pytest.mark.parametrize("d_in,d_out,K,B,abl,dtype,seed", _cases(40, 2024))
+def test_random_layer_every_algorithm(d_in, d_out, K, B, abl, dtype, seed):
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=seed)
+    Wsrc, xsrc = (L.W_bf16, L.x_bf16) if dtype == "bf16" else (L.W, L.x)
+    W_c, idx, active = oracle.condense(Wsrc, L.mask, K)
+    # condense on the GPU: bit-exact, then forward from the GPU's own arrays
+    layer = condense_layer(dev(Wsrc), dev(L.mask), K, dev(L.bias))
+    n = len(active)
+    assert layer.n_active == n
+    assert np.array_equal(host(layer.idx), idx) and np.array_equal(host(layer.W_c), W_c)
+    if n < d_out:
+        assert np.array_equal(host(layer.active), active)
+    if n:
+        assert np.array_equal(host(layer.seg), oracle_seg(idx, d_in))
+    y_ref, S = oracle.fwd(xsrc, W_c, idx, active, L.bias, d_out, want_scale=True)
+    ablated = np.setdiff1d(np.arange(d_out), active)
+    ran = 0
+    for algo in (None, B_.FWD_GENERIC, B_.FWD_KLANE, B_.FWD_ROWLANE):
+        y = torch.full((B, d_out), 3.0e38, dtype=torch.float32, device="cuda")
+        try:
+            B_.srigl_condensed_linear_fwd(dev(xsrc), B, d_in, layer.W_c, layer.idx, layer.active, n, K, layer.bias, d_out, y,
+                                          layer.seg, algo=algo)
+        except B_.SriglError as e:
+            assert e.status == B_.ERR_UNSUPPORTED and algo is not None
+            continue
+        yh = host(y)
+        gate(yh, y_ref, S, TOL_BF16 if dtype == "bf16" else TOL_F32)
+        if len(ablated):
+            assert np.array_equal(yh[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (B, 1)).view(np.uint32))
+        ran += 1
+    assert ran >= 3

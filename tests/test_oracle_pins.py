@@ -258,3 +258,14 @@ def test_fwd_degenerate_shapes():
     # K = 0
     y = oracle.fwd(L.x, np.zeros((4, 0), np.float32), np.zeros((4, 0), np.int32), None, L.bias, 4)
     assert np.array_equal(y, np.tile(L.bias, (2, 1)))
+
+
+def test_allcores_timing_companion_agrees_with_the_oracle():
+    L = si.make_layer(256, 40, 30, 9, ablate_frac=0.2, seed=50)
+    W_c, idx, active = oracle.condense(L.W, L.mask, 30)
+    y, S = oracle.fwd(L.x, W_c, idx, active, L.bias, 40, want_scale=True)
+    y2, threads = oracle.fwd_allcores(L.x, W_c, idx, active, L.bias, 40)
+    assert threads >= 1
+    assert (np.abs(y2.astype(np.float64) - y) <= 1e-5 * np.maximum(np.abs(y), S)).all()
+    ablated = np.setdiff1d(np.arange(40), active)
+    assert np.array_equal(y2[:, ablated], y[:, ablated])
