@@ -232,7 +232,8 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     RowlanePlan p{};
     p.ok = false;
     // the kernel indexes x, W_c / idx and seg with 32-bit offsets
-    if ((long long)a.B * a.d_in >= (1LL << 31) || (long long)a.n_active * a.K >= (1LL << 31) ||
+    // (term indices are formed for up to 128 slots past the last stored row before they are clamped)
+    if ((long long)a.B * a.d_in >= (1LL << 31) || ((long long)a.n_active + 256) * a.K + 4096 >= (1LL << 31) ||
         (long long)a.n_active * a.seg_stride >= (1LL << 31)) return p;
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
     p.R = t && t->rows_per_lane ? t->rows_per_lane : 1;
@@ -300,8 +301,11 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     p.NPW = npw;
     p.KPRE = rowlane_kpre(npw);
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
-    const size_t out_tile = (size_t)BT * (p.NW * npw + 1) * sizeof(float);   // the result tile reuses the LDS
-    if (out_tile > p.lds) p.lds = out_tile;
+    // the result tile sits behind the activation tile when both fit (no barrier between the last term and the
+    // transposed write), else it reuses the activation tile's space
+    const size_t out_tile = (size_t)BT * (p.NW * npw + 1) * sizeof(float);
+    if (p.lds + out_tile <= 150 * 1024) { p.out_off = (int)(p.lds / sizeof(float)); p.lds += out_tile; }
+    else { p.out_off = 0; if (out_tile > p.lds) p.lds = out_tile; }
     if (p.lds > kLdsMax) return p;
     p.ok = true;
     return p;

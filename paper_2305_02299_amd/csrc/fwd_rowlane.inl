@@ -180,7 +180,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                                                       const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
-                                                      int C, int n_chunks, int n_btiles, int n_groups) {
+                                                      int C, int n_chunks, int n_btiles, int n_groups, int out_off) {
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
@@ -356,7 +356,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #undef SRIGL_PRELOAD
 
     // ---- results: transpose through LDS, then bias + scatter with row-contiguous stores ----
-    __syncthreads();                                       // every wavefront is done reading the x tile
+    if (out_off == 0) __syncthreads();                     // shared space: every wavefront must be done reading the x tile
+    float* const out = lds + out_off;
     const int OS = NG + 1;                                 // odd stride: conflict-free transposed writes
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             float v = acc[i][r];
             if constexpr (H >= 2) v += __shfl_xor(v, LR, kWave);        // the slices hold partial sums of the same rows
             if constexpr (H >= 4) v += __shfl_xor(v, 2 * LR, kWave);
-            if (lane < LR) lds[(rowl * R + r) * OS + wv_id * NPW + i] = v;
+            if (lane < LR) out[(rowl * R + r) * OS + wv_id * NPW + i] = v;
         }
     __syncthreads();
 
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             if (col < 0) continue;
             if (active)
                 for (int cc = prevv[h]; cc < col; ++cc) yr[cc] = rl_bias_at(bias, cc);
-            if (sg0 + i < n_active && col < d_out) yr[col] = lds[row * OS + i] + biasv[h];
+            if (sg0 + i < n_active && col < d_out) yr[col] = out[row * OS + i] + biasv[h];
         }
     }
     SRIGL_STAMP(14)
@@ -420,7 +421,7 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
     if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
                        a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
-                       p.n_groups);
+                       p.n_groups, p.out_off);
     return hip_ok(hipGetLastError());
 }
 
