@@ -148,6 +148,26 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
                                              const uint16_t* seg, srigl_fwd_algo algo,
                                              const srigl_fwd_tuning* tuning, void* stream);
 
+/* ---- structured-only representation -----------------------------------------------------------------
+ * Sec. 4.4 / Fig. 4 / App. H compare the condensed layer with the same layer "accelerated using only the
+ * ablated neurons without exploiting the fine-grained sparsity": the stored neurons keep dense rows, and
+ * the paper finds it faster at larger batch and modest sparsity, from the same set of weights.
+ *
+ * srigl_densify: Wd[n_active][d_in] (w_dtype) <- the condensed rows scattered to their columns, zero
+ * elsewhere (bit copies).  idx as in the forward call (in range; not checked here).
+ *
+ * srigl_structured_linear_fwd: y[b][active[s]] = bias[active[s]] + sum_j Wd[s][j] * x[b][j] on the matrix
+ * cores (fp32 MFMA for F32 storage; bf16 MFMA with fp32 accumulate for BF16 storage), other columns = bias.
+ * Same argument conventions as srigl_condensed_linear_fwd.  x and Wd must be 16-byte aligned and d_in a
+ * multiple of 16 bytes' worth of elements (4 for F32, 8 for BF16), else SRIGL_ERR_UNSUPPORTED.
+ */
+srigl_status srigl_densify(const void* W_c, srigl_dtype w_dtype, const int32_t* idx, int32_t n_active, int32_t K,
+                           int32_t d_in, void* Wd, void* stream);
+
+srigl_status srigl_structured_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
+                                         srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
+                                         const float* bias, int32_t d_out, float* y, void* stream);
+
 /* An empty kernel on `stream`: the dispatch floor against which microsecond-scale calls are read. */
 srigl_status srigl_launch_empty(void* stream);
 

@@ -118,6 +118,34 @@ def dense_masked_fwd(x: np.ndarray, W: np.ndarray, mask: np.ndarray, bias) -> np
     return y
 
 
+def densify(W_c: np.ndarray, idx: np.ndarray, d_in: int) -> np.ndarray:
+    """Dense rows of the stored neurons (structured-only representation): [n_active, d_in], same element type."""
+    assert W_c.dtype in (np.float32, np.uint16)
+    W_c = np.ascontiguousarray(W_c)
+    idx = _c(idx, np.int32)
+    n, K = W_c.shape
+    Wd = np.empty((n, d_in), dtype=W_c.dtype)
+    _load().oracle_densify(_p(W_c), W_c.dtype.itemsize, _p(idx), n, K, int(d_in), _p(Wd))
+    return Wd
+
+
+def structured_fwd(x: np.ndarray, Wd: np.ndarray, active, bias, d_out: int) -> np.ndarray:
+    bf16 = x.dtype == np.uint16
+    assert (Wd.dtype == np.uint16) == bf16
+    x = np.ascontiguousarray(x)
+    Wd = np.ascontiguousarray(Wd)
+    active = _c(active, np.int32)
+    bias = _c(bias, np.float32)
+    B, d_in = x.shape
+    n = Wd.shape[0]
+    if active is None:
+        assert n == d_out
+    y = np.empty((B, d_out), dtype=np.float32)
+    fn = _load().oracle_structured_fwd_bf16 if bf16 else _load().oracle_structured_fwd_f32
+    fn(_p(x), B, d_in, _p(Wd), _p(active), n, _p(bias), int(d_out), _p(y))
+    return y
+
+
 def fwd_allcores(x, W_c, idx, active, bias, d_out):
     """Timing companion (fp32 accumulate, OpenMP over batch x neurons): returns (y, threads used)."""
     x = _c(x, np.float32)

@@ -20,6 +20,8 @@
 //     Sec. 4.4: ablated neurons are dropped.  Reading: which entries are
 //     "non-zero" is decided by the mask, not by the value; columns appear in
 //     ascending order; stored neurons appear in ascending order.
+//   * oracle_densify / oracle_structured_fwd_* -- the structured-only representation of Sec. 4.4 /
+//     Fig. 4: ablated neurons removed, the remaining neurons' rows kept dense.
 //   * oracle_check_fanin_*       -- the constant fan-in invariant (Fig. 1a, Sec.
 //     3.1): every neuron that is not ablated has exactly k unmasked weights.
 //
@@ -170,6 +172,44 @@ void oracle_dense_masked_fwd_f32(const float* x, int B, int d_in, const float* W
                     acc += (double)W[(size_t)r * d_in + j] * (double)x[(size_t)b * d_in + j];
             y[(size_t)b * d_out + r] = (float)(acc + (bias ? (double)bias[r] : 0.0));
         }
+}
+
+// Structured-only representation (Sec. 4.4, Fig. 4 and App. H: the same layer "accelerated using only the
+// ablated neurons without exploiting the fine-grained sparsity"): the stored neurons keep dense rows.
+// densify: Wd[s][j] = W_c[s][t] where idx[s][t] == j, zero elsewhere (elements copied bit for bit).
+void oracle_densify(const void* W_c, int elem_bytes, const int32_t* idx, int n_active, int K, int d_in, void* Wd) {
+    const unsigned char* wc = static_cast<const unsigned char*>(W_c);
+    unsigned char* wd = static_cast<unsigned char*>(Wd);
+    std::memset(wd, 0, (size_t)n_active * d_in * elem_bytes);
+    for (int s = 0; s < n_active; ++s)
+        for (int t = 0; t < K; ++t)
+            std::memcpy(wd + ((size_t)s * d_in + idx[(size_t)s * K + t]) * elem_bytes, wc + ((size_t)s * K + t) * elem_bytes, elem_bytes);
+}
+
+// y[b][active[s]] = bias + sum over ALL j of Wd[s][j] * x[b][j]; other columns hold their bias.
+static void structured_generic(const float* xf, const uint16_t* xh, int B, int d_in, const float* wf, const uint16_t* wh,
+                               const int32_t* active, int n_active, const float* bias, int d_out, float* y) {
+    for (int b = 0; b < B; ++b)
+        for (int r = 0; r < d_out; ++r) y[(size_t)b * d_out + r] = bias ? bias[r] : 0.0f;
+    for (int b = 0; b < B; ++b)
+        for (int s = 0; s < n_active; ++s) {
+            double acc = 0.0;
+            for (int j = 0; j < d_in; ++j) {
+                double xv = xf ? (double)xf[(size_t)b * d_in + j] : (double)bf16_to_float(xh[(size_t)b * d_in + j]);
+                double wv = wf ? (double)wf[(size_t)s * d_in + j] : (double)bf16_to_float(wh[(size_t)s * d_in + j]);
+                acc += xv * wv;
+            }
+            const int col = active ? active[s] : s;
+            y[(size_t)b * d_out + col] = (float)(acc + (bias ? (double)bias[col] : 0.0));
+        }
+}
+void oracle_structured_fwd_f32(const float* x, int B, int d_in, const float* Wd, const int32_t* active, int n_active,
+                               const float* bias, int d_out, float* y) {
+    structured_generic(x, nullptr, B, d_in, Wd, nullptr, active, n_active, bias, d_out, y);
+}
+void oracle_structured_fwd_bf16(const uint16_t* x, int B, int d_in, const uint16_t* Wd, const int32_t* active, int n_active,
+                                const float* bias, int d_out, float* y) {
+    structured_generic(nullptr, x, B, d_in, nullptr, Wd, active, n_active, bias, d_out, y);
 }
 
 // Timing companion of oracle_fwd_f32 (not used for parity): the same three loops of Alg. 1 with fp32

@@ -23,7 +23,7 @@ FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE = range(4)
 EXPORTS = (
     "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense",
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
-    "srigl_copy_bytes", "srigl_status_str",
+    "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
 )
 
 
@@ -58,6 +58,10 @@ def _load() -> ctypes.CDLL:
     lib.srigl_condensed_linear_fwd_algo.restype = ctypes.c_int
     lib.srigl_condensed_linear_fwd_algo.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32,
                                                     vp, vp, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
+    lib.srigl_densify.restype = ctypes.c_int
+    lib.srigl_densify.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, vp, vp]
+    lib.srigl_structured_linear_fwd.restype = ctypes.c_int
+    lib.srigl_structured_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, vp]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -149,6 +153,17 @@ def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, 
                                                  _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
                                                  int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
     _check(st, "srigl_condensed_linear_fwd")
+
+
+def srigl_densify(W_c, idx, n_active, K, d_in, Wd):
+    _check(lib.srigl_densify(_ptr(W_c), _dtype_code(W_c), _ptr(idx), int(n_active), int(K), int(d_in), _ptr(Wd), _stream()),
+           "srigl_densify")
+
+
+def srigl_structured_linear_fwd(x, B, d_in, Wd, active, n_active, bias, d_out, y):
+    st = lib.srigl_structured_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(Wd), _dtype_code(Wd if Wd is not None else x), _ptr(active),
+                                         int(n_active), _ptr(bias), int(d_out), _ptr(y), _stream())
+    _check(st, "srigl_structured_linear_fwd")
 
 
 def srigl_launch_empty():

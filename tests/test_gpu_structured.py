@@ -1,0 +1,108 @@
+"""GPU parity of the structured-only representation (Sec. 4.4 / Fig. 4 / App. H): dense rows of the stored
+neurons, product on the matrix cores, against the oracle's plain loops."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from gpu_util import TOL_BF16, TOL_F32, dev, gate, host, oracle_condensed
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B_():
+    from paper_2305_02299_amd import binding
+    return binding
+
+
+def run_case(B_, L, tol, with_active=True):
+    W_c, idx, active = oracle_condensed(L)
+    n, K = W_c.shape
+    x = L.x_bf16 if L.dtype == "bf16" else L.x
+    Wd_ref = oracle.densify(W_c, idx, L.d_in)
+    Wd = torch.full((max(n, 1), L.d_in), 0x7fc1 if L.dtype == "bf16" else 0, dtype=torch.int16 if L.dtype == "bf16" else torch.float32,
+                    device="cuda")
+    if L.dtype != "bf16":
+        Wd.fill_(float("nan"))
+    B_.srigl_densify(dev(W_c), dev(idx), n, K, L.d_in, Wd)
+    got_Wd = host(Wd)[:n]
+    assert np.array_equal(got_Wd.view(np.uint16 if L.dtype == "bf16" else np.uint32),
+                          Wd_ref.view(np.uint16 if L.dtype == "bf16" else np.uint32))
+    y = torch.full((L.B, L.d_out), float("nan"), device="cuda")
+    B_.srigl_structured_linear_fwd(dev(x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y)
+    torch.cuda.synchronize()
+    y_ref = oracle.structured_fwd(x, Wd_ref, active, L.bias, L.d_out)
+    _, S = oracle.fwd(x, W_c, idx, active, L.bias, L.d_out, want_scale=True)
+    return gate(host(y), y_ref, S, tol)
+
+
+@pytest.mark.parametrize("name,B", [("c1", 1), ("c1", 16), ("c1", 256), ("c2", 1), ("c2", 64), ("c2", 256), ("c3", 256)])
+def test_named_configs_f32(B_, name, B):
+    L = si.config(name, B=B)
+    worst = run_case(B_, L, TOL_F32)
+    print("structured %s B=%d worst err/scale %.2e" % (name, B, worst))
+
+
+@pytest.mark.parametrize("d_in,d_out,K,B,abl", [
+    (64, 64, 8, 64, 0.0), (68, 33, 5, 7, 0.3), (132, 257, 13, 130, 0.2), (200, 129, 200, 65, 0.0),
+    (36, 300, 1, 129, 0.5), (1024, 96, 100, 300, 0.1), (4, 5, 2, 3, 0.0), (260, 640, 26, 513, 0.25),
+])
+def test_ragged_shapes_f32(B_, d_in, d_out, K, B, abl):
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=d_in * 7 + B)
+    run_case(B_, L, TOL_F32)
+
+
+@pytest.mark.parametrize("d_in,d_out,K,B,abl", [
+    (64, 64, 8, 64, 0.0), (72, 33, 5, 7, 0.3), (136, 257, 13, 130, 0.2), (1024, 1024, 102, 512, 0.1), (8, 5, 2, 3, 0.0),
+])
+def test_shapes_bf16(B_, d_in, d_out, K, B, abl):
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype="bf16", seed=d_in + B)
+    run_case(B_, L, TOL_BF16)
+
+
+def test_integer_inputs_bit_exact(B_):
+    """Small integers: every product and partial sum is exact in fp32, so any summation order gives the same bits."""
+    L = si.make_layer(256, 200, 20, 96, ablate_frac=0.2, seed=5)
+    rng = np.random.default_rng(9)
+    L.W[...] = rng.integers(-8, 9, L.W.shape).astype(np.float32)
+    L.x[...] = rng.integers(-8, 9, L.x.shape).astype(np.float32)
+    L.bias[...] = rng.integers(-8, 9, L.bias.shape).astype(np.float32)
+    W_c, idx, active = oracle.condense(L.W, L.mask, L.K)
+    n = W_c.shape[0]
+    Wd = torch.empty((n, L.d_in), device="cuda")
+    B_.srigl_densify(dev(W_c), dev(idx), n, L.K, L.d_in, Wd)
+    y = torch.empty((L.B, L.d_out), device="cuda")
+    B_.srigl_structured_linear_fwd(dev(L.x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y)
+    y_ref = oracle.fwd(L.x, W_c, idx, active, L.bias, L.d_out)
+    assert np.array_equal(host(y), y_ref)
+
+
+def test_all_ablated_and_no_active_list(B_):
+    L = si.make_layer(64, 40, 8, 9, ablate_frac=0.0, seed=3)
+    y = torch.full((L.B, L.d_out), float("nan"), device="cuda")
+    B_.srigl_structured_linear_fwd(dev(L.x), L.B, L.d_in, None, None, 0, dev(L.bias), L.d_out, y)
+    assert np.array_equal(host(y), np.broadcast_to(L.bias, (L.B, L.d_out)))
+    # every neuron stored, no active list, no bias
+    W_c, idx, active = oracle.condense(L.W, L.mask, L.K)
+    Wd_ref = oracle.densify(W_c, idx, L.d_in)
+    y = torch.full((L.B, L.d_out), float("nan"), device="cuda")
+    B_.srigl_structured_linear_fwd(dev(L.x), L.B, L.d_in, dev(Wd_ref), None, L.d_out, None, L.d_out, y)
+    y_ref, S = oracle.fwd(L.x, W_c, idx, None, None, L.d_out, want_scale=True)
+    gate(host(y), y_ref, S, TOL_F32)
+
+
+def test_argument_errors(B_):
+    from paper_2305_02299_amd.binding import SriglError
+    L = si.make_layer(66, 40, 8, 9, seed=3)      # 66 fp32 columns: rows are not multiples of 16 bytes
+    W_c, idx, active = oracle.condense(L.W, L.mask, L.K)
+    Wd = dev(oracle.densify(W_c, idx, L.d_in))
+    y = torch.empty((L.B, L.d_out), device="cuda")
+    with pytest.raises(SriglError) as e:
+        B_.srigl_structured_linear_fwd(dev(L.x), L.B, L.d_in, Wd, dev(active), len(active), dev(L.bias), L.d_out, y)
+    assert e.value.status == B_.ERR_UNSUPPORTED
+    with pytest.raises(SriglError):
+        B_.srigl_structured_linear_fwd(dev(L.x), L.B, L.d_in, Wd, dev(active), L.d_out + 1, dev(L.bias), L.d_out, y)
+    with pytest.raises(SriglError):
+        B_.srigl_densify(dev(W_c), dev(idx), len(active), L.d_in + 1, L.d_in, Wd)

@@ -269,3 +269,25 @@ def test_allcores_timing_companion_agrees_with_the_oracle():
     assert (np.abs(y2.astype(np.float64) - y) <= 1e-5 * np.maximum(np.abs(y), S)).all()
     ablated = np.setdiff1d(np.arange(40), active)
     assert np.array_equal(y2[:, ablated], y[:, ablated])
+
+
+# ----------------------------------------------------------------------------- structured-only representation
+@pytest.mark.parametrize("d_in,d_out,K,B,abl,dtype", [(64, 12, 5, 3, 0.25, "f32"), (768, 40, 77, 4, 0.3, "f32"), (128, 9, 128, 2, 0.0, "f32"),
+                                                      (96, 10, 7, 3, 0.2, "bf16")])
+def test_structured_only_representation(d_in, d_out, K, B, abl, dtype):
+    """Ablated neurons removed, remaining rows dense (Sec. 4.4 / Fig. 4): same result as the dense masked product."""
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=60)
+    Wsrc, xsrc = (L.W_bf16, L.x_bf16) if dtype == "bf16" else (L.W, L.x)
+    W_c, idx, active = oracle.condense(Wsrc, L.mask, K)
+    Wd = oracle.densify(W_c, idx, d_in)
+    # densify against plain indexing of the masked dense matrix (bit for bit)
+    exp = np.where(L.mask[active] != 0, Wsrc[active], np.zeros((), Wsrc.dtype))
+    assert Wd.dtype == Wsrc.dtype and np.array_equal(Wd.view(np.uint8), exp.view(np.uint8))
+    y = oracle.structured_fwd(xsrc, Wd, active, L.bias, d_out)
+    ref = _dense_ref(L.x, L.W, L.mask, L.bias)      # numpy float64 matmul; L.W / L.x hold the widened values for bf16
+    assert np.max(np.abs(y - ref)) <= np.max(np.abs(ref)) * 2.0 ** -23
+    ablated = np.setdiff1d(np.arange(d_out), active)
+    assert np.array_equal(y[:, ablated], np.tile(L.bias[ablated], (B, 1)))
+    # and the condensed oracle agrees (both are sums of the same non-zero terms in ascending column order)
+    yc = oracle.fwd(xsrc, W_c, idx, active, L.bias, d_out)
+    assert np.max(np.abs(y - yc)) <= np.max(np.abs(ref)) * 2.0 ** -23
