@@ -120,12 +120,21 @@ def sweep(args):
         Wd = Wm.to(torch.bfloat16) if bf16 else Wm
         xd = dev(L.x).to(torch.bfloat16) if bf16 else dev(L.x)
         dense = time_graph(lambda i: torch.matmul(xd, Wd.t()), min(steps, 100), 5) * 1e3
+        # structured-only form of the same layer (dense rows of the stored neurons, matrix cores)
+        structured = None
+        if (L.d_in * elem) % 16 == 0:
+            Wrows = torch.empty((max(layer.n_active, 1), L.d_in), dtype=layer.W_c.dtype, device="cuda")
+            B_.srigl_densify(layer.W_c, layer.idx, layer.n_active, L.K, L.d_in, Wrows)
+            ys = torch.empty((B, L.d_out), device="cuda")
+            structured = time_graph(lambda i: B_.srigl_structured_linear_fwd(xs, B, L.d_in, Wrows, layer.active, layer.n_active,
+                                                                            layer.bias, L.d_out, ys), min(steps, 100), 5) * 1e3
         flops = 2.0 * B * layer.n_active * L.K
         print(json.dumps({"point": label, "d_in": L.d_in, "d_out": L.d_out, "K": L.K, "n_active": layer.n_active, "B": B,
                           "dtype": L.dtype, "us_cold": round(cold, 2), "us_warm": round(warm, 2),
                           "gbs_cold": round(nbytes / cold / 1e3, 1), "hbm_frac_cold": round(nbytes / cold / 1e3 / HBM_PEAK_GBS, 4),
                           "gflops_cold": round(flops / cold / 1e3, 1), "gflops_warm": round(flops / warm / 1e3, 1),
-                          "algorithmic_bytes": nbytes, "torch_dense_matmul_us": round(dense, 2)}), flush=True)
+                          "algorithmic_bytes": nbytes, "torch_dense_matmul_us": round(dense, 2),
+                          "structured_only_us_warm": None if structured is None else round(structured, 2)}), flush=True)
         del sets, layer
 
 

@@ -168,6 +168,21 @@ srigl_status srigl_structured_linear_fwd(const void* x, srigl_dtype x_dtype, int
                                          srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
                                          const float* bias, int32_t d_out, float* y, void* stream);
 
+/* The same call with the workgroup tile forced (tests and tuning); SRIGL_TILE_AUTO is the library's own choice. */
+typedef enum srigl_gemm_tile {
+    SRIGL_TILE_AUTO = 0,
+    SRIGL_TILE_256x256 = 1,     /* 8 wavefronts of 128x64, 2 LDS stages */
+    SRIGL_TILE_256x256_W4 = 2,  /* 4 wavefronts of 128x128, 2 LDS stages */
+    SRIGL_TILE_256x128 = 3,     /* 4 wavefronts of 128x64, 3 LDS stages */
+    SRIGL_TILE_128x128 = 4,     /* 4 wavefronts of 64x64, 2 LDS stages */
+    SRIGL_TILE_128x128_S4 = 5,  /* 4 wavefronts of 64x64, 4 LDS stages */
+    SRIGL_TILE_64x64 = 6        /* 4 wavefronts of 32x32, 4 LDS stages */
+} srigl_gemm_tile;
+
+srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
+                                              srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
+                                              const float* bias, int32_t d_out, float* y, srigl_gemm_tile tile, void* stream);
+
 /* An empty kernel on `stream`: the dispatch floor against which microsecond-scale calls are read. */
 srigl_status srigl_launch_empty(void* stream);
 

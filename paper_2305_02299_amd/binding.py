@@ -19,11 +19,15 @@ LIB_PATH = os.path.join(_PKG, "libsrigl.so")
 OK, ERR_INVALID_ARG, ERR_FANIN, ERR_CAPACITY, ERR_INDEX_RANGE, ERR_UNSUPPORTED, ERR_HIP = range(7)
 F32, BF16 = 0, 1
 FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE = range(4)
+TILE_AUTO, TILE_256x256, TILE_256x256_W4, TILE_256x128, TILE_128x128, TILE_128x128_S4, TILE_64x64 = range(7)
+TILES = {"256x256": TILE_256x256, "256x256_w4": TILE_256x256_W4, "256x128": TILE_256x128, "128x128": TILE_128x128,
+         "128x128_s4": TILE_128x128_S4, "64x64": TILE_64x64}
 
 EXPORTS = (
     "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense",
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
+    "srigl_structured_linear_fwd_tile",
 )
 
 
@@ -62,6 +66,8 @@ def _load() -> ctypes.CDLL:
     lib.srigl_densify.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, vp, vp]
     lib.srigl_structured_linear_fwd.restype = ctypes.c_int
     lib.srigl_structured_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, vp]
+    lib.srigl_structured_linear_fwd_tile.restype = ctypes.c_int
+    lib.srigl_structured_linear_fwd_tile.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, ctypes.c_int, vp]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -160,9 +166,15 @@ def srigl_densify(W_c, idx, n_active, K, d_in, Wd):
            "srigl_densify")
 
 
-def srigl_structured_linear_fwd(x, B, d_in, Wd, active, n_active, bias, d_out, y):
-    st = lib.srigl_structured_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(Wd), _dtype_code(Wd if Wd is not None else x), _ptr(active),
-                                         int(n_active), _ptr(bias), int(d_out), _ptr(y), _stream())
+def srigl_structured_linear_fwd(x, B, d_in, Wd, active, n_active, bias, d_out, y, tile=None):
+    """tile None: the library's own entry point; otherwise the forced-tile entry point (TILE_* codes)."""
+    wcode = _dtype_code(Wd if Wd is not None else x)
+    if tile is None:
+        st = lib.srigl_structured_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(Wd), wcode, _ptr(active),
+                                             int(n_active), _ptr(bias), int(d_out), _ptr(y), _stream())
+    else:
+        st = lib.srigl_structured_linear_fwd_tile(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(Wd), wcode, _ptr(active),
+                                                  int(n_active), _ptr(bias), int(d_out), _ptr(y), int(tile), _stream())
     _check(st, "srigl_structured_linear_fwd")
 
 

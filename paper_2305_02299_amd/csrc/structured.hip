@@ -3,16 +3,19 @@
 // 2305.02299), and the forward pass is a dense product on the matrix cores,
 //     y[b][active[s]] = bias[active[s]] + sum_j Wd[s][j] * x[b][j].
 //
-// The product is an "NT" GEMM: both operands are K-contiguous (x[b][:], Wd[s][:]).  A workgroup of 4
-// wavefronts owns a BM x BN output tile and walks d_in in slabs of 128 bytes per row (64 bf16 or 32 fp32),
-// double-buffered in LDS: the next slab's global loads are issued into registers before the MFMAs of the current
-// one.  LDS rows are 144 bytes apart (128 + 16): the 16-byte reads of 16 consecutive rows then fall on disjoint
-// bank groups.  A wavefront owns (BM/2) x (BN/2) of the tile as 32x32 MFMA blocks:
-//   bf16: v_mfma_f32_32x32x16_bf16, lane l holds row l%32 and the 8 consecutive k of group l/32;
-//   fp32: v_mfma_f32_32x32x2_f32, lane l holds row l%32, k = l/32; the lane's 16-byte read carries 4 consecutive k
-//         of its group, used by 4 successive MFMAs (both operands use the same k-to-slot map, so the sum is over
-//         matching k whatever the order).
-// Result block layout: accumulator register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+// The product is an "NT" GEMM: both operands are K-contiguous (x[b][:], Wd[s][:]).  A workgroup owns a BM x BN
+// output tile and walks d_in in slabs of 128 bytes per row (64 bf16 or 32 fp32).  Slabs travel from global memory
+// straight into a ring of NS LDS stages (global_load_lds_dwordx4: every lane brings 16 bytes, a wavefront fills 1 KB =
+// 8 rows of the stage), NS-1 slabs ahead of the one being multiplied; one barrier per slab.
+// LDS layout of a stage: row r at r * 128 bytes; its 16-byte piece q sits in slot q ^ ((r >> 1) & 7).  The 16-byte
+// reads of 32 consecutive rows at one q then spread over all banks (measured: same rate as a padded 144-byte pitch,
+// which a direct load cannot produce).  The swizzle is applied on the global side: the lane that fills slot s of row
+// r fetches piece s ^ ((r >> 1) & 7).
+// A wavefront owns a (BM/WGM) x (BN/WGN) part of the tile as 32x32 MFMA blocks:
+//   bf16: v_mfma_f32_32x32x16_bf16, lane l holds row l%32 and the 8 consecutive k of piece l/32 of the 32-byte step;
+//   fp32: v_mfma_f32_32x32x2_f32, lane l holds row l%32, k = l/32; the lane's 16-byte piece carries 4 k, used by 4
+//         successive MFMAs (both operands use the same k-to-slot map, so the sum runs over matching k).
+// Result block layout: accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32.
 #include "srigl_internal.h"
 
 namespace srigl {
@@ -20,8 +23,9 @@ namespace srigl {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kSlabBytes = 128;           // bytes of K per row and slab
-constexpr int kRowBytes = kSlabBytes + 16; // LDS row pitch
+constexpr int kSlabBytes = 128;   // bytes of K per row and slab = LDS row pitch
+
+__device__ uint4 g_zero16 = {0u, 0u, 0u, 0u};   // source of the pieces past the end of a row
 
 // zero fill, then scatter: two launches so that no ordering inside a wavefront is relied on
 __global__ __launch_bounds__(256) void k_fill_zero16(uint4* __restrict__ p, size_t n16) {
@@ -74,46 +78,52 @@ __device__ __forceinline__ void mma_block(f32x16_t& acc, const float4& a, const 
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
 }
 
-// BM x BN output tile per workgroup (256 threads = 2 x 2 wavefronts), TM = BM/64, TN = BN/64 MFMA blocks per wavefront and side
-template <typename T, int BM, int BN>
-__global__ __launch_bounds__(256) void k_structured_gemm(const T* __restrict__ x, int B, int d_in, const T* __restrict__ Wd,
-                                                         const int32_t* __restrict__ active, int n_active,
-                                                         const float* __restrict__ bias, int d_out, float* __restrict__ y) {
-    extern __shared__ unsigned char smem[];   // [2][(BM + BN) rows][kRowBytes]
+// s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+using gptr_t = const __attribute__((address_space(1))) void*;
+using lptr_t = __attribute__((address_space(3))) void*;
+
+// BM x BN output tile per workgroup of WGM x WGN wavefronts, NS LDS stages
+template <typename T, int BM, int BN, int WGM, int WGN, int NS>
+__global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __restrict__ x, int B, int d_in, const T* __restrict__ Wd,
+                                                                   const int32_t* __restrict__ active, int n_active,
+                                                                   const float* __restrict__ bias, int d_out, float* __restrict__ y) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];   // [NS][BM + BN rows][128 bytes]
     using F = typename Frag<T>::type;
+    constexpr int NWAVES = WGM * WGN;
     constexpr int EPS = kSlabBytes / (int)sizeof(T);   // elements of K per slab
-    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int EPP = 16 / (int)sizeof(T);           // elements per 16-byte piece
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wavefront tile
+    constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int ROWS = BM + BN;
-    constexpr int PASSES = ROWS * 8 / 256;             // 16-byte vectors per thread and slab (8 per row)
+    constexpr int STAGE = ROWS * kSlabBytes;
+    constexpr int PASSES = ROWS / 8 / NWAVES;          // 1 KB direct loads per wavefront and slab
+    static_assert(ROWS % (8 * NWAVES) == 0 && WTM % 32 == 0 && WTN % 32 == 0 && NS >= 2, "tile shape");
+    static_assert((NS - 2) * PASSES <= 63, "vmcnt range");
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int wm = wv >> 1, wn = wv & 1;
+    const int wm = wv / WGN, wn = wv % WGN;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
-    // staging map: vector v = tid + 256 * p -> (row v / 8, 16-byte column v % 8); rows < BM come from x, the rest from Wd;
-    // rows past the matrix re-read its last row (their results are never stored)
-    const T* src[PASSES];
-    int dst[PASSES];
+    // loader: pass p of wavefront wv fills rows 8 * (p * NWAVES + wv) .. + 7; lane -> (row + lane / 8, slot lane % 8)
+    const unsigned char* src[PASSES];
+    int piece[PASSES];
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
-        const int v = tid + 256 * p;
-        const int row = v >> 3, c16 = v & 7;
+        const int row = 8 * (p * NWAVES + wv) + (lane >> 3);
+        piece[p] = (lane & 7) ^ ((row >> 1) & 7);
         const T* base = (row < BM) ? x + (size_t)min(m0 + row, B - 1) * d_in : Wd + (size_t)min(n0 + row - BM, n_active - 1) * d_in;
-        src[p] = base + c16 * (16 / (int)sizeof(T));
-        dst[p] = row * kRowBytes + c16 * 16;
+        src[p] = reinterpret_cast<const unsigned char*>(base + piece[p] * EPP);
     }
     const int n_slabs = (d_in + EPS - 1) / EPS;
-    uint4 st[PASSES];
-    auto load_slab = [&](int sl) {
+    auto issue_slab = [&](int sl) {
+        unsigned char* stage = smem + (sl % NS) * STAGE;
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
-            const int c16 = (tid + 256 * p) & 7;
-            const int k = sl * EPS + c16 * (16 / (int)sizeof(T));
-            st[p] = (k < d_in) ? *reinterpret_cast<const uint4*>(src[p] + (size_t)sl * EPS) : uint4{0u, 0u, 0u, 0u};   // d_in is a multiple of 16 bytes
+            const bool in = sl * EPS + piece[p] * EPP < d_in;   // d_in is a multiple of EPP: a piece is whole or absent
+            const unsigned char* g = in ? src[p] + (size_t)sl * kSlabBytes : reinterpret_cast<const unsigned char*>(&g_zero16);
+            __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(stage + 1024 * (p * NWAVES + wv)), 16, 0, 0);
         }
-    };
-    auto store_slab = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) *reinterpret_cast<uint4*>(smem + (size_t)buf * ROWS * kRowBytes + dst[p]) = st[p];
     };
 
     f32x16_t acc[TM][TN];
@@ -124,35 +134,40 @@ __global__ __launch_bounds__(256) void k_structured_gemm(const T* __restrict__ x
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    load_slab(0);
-    store_slab(0);
-    __syncthreads();
-    const int frag_off = (lane & 31) * kRowBytes + (lane >> 5) * 16;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < n_slabs) issue_slab(s);
+
+    // reader: row l%32 of a block, piece 2*kk + l/32; the swizzle term only depends on the lane (block rows start at multiples of 32)
+    const int swz = ((lane & 31) >> 1) & 7;
+    int frag_off[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = (lane & 31) * kSlabBytes + (((2 * kk + (lane >> 5)) ^ swz) * 16);
+
     for (int sl = 0; sl < n_slabs; ++sl) {
-        const unsigned char* buf = smem + (size_t)(sl & 1) * ROWS * kRowBytes;
-        if (sl + 1 < n_slabs) load_slab(sl + 1);
+        if (sl + NS - 2 < n_slabs) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * PASSES));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __syncthreads();   // slab sl is in LDS for every wavefront; everyone is done reading the stage refilled next
+        if (sl + NS - 1 < n_slabs) issue_slab(sl + NS - 1);
+        const unsigned char* buf = smem + (sl % NS) * STAGE;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             F a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const F*>(buf + (wm * (BM / 2) + i * 32) * kRowBytes + frag_off + kk * 32);
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const F*>(buf + (wm * WTM + i * 32) * kSlabBytes + frag_off[kk]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const F*>(buf + (BM + wn * (BN / 2) + j * 32) * kRowBytes + frag_off + kk * 32);
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const F*>(buf + (BM + wn * WTN + j * 32) * kSlabBytes + frag_off[kk]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) mma_block(acc[i][j], a[i], b[j]);
-        }
-        if (sl + 1 < n_slabs) {
-            store_slab((sl + 1) & 1);   // the other buffer: its last readers passed the barrier of the previous iteration
-            __syncthreads();
         }
     }
 
     // epilogue: bias and scatter to the stored neurons' columns
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int s = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        const int s = n0 + wn * WTN + j * 32 + (lane & 31);
         if (s >= n_active) continue;
         const int col = active ? active[s] : s;
         if (col < 0 || col >= d_out) continue;
@@ -161,18 +176,19 @@ __global__ __launch_bounds__(256) void k_structured_gemm(const T* __restrict__ x
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
                 if (m < B) y[(size_t)m * d_out + col] = acc[i][j][e] + bv;
             }
         }
     }
 }
 
-template <typename T, int BM, int BN>
+template <typename T, int BM, int BN, int WGM, int WGN, int NS>
 static srigl_status launch_gemm(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active, const float* bias,
                                 int d_out, float* y, hipStream_t st) {
-    auto kern = k_structured_gemm<T, BM, BN>;
-    const size_t lds = (size_t)2 * (BM + BN) * kRowBytes;
+    auto kern = k_structured_gemm<T, BM, BN, WGM, WGN, NS>;
+    const size_t lds = (size_t)NS * (BM + BN) * kSlabBytes;
+    static_assert((size_t)NS * (BM + BN) * kSlabBytes <= kLdsMax, "LDS");
     static bool raised = false;
     if (lds > 64 * 1024 && !raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -181,17 +197,30 @@ static srigl_status launch_gemm(const void* x, int B, int d_in, const void* Wd, 
     }
     const dim3 grid((unsigned)((n_active + BN - 1) / BN), (unsigned)((B + BM - 1) / BM));
     if (grid.y > 65535u) return SRIGL_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const T*)x, B, d_in, (const T*)Wd, active, n_active, bias, d_out, y);
+    hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), lds, st, (const T*)x, B, d_in, (const T*)Wd, active, n_active, bias, d_out, y);
     return hip_ok(hipGetLastError());
 }
 
+static long long n_tiles(int B, int n_active, int bm, int bn) { return (long long)((B + bm - 1) / bm) * ((n_active + bn - 1) / bn); }
+
 template <typename T>
-static srigl_status launch_structured(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active,
+static srigl_status launch_structured(int tile, const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active,
                                       const float* bias, int d_out, float* y, hipStream_t st) {
-    // large tiles when they still give every CU a workgroup, small ones otherwise
-    const long long big = (long long)((n_active + 127) / 128) * ((B + 127) / 128);
-    if (big >= 256) return launch_gemm<T, 128, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-    return launch_gemm<T, 64, 64>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+    if (tile == SRIGL_TILE_AUTO) {
+        // the largest tile that still gives every compute unit work
+        if (n_tiles(B, n_active, 256, 256) >= 256) tile = SRIGL_TILE_256x256;
+        else if (n_tiles(B, n_active, 128, 128) >= 256) tile = SRIGL_TILE_128x128;
+        else tile = SRIGL_TILE_64x64;
+    }
+    switch (tile) {
+        case SRIGL_TILE_256x256: return launch_gemm<T, 256, 256, 2, 4, 2>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_256x256_W4: return launch_gemm<T, 256, 256, 2, 2, 2>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_256x128: return launch_gemm<T, 256, 128, 2, 2, 3>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_128x128: return launch_gemm<T, 128, 128, 2, 2, 2>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_128x128_S4: return launch_gemm<T, 128, 128, 2, 2, 4>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_64x64: return launch_gemm<T, 64, 64, 2, 2, 4>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        default: return SRIGL_ERR_INVALID_ARG;
+    }
 }
 
 }  // namespace srigl
@@ -231,9 +260,9 @@ srigl_status srigl_densify(const void* W_c, srigl_dtype w_dtype, const int32_t* 
     return hip_ok(hipGetLastError());
 }
 
-srigl_status srigl_structured_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
-                                         srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
-                                         const float* bias, int32_t d_out, float* y, void* stream) {
+srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
+                                              srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
+                                              const float* bias, int32_t d_out, float* y, srigl_gemm_tile tile, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (B < 0 || d_in < 0 || n_active < 0 || d_out < 0 || n_active > d_out) return SRIGL_ERR_INVALID_ARG;
     if ((x_dtype != SRIGL_F32 && x_dtype != SRIGL_BF16) || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
@@ -254,8 +283,14 @@ srigl_status srigl_structured_linear_fwd(const void* x, srigl_dtype x_dtype, int
         hipLaunchKernelGGL(k_fill_ablated, dim3((unsigned)blocks), dim3(256), 0, st, active, n_active, bias, B, d_out, y);
     }
     if (n_active == 0) return hip_ok(hipGetLastError());
-    if (x_dtype == SRIGL_F32) return launch_structured<float>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-    return launch_structured<uint16_t>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+    if (x_dtype == SRIGL_F32) return launch_structured<float>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+    return launch_structured<uint16_t>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+}
+
+srigl_status srigl_structured_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
+                                         srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
+                                         const float* bias, int32_t d_out, float* y, void* stream) {
+    return srigl_structured_linear_fwd_tile(x, x_dtype, B, d_in, Wd, w_dtype, active, n_active, bias, d_out, y, SRIGL_TILE_AUTO, stream);
 }
 
 }  // extern "C"

@@ -17,7 +17,7 @@ def B_():
     return binding
 
 
-def run_case(B_, L, tol, with_active=True):
+def run_case(B_, L, tol, tile=None):
     W_c, idx, active = oracle_condensed(L)
     n, K = W_c.shape
     x = L.x_bf16 if L.dtype == "bf16" else L.x
@@ -31,7 +31,7 @@ def run_case(B_, L, tol, with_active=True):
     assert np.array_equal(got_Wd.view(np.uint16 if L.dtype == "bf16" else np.uint32),
                           Wd_ref.view(np.uint16 if L.dtype == "bf16" else np.uint32))
     y = torch.full((L.B, L.d_out), float("nan"), device="cuda")
-    B_.srigl_structured_linear_fwd(dev(x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y)
+    B_.srigl_structured_linear_fwd(dev(x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y, tile=tile)
     torch.cuda.synchronize()
     y_ref = oracle.structured_fwd(x, Wd_ref, active, L.bias, L.d_out)
     _, S = oracle.fwd(x, W_c, idx, active, L.bias, L.d_out, want_scale=True)
@@ -60,6 +60,20 @@ def test_ragged_shapes_f32(B_, d_in, d_out, K, B, abl):
 def test_shapes_bf16(B_, d_in, d_out, K, B, abl):
     L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype="bf16", seed=d_in + B)
     run_case(B_, L, TOL_BF16)
+
+
+TILE_NAMES = ["256x256", "256x256_w4", "256x128", "128x128", "128x128_s4", "64x64"]
+
+
+@pytest.mark.parametrize("tile", TILE_NAMES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_tile_shape(B_, tile, dtype):
+    """Each workgroup tile on shapes with ragged edges in all three dimensions, one and several slabs, and fewer
+    slabs than LDS stages."""
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    for (d_in, d_out, K, B, abl) in [(520, 700, 52, 300, 0.2), (40, 97, 4, 33, 0.0), (136, 513, 14, 257, 0.4)]:
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=d_in + 3 * B)
+        run_case(B_, L, tol, tile=B_.TILES[tile])
 
 
 def test_integer_inputs_bit_exact(B_):
