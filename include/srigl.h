@@ -171,12 +171,12 @@ srigl_status srigl_structured_linear_fwd(const void* x, srigl_dtype x_dtype, int
 /* The same call with the workgroup tile forced (tests and tuning); SRIGL_TILE_AUTO is the library's own choice. */
 typedef enum srigl_gemm_tile {
     SRIGL_TILE_AUTO = 0,
-    SRIGL_TILE_256x256 = 1,     /* 8 wavefronts of 128x64, 2 LDS stages */
-    SRIGL_TILE_256x256_W4 = 2,  /* 4 wavefronts of 128x128, 2 LDS stages */
-    SRIGL_TILE_256x128 = 3,     /* 4 wavefronts of 128x64, 3 LDS stages */
-    SRIGL_TILE_128x128 = 4,     /* 4 wavefronts of 64x64, 2 LDS stages */
-    SRIGL_TILE_128x128_S4 = 5,  /* 4 wavefronts of 64x64, 4 LDS stages */
-    SRIGL_TILE_64x64 = 6        /* 4 wavefronts of 32x32, 4 LDS stages */
+    SRIGL_TILE_256x256 = 1,     /* 8 wavefronts of 128x64, 2 LDS stages of 128 bytes of K per row */
+    SRIGL_TILE_256x256_H = 2,   /* 8 wavefronts of 128x64, 5 LDS stages of 64 bytes */
+    SRIGL_TILE_256x128_W4 = 3,  /* 4 wavefronts of 128x64, 3 LDS stages of 128 bytes */
+    SRIGL_TILE_256x128 = 4,     /* 8 wavefronts of 64x64, 3 LDS stages of 128 bytes */
+    SRIGL_TILE_128x128 = 5,     /* 4 wavefronts of 64x64, 4 LDS stages of 128 bytes */
+    SRIGL_TILE_64x64 = 6        /* 4 wavefronts of 32x32, 4 LDS stages of 128 bytes */
 } srigl_gemm_tile;
 
 srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,

@@ -19,9 +19,9 @@ LIB_PATH = os.path.join(_PKG, "libsrigl.so")
 OK, ERR_INVALID_ARG, ERR_FANIN, ERR_CAPACITY, ERR_INDEX_RANGE, ERR_UNSUPPORTED, ERR_HIP = range(7)
 F32, BF16 = 0, 1
 FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE = range(4)
-TILE_AUTO, TILE_256x256, TILE_256x256_W4, TILE_256x128, TILE_128x128, TILE_128x128_S4, TILE_64x64 = range(7)
-TILES = {"256x256": TILE_256x256, "256x256_w4": TILE_256x256_W4, "256x128": TILE_256x128, "128x128": TILE_128x128,
-         "128x128_s4": TILE_128x128_S4, "64x64": TILE_64x64}
+TILE_AUTO, TILE_256x256, TILE_256x256_H, TILE_256x128_W4, TILE_256x128, TILE_128x128, TILE_64x64 = range(7)
+TILES = {"256x256": TILE_256x256, "256x256_h": TILE_256x256_H, "256x128_w4": TILE_256x128_W4, "256x128": TILE_256x128,
+         "128x128": TILE_128x128, "64x64": TILE_64x64}
 
 EXPORTS = (
     "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense",

@@ -4,13 +4,13 @@
 //     y[b][active[s]] = bias[active[s]] + sum_j Wd[s][j] * x[b][j].
 //
 // The product is an "NT" GEMM: both operands are K-contiguous (x[b][:], Wd[s][:]).  A workgroup owns a BM x BN
-// output tile and walks d_in in slabs of 128 bytes per row (64 bf16 or 32 fp32).  Slabs travel from global memory
-// straight into a ring of NS LDS stages (global_load_lds_dwordx4: every lane brings 16 bytes, a wavefront fills 1 KB =
-// 8 rows of the stage), NS-1 slabs ahead of the one being multiplied; one barrier per slab.
-// LDS layout of a stage: row r at r * 128 bytes; its 16-byte piece q sits in slot q ^ ((r >> 1) & 7).  The 16-byte
-// reads of 32 consecutive rows at one q then spread over all banks (measured: same rate as a padded 144-byte pitch,
-// which a direct load cannot produce).  The swizzle is applied on the global side: the lane that fills slot s of row
-// r fetches piece s ^ ((r >> 1) & 7).
+// output tile and walks d_in in stages of SLAB = 128 or 64 bytes per row.  Stages travel from global memory straight
+// into a ring of NS LDS stages (global_load_lds_dwordx4: every lane brings 16 bytes, a wavefront fills 1 KB = 1024 / SLAB
+// rows of the stage), up to NS - 1 stages ahead of the one being multiplied; one barrier per stage.
+// LDS layout of a stage: row r at r * SLAB bytes; its 16-byte piece q sits in slot q ^ ((r >> 1) & 7) for SLAB = 128 and
+// q ^ ((r >> 2) & 3) for SLAB = 64: rows that share their banks get different slots, so the 16-byte reads of consecutive
+// rows at one q spread over all banks (measured: same rate as a padded pitch, which a direct load cannot produce).  The
+// swizzle is applied on the global side: the lane that fills slot s of row r fetches piece s ^ swizzle(r).
 // A wavefront owns a (BM/WGM) x (BN/WGN) part of the tile as 32x32 MFMA blocks:
 //   bf16: v_mfma_f32_32x32x16_bf16, lane l holds row l%32 and the 8 consecutive k of piece l/32 of the 32-byte step;
 //   fp32: v_mfma_f32_32x32x2_f32, lane l holds row l%32, k = l/32; the lane's 16-byte piece carries 4 k, used by 4
@@ -84,45 +84,72 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 using gptr_t = const __attribute__((address_space(1))) void*;
 using lptr_t = __attribute__((address_space(3))) void*;
 
-// BM x BN output tile per workgroup of WGM x WGN wavefronts, NS LDS stages
-template <typename T, int BM, int BN, int WGM, int WGN, int NS>
+// BM x BN output tile per workgroup of WGM x WGN wavefronts; NS >= 2 LDS stages of SLAB (128 or 64) bytes of K per row.
+//
+// Schedule of one stage h (KSTEPS = SLAB / 32 MFMA steps): the fragments of step kk + 1 are requested before the MFMAs of
+// step kk; before the last step the wavefront waits until its own loads of stage h + 1 have landed and its own reads of
+// stage h have returned, meets the others at the barrier (after which stage h + 1 is complete and the slot of stage h is
+// free), refills that slot with stage h + NS and requests the first fragments of stage h + 1.  The MFMAs right after
+// the barrier have their operands in registers already, so the matrix pipe does not drain at the barrier.
+template <typename T, int BM, int BN, int WGM, int WGN, int NS, int SLAB, bool RAGGED>
 __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __restrict__ x, int B, int d_in, const T* __restrict__ Wd,
                                                                    const int32_t* __restrict__ active, int n_active,
                                                                    const float* __restrict__ bias, int d_out, float* __restrict__ y) {
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];   // [NS][BM + BN rows][128 bytes]
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];   // [NS][BM + BN rows][SLAB bytes]
     using F = typename Frag<T>::type;
     constexpr int NWAVES = WGM * WGN;
-    constexpr int EPS = kSlabBytes / (int)sizeof(T);   // elements of K per slab
+    constexpr int EPS = SLAB / (int)sizeof(T);         // elements of K per stage
     constexpr int EPP = 16 / (int)sizeof(T);           // elements per 16-byte piece
+    constexpr int PIECES = SLAB / 16;                  // pieces per row and stage (8 or 4)
+    constexpr int KSTEPS = SLAB / 32;                  // MFMA steps per stage (two pieces each)
+    constexpr int RPL = 1024 / SLAB;                   // rows one wavefront-wide direct load fills (8 or 16)
+    constexpr int SWZ_SHIFT = (SLAB == 128) ? 1 : 2;   // rows 2^shift apart share their banks
     constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wavefront tile
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int ROWS = BM + BN;
-    constexpr int STAGE = ROWS * kSlabBytes;
-    constexpr int PASSES = ROWS / 8 / NWAVES;          // 1 KB direct loads per wavefront and slab
-    static_assert(ROWS % (8 * NWAVES) == 0 && WTM % 32 == 0 && WTN % 32 == 0 && NS >= 2, "tile shape");
-    static_assert((NS - 2) * PASSES <= 63, "vmcnt range");
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    constexpr int STAGE = ROWS * SLAB;
+    constexpr int PASSES = ROWS / RPL / NWAVES;        // 1 KB direct loads per wavefront and stage
+    static_assert(SLAB == 128 || SLAB == 64, "stage width");
+    static_assert(ROWS % (RPL * NWAVES) == 0 && WTM % 32 == 0 && WTN % 32 == 0 && NS >= 2, "tile shape");
+    static_assert((NS - 1) * PASSES <= 63, "vmcnt range");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront index as a scalar
     const int wm = wv / WGN, wn = wv % WGN;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
-    // loader: pass p of wavefront wv fills rows 8 * (p * NWAVES + wv) .. + 7; lane -> (row + lane / 8, slot lane % 8)
-    const unsigned char* src[PASSES];
-    int piece[PASSES];
+    // loader: pass p of wavefront wv fills rows RPL * (p * NWAVES + wv) .. + RPL - 1; lane -> (row + lane / PIECES, slot lane % PIECES).
+    // The first XP passes are rows of x, the others rows of Wd; a lane keeps one 32-bit byte offset per pass from the tile's
+    // first row, the stage advance is scalar.  Rows past the matrix re-read its last row (their results are never stored).
+    constexpr int XP = BM / RPL / NWAVES;
+    static_assert((BM / RPL) % NWAVES == 0, "a pass is all x rows or all Wd rows");
+    uint32_t voff[PASSES];
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
-        const int row = 8 * (p * NWAVES + wv) + (lane >> 3);
-        piece[p] = (lane & 7) ^ ((row >> 1) & 7);
-        const T* base = (row < BM) ? x + (size_t)min(m0 + row, B - 1) * d_in : Wd + (size_t)min(n0 + row - BM, n_active - 1) * d_in;
-        src[p] = reinterpret_cast<const unsigned char*>(base + piece[p] * EPP);
+        const int row = RPL * (p * NWAVES + wv) + lane / PIECES;
+        const int piece = (lane % PIECES) ^ ((row >> SWZ_SHIFT) & (PIECES - 1));
+        const int r = (p < XP) ? min(row, B - 1 - m0) : min(row - BM, n_active - 1 - n0);
+        voff[p] = (uint32_t)r * (uint32_t)(d_in * (int)sizeof(T)) + piece * 16;
     }
-    const int n_slabs = (d_in + EPS - 1) / EPS;
-    auto issue_slab = [&](int sl) {
-        unsigned char* stage = smem + (sl % NS) * STAGE;
+    const unsigned char* xbase = reinterpret_cast<const unsigned char*>(x + (size_t)m0 * d_in);
+    const unsigned char* wbase = reinterpret_cast<const unsigned char*>(Wd + (size_t)n0 * d_in);
+    const int n_st = (d_in + EPS - 1) / EPS;
+    // RAGGED: d_in is not a multiple of EPS; the pieces of the last stage that lie past the end of the rows come from zeros.
+    // A stage index past the end re-issues the last stage (into a slot nobody reads again): the loop body has no branches
+    // and the number of loads in flight at each wait is fixed.
+    auto issue_stage = [&](int h_unclamped) {
+        const int h = min(h_unclamped, n_st - 1);
+        unsigned char* stage = smem + (h_unclamped % NS) * STAGE + 1024 * wv;
+        const unsigned char* xs = xbase + (size_t)h * SLAB;
+        const unsigned char* ws = wbase + (size_t)h * SLAB;
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
-            const bool in = sl * EPS + piece[p] * EPP < d_in;   // d_in is a multiple of EPP: a piece is whole or absent
-            const unsigned char* g = in ? src[p] + (size_t)sl * kSlabBytes : reinterpret_cast<const unsigned char*>(&g_zero16);
-            __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(stage + 1024 * (p * NWAVES + wv)), 16, 0, 0);
+            const unsigned char* g = ((p < XP) ? xs : ws) + voff[p];
+            if (RAGGED) {
+                const int row = RPL * (p * NWAVES + wv) + lane / PIECES;
+                const int piece = (lane % PIECES) ^ ((row >> SWZ_SHIFT) & (PIECES - 1));
+                if (h * EPS + piece * EPP >= d_in) g = reinterpret_cast<const unsigned char*>(&g_zero16);   // a piece is whole or absent
+            }
+            __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(stage + 1024 * NWAVES * p), 16, 0, 0);
         }
     };
 
@@ -134,33 +161,48 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+    if (n_st > 0) {
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < n_slabs) issue_slab(s);
+        for (int s = 0; s < NS; ++s) issue_stage(s);
+    }
 
     // reader: row l%32 of a block, piece 2*kk + l/32; the swizzle term only depends on the lane (block rows start at multiples of 32)
-    const int swz = ((lane & 31) >> 1) & 7;
-    int frag_off[4];
+    const int swz = ((lane & 31) >> SWZ_SHIFT) & (PIECES - 1);
+    int frag_off[KSTEPS];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = (lane & 31) * kSlabBytes + (((2 * kk + (lane >> 5)) ^ swz) * 16);
+    for (int kk = 0; kk < KSTEPS; ++kk) frag_off[kk] = (lane & 31) * SLAB + (((2 * kk + (lane >> 5)) ^ swz) * 16);
 
-    for (int sl = 0; sl < n_slabs; ++sl) {
-        if (sl + NS - 2 < n_slabs) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * PASSES));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __syncthreads();   // slab sl is in LDS for every wavefront; everyone is done reading the stage refilled next
-        if (sl + NS - 1 < n_slabs) issue_slab(sl + NS - 1);
-        const unsigned char* buf = smem + (sl % NS) * STAGE;
+    F a[2][TM], b[2][TN];
+    auto read_frags = [&](int h, int kk, int set) {
+        const unsigned char* buf = smem + (h % NS) * STAGE;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            F a[TM], b[TN];
+        for (int i = 0; i < TM; ++i) a[set][i] = *reinterpret_cast<const F*>(buf + (wm * WTM + i * 32) * SLAB + frag_off[kk]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const F*>(buf + (wm * WTM + i * 32) * kSlabBytes + frag_off[kk]);
+        for (int j = 0; j < TN; ++j) b[set][j] = *reinterpret_cast<const F*>(buf + (BM + wn * WTN + j * 32) * SLAB + frag_off[kk]);
+    };
+
+    if (n_st > 0) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 1) * PASSES));
+        __syncthreads();
+        read_frags(0, 0, 0);
+    }
+    for (int h = 0; h < n_st; ++h) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const F*>(buf + (BM + wn * WTN + j * 32) * kSlabBytes + frag_off[kk]);
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            if (kk + 1 < KSTEPS) {
+                read_frags(h, kk + 1, (kk + 1) & 1);
+            } else {
+                // stages up to h + NS - 1 are on their way; stage h + 1 must have landed.  Every fragment of stage h is in
+                // registers by now (the wait before the barrier covers the reads above), so its slot is refilled right away.
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * PASSES));
+                __syncthreads();
+                issue_stage(h + NS);
+                read_frags(min(h + 1, n_st - 1), 0, 0);
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) mma_block(acc[i][j], a[i], b[j]);
+                for (int j = 0; j < TN; ++j) mma_block(acc[i][j], a[kk & 1][i], b[kk & 1][j]);
         }
     }
 
@@ -183,12 +225,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
     }
 }
 
-template <typename T, int BM, int BN, int WGM, int WGN, int NS>
-static srigl_status launch_gemm(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active, const float* bias,
+template <typename T, int BM, int BN, int WGM, int WGN, int NS, int SLAB, bool RAGGED>
+static srigl_status launch_gemm_r(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active, const float* bias,
                                 int d_out, float* y, hipStream_t st) {
-    auto kern = k_structured_gemm<T, BM, BN, WGM, WGN, NS>;
-    const size_t lds = (size_t)NS * (BM + BN) * kSlabBytes;
-    static_assert((size_t)NS * (BM + BN) * kSlabBytes <= kLdsMax, "LDS");
+    auto kern = k_structured_gemm<T, BM, BN, WGM, WGN, NS, SLAB, RAGGED>;
+    constexpr size_t lds = (size_t)NS * (BM + BN) * SLAB;
+    static_assert(lds <= kLdsMax, "LDS");
     static bool raised = false;
     if (lds > 64 * 1024 && !raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -197,28 +239,55 @@ static srigl_status launch_gemm(const void* x, int B, int d_in, const void* Wd, 
     }
     const dim3 grid((unsigned)((n_active + BN - 1) / BN), (unsigned)((B + BM - 1) / BM));
     if (grid.y > 65535u) return SRIGL_ERR_UNSUPPORTED;
+    // a lane addresses its rows with 32-bit byte offsets from the tile's first row
+    if ((long long)(BM > BN ? BM : BN) * d_in * (long long)sizeof(T) >= (1ll << 31)) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), lds, st, (const T*)x, B, d_in, (const T*)Wd, active, n_active, bias, d_out, y);
     return hip_ok(hipGetLastError());
 }
 
-static long long n_tiles(int B, int n_active, int bm, int bn) { return (long long)((B + bm - 1) / bm) * ((n_active + bn - 1) / bn); }
+template <typename T, int BM, int BN, int WGM, int WGN, int NS, int SLAB>
+static srigl_status launch_gemm(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active, const float* bias,
+                                int d_out, float* y, hipStream_t st) {
+    if (d_in % (SLAB / (int)sizeof(T)) == 0)
+        return launch_gemm_r<T, BM, BN, WGM, WGN, NS, SLAB, false>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+    return launch_gemm_r<T, BM, BN, WGM, WGN, NS, SLAB, true>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+}
+
+// Tile choice: the estimated cost of a tile shape is (rounds of workgroups over the 256 compute units) x (tile area) /
+// (relative speed of that shape with every compute unit busy, measured on large bf16 products; fp32 products are bound by
+// the matrix pipe for every shape).  64x64 tiles leave room for two workgroups per compute unit.
+struct TileModel { srigl_gemm_tile tile; int bm, bn, per_cu; float speed_bf16; };
+static const TileModel kTileModels[] = {
+    {SRIGL_TILE_256x256_H, 256, 256, 1, 1.00f},
+    {SRIGL_TILE_256x128, 256, 128, 1, 0.885f},
+    {SRIGL_TILE_128x128, 128, 128, 1, 0.727f},
+    {SRIGL_TILE_64x64, 64, 64, 2, 0.40f},
+};
+
+static srigl_gemm_tile choose_tile(int B, int n_active, bool f32) {
+    srigl_gemm_tile best = SRIGL_TILE_64x64;
+    double best_cost = 0.0;
+    for (const TileModel& m : kTileModels) {
+        const long long tiles = (long long)((B + m.bm - 1) / m.bm) * ((n_active + m.bn - 1) / m.bn);
+        const long long slots = 256ll * m.per_cu;
+        const double rounds = (double)((tiles + slots - 1) / slots);
+        const double cost = rounds * m.per_cu * m.bm * m.bn / (f32 ? 1.0 : m.speed_bf16);
+        if (best_cost == 0.0 || cost < best_cost) { best_cost = cost; best = m.tile; }
+    }
+    return best;
+}
 
 template <typename T>
 static srigl_status launch_structured(int tile, const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active,
                                       const float* bias, int d_out, float* y, hipStream_t st) {
-    if (tile == SRIGL_TILE_AUTO) {
-        // the largest tile that still gives every compute unit work
-        if (n_tiles(B, n_active, 256, 256) >= 256) tile = SRIGL_TILE_256x256;
-        else if (n_tiles(B, n_active, 128, 128) >= 256) tile = SRIGL_TILE_128x128;
-        else tile = SRIGL_TILE_64x64;
-    }
+    if (tile == SRIGL_TILE_AUTO) tile = choose_tile(B, n_active, sizeof(T) == 4);
     switch (tile) {
-        case SRIGL_TILE_256x256: return launch_gemm<T, 256, 256, 2, 4, 2>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_256x256_W4: return launch_gemm<T, 256, 256, 2, 2, 2>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_256x128: return launch_gemm<T, 256, 128, 2, 2, 3>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_128x128: return launch_gemm<T, 128, 128, 2, 2, 2>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_128x128_S4: return launch_gemm<T, 128, 128, 2, 2, 4>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_64x64: return launch_gemm<T, 64, 64, 2, 2, 4>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_256x256: return launch_gemm<T, 256, 256, 2, 4, 2, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_256x256_H: return launch_gemm<T, 256, 256, 2, 4, 5, 64>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_256x128_W4: return launch_gemm<T, 256, 128, 2, 2, 3, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_256x128: return launch_gemm<T, 256, 128, 4, 2, 3, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_128x128: return launch_gemm<T, 128, 128, 2, 2, 4, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_64x64: return launch_gemm<T, 64, 64, 2, 2, 4, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
         default: return SRIGL_ERR_INVALID_ARG;
     }
 }

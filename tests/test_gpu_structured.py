@@ -62,7 +62,7 @@ def test_shapes_bf16(B_, d_in, d_out, K, B, abl):
     run_case(B_, L, TOL_BF16)
 
 
-TILE_NAMES = ["256x256", "256x256_w4", "256x128", "128x128", "128x128_s4", "64x64"]
+TILE_NAMES = ["256x256", "256x256_h", "256x128_w4", "256x128", "128x128", "64x64"]
 
 
 @pytest.mark.parametrize("tile", TILE_NAMES)
