@@ -95,6 +95,11 @@ def sweep(args):
               ("c3", si.config("c3", B=256), 256)]
     for (d_in, d_out, sp, K, B) in si.sweep_points():
         points.append(("sweep %d->%d @%d%%" % (d_in, d_out, sp), si.make_layer(d_in, d_out, K, B, seed=0), B))
+    # bf16 storage at the batch sizes where the two representations cross
+    for sp in (80, 90, 95, 99):
+        for B in (64, 256, 1024):
+            points.append(("bf16 768->3072 @%d%%" % sp,
+                           si.make_layer(768, 3072, si.fan_in_for_sparsity(768, sp), B, dtype="bf16", seed=0), B))
     if not args.no_large:
         points.append(("c5", si.config("c5"), 2048))
     for label, L, B in points:
@@ -128,13 +133,16 @@ def sweep(args):
             ys = torch.empty((B, L.d_out), device="cuda")
             structured = time_graph(lambda i: B_.srigl_structured_linear_fwd(xs, B, L.d_in, Wrows, layer.active, layer.n_active,
                                                                             layer.bias, L.d_out, ys), min(steps, 100), 5) * 1e3
+        sel, est_c, est_s = B_.srigl_choose_representation(B, L.d_in, layer.n_active, L.K, L.d_out, B_.BF16 if bf16 else B_.F32)
         flops = 2.0 * B * layer.n_active * L.K
         print(json.dumps({"point": label, "d_in": L.d_in, "d_out": L.d_out, "K": L.K, "n_active": layer.n_active, "B": B,
                           "dtype": L.dtype, "us_cold": round(cold, 2), "us_warm": round(warm, 2),
                           "gbs_cold": round(nbytes / cold / 1e3, 1), "hbm_frac_cold": round(nbytes / cold / 1e3 / HBM_PEAK_GBS, 4),
                           "gflops_cold": round(flops / cold / 1e3, 1), "gflops_warm": round(flops / warm / 1e3, 1),
                           "algorithmic_bytes": nbytes, "torch_dense_matmul_us": round(dense, 2),
-                          "structured_only_us_warm": None if structured is None else round(structured, 2)}), flush=True)
+                          "structured_only_us_warm": None if structured is None else round(structured, 2),
+                          "selected": "structured" if sel == B_.REPR_STRUCTURED else "condensed",
+                          "estimate_us": {"condensed": round(est_c, 1), "structured": round(est_s, 1)}}), flush=True)
         del sets, layer
 
 

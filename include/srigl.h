@@ -183,6 +183,16 @@ srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype
                                               srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
                                               const float* bias, int32_t d_out, float* y, srigl_gemm_tile tile, void* stream);
 
+/* Which of the two representations of a layer is expected to run its forward pass faster for a batch of B rows
+ * (Sec. 4.4 / Fig. 4: the condensed form wins at small batch and high sparsity, the structured-only form at large batch
+ * and modest sparsity).  Host-only arithmetic on the sizes, from timings of both kernels on MI355X; the two estimates
+ * (microseconds) are written when the pointers are not NULL.  Layers whose rows are not a multiple of 16 bytes always
+ * get SRIGL_REPR_CONDENSED. */
+typedef enum srigl_representation { SRIGL_REPR_CONDENSED = 0, SRIGL_REPR_STRUCTURED = 1 } srigl_representation;
+
+srigl_representation srigl_choose_representation(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out,
+                                                 srigl_dtype dtype, float* est_condensed_us, float* est_structured_us);
+
 /* An empty kernel on `stream`: the dispatch floor against which microsecond-scale calls are read. */
 srigl_status srigl_launch_empty(void* stream);
 

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libsrigl.so")
 
 OK, ERR_INVALID_ARG, ERR_FANIN, ERR_CAPACITY, ERR_INDEX_RANGE, ERR_UNSUPPORTED, ERR_HIP = range(7)
 F32, BF16 = 0, 1
+REPR_CONDENSED, REPR_STRUCTURED = 0, 1
 FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE = range(4)
 TILE_AUTO, TILE_256x256, TILE_256x256_H, TILE_256x128_W4, TILE_256x128, TILE_128x128, TILE_64x64 = range(7)
 TILES = {"256x256": TILE_256x256, "256x256_h": TILE_256x256_H, "256x128_w4": TILE_256x128_W4, "256x128": TILE_256x128,
@@ -27,7 +28,7 @@ EXPORTS = (
     "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense",
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
-    "srigl_structured_linear_fwd_tile",
+    "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
 )
 
 
@@ -68,6 +69,9 @@ def _load() -> ctypes.CDLL:
     lib.srigl_structured_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, vp]
     lib.srigl_structured_linear_fwd_tile.restype = ctypes.c_int
     lib.srigl_structured_linear_fwd_tile.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, ctypes.c_int, vp]
+    lib.srigl_choose_representation.restype = ctypes.c_int
+    lib.srigl_choose_representation.argtypes = [i32, i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
+                                                ctypes.POINTER(ctypes.c_float)]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -176,6 +180,14 @@ def srigl_structured_linear_fwd(x, B, d_in, Wd, active, n_active, bias, d_out, y
         st = lib.srigl_structured_linear_fwd_tile(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(Wd), wcode, _ptr(active),
                                                   int(n_active), _ptr(bias), int(d_out), _ptr(y), int(tile), _stream())
     _check(st, "srigl_structured_linear_fwd")
+
+
+def srigl_choose_representation(B, d_in, n_active, K, d_out, dtype_code):
+    """Returns (REPR_CONDENSED | REPR_STRUCTURED, estimated condensed us, estimated structured us)."""
+    c, s = ctypes.c_float(0), ctypes.c_float(0)
+    r = lib.srigl_choose_representation(int(B), int(d_in), int(n_active), int(K), int(d_out), int(dtype_code),
+                                        ctypes.byref(c), ctypes.byref(s))
+    return int(r), c.value, s.value
 
 
 def srigl_launch_empty():

@@ -253,27 +253,28 @@ static srigl_status launch_gemm(const void* x, int B, int d_in, const void* Wd, 
     return launch_gemm_r<T, BM, BN, WGM, WGN, NS, SLAB, true>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
 }
 
-// Tile choice: the estimated cost of a tile shape is (rounds of workgroups over the 256 compute units) x (tile area) /
-// (relative speed of that shape with every compute unit busy, measured on large bf16 products; fp32 products are bound by
-// the matrix pipe for every shape).  64x64 tiles leave room for two workgroups per compute unit.
-struct TileModel { srigl_gemm_tile tile; int bm, bn, per_cu; float speed_bf16; };
+// Tile choice and time estimate: a workgroup needs about ns_per_k nanoseconds per element of d_in for its tile (measured on
+// MI355X with every compute unit busy; 64x64 fp32 tiles run slower when a compute unit holds a single workgroup), and the
+// tiles take ceil(tiles / 256) rounds over the 256 compute units.
+struct TileModel { srigl_gemm_tile tile; int bm, bn; float ns_per_k_bf16, ns_per_k_f32, ns_per_k_f32_single_round; };
 static const TileModel kTileModels[] = {
-    {SRIGL_TILE_256x256_H, 256, 256, 1, 1.00f},
-    {SRIGL_TILE_256x128, 256, 128, 1, 0.885f},
-    {SRIGL_TILE_128x128, 128, 128, 1, 0.727f},
-    {SRIGL_TILE_64x64, 64, 64, 2, 0.40f},
+    {SRIGL_TILE_256x256_H, 256, 256, 28.0f, 233.0f, 233.0f},
+    {SRIGL_TILE_256x128, 256, 128, 18.0f, 125.0f, 125.0f},
+    {SRIGL_TILE_128x128, 128, 128, 13.0f, 70.0f, 70.0f},
+    {SRIGL_TILE_64x64, 64, 64, 4.2f, 19.0f, 22.0f},
 };
 
-static srigl_gemm_tile choose_tile(int B, int n_active, bool f32) {
+// ns_per_k_out: nanoseconds per element of d_in for the whole product with the chosen tile
+static srigl_gemm_tile choose_tile(int B, int n_active, bool f32, double* ns_per_k_out = nullptr) {
     srigl_gemm_tile best = SRIGL_TILE_64x64;
     double best_cost = 0.0;
     for (const TileModel& m : kTileModels) {
         const long long tiles = (long long)((B + m.bm - 1) / m.bm) * ((n_active + m.bn - 1) / m.bn);
-        const long long slots = 256ll * m.per_cu;
-        const double rounds = (double)((tiles + slots - 1) / slots);
-        const double cost = rounds * m.per_cu * m.bm * m.bn / (f32 ? 1.0 : m.speed_bf16);
+        const long long rounds = (tiles + 255) / 256;
+        const double cost = (double)rounds * (f32 ? (rounds == 1 ? m.ns_per_k_f32_single_round : m.ns_per_k_f32) : m.ns_per_k_bf16);
         if (best_cost == 0.0 || cost < best_cost) { best_cost = cost; best = m.tile; }
     }
+    if (ns_per_k_out) *ns_per_k_out = best_cost;
     return best;
 }
 
@@ -327,6 +328,30 @@ srigl_status srigl_densify(const void* W_c, srigl_dtype w_dtype, const int32_t* 
                                n_terms, K, d_in, static_cast<uint16_t*>(Wd));
     }
     return hip_ok(hipGetLastError());
+}
+
+// Estimates in microseconds, calibrated on MI355X measurements of both kernels (fp32 and bf16 storage, batches 1..2048,
+// 768x3072 / 3072x768 / 4096x16384 layers, 80-99 % sparsity):
+//   condensed  ~ 6.3 + B (d_in + d_out) / 2.2e5     (launch, staging the activations, writing the result)
+//                    + B n_active K / 1.0e7          (gathered multiply-adds)
+//                batches <= 16 run the lane-per-term kernel: 2.6 + B n_active K / 1.4e6, never above the line above
+//   structured ~ 3.5 + d_in x (rounds of tiles x nanoseconds per element of d_in of the chosen tile) / 1000
+//                  + 4 B d_out / 4.5e6              (writing the result at HBM speed)
+srigl_representation srigl_choose_representation(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out,
+                                                 srigl_dtype dtype, float* est_condensed_us, float* est_structured_us) {
+    const double b = B > 0 ? B : 0, n = n_active > 0 ? n_active : 0, k = K > 0 ? K : 0;
+    const double terms = b * n * k;
+    double cond = 6.3 + b * ((double)d_in + d_out) / 2.2e5 + terms / 1.0e7;
+    if (B <= 16) cond = fmin(cond, 2.6 + terms / 1.4e6);
+    double ns_per_k = 0.0;
+    const bool f32 = dtype == SRIGL_F32;
+    choose_tile(B > 0 ? B : 1, n_active > 0 ? n_active : 1, f32, &ns_per_k);
+    const int elem = f32 ? 4 : 2;
+    double stru = 3.5 + ns_per_k * d_in * 1e-3 + 4.0 * b * d_out / 4.5e6;
+    if ((d_in * elem) % 16 != 0) stru = 1e30;   // the matrix-core kernel needs rows of whole 16-byte pieces
+    if (est_condensed_us) *est_condensed_us = (float)cond;
+    if (est_structured_us) *est_structured_us = (float)stru;
+    return stru < cond ? SRIGL_REPR_STRUCTURED : SRIGL_REPR_CONDENSED;
 }
 
 srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,

@@ -22,12 +22,30 @@ class CondensedLinear:
     active: torch.Tensor | None
     bias: torch.Tensor | None
     seg: torch.Tensor | None
+    Wd: torch.Tensor | None = None   # dense rows of the stored neurons (structured-only form), built on first use
 
-    def forward(self, x: torch.Tensor, y: torch.Tensor | None = None, algo=None, tuning=None) -> torch.Tensor:
+    def dense_rows(self) -> torch.Tensor:
+        if self.Wd is None:
+            self.Wd = torch.empty((max(self.n_active, 1), self.d_in), dtype=self.W_c.dtype, device=self.W_c.device)
+            B_.srigl_densify(self.W_c, self.idx, self.n_active, self.K, self.d_in, self.Wd)
+        return self.Wd
+
+    def choose(self, batch: int) -> int:
+        return B_.srigl_choose_representation(batch, self.d_in, self.n_active, self.K, self.d_out, B_._dtype_code(self.W_c))[0]
+
+    def forward(self, x: torch.Tensor, y: torch.Tensor | None = None, algo=None, tuning=None,
+                representation: str = "condensed") -> torch.Tensor:
+        """representation: "condensed", "structured", or "auto" (the library's estimate for this batch size)."""
         assert x.dim() == 2 and x.shape[1] == self.d_in
         Bn = x.shape[0]
         if y is None:
             y = torch.empty((Bn, self.d_out), dtype=torch.float32, device=x.device)
+        if representation == "auto":
+            representation = "structured" if self.choose(Bn) == B_.REPR_STRUCTURED else "condensed"
+        if representation == "structured":
+            B_.srigl_structured_linear_fwd(x, Bn, self.d_in, self.dense_rows(), self.active, self.n_active, self.bias, self.d_out, y)
+            return y
+        assert representation == "condensed"
         B_.srigl_condensed_linear_fwd(x, Bn, self.d_in, self.W_c, self.idx, self.active, self.n_active, self.K, self.bias,
                                       self.d_out, y, self.seg, algo=algo, tuning=tuning)
         return y

@@ -120,3 +120,19 @@ def test_argument_errors(B_):
         B_.srigl_structured_linear_fwd(dev(L.x), L.B, L.d_in, Wd, dev(active), L.d_out + 1, dev(L.bias), L.d_out, y)
     with pytest.raises(SriglError):
         B_.srigl_densify(dev(W_c), dev(idx), len(active), L.d_in + 1, L.d_in, Wd)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_object_runs_either_representation(dtype):
+    """The device-buffer holder: "structured" and "auto" give the oracle's result like "condensed" does."""
+    from paper_2305_02299_amd import condense_layer
+    L = si.make_layer(256, 384, 26, 192, ablate_frac=0.25, dtype=dtype, seed=11)
+    Wsrc, xsrc = (L.W_bf16, L.x_bf16) if dtype == "bf16" else (L.W, L.x)
+    layer = condense_layer(dev(Wsrc), dev(L.mask), L.K, dev(L.bias))
+    W_c, idx, active = oracle_condensed(L)
+    y_ref, S = oracle.fwd(xsrc, W_c, idx, active, L.bias, L.d_out, want_scale=True)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    for rep in ("condensed", "structured", "auto"):
+        y = layer.forward(dev(xsrc), representation=rep)
+        torch.cuda.synchronize()
+        gate(host(y), y_ref, S, tol)
