@@ -146,6 +146,65 @@ def sweep(args):
         del sets, layer
 
 
+def structured(args):
+    """--structured: the structured-only form of the 4096->16384 bf16 layer at B=2048 (dense rows of the stored neurons on the
+    matrix cores), one JSON line; the condensed form of the same layer and the library's dense matmul as context."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2305_02299_amd import binding as B_
+    from paper_2305_02299_amd import condense_layer
+
+    torch.cuda.set_device(0)
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+    def time_graph(fn, steps, warmup):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for i in range(warmup):
+                fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    L = si.config("c5")
+    layer = condense_layer(dev(L.W_bf16), dev(L.mask), L.K, dev(L.bias))
+    xs = dev(L.x_bf16)
+    y = torch.empty((L.B, L.d_out), device="cuda")
+    Wd = layer.dense_rows()
+    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    t_s = time_graph(lambda i: B_.srigl_structured_linear_fwd(xs, L.B, L.d_in, Wd, layer.active, layer.n_active, layer.bias,
+                                                              L.d_out, y), steps, warmup)
+    t_c = time_graph(lambda i: B_.srigl_condensed_linear_fwd(xs, L.B, L.d_in, layer.W_c, layer.idx, layer.active, layer.n_active,
+                                                             L.K, layer.bias, L.d_out, y, layer.seg), 5, 1)
+    xt = dev(L.x).to(torch.bfloat16)
+    Wt = dev((L.W * L.mask).astype(np.float32)).to(torch.bfloat16)
+    t_d = time_graph(lambda i: torch.matmul(xt, Wt.t()), steps, warmup)
+    flops = 2.0 * L.B * layer.n_active * L.d_in
+    tf = flops / (t_s * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "structured_linear_fwd_us_per_call", "value": t_s * 1e3, "unit": "us/call", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": t_s, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c5 structured-only: %d->%d bf16, n_active=%d dense rows, B=%d" % (L.d_in, L.d_out, layer.n_active, L.B)},
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None},
+        "context": {"condensed_same_layer_us": t_c * 1e3, "library_dense_bf16_matmul_us": t_d * 1e3,
+                    "library_dense_tflops": 2.0 * L.B * L.d_out * L.d_in / (t_d * 1e-3) / 1e12}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -156,6 +215,7 @@ def main():
     ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane"])
     ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")
     ap.add_argument("--no-large", action="store_true", help="--sweep without the 4096->16384 bf16 layer")
+    ap.add_argument("--structured", action="store_true", help="time the structured-only form of the 4096->16384 bf16 layer")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus)
@@ -163,6 +223,8 @@ def main():
 
     if args.sweep:
         return sweep(args)
+    if args.structured:
+        return structured(args)
 
     import torch
 

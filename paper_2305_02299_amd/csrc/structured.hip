@@ -51,16 +51,46 @@ __global__ __launch_bounds__(256) void k_scatter_rows(const T* __restrict__ W_c,
     }
 }
 
-// columns that are not stored get their bias (the gaps of the ascending active list)
+// Columns that are not stored get their bias.  A workgroup takes 256 consecutive columns and kFillRows rows: every thread
+// looks its column up in the ascending active list, the ablated ones are gathered into a list in LDS, and the threads then
+// walk (row, listed column) pairs so that neighbouring lanes write neighbouring ablated columns of one row.
+constexpr int kFillRows = 128;
 __global__ __launch_bounds__(256) void k_fill_ablated(const int32_t* __restrict__ active, int n_active, const float* __restrict__ bias,
                                                       int B, int d_out, float* __restrict__ y) {
-    const long long total = (long long)B * (n_active + 1);
-    for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
-        const int b = (int)(t / (n_active + 1));
-        const int s = (int)(t - (long long)b * (n_active + 1));
-        const int col = min((s < n_active) ? active[s] : d_out, d_out);
-        const int prev = (s > 0) ? active[s - 1] : -1;
-        for (int c = max(prev + 1, 0); c < col; ++c) y[(size_t)b * d_out + c] = bias ? bias[c] : 0.0f;
+    __shared__ int list[256];
+    __shared__ float list_bias[256];
+    __shared__ int wave_count[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int c = blockIdx.x * 256 + tid;
+    bool ablated = c < d_out;
+    if (ablated && n_active > 0) {
+        int lo = 0, hi = n_active;   // first position whose entry is >= c
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (active[mid] < c) lo = mid + 1; else hi = mid;
+        }
+        ablated = !(lo < n_active && active[lo] == c);
+    }
+    const unsigned long long vote = __ballot(ablated);
+    const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(vote >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)vote, 0));
+    if (lane == 0) wave_count[wv] = __popcll(vote);
+    __syncthreads();
+    int base = 0, n_list = 0;
+    for (int w = 0; w < 4; ++w) {
+        if (w < wv) base += wave_count[w];
+        n_list += wave_count[w];
+    }
+    if (ablated) {
+        list[base + before] = c;
+        list_bias[base + before] = bias ? bias[c] : 0.0f;
+    }
+    __syncthreads();
+    if (n_list == 0) return;
+    const int r0 = blockIdx.y * kFillRows;
+    const int rows = min(kFillRows, B - r0);
+    for (int idx = tid; idx < rows * n_list; idx += 256) {
+        const int r = idx / n_list, k = idx - r * n_list;
+        y[(size_t)(r0 + r) * d_out + list[k]] = list_bias[k];
     }
 }
 
@@ -372,9 +402,9 @@ srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype
     }
     // ablated columns (and everything, when nothing is stored)
     if (active != nullptr || n_active == 0) {
-        long long blocks = ((long long)B * (n_active + 1) + 255) / 256;
-        if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(k_fill_ablated, dim3((unsigned)blocks), dim3(256), 0, st, active, n_active, bias, B, d_out, y);
+        const dim3 grid((unsigned)((d_out + 255) / 256), (unsigned)((B + kFillRows - 1) / kFillRows));
+        if (grid.y > 65535u) return SRIGL_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(k_fill_ablated, grid, dim3(256), 0, st, active, n_active, bias, B, d_out, y);
     }
     if (n_active == 0) return hip_ok(hipGetLastError());
     if (x_dtype == SRIGL_F32) return launch_structured<float>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
