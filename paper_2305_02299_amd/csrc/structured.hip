@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void k_scatter_rows(const T* __restrict__ W_c,
     }
 }
 
-// Columns that are not stored get their bias.  A workgroup takes 256 consecutive columns and kFillRows rows: every thread
+// Columns that are not stored get their bias (used when no neuron is stored at all; otherwise the product kernel's epilogue
+// writes them).  A workgroup takes 256 consecutive columns and kFillRows rows: every thread
 // looks its column up in the ascending active list, the ablated ones are gathered into a list in LDS, and the threads then
 // walk (row, listed column) pairs so that neighbouring lanes write neighbouring ablated columns of one row.
 constexpr int kFillRows = 128;
@@ -113,6 +114,16 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 
 using gptr_t = const __attribute__((address_space(1))) void*;
 using lptr_t = __attribute__((address_space(3))) void*;
+
+// LDS use of the epilogue: the column table with its bias values and an fp32 tile (pitch BN + 4) of all BM rows when
+// that fits, else of the rows of one wavefront row at a time
+template <int BM, int BN, int WGM>
+struct EpiLayout {
+    static constexpr int PITCH = BN + 4;
+    static constexpr int TCAP = 1024;   // columns of y per pass
+    static constexpr int PHASES = ((size_t)BM * PITCH * 4 + (size_t)TCAP * 8 <= kLdsMax) ? 1 : WGM;
+    static constexpr size_t BYTES = (size_t)(BM / PHASES) * PITCH * 4 + (size_t)TCAP * 8;
+};
 
 // BM x BN output tile per workgroup of WGM x WGN wavefronts; NS >= 2 LDS stages of SLAB (128 or 64) bytes of K per row.
 //
@@ -236,20 +247,74 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
         }
     }
 
-    // epilogue: bias and scatter to the stored neurons' columns
+    // Epilogue without an active list: stored neuron s is column s; every lane writes its accumulators where they belong
+    // (32 neighbouring lanes cover 128 contiguous bytes of a row).
+    if (active == nullptr) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int s = n0 + wn * WTN + j * 32 + (lane & 31);
-        if (s >= n_active) continue;
-        const int col = active ? active[s] : s;
-        if (col < 0 || col >= d_out) continue;
-        const float bv = bias ? bias[col] : 0.0f;
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+            if (col >= n_active) continue;
+            const float bv = bias ? bias[col] : 0.0f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (m < B) y[(size_t)m * d_out + col] = acc[i][j][e] + bv;
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                    if (m < B) y[(size_t)m * d_out + col] = acc[i][j][e] + bv;
+                }
+            }
+        }
+        return;
+    }
+
+    // Epilogue with an active list.  The stored neurons of this tile and the ablated ones between them cover one contiguous
+    // range of columns of y, [c_lo, c_hi].  The range is written row by row with neighbouring lanes on neighbouring columns:
+    // a table in LDS says, for each column of the range, which stored neuron of the tile it is (or none: the column is its
+    // bias), and the accumulators pass through an LDS tile.  No column of y is touched twice and none is left out.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // the re-issued last stages may still be landing in the ring
+    __syncthreads();
+    using EL = EpiLayout<BM, BN, WGM>;
+    constexpr int NT = NWAVES * 64;
+    constexpr int PITCH = EL::PITCH, TCAP = EL::TCAP, EPH = EL::PHASES, PROWS = BM / EPH, WPP = WGM / EPH;
+    float* tile = reinterpret_cast<float*>(smem);                         // [PROWS][PITCH]
+    int* table = reinterpret_cast<int*>(smem + PROWS * PITCH * 4);        // [TCAP] stored neuron within the tile, or -1
+    float* tbias = reinterpret_cast<float*>(table + TCAP);                // [TCAP]
+    const int s_cnt = min(BN, n_active - n0);
+    const int c_lo = max((n0 > 0) ? active[n0 - 1] + 1 : 0, 0);
+    const int c_hi = min((n0 + s_cnt == n_active) ? d_out - 1 : active[n0 + s_cnt - 1], d_out - 1);
+    for (int cc = c_lo; cc <= c_hi; cc += TCAP) {
+        const int wc = min(TCAP, c_hi - cc + 1);
+        if (cc != c_lo) __syncthreads();   // the previous pass is done with the table
+        for (int k = tid; k < wc; k += NT) {
+            tbias[k] = bias ? bias[cc + k] : 0.0f;
+            table[k] = -1;
+        }
+        __syncthreads();
+        for (int s = tid; s < s_cnt; s += NT) {
+            const int col = active[n0 + s] - cc;
+            if (col >= 0 && col < wc) table[col] = s;
+        }
+#pragma unroll
+        for (int ph = 0; ph < EPH; ++ph) {
+            if (ph > 0 || cc != c_lo) __syncthreads();   // tile free again
+            if (wm / WPP == ph) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            tile[((wm % WPP) * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * PITCH + wn * WTN + j * 32 + (lane & 31)] =
+                                acc[i][j][e];
+            }
+            __syncthreads();   // tile, table and bias values complete
+            const int rows = min(PROWS, B - (m0 + ph * PROWS));
+            for (int r = wv; r < rows; r += NWAVES) {
+                float* yr = y + (size_t)(m0 + ph * PROWS + r) * d_out + cc;
+                for (int k = lane; k < wc; k += 64) {
+                    const int tix = table[k];
+                    yr[k] = (tix >= 0 ? tile[r * PITCH + tix] : 0.0f) + tbias[k];
+                }
             }
         }
     }
@@ -259,7 +324,8 @@ template <typename T, int BM, int BN, int WGM, int WGN, int NS, int SLAB, bool R
 static srigl_status launch_gemm_r(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active, const float* bias,
                                 int d_out, float* y, hipStream_t st) {
     auto kern = k_structured_gemm<T, BM, BN, WGM, WGN, NS, SLAB, RAGGED>;
-    constexpr size_t lds = (size_t)NS * (BM + BN) * SLAB;
+    constexpr size_t ring = (size_t)NS * (BM + BN) * SLAB, epi = EpiLayout<BM, BN, WGM>::BYTES;
+    constexpr size_t lds = ring > epi ? ring : epi;
     static_assert(lds <= kLdsMax, "LDS");
     static bool raised = false;
     if (lds > 64 * 1024 && !raised) {
@@ -400,13 +466,12 @@ srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype
         if ((d_in * elem) % 16 != 0 || ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(Wd)) & 15) != 0)
             return SRIGL_ERR_UNSUPPORTED;
     }
-    // ablated columns (and everything, when nothing is stored)
-    if (active != nullptr || n_active == 0) {
+    if (n_active == 0) {   // nothing is stored: every column is its bias
         const dim3 grid((unsigned)((d_out + 255) / 256), (unsigned)((B + kFillRows - 1) / kFillRows));
         if (grid.y > 65535u) return SRIGL_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(k_fill_ablated, grid, dim3(256), 0, st, active, n_active, bias, B, d_out, y);
+        return hip_ok(hipGetLastError());
     }
-    if (n_active == 0) return hip_ok(hipGetLastError());
     if (x_dtype == SRIGL_F32) return launch_structured<float>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
     return launch_structured<uint16_t>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
 }
