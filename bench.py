@@ -91,6 +91,20 @@ def sweep(args):
             best = t if best is None else min(best, t)
         return best
 
+    def time_eager(fn, steps, warmup):
+        """Launched call by call from Python (the library's sparse product allocates, so it cannot be captured in a graph):
+        includes the host's launch rate."""
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for i in range(steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
     points = [("c1", si.config("c1"), 1), ("c2", si.config("c2"), 256), ("c3", si.config("c3", B=1), 1),
               ("c3", si.config("c3", B=256), 256)]
     for (d_in, d_out, sp, K, B) in si.sweep_points():
@@ -133,6 +147,15 @@ def sweep(args):
             ys = torch.empty((B, L.d_out), device="cuda")
             structured = time_graph(lambda i: B_.srigl_structured_linear_fwd(xs, B, L.d_in, Wrows, layer.active, layer.n_active,
                                                                             layer.bias, L.d_out, ys), min(steps, 100), 5) * 1e3
+        # unstructured context (Fig. 4's CSR line): the same masked weight as a CSR matrix through the library's sparse product
+        csr = None
+        if not bf16 and not args.no_csr:
+            try:
+                Wcsr = Wm.to_sparse_csr()
+                xT = xd.t().contiguous()
+                csr = time_eager(lambda i: torch.sparse.mm(Wcsr, xT), min(steps, 50), 3) * 1e3
+            except Exception as e:                       # noqa: BLE001  (context only: report and go on)
+                log("CSR product unavailable for %s: %s" % (label, str(e)[:200]))
         sel, est_c, est_s = B_.srigl_choose_representation(B, L.d_in, layer.n_active, L.K, L.d_out, B_.BF16 if bf16 else B_.F32)
         flops = 2.0 * B * layer.n_active * L.K
         print(json.dumps({"point": label, "d_in": L.d_in, "d_out": L.d_out, "K": L.K, "n_active": layer.n_active, "B": B,
@@ -141,6 +164,7 @@ def sweep(args):
                           "gflops_cold": round(flops / cold / 1e3, 1), "gflops_warm": round(flops / warm / 1e3, 1),
                           "algorithmic_bytes": nbytes, "torch_dense_matmul_us": round(dense, 2),
                           "structured_only_us_warm": None if structured is None else round(structured, 2),
+                          "library_csr_spmm_us": None if csr is None else round(csr, 2),
                           "selected": "structured" if sel == B_.REPR_STRUCTURED else "condensed",
                           "estimate_us": {"condensed": round(est_c, 1), "structured": round(est_s, 1)}}), flush=True)
         del sets, layer
@@ -215,6 +239,7 @@ def main():
     ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane"])
     ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")
     ap.add_argument("--no-large", action="store_true", help="--sweep without the 4096->16384 bf16 layer")
+    ap.add_argument("--no-csr", action="store_true", help="--sweep without the library CSR product (context column)")
     ap.add_argument("--structured", action="store_true", help="time the structured-only form of the 4096->16384 bf16 layer")
     args = ap.parse_args()
     if args.gpus != 1:
