@@ -148,6 +148,20 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
                                              const uint16_t* seg, srigl_fwd_algo algo,
                                              const srigl_fwd_tuning* tuning, void* stream);
 
+/* ---- MLP block: activation in the epilogue, width reduction -------------------------------------------
+ * Sec. 3.1 (neuron ablation reduces the width of a layer) and App. H (the timed layer is one linear of a ViT MLP
+ * block: linear, GELU, linear).  srigl_condensed_linear_fwd_act is the forward call with an activation applied to
+ * every written value, stored and ablated columns alike (an ablated neuron outputs act(bias)); SRIGL_ACT_GELU is
+ * v * Phi(v) with the normal distribution function (erf form). */
+typedef enum srigl_activation { SRIGL_ACT_NONE = 0, SRIGL_ACT_RELU = 1, SRIGL_ACT_GELU = 2 } srigl_activation;
+
+srigl_status srigl_condensed_linear_fwd_act(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
+                                            const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
+                                            const int32_t* active, int32_t n_active, int32_t K,
+                                            const float* bias, int32_t d_out, float* y,
+                                            const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
+                                            const srigl_fwd_tuning* tuning, void* stream);
+
 /* ---- structured-only representation -----------------------------------------------------------------
  * Sec. 4.4 / Fig. 4 / App. H compare the condensed layer with the same layer "accelerated using only the
  * ablated neurons without exploiting the fine-grained sparsity": the stored neurons keep dense rows, and

@@ -146,6 +146,38 @@ def structured_fwd(x: np.ndarray, Wd: np.ndarray, active, bias, d_out: int) -> n
     return y
 
 
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+
+
+def activate(y: np.ndarray, act: int) -> np.ndarray:
+    """Activation of an MLP block applied to fp32 values (evaluated in double): identity, ReLU, erf-form GELU."""
+    out = np.ascontiguousarray(y, dtype=np.float32).copy()
+    _load().oracle_activate(_p(out), ctypes.c_longlong(out.size), int(act))
+    return out
+
+
+def fold_ablated_inputs(idx2, W_c2, bias2, active2, d_out2, active1, d_hidden, bias1, act):
+    """Layer 2 rewritten to read the compact outputs of layer 1's stored neurons; returns (idx, W_c, bias[d_out2]).
+    Raises ValueError if layer 2's fan-in exceeds the number of stored neurons of layer 1."""
+    assert W_c2.dtype in (np.float32, np.uint16)
+    idx2 = _c(idx2, np.int32)
+    W_c2 = np.ascontiguousarray(W_c2)
+    bias2 = _c(bias2, np.float32)
+    active2 = _c(active2, np.int32)
+    active1 = _c(active1, np.int32)
+    bias1 = _c(bias1, np.float32)
+    n2, K2 = idx2.shape
+    idx_out = np.empty_like(idx2)
+    W_out = np.empty_like(W_c2)
+    bias_out = np.empty(d_out2, dtype=np.float32)
+    rc = _load().oracle_fold_ablated_inputs(_p(idx2), _p(W_c2), W_c2.dtype.itemsize, _p(bias2), _p(active2), n2, K2, int(d_out2),
+                                            _p(active1), len(active1), int(d_hidden), _p(bias1), int(act),
+                                            _p(idx_out), _p(W_out), _p(bias_out))
+    if rc != 0:
+        raise ValueError("fan-in %d exceeds the %d stored neurons of the first layer" % (K2, len(active1)))
+    return idx_out, W_out, bias_out
+
+
 def fwd_allcores(x, W_c, idx, active, bias, d_out):
     """Timing companion (fp32 accumulate, OpenMP over batch x neurons): returns (y, threads used)."""
     x = _c(x, np.float32)

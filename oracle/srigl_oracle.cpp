@@ -32,7 +32,10 @@
 
 #include <cmath>
 #include <cstdint>
+#include <algorithm>
 #include <cstring>
+#include <utility>
+#include <vector>
 #ifdef _OPENMP
 #include <omp.h>
 #endif
@@ -210,6 +213,67 @@ void oracle_structured_fwd_f32(const float* x, int B, int d_in, const float* Wd,
 void oracle_structured_fwd_bf16(const uint16_t* x, int B, int d_in, const uint16_t* Wd, const int32_t* active, int n_active,
                                 const float* bias, int d_out, float* y) {
     structured_generic(nullptr, x, B, d_in, nullptr, Wd, active, n_active, bias, d_out, y);
+}
+
+// Activation between the two linear layers of an MLP block (App. H times one linear of a ViT MLP block): 0 identity,
+// 1 max(v, 0), 2 the erf-form GELU v * Phi(v), Phi the normal distribution function.  In place, evaluated in double.
+static double activation_f64(double v, int act) {
+    if (act == 1) return v > 0.0 ? v : 0.0;
+    if (act == 2) return 0.5 * v * (1.0 + std::erf(v / std::sqrt(2.0)));
+    return v;
+}
+
+void oracle_activate(float* y, long long n, int act) {
+    for (long long i = 0; i < n; ++i) y[i] = (float)activation_f64((double)y[i], act);
+}
+
+// Width reduction (Sec. 3.1: ablating neurons reduces the width of a layer).  Layer 1 has d_hidden neurons of which
+// active1[0..n_active1) are stored; an ablated neuron r outputs the constant act(bias1[r]).  Layer 2 (n2 stored rows of
+// fan-in K2 over the d_hidden outputs of layer 1) is rewritten to read the compact vector of the n_active1 stored
+// outputs: an index that names stored neuron active1[p] becomes p; a term on an ablated neuron is a constant and moves
+// into the bias of that row's neuron; the row is filled up to K2 entries again with the smallest positions it does not use yet, weight zero,
+// and sorted ascending, so that it is a constant fan-in row like any other.  Returns 0, or 1 if K2 > n_active1 (no
+// room for K2 distinct positions).  Weights are fp32 (elem_bytes 4) or bf16 bit patterns (2), copied bit for bit.
+// bias2 / bias_out have d_out2 entries; stored row n of layer 2 is column active2[n] (n itself if active2 == NULL).
+int oracle_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, int elem_bytes, const float* bias2, const int32_t* active2,
+                               int n2, int K2, int d_out2, const int32_t* active1, int n_active1, int d_hidden,
+                               const float* bias1, int act, int32_t* idx_out, void* W_out, float* bias_out) {
+    if (K2 > n_active1) return 1;
+    for (int c = 0; c < d_out2; ++c) bias_out[c] = bias2 ? bias2[c] : 0.0f;
+    std::vector<int32_t> position(d_hidden, -1);
+    for (int p = 0; p < n_active1; ++p) position[active1[p]] = p;
+    const unsigned char* w_in = static_cast<const unsigned char*>(W_c2);
+    unsigned char* w_out = static_cast<unsigned char*>(W_out);
+    for (int n = 0; n < n2; ++n) {
+        std::vector<std::pair<int32_t, int>> entries;   // (new index, source k or -1 for a filler)
+        std::vector<char> used(n_active1, 0);
+        double constant = 0.0;
+        for (int k = 0; k < K2; ++k) {
+            const int32_t j = idx2[(size_t)n * K2 + k];
+            const int32_t p = position[j];
+            if (p >= 0) {
+                entries.push_back({p, k});
+                used[p] = 1;
+            } else {
+                double w;
+                if (elem_bytes == 4) { float f; std::memcpy(&f, w_in + ((size_t)n * K2 + k) * 4, 4); w = f; }
+                else { uint16_t h; std::memcpy(&h, w_in + ((size_t)n * K2 + k) * 2, 2); w = bf16_to_float(h); }
+                constant += w * activation_f64(bias1 ? (double)bias1[j] : 0.0, act);
+            }
+        }
+        for (int g = 0; (int)entries.size() < K2; ++g)
+            if (!used[g]) entries.push_back({g, -1});
+        std::sort(entries.begin(), entries.end());
+        for (int k = 0; k < K2; ++k) {
+            idx_out[(size_t)n * K2 + k] = entries[k].first;
+            unsigned char* dst = w_out + ((size_t)n * K2 + k) * elem_bytes;
+            if (entries[k].second >= 0) std::memcpy(dst, w_in + ((size_t)n * K2 + entries[k].second) * elem_bytes, elem_bytes);
+            else std::memset(dst, 0, elem_bytes);
+        }
+        const int col = active2 ? active2[n] : n;
+        bias_out[col] = (float)((bias2 ? (double)bias2[col] : 0.0) + constant);
+    }
+    return 0;
 }
 
 // Timing companion of oracle_fwd_f32 (not used for parity): the same three loops of Alg. 1 with fp32

@@ -28,7 +28,7 @@ template <typename XT>
 __global__ __launch_bounds__(256) void k_fwd_generic(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                      const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
                                                      int n_active, int K, const float* __restrict__ bias, int d_out,
-                                                     float* __restrict__ y) {
+                                                     float* __restrict__ y, int act) {
     const int n_slots = active ? n_active + 1 : n_active;   // +1: virtual row that fills the tail gap
     const long long total = (long long)B * n_slots;
     for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void k_fwd_generic(const XT* __restrict__ x, i
             col = (s < n_active) ? active[s] : d_out;
             prev = (s > 0) ? active[s - 1] : -1;
             col = min(col, d_out);
-            for (int c = max(prev + 1, 0); c < col; ++c) yr[c] = bias_at(bias, c);
+            for (int c = max(prev + 1, 0); c < col; ++c) yr[c] = apply_act(bias_at(bias, c), act);
         }
         if (s >= n_active || col < 0 || col >= d_out) continue;
         const XT* xr = x + (size_t)b * d_in;
@@ -51,15 +51,15 @@ __global__ __launch_bounds__(256) void k_fwd_generic(const XT* __restrict__ x, i
             const int j = min(max(ix[k], 0), d_in - 1);
             acc = fmaf(to_f32<XT>(w[k]), to_f32<XT>(xr[j]), acc);
         }
-        yr[col] = acc + bias_at(bias, col);
+        yr[col] = apply_act(acc + bias_at(bias, col), act);
     }
 }
 
 // y[b][c] = bias[c] (or 0): the whole forward pass when nothing is stored (n_active == 0 or K == 0).
-__global__ __launch_bounds__(256) void k_bias_broadcast(const float* __restrict__ bias, int B, int d_out, float* __restrict__ y) {
+__global__ __launch_bounds__(256) void k_bias_broadcast(const float* __restrict__ bias, int B, int d_out, float* __restrict__ y, int act) {
     const long long total = (long long)B * d_out;
     for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x)
-        y[t] = bias_at(bias, (int)(t % d_out));
+        y[t] = apply_act(bias_at(bias, (int)(t % d_out)), act);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -87,7 +87,7 @@ template <int RB, typename XT>
 __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                    const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
                                                    int n_active, int K, const float* __restrict__ bias, int d_out,
-                                                   float* __restrict__ y, int log2L, int rows_per_wg) {
+                                                   float* __restrict__ y, int log2L, int rows_per_wg, int act) {
     extern __shared__ float xs[];   // [RB][d_in]
     const int L = 1 << log2L;
     const int tid = threadIdx.x;
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
             prev = (s > 0) ? active[s - 1] : -1;
             // the L lanes of the group share the gap in front of this column
             for (int c = max(prev + 1, 0) + q; c < col; c += L) {
-                const float bv = bias_at(bias, c);
+                const float bv = apply_act(bias_at(bias, c), act);
 #pragma unroll
                 for (int r = 0; r < RB; ++r)
                     if (b0 + r < B) y[(size_t)(b0 + r) * d_out + c] = bv;
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
             const float bv = bias_at(bias, col);
 #pragma unroll
             for (int r = 0; r < RB; ++r)
-                if (b0 + r < B) y[(size_t)(b0 + r) * d_out + col] = acc[r] + bv;
+                if (b0 + r < B) y[(size_t)(b0 + r) * d_out + col] = apply_act(acc[r] + bv, act);
         }
     }
 }
@@ -174,10 +174,10 @@ srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st) {
     if (blocks > 65536) blocks = 65536;
     if (a.x_bf16)
         hipLaunchKernelGGL(k_fwd_generic<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, st, (const uint16_t*)a.x, a.B, a.d_in,
-                           (const uint16_t*)a.W_c, a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y);
+                           (const uint16_t*)a.W_c, a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.act);
     else
         hipLaunchKernelGGL(k_fwd_generic<float>, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)a.x, a.B, a.d_in,
-                           (const float*)a.W_c, a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y);
+                           (const float*)a.W_c, a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.act);
     return hip_ok(hipGetLastError());
 }
 
@@ -197,7 +197,7 @@ static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg,
     const unsigned gy = (unsigned)((a.B + RB - 1) / RB);
     if (gy > 65535u) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c, a.idx, a.active,
-                       a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg);
+                       a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act);
     return hip_ok(hipGetLastError());
 }
 
@@ -328,13 +328,12 @@ using namespace srigl;
 
 extern "C" {
 
-srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
-                                             const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
-                                             const int32_t* active, int32_t n_active, int32_t K,
-                                             const float* bias, int32_t d_out, float* y,
-                                             const uint16_t* seg, srigl_fwd_algo algo,
-                                             const srigl_fwd_tuning* tuning, void* stream) {
+static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* W_c, srigl_dtype w_dtype,
+                             const int32_t* idx, const int32_t* active, int32_t n_active, int32_t K, const float* bias,
+                             int32_t d_out, float* y, const uint16_t* seg, srigl_fwd_algo algo, const srigl_fwd_tuning* tuning,
+                             srigl_activation act, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (act != SRIGL_ACT_NONE && act != SRIGL_ACT_RELU && act != SRIGL_ACT_GELU) return SRIGL_ERR_INVALID_ARG;
     if (B < 0 || d_in < 0 || n_active < 0 || K < 0 || d_out < 0 || K > d_in || n_active > d_out) return SRIGL_ERR_INVALID_ARG;
     if ((x_dtype != SRIGL_F32 && x_dtype != SRIGL_BF16) || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
     if (x_dtype != w_dtype) return SRIGL_ERR_UNSUPPORTED;
@@ -347,10 +346,11 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
     a.x = x; a.x_bf16 = (x_dtype == SRIGL_BF16); a.B = B; a.d_in = d_in; a.W_c = W_c; a.idx = idx; a.active = active;
     a.n_active = n_active; a.K = K; a.bias = bias; a.d_out = d_out; a.y = y; a.seg = seg;
     a.seg_stride = srigl_seg_stride(d_in);
+    a.act = (int32_t)act;
     if (n_active == 0 || K == 0) {   // nothing is stored: every column holds its bias
         long long blocks = ((long long)B * d_out + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(k_bias_broadcast, dim3((unsigned)blocks), dim3(256), 0, st, bias, B, d_out, y);
+        hipLaunchKernelGGL(k_bias_broadcast, dim3((unsigned)blocks), dim3(256), 0, st, bias, B, d_out, y, a.act);
         return hip_ok(hipGetLastError());
     }
     switch (algo) {
@@ -364,6 +364,24 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
     srigl_status s = launch_fwd_klane(a, nullptr, st);
     if (s == SRIGL_ERR_UNSUPPORTED) s = launch_fwd_generic(a, st);
     return s;
+}
+
+srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
+                                             const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
+                                             const int32_t* active, int32_t n_active, int32_t K,
+                                             const float* bias, int32_t d_out, float* y,
+                                             const uint16_t* seg, srigl_fwd_algo algo,
+                                             const srigl_fwd_tuning* tuning, void* stream) {
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, active, n_active, K, bias, d_out, y, seg, algo, tuning, SRIGL_ACT_NONE, stream);
+}
+
+srigl_status srigl_condensed_linear_fwd_act(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
+                                            const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
+                                            const int32_t* active, int32_t n_active, int32_t K,
+                                            const float* bias, int32_t d_out, float* y,
+                                            const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
+                                            const srigl_fwd_tuning* tuning, void* stream) {
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, active, n_active, K, bias, d_out, y, seg, algo, tuning, act, stream);
 }
 
 srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,

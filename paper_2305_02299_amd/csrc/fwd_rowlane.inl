@@ -180,7 +180,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                                                       const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
-                                                      int C, int n_chunks, int n_btiles, int n_groups, int out_off) {
+                                                      int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act) {
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
@@ -401,8 +401,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             const int col = colv[h];
             if (col < 0) continue;
             if (active)
-                for (int cc = prevv[h]; cc < col; ++cc) yr[cc] = rl_bias_at(bias, cc);
-            if (sg0 + i < n_active && col < d_out) yr[col] = out[row * OS + i] + biasv[h];
+                for (int cc = prevv[h]; cc < col; ++cc) yr[cc] = apply_act(rl_bias_at(bias, cc), act);
+            if (sg0 + i < n_active && col < d_out) yr[col] = apply_act(out[row * OS + i] + biasv[h], act);
         }
     }
     SRIGL_STAMP(14)
@@ -421,7 +421,7 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
     if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
                        a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
-                       p.n_groups, p.out_off);
+                       p.n_groups, p.out_off, a.act);
     return hip_ok(hipGetLastError());
 }
 

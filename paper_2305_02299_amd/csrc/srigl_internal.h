@@ -25,6 +25,7 @@ struct FwdArgs {
     float* y;
     const uint16_t* seg;
     int32_t seg_stride;
+    int32_t act;   // srigl_activation applied to every written value (stored and ablated columns alike)
 };
 
 // Launch shape of the ROWLANE kernel, decided on the host.
@@ -54,5 +55,13 @@ bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
 inline srigl_status hip_ok(hipError_t e) { return e == hipSuccess ? SRIGL_OK : SRIGL_ERR_HIP; }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Activation between the two linear layers of an MLP block: identity, max(v, 0), or v * Phi(v) with the normal
+// distribution function Phi (the exact, erf-based GELU).
+__device__ __forceinline__ float apply_act(float v, int act) {
+    if (act == SRIGL_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == SRIGL_ACT_GELU) return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    return v;
+}
 
 }  // namespace srigl

@@ -291,3 +291,78 @@ def test_structured_only_representation(d_in, d_out, K, B, abl, dtype):
     # and the condensed oracle agrees (both are sums of the same non-zero terms in ascending column order)
     yc = oracle.fwd(xsrc, W_c, idx, active, L.bias, d_out)
     assert np.max(np.abs(y - yc)) <= np.max(np.abs(ref)) * 2.0 ** -23
+
+
+# ---- MLP block: activation and width reduction (Sec. 3.1, App. H) -----------------------------------------
+
+def test_activation_closed_forms():
+    v = np.array([0.0, 1.0, -1.0, 2.5, -2.5, 30.0, -30.0], dtype=np.float32)
+    assert np.array_equal(oracle.activate(v, oracle.ACT_NONE), v)
+    assert np.array_equal(oracle.activate(v, oracle.ACT_RELU), np.maximum(v, 0))
+    g = oracle.activate(v, oracle.ACT_GELU).astype(np.float64)
+    assert g[0] == 0.0
+    assert abs(g[1] - 0.8413447460685429) < 1e-7          # Phi(1), a tabulated constant
+    assert np.allclose(g[1] - g[2], 1.0, atol=1e-7)        # v Phi(v) - (-v) Phi(-v) = v
+    assert np.allclose(g[3] - g[4], 2.5, atol=1e-6)
+    assert g[5] == 30.0 and g[6] == 0.0                    # the tails
+    # against scipy's normal distribution function on a grid
+    from scipy.stats import norm
+    grid = np.linspace(-6, 6, 241).astype(np.float32)
+    assert np.allclose(oracle.activate(grid, oracle.ACT_GELU), grid.astype(np.float64) * norm.cdf(grid.astype(np.float64)),
+                       rtol=1.5e-7, atol=1e-30)     # the result is rounded to fp32 once
+
+
+def test_fold_handworked_fixture():
+    import json
+    import os
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "fold_handworked.json")))
+    idx, W, bias = oracle.fold_ablated_inputs(np.array(fx["idx2"], np.int32), np.array(fx["W_c2"], np.float32),
+                                              np.array(fx["bias2"], np.float32), np.array(fx["active2"], np.int32), fx["d_out2"],
+                                              np.array(fx["active1"], np.int32), fx["d_hidden"], np.array(fx["bias1"], np.float32),
+                                              fx["act"])
+    assert idx.tolist() == fx["expect_idx"]
+    assert W.tolist() == fx["expect_W_c"]
+    assert bias.tolist() == fx["expect_bias"]
+
+
+@pytest.mark.parametrize("act", [0, 1, 2])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_folded_pair_equals_the_unfolded_pair(act, dtype):
+    """linear -> activation -> linear computed two ways with the pinned forward: full-width hidden vector and the original
+    second layer, or compact hidden vector (stored neurons only) and the folded second layer."""
+    L1 = si.make_layer(48, 96, 7, 9, ablate_frac=0.4, dtype=dtype, seed=21)
+    L2 = si.make_layer(96, 40, 13, 9, ablate_frac=0.2, dtype=dtype, seed=22)
+    W1, x = (L1.W_bf16, L1.x_bf16) if dtype == "bf16" else (L1.W, L1.x)
+    W2 = L2.W_bf16 if dtype == "bf16" else L2.W
+    Wc1, idx1, act1 = oracle.condense(W1, L1.mask, L1.K)
+    Wc2, idx2, act2 = oracle.condense(W2, L2.mask, L2.K)
+    conv = (lambda h: si.f32_to_bf16_bits(h)) if dtype == "bf16" else (lambda h: h)
+    # unfolded: hidden at full width, ablated neurons hold act(bias)
+    h_full = oracle.activate(oracle.fwd(x, Wc1, idx1, act1, L1.bias, L1.d_out), act)
+    y_ref, S = oracle.fwd(conv(h_full), Wc2, idx2, act2, L2.bias, L2.d_out, want_scale=True)
+    # folded: hidden holds the stored neurons only
+    h_compact = oracle.activate(oracle.fwd(x, Wc1, idx1, None, L1.bias[act1], len(act1)), act)
+    assert np.array_equal(h_compact, h_full[:, act1])
+    idx_f, W_f, bias_f = oracle.fold_ablated_inputs(idx2, Wc2, L2.bias, act2, L2.d_out, act1, L1.d_out, L1.bias, act)
+    y = oracle.fwd(conv(h_compact), W_f, idx_f, act2, bias_f, L2.d_out)
+    # in bf16 storage the constant act(bias) is rounded to bf16 on the unfolded side only: allow that rounding
+    tol = 1e-6 if dtype == "f32" else 8e-3
+    assert np.all(np.abs(y.astype(np.float64) - y_ref) <= tol * np.maximum(S, 1e-30))
+    # shape of the folded rows
+    assert np.all(np.diff(idx_f, axis=1) > 0) and idx_f.min() >= 0 and idx_f.max() < len(act1)
+    pos = {int(c): p for p, c in enumerate(act1)}
+    for n in range(idx2.shape[0]):
+        kept = [(pos[int(j)], Wc2[n, k]) for k, j in enumerate(idx2[n]) if int(j) in pos]
+        got = {int(i): W_f[n, k] for k, i in enumerate(idx_f[n])}
+        for p_, w in kept:
+            assert got[p_].tobytes() == w.tobytes()
+        fillers = [i for i in got if i not in dict(kept)]
+        assert all(got[i].tobytes() == b"\x00" * W_f.dtype.itemsize for i in fillers)
+        unused_smaller = [g for g in range(max(fillers, default=-1)) if g not in got]
+        assert not unused_smaller                     # fillers are the smallest unused positions
+
+
+def test_fold_refuses_a_fan_in_wider_than_the_compact_layer():
+    idx2 = np.arange(5, dtype=np.int32)[None, :]
+    with pytest.raises(ValueError):
+        oracle.fold_ablated_inputs(idx2, np.ones((1, 5), np.float32), None, None, 1, np.array([0, 2, 4], np.int32), 5, None, 0)
