@@ -162,6 +162,18 @@ srigl_status srigl_condensed_linear_fwd_act(const void* x, srigl_dtype x_dtype, 
                                             const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
                                             const srigl_fwd_tuning* tuning, void* stream);
 
+/* Width reduction.  Layer 1 has d_hidden neurons of which active1[0..n_active1) are stored (NULL: all of them); an
+ * ablated neuron outputs the constant act(bias1).  Layer 2 (n2 stored rows of fan-in K2 over layer 1's d_hidden outputs;
+ * stored row n is neuron active2[n] of d_out2, NULL: n) is rewritten to read the compact vector of the n_active1 stored
+ * outputs: idx_out / W_out [n2][K2] (same element type as W_c2, bit copies; fillers are zero bits; rows ascending and
+ * without repeats, entries in [0, n_active1)), bias_out[d_out2] = bias2 plus, for each stored row, the terms that named
+ * ablated neurons.  All pointers are device memory; outputs must not alias inputs.  SRIGL_ERR_UNSUPPORTED if
+ * K2 > n_active1 (no room for K2 distinct positions) or K2 > 9216.  idx2 entries outside [0, d_hidden) are dropped. */
+srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, srigl_dtype w_dtype, const float* bias2,
+                                       const int32_t* active2, int32_t n2, int32_t K2, int32_t d_out2, const int32_t* active1,
+                                       int32_t n_active1, int32_t d_hidden, const float* bias1, srigl_activation act,
+                                       int32_t* idx_out, void* W_out, float* bias_out, void* stream);
+
 /* ---- structured-only representation -----------------------------------------------------------------
  * Sec. 4.4 / Fig. 4 / App. H compare the condensed layer with the same layer "accelerated using only the
  * ablated neurons without exploiting the fine-grained sparsity": the stored neurons keep dense rows, and

@@ -9,4 +9,4 @@ from . import binding  # noqa: F401  (loads libsrigl.so, raises if it is missing
 from .binding import (BF16, F32, FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE, SriglError,  # noqa: F401
                       srigl_check_fanin, srigl_condense, srigl_condensed_linear_fwd, srigl_seg_stride,
                       srigl_workspace_bytes)
-from .layer import CondensedLinear, condense_layer  # noqa: F401
+from .layer import CondensedLinear, CondensedMLP, condense_layer, fold_mlp  # noqa: F401

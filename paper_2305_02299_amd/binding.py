@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libsrigl.so")
 OK, ERR_INVALID_ARG, ERR_FANIN, ERR_CAPACITY, ERR_INDEX_RANGE, ERR_UNSUPPORTED, ERR_HIP = range(7)
 F32, BF16 = 0, 1
 REPR_CONDENSED, REPR_STRUCTURED = 0, 1
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE = range(4)
 TILE_AUTO, TILE_256x256, TILE_256x256_H, TILE_256x128_W4, TILE_256x128, TILE_128x128, TILE_64x64 = range(7)
 TILES = {"256x256": TILE_256x256, "256x256_h": TILE_256x256_H, "256x128_w4": TILE_256x128_W4, "256x128": TILE_256x128,
@@ -29,6 +30,7 @@ EXPORTS = (
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
+    "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs",
 )
 
 
@@ -72,6 +74,11 @@ def _load() -> ctypes.CDLL:
     lib.srigl_choose_representation.restype = ctypes.c_int
     lib.srigl_choose_representation.argtypes = [i32, i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
                                                 ctypes.POINTER(ctypes.c_float)]
+    lib.srigl_condensed_linear_fwd_act.restype = ctypes.c_int
+    lib.srigl_condensed_linear_fwd_act.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32,
+                                                   vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
+    lib.srigl_fold_ablated_inputs.restype = ctypes.c_int
+    lib.srigl_fold_ablated_inputs.argtypes = [vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, i32, i32, vp, ctypes.c_int, vp, vp, vp, vp]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -147,8 +154,20 @@ def srigl_condense(W, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, wor
     _check(st, "srigl_condense")
 
 
-def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, d_out, y, seg=None, algo=None, tuning=None):
-    """algo None: the library's own entry point; otherwise the forced-algorithm entry point."""
+def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, d_out, y, seg=None, algo=None, tuning=None, act=None):
+    """algo None: the library's own entry point; otherwise the forced-algorithm entry point; act: the entry point with an
+    activation in the epilogue (ACT_* codes)."""
+    if act is not None:
+        tn = None
+        if tuning is not None:
+            tn = FwdTuning()
+            for k, v in tuning.items():
+                setattr(tn, k, int(v))
+        st = lib.srigl_condensed_linear_fwd_act(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
+                                                _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
+                                                int(act), int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
+        _check(st, "srigl_condensed_linear_fwd_act")
+        return
     if algo is None and tuning is None:
         st = lib.srigl_condensed_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
                                             _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
@@ -188,6 +207,14 @@ def srigl_choose_representation(B, d_in, n_active, K, d_out, dtype_code):
     r = lib.srigl_choose_representation(int(B), int(d_in), int(n_active), int(K), int(d_out), int(dtype_code),
                                         ctypes.byref(c), ctypes.byref(s))
     return int(r), c.value, s.value
+
+
+def srigl_fold_ablated_inputs(idx2, W_c2, bias2, active2, n2, K2, d_out2, active1, n_active1, d_hidden, bias1, act,
+                              idx_out, W_out, bias_out):
+    st = lib.srigl_fold_ablated_inputs(_ptr(idx2), _ptr(W_c2), _dtype_code(W_c2), _ptr(bias2), _ptr(active2), int(n2), int(K2),
+                                       int(d_out2), _ptr(active1), int(n_active1), int(d_hidden), _ptr(bias1), int(act),
+                                       _ptr(idx_out), _ptr(W_out), _ptr(bias_out), _stream())
+    _check(st, "srigl_fold_ablated_inputs")
 
 
 def srigl_launch_empty():

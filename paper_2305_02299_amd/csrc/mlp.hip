@@ -1,0 +1,156 @@
+// Width reduction of an MLP block (gfx950).  Neuron ablation reduces the width of a layer (Sec. 3.1 of arXiv 2305.02299):
+// when the first linear layer of a block has ablated neurons, their outputs are the constants act(bias), and the second
+// layer can read the compact vector of the stored neurons' outputs instead of the full-width one.  srigl_fold_ablated_inputs
+// rewrites the second layer's condensed arrays for that: an index naming stored neuron active1[p] becomes p, a term on an
+// ablated neuron moves into the bias of its row's neuron, and the row is filled up to K2 entries again with the smallest
+// positions it does not use, weight zero, in ascending order: it stays a constant fan-in row (App. E layout).
+#include "srigl_internal.h"
+
+namespace srigl {
+
+constexpr size_t kFoldLdsBudget = 144 * 1024;
+
+__global__ __launch_bounds__(256) void k_copy_f32(const float* __restrict__ src, float* __restrict__ dst, int n) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = src ? src[i] : 0.0f;
+}
+
+// One wavefront per stored row of the second layer; all LDS traffic stays inside the wavefront.
+// LDS per wavefront: V[K2] (compact positions of the kept terms, ascending), Wv[K2] (their weight bits),
+// Io[K2] / Wo[K2] (the output row).
+template <typename T>
+__global__ void k_fold_rows(const int32_t* __restrict__ idx2, const T* __restrict__ W_c2, const float* __restrict__ bias2,
+                            const int32_t* __restrict__ active2, int n2, int K2, int d_out2, const int32_t* __restrict__ active1,
+                            int n_active1, int d_hidden, const float* __restrict__ bias1, int act, int32_t* __restrict__ idx_out,
+                            T* __restrict__ W_out, float* __restrict__ bias_out) {
+    extern __shared__ int32_t fold_lds[];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+    const int n = blockIdx.x * (blockDim.x >> 6) + wv;
+    if (n >= n2) return;
+    int32_t* V = fold_lds + (size_t)wv * 4 * K2;
+    uint32_t* Wv = reinterpret_cast<uint32_t*>(V + K2);
+    int32_t* Io = V + 2 * K2;
+    uint32_t* Wo = reinterpret_cast<uint32_t*>(V + 3 * K2);
+    const size_t row = (size_t)n * K2;
+
+    // kept terms -> (position among the stored neurons, weight bits), compacted in order; the others add to the constant
+    int m = 0;
+    float constant = 0.0f;
+    for (int k0 = 0; k0 < K2; k0 += kWave) {
+        const int k = k0 + lane;
+        bool kept = false;
+        int p = -1;
+        uint32_t bits = 0;
+        if (k < K2) {
+            const int j = idx2[row + k];
+            bits = (uint32_t)W_c2[row + k];
+            if (j >= 0 && j < d_hidden) {
+                if (active1 == nullptr) {
+                    kept = true;
+                    p = j;
+                } else {
+                    int lo = 0, hi = n_active1;   // first entry >= j
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (active1[mid] < j) lo = mid + 1; else hi = mid;
+                    }
+                    kept = lo < n_active1 && active1[lo] == j;
+                    p = lo;
+                }
+                if (!kept) {
+                    const float w = sizeof(T) == 4 ? __uint_as_float(bits) : bf16_bits_to_float(bits);
+                    constant = fmaf(w, apply_act(bias1 ? bias1[j] : 0.0f, act), constant);
+                }
+            }
+        }
+        const unsigned long long vote = __ballot(kept);
+        if (kept) {
+            const int at = m + __builtin_amdgcn_mbcnt_hi((unsigned)(vote >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)vote, 0));
+            V[at] = p;
+            Wv[at] = bits;
+        }
+        m += __popcll(vote);
+    }
+    for (int off = kWave / 2; off > 0; off >>= 1) constant += __shfl_xor(constant, off, kWave);
+    if (lane == 0) {
+        const int col = active2 ? active2[n] : n;
+        if (col >= 0 && col < d_out2) bias_out[col] = (bias2 ? bias2[col] : 0.0f) + constant;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    // f fillers are needed: the f smallest positions not in V.  With r* = the first rank whose entry has at least f
+    // unused positions below it (V[r] - r >= f; V[r] - r never decreases), the largest filler is G = f - 1 + r*, and the
+    // output row is 0, 1, ..., G followed by V[r*], V[r* + 1], ...
+    const int f = K2 - m;
+    int rstar = m;
+    for (int r0 = 0; r0 < m && rstar == m; r0 += kWave) {
+        const int r = r0 + lane;
+        const bool hit = r < m && V[r] - r >= f;
+        const unsigned long long vote = __ballot(hit);
+        if (vote) rstar = r0 + __builtin_ctzll(vote);
+    }
+    const int G = f - 1 + rstar;
+    for (int p = lane; p <= G; p += kWave) { Io[p] = p; Wo[p] = 0u; }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int r = lane; r < rstar; r += kWave) Wo[V[r]] = Wv[r];           // kept terms inside the prefix
+    for (int r = rstar + lane; r < m; r += kWave) {                       // kept terms past the prefix
+        Io[G + 1 + (r - rstar)] = V[r];
+        Wo[G + 1 + (r - rstar)] = Wv[r];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int k = lane; k < K2; k += kWave) {
+        idx_out[row + k] = Io[k];
+        W_out[row + k] = (T)Wo[k];
+    }
+}
+
+}  // namespace srigl
+
+using namespace srigl;
+
+extern "C" {
+
+srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, srigl_dtype w_dtype, const float* bias2,
+                                       const int32_t* active2, int32_t n2, int32_t K2, int32_t d_out2, const int32_t* active1,
+                                       int32_t n_active1, int32_t d_hidden, const float* bias1, srigl_activation act,
+                                       int32_t* idx_out, void* W_out, float* bias_out, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n2 < 0 || K2 < 0 || d_out2 < 0 || n_active1 < 0 || d_hidden < 0 || n2 > d_out2 || n_active1 > d_hidden) return SRIGL_ERR_INVALID_ARG;
+    if (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16) return SRIGL_ERR_INVALID_ARG;
+    if (act != SRIGL_ACT_NONE && act != SRIGL_ACT_RELU && act != SRIGL_ACT_GELU) return SRIGL_ERR_INVALID_ARG;
+    if (active1 == nullptr && n_active1 != d_hidden) return SRIGL_ERR_INVALID_ARG;
+    if (active2 == nullptr && n2 != d_out2 && n2 != 0) return SRIGL_ERR_INVALID_ARG;
+    if (d_out2 > 0 && bias_out == nullptr) return SRIGL_ERR_INVALID_ARG;
+    if (n2 > 0 && K2 > 0 && (idx2 == nullptr || W_c2 == nullptr || idx_out == nullptr || W_out == nullptr)) return SRIGL_ERR_INVALID_ARG;
+    if (K2 > n_active1) return SRIGL_ERR_UNSUPPORTED;   // no room for K2 distinct positions
+    if (d_out2 > 0) {
+        int blocks = (d_out2 + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(k_copy_f32, dim3(blocks), dim3(256), 0, st, bias2, bias_out, d_out2);
+    }
+    if (n2 == 0 || K2 == 0) return hip_ok(hipGetLastError());
+    const size_t per_wave = (size_t)16 * K2;
+    if (per_wave > kFoldLdsBudget) return SRIGL_ERR_UNSUPPORTED;
+    int waves = (int)(kFoldLdsBudget / per_wave);
+    if (waves > 4) waves = 4;
+    const size_t lds = per_wave * waves;
+    const unsigned blocks = (unsigned)((n2 + waves - 1) / waves);
+    if (w_dtype == SRIGL_F32) {
+        auto kern = k_fold_rows<uint32_t>;
+        if (lds > 64 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFoldLdsBudget) != hipSuccess)
+            return SRIGL_ERR_HIP;
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, st, idx2, static_cast<const uint32_t*>(W_c2), bias2, active2, n2, K2,
+                           d_out2, active1, n_active1, d_hidden, bias1, (int)act, idx_out, static_cast<uint32_t*>(W_out), bias_out);
+    } else {
+        auto kern = k_fold_rows<uint16_t>;
+        if (lds > 64 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFoldLdsBudget) != hipSuccess)
+            return SRIGL_ERR_HIP;
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, st, idx2, static_cast<const uint16_t*>(W_c2), bias2, active2, n2, K2,
+                           d_out2, active1, n_active1, d_hidden, bias1, (int)act, idx_out, static_cast<uint16_t*>(W_out), bias_out);
+    }
+    return hip_ok(hipGetLastError());
+}
+
+}  // extern "C"
