@@ -229,6 +229,65 @@ def structured(args):
                     "library_dense_tflops": 2.0 * L.B * L.d_out * L.d_in / (t_d * 1e-3) / 1e12}}), flush=True)
 
 
+def mlp(args):
+    """--mlp: the MLP block of a ViT-B (768 -> 3072, GELU, 3072 -> 768; 90 % sparse) with a share of the hidden neurons ablated:
+    both layers at full hidden width against the pair after the width-reduction fold.  One JSON line per point."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2305_02299_amd import binding as B_
+    from paper_2305_02299_amd import condense_layer, fold_mlp
+
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
+
+    def time_graph(fn, steps, warmup):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for i in range(warmup):
+                fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) / steps
+            best = t if best is None else min(best, t)
+        return best
+
+    for abl in (0.0, 0.3, 0.7):
+        for B in (1, 16, 256, 1024):
+            L1 = si.make_layer(768, 3072, 77, B, ablate_frac=abl, seed=1)
+            L2 = si.make_layer(3072, 768, 308, B, ablate_frac=0.0, seed=2)
+            l1 = condense_layer(dev(L1.W), dev(L1.mask), L1.K, dev(L1.bias))
+            l2 = condense_layer(dev(L2.W), dev(L2.mask), L2.K, dev(L2.bias))
+            pair = fold_mlp(l1, l2, B_.ACT_GELU)
+            x = dev(L1.x)
+            h_full = torch.empty((B, 3072), device="cuda")
+            h_c = torch.empty((B, pair.first.d_out), device="cuda")
+            y = torch.empty((B, 768), device="cuda")
+
+            def unfolded(i):
+                B_.srigl_condensed_linear_fwd(x, B, 768, l1.W_c, l1.idx, l1.active, l1.n_active, l1.K, l1.bias, 3072, h_full, l1.seg,
+                                              act=B_.ACT_GELU)
+                B_.srigl_condensed_linear_fwd(h_full, B, 3072, l2.W_c, l2.idx, l2.active, l2.n_active, l2.K, l2.bias, 768, y, l2.seg)
+
+            steps = 200 if B <= 256 else 50
+            t_u = time_graph(unfolded, steps, 5) * 1e3
+            t_f = time_graph(lambda i: pair.forward(x, y, h_c), steps, 5) * 1e3
+            print(json.dumps({"block": "768->3072 GELU 3072->768, K=77/308", "hidden_ablated": abl, "hidden_stored": l1.n_active, "B": B,
+                              "us_full_width": round(t_u, 2), "us_folded": round(t_f, 2)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -240,6 +299,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")
     ap.add_argument("--no-large", action="store_true", help="--sweep without the 4096->16384 bf16 layer")
     ap.add_argument("--no-csr", action="store_true", help="--sweep without the library CSR product (context column)")
+    ap.add_argument("--mlp", action="store_true", help="time the two-layer MLP block with and without the width-reduction fold")
     ap.add_argument("--structured", action="store_true", help="time the structured-only form of the 4096->16384 bf16 layer")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -250,6 +310,8 @@ def main():
         return sweep(args)
     if args.structured:
         return structured(args)
+    if args.mlp:
+        return mlp(args)
 
     import torch
 

@@ -79,8 +79,8 @@ class CondensedMLP:
     stored neurons of layer 1 only (activation applied in layer 1's epilogue) and layer 2 has been rewritten by
     srigl_fold_ablated_inputs to read it.  Holds device buffers and calls the library; no arithmetic here."""
 
-    first: CondensedLinear          # compact output: active None, d_out == n_active
-    second: CondensedLinear         # d_in == first.n_active
+    first: CondensedLinear          # compact output: column p is stored neuron p; width padded to a multiple of 16
+    second: CondensedLinear         # d_in == first.d_out
     act: int
 
     def forward(self, x: torch.Tensor, y: torch.Tensor | None = None, hidden: torch.Tensor | None = None) -> torch.Tensor:
@@ -90,7 +90,7 @@ class CondensedMLP:
             hidden = torch.empty((Bn, f.d_out), dtype=torch.float32, device=x.device)
         if y is None:
             y = torch.empty((Bn, s.d_out), dtype=torch.float32, device=x.device)
-        B_.srigl_condensed_linear_fwd(x, Bn, f.d_in, f.W_c, f.idx, None, f.n_active, f.K, f.bias, f.d_out, hidden, f.seg, act=self.act)
+        B_.srigl_condensed_linear_fwd(x, Bn, f.d_in, f.W_c, f.idx, f.active, f.n_active, f.K, f.bias, f.d_out, hidden, f.seg, act=self.act)
         B_.srigl_condensed_linear_fwd(hidden, Bn, s.d_in, s.W_c, s.idx, s.active, s.n_active, s.K, s.bias, s.d_out, y, s.seg)
         return y
 
@@ -101,19 +101,25 @@ def fold_mlp(layer1: CondensedLinear, layer2: CondensedLinear, act: int) -> Cond
     assert layer1.W_c.dtype == torch.float32 and layer2.W_c.dtype == torch.float32
     dev = layer1.W_c.device
     n1 = layer1.n_active
-    bias1_compact = layer1.bias if layer1.active is None or layer1.bias is None else layer1.bias[layer1.active.long()].contiguous()
-    first = CondensedLinear(layer1.d_in, n1, layer1.K, n1, layer1.W_c, layer1.idx, None, bias1_compact, layer1.seg)
+    # The hidden vector's width is padded to a multiple of 16 columns (the batched kernel stages rows of whole 64-byte
+    # pieces); the padding columns are "ablated neurons" with zero bias, which no row of the second layer reads.
+    n1p = (n1 + 15) // 16 * 16
+    bias1_compact = torch.zeros((n1p,), dtype=torch.float32, device=dev)
+    if layer1.bias is not None:
+        bias1_compact[:n1] = layer1.bias if layer1.active is None else layer1.bias[layer1.active.long()]
+    active_first = None if n1p == n1 else torch.arange(n1, dtype=torch.int32, device=dev)
+    first = CondensedLinear(layer1.d_in, n1p, layer1.K, n1, layer1.W_c, layer1.idx, active_first, bias1_compact, layer1.seg)
     idx_f = torch.empty_like(layer2.idx)
     W_f = torch.empty_like(layer2.W_c)
     bias_f = torch.empty((layer2.d_out,), dtype=torch.float32, device=dev)
     B_.srigl_fold_ablated_inputs(layer2.idx, layer2.W_c, layer2.bias, layer2.active, layer2.n_active, layer2.K, layer2.d_out,
                                  layer1.active, n1, layer1.d_out, layer1.bias, act, idx_f, W_f, bias_f)
     # the chunk table of the rewritten rows (and a check that they are ascending and in range)
-    seg = torch.empty((max(layer2.n_active, 1), B_.srigl_seg_stride(n1)), dtype=torch.int16, device=dev)
+    seg = torch.empty((max(layer2.n_active, 1), B_.srigl_seg_stride(n1p)), dtype=torch.int16, device=dev)
     ws, rep = B_.new_workspace(layer2.n_active, dev), B_.new_report(dev)
-    B_.srigl_check_fanin(None, idx_f, layer2.n_active, n1, layer2.K, seg, ws, rep)
+    B_.srigl_check_fanin(None, idx_f, layer2.n_active, n1p, layer2.K, seg, ws, rep)
     r = B_.read_report(rep)
     if r["status"] != B_.OK:
         raise B_.SriglError(r["status"], "srigl_fold_ablated_inputs produced a bad row (%d)" % r["first_bad_row"])
-    second = CondensedLinear(n1, layer2.d_out, layer2.K, layer2.n_active, W_f, idx_f, layer2.active, bias_f, seg)
+    second = CondensedLinear(n1p, layer2.d_out, layer2.K, layer2.n_active, W_f, idx_f, layer2.active, bias_f, seg)
     return CondensedMLP(first, second, act)

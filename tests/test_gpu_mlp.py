@@ -110,7 +110,7 @@ def test_folded_pair_end_to_end(B_, act, B):
     l1 = condense_layer(dev(L1.W), dev(L1.mask), L1.K, dev(L1.bias))
     l2 = condense_layer(dev(L2.W), dev(L2.mask), L2.K, dev(L2.bias))
     mlp = fold_mlp(l1, l2, act)
-    assert mlp.second.d_in == l1.n_active
+    assert mlp.second.d_in == (l1.n_active + 15) // 16 * 16 and mlp.first.n_active == l1.n_active
     y = mlp.forward(dev(L1.x))
     torch.cuda.synchronize()
     Wc1, idx1, act1 = oracle.condense(L1.W, L1.mask, L1.K)
