@@ -178,6 +178,24 @@ def fold_ablated_inputs(idx2, W_c2, bias2, active2, d_out2, active1, d_hidden, b
     return idx_out, W_out, bias_out
 
 
+def mask_update(W, mask, grad, k, K_upd, gamma_percent, budget=None):
+    """One SRigL connectivity update of a layer (Sec. 3.1 steps 1-7).  Returns (mask', W', info) with info =
+    {k_new, n_remaining, n_ablated_now, n_pruned}."""
+    W = _c(W, np.float32)
+    mask = _c(mask, np.uint8)
+    grad = _c(grad, np.float32)
+    d_out, d_in = mask.shape
+    if budget is None:
+        budget = int(np.count_nonzero(mask))
+    mask_out = np.empty_like(mask)
+    W_out = np.empty_like(W)
+    out4 = np.zeros(4, dtype=np.int64)
+    _load().oracle_mask_update(_p(W), _p(mask), _p(grad), d_out, d_in, int(k), ctypes.c_longlong(int(K_upd)), int(gamma_percent),
+                               ctypes.c_longlong(int(budget)), _p(mask_out), _p(W_out), _p(out4))
+    return mask_out, W_out, {"k_new": int(out4[0]), "n_remaining": int(out4[1]), "n_ablated_now": int(out4[2]),
+                             "n_pruned": int(out4[3])}
+
+
 def fwd_allcores(x, W_c, idx, active, bias, d_out):
     """Timing companion (fp32 accumulate, OpenMP over batch x neurons): returns (y, threads used)."""
     x = _c(x, np.float32)

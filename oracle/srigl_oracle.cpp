@@ -276,6 +276,95 @@ int oracle_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, int elem_b
     return 0;
 }
 
+// One SRigL connectivity update of one layer (Sec. 3.1, steps 1-7), fp32 weights and gradients, in the paper's order.
+// mask: d_out x d_in bytes, every row holds 0 (ablated) or k kept weights.  Readings where the text leaves a choice:
+//  * step 3: salient by the prune criterion = a kept weight that is not among the K_upd smallest-magnitude kept weights of
+//    the layer (it would survive the pruning); salient by the growth criterion = a pruned position among the K_upd
+//    largest-magnitude gradients at pruned positions of the layer (it would be grown); a neuron's count is how many of
+//    both lie in its row.  (Taking "top-K" of the magnitudes literally would leave no salient weight, hence no neuron,
+//    once the update fraction has annealed to zero.)
+//  * step 4: a neuron that holds weights is ablated if its count is below max(gamma * k, 1), gamma = gamma_percent / 100
+//    (App. G: the minimum is one); a neuron without weights on entry stays ablated;
+//  * step 5: k' = min(d_in, budget / number of remaining neurons) in integers (the layer keeps its weight budget);
+//  * step 6: the K_upd smallest-magnitude kept weights of the remaining neurons are pruned, layer-wide;
+//  * step 7: each remaining neuron keeps its unpruned weights (its k' largest, should it hold more than k') and grows the
+//    positions it does not keep in order of decreasing gradient magnitude until it holds k';
+//  * equal magnitudes are ordered by position (lower flat index / column first in every ranking);
+//  * grown weights start at zero, pruned weights are set to zero (as in RigL).
+// out4: {k', remaining neurons, neurons ablated by this update, weights pruned in step 6}.
+struct Ranked { uint32_t key; int64_t pos; };
+static uint32_t magnitude_bits(float v) { uint32_t u; std::memcpy(&u, &v, 4); return u & 0x7fffffffu; }
+
+void oracle_mask_update(const float* W, const uint8_t* mask, const float* grad, int d_out, int d_in, int k, long long K_upd,
+                        int gamma_percent, long long budget, uint8_t* mask_out, float* W_out, long long* out4) {
+    const int64_t N = (int64_t)d_out * d_in;
+    // steps 1-3
+    std::vector<Ranked> kept, pruned;
+    for (int64_t i = 0; i < N; ++i) {
+        if (mask[i]) kept.push_back({magnitude_bits(W[i]), i});
+        else pruned.push_back({magnitude_bits(grad[i]), i});
+    }
+    auto larger_first = [](const Ranked& a, const Ranked& b) { return a.key != b.key ? a.key > b.key : a.pos < b.pos; };
+    auto smaller_first = [](const Ranked& a, const Ranked& b) { return a.key != b.key ? a.key < b.key : a.pos < b.pos; };
+    std::sort(kept.begin(), kept.end(), smaller_first);
+    std::sort(pruned.begin(), pruned.end(), larger_first);
+    std::vector<long long> salient(d_out, 0), held(d_out, 0);
+    for (int64_t t = 0; t < (int64_t)kept.size(); ++t) {
+        ++held[kept[t].pos / d_in];
+        if (t >= K_upd) ++salient[kept[t].pos / d_in];
+    }
+    for (int64_t t = 0; t < (int64_t)pruned.size() && t < K_upd; ++t) ++salient[pruned[t].pos / d_in];
+    // step 4
+    std::vector<char> remains(d_out, 0);
+    long long n_remaining = 0, n_ablated_now = 0;
+    for (int r = 0; r < d_out; ++r) {
+        if (held[r] == 0) continue;
+        const bool too_few = salient[r] < 1 || salient[r] * 100 < (long long)gamma_percent * k;
+        if (too_few) ++n_ablated_now;
+        else { remains[r] = 1; ++n_remaining; }
+    }
+    // step 5
+    long long k_new = n_remaining > 0 ? budget / n_remaining : 0;
+    if (k_new > d_in) k_new = d_in;
+    // step 6
+    std::vector<Ranked> candidates;
+    for (const Ranked& e : kept)
+        if (remains[e.pos / d_in]) candidates.push_back(e);
+    std::sort(candidates.begin(), candidates.end(), smaller_first);
+    std::vector<char> keep(N, 0);
+    long long n_pruned = 0;
+    for (int64_t t = 0; t < (int64_t)candidates.size(); ++t) {
+        if (t < K_upd) ++n_pruned;
+        else keep[candidates[t].pos] = 1;
+    }
+    // step 7
+    for (int64_t i = 0; i < N; ++i) { mask_out[i] = 0; W_out[i] = 0.0f; }
+    for (int r = 0; r < d_out; ++r) {
+        if (!remains[r]) continue;
+        std::vector<Ranked> mine, others;
+        for (int c = 0; c < d_in; ++c) {
+            const int64_t i = (int64_t)r * d_in + c;
+            if (keep[i]) mine.push_back({magnitude_bits(W[i]), (int64_t)c});
+            else others.push_back({magnitude_bits(grad[i]), (int64_t)c});
+        }
+        std::sort(mine.begin(), mine.end(), larger_first);
+        std::sort(others.begin(), others.end(), larger_first);
+        long long have = 0;
+        for (const Ranked& e : mine) {
+            if (have == k_new) break;
+            mask_out[(int64_t)r * d_in + e.pos] = 1;
+            W_out[(int64_t)r * d_in + e.pos] = W[(int64_t)r * d_in + e.pos];
+            ++have;
+        }
+        for (const Ranked& e : others) {
+            if (have == k_new) break;
+            mask_out[(int64_t)r * d_in + e.pos] = 1;   // grown: weight starts at zero
+            ++have;
+        }
+    }
+    out4[0] = k_new; out4[1] = n_remaining; out4[2] = n_ablated_now; out4[3] = n_pruned;
+}
+
 // Timing companion of oracle_fwd_f32 (not used for parity): the same three loops of Alg. 1 with fp32
 // accumulation and the batch x neuron iterations spread over the host cores with OpenMP.  It exists so that
 // the benchmark can say what all host cores do with the plain loops; nothing else is changed or tuned.

@@ -366,3 +366,86 @@ def test_fold_refuses_a_fan_in_wider_than_the_compact_layer():
     idx2 = np.arange(5, dtype=np.int32)[None, :]
     with pytest.raises(ValueError):
         oracle.fold_ablated_inputs(idx2, np.ones((1, 5), np.float32), None, None, 1, np.array([0, 2, 4], np.int32), 5, None, 0)
+
+
+# ---- SRigL connectivity update (Sec. 3.1 steps 1-7) ---------------------------------------------------------
+
+def _mask_update_by_lexsort(W, mask, grad, k, K_upd, gamma_percent, budget):
+    """The same reading of Sec. 3.1 written with whole-array numpy primitives (lexsort rankings), for tiny inputs."""
+    d_out, d_in = mask.shape
+    mag = np.abs(W).view(np.uint32).astype(np.int64).ravel()
+    gmag = np.abs(grad).view(np.uint32).astype(np.int64).ravel()
+    pos = np.arange(d_out * d_in)
+    kept = mask.ravel() != 0
+    kp, pp = pos[kept], pos[~kept]
+    kp = kp[np.lexsort((kp, mag[kp]))]                       # ascending magnitude, then position
+    pp = pp[np.lexsort((pp, -gmag[pp]))]                     # descending gradient, then position
+    salient = np.bincount(kp[K_upd:] // d_in, minlength=d_out) + np.bincount(pp[:K_upd] // d_in, minlength=d_out)
+    held = mask.sum(axis=1)
+    remains = (held > 0) & ~((salient < 1) | (salient * 100 < gamma_percent * k))
+    n_rem = int(remains.sum())
+    k_new = min(d_in, budget // n_rem) if n_rem else 0
+    cand = kp[remains[kp // d_in]]
+    keep = np.zeros(d_out * d_in, bool)
+    keep[cand[K_upd:]] = True
+    m2 = np.zeros_like(mask)
+    W2 = np.zeros_like(W)
+    for r in np.flatnonzero(remains):
+        cols = np.arange(d_in)
+        kr = keep[r * d_in:(r + 1) * d_in]
+        mine = cols[kr][np.lexsort((cols[kr], -mag[r * d_in + cols[kr]]))][:k_new]
+        free = cols[~kr][np.lexsort((cols[~kr], -gmag[r * d_in + cols[~kr]]))][:max(k_new - len(mine), 0)]
+        m2[r, mine] = 1
+        m2[r, free] = 1
+        W2[r, mine] = W[r, mine]
+    return m2, W2, {"k_new": k_new, "n_remaining": n_rem, "n_ablated_now": int(((held > 0) & ~remains).sum()),
+                    "n_pruned": int(min(K_upd, len(cand)))}
+
+
+def test_mask_update_handworked_fixture():
+    import json
+    import os
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "mask_update_handworked.json")))
+    m, w, info = oracle.mask_update(np.array(fx["W"], np.float32), np.array(fx["mask"], np.uint8), np.array(fx["grad"], np.float32),
+                                    fx["k"], fx["K_upd"], fx["gamma_percent"], fx["budget"])
+    assert m.tolist() == fx["expect_mask"]
+    assert w.tolist() == np.array(fx["expect_W"], np.float32).tolist()
+    assert info == fx["expect_info"]
+
+
+def test_mask_update_without_pruning_or_ablation_changes_nothing():
+    L = si.make_layer(40, 30, 6, 1, ablate_frac=0.2, seed=4)
+    g = np.random.default_rng(1).normal(size=L.W.shape).astype(np.float32)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    m, w, info = oracle.mask_update(Wm, L.mask, g, L.K, 0, 0)
+    assert np.array_equal(m, L.mask) and w.tobytes() == Wm.tobytes()
+    assert info == {"k_new": L.K, "n_remaining": int((L.mask.sum(axis=1) > 0).sum()), "n_ablated_now": 0, "n_pruned": 0}
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_mask_update_invariants_and_lexsort_crosscheck(seed):
+    rng = np.random.default_rng(100 + seed)
+    d_in, d_out, k = int(rng.integers(8, 40)), int(rng.integers(6, 30)), 0
+    k = int(rng.integers(1, d_in // 2 + 1))
+    L = si.make_layer(d_in, d_out, k, 1, ablate_frac=float(rng.choice([0.0, 0.3])), seed=seed)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    g = rng.normal(size=L.W.shape).astype(np.float32)
+    if seed % 2:                      # coarse values: many equal magnitudes, so the position order decides
+        Wm = (np.round(Wm * 4) / 4).astype(np.float32)
+        g = (np.round(g * 2) / 2).astype(np.float32)
+    n_kept = int(L.mask.sum())
+    K_upd = int(rng.integers(0, n_kept // 2 + 1))
+    gamma = int(rng.choice([0, 30, 60, 95]))
+    m, w, info = oracle.mask_update(Wm, L.mask, g, k, K_upd, gamma)
+    m2, w2, info2 = _mask_update_by_lexsort(Wm, L.mask, g, k, K_upd, gamma, n_kept)
+    assert np.array_equal(m, m2) and w.tobytes() == w2.tobytes() and info == info2
+    rows = m.sum(axis=1)
+    assert set(np.unique(rows)) <= {0, info["k_new"]}                       # constant fan-in k' or ablated
+    assert int((rows > 0).sum()) == info["n_remaining"] or info["k_new"] == 0
+    assert np.all(rows[L.mask.sum(axis=1) == 0] == 0)                          # an ablated neuron stays ablated
+    assert info["k_new"] * info["n_remaining"] <= n_kept                       # the layer's weight budget is not exceeded
+    assert info["k_new"] >= k or info["n_remaining"] == 0                      # fewer neurons share the same budget
+    assert np.all(w[m == 0] == 0)
+    same = (m != 0) & (L.mask != 0) & (w != 0)
+    assert np.array_equal(w[same], Wm[same])                                   # kept weights are copied, grown ones are zero
+    assert np.all(w[(m != 0) & (L.mask == 0)] == 0)
