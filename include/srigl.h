@@ -174,6 +174,26 @@ srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, sr
                                        int32_t n_active1, int32_t d_hidden, const float* bias1, srigl_activation act,
                                        int32_t* idx_out, void* W_out, float* bias_out, void* stream);
 
+/* ---- one SRigL connectivity update of a layer ------------------------------------------------------------
+ * Sec. 3.1, steps 1-7 (with App. G's minimum of one salient weight).  W, grad: fp32 [d_out][d_in]; mask: bytes, every
+ * row holds 0 (ablated) or k kept weights; K_upd: the number of weights pruned and grown in this update (step 2, chosen
+ * by the caller's schedule); gamma_percent: the ablation threshold gamma_sal in percent; budget: the number of weights the
+ * layer may hold (normally k times its neurons that hold weights).  Outputs: mask_out (every row 0 or k' ones), W_out (kept
+ * weights copied, everything else zero: grown weights start at zero), report_dev[4] = {k', neurons that remain, neurons
+ * ablated by this update, weights pruned in step 6}.  All buffers are device memory, caller-owned; outputs must not alias
+ * inputs; workspace of srigl_mask_update_workspace_bytes(d_out) bytes.  Asynchronous on `stream`.
+ * Readings: a kept weight is salient if it is not among the K_upd smallest-magnitude kept weights of the layer, a pruned
+ * position if its gradient is among the K_upd largest at pruned positions; a neuron is ablated if it holds weights and
+ * its salient count is below max(gamma k, 1); a neuron without weights stays ablated; k' = min(d_in, budget / remaining
+ * neurons); step 6 prunes among the remaining neurons' weights; step 7 keeps a neuron's unpruned weights (its k' largest
+ * if it holds more) and grows free positions by decreasing gradient magnitude; equal magnitudes rank by position (lower
+ * first).  d_out * d_in must be below 2^32. */
+size_t srigl_mask_update_workspace_bytes(int32_t d_out);
+
+srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float* grad, int32_t d_out, int32_t d_in, int32_t k,
+                               int64_t K_upd, int32_t gamma_percent, int64_t budget, uint8_t* mask_out, float* W_out,
+                               void* workspace, size_t workspace_bytes, int64_t* report_dev, void* stream);
+
 /* ---- structured-only representation -----------------------------------------------------------------
  * Sec. 4.4 / Fig. 4 / App. H compare the condensed layer with the same layer "accelerated using only the
  * ablated neurons without exploiting the fine-grained sparsity": the stored neurons keep dense rows, and

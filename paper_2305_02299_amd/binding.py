@@ -30,7 +30,7 @@ EXPORTS = (
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
-    "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs",
+    "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
 )
 
 
@@ -79,6 +79,10 @@ def _load() -> ctypes.CDLL:
                                                    vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
     lib.srigl_fold_ablated_inputs.restype = ctypes.c_int
     lib.srigl_fold_ablated_inputs.argtypes = [vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, i32, i32, vp, ctypes.c_int, vp, vp, vp, vp]
+    lib.srigl_mask_update_workspace_bytes.restype = sz
+    lib.srigl_mask_update_workspace_bytes.argtypes = [i32]
+    lib.srigl_mask_update.restype = ctypes.c_int
+    lib.srigl_mask_update.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_int64, i32, ctypes.c_int64, vp, vp, vp, sz, vp, vp]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -215,6 +219,18 @@ def srigl_fold_ablated_inputs(idx2, W_c2, bias2, active2, n2, K2, d_out2, active
                                        int(d_out2), _ptr(active1), int(n_active1), int(d_hidden), _ptr(bias1), int(act),
                                        _ptr(idx_out), _ptr(W_out), _ptr(bias_out), _stream())
     _check(st, "srigl_fold_ablated_inputs")
+
+
+def srigl_mask_update_workspace_bytes(d_out: int) -> int:
+    return int(lib.srigl_mask_update_workspace_bytes(int(d_out)))
+
+
+def srigl_mask_update(W, mask, grad, d_out, d_in, k, K_upd, gamma_percent, budget, mask_out, W_out, workspace, report):
+    """report: int64[4] device tensor -> {k', remaining neurons, ablated by this update, pruned in step 6}."""
+    st = lib.srigl_mask_update(_ptr(W), _ptr(mask), _ptr(grad), int(d_out), int(d_in), int(k), int(K_upd), int(gamma_percent),
+                               int(budget), _ptr(mask_out), _ptr(W_out), _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(), _ptr(report), _stream())
+    _check(st, "srigl_mask_update")
 
 
 def srigl_launch_empty():

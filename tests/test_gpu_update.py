@@ -1,0 +1,126 @@
+"""GPU parity of one SRigL connectivity update (Sec. 3.1 steps 1-7) against the oracle: masks, weights and the report are
+integer / bit-copy work and must match exactly, including the order of equal magnitudes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B_():
+    from paper_2305_02299_amd import binding
+    return binding
+
+
+def run_update(B_, Wm, mask, grad, k, K_upd, gamma, budget=None):
+    d_out, d_in = mask.shape
+    if budget is None:
+        budget = int(np.count_nonzero(mask))
+    mask_o = torch.full((d_out, d_in), 7, dtype=torch.uint8, device="cuda")
+    W_o = torch.full((d_out, d_in), float("nan"), device="cuda")
+    ws = torch.empty(B_.srigl_mask_update_workspace_bytes(d_out), dtype=torch.uint8, device="cuda")
+    rep = torch.full((4,), -1, dtype=torch.int64, device="cuda")
+    B_.srigl_mask_update(dev(Wm), dev(mask), dev(grad), d_out, d_in, k, K_upd, gamma, budget, mask_o, W_o, ws, rep)
+    torch.cuda.synchronize()
+    r = rep.cpu().tolist()
+    return host(mask_o), host(W_o), {"k_new": r[0], "n_remaining": r[1], "n_ablated_now": r[2], "n_pruned": r[3]}
+
+
+def check(B_, Wm, mask, grad, k, K_upd, gamma, budget=None):
+    m_ref, w_ref, info_ref = oracle.mask_update(Wm, mask, grad, k, K_upd, gamma, budget)
+    m, w, info = run_update(B_, Wm, mask, grad, k, K_upd, gamma, budget)
+    assert info == info_ref
+    assert np.array_equal(m, m_ref)
+    assert w.tobytes() == w_ref.tobytes()
+    return info
+
+
+def test_handworked_fixture(B_):
+    import json
+    import os
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "mask_update_handworked.json")))
+    m, w, info = run_update(B_, np.array(fx["W"], np.float32), np.array(fx["mask"], np.uint8), np.array(fx["grad"], np.float32),
+                            fx["k"], fx["K_upd"], fx["gamma_percent"], fx["budget"])
+    assert m.tolist() == fx["expect_mask"] and info == fx["expect_info"]
+    assert w.tolist() == np.array(fx["expect_W"], np.float32).tolist()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_layers(B_, seed):
+    rng = np.random.default_rng(500 + seed)
+    d_in, d_out = int(rng.integers(8, 700)), int(rng.integers(4, 300))
+    k = int(rng.integers(1, max(2, d_in // 3)))
+    L = si.make_layer(d_in, d_out, k, 1, ablate_frac=float(rng.choice([0.0, 0.2, 0.5])), seed=seed)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    g = rng.normal(size=L.W.shape).astype(np.float32)
+    if seed % 3 == 1:                 # coarse values: many equal magnitudes, the position order decides
+        Wm = (np.round(Wm * 8) / 8).astype(np.float32)
+        g = (np.round(g * 2) / 2).astype(np.float32)
+    n_kept = int(L.mask.sum())
+    K_upd = int(rng.integers(0, n_kept // 2 + 1))
+    gamma = int(rng.choice([0, 30, 60, 95]))
+    info = check(B_, Wm, L.mask, g, k, K_upd, gamma)
+    print("seed %d: %dx%d k=%d K_upd=%d gamma=%d -> %s" % (seed, d_out, d_in, k, K_upd, gamma, info))
+
+
+def test_no_update_changes_nothing(B_):
+    L = si.make_layer(96, 50, 9, 1, ablate_frac=0.2, seed=4)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    g = np.random.default_rng(1).normal(size=L.W.shape).astype(np.float32)
+    m, w, info = run_update(B_, Wm, L.mask, g, L.K, 0, 0)
+    assert np.array_equal(m, L.mask) and w.tobytes() == Wm.tobytes() and info["n_pruned"] == 0 and info["k_new"] == L.K
+
+
+def test_everything_pruned_and_regrown_by_gradient(B_):
+    """K_upd = every kept weight: each remaining neuron regrows k' positions purely by gradient magnitude."""
+    L = si.make_layer(64, 20, 5, 1, seed=8)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    g = np.random.default_rng(2).normal(size=L.W.shape).astype(np.float32)
+    check(B_, Wm, L.mask, g, L.K, int(L.mask.sum()), 0)
+
+
+def test_smaller_budget_trims_rows(B_):
+    """A budget below the current weight count makes k' < k: rows keep their largest weights only."""
+    L = si.make_layer(64, 20, 8, 1, seed=9)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    g = np.random.default_rng(3).normal(size=L.W.shape).astype(np.float32)
+    info = check(B_, Wm, L.mask, g, L.K, 3, 0, budget=20 * 5)
+    assert info["k_new"] == 5
+
+
+def test_vit_sized_layer_and_the_result_condenses(B_):
+    """768 -> 3072 at 90 % sparsity, 30 % of the weights updated, gamma 30 %: exact against the oracle, and the new mask passes
+    the constant fan-in check of the forward path."""
+    L = si.config("c2")
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    g = np.random.default_rng(5).normal(size=L.W.shape).astype(np.float32)
+    # give a tenth of the neurons tiny weights and gradients so that some are ablated
+    weak = np.random.default_rng(6).choice(L.d_out, L.d_out // 10, replace=False)
+    Wm[weak] *= 1e-3
+    g[weak] *= 1e-3
+    K_upd = int(0.3 * L.mask.sum())
+    info = check(B_, Wm, L.mask, g, L.K, K_upd, 30)
+    assert info["n_ablated_now"] > 0 and info["k_new"] >= L.K
+    m, w, _ = run_update(B_, Wm, L.mask, g, L.K, K_upd, 30)
+    ws, rep = B_.new_workspace(L.d_out), B_.new_report()
+    B_.srigl_check_fanin(dev(m), None, L.d_out, L.d_in, info["k_new"], None, ws, rep)
+    r = B_.read_report(rep)
+    assert r["status"] == B_.OK and r["K"] == info["k_new"] and r["n_active"] == info["n_remaining"]
+
+
+def test_argument_errors(B_):
+    z = torch.zeros((4, 4), device="cuda")
+    zm = torch.zeros((4, 4), dtype=torch.uint8, device="cuda")
+    rep = torch.zeros(4, dtype=torch.int64, device="cuda")
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B_.SriglError) as e:
+        B_.srigl_mask_update(z, zm, z, 4, 4, 2, 1, 30, 8, zm.clone(), z.clone(), small, rep)
+    assert e.value.status == B_.ERR_CAPACITY
+    ws = torch.empty(B_.srigl_mask_update_workspace_bytes(4), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B_.SriglError):
+        B_.srigl_mask_update(z, zm, z, 4, 4, 5, 1, 30, 8, zm.clone(), z.clone(), ws, rep)     # k > d_in
