@@ -288,6 +288,58 @@ def mlp(args):
                               "us_full_width": round(t_u, 2), "us_folded": round(t_f, 2)}), flush=True)
 
 
+def update(args):
+    """--update: one SRigL connectivity update (Sec. 3.1 steps 1-7) of the 768 -> 3072 layer (90 % sparse, 30 % of the kept
+    weights pruned and regrown, gamma_sal 30 %) and of the 4096 -> 16384 layer; one JSON line per layer, the CPU oracle timed
+    on the small one."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2305_02299_amd import binding as B_
+
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
+    for name in ("c2", "c5"):
+        L = si.config(name)
+        Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+        g = np.random.default_rng(5).normal(size=L.W.shape).astype(np.float32)
+        n_kept = int(L.mask.sum())
+        K_upd = int(0.3 * n_kept)
+        W_d, m_d, g_d = dev(Wm), dev(L.mask), dev(g)
+        mask_o, W_o = torch.empty_like(m_d), torch.empty_like(W_d)
+        ws = torch.empty(B_.srigl_mask_update_workspace_bytes(L.d_out), dtype=torch.uint8, device="cuda")
+        rep = torch.zeros(4, dtype=torch.int64, device="cuda")
+
+        def call():
+            B_.srigl_mask_update(W_d, m_d, g_d, L.d_out, L.d_in, L.K, K_upd, 30, n_kept, mask_o, W_o, ws, rep)
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        steps = 20
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / steps * 1e3
+        N = L.d_out * L.d_in
+        nbytes = 14 * N            # W, grad, W_out: 4 bytes each; mask, mask_out: 1 byte each, every element once
+        cpu = None
+        if name == "c2" and not args.no_cpu:
+            import oracle
+            t0 = time.perf_counter()
+            oracle.mask_update(Wm, L.mask, g, L.K, K_upd, 30)
+            cpu = {"value": (time.perf_counter() - t0) * 1e6, "unit": "us/call", "cores": 1, "kind": "oracle", "sample": "one call"}
+        print(json.dumps({"metric": "mask_update_us_per_call", "value": us, "unit": "us/call", "n_gpus": 1, "steps": steps,
+                          "dtype": "f32", "data": "synthetic",
+                          "config": {"workload": "%s: %d x %d, k=%d, K_upd=%d, gamma_sal=30%%" % (name, L.d_out, L.d_in, L.K, K_upd)},
+                          "report": dict(zip(("k_new", "n_remaining", "n_ablated_now", "n_pruned"), rep.cpu().tolist())),
+                          "roofline": {"bound": "hbm", "achieved": nbytes / us / 1e3, "peak": 8000.0, "unit": "GB/s",
+                                       "frac": nbytes / us / 1e3 / 8000.0, "traffic": None, "algorithmic_bytes": nbytes},
+                          "cpu_baseline": cpu}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -299,6 +351,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")
     ap.add_argument("--no-large", action="store_true", help="--sweep without the 4096->16384 bf16 layer")
     ap.add_argument("--no-csr", action="store_true", help="--sweep without the library CSR product (context column)")
+    ap.add_argument("--update", action="store_true", help="time one SRigL connectivity update of a layer")
     ap.add_argument("--mlp", action="store_true", help="time the two-layer MLP block with and without the width-reduction fold")
     ap.add_argument("--structured", action="store_true", help="time the structured-only form of the 4096->16384 bf16 layer")
     args = ap.parse_args()
@@ -312,6 +365,8 @@ def main():
         return structured(args)
     if args.mlp:
         return mlp(args)
+    if args.update:
+        return update(args)
 
     import torch
 

@@ -187,7 +187,7 @@ srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, sr
  * its salient count is below max(gamma k, 1); a neuron without weights stays ablated; k' = min(d_in, budget / remaining
  * neurons); step 6 prunes among the remaining neurons' weights; step 7 keeps a neuron's unpruned weights (its k' largest
  * if it holds more) and grows free positions by decreasing gradient magnitude; equal magnitudes rank by position (lower
- * first).  d_out * d_in must be below 2^32. */
+ * first).  d_out * d_in must be below 2^32 and d_in at most 8192, else SRIGL_ERR_UNSUPPORTED. */
 size_t srigl_mask_update_workspace_bytes(int32_t d_out);
 
 srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float* grad, int32_t d_out, int32_t d_in, int32_t k,

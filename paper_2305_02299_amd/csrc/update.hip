@@ -5,24 +5,33 @@
 //
 // Every ranking is a selection of the K largest of unique 64-bit keys, (magnitude bits, position): equal magnitudes are
 // ordered by position, so the selected set is unique and no sort is needed.  Layer-wide selections (steps 3 and 6) find the
-// K-th largest key by a most-significant-digit-first radix walk: 8 passes of (histogram of one byte over the elements that
-// match the prefix found so far, pick the byte).  Row-wise selections (step 7) do the same walk inside one workgroup per row.
+// K-th largest key by a most-significant-digit-first radix walk: passes of (histogram of one byte over the elements that
+// match the prefix found so far, then the byte that holds the K-th key), ended as soon as every key of the chosen byte is
+// wanted.  The two selections of step 3 share their passes, and every workgroup of a pass picks the previous pass's byte for
+// itself from that pass's own counters (no pick launches, no device-wide fences); step 6 reuses step 3's answer when no
+// neuron was ablated.  Row-wise selections (step 7) do the same walk inside one workgroup per row, on keys held in registers.
 #include "srigl_internal.h"
 
 namespace srigl {
 
 struct SelState {
-    unsigned long long threshold;   // after the walk: the K-th largest key (select key >= threshold)
-    unsigned long long k_rem;       // how many of the keys with the current prefix are still wanted
+    unsigned long long prefix;      // the bytes of the K-th largest key found so far (right-aligned); at the end: the key itself
+    unsigned long long k_rem;       // how many of the keys with this prefix are still wanted
     unsigned long long total;       // number of candidate keys
-    int done;                       // the threshold is final (nothing wanted: ~0; everything wanted: 0; or 8 passes walked)
+    int done;                       // the threshold is final (nothing wanted: ~0; everything wanted: 0; or the walk has ended)
     int pad;
 };
 
-struct UpdateScratch {              // head of the workspace
-    unsigned int hist[256];
-    SelState sel[3];                // 0: smallest kept weights of the layer, 1: largest gradients at pruned positions,
-                                    // 2: smallest kept weights of the remaining neurons
+// Head of the workspace.  Selections: 0 = smallest kept weights of the layer, 1 = largest gradients at pruned positions,
+// 2 = smallest kept weights of the remaining neurons.  Pass p of a walk adds into hist[sel][p]; the launch of pass p + 1
+// reads it (every workgroup picks the byte of pass p for itself), so no launch reads and clears the same counters, and no
+// device-wide fence is needed (on this multi-die GPU such a fence costs about 0.1 ms per launch).
+// slot[sel][p & 1] = the walk's state before pass p (written by workgroup 0 of the launch of pass p, read by the next launch);
+// fin[sel] = the finished selection: select key >= fin.prefix.
+struct UpdateScratch {
+    unsigned int hist[3][8][256];
+    SelState slot[3][2];
+    SelState fin[3];
     long long k_new, n_remaining, n_ablated_now, n_pruned;
 };
 
@@ -36,87 +45,145 @@ __device__ __forceinline__ unsigned long long key_large_first(unsigned int mag, 
     return ((unsigned long long)mag << 32) | (0xffffffffu - pos);
 }
 
-__global__ void k_update_init(UpdateScratch* s, long long K_upd) {
+__global__ __launch_bounds__(256) void k_update_init(UpdateScratch* s, long long K_upd) {
     const int t = threadIdx.x;
-    if (t < 256) s->hist[t] = 0;
+    for (int i = t; i < 3 * 8 * 256; i += 256) (&s->hist[0][0][0])[i] = 0;
     if (t < 3) {
-        s->sel[t].threshold = 0;
-        s->sel[t].k_rem = (unsigned long long)K_upd;
-        s->sel[t].total = 0;
-        s->sel[t].done = 0;
+        SelState z;
+        z.prefix = 0; z.k_rem = (unsigned long long)K_upd; z.total = 0; z.done = 0; z.pad = 0;
+        s->slot[t][0] = z;
+        s->slot[t][1] = z;
+        s->fin[t] = z;
     }
 }
 
-// MODE 0: kept weights, key_small_first(|w|);  1: pruned positions, key_large_first(|grad|);
-// MODE 2: kept weights of remaining neurons, key_small_first(|w|)
-template <int MODE>
-__device__ __forceinline__ bool layer_key(const float* __restrict__ W, const uint8_t* __restrict__ mask, const float* __restrict__ grad,
-                                          const int* __restrict__ remains, unsigned int i, int d_in, unsigned long long& key) {
-    const bool kept = mask[i] != 0;
-    if (MODE == 1) {
-        if (kept) return false;
-        key = key_large_first(mag_bits(grad[i]), i);
-        return true;
+// From a 256-bin histogram (lane l reads bins 4l .. 4l + 3), for one wavefront: the byte d with suffix(d) >= want >
+// suffix(d + 1), suffix(d) = number of keys whose byte is >= d; `above` = suffix(d + 1), `in_bin` = keys with byte d, `total`
+// = suffix(0).  The results are the same on every lane.
+__device__ __forceinline__ void pick_byte(const unsigned int* h, unsigned long long want, int lane, unsigned long long& digit,
+                                          unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
+    unsigned long long v[4], part[5];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = h[4 * lane + j];
+    part[4] = 0;
+#pragma unroll
+    for (int j = 3; j >= 0; --j) part[j] = part[j + 1] + v[j];
+    unsigned long long incl = part[0];   // becomes the sum over this lane and the lanes above it
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long up = __shfl_down(incl, off, 64);
+        if (lane + off < 64) incl += up;
     }
-    if (!kept) return false;
-    if (MODE == 2 && !remains[i / (unsigned)d_in]) return false;
-    key = key_small_first(mag_bits(W[i]), i);
-    return true;
+    const unsigned long long excl = incl - part[0];
+    total = __shfl(incl, 0, 64);
+    bool found = false;
+    digit = 0; above = 0; in_bin = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (excl + part[j] >= want && excl + part[j + 1] < want) {
+            found = true;
+            digit = 4 * lane + j;
+            above = excl + part[j + 1];
+            in_bin = v[j];
+        }
+    }
+    const unsigned long long owner = __ballot(found);
+    const int src = owner ? __builtin_ctzll(owner) : 0;
+    digit = __shfl(digit, src, 64);
+    above = __shfl(above, src, 64);
+    in_bin = __shfl(in_bin, src, 64);
 }
 
-template <int MODE>
+// The state of a layer-wide walk before pass `pass` (1..8), from the state before pass - 1 and the histogram of pass - 1.
+// Called by one whole wavefront; the result is the same on every lane.
+__device__ SelState advance(const SelState& before, const unsigned int* __restrict__ hist_prev, int pass, int lane) {
+    SelState st = before;
+    if (st.done) return st;
+    unsigned long long digit, above, in_bin, total;
+    pick_byte(hist_prev, st.k_rem == 0 ? 1 : st.k_rem, lane, digit, above, in_bin, total);
+    if (pass == 1) {
+        st.total = total;
+        if (st.k_rem == 0 || total < st.k_rem) {
+            st.prefix = (st.k_rem == 0) ? ~0ull : 0ull;   // nothing / everything
+            st.done = 1;
+            return st;
+        }
+    }
+    st.prefix = (st.prefix << 8) | digit;
+    st.k_rem -= above;
+    // every key of the chosen byte is wanted (always so once the keys under the prefix are down to one): the walk is over,
+    // the threshold is the smallest key with this prefix
+    if (pass == 8 || st.k_rem == in_bin) {
+        if (pass < 8) st.prefix <<= 64 - 8 * pass;
+        st.done = 1;
+    }
+    return st;
+}
+
+// One pass of the walk.  PAIR: selections 0 (kept weights, smallest first) and 1 (pruned positions, largest gradient first)
+// together: every element belongs to exactly one of them, so one read of the layer serves both.  Otherwise selection 2
+// (kept weights of the remaining neurons).  kCopies sub-histograms spread the LDS atomics of equal bytes.
+constexpr int kCopies = 8;
+template <bool PAIR>
 __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, const int* __restrict__ remains, unsigned int N,
                                                     int d_in, int pass, UpdateScratch* __restrict__ s) {
-    __shared__ unsigned int h[256];
-    if (s->sel[MODE].done) return;
-    h[threadIdx.x] = 0;
+    __shared__ unsigned int h[2][kCopies][256];
+    __shared__ SelState cur[2];
+    const int t = threadIdx.x;
+    const int selA = PAIR ? 0 : 2;
+    if (t < 64) {
+        SelState a = s->slot[selA][(pass + 1) & 1], b = s->slot[1][(pass + 1) & 1];   // the states before pass - 1
+        if (pass > 0) {
+            a = advance(a, s->hist[selA][pass - 1], pass, t);
+            if (PAIR) b = advance(b, s->hist[1][pass - 1], pass, t);
+            if (blockIdx.x == 0 && t == 0) {
+                s->slot[selA][pass & 1] = a;
+                if (PAIR) s->slot[1][pass & 1] = b;
+            }
+        } else {
+            a = s->slot[selA][0];
+            b = s->slot[1][0];
+        }
+        if (t == 0) { cur[0] = a; cur[1] = b; }
+    }
+    for (int i = t; i < 2 * kCopies * 256; i += 256) (&h[0][0][0])[i] = 0;
     __syncthreads();
+    const bool doneA = cur[0].done != 0, doneB = PAIR ? cur[1].done != 0 : true;
+    if (doneA && doneB) return;
     const int shift = 56 - 8 * pass;
-    const unsigned long long prefix = s->sel[MODE].threshold;   // the bytes found so far, right-aligned
-    for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x; i < N; i += (unsigned long long)gridDim.x * 256) {
-        unsigned long long key;
-        if (!layer_key<MODE>(W, mask, grad, remains, (unsigned int)i, d_in, key)) continue;
-        if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
-        atomicAdd(&h[(unsigned int)(key >> shift) & 255u], 1u);
+    const unsigned long long prefixA = cur[0].prefix, prefixB = cur[1].prefix;
+    const int copy = t & (kCopies - 1);
+    for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < N; i += (unsigned long long)gridDim.x * 256) {
+        const unsigned int ii = (unsigned int)i;
+        if (mask[ii] != 0) {
+            if (doneA || (!PAIR && !remains[ii / (unsigned)d_in])) continue;
+            const unsigned long long key = key_small_first(mag_bits(W[ii]), ii);
+            if (pass > 0 && (key >> (shift + 8)) != prefixA) continue;
+            atomicAdd(&h[0][copy][(unsigned int)(key >> shift) & 255u], 1u);
+        } else if (PAIR && !doneB) {
+            const unsigned long long key = key_large_first(mag_bits(grad[ii]), ii);
+            if (pass > 0 && (key >> (shift + 8)) != prefixB) continue;
+            atomicAdd(&h[1][copy][(unsigned int)(key >> shift) & 255u], 1u);
+        }
     }
     __syncthreads();
-    if (h[threadIdx.x]) atomicAdd(&s->hist[threadIdx.x], h[threadIdx.x]);
+    unsigned int a = 0, b = 0;
+#pragma unroll
+    for (int c = 0; c < kCopies; ++c) { a += h[0][c][t]; b += h[1][c][t]; }
+    if (a) atomicAdd(&s->hist[selA][pass][t], a);
+    if (PAIR && b) atomicAdd(&s->hist[1][pass][t], b);
 }
 
-// One workgroup of 256 threads: picks the byte of this pass from the histogram and clears it.
-__global__ __launch_bounds__(256) void k_layer_pick(int which, int pass, UpdateScratch* __restrict__ s) {
-    __shared__ unsigned long long suffix[257];
+// After the eighth pass: the last byte, and the finished selection.  One wavefront.
+template <bool PAIR>
+__global__ __launch_bounds__(64) void k_layer_finish(UpdateScratch* __restrict__ s) {
     const int t = threadIdx.x;
-    SelState& st = s->sel[which];
-    if (st.done) { s->hist[t] = 0; return; }
-    const unsigned int mine = s->hist[t];
-    s->hist[t] = 0;
-    suffix[t] = mine;
-    if (t == 0) suffix[256] = 0;
-    __syncthreads();
-    // suffix[d] = number of keys whose byte is >= d (Hillis-Steele from the top)
-    for (int off = 1; off < 256; off <<= 1) {
-        const unsigned long long add = (t + off < 256) ? suffix[t + off] : 0ull;
-        __syncthreads();
-        suffix[t] += add;
-        __syncthreads();
-    }
-    const unsigned long long want = st.k_rem;
-    if (pass == 0 && t == 0) st.total = suffix[0];
-    if (pass == 0 && (want == 0 || suffix[0] < want)) {
-        __syncthreads();
-        if (t == 0) {
-            st.threshold = (want == 0) ? ~0ull : 0ull;   // nothing / everything
-            st.done = 1;
-        }
-        return;
-    }
-    // the byte d with suffix[d] >= want > suffix[d + 1]
-    if (suffix[t] >= want && suffix[t + 1] < want) {
-        st.threshold = (pass == 0 ? 0ull : (st.threshold << 8)) | (unsigned long long)t;
-        st.k_rem = want - suffix[t + 1];
-        if (pass == 7) st.done = 1;
+    const int selA = PAIR ? 0 : 2;
+    const SelState a = advance(s->slot[selA][1], s->hist[selA][7], 8, t);
+    if (t == 0) s->fin[selA] = a;
+    if (PAIR) {
+        const SelState b = advance(s->slot[1][1], s->hist[1][7], 8, t);
+        if (t == 0) s->fin[1] = b;
     }
 }
 
@@ -127,7 +194,7 @@ __global__ __launch_bounds__(256) void k_row_salient(const float* __restrict__ W
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= d_out) return;
-    const unsigned long long t_small = s->sel[0].threshold, t_grad = s->sel[1].threshold;
+    const unsigned long long t_small = s->fin[0].prefix, t_grad = s->fin[1].prefix;
     int h = 0, sal = 0;
     for (int c = lane; c < d_in; c += 64) {
         const unsigned int i = (unsigned int)r * d_in + c;
@@ -168,56 +235,59 @@ __global__ __launch_bounds__(1024) void k_decide(const int* __restrict__ held, c
         s->k_new = k_new;
         s->n_remaining = n_rem;
         s->n_ablated_now = n_abl;
+        if (n_abl == 0) {   // same candidates, same count: the walk of step 3 already has the answer
+            s->slot[2][0] = s->fin[0];
+            s->slot[2][1] = s->fin[0];
+        }
     }
 }
 
-// Radix walk inside one workgroup: the threshold of the `want` largest keys among the row's candidates.
-// key_of(c, key) returns whether column c is a candidate.  want >= 1 and at most the number of candidates.
-template <typename KeyOf>
-__device__ unsigned long long row_select(int d_in, unsigned long long want, KeyOf key_of, unsigned int* h, unsigned long long* suffix,
-                                         unsigned long long* shared2) {
+// Radix walk inside one workgroup of 256 threads: the threshold of the `want` largest keys among the row's candidates.
+// key_of(j, key): whether the thread's j-th column is a candidate, and its key.  1 <= want <= number of candidates.
+template <int CPT, typename KeyOf>
+__device__ unsigned long long row_select(unsigned long long want, KeyOf key_of, unsigned int* h, unsigned long long* shared3) {
     const int t = threadIdx.x;
     unsigned long long prefix = 0;
+#pragma unroll 1
     for (int pass = 0; pass < 8; ++pass) {
         const int shift = 56 - 8 * pass;
         h[t] = 0;
         __syncthreads();
-        for (int c = t; c < d_in; c += 256) {
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
             unsigned long long key;
-            if (!key_of(c, key)) continue;
+            if (!key_of(j, key)) continue;
             if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
             atomicAdd(&h[(unsigned int)(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        suffix[t] = h[t];
-        if (t == 0) suffix[256] = 0;
-        __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {
-            const unsigned long long add = (t + off < 256) ? suffix[t + off] : 0ull;
-            __syncthreads();
-            suffix[t] += add;
-            __syncthreads();
-        }
-        if (suffix[t] >= want && suffix[t + 1] < want) {
-            shared2[0] = (prefix << 8) | (unsigned long long)t;
-            shared2[1] = want - suffix[t + 1];
+        if (t < 64) {
+            unsigned long long digit, above, in_bin, total;
+            pick_byte(h, want, t, digit, above, in_bin, total);
+            if (t == 0) {
+                shared3[0] = (prefix << 8) | digit;
+                shared3[1] = want - above;
+                shared3[2] = (want - above == in_bin) ? 1ull : 0ull;   // every key of this byte is wanted: the walk is over
+            }
         }
         __syncthreads();
-        prefix = shared2[0];
-        want = shared2[1];
-        __syncthreads();
+        prefix = shared3[0];
+        want = shared3[1];
+        if (shared3[2] != 0 && pass < 7) return prefix << (56 - 8 * pass);   // the smallest key with this prefix
     }
     return prefix;
 }
 
-// Steps 6 (applied) and 7.  One workgroup of 256 threads per row.
+// Steps 6 (applied) and 7.  One workgroup of 256 threads per row; a thread holds CPT columns of the row (d_in <= 256 CPT):
+// whether the weight survives step 6, and the one key the column can be ranked by (its weight magnitude if it survives,
+// else its gradient magnitude), so the walks read registers only.
+template <int CPT>
 __global__ __launch_bounds__(256) void k_row_update(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, int d_in, const int* __restrict__ remains,
                                                     const UpdateScratch* __restrict__ s, uint8_t* __restrict__ mask_out,
                                                     float* __restrict__ W_out) {
     __shared__ unsigned int h[256];
-    __shared__ unsigned long long suffix[257];
-    __shared__ unsigned long long shared2[2];
+    __shared__ unsigned long long shared3[3];
     __shared__ int n_kept;
     const int r = blockIdx.x, t = threadIdx.x;
     const unsigned int row0 = (unsigned int)r * d_in;
@@ -225,38 +295,54 @@ __global__ __launch_bounds__(256) void k_row_update(const float* __restrict__ W,
         for (int c = t; c < d_in; c += 256) { mask_out[row0 + c] = 0; W_out[row0 + c] = 0.0f; }
         return;
     }
-    const unsigned long long t_prune = s->sel[2].threshold;
+    const unsigned long long t_prune = s->fin[2].prefix;
     const long long k_new = s->k_new;
-    auto survives = [&](int c) { return mask[row0 + c] != 0 && key_small_first(mag_bits(W[row0 + c]), row0 + c) < t_prune; };
+    unsigned long long key[CPT];
+    unsigned int survives = 0, valid = 0;   // bit j: the thread's j-th column
     if (t == 0) n_kept = 0;
     __syncthreads();
-    int mine = 0;
-    for (int c = t; c < d_in; c += 256) mine += survives(c) ? 1 : 0;
-    if (mine) atomicAdd(&n_kept, mine);
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+        const int c = t + 256 * j;
+        key[j] = 0;
+        if (c < d_in) {
+            valid |= 1u << j;
+            const unsigned int i = row0 + c;
+            const float w = W[i];
+            if (mask[i] != 0 && key_small_first(mag_bits(w), i) < t_prune) {
+                survives |= 1u << j;
+                key[j] = key_large_first(mag_bits(w), (unsigned int)c);
+            } else {
+                key[j] = key_large_first(mag_bits(grad[i]), (unsigned int)c);
+            }
+        }
+    }
+    if (survives) atomicAdd(&n_kept, __popc(survives));
     __syncthreads();
     const long long kept = n_kept;
     unsigned long long t_keep = 0;       // keep a surviving weight iff its key >= t_keep
     unsigned long long t_grow = ~0ull;   // grow a free position iff its key >= t_grow
     if (kept > k_new) {
         if (k_new == 0) t_keep = ~0ull;
-        else t_keep = row_select(d_in, (unsigned long long)k_new, [&](int c, unsigned long long& key) {
-            if (!survives(c)) return false;
-            key = key_large_first(mag_bits(W[row0 + c]), (unsigned int)c);
-            return true;
-        }, h, suffix, shared2);
+        else t_keep = row_select<CPT>((unsigned long long)k_new, [&](int j, unsigned long long& k_out) {
+            k_out = key[j];
+            return ((survives >> j) & 1u) != 0;
+        }, h, shared3);
     } else if (kept < k_new) {
-        t_grow = row_select(d_in, (unsigned long long)(k_new - kept), [&](int c, unsigned long long& key) {
-            if (survives(c)) return false;
-            key = key_large_first(mag_bits(grad[row0 + c]), (unsigned int)c);
-            return true;
-        }, h, suffix, shared2);
+        t_grow = row_select<CPT>((unsigned long long)(k_new - kept), [&](int j, unsigned long long& k_out) {
+            k_out = key[j];
+            return ((valid >> j) & 1u) != 0 && ((survives >> j) & 1u) == 0;
+        }, h, shared3);
     }
-    for (int c = t; c < d_in; c += 256) {
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+        const int c = t + 256 * j;
+        if (c >= d_in) continue;
         uint8_t m = 0;
         float w = 0.0f;
-        if (survives(c)) {
-            if (key_large_first(mag_bits(W[row0 + c]), (unsigned int)c) >= t_keep) { m = 1; w = W[row0 + c]; }
-        } else if (key_large_first(mag_bits(grad[row0 + c]), (unsigned int)c) >= t_grow) {
+        if ((survives >> j) & 1u) {
+            if (key[j] >= t_keep) { m = 1; w = W[row0 + c]; }
+        } else if (key[j] >= t_grow) {
             m = 1;   // grown: the weight starts at zero
         }
         mask_out[row0 + c] = m;
@@ -269,20 +355,19 @@ __global__ void k_update_report(const UpdateScratch* __restrict__ s, long long K
         report[0] = s->k_new;
         report[1] = s->n_remaining;
         report[2] = s->n_ablated_now;
-        const unsigned long long cand = s->sel[2].total;
+        const unsigned long long cand = s->fin[2].total;
         report[3] = (long long)((unsigned long long)K_upd < cand ? (unsigned long long)K_upd : cand);
     }
 }
 
-template <int MODE>
+template <bool PAIR>
 static void layer_select(const float* W, const uint8_t* mask, const float* grad, const int* remains, unsigned int N, int d_in,
                          UpdateScratch* s, hipStream_t st) {
     unsigned int blocks = (N + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    for (int pass = 0; pass < 8; ++pass) {
-        hipLaunchKernelGGL(k_layer_hist<MODE>, dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s);
-        hipLaunchKernelGGL(k_layer_pick, dim3(1), dim3(256), 0, st, MODE, pass, s);
-    }
+    for (int pass = 0; pass < 8; ++pass)
+        hipLaunchKernelGGL(k_layer_hist<PAIR>, dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s);
+    hipLaunchKernelGGL(k_layer_finish<PAIR>, dim3(1), dim3(64), 0, st, s);
 }
 
 }  // namespace srigl
@@ -303,6 +388,7 @@ srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float*
     if (d_out < 0 || d_in < 0 || k < 0 || k > d_in || K_upd < 0 || gamma_percent < 0 || budget < 0 || report_dev == nullptr)
         return SRIGL_ERR_INVALID_ARG;
     if ((long long)d_out * d_in >= (1ll << 32)) return SRIGL_ERR_UNSUPPORTED;   // positions are ranked as 32-bit numbers
+    if (d_in > 8192) return SRIGL_ERR_UNSUPPORTED;                              // a row is held in the registers of one workgroup
     if (workspace == nullptr) return SRIGL_ERR_INVALID_ARG;
     if (workspace_bytes < srigl_mask_update_workspace_bytes(d_out)) return SRIGL_ERR_CAPACITY;
     const unsigned int N = (unsigned int)((long long)d_out * d_in);
@@ -313,14 +399,15 @@ srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float*
     int* remains = salient + d_out;
     hipLaunchKernelGGL(k_update_init, dim3(1), dim3(256), 0, st, s, (long long)K_upd);
     if (N > 0) {
-        layer_select<0>(W, mask, grad, remains, N, d_in, s, st);
-        layer_select<1>(W, mask, grad, remains, N, d_in, s, st);
+        layer_select<true>(W, mask, grad, remains, N, d_in, s, st);
         hipLaunchKernelGGL(k_row_salient, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, s, held, salient);
     }
     hipLaunchKernelGGL(k_decide, dim3(1), dim3(1024), 0, st, held, salient, d_out, d_in, k, gamma_percent, (long long)budget, remains, s);
     if (N > 0) {
-        layer_select<2>(W, mask, grad, remains, N, d_in, s, st);
-        hipLaunchKernelGGL(k_row_update, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
+        layer_select<false>(W, mask, grad, remains, N, d_in, s, st);
+        if (d_in <= 1024) hipLaunchKernelGGL(k_row_update<4>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
+        else if (d_in <= 4096) hipLaunchKernelGGL(k_row_update<16>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
+        else hipLaunchKernelGGL(k_row_update<32>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
     }
     hipLaunchKernelGGL(k_update_report, dim3(1), dim3(64), 0, st, s, (long long)K_upd, reinterpret_cast<long long*>(report_dev));
     return hip_ok(hipGetLastError());
