@@ -57,3 +57,34 @@ def test_random_layer_every_algorithm(d_in, d_out, K, B, abl, dtype, seed):
             assert np.array_equal(yh[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (B, 1)).view(np.uint32))
         ran += 1
     assert ran >= 3
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_structured_random_shapes(seed):
+    """Seeded random shapes through the structured-only path: densify bit-exact, forward within tolerance, every tile choice
+    the library makes on its own plus one forced tile per case."""
+    import oracle
+    from paper_2305_02299_amd import binding as B_
+    from gpu_util import TOL_BF16, TOL_F32, dev, gate, host, oracle_condensed
+    rng = np.random.default_rng(9000 + seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    unit = 8 if dtype == "bf16" else 4
+    d_in = int(rng.integers(1, 200)) * unit
+    d_out = int(rng.integers(1, 900))
+    K = int(rng.integers(1, min(d_in, 64) + 1))
+    B = int(rng.choice([1, 3, 17, 64, 100, 257, 600]))
+    abl = float(rng.choice([0.0, 0.0, 0.3, 0.8]))
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=seed)
+    W_c, idx, active = oracle_condensed(L)
+    n = W_c.shape[0]
+    x = L.x_bf16 if dtype == "bf16" else L.x
+    Wd_ref = oracle.densify(W_c, idx, d_in)
+    Wd = torch.empty((max(n, 1), d_in), dtype=torch.int16 if dtype == "bf16" else torch.float32, device="cuda")
+    B_.srigl_densify(dev(W_c), dev(idx), n, K, d_in, Wd)
+    assert host(Wd)[:n].tobytes() == Wd_ref.tobytes()
+    y_ref, S = oracle.fwd(x, W_c, idx, active, L.bias, d_out, want_scale=True)
+    for tile in (None, int(rng.integers(1, 7))):
+        y = torch.full((B, d_out), float("nan"), device="cuda")
+        B_.srigl_structured_linear_fwd(dev(x), B, d_in, Wd, dev(active), n, dev(L.bias), d_out, y, tile=tile)
+        torch.cuda.synchronize()
+        gate(host(y), y_ref, S, TOL_BF16 if dtype == "bf16" else TOL_F32)

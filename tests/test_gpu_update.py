@@ -124,3 +124,34 @@ def test_argument_errors(B_):
     ws = torch.empty(B_.srigl_mask_update_workspace_bytes(4), dtype=torch.uint8, device="cuda")
     with pytest.raises(B_.SriglError):
         B_.srigl_mask_update(z, zm, z, 4, 4, 5, 1, 30, 8, zm.clone(), z.clone(), ws, rep)     # k > d_in
+
+
+def test_degenerate_updates(B_):
+    rng = np.random.default_rng(77)
+    # every neuron ablated on entry: nothing to do, everything stays zero
+    z = np.zeros((6, 10), np.float32)
+    zm = np.zeros((6, 10), np.uint8)
+    check(B_, z, zm, rng.normal(size=z.shape).astype(np.float32), 3, 4, 30, budget=0)
+    # a dense layer (k = d_in): there are no pruned positions; K_upd weights are pruned and the same number regrown
+    L = si.make_layer(12, 7, 12, 1, seed=1)
+    check(B_, L.W.astype(np.float32), L.mask, rng.normal(size=L.W.shape).astype(np.float32), 12, 9, 0)
+    # more weights asked for than are kept: everything is pruned, rows regrow by gradient alone
+    L = si.make_layer(20, 9, 3, 1, ablate_frac=0.3, seed=2)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    check(B_, Wm, L.mask, rng.normal(size=L.W.shape).astype(np.float32), 3, 10 ** 6, 0)
+    # a threshold that ablates every neuron
+    check(B_, Wm, L.mask, np.zeros_like(Wm), 3, int(L.mask.sum()), 100)
+    # all magnitudes equal: positions alone decide
+    ones = np.where(L.mask != 0, 1.0, 0.0).astype(np.float32)
+    check(B_, ones, L.mask, np.ones_like(ones), 3, 7, 30)
+    # one row, one column
+    check(B_, np.array([[0.5]], np.float32), np.array([[1]], np.uint8), np.array([[1.0]], np.float32), 1, 1, 0)
+
+
+def test_wide_rows_use_the_larger_row_kernels(B_):
+    """d_in above 1024 and above 4096 (16 and 32 columns per thread in step 7)."""
+    rng = np.random.default_rng(5)
+    for d_in, d_out, k in ((1500, 40, 60), (5000, 12, 100)):
+        L = si.make_layer(d_in, d_out, k, 1, ablate_frac=0.25, seed=d_in)
+        Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+        check(B_, Wm, L.mask, rng.normal(size=L.W.shape).astype(np.float32), k, int(0.3 * L.mask.sum()), 30)
