@@ -23,6 +23,8 @@ namespace srigl {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
+constexpr int kXcds = 8;                  // dies with an L2 of their own; workgroup id % 8 selects the die
+constexpr int kPanelN = 8;                // tile columns per panel of the tile order
 constexpr int kSlabBytes = 128;   // bytes of K per row and slab = LDS row pitch
 
 __device__ uint4 g_zero16 = {0u, 0u, 0u, 0u};   // source of the pieces past the end of a row
@@ -156,7 +158,25 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront index as a scalar
     const int wm = wv / WGN, wn = wv % WGN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // Workgroup -> tile.  Consecutive workgroup ids go round-robin to the 8 XCDs, each with its own L2.  The tiles are put
+    // in an order in which neighbours share operands (panels of kPanelN tile columns, row by row inside a panel), that order
+    // is cut into 8 equal runs, and XCD c walks run c: the 32 tiles it holds at a time cover about 4 x 8 tiles, which
+    // share their rows of x and of Wd through that L2, and every XCD gets the same number of tiles.
+    int tile_m, tile_n;
+    {
+        const int tiles_m = (B + BM - 1) / BM, tiles_n = (n_active + BN - 1) / BN;
+        const int total = tiles_m * tiles_n;
+        const int per_xcd = (total + kXcds - 1) / kXcds;
+        const int id = blockIdx.x;
+        const int q = (id % kXcds) * per_xcd + id / kXcds;
+        if (id / kXcds >= per_xcd || q >= total) return;   // padding of the last run
+        const int full_panel = tiles_m * kPanelN;
+        const int panel = q / full_panel, r = q - panel * full_panel;
+        const int width = min(kPanelN, tiles_n - panel * kPanelN);
+        tile_m = r / width;
+        tile_n = panel * kPanelN + r - tile_m * width;
+    }
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // loader: pass p of wavefront wv fills rows RPL * (p * NWAVES + wv) .. + RPL - 1; lane -> (row + lane / PIECES, slot lane % PIECES).
     // The first XP passes are rows of x, the others rows of Wd; a lane keeps one 32-bit byte offset per pass from the tile's
@@ -333,8 +353,10 @@ static srigl_status launch_gemm_r(const void* x, int B, int d_in, const void* Wd
             return SRIGL_ERR_HIP;
         raised = true;
     }
-    const dim3 grid((unsigned)((n_active + BN - 1) / BN), (unsigned)((B + BM - 1) / BM));
-    if (grid.y > 65535u) return SRIGL_ERR_UNSUPPORTED;
+    const long long tiles_m = (B + BM - 1) / BM, tiles_n = (n_active + BN - 1) / BN;
+    const long long n_wg = ((tiles_m * tiles_n + kXcds - 1) / kXcds) * kXcds;   // 8 equal runs of tiles, one per XCD
+    if (n_wg > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)n_wg);
     // a lane addresses its rows with 32-bit byte offsets from the tile's first row
     if ((long long)(BM > BN ? BM : BN) * d_in * (long long)sizeof(T) >= (1ll << 31)) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), lds, st, (const T*)x, B, d_in, (const T*)Wd, active, n_active, bias, d_out, y);
@@ -356,8 +378,8 @@ struct TileModel { srigl_gemm_tile tile; int bm, bn; float ns_per_k_bf16, ns_per
 static const TileModel kTileModels[] = {
     {SRIGL_TILE_256x256_H, 256, 256, 28.0f, 233.0f, 233.0f},
     {SRIGL_TILE_256x128, 256, 128, 18.0f, 125.0f, 125.0f},
-    {SRIGL_TILE_128x128, 128, 128, 13.0f, 70.0f, 70.0f},
-    {SRIGL_TILE_64x64, 64, 64, 4.2f, 19.0f, 22.0f},
+    {SRIGL_TILE_128x128, 128, 128, 12.0f, 70.0f, 70.0f},
+    {SRIGL_TILE_64x64, 64, 64, 3.8f, 19.0f, 22.0f},
 };
 
 // ns_per_k_out: nanoseconds per element of d_in for the whole product with the chosen tile
