@@ -170,7 +170,7 @@ def sweep(args):
         del sets, layer
 
 
-def structured(args):
+def structured(args, emit=True):
     """--structured: the structured-only form of the 4096->16384 bf16 layer at B=2048 (dense rows of the stored neurons on the
     matrix cores), one JSON line; the condensed form of the same layer and the library's dense matmul as context."""
     import torch
@@ -219,17 +219,20 @@ def structured(args):
     t_d = time_graph(lambda i: torch.matmul(xt, Wt.t()), steps, warmup)
     flops = 2.0 * L.B * layer.n_active * L.d_in
     tf = flops / (t_s * 1e-3) / 1e12
-    print(json.dumps({
+    out = ({
         "metric": "structured_linear_fwd_us_per_call", "value": t_s * 1e3, "unit": "us/call", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": t_s, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "c5 structured-only: %d->%d bf16, n_active=%d dense rows, B=%d" % (L.d_in, L.d_out, layer.n_active, L.B)},
         "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None},
         "context": {"condensed_same_layer_us": t_c * 1e3, "library_dense_bf16_matmul_us": t_d * 1e3,
-                    "library_dense_tflops": 2.0 * L.B * L.d_out * L.d_in / (t_d * 1e-3) / 1e12}}), flush=True)
+                    "library_dense_tflops": 2.0 * L.B * L.d_out * L.d_in / (t_d * 1e-3) / 1e12}})
+    if emit:
+        print(json.dumps(out), flush=True)
+    return out
 
 
-def mlp(args):
+def mlp(args, emit=True, points=None):
     """--mlp: the MLP block of a ViT-B (768 -> 3072, GELU, 3072 -> 768; 90 % sparse) with a share of the hidden neurons ablated:
     both layers at full hidden width against the pair after the width-reduction fold.  One JSON line per point."""
     import torch
@@ -264,8 +267,11 @@ def mlp(args):
             best = t if best is None else min(best, t)
         return best
 
+    rows = []
     for abl in (0.0, 0.3, 0.7):
         for B in (1, 16, 256, 1024):
+            if points is not None and (abl, B) not in points:
+                continue
             L1 = si.make_layer(768, 3072, 77, B, ablate_frac=abl, seed=1)
             L2 = si.make_layer(3072, 768, 308, B, ablate_frac=0.0, seed=2)
             l1 = condense_layer(dev(L1.W), dev(L1.mask), L1.K, dev(L1.bias))
@@ -284,11 +290,14 @@ def mlp(args):
             steps = 200 if B <= 256 else 50
             t_u = time_graph(unfolded, steps, 5) * 1e3
             t_f = time_graph(lambda i: pair.forward(x, y, h_c), steps, 5) * 1e3
-            print(json.dumps({"block": "768->3072 GELU 3072->768, K=77/308", "hidden_ablated": abl, "hidden_stored": l1.n_active, "B": B,
-                              "us_full_width": round(t_u, 2), "us_folded": round(t_f, 2)}), flush=True)
+            rows.append({"block": "768->3072 GELU 3072->768, K=77/308", "hidden_ablated": abl, "hidden_stored": l1.n_active, "B": B,
+                         "us_full_width": round(t_u, 2), "us_folded": round(t_f, 2)})
+            if emit:
+                print(json.dumps(rows[-1]), flush=True)
+    return rows
 
 
-def update(args):
+def update(args, emit=True, names=("c2", "c5")):
     """--update: one SRigL connectivity update (Sec. 3.1 steps 1-7) of the 768 -> 3072 layer (90 % sparse, 30 % of the kept
     weights pruned and regrown, gamma_sal 30 %) and of the 4096 -> 16384 layer; one JSON line per layer, the CPU oracle timed
     on the small one."""
@@ -299,7 +308,8 @@ def update(args):
 
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
-    for name in ("c2", "c5"):
+    rows = []
+    for name in names:
         L = si.config(name)
         Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
         g = np.random.default_rng(5).normal(size=L.W.shape).astype(np.float32)
@@ -331,13 +341,16 @@ def update(args):
             t0 = time.perf_counter()
             oracle.mask_update(Wm, L.mask, g, L.K, K_upd, 30)
             cpu = {"value": (time.perf_counter() - t0) * 1e6, "unit": "us/call", "cores": 1, "kind": "oracle", "sample": "one call"}
-        print(json.dumps({"metric": "mask_update_us_per_call", "value": us, "unit": "us/call", "n_gpus": 1, "steps": steps,
+        rows.append({"metric": "mask_update_us_per_call", "value": us, "unit": "us/call", "n_gpus": 1, "steps": steps,
                           "dtype": "f32", "data": "synthetic",
                           "config": {"workload": "%s: %d x %d, k=%d, K_upd=%d, gamma_sal=30%%" % (name, L.d_out, L.d_in, L.K, K_upd)},
                           "report": dict(zip(("k_new", "n_remaining", "n_ablated_now", "n_pruned"), rep.cpu().tolist())),
                           "roofline": {"bound": "hbm", "achieved": nbytes / us / 1e3, "peak": 8000.0, "unit": "GB/s",
                                        "frac": nbytes / us / 1e3 / 8000.0, "traffic": None, "algorithmic_bytes": nbytes},
-                          "cpu_baseline": cpu}), flush=True)
+                          "cpu_baseline": cpu})
+        if emit:
+            print(json.dumps(rows[-1]), flush=True)
+    return rows
 
 
 def main():
@@ -351,6 +364,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")
     ap.add_argument("--no-large", action="store_true", help="--sweep without the 4096->16384 bf16 layer")
     ap.add_argument("--no-csr", action="store_true", help="--sweep without the library CSR product (context column)")
+    ap.add_argument("--no-next", action="store_true", help="default run without the structured-only / MLP / update figures")
     ap.add_argument("--update", action="store_true", help="time one SRigL connectivity update of a layer")
     ap.add_argument("--mlp", action="store_true", help="time the two-layer MLP block with and without the width-reduction fold")
     ap.add_argument("--structured", action="store_true", help="time the structured-only form of the 4096->16384 bf16 layer")
@@ -545,6 +559,14 @@ def main():
         "context": {"empty_kernel_us": t_empty * 1e3, "copy_kernel_gbs": copy_gbs, "torch_dense_linear_us": t_dense * 1e3,
                     "paper_speedups": "3.4x/2.5x vs dense/CSR (Xeon W-2145, B=1), 1.7x/13.0x (Titan V, B=256): other hardware"},
     }
+    if not args.no_next:
+        # the rows built beyond the hot path, each measured by its own mode of this script (same code, fewer points)
+        args.no_cpu = True
+        out["next_rows"] = {
+            "structured_only": structured(args, emit=False),
+            "mlp_block_width_reduction": mlp(args, emit=False, points={(0.7, 1), (0.7, 256), (0.3, 256)}),
+            "mask_update": update(args, emit=False, names=("c2",)),
+        }
     print(json.dumps(out), flush=True)
 
 
