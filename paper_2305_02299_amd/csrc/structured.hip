@@ -379,7 +379,7 @@ static const TileModel kTileModels[] = {
     {SRIGL_TILE_256x256_H, 256, 256, 28.0f, 233.0f, 233.0f},
     {SRIGL_TILE_256x128, 256, 128, 18.0f, 125.0f, 125.0f},
     {SRIGL_TILE_128x128, 128, 128, 12.0f, 70.0f, 70.0f},
-    {SRIGL_TILE_64x64, 64, 64, 3.8f, 19.0f, 22.0f},
+    {SRIGL_TILE_64x64, 64, 64, 3.8f, 19.0f, 26.0f},
 };
 
 // ns_per_k_out: nanoseconds per element of d_in for the whole product with the chosen tile
