@@ -136,3 +136,31 @@ def test_layer_object_runs_either_representation(dtype):
         y = layer.forward(dev(xsrc), representation=rep)
         torch.cuda.synchronize()
         gate(host(y), y_ref, S, tol)
+
+
+def test_large_layer_sampled_rows_in_the_timed_configuration(B_):
+    """4096 -> 16384, bf16 storage, B = 2048, 20 % of the neurons ablated: the configuration `bench.py --structured` times,
+    through the library's own tile choice.  The GPU runs the whole batch; the oracle recomputes a sample of batch rows
+    (first, last, tile edges, random) from the condensed arrays; ablated columns must equal the bias bit for bit."""
+    L = si.config("c5")
+    W_c, idx, active = oracle_condensed(L)
+    n = W_c.shape[0]
+    Wd = torch.empty((n, L.d_in), dtype=torch.int16, device="cuda")
+    B_.srigl_densify(dev(W_c), dev(idx), n, L.K, L.d_in, Wd)
+    y = torch.full((L.B, L.d_out), float("nan"), device="cuda")
+    B_.srigl_structured_linear_fwd(dev(L.x_bf16), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y)
+    torch.cuda.synchronize()
+    y = host(y)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, 257, 1023, 1024, 2046, 2047],
+                                     np.random.default_rng(6).integers(0, 2048, size=5)]))
+    y_ref, S = oracle.fwd(L.x_bf16[rows], W_c, idx, active, L.bias, L.d_out, want_scale=True)
+    gate(y[rows], y_ref, S, TOL_BF16)
+    ablated = np.setdiff1d(np.arange(L.d_out), active)
+    assert np.array_equal(y[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (L.B, 1)).view(np.uint32))
+    assert np.isfinite(y).all()
+    # densify at full size: a sample of rows against the definition
+    got = host(Wd)
+    for s in (0, 1, n // 2, n - 1):
+        ref = np.zeros(L.d_in, np.uint16)
+        ref[idx[s]] = W_c[s]
+        assert np.array_equal(got[s], ref)
