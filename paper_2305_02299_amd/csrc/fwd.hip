@@ -146,7 +146,8 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
             prev = (s > 0) ? active[s - 1] : -1;
             // the L lanes of the group share the gap in front of this column
             for (int c = max(prev + 1, 0) + q; c < col; c += L) {
-                const float bv = apply_act(bias_at(bias, c), act);
+                const float braw = bias_at(bias, c);
+                const float bv = act == SRIGL_ACT_NONE ? braw : apply_act(braw, act);
 #pragma unroll
                 for (int r = 0; r < RB; ++r)
                     if (b0 + r < B) y[(size_t)(b0 + r) * d_out + c] = bv;
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
             const float bv = bias_at(bias, col);
 #pragma unroll
             for (int r = 0; r < RB; ++r)
-                if (b0 + r < B) y[(size_t)(b0 + r) * d_out + col] = apply_act(acc[r] + bv, act);
+                if (b0 + r < B) y[(size_t)(b0 + r) * d_out + col] = act == SRIGL_ACT_NONE ? acc[r] + bv : apply_act(acc[r] + bv, act);
         }
     }
 }

@@ -1,6 +1,8 @@
 // ROWLANE forward kernel and its launchers, included once per element type (one translation unit each,
 // so that the instantiations compile in parallel).
 #pragma once
+#include <type_traits>
+
 #include "srigl_internal.h"
 
 namespace srigl {
@@ -393,18 +395,29 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     }
     SRIGL_STAMP(13)
     const int n_rows = min(BT, B - b0);
-    for (int row = wv_id; row < n_rows; row += nw) {
-        float* yr = y + (size_t)(b0 + row) * d_out;
+    // the loop exists twice so that the plain forward pass carries no test of the activation code per store
+    auto store_rows = [&](auto with_act) {
+        for (int row = wv_id; row < n_rows; row += nw) {
+            float* yr = y + (size_t)(b0 + row) * d_out;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int i = lane + h * kWave;
-            const int col = colv[h];
-            if (col < 0) continue;
-            if (active)
-                for (int cc = prevv[h]; cc < col; ++cc) yr[cc] = apply_act(rl_bias_at(bias, cc), act);
-            if (sg0 + i < n_active && col < d_out) yr[col] = apply_act(out[row * OS + i] + biasv[h], act);
+            for (int h = 0; h < 2; ++h) {
+                const int i = lane + h * kWave;
+                const int col = colv[h];
+                if (col < 0) continue;
+                if (active)
+                    for (int cc = prevv[h]; cc < col; ++cc) {
+                        const float bv = rl_bias_at(bias, cc);
+                        yr[cc] = decltype(with_act)::value ? apply_act(bv, act) : bv;
+                    }
+                if (sg0 + i < n_active && col < d_out) {
+                    const float v = out[row * OS + i] + biasv[h];
+                    yr[col] = decltype(with_act)::value ? apply_act(v, act) : v;
+                }
+            }
         }
-    }
+    };
+    if (act == SRIGL_ACT_NONE) store_rows(std::false_type{});
+    else store_rows(std::true_type{});
     SRIGL_STAMP(14)
 }
 
