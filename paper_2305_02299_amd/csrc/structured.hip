@@ -451,7 +451,7 @@ srigl_status srigl_densify(const void* W_c, srigl_dtype w_dtype, const int32_t* 
 // Estimates in microseconds, calibrated on MI355X measurements of both kernels (fp32 and bf16 storage, batches 1..2048,
 // 768x3072 / 3072x768 / 4096x16384 layers, 80-99 % sparsity):
 //   condensed  ~ 6.3 + B (d_in + d_out) / 2.2e5     (launch, staging the activations, writing the result)
-//                    + B n_active K / 1.0e7          (gathered multiply-adds)
+//                    + B n_active K / 1.0e7          (gathered multiply-adds; 1.7e7 for batches >= 512 with K >= 32)
 //                batches <= 16 run the lane-per-term kernel: 2.6 + B n_active K / 1.4e6, never above the line above
 //   structured ~ 3.5 + d_in x (rounds of tiles x nanoseconds per element of d_in of the chosen tile) / 1000
 //                  + 4 B d_out / 4.5e6              (writing the result at HBM speed)
@@ -459,7 +459,8 @@ srigl_representation srigl_choose_representation(int32_t B, int32_t d_in, int32_
                                                  srigl_dtype dtype, float* est_condensed_us, float* est_structured_us) {
     const double b = B > 0 ? B : 0, n = n_active > 0 ? n_active : 0, k = K > 0 ? K : 0;
     const double terms = b * n * k;
-    double cond = 6.3 + b * ((double)d_in + d_out) / 2.2e5 + terms / 1.0e7;
+    const bool two_rows = B >= 512 && K >= 32;   // the batched kernel's 128-row tiles (about 1.7x the term rate)
+    double cond = 6.3 + b * ((double)d_in + d_out) / 2.2e5 + terms / (two_rows ? 1.7e7 : 1.0e7);
     if (B <= 16) cond = fmin(cond, 2.6 + terms / 1.4e6);
     double ns_per_k = 0.0;
     const bool f32 = dtype == SRIGL_F32;
