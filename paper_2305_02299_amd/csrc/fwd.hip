@@ -252,8 +252,9 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
         p.H = 1;
         if (p.fast && p.R == 1 && a.B <= 512) p.H = a.d_in <= 1024 ? 1 : (a.d_in <= 2048 ? 2 : 4);
         // batches below one 64-row tile: a tile no taller than the batch keeps every lane on real rows
+        // (and up to one 64-row tile two 32-row tiles run faster: twice the workgroups, half the terms per lane)
         if (p.fast && p.R == 1) {
-            const int hb = a.B <= 16 ? 4 : (a.B <= 32 ? 2 : 1);
+            const int hb = a.B <= 16 ? 4 : (a.B <= 64 ? 2 : 1);
             if (hb > p.H) p.H = hb;
         }
     }
@@ -327,7 +328,9 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     two.rows_per_lane = 2;
     two.term_slices = 1;
     const RowlanePlan p2 = plan_rowlane_with(a, &two);
-    if (p2.ok && (long long)p2.n_groups * p2.n_btiles >= 256) return p2;
+    // ... with at least three stored rows per wavefront: a launch that only reaches 256 workgroups by giving every wavefront a
+    // single row has too little arithmetic per staged tile
+    if (p2.ok && p2.NPW >= 3 && a.B >= 256 && (long long)p2.n_groups * p2.n_btiles >= 256) return p2;
     return one;
 }
 
