@@ -24,7 +24,10 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kXcds = 8;                  // dies with an L2 of their own; workgroup id % 8 selects the die
-constexpr int kPanelN = 8;                // tile columns per panel of the tile order
+#ifndef SRIGL_PANEL_N
+#define SRIGL_PANEL_N 8
+#endif
+constexpr int kPanelN = SRIGL_PANEL_N;    // tile columns per panel of the tile order
 constexpr int kSlabBytes = 128;   // bytes of K per row and slab = LDS row pitch
 
 __device__ uint4 g_zero16 = {0u, 0u, 0u, 0u};   // source of the pieces past the end of a row
@@ -280,7 +283,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                    if (m < B) y[(size_t)m * d_out + col] = acc[i][j][e] + bv;
+                    if (m < B) __builtin_nontemporal_store(acc[i][j][e] + bv, &y[(size_t)m * d_out + col]);   // y is not read again here
                 }
             }
         }
@@ -333,7 +336,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
                 float* yr = y + (size_t)(m0 + ph * PROWS + r) * d_out + cc;
                 for (int k = lane; k < wc; k += 64) {
                     const int tix = table[k];
-                    yr[k] = (tix >= 0 ? tile[r * PITCH + tix] : 0.0f) + tbias[k];
+                    __builtin_nontemporal_store((tix >= 0 ? tile[r * PITCH + tix] : 0.0f) + tbias[k], &yr[k]);
                 }
             }
         }
