@@ -210,7 +210,9 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     if (L == 0) { L = 4; while (L < 64 && L * kKlaneTerms < a.K) L <<= 1; }
     if (L < 1 || L > 64 || (L & (L - 1)) != 0) return SRIGL_ERR_UNSUPPORTED;
     int RB = t && t->rows_per_block ? t->rows_per_block : 0;
-    if (RB == 0) RB = a.B > 4 ? 2 : 1;   // measured: one row per workgroup up to batch 4, two beat four and eight above
+    // measured: one row per workgroup up to batch 4 and for wide inputs (staging two rows of x then costs more
+    // than the second pass over W_c/idx saves); two rows beat four and eight elsewhere
+    if (RB == 0) RB = (a.B > 4 && a.d_in <= 1024) ? 2 : 1;
     while (RB > 1 && (size_t)RB * a.d_in * sizeof(float) > kLdsMax / 2) RB >>= 1;
     if (RB != 1 && RB != 2 && RB != 4 && RB != 8) return SRIGL_ERR_UNSUPPORTED;
     const int log2L = ilog2_floor(L);
@@ -254,7 +256,10 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
         // batches below one 64-row tile: a tile no taller than the batch keeps every lane on real rows
         // (and up to one 64-row tile two 32-row tiles run faster: twice the workgroups, half the terms per lane)
         if (p.fast && p.R == 1) {
-            const int hb = a.B <= 16 ? 4 : (a.B <= 64 ? 2 : 1);
+            int hb = a.B <= 16 ? 4 : (a.B <= 64 ? 2 : 1);
+            // inputs wider than 1024: 16-row tiles stay ahead up to a batch of 32, and up to 64 when the layer
+            // has too few stored rows to fill the GPU otherwise (measured on 1536- and 2048-wide inputs)
+            if (a.d_in > 1024 && (a.B <= 32 || (a.B <= 64 && a.n_active <= 1024))) hb = 4;
             if (hb > p.H) p.H = hb;
         }
     }
@@ -383,8 +388,25 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
         case SRIGL_FWD_AUTO: break;
         default: return SRIGL_ERR_INVALID_ARG;
     }
-    if (B > 16 && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
+    // Small batches: the lanes-along-K kernel costs a fixed part plus a part per term slot (K rounded up to the
+    // lanes it spreads a row over; dearer with one batch row per workgroup, the wide-input setting); the batched
+    // kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in).
+    // Fits of timings of 512- to 4096-wide layers at 80-90 % sparsity, the cold read of W_c / idx left out of both;
+    // above 64 rows the batched kernel always wins.
+    bool batched = B > 16;
+    if (B > 4 && B <= 64 && d_in % 16 == 0) {
+        int L = 4;
+        while (L < 64 && L * kKlaneTerms < K) L <<= 1;
+        const int req = L * kKlaneTerms;   // term slots one request of a lane group covers
+        const double slots = (double)B * n_active * ((K + req - 1) / req * req);
+        const double small_us = 3.2 + 0.0005 * d_in + (d_in <= 1024 ? 0.44e-6 : 0.6e-6) * slots;
+        // (few stored rows: too few workgroups share the staging)
+        const double batched_us = 4.6 + 0.0014 * d_in + (n_active <= 1024 ? 0.5 : 0.0);
+        batched = batched_us < small_us;
+    }
+    if (batched && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
     srigl_status s = launch_fwd_klane(a, nullptr, st);
+    if (s == SRIGL_ERR_UNSUPPORTED && B > 16 && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
     if (s == SRIGL_ERR_UNSUPPORTED) s = launch_fwd_generic(a, st);
     return s;
 }
