@@ -297,6 +297,82 @@ def mlp(args, emit=True, points=None):
     return rows
 
 
+def narrow(args, emit=True, points=None):
+    """--narrow: the forward pass with 16-bit column indices against the same layer with 32-bit indices (App. E: the
+    index array is what the condensed form stores beside the weights).  Cold = operands rotated through copies that
+    exceed the Infinity Cache; warm = one operand set.  One JSON line per point."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2305_02299_amd import condense_layer
+
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
+
+    def time_graph(fn, steps, warmup):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for i in range(warmup):
+                fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) / steps
+            best = t if best is None else min(best, t)
+        return best
+
+    rows = []
+    shapes = [(768, 3072, 77, "f32"), (768, 3072, 77, "bf16"), (3072, 768, 308, "f32"), (4096, 16384, 205, "bf16")]
+    for (d_in, d_out, K, dtype) in shapes:
+        for B in (1, 16, 256):
+            if points is not None and (d_in, dtype, B) not in points:
+                continue
+            L = si.make_layer(d_in, d_out, K, B, dtype=dtype, seed=0)
+            bf = dtype == "bf16"
+            wide = condense_layer(dev(L.W_bf16.view(np.int16) if bf else L.W), dev(L.mask), K, dev(L.bias))
+            x = dev(L.x_bf16.view(np.int16) if bf else L.x)
+            elem = 2 if bf else 4
+            n_terms = wide.n_active * K
+            nbytes32 = algorithmic_bytes(wide.n_active, K, B, d_in, d_out, elem)
+            nbytes16 = nbytes32 - 2 * n_terms
+            n_sets = min(max(2, -(-2 * CACHE_BYTES // nbytes16)), 400)
+            res = {}
+            for name, layer in (("idx32", wide), ("idx16", wide.narrow())):
+                sets = []
+                for _ in range(n_sets):
+                    c = type(layer)(layer.d_in, layer.d_out, layer.K, layer.n_active, layer.W_c.clone(), layer.idx.clone(),
+                                    None if layer.active is None else layer.active.clone(), layer.bias.clone(), layer.seg.clone())
+                    sets.append((c, x.clone(), torch.empty((B, d_out), device="cuda")))
+
+                def f_cold(i):
+                    c, xi, yi = sets[i % n_sets]
+                    c.forward(xi, yi)
+
+                def f_warm(i):
+                    c, xi, yi = sets[0]
+                    c.forward(xi, yi)
+
+                res[name] = (time_graph(f_cold, n_sets, 2) * 1e3, time_graph(f_warm, 200, 5) * 1e3)
+                del sets
+            rows.append({"layer": "%d->%d K=%d %s" % (d_in, d_out, K, dtype), "B": B, "bytes_idx32": nbytes32, "bytes_idx16": nbytes16,
+                         "us_cold_idx32": round(res["idx32"][0], 2), "us_cold_idx16": round(res["idx16"][0], 2),
+                         "us_warm_idx32": round(res["idx32"][1], 2), "us_warm_idx16": round(res["idx16"][1], 2)})
+            if emit:
+                print(json.dumps(rows[-1]), flush=True)
+    return rows
+
+
 def update(args, emit=True, names=("c2", "c5")):
     """--update: one SRigL connectivity update (Sec. 3.1 steps 1-7) of the 768 -> 3072 layer (90 % sparse, 30 % of the kept
     weights pruned and regrown, gamma_sal 30 %) and of the 4096 -> 16384 layer; one JSON line per layer, the CPU oracle timed
@@ -367,6 +443,7 @@ def main():
     ap.add_argument("--no-next", action="store_true", help="default run without the structured-only / MLP / update figures")
     ap.add_argument("--update", action="store_true", help="time one SRigL connectivity update of a layer")
     ap.add_argument("--mlp", action="store_true", help="time the two-layer MLP block with and without the width-reduction fold")
+    ap.add_argument("--narrow", action="store_true", help="time the forward pass with 16-bit against 32-bit column indices")
     ap.add_argument("--structured", action="store_true", help="time the structured-only form of the 4096->16384 bf16 layer")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -381,6 +458,8 @@ def main():
         return mlp(args)
     if args.update:
         return update(args)
+    if args.narrow:
+        return narrow(args)
 
     import torch
 
@@ -566,6 +645,7 @@ def main():
             "structured_only": structured(args, emit=False),
             "mlp_block_width_reduction": mlp(args, emit=False, points={(0.7, 1), (0.7, 256), (0.3, 256)}),
             "mask_update": update(args, emit=False, names=("c2",)),
+            "narrow_indices": narrow(args, emit=False, points={(768, "f32", 1), (768, "f32", 256), (768, "bf16", 1)}),
         }
     print(json.dumps(out), flush=True)
 

@@ -174,6 +174,27 @@ srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, sr
                                        int32_t n_active1, int32_t d_hidden, const float* bias1, srigl_activation act,
                                        int32_t* idx_out, void* W_out, float* bias_out, void* stream);
 
+/* ---- narrow column indices ------------------------------------------------------------------------------
+ * App. E: the condensed layer stores one column index per kept weight; that index array is all the representation
+ * adds to the weights themselves.  A layer with d_in <= 65536 can hold it in 16 bits (half the index bytes; with
+ * bf16 weights the whole representation is then 4 bytes per weight instead of 6).
+ *
+ * srigl_narrow_idx: idx16[i] = idx[i] for i in [0, n); device pointers, distinct arrays.  Entries must lie in
+ * [0, d_in) as srigl_condense writes them (others are clamped into that range).  SRIGL_ERR_UNSUPPORTED if
+ * d_in > 65536, SRIGL_ERR_INVALID_ARG on negative sizes or NULL pointers with n > 0.
+ *
+ * srigl_condensed_linear_fwd_idx16: srigl_condensed_linear_fwd_act with idx16[n_active][K] in place of idx; every
+ * other argument, the result and the errors are the same (same kernels, same order of additions: the output is
+ * bit-identical to the 32-bit call on the same layer).  d_in > 65536 is SRIGL_ERR_UNSUPPORTED. */
+srigl_status srigl_narrow_idx(const int32_t* idx, int64_t n, int32_t d_in, uint16_t* idx16, void* stream);
+
+srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
+                                              const void* W_c, srigl_dtype w_dtype, const uint16_t* idx16,
+                                              const int32_t* active, int32_t n_active, int32_t K,
+                                              const float* bias, int32_t d_out, float* y,
+                                              const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
+                                              const srigl_fwd_tuning* tuning, void* stream);
+
 /* ---- one SRigL connectivity update of a layer ------------------------------------------------------------
  * Sec. 3.1, steps 1-7 (with App. G's minimum of one salient weight).  W, grad: fp32 [d_out][d_in]; mask: bytes, every
  * row holds 0 (ablated) or k kept weights; K_upd: the number of weights pruned and grown in this update (step 2, chosen

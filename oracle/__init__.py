@@ -209,3 +209,18 @@ def fwd_allcores(x, W_c, idx, active, bias, d_out):
     lib = _load()
     lib.oracle_fwd_f32_allcores(_p(x), B, d_in, _p(W_c), _p(idx), _p(active), n_active, K, _p(bias), int(d_out), _p(y))
     return y, int(lib.oracle_num_threads())
+
+
+def narrow_idx(idx: np.ndarray, d_in: int) -> np.ndarray:
+    """App. E's index array held in 16 bits: the same column numbers, one 16-bit word each.  Defined only when every
+    column number fits (d_in <= 65536) and every entry names a column of the layer."""
+    idx = np.asarray(idx)
+    if d_in > 65536:
+        raise ValueError("column numbers of a layer this wide do not fit 16 bits")
+    if idx.size and (idx.min() < 0 or idx.max() >= d_in):
+        raise ValueError("an entry names no column of the layer")
+    out = np.empty(idx.shape, dtype=np.uint16)
+    flat_in, flat_out = idx.reshape(-1), out.reshape(-1)
+    for i in range(flat_in.size):
+        flat_out[i] = int(flat_in[i])
+    return out

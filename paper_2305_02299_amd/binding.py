@@ -31,6 +31,7 @@ EXPORTS = (
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
     "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
+    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16",
 )
 
 
@@ -83,6 +84,11 @@ def _load() -> ctypes.CDLL:
     lib.srigl_mask_update_workspace_bytes.argtypes = [i32]
     lib.srigl_mask_update.restype = ctypes.c_int
     lib.srigl_mask_update.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_int64, i32, ctypes.c_int64, vp, vp, vp, sz, vp, vp]
+    lib.srigl_narrow_idx.restype = ctypes.c_int
+    lib.srigl_narrow_idx.argtypes = [vp, ctypes.c_int64, i32, vp, vp]
+    lib.srigl_condensed_linear_fwd_idx16.restype = ctypes.c_int
+    lib.srigl_condensed_linear_fwd_idx16.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32,
+                                                     vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -160,17 +166,19 @@ def srigl_condense(W, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, wor
 
 def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, d_out, y, seg=None, algo=None, tuning=None, act=None):
     """algo None: the library's own entry point; otherwise the forced-algorithm entry point; act: the entry point with an
-    activation in the epilogue (ACT_* codes)."""
-    if act is not None:
+    activation in the epilogue (ACT_* codes); idx in a 16-bit container: the narrow-index entry point."""
+    if idx.dtype in (torch.int16, torch.uint16) or act is not None:
         tn = None
         if tuning is not None:
             tn = FwdTuning()
             for k, v in tuning.items():
                 setattr(tn, k, int(v))
-        st = lib.srigl_condensed_linear_fwd_act(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
-                                                _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
-                                                int(act), int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
-        _check(st, "srigl_condensed_linear_fwd_act")
+        narrow = idx.dtype != torch.int32   # a 16-bit container carries unsigned 16-bit column indices
+        fn = lib.srigl_condensed_linear_fwd_idx16 if narrow else lib.srigl_condensed_linear_fwd_act
+        st = fn(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
+                _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
+                int(act or ACT_NONE), int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
+        _check(st, "srigl_condensed_linear_fwd_idx16" if narrow else "srigl_condensed_linear_fwd_act")
         return
     if algo is None and tuning is None:
         st = lib.srigl_condensed_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
@@ -186,6 +194,12 @@ def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, 
                                                  _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
                                                  int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
     _check(st, "srigl_condensed_linear_fwd")
+
+
+def srigl_narrow_idx(idx, d_in, idx16):
+    """idx int32 (any shape, contiguous) -> idx16, a 16-bit container of the same number of elements."""
+    assert idx.dtype == torch.int32 and idx16.dtype in (torch.int16, torch.uint16) and idx16.numel() == idx.numel()
+    _check(lib.srigl_narrow_idx(_ptr(idx), int(idx.numel()), int(d_in), _ptr(idx16), _stream()), "srigl_narrow_idx")
 
 
 def srigl_densify(W_c, idx, n_active, K, d_in, Wd):

@@ -24,9 +24,9 @@ __device__ __forceinline__ float bias_at(const float* __restrict__ bias, int col
 // GENERIC: one thread per (batch row, stored row).  Reads x from global memory, clamps indices.
 // Correct for any index order; the fallback when nothing better applies.
 // ------------------------------------------------------------------------------------------------
-template <typename XT>
+template <typename XT, typename IT>
 __global__ __launch_bounds__(256) void k_fwd_generic(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
-                                                     const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
+                                                     const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                      int n_active, int K, const float* __restrict__ bias, int d_out,
                                                      float* __restrict__ y, int act) {
     const int n_slots = active ? n_active + 1 : n_active;   // +1: virtual row that fills the tail gap
@@ -45,10 +45,10 @@ __global__ __launch_bounds__(256) void k_fwd_generic(const XT* __restrict__ x, i
         if (s >= n_active || col < 0 || col >= d_out) continue;
         const XT* xr = x + (size_t)b * d_in;
         const XT* w = W_c + (size_t)s * K;
-        const int32_t* ix = idx + (size_t)s * K;
+        const IT* ix = idx + (size_t)s * K;
         float acc = 0.0f;
         for (int k = 0; k < K; ++k) {
-            const int j = min(max(ix[k], 0), d_in - 1);
+            const int j = min(max((int)ix[k], 0), d_in - 1);
             acc = fmaf(to_f32<XT>(w[k]), to_f32<XT>(xr[j]), acc);
         }
         yr[col] = apply_act(acc + bias_at(bias, col), act);
@@ -72,20 +72,20 @@ constexpr int kKlaneTerms = 4;   // terms a lane keeps in flight per request
 
 // Lane q of a group asks for terms kb + q, kb + q + L, ... (kKlaneTerms of them) of stored row s.  The loads are
 // unconditional (term index clamped into the row) and nothing here consumes them, so they all stay in flight.
-template <typename XT>
-__device__ __forceinline__ void klane_request(const XT* __restrict__ W_c, const int32_t* __restrict__ idx, size_t row, int kb, int q,
+template <typename XT, typename IT>
+__device__ __forceinline__ void klane_request(const XT* __restrict__ W_c, const IT* __restrict__ idx, size_t row, int kb, int q,
                                               int L, int K, XT (&wr)[kKlaneTerms], int (&ir)[kKlaneTerms]) {
 #pragma unroll
     for (int t = 0; t < kKlaneTerms; ++t) {
         const size_t e = row + (size_t)min(kb + q + t * L, K - 1);
         wr[t] = W_c[e];
-        ir[t] = idx[e];
+        ir[t] = (int)idx[e];
     }
 }
 
-template <int RB, typename XT>
+template <int RB, typename XT, typename IT>
 __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
-                                                   const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
+                                                   const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                    int n_active, int K, const float* __restrict__ bias, int d_out,
                                                    float* __restrict__ y, int log2L, int rows_per_wg, int act) {
     extern __shared__ float xs[];   // [RB][d_in]
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
     int s = s_begin + grp;
     XT wr[kKlaneTerms];
     int ir[kKlaneTerms];
-    klane_request<XT>(W_c, idx, (size_t)min(s, n_active - 1) * K, 0, q, L, K, wr, ir);
+    klane_request<XT, IT>(W_c, idx, (size_t)min(s, n_active - 1) * K, 0, q, L, K, wr, ir);
 
     for (int r = 0; r < RB; ++r) {
         const int b = min(b0 + r, B - 1);             // rows past B re-read the last row; they are never stored
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
                 int ic[kKlaneTerms];
 #pragma unroll
                 for (int t = 0; t < kKlaneTerms; ++t) { wc[t] = wr[t]; ic[t] = ir[t]; }
-                if (kb + kKlaneTerms * L < K) klane_request<XT>(W_c, idx, row, kb + kKlaneTerms * L, q, L, K, wr, ir);
+                if (kb + kKlaneTerms * L < K) klane_request<XT, IT>(W_c, idx, row, kb + kKlaneTerms * L, q, L, K, wr, ir);
 #pragma unroll
                 for (int t = 0; t < kKlaneTerms; ++t) {
                     if (kb + q + t * L < K) {
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
         }
         // next row's first terms: in flight during the reduction and the stores
         const int sn = s + groups;
-        if (sn < min(s_end, n_active)) klane_request<XT>(W_c, idx, (size_t)sn * K, 0, q, L, K, wr, ir);
+        if (sn < min(s_end, n_active)) klane_request<XT, IT>(W_c, idx, (size_t)sn * K, 0, q, L, K, wr, ir);
         for (int off = L >> 1; off > 0; off >>= 1) {
 #pragma unroll
             for (int r = 0; r < RB; ++r) acc[r] += __shfl_xor(acc[r], off, kWave);
@@ -163,6 +163,30 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
 }
 
 // ------------------------------------------------------------------------------------------------
+// 16-bit copy of the index array (App. E: one index per kept weight).  Eight entries per thread when both arrays
+// are 16-byte aligned (two 16-byte loads, one 16-byte store), the tail and unaligned arrays one entry per thread.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t narrow_one(int v, int hi) { return (uint32_t)min(max(v, 0), hi); }
+
+__global__ __launch_bounds__(256) void k_narrow_idx8(const int4* __restrict__ idx, long long n8, int hi, uint4* __restrict__ out) {
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long long)gridDim.x * blockDim.x) {
+        const int4 a = idx[2 * i], b = idx[2 * i + 1];
+        uint4 o;
+        o.x = narrow_one(a.x, hi) | (narrow_one(a.y, hi) << 16);
+        o.y = narrow_one(a.z, hi) | (narrow_one(a.w, hi) << 16);
+        o.z = narrow_one(b.x, hi) | (narrow_one(b.y, hi) << 16);
+        o.w = narrow_one(b.z, hi) | (narrow_one(b.w, hi) << 16);
+        out[i] = o;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_narrow_idx1(const int32_t* __restrict__ idx, long long begin, long long n, int hi,
+                                                     uint16_t* __restrict__ out) {
+    for (long long i = begin + (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+        out[i] = (uint16_t)narrow_one(idx[i], hi);
+}
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 static int ilog2_floor(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
@@ -173,21 +197,21 @@ srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st) {
     if (total == 0) return SRIGL_OK;
     long long blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    if (a.x_bf16)
-        hipLaunchKernelGGL(k_fwd_generic<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, st, (const uint16_t*)a.x, a.B, a.d_in,
-                           (const uint16_t*)a.W_c, a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.act);
-    else
-        hipLaunchKernelGGL(k_fwd_generic<float>, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)a.x, a.B, a.d_in,
-                           (const float*)a.W_c, a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.act);
+#define SRIGL_GENERIC(XT, IT)                                                                                              \
+    hipLaunchKernelGGL((k_fwd_generic<XT, IT>), dim3((unsigned)blocks), dim3(256), 0, st, (const XT*)a.x, a.B, a.d_in,      \
+                       (const XT*)a.W_c, (const IT*)a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.act)
+    if (a.x_bf16) { if (a.idx_u16) SRIGL_GENERIC(uint16_t, uint16_t); else SRIGL_GENERIC(uint16_t, int32_t); }
+    else { if (a.idx_u16) SRIGL_GENERIC(float, uint16_t); else SRIGL_GENERIC(float, int32_t); }
+#undef SRIGL_GENERIC
     return hip_ok(hipGetLastError());
 }
 
-template <int RB, typename XT>
+template <int RB, typename XT, typename IT>
 static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg, hipStream_t st) {
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
     const size_t lds = (size_t)RB * a.d_in * sizeof(float);
     if (lds > kLdsMax) return SRIGL_ERR_UNSUPPORTED;
-    auto kern = k_fwd_klane<RB, XT>;
+    auto kern = k_fwd_klane<RB, XT, IT>;
     static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
     if (lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
@@ -197,8 +221,8 @@ static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg,
     const unsigned gx = (unsigned)((n_slots + rows_per_wg - 1) / rows_per_wg);
     const unsigned gy = (unsigned)((a.B + RB - 1) / RB);
     if (gy > 65535u) return SRIGL_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c, a.idx, a.active,
-                       a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act);
+    hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c, (const IT*)a.idx,
+                       a.active, a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act);
     return hip_ok(hipGetLastError());
 }
 
@@ -221,7 +245,10 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     int rows_per_wg = groups;
     while ((long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB) > 256 * 8) rows_per_wg += groups;
 #define SRIGL_KLANE(RBV)                                                                               \
-    return a.x_bf16 ? launch_klane_t<RBV, uint16_t>(a, log2L, rows_per_wg, st) : launch_klane_t<RBV, float>(a, log2L, rows_per_wg, st)
+    return a.x_bf16 ? (a.idx_u16 ? launch_klane_t<RBV, uint16_t, uint16_t>(a, log2L, rows_per_wg, st)                  \
+                                 : launch_klane_t<RBV, uint16_t, int32_t>(a, log2L, rows_per_wg, st))                  \
+                    : (a.idx_u16 ? launch_klane_t<RBV, float, uint16_t>(a, log2L, rows_per_wg, st)                     \
+                                 : launch_klane_t<RBV, float, int32_t>(a, log2L, rows_per_wg, st))
     switch (RB) {
         case 1: SRIGL_KLANE(1);
         case 2: SRIGL_KLANE(2);
@@ -346,6 +373,7 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
     if (a.B == 0 || n_slots == 0) return SRIGL_OK;
     const RowlanePlan p = plan_rowlane(a, t);
     if (!p.ok) return SRIGL_ERR_UNSUPPORTED;
+    if (a.idx_u16) return a.x_bf16 ? launch_rowlane_bf16_i16(a, p, st) : launch_rowlane_f32_i16(a, p, st);
     return a.x_bf16 ? launch_rowlane_bf16(a, p, st) : launch_rowlane_f32(a, p, st);
 }
 
@@ -357,7 +385,7 @@ using namespace srigl;
 extern "C" {
 
 static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* W_c, srigl_dtype w_dtype,
-                             const int32_t* idx, const int32_t* active, int32_t n_active, int32_t K, const float* bias,
+                             const void* idx, bool idx_u16, const int32_t* active, int32_t n_active, int32_t K, const float* bias,
                              int32_t d_out, float* y, const uint16_t* seg, srigl_fwd_algo algo, const srigl_fwd_tuning* tuning,
                              srigl_activation act, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -365,13 +393,14 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     if (B < 0 || d_in < 0 || n_active < 0 || K < 0 || d_out < 0 || K > d_in || n_active > d_out) return SRIGL_ERR_INVALID_ARG;
     if ((x_dtype != SRIGL_F32 && x_dtype != SRIGL_BF16) || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
     if (x_dtype != w_dtype) return SRIGL_ERR_UNSUPPORTED;
+    if (idx_u16 && d_in > 65536) return SRIGL_ERR_UNSUPPORTED;
     if (active == nullptr && n_active != d_out && n_active != 0) return SRIGL_ERR_INVALID_ARG;
     if (B == 0 || d_out == 0) return SRIGL_OK;
     if (y == nullptr) return SRIGL_ERR_INVALID_ARG;
     if (n_active > 0 && K > 0 && (x == nullptr || W_c == nullptr || idx == nullptr)) return SRIGL_ERR_INVALID_ARG;
 
     FwdArgs a;
-    a.x = x; a.x_bf16 = (x_dtype == SRIGL_BF16); a.B = B; a.d_in = d_in; a.W_c = W_c; a.idx = idx; a.active = active;
+    a.x = x; a.x_bf16 = (x_dtype == SRIGL_BF16); a.B = B; a.d_in = d_in; a.W_c = W_c; a.idx = idx; a.idx_u16 = idx_u16 ? 1 : 0; a.active = active;
     a.n_active = n_active; a.K = K; a.bias = bias; a.d_out = d_out; a.y = y; a.seg = seg;
     a.seg_stride = srigl_seg_stride(d_in);
     a.act = (int32_t)act;
@@ -417,7 +446,7 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
                                              const float* bias, int32_t d_out, float* y,
                                              const uint16_t* seg, srigl_fwd_algo algo,
                                              const srigl_fwd_tuning* tuning, void* stream) {
-    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, active, n_active, K, bias, d_out, y, seg, algo, tuning, SRIGL_ACT_NONE, stream);
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, false, active, n_active, K, bias, d_out, y, seg, algo, tuning, SRIGL_ACT_NONE, stream);
 }
 
 srigl_status srigl_condensed_linear_fwd_act(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
@@ -426,7 +455,7 @@ srigl_status srigl_condensed_linear_fwd_act(const void* x, srigl_dtype x_dtype, 
                                             const float* bias, int32_t d_out, float* y,
                                             const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
                                             const srigl_fwd_tuning* tuning, void* stream) {
-    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, active, n_active, K, bias, d_out, y, seg, algo, tuning, act, stream);
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, false, active, n_active, K, bias, d_out, y, seg, algo, tuning, act, stream);
 }
 
 srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
@@ -436,6 +465,39 @@ srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int3
                                         const uint16_t* seg, void* stream) {
     return srigl_condensed_linear_fwd_algo(x, x_dtype, B, d_in, W_c, w_dtype, idx, active, n_active, K, bias, d_out, y, seg,
                                            SRIGL_FWD_AUTO, nullptr, stream);
+}
+
+srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
+                                              const void* W_c, srigl_dtype w_dtype, const uint16_t* idx16,
+                                              const int32_t* active, int32_t n_active, int32_t K,
+                                              const float* bias, int32_t d_out, float* y,
+                                              const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
+                                              const srigl_fwd_tuning* tuning, void* stream) {
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx16, true, active, n_active, K, bias, d_out, y, seg, algo, tuning, act, stream);
+}
+
+srigl_status srigl_narrow_idx(const int32_t* idx, int64_t n, int32_t d_in, uint16_t* idx16, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n < 0 || d_in < 0) return SRIGL_ERR_INVALID_ARG;
+    if (d_in > 65536) return SRIGL_ERR_UNSUPPORTED;
+    if (n == 0) return SRIGL_OK;
+    if (idx == nullptr || idx16 == nullptr || d_in == 0) return SRIGL_ERR_INVALID_ARG;
+    const int hi = d_in - 1;
+    long long done = 0;
+    if (reinterpret_cast<uintptr_t>(idx) % 16 == 0 && reinterpret_cast<uintptr_t>(idx16) % 16 == 0 && n >= 8) {
+        const long long n8 = n / 8;
+        long long blocks = (n8 + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(k_narrow_idx8, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<const int4*>(idx), n8, hi,
+                           reinterpret_cast<uint4*>(idx16));
+        done = n8 * 8;
+    }
+    if (done < n) {
+        long long blocks = (n - done + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(k_narrow_idx1, dim3((unsigned)blocks), dim3(256), 0, st, idx, done, (long long)n, hi, idx16);
+    }
+    return hip_ok(hipGetLastError());
 }
 
 }  // extern "C"

@@ -160,13 +160,13 @@ __device__ __forceinline__ void pipe_groups(float (&acc)[R], const float (&wv)[N
 // array).  The loads are unconditional (the term index is clamped into the arrays) and nothing here consumes their
 // result, so that they stay in flight; finish_terms() turns the raw words into a weight and an LDS byte offset
 // when the block is about to be used.
-template <typename XT>
-__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const int32_t* __restrict__ idx, int t0, int tofs, int t_last,
+template <typename XT, typename IT>
+__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const IT* __restrict__ idx, int t0, int tofs, int t_last,
                                               XT& w_raw, int& i_raw) {
     // 32-bit unsigned byte offsets from the (wave-uniform) array bases: one address instruction per load
     const unsigned t = (unsigned)min(t0 + tofs, t_last);
     w_raw = *reinterpret_cast<const XT*>(reinterpret_cast<const char*>(W_c) + t * (unsigned)sizeof(XT));
-    i_raw = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(idx) + t * 4u);
+    i_raw = (int)*reinterpret_cast<const IT*>(reinterpret_cast<const char*>(idx) + t * (unsigned)sizeof(IT));
 }
 // n_valid (wave-uniform, may be <= 0) of the block's terms are real; the others become (weight 0, all-zero column).
 template <typename XT>
@@ -177,9 +177,9 @@ __device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, i
     ov = real ? i_raw * off_mul + off_add : zero_off;
 }
 
-template <int R, int H, int NPW, int KPRE, typename XT, bool FAST>
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT>
 __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
-                                                      const int32_t* __restrict__ idx, const int32_t* __restrict__ active,
+                                                      const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
                                                       int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act) {
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     {                                                                                                           \
         const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
         _Pragma("unroll") for (int p = 0; p < KPRE; ++p)                                                        \
-            request_terms<XT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, tofs, t_last, rw[i][p], ri[i][p]);      \
+            request_terms<XT, IT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, tofs, t_last, rw[i][p], ri[i][p]);      \
     }
 
     float acc[NPW][R];
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
-        for (int p = 0; p < KPRE; ++p) request_terms<XT>(W_c, idx, (s0 + i) * K + p * TB, tofs, t_last, rw[i][p], ri[i][p]);
+        for (int p = 0; p < KPRE; ++p) request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, tofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
     SRIGL_STAGE_LOAD(0)
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
@@ -329,12 +329,12 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                     const int row = (s0 + i) * K + k0n[i];
                     XT wr;
                     int ir;
-                    request_terms<XT>(W_c, idx, row + KPRE * TB, tofs, t_last, wr, ir);
+                    request_terms<XT, IT>(W_c, idx, row + KPRE * TB, tofs, t_last, wr, ir);
                     for (int kb = KPRE * TB; kb < n_terms; kb += TB) {
                         float wc[1];
                         int oc[1];
                         finish_terms<XT>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
-                        if (kb + TB < n_terms) request_terms<XT>(W_c, idx, row + kb + TB, tofs, t_last, wr, ir);
+                        if (kb + TB < n_terms) request_terms<XT, IT>(W_c, idx, row + kb + TB, tofs, t_last, wr, ir);
                         group_reads<R, 0>(xa, oc[0], xb);
                         pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, (n_terms - kb + H - 1) / H, xa, xc);
                     }
@@ -421,9 +421,9 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     SRIGL_STAMP(14)
 }
 
-template <int R, int H, int NPW, int KPRE, typename XT, bool FAST>
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT>
 static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
-    auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST>;
+    auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST, IT>;
     static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
     if (p.lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
@@ -433,40 +433,40 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
     const long long blocks = 8LL * ((p.n_groups + 7) / 8) * p.n_btiles;
     if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
-                       a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
+                       (const IT*)a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
                        p.n_groups, p.out_off, a.act);
     return hip_ok(hipGetLastError());
 }
 
-template <int R, int H, int NPW, typename XT>
+template <int R, int H, int NPW, typename XT, typename IT>
 static srigl_status launch_rowlane_k(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     constexpr int KPRE = rowlane_kpre(NPW);
-    if (p.fast) return launch_rowlane_f<R, H, NPW, KPRE, XT, true>(a, p, st);
-    if constexpr (R == 1 && H == 1) return launch_rowlane_f<R, H, NPW, KPRE, XT, false>(a, p, st);
+    if (p.fast) return launch_rowlane_f<R, H, NPW, KPRE, XT, true, IT>(a, p, st);
+    if constexpr (R == 1 && H == 1) return launch_rowlane_f<R, H, NPW, KPRE, XT, false, IT>(a, p, st);
     return SRIGL_ERR_UNSUPPORTED;   // the planner keeps R = 1, H = 1 when the fast staging does not apply
 }
 
-template <int R, int H, typename XT>
+template <int R, int H, typename XT, typename IT>
 static srigl_status launch_rowlane_r(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     constexpr int MAXN = rowlane_max_npw(R);
     switch (p.NPW) {
-        case 1: return launch_rowlane_k<R, H, 1, XT>(a, p, st);
-        case 2: return launch_rowlane_k<R, H, 2, XT>(a, p, st);
-        case 3: return launch_rowlane_k<R, H, 3, XT>(a, p, st);
-        case 4: return launch_rowlane_k<R, H, 4, XT>(a, p, st);
-        case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, H, 6, XT>(a, p, st); else break;
+        case 1: return launch_rowlane_k<R, H, 1, XT, IT>(a, p, st);
+        case 2: return launch_rowlane_k<R, H, 2, XT, IT>(a, p, st);
+        case 3: return launch_rowlane_k<R, H, 3, XT, IT>(a, p, st);
+        case 4: return launch_rowlane_k<R, H, 4, XT, IT>(a, p, st);
+        case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, H, 6, XT, IT>(a, p, st); else break;
         default: break;
     }
     return SRIGL_ERR_UNSUPPORTED;
 }
 
-template <typename XT>
+template <typename XT, typename IT>
 static srigl_status launch_rowlane_x(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     switch (p.R * 10 + p.H) {
-        case 11: return launch_rowlane_r<1, 1, XT>(a, p, st);
-        case 12: return launch_rowlane_r<1, 2, XT>(a, p, st);
-        case 14: return launch_rowlane_r<1, 4, XT>(a, p, st);
-        case 21: return launch_rowlane_r<2, 1, XT>(a, p, st);
+        case 11: return launch_rowlane_r<1, 1, XT, IT>(a, p, st);
+        case 12: return launch_rowlane_r<1, 2, XT, IT>(a, p, st);
+        case 14: return launch_rowlane_r<1, 4, XT, IT>(a, p, st);
+        case 21: return launch_rowlane_r<2, 1, XT, IT>(a, p, st);
         default: return SRIGL_ERR_UNSUPPORTED;
     }
 }

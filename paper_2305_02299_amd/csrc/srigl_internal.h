@@ -17,7 +17,8 @@ struct FwdArgs {
     int32_t x_bf16;
     int32_t B, d_in;
     const void* W_c;
-    const int32_t* idx;
+    const void* idx;     // int32_t, or uint16_t when idx_u16
+    int32_t idx_u16;
     const int32_t* active;
     int32_t n_active, K;
     const float* bias;
@@ -45,6 +46,8 @@ constexpr int rowlane_max_npw(int R) { return R == 1 ? 6 : 4; }
 constexpr int rowlane_kpre(int npw) { return npw <= 3 ? 3 : (npw <= 4 ? 2 : 1); }
 srigl_status launch_rowlane_f32(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);
 srigl_status launch_rowlane_bf16(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);
+srigl_status launch_rowlane_f32_i16(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);
+srigl_status launch_rowlane_bf16_i16(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);
 
 // Each returns SRIGL_OK, SRIGL_ERR_UNSUPPORTED (cannot run these sizes) or SRIGL_ERR_HIP.
 srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st);

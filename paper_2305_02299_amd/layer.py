@@ -23,11 +23,21 @@ class CondensedLinear:
     bias: torch.Tensor | None
     seg: torch.Tensor | None
     Wd: torch.Tensor | None = None   # dense rows of the stored neurons (structured-only form), built on first use
+    idx_wide: torch.Tensor | None = None   # the int32 indices when idx holds the 16-bit copy
+
+    def narrow(self) -> "CondensedLinear":
+        """The same layer with 16-bit column indices (d_in <= 65536); weights, active, bias and seg are shared."""
+        if self.idx.dtype != torch.int32:
+            return self
+        idx16 = torch.empty(self.idx.shape, dtype=torch.int16, device=self.idx.device)
+        B_.srigl_narrow_idx(self.idx, self.d_in, idx16)
+        return CondensedLinear(self.d_in, self.d_out, self.K, self.n_active, self.W_c, idx16, self.active, self.bias, self.seg,
+                               self.Wd, self.idx)
 
     def dense_rows(self) -> torch.Tensor:
         if self.Wd is None:
             self.Wd = torch.empty((max(self.n_active, 1), self.d_in), dtype=self.W_c.dtype, device=self.W_c.device)
-            B_.srigl_densify(self.W_c, self.idx, self.n_active, self.K, self.d_in, self.Wd)
+            B_.srigl_densify(self.W_c, self.idx if self.idx_wide is None else self.idx_wide, self.n_active, self.K, self.d_in, self.Wd)
         return self.Wd
 
     def choose(self, batch: int) -> int:

@@ -449,3 +449,23 @@ def test_mask_update_invariants_and_lexsort_crosscheck(seed):
     same = (m != 0) & (L.mask != 0) & (w != 0)
     assert np.array_equal(w[same], Wm[same])                                   # kept weights are copied, grown ones are zero
     assert np.all(w[(m != 0) & (L.mask == 0)] == 0)
+
+
+def test_narrow_idx_is_the_same_numbers_in_two_bytes():
+    """App. E's index array in 16-bit words: read back byte by byte (low byte first) the words give the same column
+    numbers, at both ends of the range; a layer wider than 65536 columns, or an entry that names no column, has no
+    such form."""
+    rng = np.random.default_rng(5)
+    idx = rng.integers(0, 65536, (37, 11)).astype(np.int32)
+    idx[0, 0], idx[0, 1], idx[1, 0] = 0, 65535, 32768
+    out = oracle.narrow_idx(idx, 65536)
+    assert out.dtype == np.uint16 and out.shape == idx.shape
+    b = out.reshape(-1).view(np.uint8).astype(np.int64)
+    assert np.array_equal(b[0::2] + 256 * b[1::2], idx.reshape(-1))
+    with pytest.raises(ValueError):
+        oracle.narrow_idx(idx, 65537)
+    with pytest.raises(ValueError):
+        oracle.narrow_idx(np.array([3, 100], dtype=np.int32), 100)
+    with pytest.raises(ValueError):
+        oracle.narrow_idx(np.array([-1], dtype=np.int32), 100)
+    assert oracle.narrow_idx(np.empty((0, 4), np.int32), 8).shape == (0, 4)
