@@ -393,7 +393,7 @@ def update(args, emit=True, names=("c2", "c5")):
         K_upd = int(0.3 * n_kept)
         W_d, m_d, g_d = dev(Wm), dev(L.mask), dev(g)
         mask_o, W_o = torch.empty_like(m_d), torch.empty_like(W_d)
-        ws = torch.empty(B_.srigl_mask_update_workspace_bytes(L.d_out), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(B_.srigl_mask_update_workspace_bytes(L.d_out, L.d_in), dtype=torch.uint8, device="cuda")
         rep = torch.zeros(4, dtype=torch.int64, device="cuda")
 
         def call():

@@ -202,14 +202,15 @@ srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype
  * layer may hold (normally k times its neurons that hold weights).  Outputs: mask_out (every row 0 or k' ones), W_out (kept
  * weights copied, everything else zero: grown weights start at zero), report_dev[4] = {k', neurons that remain, neurons
  * ablated by this update, weights pruned in step 6}.  All buffers are device memory, caller-owned; outputs must not alias
- * inputs; workspace of srigl_mask_update_workspace_bytes(d_out) bytes.  Asynchronous on `stream`.
+ * inputs; workspace of srigl_mask_update_workspace_bytes(d_out, d_in) bytes (counters, three integers per neuron and two
+ * candidate lists of d_out * d_in / 16 eight-byte keys each, at least 4096), 256-byte aligned.  Asynchronous on `stream`.
  * Readings: a kept weight is salient if it is not among the K_upd smallest-magnitude kept weights of the layer, a pruned
  * position if its gradient is among the K_upd largest at pruned positions; a neuron is ablated if it holds weights and
  * its salient count is below max(gamma k, 1); a neuron without weights stays ablated; k' = min(d_in, budget / remaining
  * neurons); step 6 prunes among the remaining neurons' weights; step 7 keeps a neuron's unpruned weights (its k' largest
  * if it holds more) and grows free positions by decreasing gradient magnitude; equal magnitudes rank by position (lower
  * first).  d_out * d_in must be below 2^32 and d_in at most 8192, else SRIGL_ERR_UNSUPPORTED. */
-size_t srigl_mask_update_workspace_bytes(int32_t d_out);
+size_t srigl_mask_update_workspace_bytes(int32_t d_out, int32_t d_in);
 
 srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float* grad, int32_t d_out, int32_t d_in, int32_t k,
                                int64_t K_upd, int32_t gamma_percent, int64_t budget, uint8_t* mask_out, float* W_out,

@@ -81,7 +81,7 @@ def _load() -> ctypes.CDLL:
     lib.srigl_fold_ablated_inputs.restype = ctypes.c_int
     lib.srigl_fold_ablated_inputs.argtypes = [vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, i32, i32, vp, ctypes.c_int, vp, vp, vp, vp]
     lib.srigl_mask_update_workspace_bytes.restype = sz
-    lib.srigl_mask_update_workspace_bytes.argtypes = [i32]
+    lib.srigl_mask_update_workspace_bytes.argtypes = [i32, i32]
     lib.srigl_mask_update.restype = ctypes.c_int
     lib.srigl_mask_update.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_int64, i32, ctypes.c_int64, vp, vp, vp, sz, vp, vp]
     lib.srigl_narrow_idx.restype = ctypes.c_int
@@ -235,8 +235,8 @@ def srigl_fold_ablated_inputs(idx2, W_c2, bias2, active2, n2, K2, d_out2, active
     _check(st, "srigl_fold_ablated_inputs")
 
 
-def srigl_mask_update_workspace_bytes(d_out: int) -> int:
-    return int(lib.srigl_mask_update_workspace_bytes(int(d_out)))
+def srigl_mask_update_workspace_bytes(d_out: int, d_in: int) -> int:
+    return int(lib.srigl_mask_update_workspace_bytes(int(d_out), int(d_in)))
 
 
 def srigl_mask_update(W, mask, grad, d_out, d_in, k, K_upd, gamma_percent, budget, mask_out, W_out, workspace, report):

@@ -5,9 +5,12 @@
 //
 // Every ranking is a selection of the K largest of unique 64-bit keys, (magnitude bits, position): equal magnitudes are
 // ordered by position, so the selected set is unique and no sort is needed.  Layer-wide selections (steps 3 and 6) find the
-// K-th largest key by a most-significant-digit-first radix walk: passes of (histogram of one byte over the elements that
-// match the prefix found so far, then the byte that holds the K-th key), ended as soon as every key of the chosen byte is
-// wanted.  The two selections of step 3 share their passes, and every workgroup of a pass picks the previous pass's byte for
+// K-th largest key by a most-significant-digit-first radix walk: passes of (histogram of one digit over the elements that
+// match the prefix found so far, then the digit that holds the K-th key), ended as soon as every key of the chosen digit is
+// wanted.  The top bit of every key is zero, so the digits are bits 62-55, 54-47, ..., 14-7 and 6-0: two passes fix the
+// exponent and 8 mantissa bits of the threshold; the third pass also copies the keys that match those 16 bits (a fraction
+// of a percent of a layer with real-valued contents) into a candidate list, and the remaining passes read that list
+// instead of the layer (a list that would overflow is dropped and the passes stay on the layer).  The two selections of step 3 share their passes, and every workgroup of a pass picks the previous pass's byte for
 // itself from that pass's own counters (no pick launches, no device-wide fences); step 6 reuses step 3's answer when no
 // neuron was ablated.  Row-wise selections (step 7) do the same walk inside one workgroup per row, on keys held in registers.
 #include "srigl_internal.h"
@@ -33,7 +36,16 @@ struct UpdateScratch {
     SelState slot[3][2];
     SelState fin[3];
     long long k_new, n_remaining, n_ablated_now, n_pruned;
+    unsigned long long cand_count[3];   // keys in the selection's candidate list; above the capacity: the list is not valid
 };
+
+// Pass p of a walk decides `pass_bits(p)` bits of the key, found at `pass_shift(p)`; before pass p the top
+// `bits_done(p)` bits are fixed (the always-zero top bit counts as fixed from the start).
+__host__ __device__ constexpr int pass_shift(int p) { return p < 7 ? 55 - 8 * p : 0; }
+__host__ __device__ constexpr int pass_bits(int p) { return p < 7 ? 8 : 7; }
+__host__ __device__ constexpr int bits_done(int p) { return p < 8 ? 1 + 8 * p : 64; }
+constexpr int kCompactPass = 2;      // the pass that also writes the candidate lists
+constexpr int kBlockList = 512;      // candidate keys a workgroup collects in LDS before it appends them
 
 __device__ __forceinline__ unsigned int mag_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 // larger key = smaller magnitude, then lower position
@@ -54,6 +66,7 @@ __global__ __launch_bounds__(256) void k_update_init(UpdateScratch* s, long long
         s->slot[t][0] = z;
         s->slot[t][1] = z;
         s->fin[t] = z;
+        s->cand_count[t] = 0;
     }
 }
 
@@ -108,12 +121,12 @@ __device__ SelState advance(const SelState& before, const unsigned int* __restri
             return st;
         }
     }
-    st.prefix = (st.prefix << 8) | digit;
+    st.prefix = (st.prefix << pass_bits(pass - 1)) | digit;
     st.k_rem -= above;
-    // every key of the chosen byte is wanted (always so once the keys under the prefix are down to one): the walk is over,
+    // every key of the chosen digit is wanted (always so once the keys under the prefix are down to one): the walk is over,
     // the threshold is the smallest key with this prefix
     if (pass == 8 || st.k_rem == in_bin) {
-        if (pass < 8) st.prefix <<= 64 - 8 * pass;
+        if (pass < 8) st.prefix <<= 64 - bits_done(pass);
         st.done = 1;
     }
     return st;
@@ -121,16 +134,32 @@ __device__ SelState advance(const SelState& before, const unsigned int* __restri
 
 // One pass of the walk.  PAIR: selections 0 (kept weights, smallest first) and 1 (pruned positions, largest gradient first)
 // together: every element belongs to exactly one of them, so one read of the layer serves both.  Otherwise selection 2
-// (kept weights of the remaining neurons).  kCopies sub-histograms spread the LDS atomics of equal bytes.
+// (kept weights of the remaining neurons).  kCopies sub-histograms spread the LDS atomics of equal digits.
+// COMPACT (the launch of pass kCompactPass): every key that matches the prefix is also appended to the selection's candidate
+// list (collected per workgroup in LDS, one counter update per workgroup); a workgroup that meets more than kBlockList of
+// them, or a list longer than `cap`, leaves the counter above `cap`, and the later passes then keep reading the layer.
 constexpr int kCopies = 8;
-template <bool PAIR>
+template <bool PAIR, bool COMPACT>
 __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, const int* __restrict__ remains, unsigned int N,
-                                                    int d_in, int pass, UpdateScratch* __restrict__ s) {
+                                                    int d_in, int pass, UpdateScratch* __restrict__ s,
+                                                    unsigned long long* __restrict__ candA, unsigned long long* __restrict__ candB,
+                                                    unsigned long long cap) {
     __shared__ unsigned int h[2][kCopies][256];
     __shared__ SelState cur[2];
+    __shared__ unsigned long long keep[COMPACT ? 2 : 1][COMPACT ? kBlockList : 1];
+    __shared__ unsigned int keep_n[2];
+    __shared__ unsigned long long keep_base[2];
     const int t = threadIdx.x;
     const int selA = PAIR ? 0 : 2;
+    // walks that had ended before the previous pass: nothing to count (every thread reads the two flags for itself)
+    if (pass > 0 && s->slot[selA][(pass + 1) & 1].done != 0 && (!PAIR || s->slot[1][(pass + 1) & 1].done != 0)) {
+        if (blockIdx.x == 0 && t == 0) {
+            s->slot[selA][pass & 1] = s->slot[selA][(pass + 1) & 1];
+            if (PAIR) s->slot[1][pass & 1] = s->slot[1][(pass + 1) & 1];
+        }
+        return;
+    }
     if (t < 64) {
         SelState a = s->slot[selA][(pass + 1) & 1], b = s->slot[1][(pass + 1) & 1];   // the states before pass - 1
         if (pass > 0) {
@@ -147,23 +176,52 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
         if (t == 0) { cur[0] = a; cur[1] = b; }
     }
     for (int i = t; i < 2 * kCopies * 256; i += 256) (&h[0][0][0])[i] = 0;
+    if (t < 2) keep_n[t] = 0;
     __syncthreads();
     const bool doneA = cur[0].done != 0, doneB = PAIR ? cur[1].done != 0 : true;
     if (doneA && doneB) return;
-    const int shift = 56 - 8 * pass;
+    const int shift = pass_shift(pass);
+    const unsigned int dmask = (1u << pass_bits(pass)) - 1u;
+    const int pshift = 64 - bits_done(pass);   // pass > 0: a key is still in the walk iff key >> pshift == prefix
     const unsigned long long prefixA = cur[0].prefix, prefixB = cur[1].prefix;
     const int copy = t & (kCopies - 1);
-    for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < N; i += (unsigned long long)gridDim.x * 256) {
-        const unsigned int ii = (unsigned int)i;
-        if (mask[ii] != 0) {
-            if (doneA || (!PAIR && !remains[ii / (unsigned)d_in])) continue;
-            const unsigned long long key = key_small_first(mag_bits(W[ii]), ii);
-            if (pass > 0 && (key >> (shift + 8)) != prefixA) continue;
-            atomicAdd(&h[0][copy][(unsigned int)(key >> shift) & 255u], 1u);
-        } else if (PAIR && !doneB) {
-            const unsigned long long key = key_large_first(mag_bits(grad[ii]), ii);
-            if (pass > 0 && (key >> (shift + 8)) != prefixB) continue;
-            atomicAdd(&h[1][copy][(unsigned int)(key >> shift) & 255u], 1u);
+    const bool lists = !COMPACT && pass > kCompactPass && cap > 0;
+    const unsigned long long countA = lists ? s->cand_count[selA] : 0, countB = (lists && PAIR) ? s->cand_count[1] : 0;
+    const bool listA = lists && countA <= cap, listB = lists && PAIR && countB <= cap;
+    const bool scanA = !doneA && !listA, scanB = PAIR && !doneB && !listB;
+    if (scanA || scanB) {
+        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < N; i += (unsigned long long)gridDim.x * 256) {
+            const unsigned int ii = (unsigned int)i;
+            if (mask[ii] != 0) {
+                if (!scanA || (!PAIR && !remains[ii / (unsigned)d_in])) continue;
+                const unsigned long long key = key_small_first(mag_bits(W[ii]), ii);
+                if (pass > 0 && (key >> pshift) != prefixA) continue;
+                atomicAdd(&h[0][copy][(unsigned int)(key >> shift) & dmask], 1u);
+                if (COMPACT) {
+                    const unsigned int slot = atomicAdd(&keep_n[0], 1u);
+                    if (slot < (unsigned)kBlockList) keep[0][slot] = key;
+                }
+            } else if (scanB) {
+                const unsigned long long key = key_large_first(mag_bits(grad[ii]), ii);
+                if (pass > 0 && (key >> pshift) != prefixB) continue;
+                atomicAdd(&h[1][copy][(unsigned int)(key >> shift) & dmask], 1u);
+                if (COMPACT) {
+                    const unsigned int slot = atomicAdd(&keep_n[1], 1u);
+                    if (slot < (unsigned)kBlockList) keep[1][slot] = key;
+                }
+            }
+        }
+    }
+    if (!doneA && listA) {
+        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < countA; i += (unsigned long long)gridDim.x * 256) {
+            const unsigned long long key = candA[i];
+            if ((key >> pshift) == prefixA) atomicAdd(&h[0][copy][(unsigned int)(key >> shift) & dmask], 1u);
+        }
+    }
+    if (PAIR && !doneB && listB) {
+        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < countB; i += (unsigned long long)gridDim.x * 256) {
+            const unsigned long long key = candB[i];
+            if ((key >> pshift) == prefixB) atomicAdd(&h[1][copy][(unsigned int)(key >> shift) & dmask], 1u);
         }
     }
     __syncthreads();
@@ -172,9 +230,24 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
     for (int c = 0; c < kCopies; ++c) { a += h[0][c][t]; b += h[1][c][t]; }
     if (a) atomicAdd(&s->hist[selA][pass][t], a);
     if (PAIR && b) atomicAdd(&s->hist[1][pass][t], b);
+    if (COMPACT) {
+        if (t < 2) {
+            const unsigned int n = keep_n[t];
+            // more keys than the workgroup can hold: the counter goes past `cap` for good, the list is not used
+            keep_base[t] = n ? atomicAdd(&s->cand_count[t == 0 ? selA : 1], n > (unsigned)kBlockList ? cap + 1ull : (unsigned long long)n) : 0ull;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const unsigned int n = keep_n[q];
+            unsigned long long* __restrict__ dst = q == 0 ? candA : candB;
+            if (n == 0 || n > (unsigned)kBlockList || keep_base[q] + n > cap) continue;
+            for (unsigned int e = t; e < n; e += 256) dst[keep_base[q] + e] = keep[q][e];
+        }
+    }
 }
 
-// After the eighth pass: the last byte, and the finished selection.  One wavefront.
+// After the eighth pass: the last digit, and the finished selection.  One wavefront.
 template <bool PAIR>
 __global__ __launch_bounds__(64) void k_layer_finish(UpdateScratch* __restrict__ s) {
     const int t = threadIdx.x;
@@ -362,12 +435,28 @@ __global__ void k_update_report(const UpdateScratch* __restrict__ s, long long K
 
 template <bool PAIR>
 static void layer_select(const float* W, const uint8_t* mask, const float* grad, const int* remains, unsigned int N, int d_in,
-                         UpdateScratch* s, hipStream_t st) {
+                         UpdateScratch* s, unsigned long long* candA, unsigned long long* candB, unsigned long long cap, hipStream_t st) {
     unsigned int blocks = (N + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    for (int pass = 0; pass < 8; ++pass)
-        hipLaunchKernelGGL(k_layer_hist<PAIR>, dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s);
+    for (int pass = 0; pass < 8; ++pass) {
+        if (pass == kCompactPass && cap > 0)
+            hipLaunchKernelGGL((k_layer_hist<PAIR, true>), dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s, candA, candB, cap);
+        else
+            hipLaunchKernelGGL((k_layer_hist<PAIR, false>), dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s, candA, candB, cap);
+    }
     hipLaunchKernelGGL(k_layer_finish<PAIR>, dim3(1), dim3(64), 0, st, s);
+}
+
+// Keys per candidate list: a sixteenth of the layer, at least 4096 (a list holds the keys that share 16 leading bits with
+// the threshold: a fraction of a percent of real-valued contents; constant contents overflow it and do without).
+static size_t cand_capacity(int32_t d_out, int32_t d_in) {
+    const size_t n = (d_out > 0 && d_in > 0) ? (size_t)d_out * (size_t)d_in : 0;
+    const size_t c = n / 16;
+    return c < 4096 ? 4096 : c;
+}
+static size_t update_head_bytes(int32_t d_out) {
+    const size_t rows = d_out > 0 ? (size_t)d_out : 0;
+    return ((sizeof(UpdateScratch) + 3 * rows * sizeof(int32_t) + 255) / 256) * 256;
 }
 
 }  // namespace srigl
@@ -376,9 +465,8 @@ using namespace srigl;
 
 extern "C" {
 
-size_t srigl_mask_update_workspace_bytes(int32_t d_out) {
-    const size_t rows = d_out > 0 ? (size_t)d_out : 0;
-    return ((sizeof(UpdateScratch) + 255) / 256) * 256 + 3 * rows * sizeof(int32_t);
+size_t srigl_mask_update_workspace_bytes(int32_t d_out, int32_t d_in) {
+    return update_head_bytes(d_out) + 2 * cand_capacity(d_out, d_in) * sizeof(unsigned long long);
 }
 
 srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float* grad, int32_t d_out, int32_t d_in, int32_t k,
@@ -390,21 +478,24 @@ srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float*
     if ((long long)d_out * d_in >= (1ll << 32)) return SRIGL_ERR_UNSUPPORTED;   // positions are ranked as 32-bit numbers
     if (d_in > 8192) return SRIGL_ERR_UNSUPPORTED;                              // a row is held in the registers of one workgroup
     if (workspace == nullptr) return SRIGL_ERR_INVALID_ARG;
-    if (workspace_bytes < srigl_mask_update_workspace_bytes(d_out)) return SRIGL_ERR_CAPACITY;
+    if (workspace_bytes < srigl_mask_update_workspace_bytes(d_out, d_in)) return SRIGL_ERR_CAPACITY;
     const unsigned int N = (unsigned int)((long long)d_out * d_in);
     if (N > 0 && (W == nullptr || mask == nullptr || grad == nullptr || mask_out == nullptr || W_out == nullptr)) return SRIGL_ERR_INVALID_ARG;
     UpdateScratch* s = static_cast<UpdateScratch*>(workspace);
-    int* held = reinterpret_cast<int*>(static_cast<unsigned char*>(workspace) + ((sizeof(UpdateScratch) + 255) / 256) * 256);
+    int* held = reinterpret_cast<int*>(static_cast<unsigned char*>(workspace) + sizeof(UpdateScratch));
     int* salient = held + d_out;
     int* remains = salient + d_out;
+    const unsigned long long cap = cand_capacity(d_out, d_in);
+    unsigned long long* candA = reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(workspace) + update_head_bytes(d_out));
+    unsigned long long* candB = candA + cap;
     hipLaunchKernelGGL(k_update_init, dim3(1), dim3(256), 0, st, s, (long long)K_upd);
     if (N > 0) {
-        layer_select<true>(W, mask, grad, remains, N, d_in, s, st);
+        layer_select<true>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
         hipLaunchKernelGGL(k_row_salient, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, s, held, salient);
     }
     hipLaunchKernelGGL(k_decide, dim3(1), dim3(1024), 0, st, held, salient, d_out, d_in, k, gamma_percent, (long long)budget, remains, s);
     if (N > 0) {
-        layer_select<false>(W, mask, grad, remains, N, d_in, s, st);
+        layer_select<false>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
         if (d_in <= 1024) hipLaunchKernelGGL(k_row_update<4>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
         else if (d_in <= 4096) hipLaunchKernelGGL(k_row_update<16>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
         else hipLaunchKernelGGL(k_row_update<32>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);

@@ -62,7 +62,7 @@ def test_condense_and_update_in_a_graph():
     g_np = np.random.default_rng(3).normal(size=Wm.shape).astype(np.float32)
     W_d, m_d, g_d = dev(Wm), dev(L.mask), dev(g_np)
     mask_o, W_o = torch.empty_like(m_d), torch.empty_like(W_d)
-    ws_u = torch.empty(B_.srigl_mask_update_workspace_bytes(150), dtype=torch.uint8, device="cuda")
+    ws_u = torch.empty(B_.srigl_mask_update_workspace_bytes(150, 200), dtype=torch.uint8, device="cuda")
     rep_u = torch.zeros(4, dtype=torch.int64, device="cuda")
     W_c = torch.empty((150, 20), device="cuda")
     idx = torch.empty((150, 20), dtype=torch.int32, device="cuda")

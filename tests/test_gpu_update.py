@@ -23,7 +23,7 @@ def run_update(B_, Wm, mask, grad, k, K_upd, gamma, budget=None):
         budget = int(np.count_nonzero(mask))
     mask_o = torch.full((d_out, d_in), 7, dtype=torch.uint8, device="cuda")
     W_o = torch.full((d_out, d_in), float("nan"), device="cuda")
-    ws = torch.empty(B_.srigl_mask_update_workspace_bytes(d_out), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B_.srigl_mask_update_workspace_bytes(d_out, d_in), dtype=torch.uint8, device="cuda")
     rep = torch.full((4,), -1, dtype=torch.int64, device="cuda")
     B_.srigl_mask_update(dev(Wm), dev(mask), dev(grad), d_out, d_in, k, K_upd, gamma, budget, mask_o, W_o, ws, rep)
     torch.cuda.synchronize()
@@ -121,7 +121,7 @@ def test_argument_errors(B_):
     with pytest.raises(B_.SriglError) as e:
         B_.srigl_mask_update(z, zm, z, 4, 4, 2, 1, 30, 8, zm.clone(), z.clone(), small, rep)
     assert e.value.status == B_.ERR_CAPACITY
-    ws = torch.empty(B_.srigl_mask_update_workspace_bytes(4), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B_.srigl_mask_update_workspace_bytes(4, 4), dtype=torch.uint8, device="cuda")
     with pytest.raises(B_.SriglError):
         B_.srigl_mask_update(z, zm, z, 4, 4, 5, 1, 30, 8, zm.clone(), z.clone(), ws, rep)     # k > d_in
 
@@ -155,3 +155,30 @@ def test_wide_rows_use_the_larger_row_kernels(B_):
         L = si.make_layer(d_in, d_out, k, 1, ablate_frac=0.25, seed=d_in)
         Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
         check(B_, Wm, L.mask, rng.normal(size=L.W.shape).astype(np.float32), k, int(0.3 * L.mask.sum()), 30)
+
+
+@pytest.mark.parametrize("shape", [(3072, 768, 77), (2304, 2048, 205)])
+def test_constant_contents_overflow_the_candidate_lists(B_, shape):
+    """Equal gradients everywhere and coarse weights: the keys that share the threshold's leading bits are most of the layer,
+    more than a candidate list (and, for the larger shape, a workgroup's share of it) holds, so the layer-wide selections
+    stay on the full layer; positions alone order the gradients."""
+    d_out, d_in, k = shape
+    L = si.make_layer(d_in, d_out, k, 1, ablate_frac=0.1, seed=3)
+    Wm = np.where(L.mask != 0, np.round(L.W * 4 * np.sqrt(k)) / 4, 0).astype(np.float32)
+    g = np.full(L.W.shape, 0.5, np.float32)
+    K_upd = int(0.3 * L.mask.sum())
+    info = check(B_, Wm, L.mask, g, k, K_upd, 30)
+    assert info["n_pruned"] == K_upd
+
+
+def test_large_layer_uses_the_candidate_lists(B_):
+    """4.7 million real-valued elements: the third pass leaves a few thousand candidates per selection, which the remaining
+    passes read instead of the layer; ties inside them (duplicated magnitudes) still rank by position."""
+    d_out, d_in, k = 2304, 2048, 205
+    L = si.make_layer(d_in, d_out, k, 1, ablate_frac=0.05, seed=4)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    rng = np.random.default_rng(9)
+    g = rng.normal(size=L.W.shape).astype(np.float32)
+    g[rng.integers(0, d_out, 50000), rng.integers(0, d_in, 50000)] = np.float32(0.8125)   # duplicated magnitudes near the top
+    K_upd = int(0.3 * L.mask.sum())
+    check(B_, Wm, L.mask, g, k, K_upd, 30)
