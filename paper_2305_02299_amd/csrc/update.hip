@@ -73,11 +73,9 @@ __global__ __launch_bounds__(256) void k_update_init(UpdateScratch* s, long long
 // From a 256-bin histogram (lane l reads bins 4l .. 4l + 3), for one wavefront: the byte d with suffix(d) >= want >
 // suffix(d + 1), suffix(d) = number of keys whose byte is >= d; `above` = suffix(d + 1), `in_bin` = keys with byte d, `total`
 // = suffix(0).  The results are the same on every lane.
-__device__ __forceinline__ void pick_byte(const unsigned int* h, unsigned long long want, int lane, unsigned long long& digit,
+__device__ __forceinline__ void pick_from(const unsigned long long (&v)[4], unsigned long long want, int lane, unsigned long long& digit,
                                           unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
-    unsigned long long v[4], part[5];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = h[4 * lane + j];
+    unsigned long long part[5];
     part[4] = 0;
 #pragma unroll
     for (int j = 3; j >= 0; --j) part[j] = part[j + 1] + v[j];
@@ -104,6 +102,27 @@ __device__ __forceinline__ void pick_byte(const unsigned int* h, unsigned long l
     digit = __shfl(digit, src, 64);
     above = __shfl(above, src, 64);
     in_bin = __shfl(in_bin, src, 64);
+}
+__device__ __forceinline__ void pick_byte(const unsigned int* h, unsigned long long want, int lane, unsigned long long& digit,
+                                          unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
+    unsigned long long v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = h[4 * lane + j];
+    pick_from(v, want, lane, digit, above, in_bin, total);
+}
+// the same over the sum of COPIES sub-histograms; copy c keeps the count of digit d at index (d + kCopyTurn * c) mod 256, so that
+// equal digits of different copies sit in different LDS banks
+constexpr int kCopyTurn = 16;
+template <int COPIES>
+__device__ __forceinline__ void pick_byte_copies(const unsigned int (*h)[256], unsigned long long want, int lane, unsigned long long& digit,
+                                                 unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
+    unsigned long long v[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < COPIES; ++c) {
+        const uint4 q = *reinterpret_cast<const uint4*>(&h[c][(4 * lane + kCopyTurn * c) & 255]);
+        v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
+    }
+    pick_from(v, want, lane, digit, above, in_bin, total);
 }
 
 // The state of a layer-wide walk before pass `pass` (1..8), from the state before pass - 1 and the histogram of pass - 1.
@@ -317,36 +336,40 @@ __global__ __launch_bounds__(1024) void k_decide(const int* __restrict__ held, c
 
 // Radix walk inside one workgroup of 256 threads: the threshold of the `want` largest keys among the row's candidates.
 // key_of(j, key): whether the thread's j-th column is a candidate, and its key.  1 <= want <= number of candidates.
+// Same digits as the layer-wide walk (the top bit of a key is zero).  One barrier per pass: the histograms rotate through
+// three buffers (a pass adds into one, clears the next; the one before may still be read by a wavefront that is late), and
+// every wavefront sums the kRowCopies sub-histograms and picks the digit for itself, so nothing is handed round.
+constexpr int kRowCopies = 4;
 template <int CPT, typename KeyOf>
-__device__ unsigned long long row_select(unsigned long long want, KeyOf key_of, unsigned int* h, unsigned long long* shared3) {
-    const int t = threadIdx.x;
+__device__ unsigned long long row_select(unsigned long long want, KeyOf key_of, unsigned int (*h)[kRowCopies][256]) {
+    const int t = threadIdx.x, lane = t & 63;
+    const int copy = t & (kRowCopies - 1);
     unsigned long long prefix = 0;
+#pragma unroll
+    for (int c = 0; c < kRowCopies; ++c) h[0][c][t] = 0;
+    __syncthreads();
 #pragma unroll 1
     for (int pass = 0; pass < 8; ++pass) {
-        const int shift = 56 - 8 * pass;
-        h[t] = 0;
-        __syncthreads();
+        const int cur = pass % 3, nxt = (pass + 1) % 3;
+        const int shift = pass_shift(pass);
+        const unsigned int dmask = (1u << pass_bits(pass)) - 1u;
+        const int pshift = 64 - bits_done(pass);
+#pragma unroll
+        for (int c = 0; c < kRowCopies; ++c) h[nxt][c][t] = 0;
 #pragma unroll
         for (int j = 0; j < CPT; ++j) {
             unsigned long long key;
             if (!key_of(j, key)) continue;
-            if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
-            atomicAdd(&h[(unsigned int)(key >> shift) & 255u], 1u);
+            if (pass > 0 && (key >> pshift) != prefix) continue;
+            atomicAdd(&h[cur][copy][(((unsigned int)(key >> shift) & dmask) + kCopyTurn * copy) & 255u], 1u);
         }
         __syncthreads();
-        if (t < 64) {
-            unsigned long long digit, above, in_bin, total;
-            pick_byte(h, want, t, digit, above, in_bin, total);
-            if (t == 0) {
-                shared3[0] = (prefix << 8) | digit;
-                shared3[1] = want - above;
-                shared3[2] = (want - above == in_bin) ? 1ull : 0ull;   // every key of this byte is wanted: the walk is over
-            }
-        }
-        __syncthreads();
-        prefix = shared3[0];
-        want = shared3[1];
-        if (shared3[2] != 0 && pass < 7) return prefix << (56 - 8 * pass);   // the smallest key with this prefix
+        unsigned long long digit, above, in_bin, total;
+        pick_byte_copies<kRowCopies>(h[cur], want, lane, digit, above, in_bin, total);
+        prefix = (prefix << pass_bits(pass)) | digit;
+        want -= above;
+        // every key of this digit is wanted: the walk is over, the threshold is the smallest key with this prefix
+        if (want == in_bin && pass < 7) return prefix << (64 - bits_done(pass + 1));
     }
     return prefix;
 }
@@ -355,12 +378,11 @@ __device__ unsigned long long row_select(unsigned long long want, KeyOf key_of, 
 // whether the weight survives step 6, and the one key the column can be ranked by (its weight magnitude if it survives,
 // else its gradient magnitude), so the walks read registers only.
 template <int CPT>
-__global__ __launch_bounds__(256) void k_row_update(const float* __restrict__ W, const uint8_t* __restrict__ mask,
+__global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, int d_in, const int* __restrict__ remains,
                                                     const UpdateScratch* __restrict__ s, uint8_t* __restrict__ mask_out,
                                                     float* __restrict__ W_out) {
-    __shared__ unsigned int h[256];
-    __shared__ unsigned long long shared3[3];
+    __shared__ __align__(16) unsigned int h[3][kRowCopies][256];
     __shared__ int n_kept;
     const int r = blockIdx.x, t = threadIdx.x;
     const unsigned int row0 = (unsigned int)r * d_in;
@@ -381,12 +403,14 @@ __global__ __launch_bounds__(256) void k_row_update(const float* __restrict__ W,
         if (c < d_in) {
             valid |= 1u << j;
             const unsigned int i = row0 + c;
-            const float w = W[i];
-            if (mask[i] != 0 && key_small_first(mag_bits(w), i) < t_prune) {
+            // all three loads go out at once (the lines are fetched either way)
+            const float w = W[i], g = grad[i];
+            const uint8_t m = mask[i];
+            if (m != 0 && key_small_first(mag_bits(w), i) < t_prune) {
                 survives |= 1u << j;
                 key[j] = key_large_first(mag_bits(w), (unsigned int)c);
             } else {
-                key[j] = key_large_first(mag_bits(grad[i]), (unsigned int)c);
+                key[j] = key_large_first(mag_bits(g), (unsigned int)c);
             }
         }
     }
@@ -400,12 +424,12 @@ __global__ __launch_bounds__(256) void k_row_update(const float* __restrict__ W,
         else t_keep = row_select<CPT>((unsigned long long)k_new, [&](int j, unsigned long long& k_out) {
             k_out = key[j];
             return ((survives >> j) & 1u) != 0;
-        }, h, shared3);
+        }, h);
     } else if (kept < k_new) {
         t_grow = row_select<CPT>((unsigned long long)(k_new - kept), [&](int j, unsigned long long& k_out) {
             k_out = key[j];
             return ((valid >> j) & 1u) != 0 && ((survives >> j) & 1u) == 0;
-        }, h, shared3);
+        }, h);
     }
 #pragma unroll
     for (int j = 0; j < CPT; ++j) {
