@@ -409,6 +409,23 @@ def update(args, emit=True, names=("c2", "c5")):
         e1.record()
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) / steps * 1e3
+        # the same calls replayed from a HIP graph: what the ~25 dependent launches of a call cost without the host in the loop
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            call()
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for _ in range(5):
+                call()
+        gr.replay()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(4):
+            gr.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us_graph = e0.elapsed_time(e1) / 20 * 1e3
         N = L.d_out * L.d_in
         nbytes = 14 * N            # W, grad, W_out: 4 bytes each; mask, mask_out: 1 byte each, every element once
         cpu = None
@@ -420,6 +437,7 @@ def update(args, emit=True, names=("c2", "c5")):
         rows.append({"metric": "mask_update_us_per_call", "value": us, "unit": "us/call", "n_gpus": 1, "steps": steps,
                           "dtype": "f32", "data": "synthetic",
                           "config": {"workload": "%s: %d x %d, k=%d, K_upd=%d, gamma_sal=30%%" % (name, L.d_out, L.d_in, L.K, K_upd)},
+                          "us_per_call_graph_replay": us_graph,
                           "report": dict(zip(("k_new", "n_remaining", "n_ablated_now", "n_pruned"), rep.cpu().tolist())),
                           "roofline": {"bound": "hbm", "achieved": nbytes / us / 1e3, "peak": 8000.0, "unit": "GB/s",
                                        "frac": nbytes / us / 1e3 / 8000.0, "traffic": None, "algorithmic_bytes": nbytes},

@@ -157,8 +157,11 @@ __device__ SelState advance(const SelState& before, const unsigned int* __restri
 // COMPACT (the launch of pass kCompactPass): every key that matches the prefix is also appended to the selection's candidate
 // list (collected per workgroup in LDS, one counter update per workgroup); a workgroup that meets more than kBlockList of
 // them, or a list longer than `cap`, leaves the counter above `cap`, and the later passes then keep reading the layer.
+// VEC (d_in a multiple of 4, 16-byte aligned arrays): four consecutive elements per thread and step, moved with one 4-byte
+// and two 16-byte loads that do not wait for each other (a line of W or grad is fetched for almost every run of 32 elements
+// anyway, so reading both arrays in full costs no extra traffic).
 constexpr int kCopies = 8;
-template <bool PAIR, bool COMPACT>
+template <bool PAIR, bool COMPACT, bool VEC>
 __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, const int* __restrict__ remains, unsigned int N,
                                                     int d_in, int pass, UpdateScratch* __restrict__ s,
@@ -208,26 +211,49 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
     const unsigned long long countA = lists ? s->cand_count[selA] : 0, countB = (lists && PAIR) ? s->cand_count[1] : 0;
     const bool listA = lists && countA <= cap, listB = lists && PAIR && countB <= cap;
     const bool scanA = !doneA && !listA, scanB = PAIR && !doneB && !listB;
-    if (scanA || scanB) {
+    // one element: position ii, mask byte m, weight w, gradient g, whether its neuron remains (selection 2 only)
+    auto element = [&](unsigned int ii, unsigned int m, float w, float g, bool rem) {
+        if (m != 0) {
+            if (!scanA || (!PAIR && !rem)) return;
+            const unsigned long long key = key_small_first(mag_bits(w), ii);
+            if (pass > 0 && (key >> pshift) != prefixA) return;
+            atomicAdd(&h[0][copy][(unsigned int)(key >> shift) & dmask], 1u);
+            if (COMPACT) {
+                const unsigned int slot = atomicAdd(&keep_n[0], 1u);
+                if (slot < (unsigned)kBlockList) keep[0][slot] = key;
+            }
+        } else if (scanB) {
+            const unsigned long long key = key_large_first(mag_bits(g), ii);
+            if (pass > 0 && (key >> pshift) != prefixB) return;
+            atomicAdd(&h[1][copy][(unsigned int)(key >> shift) & dmask], 1u);
+            if (COMPACT) {
+                const unsigned int slot = atomicAdd(&keep_n[1], 1u);
+                if (slot < (unsigned)kBlockList) keep[1][slot] = key;
+            }
+        }
+    };
+    if ((scanA || scanB) && VEC) {
+        const unsigned int N4 = N / 4;   // d_in is a multiple of 4, so N is, and a run of 4 stays inside one row
+        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < N4; i += (unsigned long long)gridDim.x * 256) {
+            const unsigned int base = 4u * (unsigned int)i;
+            const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + base);
+            float4 w4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), g4 = w4;
+            if (scanA) w4 = *reinterpret_cast<const float4*>(W + base);
+            if (scanB) g4 = *reinterpret_cast<const float4*>(grad + base);
+            const bool rem = (PAIR || m4 == 0) ? true : remains[base / (unsigned)d_in] != 0;
+            element(base + 0, m4 & 0xffu, w4.x, g4.x, rem);
+            element(base + 1, (m4 >> 8) & 0xffu, w4.y, g4.y, rem);
+            element(base + 2, (m4 >> 16) & 0xffu, w4.z, g4.z, rem);
+            element(base + 3, m4 >> 24, w4.w, g4.w, rem);
+        }
+    } else if (scanA || scanB) {
         for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < N; i += (unsigned long long)gridDim.x * 256) {
             const unsigned int ii = (unsigned int)i;
-            if (mask[ii] != 0) {
-                if (!scanA || (!PAIR && !remains[ii / (unsigned)d_in])) continue;
-                const unsigned long long key = key_small_first(mag_bits(W[ii]), ii);
-                if (pass > 0 && (key >> pshift) != prefixA) continue;
-                atomicAdd(&h[0][copy][(unsigned int)(key >> shift) & dmask], 1u);
-                if (COMPACT) {
-                    const unsigned int slot = atomicAdd(&keep_n[0], 1u);
-                    if (slot < (unsigned)kBlockList) keep[0][slot] = key;
-                }
+            const unsigned int m = mask[ii];
+            if (m != 0) {
+                if (scanA) element(ii, m, W[ii], 0.0f, PAIR ? true : remains[ii / (unsigned)d_in] != 0);
             } else if (scanB) {
-                const unsigned long long key = key_large_first(mag_bits(grad[ii]), ii);
-                if (pass > 0 && (key >> pshift) != prefixB) continue;
-                atomicAdd(&h[1][copy][(unsigned int)(key >> shift) & dmask], 1u);
-                if (COMPACT) {
-                    const unsigned int slot = atomicAdd(&keep_n[1], 1u);
-                    if (slot < (unsigned)kBlockList) keep[1][slot] = key;
-                }
+                element(ii, 0u, 0.0f, grad[ii], true);
             }
         }
     }
@@ -280,6 +306,8 @@ __global__ __launch_bounds__(64) void k_layer_finish(UpdateScratch* __restrict__
 }
 
 // Steps 3 and the start of 4: per neuron, how many weights it holds and how many salient ones.  One wavefront per row.
+// VEC as in k_layer_hist: a lane takes runs of 4 columns.
+template <bool VEC>
 __global__ __launch_bounds__(256) void k_row_salient(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                      const float* __restrict__ grad, int d_out, int d_in,
                                                      const UpdateScratch* __restrict__ s, int* __restrict__ held, int* __restrict__ salient) {
@@ -288,13 +316,30 @@ __global__ __launch_bounds__(256) void k_row_salient(const float* __restrict__ W
     if (r >= d_out) return;
     const unsigned long long t_small = s->fin[0].prefix, t_grad = s->fin[1].prefix;
     int h = 0, sal = 0;
-    for (int c = lane; c < d_in; c += 64) {
-        const unsigned int i = (unsigned int)r * d_in + c;
-        if (mask[i]) {
+    auto element = [&](unsigned int i, unsigned int m, float w, float g) {
+        if (m) {
             ++h;
-            if (key_small_first(mag_bits(W[i]), i) < t_small) ++sal;    // survives the layer-wide pruning
-        } else if (key_large_first(mag_bits(grad[i]), i) >= t_grad) {
-            ++sal;                                                        // would be grown
+            if (key_small_first(mag_bits(w), i) < t_small) ++sal;    // survives the layer-wide pruning
+        } else if (key_large_first(mag_bits(g), i) >= t_grad) {
+            ++sal;                                                    // would be grown
+        }
+    };
+    if (VEC) {
+        for (int c = 4 * lane; c < d_in; c += 256) {
+            const unsigned int i = (unsigned int)r * d_in + c;
+            const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + i);
+            const float4 w4 = *reinterpret_cast<const float4*>(W + i);
+            const float4 g4 = *reinterpret_cast<const float4*>(grad + i);
+            element(i + 0, m4 & 0xffu, w4.x, g4.x);
+            element(i + 1, (m4 >> 8) & 0xffu, w4.y, g4.y);
+            element(i + 2, (m4 >> 16) & 0xffu, w4.z, g4.z);
+            element(i + 3, m4 >> 24, w4.w, g4.w);
+        }
+    } else {
+        for (int c = lane; c < d_in; c += 64) {
+            const unsigned int i = (unsigned int)r * d_in + c;
+            const unsigned int m = mask[i];
+            element(i, m, m ? W[i] : 0.0f, m ? 0.0f : grad[i]);
         }
     }
     for (int off = 32; off > 0; off >>= 1) { h += __shfl_xor(h, off, 64); sal += __shfl_xor(sal, off, 64); }
@@ -376,8 +421,9 @@ __device__ unsigned long long row_select(unsigned long long want, KeyOf key_of, 
 
 // Steps 6 (applied) and 7.  One workgroup of 256 threads per row; a thread holds CPT columns of the row (d_in <= 256 CPT):
 // whether the weight survives step 6, and the one key the column can be ranked by (its weight magnitude if it survives,
-// else its gradient magnitude), so the walks read registers only.
-template <int CPT>
+// else its gradient magnitude), so the walks read registers only.  VEC (d_in a multiple of 4, 16-byte aligned arrays): a
+// thread's columns are runs of 4, moved with 16-byte loads and stores; otherwise column t + 256 j, one element at a time.
+template <int CPT, bool VEC>
 __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, int d_in, const int* __restrict__ remains,
                                                     const UpdateScratch* __restrict__ s, uint8_t* __restrict__ mask_out,
@@ -386,8 +432,17 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
     __shared__ int n_kept;
     const int r = blockIdx.x, t = threadIdx.x;
     const unsigned int row0 = (unsigned int)r * d_in;
+    // column of the thread's j-th element
+    auto col_of = [&](int j) { return VEC ? 4 * (t + 256 * (j >> 2)) + (j & 3) : t + 256 * j; };
     if (!remains[r]) {
-        for (int c = t; c < d_in; c += 256) { mask_out[row0 + c] = 0; W_out[row0 + c] = 0.0f; }
+        if (VEC) {
+            for (int c = 4 * t; c < d_in; c += 1024) {
+                *reinterpret_cast<uint32_t*>(mask_out + row0 + c) = 0u;
+                *reinterpret_cast<float4*>(W_out + row0 + c) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
+        } else {
+            for (int c = t; c < d_in; c += 256) { mask_out[row0 + c] = 0; W_out[row0 + c] = 0.0f; }
+        }
         return;
     }
     const unsigned long long t_prune = s->fin[2].prefix;
@@ -396,21 +451,42 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
     unsigned int survives = 0, valid = 0;   // bit j: the thread's j-th column
     if (t == 0) n_kept = 0;
     __syncthreads();
+    auto take = [&](int j, int c, float w, float g, uint8_t m) {
+        valid |= 1u << j;
+        const unsigned int i = row0 + c;
+        if (m != 0 && key_small_first(mag_bits(w), i) < t_prune) {
+            survives |= 1u << j;
+            key[j] = key_large_first(mag_bits(w), (unsigned int)c);
+        } else {
+            key[j] = key_large_first(mag_bits(g), (unsigned int)c);
+        }
+    };
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-        const int c = t + 256 * j;
-        key[j] = 0;
-        if (c < d_in) {
-            valid |= 1u << j;
-            const unsigned int i = row0 + c;
-            // all three loads go out at once (the lines are fetched either way)
-            const float w = W[i], g = grad[i];
-            const uint8_t m = mask[i];
-            if (m != 0 && key_small_first(mag_bits(w), i) < t_prune) {
-                survives |= 1u << j;
-                key[j] = key_large_first(mag_bits(w), (unsigned int)c);
-            } else {
-                key[j] = key_large_first(mag_bits(g), (unsigned int)c);
+    for (int j = 0; j < CPT; ++j) key[j] = 0;
+    if (VEC) {
+#pragma unroll
+        for (int q = 0; q < CPT / 4; ++q) {
+            const int c0 = 4 * (t + 256 * q);
+            if (c0 < d_in) {
+                // all three loads go out at once (the lines are fetched either way)
+                const float4 w4 = *reinterpret_cast<const float4*>(W + row0 + c0);
+                const float4 g4 = *reinterpret_cast<const float4*>(grad + row0 + c0);
+                const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + row0 + c0);
+                take(4 * q + 0, c0 + 0, w4.x, g4.x, (uint8_t)(m4 & 0xffu));
+                take(4 * q + 1, c0 + 1, w4.y, g4.y, (uint8_t)((m4 >> 8) & 0xffu));
+                take(4 * q + 2, c0 + 2, w4.z, g4.z, (uint8_t)((m4 >> 16) & 0xffu));
+                take(4 * q + 3, c0 + 3, w4.w, g4.w, (uint8_t)(m4 >> 24));
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            const int c = t + 256 * j;
+            if (c < d_in) {
+                const unsigned int i = row0 + c;
+                const float w = W[i], g = grad[i];
+                const uint8_t m = mask[i];
+                take(j, c, w, g, m);
             }
         }
     }
@@ -431,19 +507,31 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
             return ((valid >> j) & 1u) != 0 && ((survives >> j) & 1u) == 0;
         }, h);
     }
+    // column j of the thread: kept (its weight is copied), grown (weight zero) or free
+    auto kept_j = [&](int j) { return ((survives >> j) & 1u) != 0 && key[j] >= t_keep; };
+    auto grown_j = [&](int j) { return ((valid >> j) & 1u) != 0 && ((survives >> j) & 1u) == 0 && key[j] >= t_grow; };
+    if (VEC) {
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-        const int c = t + 256 * j;
-        if (c >= d_in) continue;
-        uint8_t m = 0;
-        float w = 0.0f;
-        if ((survives >> j) & 1u) {
-            if (key[j] >= t_keep) { m = 1; w = W[row0 + c]; }
-        } else if (key[j] >= t_grow) {
-            m = 1;   // grown: the weight starts at zero
+        for (int q = 0; q < CPT / 4; ++q) {
+            const int c0 = 4 * (t + 256 * q);
+            if (c0 >= d_in) continue;
+            const bool k0 = kept_j(4 * q), k1 = kept_j(4 * q + 1), k2 = kept_j(4 * q + 2), k3 = kept_j(4 * q + 3);
+            float4 w4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (k0 || k1 || k2 || k3) w4 = *reinterpret_cast<const float4*>(W + row0 + c0);
+            const uint32_t m4 = (uint32_t)(k0 || grown_j(4 * q)) | ((uint32_t)(k1 || grown_j(4 * q + 1)) << 8) |
+                                ((uint32_t)(k2 || grown_j(4 * q + 2)) << 16) | ((uint32_t)(k3 || grown_j(4 * q + 3)) << 24);
+            *reinterpret_cast<uint32_t*>(mask_out + row0 + c0) = m4;
+            *reinterpret_cast<float4*>(W_out + row0 + c0) = make_float4(k0 ? w4.x : 0.0f, k1 ? w4.y : 0.0f, k2 ? w4.z : 0.0f, k3 ? w4.w : 0.0f);
         }
-        mask_out[row0 + c] = m;
-        W_out[row0 + c] = w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            const int c = t + 256 * j;
+            if (c >= d_in) continue;
+            const bool kj = kept_j(j);
+            mask_out[row0 + c] = (uint8_t)(kj || grown_j(j));
+            W_out[row0 + c] = kj ? W[row0 + c] : 0.0f;
+        }
     }
 }
 
@@ -462,12 +550,21 @@ static void layer_select(const float* W, const uint8_t* mask, const float* grad,
                          UpdateScratch* s, unsigned long long* candA, unsigned long long* candB, unsigned long long cap, hipStream_t st) {
     unsigned int blocks = (N + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    for (int pass = 0; pass < 8; ++pass) {
-        if (pass == kCompactPass && cap > 0)
-            hipLaunchKernelGGL((k_layer_hist<PAIR, true>), dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s, candA, candB, cap);
-        else
-            hipLaunchKernelGGL((k_layer_hist<PAIR, false>), dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s, candA, candB, cap);
+    const bool vec = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(mask) % 4 == 0;
+    if (vec) {   // a thread takes 4 elements per step
+        blocks = (N / 4 + 255) / 256;
+        if (blocks > 2048) blocks = 2048;
+        if (blocks == 0) blocks = 1;
     }
+#define SRIGL_HIST(COMPACT, VEC)                                                                                                   \
+    hipLaunchKernelGGL((k_layer_hist<PAIR, COMPACT, VEC>), dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s, \
+                       candA, candB, cap)
+    for (int pass = 0; pass < 8; ++pass) {
+        if (pass == kCompactPass && cap > 0) { if (vec) SRIGL_HIST(true, true); else SRIGL_HIST(true, false); }
+        else { if (vec) SRIGL_HIST(false, true); else SRIGL_HIST(false, false); }
+    }
+#undef SRIGL_HIST
     hipLaunchKernelGGL(k_layer_finish<PAIR>, dim3(1), dim3(64), 0, st, s);
 }
 
@@ -515,14 +612,25 @@ srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float*
     hipLaunchKernelGGL(k_update_init, dim3(1), dim3(256), 0, st, s, (long long)K_upd);
     if (N > 0) {
         layer_select<true>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
-        hipLaunchKernelGGL(k_row_salient, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, s, held, salient);
+        const bool vec_in = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
+                            reinterpret_cast<uintptr_t>(mask) % 4 == 0;
+        if (vec_in) hipLaunchKernelGGL(k_row_salient<true>, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, s, held, salient);
+        else hipLaunchKernelGGL(k_row_salient<false>, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, s, held, salient);
     }
     hipLaunchKernelGGL(k_decide, dim3(1), dim3(1024), 0, st, held, salient, d_out, d_in, k, gamma_percent, (long long)budget, remains, s);
     if (N > 0) {
         layer_select<false>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
-        if (d_in <= 1024) hipLaunchKernelGGL(k_row_update<4>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
-        else if (d_in <= 4096) hipLaunchKernelGGL(k_row_update<16>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
-        else hipLaunchKernelGGL(k_row_update<32>, dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out);
+        // 16-byte moves need rows that start on 16-byte (mask: 4-byte) boundaries
+        const bool vec = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(W_out) % 16 == 0 && reinterpret_cast<uintptr_t>(mask) % 4 == 0 &&
+                         reinterpret_cast<uintptr_t>(mask_out) % 4 == 0;
+#define SRIGL_ROW_UPDATE(CPT)                                                                                                      \
+    if (vec) hipLaunchKernelGGL((k_row_update<CPT, true>), dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out); \
+    else hipLaunchKernelGGL((k_row_update<CPT, false>), dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out)
+        if (d_in <= 1024) { SRIGL_ROW_UPDATE(4); }
+        else if (d_in <= 4096) { SRIGL_ROW_UPDATE(16); }
+        else { SRIGL_ROW_UPDATE(32); }
+#undef SRIGL_ROW_UPDATE
     }
     hipLaunchKernelGGL(k_update_report, dim3(1), dim3(64), 0, st, s, (long long)K_upd, reinterpret_cast<long long*>(report_dev));
     return hip_ok(hipGetLastError());
