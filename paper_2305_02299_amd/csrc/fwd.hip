@@ -424,11 +424,8 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     // above 64 rows the batched kernel always wins.
     bool batched = B > 16;
     if (B > 4 && B <= 64 && d_in % 16 == 0) {
-        int L = 4;
-        while (L < 64 && L * kKlaneTerms < K) L <<= 1;
-        const int req = L * kKlaneTerms;   // term slots one request of a lane group covers
-        const double slots = (double)B * n_active * ((K + req - 1) / req * req);
-        const double small_us = 3.2 + 0.0005 * d_in + (d_in <= 1024 ? 0.44e-6 : 0.6e-6) * slots;
+        static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
+        const double small_us = klane_estimate_us(B, d_in, n_active, K);
         // (few stored rows: too few workgroups share the staging)
         const double batched_us = 4.6 + 0.0014 * d_in + (n_active <= 1024 ? 0.5 : 0.0);
         batched = batched_us < small_us;

@@ -55,6 +55,18 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
 srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
 bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
 
+// Estimated time (us, operands in cache) of the small-batch forward kernel: a fixed part plus a part per term slot (K rounded
+// up to the slots one request of a lane group covers; dearer with one batch row per workgroup, the wide-input setting).
+// A fit of timings of 512- to 4096-wide layers at 80-90 % sparsity; used to pick the kernel for batches of 5 to 64 rows and
+// by the choice between the condensed and the structured-only form.
+inline double klane_estimate_us(int B, int d_in, int n_active, int K) {
+    int L = 4;
+    while (L < 64 && L * 4 < K) L <<= 1;
+    const int req = L * 4;   // term slots one request of a lane group covers (4 terms per lane)
+    const double slots = (double)B * n_active * ((K + req - 1) / req * req);
+    return 3.2 + 0.0005 * d_in + (d_in <= 1024 ? 0.44e-6 : 0.6e-6) * slots;
+}
+
 inline srigl_status hip_ok(hipError_t e) { return e == hipSuccess ? SRIGL_OK : SRIGL_ERR_HIP; }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
