@@ -419,15 +419,16 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     }
     // Small batches: the lanes-along-K kernel costs a fixed part plus a part per term slot (K rounded up to the
     // lanes it spreads a row over; dearer with one batch row per workgroup, the wide-input setting); the batched
-    // kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in).
+    // kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its
+    // share of the stored terms.
     // Fits of timings of 512- to 4096-wide layers at 80-90 % sparsity, the cold read of W_c / idx left out of both;
     // above 64 rows the batched kernel always wins.
     bool batched = B > 16;
-    if (B > 4 && B <= 64 && d_in % 16 == 0) {
+    if (B > 1 && B <= 64 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
         const double small_us = klane_estimate_us(B, d_in, n_active, K);
         // (few stored rows: too few workgroups share the staging)
-        const double batched_us = 4.6 + 0.0014 * d_in + (n_active <= 1024 ? 0.5 : 0.0);
+        const double batched_us = 4.3 + 0.0014 * d_in + 1.5e-6 * (double)n_active * K + (n_active <= 1024 ? 0.5 : 0.0);
         batched = batched_us < small_us;
     }
     if (batched && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);

@@ -466,7 +466,7 @@ srigl_representation srigl_choose_representation(int32_t B, int32_t d_in, int32_
     const bool two_rows = B >= 512 && K >= 32;   // the batched kernel's 128-row tiles (about 1.7x the term rate)
     double cond = 6.3 + b * ((double)d_in + d_out) / 2.2e5 + terms / (two_rows ? 1.7e7 : 1.0e7);
     if (B <= 16) cond = fmin(cond, 2.6 + terms / 1.4e6);
-    if (B > 4 && B <= 64 && d_in % 16 == 0) cond = fmin(cond, klane_estimate_us(B, d_in, n_active, K));
+    if (B > 1 && B <= 64 && d_in % 16 == 0) cond = fmin(cond, klane_estimate_us(B, d_in, n_active, K));
     double ns_per_k = 0.0;
     const bool f32 = dtype == SRIGL_F32;
     choose_tile(B > 0 ? B : 1, n_active > 0 ? n_active : 1, f32, &ns_per_k);
