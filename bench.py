@@ -33,6 +33,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VALU_PEAK_TFLOPS = 157.3  # published vector fp32 (packed forms); 78.6 without packed fp32
+LDS_PEAK_GBS = 256 * 128 * 2.4    # 256 CUs x 128 bytes per clock x 2.4 GHz = 78,643 GB/s
 CACHE_BYTES = 256 << 20        # Infinity Cache; the cold loop cycles through >= 2x this
 
 # Bytes per launch between L2 and the fabric (HBM / Infinity Cache) of the forward kernel, from the rocprofv3 --pmc
@@ -652,6 +653,10 @@ def main():
         "gflops_effective": r["gflops_cold"],
         "hbm_frac_of_measured_copy_bw": r["hbm_gbs_cold"] / copy_gbs,
         "valu_frac_of_fp32_peak": r["gflops_cold"] / 1e3 / FP32_VALU_PEAK_TFLOPS,
+        # what the gather formulation is bound by: every term reads 4 bytes per batch row from LDS (256 CUs x 128 B/clk x 2.4 GHz)
+        "lds_gather": {"bytes_per_call": 4 * Bn * n_active * K, "peak_gbs": LDS_PEAK_GBS,
+                       "achieved_gbs_warm": 4 * Bn * n_active * K / (r["us_per_call_warm"] * 1e-6) / 1e9,
+                       "frac_warm": 4 * Bn * n_active * K / (r["us_per_call_warm"] * 1e-6) / 1e9 / LDS_PEAK_GBS},
         "setup_us": {"check_fanin": t_check * 1e3, "condense": t_cond * 1e3},
         "context": {"empty_kernel_us": t_empty * 1e3, "copy_kernel_gbs": copy_gbs, "torch_dense_linear_us": t_dense * 1e3,
                     "paper_speedups": "3.4x/2.5x vs dense/CSR (Xeon W-2145, B=1), 1.7x/13.0x (Titan V, B=256): other hardware"},
