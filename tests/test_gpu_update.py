@@ -182,3 +182,34 @@ def test_large_layer_uses_the_candidate_lists(B_):
     g[rng.integers(0, d_out, 50000), rng.integers(0, d_in, 50000)] = np.float32(0.8125)   # duplicated magnitudes near the top
     K_upd = int(0.3 * L.mask.sum())
     check(B_, Wm, L.mask, g, k, K_upd, 30)
+
+
+def test_unaligned_arrays_take_the_element_wise_kernels(B_):
+    """d_in a multiple of 4 but arrays that start off a 16-byte (mask: 4-byte) boundary: same result through the kernels that
+    move one element at a time."""
+    d_out, d_in, k = 40, 64, 7
+    L = si.make_layer(d_in, d_out, k, 1, ablate_frac=0.1, seed=21)
+    Wm = np.where(L.mask != 0, L.W, 0).astype(np.float32)
+    g = np.random.default_rng(22).normal(size=L.W.shape).astype(np.float32)
+    n = d_out * d_in
+    K_upd = int(0.3 * L.mask.sum())
+    m_ref, w_ref, info_ref = oracle.mask_update(Wm, L.mask, g, k, K_upd, 30, int(L.mask.sum()))
+
+    def shifted(a, dtype, shift):
+        buf = torch.zeros(n + 8, dtype=dtype, device="cuda")
+        view = buf[shift:shift + n].view(d_out, d_in)
+        view.copy_(torch.from_numpy(np.ascontiguousarray(a)).cuda())
+        return buf, view
+    _, W_v = shifted(Wm, torch.float32, 1)        # 4 bytes past a 16-byte boundary
+    _, g_v = shifted(g, torch.float32, 3)
+    _, m_v = shifted(L.mask, torch.uint8, 1)      # 1 byte past a 4-byte boundary
+    bo, mask_o = shifted(np.zeros_like(L.mask), torch.uint8, 2)
+    bw, W_o = shifted(np.zeros_like(Wm), torch.float32, 1)
+    assert W_v.data_ptr() % 16 != 0 and m_v.data_ptr() % 4 != 0
+    ws = torch.empty(B_.srigl_mask_update_workspace_bytes(d_out, d_in), dtype=torch.uint8, device="cuda")
+    rep = torch.full((4,), -1, dtype=torch.int64, device="cuda")
+    B_.srigl_mask_update(W_v, m_v, g_v, d_out, d_in, k, K_upd, 30, int(L.mask.sum()), mask_o, W_o, ws, rep)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(mask_o), m_ref) and host(W_o).tobytes() == w_ref.tobytes()
+    assert rep.cpu().tolist() == [info_ref["k_new"], info_ref["n_remaining"], info_ref["n_ablated_now"], info_ref["n_pruned"]]
+    assert float(bw[0]) == 0.0 and float(bw[-1]) == 0.0 and int(bo[0]) == 0 and int(bo[-1]) == 0   # nothing written outside
