@@ -318,23 +318,35 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     if (p.n_chunks < 1) p.n_chunks = 1;
     if (p.n_chunks > 1 && a.seg == nullptr) return p;   // chunk walking needs ascending rows + seg
     p.lds = (size_t)(C + 1) * S * sizeof(float);
-    // stored rows per wavefront: fewest rounds of 256 workgroups (one per CU), each round costing a fixed
-    // part (staging, barriers, stores: about two stored rows' worth) plus one unit per stored row
+    // stored rows per wavefront: fewest rounds times the cost of a workgroup, a fixed part (staging the tile, barriers,
+    // stores) plus a part per stored row of a wavefront.  Rounds are counted per XCD (32 compute units; the kernel gives
+    // all batch tiles of a group of stored rows to one XCD): 12 groups are two rounds on four of the eight XCDs even when
+    // the launch has fewer than 256 workgroups.  Whole-row tiles (one term slice): in units of one term of a 64-row tile,
+    // staging costs 0.15 per column and 64 rows, a term of a 128-row tile 1.3, six rows per wavefront (one block of
+    // terms held in registers) a tenth more; with term slices the fixed part is about two stored rows' worth.  Fits of
+    // the measured ranking of eight launch shapes each at batches 320..768 of three layers.
+    const double fixed = p.H == 1 ? 0.15 * a.d_in * p.R : 2.0 * a.K;
+    const double per_row = (double)a.K * (p.H == 1 && p.R == 2 ? 1.3 : 1.0);
+    auto shape_cost = [&](int c) {
+        const long long groups = (n_slots + p.NW * c - 1) / (p.NW * c);
+        const long long per_xcd = ((groups + 7) / 8) * p.n_btiles;
+        return (double)((per_xcd + 31) / 32) * (fixed + c * per_row) * (p.H == 1 && c >= 6 ? 1.1 : 1.0);
+    };
     int npw = t && t->neurons_per_wave ? t->neurons_per_wave : 0;
     if (npw == 0) {
         static const int cand[6] = {1, 2, 3, 4, 6, 8};
-        long long best = -1;
+        double best = -1.0;
         for (int ci = 0; ci < 6; ++ci) {
             const int c = cand[ci];
             if (c > rowlane_max_npw(p.R)) break;
-            const long long wgs = (long long)((n_slots + p.NW * c - 1) / (p.NW * c)) * p.n_btiles;
-            const long long cost = ((wgs + 255) / 256) * (2 + c);
+            const double cost = shape_cost(c);
             if (best < 0 || cost < best) { best = cost; npw = c; }
         }
     }
     if (npw != 1 && npw != 2 && npw != 3 && npw != 4 && npw != 6 && npw != 8) return p;
     if (npw > rowlane_max_npw(p.R)) return p;
     p.NPW = npw;
+    p.cost = shape_cost(npw);
     p.KPRE = rowlane_kpre(npw);
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
     // the result tile sits behind the activation tile when both fit (no barrier between the last term and the
@@ -348,9 +360,8 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
 }
 
 // Two batch rows per lane (128-row tiles) halve the LDS reads per multiply-add (one 8-byte read feeds two rows), but also
-// halve the number of workgroups: taken when nothing is forced, the rows are long enough for the term loop to matter and
-// the launch still fills every compute unit.  Measured on 768x3072, 3072x768 and 1024x4096 layers, batches 512..4096:
-// 7..33 % faster; slower at fan-in 8 and whenever fewer than 256 workgroups remain.
+// halve the number of workgroups and double the staging of each: taken when nothing is forced, the rows are long enough for
+// the term loop to matter (slower at fan-in 8) and the cost of its best launch shape is below that of the best 64-row shape.
 static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     const RowlanePlan one = plan_rowlane_with(a, t);
     const bool forced = t && (t->rows_per_lane || t->term_slices);
@@ -360,9 +371,7 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     two.rows_per_lane = 2;
     two.term_slices = 1;
     const RowlanePlan p2 = plan_rowlane_with(a, &two);
-    // ... with at least three stored rows per wavefront: a launch that only reaches 256 workgroups by giving every wavefront a
-    // single row has too little arithmetic per staged tile
-    if (p2.ok && p2.NPW >= 3 && a.B >= 256 && (long long)p2.n_groups * p2.n_btiles >= 256) return p2;
+    if (p2.ok && p2.cost < one.cost) return p2;
     return one;
 }
 
@@ -422,13 +431,15 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     // kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its
     // share of the stored terms.
     // Fits of timings of 512- to 4096-wide layers at 80-90 % sparsity, the cold read of W_c / idx left out of both;
-    // above 64 rows the batched kernel always wins.
+    // above 512 rows the batched kernel always wins.
     bool batched = B > 16;
-    if (B > 1 && B <= 64 && d_in % 16 == 0) {
+    if (B > 1 && B <= 512 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
         const double small_us = klane_estimate_us(B, d_in, n_active, K);
-        // (few stored rows: too few workgroups share the staging)
-        const double batched_us = 4.3 + 0.0014 * d_in + 1.5e-6 * (double)n_active * K + (n_active <= 1024 ? 0.5 : 0.0);
+        // up to 64 rows: one or two row tiles (few stored rows: too few workgroups share the staging); above: a fit of
+        // 96 to 512 rows, where only layers with a few dozen terms per row still favour the small-batch kernel
+        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + 1.5e-6 * (double)n_active * K + (n_active <= 1024 ? 0.5 : 0.0)
+                                          : 7.7 + 0.0012 * d_in + 0.008 * B + 8e-8 * (double)B * n_active * K;
         batched = batched_us < small_us;
     }
     if (batched && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);

@@ -33,6 +33,7 @@ struct FwdArgs {
 struct RowlanePlan {
     int R, H, NW, NPW, KPRE, C, n_chunks, n_btiles, n_groups;
     size_t lds;
+    double cost;  // the planner's estimate for this shape (arbitrary units), to compare shapes
     int out_off;  // word offset of the result tile in LDS (0: it reuses the activation tile after a barrier)
     bool fast;   // x rows allow aligned 4-element loads and d_in is a multiple of 16
     bool ok;
