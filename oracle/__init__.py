@@ -106,6 +106,23 @@ def fwd(x: np.ndarray, W_c: np.ndarray, idx: np.ndarray, active, bias, d_out: in
     return (y, scale) if want_scale else y
 
 
+def csr_fwd(x: np.ndarray, values: np.ndarray, col_idx: np.ndarray, row_ptr: np.ndarray, bias, want_scale: bool = False):
+    """The same weights in compressed sparse row form (the unstructured comparison of Sec. 4.4 / Fig. 4), fp32."""
+    x = _c(x, np.float32)
+    values = _c(values, np.float32)
+    col_idx = _c(col_idx, np.int32)
+    row_ptr = _c(row_ptr, np.int32)
+    bias = _c(bias, np.float32)
+    B, d_in = x.shape
+    d_out = row_ptr.shape[0] - 1
+    assert row_ptr[0] == 0 and row_ptr[-1] == values.shape[0] == col_idx.shape[0]
+    assert col_idx.size == 0 or (col_idx.min() >= 0 and col_idx.max() < d_in)
+    y = np.empty((B, d_out), dtype=np.float32)
+    scale = np.empty((B, d_out), dtype=np.float64) if want_scale else None
+    _load().oracle_csr_fwd_f32(_p(x), B, d_in, _p(values), _p(col_idx), _p(row_ptr), _p(bias), d_out, _p(y), _p(scale))
+    return (y, scale) if want_scale else y
+
+
 def dense_masked_fwd(x: np.ndarray, W: np.ndarray, mask: np.ndarray, bias) -> np.ndarray:
     x = _c(x, np.float32)
     W = _c(W, np.float32)

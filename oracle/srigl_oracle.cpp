@@ -177,6 +177,26 @@ void oracle_dense_masked_fwd_f32(const float* x, int B, int d_in, const float* W
         }
 }
 
+// The unstructured comparison of Sec. 4.4 / Fig. 4 (the same weights in compressed sparse row form): row r holds the
+// entries values[row_ptr[r] .. row_ptr[r+1]) at columns col_idx[...]; y[b][r] = bias[r] + sum over the row's entries of
+// value * x[b][column].  A row without entries outputs its bias.  fp32 storage, fp64 accumulation; scale as in fwd.
+void oracle_csr_fwd_f32(const float* x, int B, int d_in, const float* values, const int32_t* col_idx, const int32_t* row_ptr,
+                        const float* bias, int d_out, float* y, double* scale) {
+    (void)d_in;
+    for (int b = 0; b < B; ++b)
+        for (int r = 0; r < d_out; ++r) {
+            double acc = 0.0, mag = 0.0;
+            for (int t = row_ptr[r]; t < row_ptr[r + 1]; ++t) {
+                const double term = (double)values[t] * (double)x[(size_t)b * d_in + col_idx[t]];
+                acc += term;
+                mag += std::fabs(term);
+            }
+            const double bv = bias ? (double)bias[r] : 0.0;
+            y[(size_t)b * d_out + r] = (float)(acc + bv);
+            if (scale) scale[(size_t)b * d_out + r] = mag + std::fabs(bv);
+        }
+}
+
 // Structured-only representation (Sec. 4.4, Fig. 4 and App. H: the same layer "accelerated using only the
 // ablated neurons without exploiting the fine-grained sparsity"): the stored neurons keep dense rows.
 // densify: Wd[s][j] = W_c[s][t] where idx[s][t] == j, zero elsewhere (elements copied bit for bit).

@@ -469,3 +469,42 @@ def test_narrow_idx_is_the_same_numbers_in_two_bytes():
     with pytest.raises(ValueError):
         oracle.narrow_idx(np.array([-1], dtype=np.int32), 100)
     assert oracle.narrow_idx(np.empty((0, 4), np.int32), 8).shape == (0, 4)
+
+
+def _csr_of(W, mask):
+    """Compressed sparse row form of the kept weights, built here with plain loops (test-side helper)."""
+    vals, cols, ptr = [], [], [0]
+    for r in range(mask.shape[0]):
+        for j in range(mask.shape[1]):
+            if mask[r, j]:
+                vals.append(W[r, j])
+                cols.append(j)
+        ptr.append(len(vals))
+    return np.array(vals, np.float32), np.array(cols, np.int32), np.array(ptr, np.int32)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_csr_forward_equals_the_masked_matmul_and_the_library_product(seed):
+    """The unstructured comparison (Sec. 4.4 / Fig. 4) computes the same function as the masked dense layer: against the
+    all-terms definition, against scipy's own CSR product in fp64, and - on a constant fan-in mask - against Alg. 1 on the
+    condensed form of the same weights.  Rows without entries output their bias."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(40 + seed)
+    d_in, d_out, B = 37, 23, 5
+    W = rng.normal(size=(d_out, d_in)).astype(np.float32)
+    mask = (rng.random((d_out, d_in)) < 0.2).astype(np.uint8)     # unstructured: row lengths differ
+    mask[3] = 0
+    mask[d_out - 1] = 0
+    x = rng.normal(size=(B, d_in)).astype(np.float32)
+    bias = rng.normal(size=d_out).astype(np.float32)
+    vals, cols, ptr = _csr_of(W, mask)
+    y = oracle.csr_fwd(x, vals, cols, ptr, bias)
+    assert np.array_equal(y, oracle.dense_masked_fwd(x, W, mask, bias))
+    lib = sp.csr_matrix((vals.astype(np.float64), cols, ptr), shape=(d_out, d_in))
+    assert np.allclose(y, (lib @ x.astype(np.float64).T).T + bias, rtol=1e-6, atol=1e-6)
+    assert np.array_equal(y[:, 3], np.broadcast_to(bias[3], (B,)))
+    # constant fan-in: the condensed form of the same weights gives the same numbers
+    L = si.make_layer(48, 20, 7, 4, ablate_frac=0.2, seed=seed)
+    W_c, idx, active = oracle.condense(L.W, L.mask, L.K)
+    v2, c2, p2 = _csr_of(L.W, L.mask)
+    assert np.array_equal(oracle.csr_fwd(L.x, v2, c2, p2, L.bias), oracle.fwd(L.x, W_c, idx, active, L.bias, L.d_out))
