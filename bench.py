@@ -157,6 +157,16 @@ def sweep(args):
                 csr = time_eager(lambda i: torch.sparse.mm(Wcsr, xT), min(steps, 50), 3) * 1e3
             except Exception as e:                       # noqa: BLE001  (context only: report and go on)
                 log("CSR product unavailable for %s: %s" % (label, str(e)[:200]))
+        # the same comparison through this library's own CSR kernel (built like the small-batch condensed kernel), in a graph
+        own_csr = None
+        if not bf16 and B <= 65535:
+            rows_h, cols_h = np.nonzero(L.mask)
+            ptr_h = np.zeros(L.d_out + 1, np.int32)
+            np.cumsum(np.bincount(rows_h, minlength=L.d_out), out=ptr_h[1:])
+            vals_d, cols_d, ptr_d = dev(L.W[rows_h, cols_h].astype(np.float32)), dev(cols_h.astype(np.int32)), dev(ptr_h)
+            yc = torch.empty((B, L.d_out), device="cuda")
+            own_csr = time_graph(lambda i: B_.srigl_csr_linear_fwd(xs, B, L.d_in, vals_d, cols_d, ptr_d, layer.bias, L.d_out, yc),
+                                 min(steps, 100), 5) * 1e3
         sel, est_c, est_s = B_.srigl_choose_representation(B, L.d_in, layer.n_active, L.K, L.d_out, B_.BF16 if bf16 else B_.F32)
         flops = 2.0 * B * layer.n_active * L.K
         print(json.dumps({"point": label, "d_in": L.d_in, "d_out": L.d_out, "K": L.K, "n_active": layer.n_active, "B": B,
@@ -166,6 +176,7 @@ def sweep(args):
                           "algorithmic_bytes": nbytes, "torch_dense_matmul_us": round(dense, 2),
                           "structured_only_us_warm": None if structured is None else round(structured, 2),
                           "library_csr_spmm_us": None if csr is None else round(csr, 2),
+                          "own_csr_us_warm": None if own_csr is None else round(own_csr, 2),
                           "selected": "structured" if sel == B_.REPR_STRUCTURED else "condensed",
                           "estimate_us": {"condensed": round(est_c, 1), "structured": round(est_s, 1)}}), flush=True)
         del sets, layer

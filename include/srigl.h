@@ -195,6 +195,19 @@ srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype
                                               const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
                                               const srigl_fwd_tuning* tuning, void* stream);
 
+/* ---- unstructured comparison: the same weights in compressed sparse row form ------------------------------
+ * Sec. 4.4 / Fig. 4 and App. H time the condensed layer against the layer's kept weights held as an unstructured sparse
+ * matrix.  srigl_csr_linear_fwd is that comparison on this GPU, built like the small-batch condensed kernel:
+ * y[b][r] = act(bias[r] + sum over t in [row_ptr[r], row_ptr[r+1]) of values[t] * x[b][col_idx[t]]), r in [0, d_out).
+ * x[B][d_in] and values[nnz] fp32 (x_dtype == w_dtype == SRIGL_F32; BF16 is SRIGL_ERR_UNSUPPORTED), col_idx[nnz] int32 in [0, d_in) (not checked),
+ * row_ptr[d_out + 1] int32 ascending with row_ptr[0] == 0 and row_ptr[d_out] == nnz (not checked; nnz is passed so that
+ * the launch shape can follow the mean row length), bias[d_out] fp32 or NULL, y[B][d_out] fp32, fully overwritten
+ * (a row without entries outputs act(bias)).  Device pointers, caller's stream, no allocation.
+ * SRIGL_ERR_UNSUPPORTED if a row of x does not fit the LDS (d_in > 40960) or B > 65535. */
+srigl_status srigl_csr_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* values,
+                                  srigl_dtype w_dtype, const int32_t* col_idx, const int32_t* row_ptr, int64_t nnz,
+                                  const float* bias, int32_t d_out, float* y, srigl_activation act, void* stream);
+
 /* ---- one SRigL connectivity update of a layer ------------------------------------------------------------
  * Sec. 3.1, steps 1-7 (with App. G's minimum of one salient weight).  W, grad: fp32 [d_out][d_in]; mask: bytes, every
  * row holds 0 (ablated) or k kept weights; K_upd: the number of weights pruned and grown in this update (step 2, chosen

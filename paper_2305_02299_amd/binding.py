@@ -31,7 +31,7 @@ EXPORTS = (
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
     "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
-    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16",
+    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd",
 )
 
 
@@ -89,6 +89,8 @@ def _load() -> ctypes.CDLL:
     lib.srigl_condensed_linear_fwd_idx16.restype = ctypes.c_int
     lib.srigl_condensed_linear_fwd_idx16.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32,
                                                      vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
+    lib.srigl_csr_linear_fwd.restype = ctypes.c_int
+    lib.srigl_csr_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, i32, vp, ctypes.c_int, vp]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -200,6 +202,14 @@ def srigl_narrow_idx(idx, d_in, idx16):
     """idx int32 (any shape, contiguous) -> idx16, a 16-bit container of the same number of elements."""
     assert idx.dtype == torch.int32 and idx16.dtype in (torch.int16, torch.uint16) and idx16.numel() == idx.numel()
     _check(lib.srigl_narrow_idx(_ptr(idx), int(idx.numel()), int(d_in), _ptr(idx16), _stream()), "srigl_narrow_idx")
+
+
+def srigl_csr_linear_fwd(x, B, d_in, values, col_idx, row_ptr, bias, d_out, y, act=None):
+    """The layer's kept weights in compressed sparse row form (the unstructured comparison)."""
+    nnz = int(values.numel())
+    _check(lib.srigl_csr_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(values), _dtype_code(values), _ptr(col_idx),
+                                    _ptr(row_ptr), nnz, _ptr(bias), int(d_out), _ptr(y), int(act or ACT_NONE), _stream()),
+           "srigl_csr_linear_fwd")
 
 
 def srigl_densify(W_c, idx, n_active, K, d_in, Wd):

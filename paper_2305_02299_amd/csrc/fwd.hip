@@ -431,14 +431,16 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     // kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its
     // share of the stored terms.
     // Fits of timings of 512- to 4096-wide layers at 80-90 % sparsity, the cold read of W_c / idx left out of both;
-    // above 512 rows the batched kernel always wins.
+    // above 2048 rows the batched kernel always wins.
     bool batched = B > 16;
-    if (B > 1 && B <= 512 && d_in % 16 == 0) {
+    if (B > 1 && B <= 2048 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
         const double small_us = klane_estimate_us(B, d_in, n_active, K);
         // up to 64 rows: one or two row tiles (few stored rows: too few workgroups share the staging); above: a fit of
         // 96 to 512 rows, where only layers with a few dozen terms per row still favour the small-batch kernel
-        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + 1.5e-6 * (double)n_active * K + (n_active <= 1024 ? 0.5 : 0.0)
+        // (16-row tiles of inputs wider than 2048: three times the cost per stored term)
+        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + (d_in > 2048 ? 4.5e-6 : 1.5e-6) * (double)n_active * K +
+                                                (n_active <= 1024 ? 0.5 : 0.0)
                                           : 7.7 + 0.0012 * d_in + 0.008 * B + 8e-8 * (double)B * n_active * K;
         batched = batched_us < small_us;
     }
