@@ -446,7 +446,7 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     }
     if (batched && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
     srigl_status s = launch_fwd_klane(a, nullptr, st);
-    if (s == SRIGL_ERR_UNSUPPORTED && B > 16 && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
+    if (s == SRIGL_ERR_UNSUPPORTED && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
     if (s == SRIGL_ERR_UNSUPPORTED) s = launch_fwd_generic(a, st);
     return s;
 }

@@ -288,3 +288,13 @@ def test_non_finite_activation_only_reaches_its_own_terms(algo):
     fin = np.isfinite(y_ref)
     assert np.array_equal(np.isfinite(y), fin)
     assert np.max(np.abs(y[fin] - y_ref[fin]) / np.maximum(np.maximum(np.abs(y_ref[fin]), S[fin]), 1e-30)) < TOL_F32
+
+
+@pytest.mark.parametrize("B", [1, 3, 40])
+def test_input_wider_than_the_lds_row_of_the_small_batch_kernel(B):
+    """d_in = 49152: one fp32 row of x (192 KB) does not fit the LDS, so the small-batch kernel cannot run and the library's own
+    choice must fall through to the batched kernel (chunks of columns), not to the one-thread-per-output fallback only."""
+    L = si.make_layer(49152, 48, 64, B, ablate_frac=0.1, seed=11)
+    assert check_layer(L, None, None) is not None
+    assert check_layer(L, B_.FWD_KLANE, None, unsupported_ok=True) is None       # the small-batch kernel refuses
+    assert check_layer(L, B_.FWD_ROWLANE, None, unsupported_ok=True) is not None  # the batched kernel runs it
