@@ -31,8 +31,11 @@ struct SelState {
 // device-wide fence is needed (on this multi-die GPU such a fence costs about 0.1 ms per launch).
 // slot[sel][p & 1] = the walk's state before pass p (written by workgroup 0 of the launch of pass p, read by the next launch);
 // fin[sel] = the finished selection: select key >= fin.prefix.
+// Copies of every layer-wide histogram: a pass ends with one atomic per non-empty digit and workgroup, and 2048 workgroups
+// adding to the same 256 counters took longer than reading a 2.4-million-element layer (43 us of a 167 us update).
+constexpr int kHistCopies = 8;
 struct UpdateScratch {
-    unsigned int hist[3][8][256];
+    unsigned int hist[3][8][kHistCopies][256];   // workgroup w adds into copy w % kHistCopies
     SelState slot[3][2];
     SelState fin[3];
     long long k_new, n_remaining, n_ablated_now, n_pruned;
@@ -45,7 +48,7 @@ __host__ __device__ constexpr int pass_shift(int p) { return p < 7 ? 55 - 8 * p 
 __host__ __device__ constexpr int pass_bits(int p) { return p < 7 ? 8 : 7; }
 __host__ __device__ constexpr int bits_done(int p) { return p < 8 ? 1 + 8 * p : 64; }
 constexpr int kCompactPass = 2;      // the pass that also writes the candidate lists
-constexpr int kBlockList = 512;      // candidate keys a workgroup collects in LDS before it appends them
+constexpr int kBlockList = 1024;     // candidate keys a workgroup collects in LDS before it appends them
 
 __device__ __forceinline__ unsigned int mag_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 // larger key = smaller magnitude, then lower position
@@ -59,8 +62,9 @@ __device__ __forceinline__ unsigned long long key_large_first(unsigned int mag, 
 
 __global__ __launch_bounds__(256) void k_update_init(UpdateScratch* s, long long K_upd) {
     const int t = threadIdx.x;
-    for (int i = t; i < 3 * 8 * 256; i += 256) (&s->hist[0][0][0])[i] = 0;
-    if (t < 3) {
+    const int n = 3 * 8 * kHistCopies * 256;
+    for (int i = blockIdx.x * 256 + t; i < n; i += gridDim.x * 256) (&s->hist[0][0][0][0])[i] = 0;
+    if (blockIdx.x == 0 && t < 3) {
         SelState z;
         z.prefix = 0; z.k_rem = (unsigned long long)K_upd; z.total = 0; z.done = 0; z.pad = 0;
         s->slot[t][0] = z;
@@ -103,23 +107,16 @@ __device__ __forceinline__ void pick_from(const unsigned long long (&v)[4], unsi
     above = __shfl(above, src, 64);
     in_bin = __shfl(in_bin, src, 64);
 }
-__device__ __forceinline__ void pick_byte(const unsigned int* h, unsigned long long want, int lane, unsigned long long& digit,
-                                          unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
-    unsigned long long v[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = h[4 * lane + j];
-    pick_from(v, want, lane, digit, above, in_bin, total);
-}
-// the same over the sum of COPIES sub-histograms; copy c keeps the count of digit d at index (d + kCopyTurn * c) mod 256, so that
-// equal digits of different copies sit in different LDS banks
+// Over the sum of COPIES sub-histograms (lane l reads bins 4l .. 4l + 3 of each); copy c keeps the count of digit d at index (d + TURN * c) mod 256 (in LDS a
+// turn of kCopyTurn puts equal digits of different copies in different banks)
 constexpr int kCopyTurn = 16;
-template <int COPIES>
+template <int COPIES, int TURN>
 __device__ __forceinline__ void pick_byte_copies(const unsigned int (*h)[256], unsigned long long want, int lane, unsigned long long& digit,
                                                  unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
     unsigned long long v[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < COPIES; ++c) {
-        const uint4 q = *reinterpret_cast<const uint4*>(&h[c][(4 * lane + kCopyTurn * c) & 255]);
+        const uint4 q = *reinterpret_cast<const uint4*>(&h[c][(4 * lane + TURN * c) & 255]);
         v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
     }
     pick_from(v, want, lane, digit, above, in_bin, total);
@@ -127,11 +124,11 @@ __device__ __forceinline__ void pick_byte_copies(const unsigned int (*h)[256], u
 
 // The state of a layer-wide walk before pass `pass` (1..8), from the state before pass - 1 and the histogram of pass - 1.
 // Called by one whole wavefront; the result is the same on every lane.
-__device__ SelState advance(const SelState& before, const unsigned int* __restrict__ hist_prev, int pass, int lane) {
+__device__ SelState advance(const SelState& before, const unsigned int (*hist_prev)[256], int pass, int lane) {
     SelState st = before;
     if (st.done) return st;
     unsigned long long digit, above, in_bin, total;
-    pick_byte(hist_prev, st.k_rem == 0 ? 1 : st.k_rem, lane, digit, above, in_bin, total);
+    pick_byte_copies<kHistCopies, 0>(hist_prev, st.k_rem == 0 ? 1 : st.k_rem, lane, digit, above, in_bin, total);
     if (pass == 1) {
         st.total = total;
         if (st.k_rem == 0 || total < st.k_rem) {
@@ -273,8 +270,8 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
     unsigned int a = 0, b = 0;
 #pragma unroll
     for (int c = 0; c < kCopies; ++c) { a += h[0][c][t]; b += h[1][c][t]; }
-    if (a) atomicAdd(&s->hist[selA][pass][t], a);
-    if (PAIR && b) atomicAdd(&s->hist[1][pass][t], b);
+    if (a) atomicAdd(&s->hist[selA][pass][blockIdx.x % kHistCopies][t], a);
+    if (PAIR && b) atomicAdd(&s->hist[1][pass][blockIdx.x % kHistCopies][t], b);
     if (COMPACT) {
         if (t < 2) {
             const unsigned int n = keep_n[t];
@@ -410,7 +407,7 @@ __device__ unsigned long long row_select(unsigned long long want, KeyOf key_of, 
         }
         __syncthreads();
         unsigned long long digit, above, in_bin, total;
-        pick_byte_copies<kRowCopies>(h[cur], want, lane, digit, above, in_bin, total);
+        pick_byte_copies<kRowCopies, kCopyTurn>(h[cur], want, lane, digit, above, in_bin, total);
         prefix = (prefix << pass_bits(pass)) | digit;
         want -= above;
         // every key of this digit is wanted: the walk is over, the threshold is the smallest key with this prefix
@@ -548,15 +545,14 @@ __global__ void k_update_report(const UpdateScratch* __restrict__ s, long long K
 template <bool PAIR>
 static void layer_select(const float* W, const uint8_t* mask, const float* grad, const int* remains, unsigned int N, int d_in,
                          UpdateScratch* s, unsigned long long* candA, unsigned long long* candB, unsigned long long cap, hipStream_t st) {
-    unsigned int blocks = (N + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
     const bool vec = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
                      reinterpret_cast<uintptr_t>(mask) % 4 == 0;
-    if (vec) {   // a thread takes 4 elements per step
-        blocks = (N / 4 + 255) / 256;
-        if (blocks > 2048) blocks = 2048;
-        if (blocks == 0) blocks = 1;
-    }
+    // a thread takes 1 or 4 elements per step and at least 8 steps (every workgroup ends with up to 512 atomics), at most
+    // four workgroups per compute unit
+    const unsigned int per_step = vec ? 1024u : 256u;
+    unsigned int blocks = (N / 8 + per_step - 1) / per_step;
+    if (blocks > 1024) blocks = 1024;
+    if (blocks == 0) blocks = 1;
 #define SRIGL_HIST(COMPACT, VEC)                                                                                                   \
     hipLaunchKernelGGL((k_layer_hist<PAIR, COMPACT, VEC>), dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s, \
                        candA, candB, cap)
@@ -609,7 +605,7 @@ srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float*
     const unsigned long long cap = cand_capacity(d_out, d_in);
     unsigned long long* candA = reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(workspace) + update_head_bytes(d_out));
     unsigned long long* candB = candA + cap;
-    hipLaunchKernelGGL(k_update_init, dim3(1), dim3(256), 0, st, s, (long long)K_upd);
+    hipLaunchKernelGGL(k_update_init, dim3(48), dim3(256), 0, st, s, (long long)K_upd);
     if (N > 0) {
         layer_select<true>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
         const bool vec_in = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
