@@ -148,6 +148,19 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
                                              const uint16_t* seg, srigl_fwd_algo algo,
                                              const srigl_fwd_tuning* tuning, void* stream);
 
+/* What the library's own choice (SRIGL_FWD_AUTO) would launch for a forward call of these sizes: the kernel and its
+ * launch shape.  Host arithmetic only (no GPU call, no device pointers: has_active / has_seg say whether the call would
+ * pass an active list / a seg table; arrays are taken to be 16-byte aligned).  All fields are 0 when no forward kernel
+ * would run (B, d_out, n_active or K zero).  For tests of the planner and for users who want to know. */
+typedef struct {
+    int32_t algo;             /* srigl_fwd_algo: SRIGL_FWD_GENERIC, _KLANE or _ROWLANE                       */
+    int32_t rows_per_lane, term_slices, waves, neurons_per_wave, chunk_cols;   /* ROWLANE, else 0          */
+    int32_t lanes_per_neuron, rows_per_block;                                 /* KLANE, else 0            */
+    int64_t workgroups;       /* workgroups that do work                                                    */
+} srigl_fwd_plan;
+srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
+                                  int32_t has_active, int32_t has_seg, srigl_fwd_plan* plan);
+
 /* ---- MLP block: activation in the epilogue, width reduction -------------------------------------------
  * Sec. 3.1 (neuron ablation reduces the width of a layer) and App. H (the timed layer is one linear of a ViT MLP
  * block: linear, GELU, linear).  srigl_condensed_linear_fwd_act is the forward call with an activation applied to

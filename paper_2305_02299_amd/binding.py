@@ -31,7 +31,7 @@ EXPORTS = (
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
     "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
-    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd",
+    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query",
 )
 
 
@@ -45,6 +45,12 @@ class FwdTuning(ctypes.Structure):
     _fields_ = [("rows_per_lane", ctypes.c_int32), ("waves", ctypes.c_int32), ("neurons_per_wave", ctypes.c_int32),
                 ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32), ("rows_per_block", ctypes.c_int32),
                 ("term_slices", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
+
+
+class FwdPlan(ctypes.Structure):
+    _fields_ = [("algo", ctypes.c_int32), ("rows_per_lane", ctypes.c_int32), ("term_slices", ctypes.c_int32), ("waves", ctypes.c_int32),
+                ("neurons_per_wave", ctypes.c_int32), ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32),
+                ("rows_per_block", ctypes.c_int32), ("workgroups", ctypes.c_int64)]
 
 
 def _load() -> ctypes.CDLL:
@@ -91,6 +97,8 @@ def _load() -> ctypes.CDLL:
                                                      vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
     lib.srigl_csr_linear_fwd.restype = ctypes.c_int
     lib.srigl_csr_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, i32, vp, ctypes.c_int, vp]
+    lib.srigl_fwd_plan_query.restype = ctypes.c_int
+    lib.srigl_fwd_plan_query.argtypes = [i32, i32, i32, i32, i32, ctypes.c_int, i32, i32, ctypes.POINTER(FwdPlan)]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -210,6 +218,14 @@ def srigl_csr_linear_fwd(x, B, d_in, values, col_idx, row_ptr, bias, d_out, y, a
     _check(lib.srigl_csr_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(values), _dtype_code(values), _ptr(col_idx),
                                     _ptr(row_ptr), nnz, _ptr(bias), int(d_out), _ptr(y), int(act or ACT_NONE), _stream()),
            "srigl_csr_linear_fwd")
+
+
+def srigl_fwd_plan_query(B, d_in, n_active, K, d_out, dtype_code=F32, has_active=False, has_seg=True) -> dict:
+    """The kernel and launch shape the library's own choice takes for these sizes (host arithmetic, no GPU call)."""
+    p = FwdPlan()
+    _check(lib.srigl_fwd_plan_query(int(B), int(d_in), int(n_active), int(K), int(d_out), int(dtype_code), int(bool(has_active)),
+                                    int(bool(has_seg)), ctypes.byref(p)), "srigl_fwd_plan_query")
+    return {name: int(getattr(p, name)) for name, _ in FwdPlan._fields_}
 
 
 def srigl_densify(W_c, idx, n_active, K, d_in, Wd):

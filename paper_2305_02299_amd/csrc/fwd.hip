@@ -226,24 +226,41 @@ static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg,
     return hip_ok(hipGetLastError());
 }
 
-srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st) {
+// Launch shape of the small-batch kernel, decided on the host.
+struct KlanePlan { int L, RB, rows_per_wg; long long workgroups; bool ok; };
+static KlanePlan plan_klane(const FwdArgs& a, const srigl_fwd_tuning* t) {
+    KlanePlan p{};
+    p.ok = false;
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
-    if (a.B == 0 || n_slots == 0) return SRIGL_OK;
     // lanes per stored row: enough that a lane has at most ~4 terms, at least 4, at most 64
     int L = t && t->lanes_per_neuron ? t->lanes_per_neuron : 0;
     if (L == 0) { L = 4; while (L < 64 && L * kKlaneTerms < a.K) L <<= 1; }
-    if (L < 1 || L > 64 || (L & (L - 1)) != 0) return SRIGL_ERR_UNSUPPORTED;
+    if (L < 1 || L > 64 || (L & (L - 1)) != 0) return p;
     int RB = t && t->rows_per_block ? t->rows_per_block : 0;
     // measured: one row per workgroup up to batch 4 and for wide inputs (staging two rows of x then costs more
     // than the second pass over W_c/idx saves); two rows beat four and eight elsewhere
     if (RB == 0) RB = (a.B > 4 && a.d_in <= 1024) ? 2 : 1;
     while (RB > 1 && (size_t)RB * a.d_in * sizeof(float) > kLdsMax / 2) RB >>= 1;
-    if (RB != 1 && RB != 2 && RB != 4 && RB != 8) return SRIGL_ERR_UNSUPPORTED;
-    const int log2L = ilog2_floor(L);
+    if (RB != 1 && RB != 2 && RB != 4 && RB != 8) return p;
+    if ((size_t)RB * a.d_in * sizeof(float) > kLdsMax) return p;          // a row of x must fit the LDS
+    if ((a.B + RB - 1) / RB > 65535) return p;                            // the batch is the grid's second dimension
     const int groups = 256 / L;
     // stored rows per workgroup: one pass of all groups, more when that still leaves > 8 workgroups per CU
     int rows_per_wg = groups;
     while ((long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB) > 256 * 8) rows_per_wg += groups;
+    p.L = L; p.RB = RB; p.rows_per_wg = rows_per_wg;
+    p.workgroups = (long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB);
+    p.ok = true;
+    return p;
+}
+
+srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st) {
+    const int n_slots = a.active ? a.n_active + 1 : a.n_active;
+    if (a.B == 0 || n_slots == 0) return SRIGL_OK;
+    const KlanePlan kp = plan_klane(a, t);
+    if (!kp.ok) return SRIGL_ERR_UNSUPPORTED;
+    const int RB = kp.RB, rows_per_wg = kp.rows_per_wg;
+    const int log2L = ilog2_floor(kp.L);
 #define SRIGL_KLANE(RBV)                                                                               \
     return a.x_bf16 ? (a.idx_u16 ? launch_klane_t<RBV, uint16_t, uint16_t>(a, log2L, rows_per_wg, st)                  \
                                  : launch_klane_t<RBV, uint16_t, int32_t>(a, log2L, rows_per_wg, st))                  \
@@ -386,6 +403,31 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
     return a.x_bf16 ? launch_rowlane_bf16(a, p, st) : launch_rowlane_f32(a, p, st);
 }
 
+// The library's own choice of kernel.  Small batches: the lanes-along-K kernel costs a fixed part plus a part per term slot
+// (K rounded up to the lanes it spreads a row over; dearer with one batch row per workgroup, the wide-input setting); the
+// batched kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its
+// share of the stored terms.  Fits of timings of 512- to 4096-wide layers at 80-99 % sparsity, the cold read of W_c / idx
+// left out of both; a single row always takes the small-batch kernel, above 2048 rows the batched kernel always wins.
+srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
+    const int B = a.B, d_in = a.d_in, n_active = a.n_active, K = a.K;
+    bool batched = B > 16;
+    if (B > 1 && B <= 2048 && d_in % 16 == 0) {
+        static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
+        const double small_us = klane_estimate_us(B, d_in, n_active, K);
+        // up to 64 rows: one or two row tiles (few stored rows: too few workgroups share the staging); above: a fit of
+        // 96 to 512 rows, where only layers with a few dozen terms per row still favour the small-batch kernel
+        // (16-row tiles of inputs wider than 2048: three times the cost per stored term)
+        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + (d_in > 2048 ? 4.5e-6 : 1.5e-6) * (double)n_active * K +
+                                                (n_active <= 1024 ? 0.5 : 0.0)
+                                          : 7.7 + 0.0012 * d_in + 0.008 * B + 8e-8 * (double)B * n_active * K;
+        batched = batched_us < small_us;
+    }
+    const bool can_batch = rowlane_supported(a, nullptr);
+    if (batched && can_batch) return SRIGL_FWD_ROWLANE;
+    if (plan_klane(a, nullptr).ok) return SRIGL_FWD_KLANE;
+    return can_batch ? SRIGL_FWD_ROWLANE : SRIGL_FWD_GENERIC;
+}
+
 }  // namespace srigl
 
 using namespace srigl;
@@ -426,29 +468,11 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
         case SRIGL_FWD_AUTO: break;
         default: return SRIGL_ERR_INVALID_ARG;
     }
-    // Small batches: the lanes-along-K kernel costs a fixed part plus a part per term slot (K rounded up to the
-    // lanes it spreads a row over; dearer with one batch row per workgroup, the wide-input setting); the batched
-    // kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its
-    // share of the stored terms.
-    // Fits of timings of 512- to 4096-wide layers at 80-90 % sparsity, the cold read of W_c / idx left out of both;
-    // above 2048 rows the batched kernel always wins.
-    bool batched = B > 16;
-    if (B > 1 && B <= 2048 && d_in % 16 == 0) {
-        static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
-        const double small_us = klane_estimate_us(B, d_in, n_active, K);
-        // up to 64 rows: one or two row tiles (few stored rows: too few workgroups share the staging); above: a fit of
-        // 96 to 512 rows, where only layers with a few dozen terms per row still favour the small-batch kernel
-        // (16-row tiles of inputs wider than 2048: three times the cost per stored term)
-        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + (d_in > 2048 ? 4.5e-6 : 1.5e-6) * (double)n_active * K +
-                                                (n_active <= 1024 ? 0.5 : 0.0)
-                                          : 7.7 + 0.0012 * d_in + 0.008 * B + 8e-8 * (double)B * n_active * K;
-        batched = batched_us < small_us;
+    switch (choose_fwd_algo(a)) {
+        case SRIGL_FWD_ROWLANE: return launch_fwd_rowlane(a, nullptr, st);
+        case SRIGL_FWD_KLANE: return launch_fwd_klane(a, nullptr, st);
+        default: return launch_fwd_generic(a, st);
     }
-    if (batched && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
-    srigl_status s = launch_fwd_klane(a, nullptr, st);
-    if (s == SRIGL_ERR_UNSUPPORTED && rowlane_supported(a, nullptr)) return launch_fwd_rowlane(a, nullptr, st);
-    if (s == SRIGL_ERR_UNSUPPORTED) s = launch_fwd_generic(a, st);
-    return s;
 }
 
 srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
@@ -509,6 +533,36 @@ srigl_status srigl_narrow_idx(const int32_t* idx, int64_t n, int32_t d_in, uint1
         hipLaunchKernelGGL(k_narrow_idx1, dim3((unsigned)blocks), dim3(256), 0, st, idx, done, (long long)n, hi, idx16);
     }
     return hip_ok(hipGetLastError());
+}
+
+srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
+                                  int32_t has_active, int32_t has_seg, srigl_fwd_plan* plan) {
+    if (plan == nullptr || B < 0 || d_in < 0 || n_active < 0 || K < 0 || d_out < 0 || K > d_in || n_active > d_out)
+        return SRIGL_ERR_INVALID_ARG;
+    if (dtype != SRIGL_F32 && dtype != SRIGL_BF16) return SRIGL_ERR_INVALID_ARG;
+    *plan = srigl_fwd_plan{};
+    if (B == 0 || d_out == 0 || n_active == 0 || K == 0) return SRIGL_OK;   // nothing to gather: no forward kernel runs
+    // stand-ins for the device arrays: the planner looks at their alignment and at which ones are present, never at
+    // their contents
+    alignas(64) static const unsigned char aligned[64] = {0};
+    FwdArgs a;
+    a.x = aligned; a.x_bf16 = (dtype == SRIGL_BF16); a.B = B; a.d_in = d_in; a.W_c = aligned; a.idx = aligned; a.idx_u16 = 0;
+    a.active = has_active ? reinterpret_cast<const int32_t*>(aligned) : nullptr;
+    a.n_active = n_active; a.K = K; a.bias = nullptr; a.d_out = d_out; a.y = nullptr;
+    a.seg = has_seg ? reinterpret_cast<const uint16_t*>(aligned) : nullptr;
+    a.seg_stride = srigl_seg_stride(d_in);
+    a.act = SRIGL_ACT_NONE;
+    const srigl_fwd_algo algo = choose_fwd_algo(a);
+    plan->algo = (int32_t)algo;
+    if (algo == SRIGL_FWD_ROWLANE) {
+        const RowlanePlan p = plan_rowlane(a, nullptr);
+        plan->rows_per_lane = p.R; plan->term_slices = p.H; plan->waves = p.NW; plan->neurons_per_wave = p.NPW;
+        plan->chunk_cols = p.C; plan->workgroups = (int64_t)p.n_groups * p.n_btiles;
+    } else if (algo == SRIGL_FWD_KLANE) {
+        const KlanePlan p = plan_klane(a, nullptr);
+        plan->lanes_per_neuron = p.L; plan->rows_per_block = p.RB; plan->workgroups = p.workgroups;
+    }
+    return SRIGL_OK;
 }
 
 }  // extern "C"

@@ -55,6 +55,7 @@ srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st);
 srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
 srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
 bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
+srigl_fwd_algo choose_fwd_algo(const FwdArgs& a);
 
 // Estimated time (us, operands in cache) of the small-batch forward kernel: a fixed part plus a part per term slot (K rounded
 // up to the slots one request of a lane group covers; dearer with one batch row per workgroup, the wide-input setting).

@@ -1,0 +1,72 @@
+"""Host logic of the forward pass: which kernel and launch shape the library's own choice takes (srigl_fwd_plan_query is host
+arithmetic only, so these run without a GPU).  The expectations are the shapes that measured best on MI355X for the
+named configurations and for the corner cases the planner's rules exist for."""
+import pytest
+
+from paper_2305_02299_amd import binding as B_
+
+
+def plan(B, d_in, d_out, K, n_active=None, **kw):
+    n = d_out if n_active is None else n_active
+    return B_.srigl_fwd_plan_query(B, d_in, n, K, d_out, has_active=(n != d_out), **kw)
+
+
+def test_single_row_takes_the_small_batch_kernel():
+    for (d_in, d_out, K) in ((768, 3072, 77), (3072, 768, 308), (4096, 16384, 205), (64, 8, 3)):
+        p = plan(1, d_in, d_out, K)
+        assert p["algo"] == B_.FWD_KLANE and p["rows_per_block"] == 1 and p["rows_per_lane"] == 0
+    assert plan(1, 768, 3072, 77)["lanes_per_neuron"] == 32      # 77 terms: at most 4 per lane
+    assert plan(1, 768, 3072, 8)["lanes_per_neuron"] == 4
+
+
+def test_headline_batch_is_one_workgroup_per_compute_unit():
+    p = plan(256, 768, 3072, 77)
+    assert p["algo"] == B_.FWD_ROWLANE
+    assert (p["rows_per_lane"], p["term_slices"], p["waves"], p["neurons_per_wave"]) == (1, 1, 16, 3)
+    assert p["workgroups"] == 256 and p["chunk_cols"] == 384
+
+
+def test_wide_inputs_get_16_row_tiles_and_one_row_per_workgroup():
+    p = plan(256, 3072, 768, 307, n_active=538)
+    assert p["algo"] == B_.FWD_ROWLANE and p["term_slices"] == 4 and p["neurons_per_wave"] == 3
+    p = plan(8, 3072, 768, 308)
+    assert p["algo"] == B_.FWD_KLANE and p["rows_per_block"] == 1
+    assert plan(8, 768, 3072, 77)["rows_per_block"] == 2
+
+
+def test_rounds_are_counted_per_xcd():
+    """3072 -> 768 at B = 320: four stored rows per wavefront would be 12 groups, two of them on four of the eight XCDs (40
+    workgroups on 32 compute units); two or six rows per wavefront fit in one round per XCD or split evenly."""
+    p = plan(320, 3072, 768, 308)
+    assert p["algo"] == B_.FWD_ROWLANE and p["neurons_per_wave"] in (2, 6)
+    # 768 -> 3072 at B = 384: 128-row tiles with three rows per wavefront are one round of 192 workgroups
+    p = plan(384, 768, 3072, 77)
+    assert (p["rows_per_lane"], p["neurons_per_wave"], p["workgroups"]) == (2, 3, 192)
+    p = plan(640, 768, 3072, 77)
+    assert (p["rows_per_lane"], p["neurons_per_wave"]) == (2, 4)
+
+
+def test_very_sparse_layers_stay_on_the_small_batch_kernel_at_larger_batches():
+    assert plan(256, 3072, 768, 31)["algo"] == B_.FWD_KLANE
+    assert plan(256, 768, 3072, 8)["algo"] == B_.FWD_KLANE
+    assert plan(256, 768, 3072, 39)["algo"] == B_.FWD_ROWLANE
+    assert plan(4096, 3072, 768, 31)["algo"] == B_.FWD_ROWLANE      # above 2048 rows always the batched kernel
+
+
+def test_mid_batches_follow_the_estimates():
+    assert plan(8, 768, 3072, 77)["algo"] == B_.FWD_KLANE
+    assert plan(32, 768, 3072, 77)["algo"] == B_.FWD_ROWLANE
+    assert plan(32, 2048, 512, 205)["algo"] == B_.FWD_KLANE         # few stored rows: the batched kernel cannot fill the GPU
+    assert plan(48, 2048, 512, 205)["algo"] == B_.FWD_ROWLANE
+
+
+def test_fallbacks():
+    # a row of x that does not fit the LDS of the small-batch kernel
+    assert plan(2, 49152, 48, 64)["algo"] == B_.FWD_ROWLANE
+    # d_in not a multiple of 16 and no seg table: the batched kernel needs the whole row in one LDS tile
+    p = plan(64, 100, 40, 7, has_seg=False)
+    assert p["algo"] in (B_.FWD_ROWLANE, B_.FWD_KLANE)
+    # nothing stored: no forward kernel at all
+    assert plan(4, 64, 8, 0)["algo"] == 0 and plan(0, 64, 8, 3)["workgroups"] == 0
+    with pytest.raises(B_.SriglError):
+        B_.srigl_fwd_plan_query(4, 8, 9, 3, 8)                      # more stored neurons than neurons
