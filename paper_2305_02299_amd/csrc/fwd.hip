@@ -416,8 +416,8 @@ srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
         const double small_us = klane_estimate_us(B, d_in, n_active, K);
         // up to 64 rows: one or two row tiles (few stored rows: too few workgroups share the staging); above: a fit of
         // 96 to 512 rows, where only layers with a few dozen terms per row still favour the small-batch kernel
-        // (16-row tiles of inputs wider than 2048: three times the cost per stored term)
-        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + (d_in > 2048 ? 4.5e-6 : 1.5e-6) * (double)n_active * K +
+        // (16-row tiles of inputs wider than 2048 with few stored rows: three times the cost per stored term)
+        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + (d_in > 2048 && n_active <= 1024 ? 4.5e-6 : 1.5e-6) * (double)n_active * K +
                                                 (n_active <= 1024 ? 0.5 : 0.0)
                                           : 7.7 + 0.0012 * d_in + 0.008 * B + 8e-8 * (double)B * n_active * K;
         batched = batched_us < small_us;

@@ -58,6 +58,8 @@ def test_mid_batches_follow_the_estimates():
     assert plan(32, 768, 3072, 77)["algo"] == B_.FWD_ROWLANE
     assert plan(32, 2048, 512, 205)["algo"] == B_.FWD_KLANE         # few stored rows: the batched kernel cannot fill the GPU
     assert plan(48, 2048, 512, 205)["algo"] == B_.FWD_ROWLANE
+    assert plan(16, 2560, 2560, 256)["algo"] == B_.FWD_ROWLANE        # wide input, many stored rows: 9.6 vs 13.7 us measured
+    assert plan(16, 3072, 768, 615)["algo"] == B_.FWD_KLANE           # wide input, few stored rows: 8.1 vs 11.9 us
 
 
 def test_fallbacks():
