@@ -231,6 +231,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     // ---- staging: 16 rows x 16 columns per unit; unit u = wv_id + i * nw -> (row tile, column tile) ----
     const int dq = lane & 3, db = lane >> 2;             // 4 column quads x 16 rows per wavefront pass
     const int col_tiles = C >> 4;                         // C is a multiple of 64
+    const float inv_col_tiles = 1.0f / (float)col_tiles;
     const int units = (BT / 16) * col_tiles;              // <= kStageUnits * nw (checked by the host)
     unsigned g_off[kStageUnits];                          // element offset into x of this lane's 4 columns (chunk 0)
     int l_off[kStageUnits];                               // word offset into the LDS tile
@@ -238,7 +239,9 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
     for (int i = 0; i < kStageUnits; ++i) {
         const int u = wv_id + i * nw;
-        const int rt = u / col_tiles, ct = u - rt * col_tiles;
+        // u / col_tiles without an integer division (exact: u and col_tiles are below 2^11, the half keeps the quotient
+        // at least 0.5 / col_tiles away from the next integer)
+        const int rt = (int)(((float)u + 0.5f) * inv_col_tiles), ct = u - rt * col_tiles;
         const int rl = rt * 16 + db;
         const int f = ct * 16 + dq * 4;
         // rows past B re-read row B - 1: their lanes compute values that are never stored
@@ -285,13 +288,15 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
         for (int r = 0; r < R; ++r) acc[i][r] = 0.0f;
 
+    // The activations of chunk 0 go out first: vector loads return in order, and the barrier in front of the first term
+    // waits for these only, while the term blocks and the boundaries requested behind them are still in flight.
     // Chunk 0 starts at term 0 of every row, so its blocks are requested before the boundaries are known.
+    SRIGL_STAGE_LOAD(0)
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
         for (int p = 0; p < KPRE; ++p) request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, tofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
-    SRIGL_STAGE_LOAD(0)
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
     SRIGL_STAMP(1)
     SRIGL_STAGE_STORE()
