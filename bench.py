@@ -623,7 +623,7 @@ def main():
         % (t_empty * 1e3, copy_gbs, Bn, t_dense * 1e3))
 
     # ---- CPU oracle on the host cores (reported baseline, one thread, never tuned) ----
-    cpu = cpu_all = None
+    cpu = cpu_all = parity = None
     if not args.no_cpu:
         import oracle
         W_c_h, idx_h = layer.W_c.cpu().numpy(), layer.idx.cpu().numpy()
@@ -634,6 +634,20 @@ def main():
             t0 = time.perf_counter()
             oracle.fwd(L.x, W_c_h, idx_h, act_h, L.bias, d_out)
             times.append(time.perf_counter() - t0)
+        # the timed configuration against the oracle (same inputs): error relative to the size of the summed terms (the
+        # gate of the parity tests), relative to the largest output, and the worst plain relative error
+        y_ref, S_ref = oracle.fwd(L.x, W_c_h, idx_h, act_h, L.bias, d_out, want_scale=True)
+        y_gpu = torch.empty((Bn, d_out), device="cuda")
+        B_.srigl_condensed_linear_fwd(dev(L.x), Bn, d_in, layer.W_c, layer.idx, layer.active, n_active, K, layer.bias, d_out, y_gpu,
+                                      layer.seg, algo=algo)
+        torch.cuda.synchronize()
+        err = np.abs(y_gpu.cpu().numpy().astype(np.float64) - y_ref.astype(np.float64))
+        parity = {"max_err_over_term_scale": float(np.max(err / np.maximum(np.maximum(np.abs(y_ref), S_ref), 1e-300))),
+                  "max_err_over_max_output": float(err.max() / np.abs(y_ref).max()),
+                  "worst_plain_relative_error": float(np.max(err / np.maximum(np.abs(y_ref), 1e-30))),
+                  "tolerance_on_term_scale": 1e-5}
+        log("parity of the timed configuration: err/scale %.2e, err/max|y| %.2e, worst plain relative %.2e"
+            % (parity["max_err_over_term_scale"], parity["max_err_over_max_output"], parity["worst_plain_relative_error"]))
         cpu = {"value": statistics.median(times) * 1e6, "unit": "us/call", "cores": 1, "kind": "oracle",
                "sample": "the whole %s forward (B=%d), median of %d calls, fp64 accumulate, g++ -O2, 1 thread of %d host cores"
                          % (args.workload, Bn, len(times), os.cpu_count())}
@@ -659,7 +673,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": r["hbm_gbs_cold"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": r["hbm_roofline_frac_cold"], "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, Bn)),
                      "algorithmic_bytes": r["algorithmic_bytes"]},
-        "cpu_baseline": cpu, "cpu_baseline_all_cores": cpu_all,
+        "cpu_baseline": cpu, "cpu_baseline_all_cores": cpu_all, "parity_vs_oracle": parity,
         "batch256": r, "batch1": results[1],
         "gflops_effective": r["gflops_cold"],
         "hbm_frac_of_measured_copy_bw": r["hbm_gbs_cold"] / copy_gbs,
