@@ -135,7 +135,7 @@ typedef struct {
     int32_t rows_per_block;   /* KLANE: batch rows staged per workgroup, 1, 2, 4 or 8                      */
     int32_t term_slices;      /* ROWLANE: 1, 2 or 4 groups of lanes that work on different terms of a stored
                                  row at once (batch tile = 64 * rows_per_lane / term_slices rows)           */
-    int32_t reserved[1];
+    int32_t direct_gather;    /* KLANE: 1 = gather activations from global memory, 2 = stage rows of x in LDS     */
 } srigl_fwd_tuning;
 
 /* Same, with the algorithm and launch shape forced (for tests and measurements).  tuning may be
@@ -157,9 +157,16 @@ typedef struct {
     int32_t rows_per_lane, term_slices, waves, neurons_per_wave, chunk_cols;   /* ROWLANE, else 0          */
     int32_t lanes_per_neuron, rows_per_block;                                 /* KLANE, else 0            */
     int64_t workgroups;       /* workgroups that do work                                                    */
+    int32_t direct_gather;    /* KLANE: 1 = activations gathered from global memory, 0 = rows of x staged in LDS */
+    int32_t reserved;
 } srigl_fwd_plan;
 srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
                                   int32_t has_active, int32_t has_seg, srigl_fwd_plan* plan);
+/* Same for a forced algorithm and launch shape (algo and tuning as in srigl_condensed_linear_fwd_algo; tuning may be NULL;
+ * SRIGL_FWD_AUTO is the call above): SRIGL_ERR_UNSUPPORTED where that forward call would return it. */
+srigl_status srigl_fwd_plan_query_algo(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
+                                       int32_t has_active, int32_t has_seg, srigl_fwd_algo algo, const srigl_fwd_tuning* tuning,
+                                       srigl_fwd_plan* plan);
 
 /* ---- MLP block: activation in the epilogue, width reduction -------------------------------------------
  * Sec. 3.1 (neuron ablation reduces the width of a layer) and App. H (the timed layer is one linear of a ViT MLP

@@ -31,7 +31,7 @@ EXPORTS = (
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
     "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
-    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query",
+    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query", "srigl_fwd_plan_query_algo",
 )
 
 
@@ -44,13 +44,14 @@ class SriglError(RuntimeError):
 class FwdTuning(ctypes.Structure):
     _fields_ = [("rows_per_lane", ctypes.c_int32), ("waves", ctypes.c_int32), ("neurons_per_wave", ctypes.c_int32),
                 ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32), ("rows_per_block", ctypes.c_int32),
-                ("term_slices", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
+                ("term_slices", ctypes.c_int32), ("direct_gather", ctypes.c_int32)]
 
 
 class FwdPlan(ctypes.Structure):
     _fields_ = [("algo", ctypes.c_int32), ("rows_per_lane", ctypes.c_int32), ("term_slices", ctypes.c_int32), ("waves", ctypes.c_int32),
                 ("neurons_per_wave", ctypes.c_int32), ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32),
-                ("rows_per_block", ctypes.c_int32), ("workgroups", ctypes.c_int64)]
+                ("rows_per_block", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("direct_gather", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -99,6 +100,9 @@ def _load() -> ctypes.CDLL:
     lib.srigl_csr_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, i32, vp, ctypes.c_int, vp]
     lib.srigl_fwd_plan_query.restype = ctypes.c_int
     lib.srigl_fwd_plan_query.argtypes = [i32, i32, i32, i32, i32, ctypes.c_int, i32, i32, ctypes.POINTER(FwdPlan)]
+    lib.srigl_fwd_plan_query_algo.restype = ctypes.c_int
+    lib.srigl_fwd_plan_query_algo.argtypes = [i32, i32, i32, i32, i32, ctypes.c_int, i32, i32, ctypes.c_int, ctypes.POINTER(FwdTuning),
+                                              ctypes.POINTER(FwdPlan)]
     lib.srigl_launch_empty.restype = ctypes.c_int
     lib.srigl_launch_empty.argtypes = [vp]
     lib.srigl_copy_bytes.restype = ctypes.c_int
@@ -220,11 +224,18 @@ def srigl_csr_linear_fwd(x, B, d_in, values, col_idx, row_ptr, bias, d_out, y, a
            "srigl_csr_linear_fwd")
 
 
-def srigl_fwd_plan_query(B, d_in, n_active, K, d_out, dtype_code=F32, has_active=False, has_seg=True) -> dict:
-    """The kernel and launch shape the library's own choice takes for these sizes (host arithmetic, no GPU call)."""
+def srigl_fwd_plan_query(B, d_in, n_active, K, d_out, dtype_code=F32, has_active=False, has_seg=True, algo=None, tuning=None) -> dict:
+    """The kernel and launch shape the library's own choice (or the forced algo / tuning dict) takes for these sizes (host
+    arithmetic, no GPU call)."""
     p = FwdPlan()
-    _check(lib.srigl_fwd_plan_query(int(B), int(d_in), int(n_active), int(K), int(d_out), int(dtype_code), int(bool(has_active)),
-                                    int(bool(has_seg)), ctypes.byref(p)), "srigl_fwd_plan_query")
+    tn = None
+    if tuning is not None:
+        tn = FwdTuning()
+        for k, v in tuning.items():
+            setattr(tn, k, int(v))
+    _check(lib.srigl_fwd_plan_query_algo(int(B), int(d_in), int(n_active), int(K), int(d_out), int(dtype_code), int(bool(has_active)),
+                                         int(bool(has_seg)), int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None,
+                                         ctypes.byref(p)), "srigl_fwd_plan_query_algo")
     return {name: int(getattr(p, name)) for name, _ in FwdPlan._fields_}
 
 

@@ -7,6 +7,7 @@
 // consecutive entries; the thread (or wavefront) that owns stored row s also fills the gap in front
 // of column active[s], and a virtual row s == n_active fills the tail.
 #include "srigl_internal.h"
+#include <algorithm>
 
 namespace srigl {
 
@@ -87,8 +88,8 @@ template <int RB, typename XT, typename IT>
 __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                    const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                    int n_active, int K, const float* __restrict__ bias, int d_out,
-                                                   float* __restrict__ y, int log2L, int rows_per_wg, int act) {
-    extern __shared__ float xs[];   // [RB][d_in]
+                                                   float* __restrict__ y, int log2L, int rows_per_wg, int act, int direct) {
+    extern __shared__ float xs[];   // [RB][d_in]; unused when `direct` (activations gathered from global memory)
     const int L = 1 << log2L;
     const int tid = threadIdx.x;
     const int q = tid & (L - 1);                      // lane within the neuron's group
@@ -105,11 +106,13 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
     int ir[kKlaneTerms];
     klane_request<XT, IT>(W_c, idx, (size_t)min(s, n_active - 1) * K, 0, q, L, K, wr, ir);
 
-    for (int r = 0; r < RB; ++r) {
-        const int b = min(b0 + r, B - 1);             // rows past B re-read the last row; they are never stored
-        for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = to_f32<XT>(x[(size_t)b * d_in + j]);
+    if (!direct) {
+        for (int r = 0; r < RB; ++r) {
+            const int b = min(b0 + r, B - 1);         // rows past B re-read the last row; they are never stored
+            for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = to_f32<XT>(x[(size_t)b * d_in + j]);
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     for (; s < s_end; s += groups) {
         float acc[RB];
@@ -123,12 +126,28 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
 #pragma unroll
                 for (int t = 0; t < kKlaneTerms; ++t) { wc[t] = wr[t]; ic[t] = ir[t]; }
                 if (kb + kKlaneTerms * L < K) klane_request<XT, IT>(W_c, idx, row, kb + kKlaneTerms * L, q, L, K, wr, ir);
+                if (direct) {   // a second round trip (the gather needs the indices), but no staging of whole rows of x
+                    XT xg[kKlaneTerms][RB];
 #pragma unroll
-                for (int t = 0; t < kKlaneTerms; ++t) {
-                    if (kb + q + t * L < K) {
-                        const float wv = to_f32<XT>(wc[t]);
+                    for (int t = 0; t < kKlaneTerms; ++t)
 #pragma unroll
-                        for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + ic[t]], acc[r]);
+                        for (int r = 0; r < RB; ++r) xg[t][r] = x[(size_t)min(b0 + r, B - 1) * d_in + ic[t]];
+#pragma unroll
+                    for (int t = 0; t < kKlaneTerms; ++t) {
+                        if (kb + q + t * L < K) {
+                            const float wv = to_f32<XT>(wc[t]);
+#pragma unroll
+                            for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, to_f32<XT>(xg[t][r]), acc[r]);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < kKlaneTerms; ++t) {
+                        if (kb + q + t * L < K) {
+                            const float wv = to_f32<XT>(wc[t]);
+#pragma unroll
+                            for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + ic[t]], acc[r]);
+                        }
                     }
                 }
             }
@@ -207,9 +226,9 @@ srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st) {
 }
 
 template <int RB, typename XT, typename IT>
-static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg, hipStream_t st) {
+static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg, int direct, hipStream_t st) {
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
-    const size_t lds = (size_t)RB * a.d_in * sizeof(float);
+    const size_t lds = direct ? 0 : (size_t)RB * a.d_in * sizeof(float);
     if (lds > kLdsMax) return SRIGL_ERR_UNSUPPORTED;
     auto kern = k_fwd_klane<RB, XT, IT>;
     static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
@@ -222,12 +241,12 @@ static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg,
     const unsigned gy = (unsigned)((a.B + RB - 1) / RB);
     if (gy > 65535u) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c, (const IT*)a.idx,
-                       a.active, a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act);
+                       a.active, a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act, direct);
     return hip_ok(hipGetLastError());
 }
 
 // Launch shape of the small-batch kernel, decided on the host.
-struct KlanePlan { int L, RB, rows_per_wg; long long workgroups; bool ok; };
+struct KlanePlan { int L, RB, rows_per_wg, direct; long long workgroups; bool ok; };
 static KlanePlan plan_klane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     KlanePlan p{};
     p.ok = false;
@@ -236,18 +255,25 @@ static KlanePlan plan_klane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     int L = t && t->lanes_per_neuron ? t->lanes_per_neuron : 0;
     if (L == 0) { L = 4; while (L < 64 && L * kKlaneTerms < a.K) L <<= 1; }
     if (L < 1 || L > 64 || (L & (L - 1)) != 0) return p;
+    // activations: gathered from global memory, or staged in LDS (the tuning can force either: 1 = gather, 2 = stage);
+    // an input row too long for the LDS is always gathered
+    const int dg = t ? t->direct_gather : 0;
+    if (dg < 0 || dg > 2) return p;
+    p.direct = dg == 1 || (dg == 0 && klane_gathers(a.B, a.d_in, a.n_active, a.K)) ? 1 : 0;
     int RB = t && t->rows_per_block ? t->rows_per_block : 0;
-    // measured: one row per workgroup up to batch 4 and for wide inputs (staging two rows of x then costs more
-    // than the second pass over W_c/idx saves); two rows beat four and eight elsewhere
-    if (RB == 0) RB = (a.B > 4 && a.d_in <= 1024) ? 2 : 1;
-    while (RB > 1 && (size_t)RB * a.d_in * sizeof(float) > kLdsMax / 2) RB >>= 1;
-    if (RB != 1 && RB != 2 && RB != 4 && RB != 8) return p;
-    if ((size_t)RB * a.d_in * sizeof(float) > kLdsMax) return p;          // a row of x must fit the LDS
+    if (RB != 0 && RB != 1 && RB != 2 && RB != 4 && RB != 8) return p;
+    if (RB == 0) RB = p.direct ? klane_gather_rows(a.B, a.n_active, a.K) : klane_stage_rows(a.B, a.d_in);
+    if (!p.direct) {
+        while (RB > 1 && (size_t)RB * a.d_in * sizeof(float) > kLdsMax / 2) RB >>= 1;
+        if ((size_t)RB * a.d_in * sizeof(float) > kLdsMax) return p;   // the staged rows of x must fit the LDS
+    }
     if ((a.B + RB - 1) / RB > 65535) return p;                            // the batch is the grid's second dimension
     const int groups = 256 / L;
     // stored rows per workgroup: one pass of all groups, more when that still leaves > 8 workgroups per CU
     int rows_per_wg = groups;
-    while ((long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB) > 256 * 8) rows_per_wg += groups;
+    // (the gathering form has no staging to share between passes: it takes more of them only beyond 32 workgroups per CU)
+    const long long max_wgs = p.direct ? 256 * 32 : 256 * 8;
+    while ((long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB) > max_wgs) rows_per_wg += groups;
     p.L = L; p.RB = RB; p.rows_per_wg = rows_per_wg;
     p.workgroups = (long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB);
     p.ok = true;
@@ -259,13 +285,13 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     if (a.B == 0 || n_slots == 0) return SRIGL_OK;
     const KlanePlan kp = plan_klane(a, t);
     if (!kp.ok) return SRIGL_ERR_UNSUPPORTED;
-    const int RB = kp.RB, rows_per_wg = kp.rows_per_wg;
+    const int RB = kp.RB, rows_per_wg = kp.rows_per_wg, direct = kp.direct;
     const int log2L = ilog2_floor(kp.L);
 #define SRIGL_KLANE(RBV)                                                                               \
-    return a.x_bf16 ? (a.idx_u16 ? launch_klane_t<RBV, uint16_t, uint16_t>(a, log2L, rows_per_wg, st)                  \
-                                 : launch_klane_t<RBV, uint16_t, int32_t>(a, log2L, rows_per_wg, st))                  \
-                    : (a.idx_u16 ? launch_klane_t<RBV, float, uint16_t>(a, log2L, rows_per_wg, st)                     \
-                                 : launch_klane_t<RBV, float, int32_t>(a, log2L, rows_per_wg, st))
+    return a.x_bf16 ? (a.idx_u16 ? launch_klane_t<RBV, uint16_t, uint16_t>(a, log2L, rows_per_wg, direct, st)                  \
+                                 : launch_klane_t<RBV, uint16_t, int32_t>(a, log2L, rows_per_wg, direct, st))                  \
+                    : (a.idx_u16 ? launch_klane_t<RBV, float, uint16_t>(a, log2L, rows_per_wg, direct, st)                     \
+                                 : launch_klane_t<RBV, float, int32_t>(a, log2L, rows_per_wg, direct, st))
     switch (RB) {
         case 1: SRIGL_KLANE(1);
         case 2: SRIGL_KLANE(2);
@@ -403,23 +429,35 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
     return a.x_bf16 ? launch_rowlane_bf16(a, p, st) : launch_rowlane_f32(a, p, st);
 }
 
-// The library's own choice of kernel.  Small batches: the lanes-along-K kernel costs a fixed part plus a part per term slot
-// (K rounded up to the lanes it spreads a row over; dearer with one batch row per workgroup, the wide-input setting); the
-// batched kernel below one or two row tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its
-// share of the stored terms.  Fits of timings of 512- to 4096-wide layers at 80-99 % sparsity, the cold read of W_c / idx
-// left out of both; a single row always takes the small-batch kernel, above 2048 rows the batched kernel always wins.
+// The library's own choice of kernel: the smaller of two estimated times.  The small-batch kernel's estimate (gathered or
+// staged activations, whichever is less) grows with the batch times the stored terms; the batched kernel below one or two row
+// tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its share of the stored terms.  Fits of
+// timings (mean of cold and cached operands) of 512- to 4096-wide layers at 80-99 % sparsity; a single row always takes the
+// small-batch kernel, above 2048 rows the batched kernel always wins.
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
     const int B = a.B, d_in = a.d_in, n_active = a.n_active, K = a.K;
     bool batched = B > 16;
     if (B > 1 && B <= 2048 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
         const double small_us = klane_estimate_us(B, d_in, n_active, K);
-        // up to 64 rows: one or two row tiles (few stored rows: too few workgroups share the staging); above: a fit of
-        // 96 to 512 rows, where only layers with a few dozen terms per row still favour the small-batch kernel
-        // (16-row tiles of inputs wider than 2048 with few stored rows: three times the cost per stored term)
-        const double batched_us = B <= 64 ? 4.3 + 0.0014 * d_in + (d_in > 2048 && n_active <= 1024 ? 4.5e-6 : 1.5e-6) * (double)n_active * K +
-                                                (n_active <= 1024 ? 0.5 : 0.0)
-                                          : 7.7 + 0.0012 * d_in + 0.008 * B + 8e-8 * (double)B * n_active * K;
+        // up to 64 rows: staging x (grows with d_in) plus the stored terms (16-row tiles of inputs wider than 2048 with few
+        // stored rows: three times the cost per term; large layers: the stream of W_c / idx); once the row tiles times the
+        // groups of stored rows exceed the compute units, a wavefront takes `more` times the stored rows and everything
+        // but the launch grows with it.  Above 64 rows: a fit of 96 to 512 rows (staging x, the terms, writing y), where
+        // only layers with a few dozen terms per row still favour the small-batch kernel.
+        const double terms = (double)n_active * K;
+        double more = 1.0;
+        if (B <= 64) {
+            const RowlanePlan rp = plan_rowlane(a, nullptr);
+            if (rp.ok) {
+                const int n_slots = a.active ? n_active + 1 : n_active;
+                const int one_tile = std::max(1, (n_slots + rp.NW * 256 - 1) / (rp.NW * 256));
+                more = std::max(1.0, (double)rp.NPW / one_tile);
+            }
+        }
+        const double batched_us = B <= 64 ? 4.3 + (1.0 + 0.85 * (more - 1.0)) * (0.0014 * d_in + (d_in > 2048 && n_active <= 1024 ? 4.5e-6 : 1.5e-6) * terms +
+                                                                                (n_active <= 1024 ? 0.5 : 0.0)) + (terms > 1.5e6 ? 3.0e-6 * terms : 0.0)
+                                          : 4.4 + 0.0015 * d_in + 7e-6 * d_in * B + 8e-8 * B * terms + 2.5e-6 * B * (double)a.d_out;
         batched = batched_us < small_us;
     }
     const bool can_batch = rowlane_supported(a, nullptr);
@@ -537,6 +575,14 @@ srigl_status srigl_narrow_idx(const int32_t* idx, int64_t n, int32_t d_in, uint1
 
 srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
                                   int32_t has_active, int32_t has_seg, srigl_fwd_plan* plan) {
+    return srigl_fwd_plan_query_algo(B, d_in, n_active, K, d_out, dtype, has_active, has_seg, SRIGL_FWD_AUTO, nullptr, plan);
+}
+
+srigl_status srigl_fwd_plan_query_algo(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
+                                       int32_t has_active, int32_t has_seg, srigl_fwd_algo forced, const srigl_fwd_tuning* tuning,
+                                       srigl_fwd_plan* plan) {
+    if (forced != SRIGL_FWD_AUTO && forced != SRIGL_FWD_GENERIC && forced != SRIGL_FWD_KLANE && forced != SRIGL_FWD_ROWLANE)
+        return SRIGL_ERR_INVALID_ARG;
     if (plan == nullptr || B < 0 || d_in < 0 || n_active < 0 || K < 0 || d_out < 0 || K > d_in || n_active > d_out)
         return SRIGL_ERR_INVALID_ARG;
     if (dtype != SRIGL_F32 && dtype != SRIGL_BF16) return SRIGL_ERR_INVALID_ARG;
@@ -552,15 +598,17 @@ srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int
     a.seg = has_seg ? reinterpret_cast<const uint16_t*>(aligned) : nullptr;
     a.seg_stride = srigl_seg_stride(d_in);
     a.act = SRIGL_ACT_NONE;
-    const srigl_fwd_algo algo = choose_fwd_algo(a);
+    const srigl_fwd_algo algo = forced == SRIGL_FWD_AUTO ? choose_fwd_algo(a) : forced;
     plan->algo = (int32_t)algo;
     if (algo == SRIGL_FWD_ROWLANE) {
-        const RowlanePlan p = plan_rowlane(a, nullptr);
+        const RowlanePlan p = plan_rowlane(a, tuning);
+        if (!p.ok) return SRIGL_ERR_UNSUPPORTED;
         plan->rows_per_lane = p.R; plan->term_slices = p.H; plan->waves = p.NW; plan->neurons_per_wave = p.NPW;
         plan->chunk_cols = p.C; plan->workgroups = (int64_t)p.n_groups * p.n_btiles;
     } else if (algo == SRIGL_FWD_KLANE) {
-        const KlanePlan p = plan_klane(a, nullptr);
-        plan->lanes_per_neuron = p.L; plan->rows_per_block = p.RB; plan->workgroups = p.workgroups;
+        const KlanePlan p = plan_klane(a, tuning);
+        if (!p.ok) return SRIGL_ERR_UNSUPPORTED;
+        plan->lanes_per_neuron = p.L; plan->rows_per_block = p.RB; plan->workgroups = p.workgroups; plan->direct_gather = p.direct;
     }
     return SRIGL_OK;
 }

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <cmath>
 #include <stdint.h>
 
 #include "srigl.h"
@@ -57,16 +58,54 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
 bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a);
 
-// Estimated time (us, operands in cache) of the small-batch forward kernel: a fixed part plus a part per term slot (K rounded
-// up to the slots one request of a lane group covers; dearer with one batch row per workgroup, the wide-input setting).
-// A fit of timings of 512- to 4096-wide layers at 80-90 % sparsity; used to pick the kernel for batches of 5 to 64 rows and
-// by the choice between the condensed and the structured-only form.
-inline double klane_estimate_us(int B, int d_in, int n_active, int K) {
+// The small-batch forward kernel takes its activations either from global memory through the vector caches (a gather:
+// no staging pass, no barrier, any d_in) or from rows of x staged in LDS.  Estimated times (us) of both, fits of timings
+// (mean of cold and cached operands) of 512- to 4096-wide layers at 80-99 % sparsity and batches of 2 to 256; they pick the
+// source of the activations, the kernel for batches of 2 to 2048 rows, and feed the choice between the condensed and the
+// structured-only form.  Layers of more than ~1.5 M stored terms no longer sit in one XCD's L2: every pass over
+// W_c / idx (one per workgroup row of the batch) then also pays for that stream.
+//
+// Batch rows per workgroup of the gathering form: a second and a fourth row pay once the pass over W_c / idx they save
+// outweighs the longer chain of gathers per lane (measured: from ~1.2 M and ~3.5 M gathered terms).
+inline int klane_gather_rows(int B, int n_active, int K) {
+    const double work = (double)B * n_active * K;
+    int RB = work < 1.2e6 ? 1 : (work < 3.5e6 ? 2 : 4);
+    while (RB > 1 && RB > B) RB >>= 1;
+    return RB;
+}
+// Batch rows per workgroup of the staging form (measured: one row up to batch 4 and for wide inputs, where staging two rows
+// of x costs more than the second pass over W_c / idx saves; two rows beat four and eight elsewhere).
+inline int klane_stage_rows(int B, int d_in) { return (B > 4 && d_in <= 1024) ? 2 : 1; }
+
+// Gathering: a fixed part plus a part per gathered term that grows with the number of distinct 128-byte lines of x a
+// wavefront's gather touches (rho = stored terms per line of a row of x: a lane group's consecutive terms share lines
+// when rho is large) and with how far the rows of x a workgroup gathers from overflow the vector L1 (the width factor):
+// ~1.0 us per million terms at 90 % sparsity, 1.3 at 99 % on 768- to 1024-wide inputs, 2.0 at 99 % on 4096-wide ones.
+inline double klane_gather_estimate_us(int B, int d_in, int n_active, int K) {
+    const double terms = (double)n_active * K;
+    const double rho = 32.0 * K / (d_in > 0 ? d_in : 1);
+    const double lines_per_term = rho > 1e-6 ? (1.0 - exp(-rho)) / rho : 1.0;
+    const double width = d_in <= 1024 ? 0.4 : (d_in <= 3072 ? 0.7 : 1.0);
+    const int RB = klane_gather_rows(B, n_active, K);
+    return 2.6 + (0.8 + 1.4 * lines_per_term * width) * 1e-6 * B * terms + (terms > 1.5e6 ? 3.0e-6 * terms * ((B + RB - 1) / RB) : 0.0);
+}
+// Staging: a fixed part that grows with the row of x every workgroup stages, plus a part per term slot (K rounded up to the
+// slots one request of a lane group covers).
+inline double klane_stage_estimate_us(int B, int d_in, int n_active, int K) {
     int L = 4;
     while (L < 64 && L * 4 < K) L <<= 1;
     const int req = L * 4;   // term slots one request of a lane group covers (4 terms per lane)
     const double slots = (double)B * n_active * ((K + req - 1) / req * req);
-    return 3.2 + 0.0005 * d_in + (d_in <= 1024 ? 0.44e-6 : 0.6e-6) * slots;
+    const double terms = (double)n_active * K;
+    const int RB = klane_stage_rows(B, d_in);
+    return 3.0 + 0.0007 * d_in + (d_in <= 1024 ? 0.65e-6 : 0.75e-6) * slots + (terms > 1.5e6 ? 3.0e-6 * terms * ((B + RB - 1) / RB) : 0.0);
+}
+inline bool klane_row_fits_lds(int d_in) { return (size_t)d_in * sizeof(float) <= kLdsMax; }
+inline bool klane_gathers(int B, int d_in, int n_active, int K) {
+    return !klane_row_fits_lds(d_in) || klane_gather_estimate_us(B, d_in, n_active, K) <= klane_stage_estimate_us(B, d_in, n_active, K);
+}
+inline double klane_estimate_us(int B, int d_in, int n_active, int K) {
+    return klane_gathers(B, d_in, n_active, K) ? klane_gather_estimate_us(B, d_in, n_active, K) : klane_stage_estimate_us(B, d_in, n_active, K);
 }
 
 inline srigl_status hip_ok(hipError_t e) { return e == hipSuccess ? SRIGL_OK : SRIGL_ERR_HIP; }

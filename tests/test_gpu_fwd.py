@@ -292,9 +292,21 @@ def test_non_finite_activation_only_reaches_its_own_terms(algo):
 
 @pytest.mark.parametrize("B", [1, 3, 40])
 def test_input_wider_than_the_lds_row_of_the_small_batch_kernel(B):
-    """d_in = 49152: one fp32 row of x (192 KB) does not fit the LDS, so the small-batch kernel cannot run and the library's own
-    choice must fall through to the batched kernel (chunks of columns), not to the one-thread-per-output fallback only."""
+    """d_in = 49152: one fp32 row of x (192 KB) does not fit the LDS.  The small-batch kernel then gathers its activations from
+    global memory (its staged form refuses), the batched kernel walks chunks of columns; every path matches the oracle."""
     L = si.make_layer(49152, 48, 64, B, ablate_frac=0.1, seed=11)
     assert check_layer(L, None, None) is not None
-    assert check_layer(L, B_.FWD_KLANE, None, unsupported_ok=True) is None       # the small-batch kernel refuses
-    assert check_layer(L, B_.FWD_ROWLANE, None, unsupported_ok=True) is not None  # the batched kernel runs it
+    assert check_layer(L, B_.FWD_KLANE, None, unsupported_ok=True) is not None                          # gathers
+    assert check_layer(L, B_.FWD_KLANE, dict(direct_gather=2), unsupported_ok=True) is None             # staging refuses
+    assert check_layer(L, B_.FWD_ROWLANE, None, unsupported_ok=True) is not None                        # the batched kernel runs it
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("gather", [1, 2])
+@pytest.mark.parametrize("B,rb", [(1, 1), (2, 2), (3, 2), (5, 4), (9, 8), (33, 4), (7, 1)])
+def test_small_batch_kernel_gathered_and_staged_activations(B, rb, gather, dtype):
+    """Both sources of the activations (gathered from global memory, staged in LDS), every rows-per-workgroup setting, batches
+    that leave the last workgroup row ragged; K = 77 leaves the last request of a lane group partly past the row."""
+    L = si.make_layer(320, 200, 77, B, ablate_frac=0.15, seed=B + 10 * rb, dtype=dtype)
+    worst = check_layer(L, B_.FWD_KLANE, dict(direct_gather=gather, rows_per_block=rb))
+    assert worst < (TOL_BF16 if dtype == "bf16" else 2e-6)

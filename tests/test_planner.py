@@ -29,9 +29,26 @@ def test_headline_batch_is_one_workgroup_per_compute_unit():
 def test_wide_inputs_get_16_row_tiles_and_one_row_per_workgroup():
     p = plan(256, 3072, 768, 307, n_active=538)
     assert p["algo"] == B_.FWD_ROWLANE and p["term_slices"] == 4 and p["neurons_per_wave"] == 3
-    p = plan(8, 3072, 768, 308)
-    assert p["algo"] == B_.FWD_KLANE and p["rows_per_block"] == 1
-    assert plan(8, 768, 3072, 77)["rows_per_block"] == 2
+    # staged activations: one row per workgroup for wide inputs, two for narrow ones from batch 5
+    assert plan(256, 3072, 768, 31)["rows_per_block"] == 1
+    assert plan(8, 768, 3072, 77, algo=B_.FWD_KLANE, tuning=dict(direct_gather=2))["rows_per_block"] == 2
+
+
+def test_small_batches_gather_their_activations():
+    """Measured: up to a few million gathered terms the small-batch kernel is faster reading x through the caches than staging
+    rows of it in LDS (3072 -> 768 at B = 1: 3.7 vs 6.4 us cold), with one, two or four batch rows per workgroup."""
+    for (B, d_in, d_out, K, rb) in ((1, 768, 3072, 77, 1), (1, 3072, 768, 308, 1), (4, 3072, 768, 308, 1), (8, 3072, 768, 308, 2),
+                                    (8, 768, 3072, 77, 2), (16, 4096, 1024, 410, 4), (2, 4096, 16384, 205, 2)):
+        p = plan(B, d_in, d_out, K)
+        assert (p["algo"], p["direct_gather"], p["rows_per_block"]) == (B_.FWD_KLANE, 1, rb), (B, d_in, d_out, K, p)
+    # very sparse layers at large batches: many distinct lines per gather, the staged rows win
+    assert plan(256, 3072, 768, 31)["direct_gather"] == 0
+    assert plan(32, 4096, 4096, 41)["direct_gather"] == 0
+    # a row of x that does not fit the LDS can only be gathered
+    p = plan(1, 49152, 48, 64)
+    assert (p["algo"], p["direct_gather"]) == (B_.FWD_KLANE, 1)
+    # large layers from three rows on: the batched kernel (every further pass re-reads W_c / idx from beyond the L2)
+    assert plan(4, 4096, 16384, 205)["algo"] == B_.FWD_ROWLANE
 
 
 def test_rounds_are_counted_per_xcd():
@@ -47,8 +64,9 @@ def test_rounds_are_counted_per_xcd():
 
 
 def test_very_sparse_layers_stay_on_the_small_batch_kernel_at_larger_batches():
-    assert plan(256, 3072, 768, 31)["algo"] == B_.FWD_KLANE
-    assert plan(256, 768, 3072, 8)["algo"] == B_.FWD_KLANE
+    assert plan(256, 3072, 768, 31)["algo"] == B_.FWD_KLANE           # 11.0 / 8.1 us (cold / cached) vs 15.4 / 14.3
+    assert plan(96, 768, 3072, 8)["algo"] == B_.FWD_KLANE             # 6.0 / 5.0 vs 8.1 / 7.4
+    assert plan(256, 768, 3072, 8)["algo"] == B_.FWD_ROWLANE          # 9.4 / 8.4 vs 10.8 / 9.4: many neurons, y is 3 MB
     assert plan(256, 768, 3072, 39)["algo"] == B_.FWD_ROWLANE
     assert plan(4096, 3072, 768, 31)["algo"] == B_.FWD_ROWLANE      # above 2048 rows always the batched kernel
 
@@ -63,8 +81,8 @@ def test_mid_batches_follow_the_estimates():
 
 
 def test_fallbacks():
-    # a row of x that does not fit the LDS of the small-batch kernel
-    assert plan(2, 49152, 48, 64)["algo"] == B_.FWD_ROWLANE
+    # a row of x that does not fit the LDS of the small-batch kernel: gathered, or the batched kernel
+    assert plan(2, 49152, 48, 64)["algo"] in (B_.FWD_KLANE, B_.FWD_ROWLANE)
     # d_in not a multiple of 16 and no seg table: the batched kernel needs the whole row in one LDS tile
     p = plan(64, 100, 40, 7, has_seg=False)
     assert p["algo"] in (B_.FWD_ROWLANE, B_.FWD_KLANE)
