@@ -132,7 +132,7 @@ typedef struct {
     int32_t neurons_per_wave; /* ROWLANE: stored neurons accumulated per wavefront, 1..8                   */
     int32_t chunk_cols;       /* ROWLANE: activation columns per LDS tile, multiple of 64                  */
     int32_t lanes_per_neuron; /* KLANE: lanes that share one neuron, power of two 1..64                    */
-    int32_t rows_per_block;   /* KLANE: batch rows staged per workgroup, 1, 2, 4 or 8                      */
+    int32_t rows_per_block;   /* KLANE: batch rows per workgroup, 1, 2, 4 or 8                             */
     int32_t term_slices;      /* ROWLANE: 1, 2 or 4 groups of lanes that work on different terms of a stored
                                  row at once (batch tile = 64 * rows_per_lane / term_slices rows)           */
     int32_t direct_gather;    /* KLANE: 1 = gather activations from global memory, 2 = stage rows of x in LDS     */
@@ -223,7 +223,7 @@ srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype
  * row_ptr[d_out + 1] int32 ascending with row_ptr[0] == 0 and row_ptr[d_out] == nnz (not checked; nnz is passed so that
  * the launch shape can follow the mean row length), bias[d_out] fp32 or NULL, y[B][d_out] fp32, fully overwritten
  * (a row without entries outputs act(bias)).  Device pointers, caller's stream, no allocation.
- * SRIGL_ERR_UNSUPPORTED if a row of x does not fit the LDS (d_in > 40960) or B > 65535. */
+ * SRIGL_ERR_UNSUPPORTED if B > 65535. */
 srigl_status srigl_csr_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* values,
                                   srigl_dtype w_dtype, const int32_t* col_idx, const int32_t* row_ptr, int64_t nnz,
                                   const float* bias, int32_t d_out, float* y, srigl_activation act, void* stream);

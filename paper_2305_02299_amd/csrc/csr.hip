@@ -1,9 +1,11 @@
 // The unstructured comparison of Sec. 4.4 / Fig. 4 of arXiv 2305.02299 on the same GPU: the layer's kept weights in
 // compressed sparse row form, y[b][r] = bias[r] + sum over row r's entries of value * x[b][column].  The kernel has the
-// shape of the small-batch condensed kernel (a workgroup stages RB rows of x in LDS, L lanes share one row of the matrix
-// and take its entries L apart, partial sums meet in a butterfly of cross-lane shuffles); what differs is what the format
-// forces: a row's extent comes from row_ptr (one more dependent load per row) and rows differ in length.
+// shape of the small-batch condensed kernel (activations gathered from global memory or from RB rows of x staged in LDS,
+// by the same rule; L lanes share one row of the matrix and take its entries L apart, partial sums meet in a butterfly of
+// cross-lane shuffles); what differs is what the format forces: a row's extent comes from row_ptr (one more dependent
+// load per row) and rows differ in length.
 #include "srigl_internal.h"
+#include <algorithm>
 
 namespace srigl {
 
@@ -12,12 +14,12 @@ template <> __device__ __forceinline__ float csr_to_f32<float>(float v) { return
 
 constexpr int kCsrTerms = 4;   // entries a lane keeps in flight per request
 
-template <int RB, typename XT>
+template <int RB, bool GATHER, typename XT>
 __global__ __launch_bounds__(256) void k_fwd_csr(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ values,
                                                  const int32_t* __restrict__ col_idx, const int32_t* __restrict__ row_ptr,
                                                  const float* __restrict__ bias, int d_out, float* __restrict__ y, int log2L,
                                                  int rows_per_wg, int act) {
-    extern __shared__ float xs[];   // [RB][d_in]
+    extern __shared__ float xs[];   // [RB][d_in]; unused when GATHER
     const int L = 1 << log2L;
     const int tid = threadIdx.x;
     const int q = tid & (L - 1);
@@ -30,11 +32,13 @@ __global__ __launch_bounds__(256) void k_fwd_csr(const XT* __restrict__ x, int B
     int beg = 0, end = 0;
     if (s < s_end) { beg = row_ptr[s]; end = row_ptr[s + 1]; }   // in flight while x is staged
 
-    for (int r = 0; r < RB; ++r) {
-        const int b = min(b0 + r, B - 1);             // rows past B re-read the last row; they are never stored
-        for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = csr_to_f32<XT>(x[(size_t)b * d_in + j]);
+    if (!GATHER) {
+        for (int r = 0; r < RB; ++r) {
+            const int b = min(b0 + r, B - 1);         // rows past B re-read the last row; they are never stored
+            for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = csr_to_f32<XT>(x[(size_t)b * d_in + j]);
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     for (; s < s_end; s += groups) {
         float acc[RB];
@@ -52,12 +56,31 @@ __global__ __launch_bounds__(256) void k_fwd_csr(const XT* __restrict__ x, int B
                 w[j] = values[tt];
                 c[j] = col_idx[tt];
             }
+            if (GATHER) {
+                // a column outside [0, d_in) must not become an address outside x
 #pragma unroll
-            for (int j = 0; j < kCsrTerms; ++j) {
-                if (t + j * L < end) {
-                    const float wv = csr_to_f32<XT>(w[j]);
+                for (int j = 0; j < kCsrTerms; ++j) c[j] = min(max(c[j], 0), d_in - 1);
+                XT xg[kCsrTerms][RB];
 #pragma unroll
-                    for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + c[j]], acc[r]);
+                for (int j = 0; j < kCsrTerms; ++j)
+#pragma unroll
+                    for (int r = 0; r < RB; ++r) xg[j][r] = x[(size_t)min(b0 + r, B - 1) * d_in + c[j]];
+#pragma unroll
+                for (int j = 0; j < kCsrTerms; ++j) {
+                    if (t + j * L < end) {
+                        const float wv = csr_to_f32<XT>(w[j]);
+#pragma unroll
+                        for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, csr_to_f32<XT>(xg[j][r]), acc[r]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < kCsrTerms; ++j) {
+                    if (t + j * L < end) {
+                        const float wv = csr_to_f32<XT>(w[j]);
+#pragma unroll
+                        for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + c[j]], acc[r]);
+                    }
                 }
             }
         }
@@ -76,12 +99,12 @@ __global__ __launch_bounds__(256) void k_fwd_csr(const XT* __restrict__ x, int B
     }
 }
 
-template <int RB, typename XT>
+template <int RB, bool GATHER, typename XT>
 static srigl_status launch_csr(const void* x, int B, int d_in, const void* values, const int32_t* col_idx, const int32_t* row_ptr,
                                const float* bias, int d_out, float* y, int log2L, int act, hipStream_t st) {
-    const size_t lds = (size_t)RB * d_in * sizeof(float);
+    const size_t lds = GATHER ? 0 : (size_t)RB * d_in * sizeof(float);
     if (lds > kLdsMax) return SRIGL_ERR_UNSUPPORTED;
-    auto kern = k_fwd_csr<RB, XT>;
+    auto kern = k_fwd_csr<RB, GATHER, XT>;
     static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
     if (lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
@@ -91,9 +114,9 @@ static srigl_status launch_csr(const void* x, int B, int d_in, const void* value
     const int groups = 256 >> log2L;
     const int gy = (B + RB - 1) / RB;
     if (gy > 65535) return SRIGL_ERR_UNSUPPORTED;
-    // rows per workgroup: one pass of all groups, more when that still leaves > 8 workgroups per CU
+    // rows per workgroup: one pass of all groups, more when that still leaves > 8 (gathering: 32) workgroups per CU
     int rows_per_wg = groups;
-    while ((long long)((d_out + rows_per_wg - 1) / rows_per_wg) * gy > 256 * 8) rows_per_wg += groups;
+    while ((long long)((d_out + rows_per_wg - 1) / rows_per_wg) * gy > 256 * (GATHER ? 32 : 8)) rows_per_wg += groups;
     const unsigned gx = (unsigned)((d_out + rows_per_wg - 1) / rows_per_wg);
     hipLaunchKernelGGL(kern, dim3(gx, (unsigned)gy), dim3(256), lds, st, (const XT*)x, B, d_in, (const XT*)values, col_idx, row_ptr,
                        bias, d_out, y, log2L, rows_per_wg, act);
@@ -120,7 +143,16 @@ extern "C" srigl_status srigl_csr_linear_fwd(const void* x, srigl_dtype x_dtype,
     const long long mean = (nnz + d_out - 1) / d_out;
     int L = 4, log2L = 2;
     while (L < 64 && (long long)L * kCsrTerms < mean) { L <<= 1; ++log2L; }
-    const bool two = B > 4 && d_in <= 1024;   // batch rows per workgroup, as in the condensed small-batch kernel
-    if (two) return launch_csr<2, float>(x, B, d_in, values, col_idx, row_ptr, bias, d_out, y, log2L, (int)act, st);
-    return launch_csr<1, float>(x, B, d_in, values, col_idx, row_ptr, bias, d_out, y, log2L, (int)act, st);
+    // source of the activations and batch rows per workgroup: the rules of the condensed small-batch kernel, with the mean
+    // row length in the place of K
+    const int K_mean = (int)std::min<long long>(mean, d_in);
+    const int direct = klane_gathers(B, d_in, d_out, K_mean) ? 1 : 0;
+    const int RB = direct ? klane_gather_rows(B, d_out, K_mean) : klane_stage_rows(B, d_in);
+#define SRIGL_CSR(RBV)                                                                                                        \
+    return direct ? launch_csr<RBV, true, float>(x, B, d_in, values, col_idx, row_ptr, bias, d_out, y, log2L, (int)act, st)    \
+                  : launch_csr<RBV, false, float>(x, B, d_in, values, col_idx, row_ptr, bias, d_out, y, log2L, (int)act, st)
+    if (RB == 4) SRIGL_CSR(4);
+    if (RB == 2) SRIGL_CSR(2);
+    SRIGL_CSR(1);
+#undef SRIGL_CSR
 }

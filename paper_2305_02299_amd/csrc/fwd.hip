@@ -64,32 +64,20 @@ __global__ __launch_bounds__(256) void k_bias_broadcast(const float* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------------
-// KLANE (small batch, online inference).  A workgroup stages RB rows of x in LDS (fp32, row-major)
-// and walks over stored rows; L lanes (a power of two) share one stored row: lane q takes the terms
-// k = q, q+L, ... so that a wavefront's loads of W_c and idx are runs of L contiguous words, and the
-// partial sums are combined with a butterfly of cross-lane shuffles.
+// KLANE (small batch, online inference).  A workgroup walks over stored rows for RB rows of the batch; L lanes (a power
+// of two) share one stored row: lane q takes the terms k = q, q+L, ... so that a wavefront's loads of W_c and idx are
+// runs of L contiguous words, and the partial sums are combined with a butterfly of cross-lane shuffles.  The
+// activations are gathered from global memory through the vector caches (GATHER), or from RB rows of x the workgroup
+// first stages in LDS (fp32, row-major).
 // ------------------------------------------------------------------------------------------------
 constexpr int kKlaneTerms = 4;   // terms a lane keeps in flight per request
 
-// Lane q of a group asks for terms kb + q, kb + q + L, ... (kKlaneTerms of them) of stored row s.  The loads are
-// unconditional (term index clamped into the row) and nothing here consumes them, so they all stay in flight.
-template <typename XT, typename IT>
-__device__ __forceinline__ void klane_request(const XT* __restrict__ W_c, const IT* __restrict__ idx, size_t row, int kb, int q,
-                                              int L, int K, XT (&wr)[kKlaneTerms], int (&ir)[kKlaneTerms]) {
-#pragma unroll
-    for (int t = 0; t < kKlaneTerms; ++t) {
-        const size_t e = row + (size_t)min(kb + q + t * L, K - 1);
-        wr[t] = W_c[e];
-        ir[t] = (int)idx[e];
-    }
-}
-
-template <int RB, typename XT, typename IT>
+template <int RB, bool GATHER, typename XT, typename IT>
 __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                    const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                    int n_active, int K, const float* __restrict__ bias, int d_out,
-                                                   float* __restrict__ y, int log2L, int rows_per_wg, int act, int direct) {
-    extern __shared__ float xs[];   // [RB][d_in]; unused when `direct` (activations gathered from global memory)
+                                                   float* __restrict__ y, int log2L, int rows_per_wg, int act) {
+    extern __shared__ float xs[];   // [RB][d_in]; unused when GATHER
     const int L = 1 << log2L;
     const int tid = threadIdx.x;
     const int q = tid & (L - 1);                      // lane within the neuron's group
@@ -100,42 +88,47 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
     const int s_begin = blockIdx.x * rows_per_wg;
     const int s_end = min(s_begin + rows_per_wg, n_slots);
 
-    // the first terms of the first stored row are requested before the staging barrier
-    int s = s_begin + grp;
-    XT wr[kKlaneTerms];
-    int ir[kKlaneTerms];
-    klane_request<XT, IT>(W_c, idx, (size_t)min(s, n_active - 1) * K, 0, q, L, K, wr, ir);
-
-    if (!direct) {
-        for (int r = 0; r < RB; ++r) {
-            const int b = min(b0 + r, B - 1);         // rows past B re-read the last row; they are never stored
-            for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = to_f32<XT>(x[(size_t)b * d_in + j]);
-        }
+    const XT* xrow[RB];                               // rows past B re-read the last row; they are never stored
+#pragma unroll
+    for (int r = 0; r < RB; ++r) xrow[r] = x + (size_t)min(b0 + r, B - 1) * d_in;
+    if (!GATHER) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+            for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = to_f32<XT>(xrow[r][j]);
         __syncthreads();
     }
 
-    for (; s < s_end; s += groups) {
+    for (int s = s_begin + grp; s < s_end; s += groups) {
         float acc[RB];
 #pragma unroll
         for (int r = 0; r < RB; ++r) acc[r] = 0.0f;
         if (s < n_active) {
-            const size_t row = (size_t)s * K;
-            for (int kb = 0; kb < K; kb += kKlaneTerms * L) {
-                XT wc[kKlaneTerms];
-                int ic[kKlaneTerms];
+            const XT* wrow = W_c + (size_t)s * K;
+            const IT* irow = idx + (size_t)s * K;
+            for (int k = q; k < K; k += kKlaneTerms * L) {
+                XT w[kKlaneTerms];
+                int c[kKlaneTerms];
 #pragma unroll
-                for (int t = 0; t < kKlaneTerms; ++t) { wc[t] = wr[t]; ic[t] = ir[t]; }
-                if (kb + kKlaneTerms * L < K) klane_request<XT, IT>(W_c, idx, row, kb + kKlaneTerms * L, q, L, K, wr, ir);
-                if (direct) {   // a second round trip (the gather needs the indices), but no staging of whole rows of x
+                for (int t = 0; t < kKlaneTerms; ++t) {   // unconditional loads (term index clamped into the row)
+                    const int kk = min(k + t * L, K - 1);
+                    w[t] = wrow[kk];
+                    c[t] = (int)irow[kk];
+                }
+                if (GATHER) {
+                    // an index outside [0, d_in) must not become an address outside x (from LDS it only reads a wrong word)
+#pragma unroll
+                    for (int t = 0; t < kKlaneTerms; ++t) c[t] = min(max(c[t], 0), d_in - 1);
+                }
+                if (GATHER) {   // a second round trip (the gather needs the indices), all of it in flight at once
                     XT xg[kKlaneTerms][RB];
 #pragma unroll
                     for (int t = 0; t < kKlaneTerms; ++t)
 #pragma unroll
-                        for (int r = 0; r < RB; ++r) xg[t][r] = x[(size_t)min(b0 + r, B - 1) * d_in + ic[t]];
+                        for (int r = 0; r < RB; ++r) xg[t][r] = xrow[r][c[t]];
 #pragma unroll
                     for (int t = 0; t < kKlaneTerms; ++t) {
-                        if (kb + q + t * L < K) {
-                            const float wv = to_f32<XT>(wc[t]);
+                        if (k + t * L < K) {
+                            const float wv = to_f32<XT>(w[t]);
 #pragma unroll
                             for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, to_f32<XT>(xg[t][r]), acc[r]);
                         }
@@ -143,18 +136,15 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
                 } else {
 #pragma unroll
                     for (int t = 0; t < kKlaneTerms; ++t) {
-                        if (kb + q + t * L < K) {
-                            const float wv = to_f32<XT>(wc[t]);
+                        if (k + t * L < K) {
+                            const float wv = to_f32<XT>(w[t]);
 #pragma unroll
-                            for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + ic[t]], acc[r]);
+                            for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + c[t]], acc[r]);
                         }
                     }
                 }
             }
         }
-        // next row's first terms: in flight during the reduction and the stores
-        const int sn = s + groups;
-        if (sn < min(s_end, n_active)) klane_request<XT, IT>(W_c, idx, (size_t)sn * K, 0, q, L, K, wr, ir);
         for (int off = L >> 1; off > 0; off >>= 1) {
 #pragma unroll
             for (int r = 0; r < RB; ++r) acc[r] += __shfl_xor(acc[r], off, kWave);
@@ -225,12 +215,12 @@ srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st) {
     return hip_ok(hipGetLastError());
 }
 
-template <int RB, typename XT, typename IT>
-static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg, int direct, hipStream_t st) {
+template <int RB, bool GATHER, typename XT, typename IT>
+static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg, hipStream_t st) {
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
-    const size_t lds = direct ? 0 : (size_t)RB * a.d_in * sizeof(float);
+    const size_t lds = GATHER ? 0 : (size_t)RB * a.d_in * sizeof(float);
     if (lds > kLdsMax) return SRIGL_ERR_UNSUPPORTED;
-    auto kern = k_fwd_klane<RB, XT, IT>;
+    auto kern = k_fwd_klane<RB, GATHER, XT, IT>;
     static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
     if (lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
@@ -241,7 +231,7 @@ static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg,
     const unsigned gy = (unsigned)((a.B + RB - 1) / RB);
     if (gy > 65535u) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c, (const IT*)a.idx,
-                       a.active, a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act, direct);
+                       a.active, a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act);
     return hip_ok(hipGetLastError());
 }
 
@@ -253,7 +243,7 @@ static KlanePlan plan_klane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
     // lanes per stored row: enough that a lane has at most ~4 terms, at least 4, at most 64
     int L = t && t->lanes_per_neuron ? t->lanes_per_neuron : 0;
-    if (L == 0) { L = 4; while (L < 64 && L * kKlaneTerms < a.K) L <<= 1; }
+    if (L == 0) L = klane_lanes(a.K);
     if (L < 1 || L > 64 || (L & (L - 1)) != 0) return p;
     // activations: gathered from global memory, or staged in LDS (the tuning can force either: 1 = gather, 2 = stage);
     // an input row too long for the LDS is always gathered
@@ -287,17 +277,21 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     if (!kp.ok) return SRIGL_ERR_UNSUPPORTED;
     const int RB = kp.RB, rows_per_wg = kp.rows_per_wg, direct = kp.direct;
     const int log2L = ilog2_floor(kp.L);
-#define SRIGL_KLANE(RBV)                                                                               \
-    return a.x_bf16 ? (a.idx_u16 ? launch_klane_t<RBV, uint16_t, uint16_t>(a, log2L, rows_per_wg, direct, st)                  \
-                                 : launch_klane_t<RBV, uint16_t, int32_t>(a, log2L, rows_per_wg, direct, st))                  \
-                    : (a.idx_u16 ? launch_klane_t<RBV, float, uint16_t>(a, log2L, rows_per_wg, direct, st)                     \
-                                 : launch_klane_t<RBV, float, int32_t>(a, log2L, rows_per_wg, direct, st))
+#define SRIGL_KLANE_G(RBV, G)                                                                           \
+    return a.x_bf16 ? (a.idx_u16 ? launch_klane_t<RBV, G, uint16_t, uint16_t>(a, log2L, rows_per_wg, st)  \
+                                 : launch_klane_t<RBV, G, uint16_t, int32_t>(a, log2L, rows_per_wg, st))  \
+                    : (a.idx_u16 ? launch_klane_t<RBV, G, float, uint16_t>(a, log2L, rows_per_wg, st)     \
+                                 : launch_klane_t<RBV, G, float, int32_t>(a, log2L, rows_per_wg, st))
+#define SRIGL_KLANE(RBV)                    \
+    if (direct) { SRIGL_KLANE_G(RBV, true); } \
+    SRIGL_KLANE_G(RBV, false)
     switch (RB) {
         case 1: SRIGL_KLANE(1);
         case 2: SRIGL_KLANE(2);
         case 4: SRIGL_KLANE(4);
         default: SRIGL_KLANE(8);
     }
+#undef SRIGL_KLANE_G
 #undef SRIGL_KLANE
 }
 

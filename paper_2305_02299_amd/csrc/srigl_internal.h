@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cmath>
 #include <stdint.h>
 
@@ -59,11 +60,12 @@ bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a);
 
 // The small-batch forward kernel takes its activations either from global memory through the vector caches (a gather:
-// no staging pass, no barrier, any d_in) or from rows of x staged in LDS.  Estimated times (us) of both, fits of timings
-// (mean of cold and cached operands) of 512- to 4096-wide layers at 80-99 % sparsity and batches of 2 to 256; they pick the
-// source of the activations, the kernel for batches of 2 to 2048 rows, and feed the choice between the condensed and the
-// structured-only form.  Layers of more than ~1.5 M stored terms no longer sit in one XCD's L2: every pass over
-// W_c / idx (one per workgroup row of the batch) then also pays for that stream.
+// no staging pass, no barrier, any d_in) or from rows of x staged in LDS.  Estimated times (us) of both: least-squares
+// fits (relative error) of the mean of cold and cached timings of 13 layer shapes, 512- to 4096-wide, 80-99 % sparse, at
+// batches of 1 to 512 (mean error 7-8 %).  They pick the source of the activations and the kernel for batches of 2 to
+// 2048 rows, and feed the choice between the condensed and the structured-only form.  Layers of more than ~1.5 M stored
+// terms no longer sit in one XCD's L2: every pass over W_c / idx (one per workgroup row of the batch) then also pays for
+// that stream.
 //
 // Batch rows per workgroup of the gathering form: a second and a fourth row pay once the pass over W_c / idx they save
 // outweighs the longer chain of gathers per lane (measured: from ~1.2 M and ~3.5 M gathered terms).
@@ -73,32 +75,38 @@ inline int klane_gather_rows(int B, int n_active, int K) {
     while (RB > 1 && RB > B) RB >>= 1;
     return RB;
 }
-// Batch rows per workgroup of the staging form (measured: one row up to batch 4 and for wide inputs, where staging two rows
-// of x costs more than the second pass over W_c / idx saves; two rows beat four and eight elsewhere).
+// Batch rows per workgroup of the staging form (measured: two rows for inputs up to 1024 wide from batch 5, else one: on
+// wider inputs the second staged row costs more than the saved pass over W_c / idx, four rows always lose).
 inline int klane_stage_rows(int B, int d_in) { return (B > 4 && d_in <= 1024) ? 2 : 1; }
+// Lanes that share one stored row: enough that a lane has at most ~4 terms, at least 4, at most a wavefront.
+inline int klane_lanes(int K) {
+    int L = 4;
+    while (L < 64 && L * 4 < K) L <<= 1;
+    return L;
+}
 
-// Gathering: a fixed part plus a part per gathered term that grows with the number of distinct 128-byte lines of x a
-// wavefront's gather touches (rho = stored terms per line of a row of x: a lane group's consecutive terms share lines
-// when rho is large) and with how far the rows of x a workgroup gathers from overflow the vector L1 (the width factor):
-// ~1.0 us per million terms at 90 % sparsity, 1.3 at 99 % on 768- to 1024-wide inputs, 2.0 at 99 % on 4096-wide ones.
+// Gathering: a fixed part plus ~1 us per million gathered terms, more where a wavefront's gather touches many distinct
+// 128-byte lines of x (rho = stored terms per line of a row of x; a lane group's consecutive terms share lines when rho
+// is large) and the rows gathered from overflow the vector L1 (4096-wide inputs at 99 % sparsity: 2 us per million).
 inline double klane_gather_estimate_us(int B, int d_in, int n_active, int K) {
     const double terms = (double)n_active * K;
     const double rho = 32.0 * K / (d_in > 0 ? d_in : 1);
     const double lines_per_term = rho > 1e-6 ? (1.0 - exp(-rho)) / rho : 1.0;
-    const double width = d_in <= 1024 ? 0.4 : (d_in <= 3072 ? 0.7 : 1.0);
+    const double width = d_in <= 1024 ? 0.19 : (d_in <= 3072 ? 0.22 : 0.93);
     const int RB = klane_gather_rows(B, n_active, K);
-    return 2.6 + (0.8 + 1.4 * lines_per_term * width) * 1e-6 * B * terms + (terms > 1.5e6 ? 3.0e-6 * terms * ((B + RB - 1) / RB) : 0.0);
+    return 2.5 + (0.96 + width * lines_per_term) * 1e-6 * B * terms + (terms > 1.5e6 ? 0.31e-6 * terms * ((B + RB - 1) / RB) : 0.0);
 }
-// Staging: a fixed part that grows with the row of x every workgroup stages, plus a part per term slot (K rounded up to the
-// slots one request of a lane group covers).
+// Staging: a fixed part, the rows of x every workgroup copies into its LDS (at most 2048 workgroups), and the terms: on
+// inputs up to 1024 wide mostly per term slot (K rounded up to the slots one request of a lane group covers), on wider
+// ones per stored term.
 inline double klane_stage_estimate_us(int B, int d_in, int n_active, int K) {
-    int L = 4;
-    while (L < 64 && L * 4 < K) L <<= 1;
-    const int req = L * 4;   // term slots one request of a lane group covers (4 terms per lane)
+    const int L = klane_lanes(K), req = L * 4;   // term slots one request of a lane group covers (4 terms per lane)
     const double slots = (double)B * n_active * ((K + req - 1) / req * req);
     const double terms = (double)n_active * K;
     const int RB = klane_stage_rows(B, d_in);
-    return 3.0 + 0.0007 * d_in + (d_in <= 1024 ? 0.65e-6 : 0.75e-6) * slots + (terms > 1.5e6 ? 3.0e-6 * terms * ((B + RB - 1) / RB) : 0.0);
+    const double wgs = std::min(2048.0, ceil((double)n_active / (256 / L)) * ((B + RB - 1) / RB));
+    const double per_term = d_in <= 1024 ? 0.30e-6 * slots + 0.15e-6 * B * terms : 1.0e-6 * B * terms;
+    return 2.7 + 0.00046 * d_in + 4.6e-8 * wgs * RB * d_in * 4.0 + per_term + (terms > 1.5e6 ? 0.40e-6 * terms * ((B + RB - 1) / RB) : 0.0);
 }
 inline bool klane_row_fits_lds(int d_in) { return (size_t)d_in * sizeof(float) <= kLdsMax; }
 inline bool klane_gathers(int B, int d_in, int n_active, int K) {

@@ -27,8 +27,10 @@ def csr_of(W, mask):
 
 @pytest.mark.parametrize("act", [0, 2])
 @pytest.mark.parametrize("shape", [(37, 23, 1, 0.2), (768, 300, 1, 0.1), (768, 300, 7, 0.1), (3072, 200, 3, 0.1), (3072, 200, 33, 0.02),
-                                   (200, 1000, 70, 0.5), (64, 5, 2, 1.0)])
+                                   (200, 1000, 70, 0.5), (64, 5, 2, 1.0), (512, 2048, 400, 0.02), (49152, 40, 3, 0.002)])
 def test_unstructured_masks(B_, shape, act):
+    """Small cases gather their activations from global memory; 512 -> 2048 at 2 % and 400 rows stages rows of x in LDS; the
+    49152-wide input does not fit the LDS and can only be gathered."""
     d_in, d_out, B, density = shape
     rng = np.random.default_rng(d_in + d_out + B)
     W = rng.normal(0, 1 / np.sqrt(max(density * d_in, 1)), (d_out, d_in)).astype(np.float32)
