@@ -136,6 +136,8 @@ typedef struct {
     int32_t term_slices;      /* ROWLANE: 1, 2 or 4 groups of lanes that work on different terms of a stored
                                  row at once (batch tile = 64 * rows_per_lane / term_slices rows)           */
     int32_t direct_gather;    /* KLANE: 1 = gather activations from global memory, 2 = stage rows of x in LDS     */
+    int32_t xcd_order;        /* ROWLANE: which workgroups share an XCD (one L2): 1 = all batch tiles of a group of
+                                 stored rows (W_c / idx fetched once, x by every XCD), 2 = all groups of a batch tile */
 } srigl_fwd_tuning;
 
 /* Same, with the algorithm and launch shape forced (for tests and measurements).  tuning may be
@@ -158,7 +160,7 @@ typedef struct {
     int32_t lanes_per_neuron, rows_per_block;                                 /* KLANE, else 0            */
     int64_t workgroups;       /* workgroups that do work                                                    */
     int32_t direct_gather;    /* KLANE: 1 = activations gathered from global memory, 0 = rows of x staged in LDS */
-    int32_t reserved;
+    int32_t xcd_order;        /* ROWLANE: 1 or 2 as in srigl_fwd_tuning                                     */
 } srigl_fwd_plan;
 srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
                                   int32_t has_active, int32_t has_seg, srigl_fwd_plan* plan);

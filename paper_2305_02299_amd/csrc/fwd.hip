@@ -364,10 +364,25 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     // the measured ranking of eight launch shapes each at batches 320..768 of three layers.
     const double fixed = p.H == 1 ? 0.15 * a.d_in * p.R : 2.0 * a.K;
     const double per_row = (double)a.K * (p.H == 1 && p.R == 2 ? 1.3 : 1.0);
+    // which workgroups share an XCD: the order that makes the 8 L2s fetch fewer bytes in all (all of x by each XCD, or
+    // all of W_c / idx by each), unless it needs more rounds per XCD; the tuning can force either
+    const int xo = t ? t->xcd_order : 0;
+    if (xo < 0 || xo > 2) return p;
+    const double x_bytes = (double)a.B * a.d_in * (a.x_bf16 ? 2 : 4);
+    const double w_bytes = (double)a.n_active * a.K * ((a.x_bf16 ? 2 : 4) + (a.idx_u16 ? 2 : 4));
+    auto rounds = [&](long long groups, bool by_tiles) {
+        const long long per_xcd = by_tiles ? ((p.n_btiles + 7) / 8) * groups : ((groups + 7) / 8) * p.n_btiles;
+        return (per_xcd + 31) / 32;
+    };
+    auto by_tiles = [&](long long groups) {
+        if (xo) return xo == 2;
+        // (measured: 3-8 % at 512 rows and more on 3072- and 4096-wide inputs, 20 % at 99 % sparsity; nothing or a loss
+        // with fewer than two batch tiles per XCD)
+        return x_bytes > w_bytes && p.n_btiles >= 16 && rounds(groups, true) <= rounds(groups, false);
+    };
     auto shape_cost = [&](int c) {
         const long long groups = (n_slots + p.NW * c - 1) / (p.NW * c);
-        const long long per_xcd = ((groups + 7) / 8) * p.n_btiles;
-        return (double)((per_xcd + 31) / 32) * (fixed + c * per_row) * (p.H == 1 && c >= 6 ? 1.1 : 1.0);
+        return (double)rounds(groups, by_tiles(groups)) * (fixed + c * per_row) * (p.H == 1 && c >= 6 ? 1.1 : 1.0);
     };
     int npw = t && t->neurons_per_wave ? t->neurons_per_wave : 0;
     if (npw == 0) {
@@ -386,6 +401,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     p.cost = shape_cost(npw);
     p.KPRE = rowlane_kpre(npw);
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
+    p.bt_major = by_tiles(p.n_groups) ? 1 : 0;
     // the result tile sits behind the activation tile when both fit (no barrier between the last term and the
     // transposed write), else it reuses the activation tile's space
     const size_t out_tile = (size_t)BT * (p.NW * npw + 1) * sizeof(float);
@@ -598,7 +614,7 @@ srigl_status srigl_fwd_plan_query_algo(int32_t B, int32_t d_in, int32_t n_active
         const RowlanePlan p = plan_rowlane(a, tuning);
         if (!p.ok) return SRIGL_ERR_UNSUPPORTED;
         plan->rows_per_lane = p.R; plan->term_slices = p.H; plan->waves = p.NW; plan->neurons_per_wave = p.NPW;
-        plan->chunk_cols = p.C; plan->workgroups = (int64_t)p.n_groups * p.n_btiles;
+        plan->chunk_cols = p.C; plan->workgroups = (int64_t)p.n_groups * p.n_btiles; plan->xcd_order = p.bt_major ? 2 : 1;
     } else if (algo == SRIGL_FWD_KLANE) {
         const KlanePlan p = plan_klane(a, tuning);
         if (!p.ok) return SRIGL_ERR_UNSUPPORTED;

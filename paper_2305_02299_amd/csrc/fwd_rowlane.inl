@@ -182,7 +182,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                                                       const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
-                                                      int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act) {
+                                                      int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act, int bt_major) {
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
@@ -191,14 +191,22 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     constexpr int TB = kBlock * H;           // terms per block (16 steps of H terms)
     using V = typename RowVec<R>::type;
 
-    // XCD-aware decode: consecutive workgroup ids go to different XCDs (8 of them), so the id modulo 8
-    // selects the XCD; all batch tiles of one neuron group are given to the same XCD, whose L2 then
-    // holds that group's W_c / idx once.
+    // XCD-aware decode: consecutive workgroup ids go to different XCDs (8 of them), so the id modulo 8 selects the XCD.
+    // Either all batch tiles of one group of stored rows are given to the same XCD, whose L2 then holds that group's
+    // W_c / idx once while every XCD fetches all of x; or (bt_major) all groups of one batch tile, so that an XCD fetches
+    // only its own rows of x and every XCD all of W_c / idx.  The host picks the order that fetches fewer bytes.
     const int wg = blockIdx.x;
     const int xcd = wg & 7, inx = wg >> 3;
-    const int bt = inx % n_btiles;
-    const int g = (inx / n_btiles) * 8 + xcd;
-    if (g >= n_groups) return;
+    int bt, g;
+    if (bt_major) {
+        g = inx % n_groups;
+        bt = (inx / n_groups) * 8 + xcd;
+        if (bt >= n_btiles) return;
+    } else {
+        bt = inx % n_btiles;
+        g = (inx / n_btiles) * 8 + xcd;
+        if (g >= n_groups) return;
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -435,11 +443,11 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
             return SRIGL_ERR_HIP;
         lds_allowed = kLdsMax;
     }
-    const long long blocks = 8LL * ((p.n_groups + 7) / 8) * p.n_btiles;
+    const long long blocks = p.bt_major ? 8LL * ((p.n_btiles + 7) / 8) * p.n_groups : 8LL * ((p.n_groups + 7) / 8) * p.n_btiles;
     if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
                        (const IT*)a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
-                       p.n_groups, p.out_off, a.act);
+                       p.n_groups, p.out_off, a.act, p.bt_major);
     return hip_ok(hipGetLastError());
 }
 

@@ -34,6 +34,7 @@ struct FwdArgs {
 // Launch shape of the ROWLANE kernel, decided on the host.
 struct RowlanePlan {
     int R, H, NW, NPW, KPRE, C, n_chunks, n_btiles, n_groups;
+    int bt_major;  // 1: an XCD owns batch tiles (and runs every group of stored rows on them), 0: it owns groups of stored rows
     size_t lds;
     double cost;  // the planner's estimate for this shape (arbitrary units), to compare shapes
     int out_off;  // word offset of the result tile in LDS (0: it reuses the activation tile after a barrier)

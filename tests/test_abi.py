@@ -32,8 +32,14 @@ def test_host_only_entry_points():
     assert binding.srigl_seg_stride(768) == 13 and binding.srigl_seg_stride(1) == 2 and binding.srigl_seg_stride(0) == 1
     assert binding.srigl_workspace_bytes(3072) >= 2 * 4 * 3072
     assert binding.status_str(0) == "ok" and "fan" in binding.status_str(2).lower() or "K" in binding.status_str(2)
-    s = ctypes.sizeof(binding.FwdTuning)
-    assert s == 32
+    # the ctypes mirrors hold exactly the fields, in order, that the header's structs declare
+    import re
+    header = open(os.path.join(ROOT, "include", "srigl.h")).read()
+    for struct, mirror in (("srigl_fwd_tuning", binding.FwdTuning), ("srigl_fwd_plan", binding.FwdPlan)):
+        body = header[:header.index("} %s;" % struct)]
+        body = re.sub(r"/\*.*?\*/", "", body[body.rindex("typedef struct {"):], flags=re.S)
+        names = [n.strip() for decl in re.findall(r"int(?:32|64)_t\s+([^;]+);", body) for n in decl.split(",")]
+        assert names == [n for n, _ in mirror._fields_], struct
 
 
 def test_product_does_not_import_the_oracle():

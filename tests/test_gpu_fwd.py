@@ -310,3 +310,14 @@ def test_small_batch_kernel_gathered_and_staged_activations(B, rb, gather, dtype
     L = si.make_layer(320, 200, 77, B, ablate_frac=0.15, seed=B + 10 * rb, dtype=dtype)
     worst = check_layer(L, B_.FWD_KLANE, dict(direct_gather=gather, rows_per_block=rb))
     assert worst < (TOL_BF16 if dtype == "bf16" else 2e-6)
+
+
+@pytest.mark.parametrize("xcd_order", [1, 2])
+@pytest.mark.parametrize("shape", [(768, 300, 77, 300), (3072, 200, 307, 200), (320, 130, 40, 1100), (2048, 96, 64, 530)])
+def test_batched_kernel_either_xcd_order(shape, xcd_order):
+    """Both assignments of workgroups to XCDs (by groups of stored rows, by batch tiles), with tile and group counts that are
+    not multiples of eight, so that some workgroup ids of the padded grid have nothing to do."""
+    d_in, d_out, K, B = shape
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=0.2, seed=d_in + B)
+    worst = check_layer(L, B_.FWD_ROWLANE, dict(xcd_order=xcd_order))
+    assert worst < 2e-6

@@ -65,6 +65,15 @@ def test_rounds_are_counted_per_xcd():
     assert (p["rows_per_lane"], p["neurons_per_wave"]) == (2, 4)
 
 
+def test_which_workgroups_share_an_xcd():
+    """Each of the 8 XCDs has its own L2: either every XCD fetches all of x (and one group's W_c / idx), or its own batch tiles
+    of x and all of W_c / idx; the batched kernel takes the order that fetches fewer bytes once an XCD has two tiles."""
+    assert plan(256, 768, 3072, 77)["xcd_order"] == 1          # x 0.8 MB < W_c + idx 1.9 MB; only four batch tiles
+    assert plan(2048, 768, 3072, 77)["xcd_order"] == 2         # x 6.3 MB; 65.9 -> 62.0 us
+    assert plan(256, 3072, 768, 307, n_active=538)["xcd_order"] == 2   # 16 tiles of 16 rows; x 3.1 MB > 1.3 MB
+    assert plan(128, 2048, 512, 205, algo=B_.FWD_ROWLANE)["xcd_order"] == 1   # one tile per XCD: 9.6 vs 10.4 us
+
+
 def test_very_sparse_layers_stay_on_the_small_batch_kernel_at_larger_batches():
     assert plan(256, 3072, 768, 31)["algo"] == B_.FWD_KLANE           # 11.1 / 7.7 us (cold / cached) vs 15.5 / 14.3
     assert plan(96, 768, 3072, 8)["algo"] == B_.FWD_KLANE             # 6.0 / 5.0 vs 8.1 / 7.4
