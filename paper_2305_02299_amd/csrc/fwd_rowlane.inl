@@ -18,6 +18,10 @@ static __device__ long long g_timeline[16 * 4096];
 template <typename XT> __device__ __forceinline__ float rl_to_f32(XT v);
 template <> __device__ __forceinline__ float rl_to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float rl_to_f32<uint16_t>(uint16_t v) { return bf16_bits_to_float(v); }
+// the value lane `byte_addr / 4` holds (every lane names its own source lane)
+__device__ __forceinline__ float lane_fetch(float v, int byte_addr) { return __int_as_float(__builtin_amdgcn_ds_bpermute(byte_addr, __float_as_int(v))); }
+__device__ __forceinline__ uint16_t lane_fetch(uint16_t v, int byte_addr) { return (uint16_t)__builtin_amdgcn_ds_bpermute(byte_addr, (int)v); }
+__device__ __forceinline__ int lane_fetch(int v, int byte_addr) { return __builtin_amdgcn_ds_bpermute(byte_addr, v); }
 __device__ __forceinline__ float rl_bias_at(const float* __restrict__ bias, int col) { return bias ? bias[col] : 0.0f; }
 
 // ------------------------------------------------------------------------------------------------
@@ -155,23 +159,31 @@ __device__ __forceinline__ void pipe_groups(float (&acc)[R], const float (&wv)[N
     group_fmacs<R, G % GPB>(acc, wv[G / GPB], cur);
 }
 
-// One block of terms of stored-row data starting at term index t0 (wave-uniform): the lane at position l16 of
-// slice p requests term t0 + tofs, tofs = H * l16 + p (16 * H consecutive terms per block, one vector load per
-// array).  The loads are unconditional (the term index is clamped into the arrays) and nothing here consumes their
-// result, so that they stay in flight; finish_terms() turns the raw words into a weight and an LDS byte offset
-// when the block is about to be used.
+// One block of terms of stored-row data starting at term index t0 (wave-uniform): 16 * H consecutive terms, one vector
+// load per array.  The lane at position l16 of slice p works on term t0 + tofs, tofs = H * l16 + p (so that a partly
+// filled block ends after ceil(n / H) of its 16 steps).  With one slice the lanes load their own terms (16 consecutive
+// words, four copies); with 2 or 4 slices that pattern would be a stride of H words across the lanes of a quad, which
+// the vector L1 serves as H times the accesses (counters: 5.0 M tag lookups per call on the 3072-wide layer against
+// 1.8 M on the 768-wide one), so there lane l loads term t0 + lofs, lofs = l mod 16H (consecutive words), and
+// finish_terms() fetches the lane's own term from lane tofs with one cross-lane read per array.  The loads are
+// unconditional (the term index is clamped into the arrays) and nothing here consumes their result, so that they stay
+// in flight; finish_terms() turns the raw words into a weight and an LDS byte offset when the block is about to be used.
 template <typename XT, typename IT>
-__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const IT* __restrict__ idx, int t0, int tofs, int t_last,
+__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const IT* __restrict__ idx, int t0, int lofs, int t_last,
                                               XT& w_raw, int& i_raw) {
     // 32-bit unsigned byte offsets from the (wave-uniform) array bases: one address instruction per load
-    const unsigned t = (unsigned)min(t0 + tofs, t_last);
+    const unsigned t = (unsigned)min(t0 + lofs, t_last);
     w_raw = *reinterpret_cast<const XT*>(reinterpret_cast<const char*>(W_c) + t * (unsigned)sizeof(XT));
     i_raw = (int)*reinterpret_cast<const IT*>(reinterpret_cast<const char*>(idx) + t * (unsigned)sizeof(IT));
 }
 // n_valid (wave-uniform, may be <= 0) of the block's terms are real; the others become (weight 0, all-zero column).
-template <typename XT>
+template <typename XT, int H>
 __device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, int tofs, int off_mul, int off_add, int zero_off,
                                              float& wv, int& ov) {
+    if (H > 1) {
+        w_raw = lane_fetch(w_raw, tofs * 4);
+        i_raw = lane_fetch(i_raw, tofs * 4);
+    }
     const bool real = tofs < n_valid;
     wv = real ? rl_to_f32<XT>(w_raw) : 0.0f;
     ov = real ? i_raw * off_mul + off_add : zero_off;
@@ -212,6 +224,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     const int lane = tid & (kWave - 1);
     const int rowl = lane & (LR - 1);        // this lane's first row inside the tile is rowl * R
     const int tofs = H * (lane & (kBlock - 1)) + lane / LR;   // this lane's term inside a block
+    const int lofs = H == 1 ? tofs : (lane & (kBlock * H - 1));   // the term this lane loads
     const int wv_id = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nw = blockDim.x >> 6;
     const int NG = nw * NPW;                 // stored rows (slots) per workgroup
@@ -287,7 +300,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     {                                                                                                           \
         const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
         _Pragma("unroll") for (int p = 0; p < KPRE; ++p)                                                        \
-            request_terms<XT, IT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, tofs, t_last, rw[i][p], ri[i][p]);      \
+            request_terms<XT, IT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, lofs, t_last, rw[i][p], ri[i][p]);      \
     }
 
     float acc[NPW][R];
@@ -303,7 +316,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
-        for (int p = 0; p < KPRE; ++p) request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, tofs, t_last, rw[i][p], ri[i][p]);
+        for (int p = 0; p < KPRE; ++p) request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, lofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
     SRIGL_STAMP(1)
@@ -334,7 +347,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 int po[KPRE];
 #pragma unroll
                 for (int p = 0; p < KPRE; ++p)
-                    finish_terms<XT>(rw[i][p], ri[i][p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p]);
+                    finish_terms<XT, H>(rw[i][p], ri[i][p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p]);
                 group_reads<R, 0>(xa, po[0], xb);
                 pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, (n_terms + H - 1) / H, xa, xc);
                 // long ranges: the remaining blocks, one at a time, each requested one block ahead
@@ -342,12 +355,12 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                     const int row = (s0 + i) * K + k0n[i];
                     XT wr;
                     int ir;
-                    request_terms<XT, IT>(W_c, idx, row + KPRE * TB, tofs, t_last, wr, ir);
+                    request_terms<XT, IT>(W_c, idx, row + KPRE * TB, lofs, t_last, wr, ir);
                     for (int kb = KPRE * TB; kb < n_terms; kb += TB) {
                         float wc[1];
                         int oc[1];
-                        finish_terms<XT>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
-                        if (kb + TB < n_terms) request_terms<XT, IT>(W_c, idx, row + kb + TB, tofs, t_last, wr, ir);
+                        finish_terms<XT, H>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
+                        if (kb + TB < n_terms) request_terms<XT, IT>(W_c, idx, row + kb + TB, lofs, t_last, wr, ir);
                         group_reads<R, 0>(xa, oc[0], xb);
                         pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, (n_terms - kb + H - 1) / H, xa, xc);
                     }
