@@ -439,41 +439,58 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
     return a.x_bf16 ? launch_rowlane_bf16(a, p, st) : launch_rowlane_f32(a, p, st);
 }
 
-// The library's own choice of kernel: the smaller of two estimated times.  The small-batch kernel's estimate (gathered or
-// staged activations, whichever is less) grows with the batch times the stored terms; the batched kernel below one or two row
-// tiles costs about the same at any batch, mostly staging x (grows with d_in) plus its share of the stored terms.  Fits of
-// timings (mean of cold and cached operands) of 512- to 4096-wide layers at 80-99 % sparsity; a single row always takes the
-// small-batch kernel, above 2048 rows the batched kernel always wins.
+// Estimated time (us) of the batched kernel in launch shape p: a fixed part, and per round of 256 workgroups the chunks
+// of columns it walks (two barriers and a staging burst each), the bytes of x a workgroup stages, the 16-step blocks of
+// terms a wavefront walks (a partly filled block costs a whole one) and the result tile; large layers also the stream of
+// W_c / idx.  A least-squares fit (relative error, mean 8 %) of the mean of cold and cached timings of 13 layer shapes,
+// 512- to 4096-wide, 80-99 % sparse, at batches 2 to 1024.
+static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
+    const int BT = kWave * p.R / p.H;
+    const double rounds = std::max(1.0, (double)p.n_btiles * p.n_groups / 256.0);
+    const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
+    const double terms = (double)a.n_active * a.K;
+    return 1.94 + rounds * (1.59 * p.n_chunks + 5.72e-6 * BT * a.d_in * 4.0 + 0.032 * steps + 1.0e-4 * BT * p.NW * p.NPW * 4.0) +
+           (terms > 1.5e6 ? 0.76e-6 * terms : 0.0);
+}
+
+// The library's own choice of kernel: the smallest of the estimated times of the small-batch kernel (gathered or staged
+// activations) and of the batched kernel in the launch shape it would take.  A single row always takes the small-batch
+// kernel, above 2048 rows the batched kernel always wins.
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
     const int B = a.B, d_in = a.d_in, n_active = a.n_active, K = a.K;
     bool batched = B > 16;
     if (B > 1 && B <= 2048 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
-        const double small_us = klane_estimate_us(B, d_in, n_active, K);
-        // up to 64 rows: staging x (grows with d_in) plus the stored terms (16-row tiles of inputs wider than 2048 with few
-        // stored rows: three times the cost per term; large layers: the stream of W_c / idx); once the row tiles times the
-        // groups of stored rows exceed the compute units, a wavefront takes `more` times the stored rows and everything
-        // but the launch grows with it.  Above 64 rows: a fit of 96 to 512 rows (staging x, the terms, writing y), where
-        // only layers with a few dozen terms per row still favour the small-batch kernel.
-        const double terms = (double)n_active * K;
-        double more = 1.0;
-        if (B <= 64) {
-            const RowlanePlan rp = plan_rowlane(a, nullptr);
-            if (rp.ok) {
-                const int n_slots = a.active ? n_active + 1 : n_active;
-                const int one_tile = std::max(1, (n_slots + rp.NW * 256 - 1) / (rp.NW * 256));
-                more = std::max(1.0, (double)rp.NPW / one_tile);
-            }
-        }
-        const double batched_us = B <= 64 ? 4.3 + (1.0 + 0.85 * (more - 1.0)) * (0.0014 * d_in + (d_in > 2048 && n_active <= 1024 ? 4.5e-6 : 1.5e-6) * terms +
-                                                                                (n_active <= 1024 ? 0.5 : 0.0)) + (terms > 1.5e6 ? 3.0e-6 * terms : 0.0)
-                                          : 4.4 + 0.0015 * d_in + 7e-6 * d_in * B + 8e-8 * B * terms + 2.5e-6 * B * (double)a.d_out;
-        batched = batched_us < small_us;
+        const RowlanePlan rp = plan_rowlane(a, nullptr);
+        batched = rp.ok && rowlane_estimate_us(a, rp) < klane_estimate_us(B, d_in, n_active, K);
     }
     const bool can_batch = rowlane_supported(a, nullptr);
     if (batched && can_batch) return SRIGL_FWD_ROWLANE;
     if (plan_klane(a, nullptr).ok) return SRIGL_FWD_KLANE;
     return can_batch ? SRIGL_FWD_ROWLANE : SRIGL_FWD_GENERIC;
+}
+
+// stand-ins for the device arrays of a call of these sizes: the planner looks at their alignment and at which ones are
+// present, never at their contents
+static FwdArgs standin_args(int B, int d_in, int n_active, int K, int d_out, bool bf16, bool has_active, bool has_seg) {
+    alignas(64) static const unsigned char aligned[64] = {0};
+    FwdArgs a;
+    a.x = aligned; a.x_bf16 = bf16; a.B = B; a.d_in = d_in; a.W_c = aligned; a.idx = aligned; a.idx_u16 = 0;
+    a.active = has_active ? reinterpret_cast<const int32_t*>(aligned) : nullptr;
+    a.n_active = n_active; a.K = K; a.bias = nullptr; a.d_out = d_out; a.y = nullptr;
+    a.seg = has_seg ? reinterpret_cast<const uint16_t*>(aligned) : nullptr;
+    a.seg_stride = srigl_seg_stride(d_in);
+    a.act = SRIGL_ACT_NONE;
+    return a;
+}
+
+double condensed_estimate_us(int B, int d_in, int n_active, int K, int d_out, bool bf16, bool has_active) {
+    if (B <= 0 || n_active <= 0 || K <= 0 || d_in <= 0) return 2.0;
+    const FwdArgs a = standin_args(B, d_in, n_active, K, d_out, bf16, has_active, true);
+    const RowlanePlan rp = plan_rowlane(a, nullptr);
+    const double batched = rp.ok ? rowlane_estimate_us(a, rp) : 1e30;
+    if (B > 2048 && rp.ok) return batched;
+    return std::min(batched, klane_estimate_us(B, d_in, n_active, K));
 }
 
 }  // namespace srigl
@@ -598,16 +615,7 @@ srigl_status srigl_fwd_plan_query_algo(int32_t B, int32_t d_in, int32_t n_active
     if (dtype != SRIGL_F32 && dtype != SRIGL_BF16) return SRIGL_ERR_INVALID_ARG;
     *plan = srigl_fwd_plan{};
     if (B == 0 || d_out == 0 || n_active == 0 || K == 0) return SRIGL_OK;   // nothing to gather: no forward kernel runs
-    // stand-ins for the device arrays: the planner looks at their alignment and at which ones are present, never at
-    // their contents
-    alignas(64) static const unsigned char aligned[64] = {0};
-    FwdArgs a;
-    a.x = aligned; a.x_bf16 = (dtype == SRIGL_BF16); a.B = B; a.d_in = d_in; a.W_c = aligned; a.idx = aligned; a.idx_u16 = 0;
-    a.active = has_active ? reinterpret_cast<const int32_t*>(aligned) : nullptr;
-    a.n_active = n_active; a.K = K; a.bias = nullptr; a.d_out = d_out; a.y = nullptr;
-    a.seg = has_seg ? reinterpret_cast<const uint16_t*>(aligned) : nullptr;
-    a.seg_stride = srigl_seg_stride(d_in);
-    a.act = SRIGL_ACT_NONE;
+    const FwdArgs a = standin_args(B, d_in, n_active, K, d_out, dtype == SRIGL_BF16, has_active != 0, has_seg != 0);
     const srigl_fwd_algo algo = forced == SRIGL_FWD_AUTO ? choose_fwd_algo(a) : forced;
     plan->algo = (int32_t)algo;
     if (algo == SRIGL_FWD_ROWLANE) {

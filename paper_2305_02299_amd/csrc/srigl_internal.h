@@ -59,6 +59,8 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
 srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
 bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a);
+// Estimated time (us) of the condensed forward call of these sizes in the kernel the library's own choice takes.
+double condensed_estimate_us(int B, int d_in, int n_active, int K, int d_out, bool bf16, bool has_active);
 
 // The small-batch forward kernel takes its activations either from global memory through the vector caches (a gather:
 // no staging pass, no barrier, any d_in) or from rows of x staged in LDS.  Estimated times (us) of both: least-squares

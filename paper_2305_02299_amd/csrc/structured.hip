@@ -451,22 +451,15 @@ srigl_status srigl_densify(const void* W_c, srigl_dtype w_dtype, const int32_t* 
     return hip_ok(hipGetLastError());
 }
 
-// Estimates in microseconds, calibrated on MI355X measurements of both kernels (fp32 and bf16 storage, batches 1..2048,
-// 768x3072 / 3072x768 / 4096x16384 layers, 80-99 % sparsity):
-//   condensed  ~ 6.3 + B (d_in + d_out) / 2.2e5     (launch, staging the activations, writing the result)
-//                    + B n_active K / 1.0e7          (gathered multiply-adds; 1.7e7 for batches >= 512 with K >= 32)
-//                batches <= 16 run the lane-per-term kernel: 2.6 + B n_active K / 1.4e6, never above the line above;
-//                batches of 2 to 2048 rows: also never above that kernel's own estimate (klane_estimate_us)
+// Estimates in microseconds, calibrated on MI355X measurements of both forms (fp32 and bf16 storage, batches 1..2048,
+// 512- to 4096-wide layers, 80-99 % sparsity):
+//   condensed  = the estimate of the forward kernel the library's own choice takes for these sizes (condensed_estimate_us)
 //   structured ~ 3.5 + d_in x (rounds of tiles x nanoseconds per element of d_in of the chosen tile) / 1000
 //                  + 4 B d_out / 4.5e6              (writing the result at HBM speed)
 srigl_representation srigl_choose_representation(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out,
                                                  srigl_dtype dtype, float* est_condensed_us, float* est_structured_us) {
-    const double b = B > 0 ? B : 0, n = n_active > 0 ? n_active : 0, k = K > 0 ? K : 0;
-    const double terms = b * n * k;
-    const bool two_rows = B >= 512 && K >= 32;   // the batched kernel's 128-row tiles (about 1.7x the term rate)
-    double cond = 6.3 + b * ((double)d_in + d_out) / 2.2e5 + terms / (two_rows ? 1.7e7 : 1.0e7);
-    if (B <= 16) cond = fmin(cond, 2.6 + terms / 1.4e6);
-    if (B > 1 && B <= 2048 && d_in % 16 == 0) cond = fmin(cond, klane_estimate_us(B, d_in, n_active, K));
+    const double b = B > 0 ? B : 0;
+    const double cond = condensed_estimate_us(B, d_in, n_active, K, d_out, dtype == SRIGL_BF16, n_active < d_out);
     double ns_per_k = 0.0;
     const bool f32 = dtype == SRIGL_F32;
     choose_tile(B > 0 ? B : 1, n_active > 0 ? n_active : 1, f32, &ns_per_k);
