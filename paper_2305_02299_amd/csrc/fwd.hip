@@ -412,20 +412,46 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     return p;
 }
 
-// Two batch rows per lane (128-row tiles) halve the LDS reads per multiply-add (one 8-byte read feeds two rows), but also
-// halve the number of workgroups and double the staging of each: taken when nothing is forced, the rows are long enough for
-// the term loop to matter (slower at fan-in 8) and the cost of its best launch shape is below that of the best 64-row shape.
+// Estimated time (us) of the batched kernel in launch shape p: a fixed part, and per round of 256 workgroups the chunks
+// of columns it walks (two barriers and a staging burst each), the bytes of x a workgroup stages, the 16-step blocks of
+// terms a wavefront walks (a partly filled block costs a whole one; a step of four term slices costs 1.6 times a step of
+// one: its LDS reads collide) and the result tile; large layers also the stream of W_c / idx.  A least-squares fit
+// (relative error, mean 6 %) of the mean of cold and cached timings of 326 points: 15 layer shapes, 512- to 4096-wide,
+// 80-99 % sparse, at batches 2 to 1024, every term-slice count on seven of them.
+static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
+    const int BT = kWave * p.R / p.H;
+    const double rounds = std::max(1.0, (double)p.n_btiles * p.n_groups / 256.0);
+    const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
+    const double per_step = p.R == 2 ? 0.0216 : (p.H == 1 ? 0.0226 : (p.H == 2 ? 0.0256 : 0.0370));
+    const double terms = (double)a.n_active * a.K;
+    return 1.88 + rounds * (1.63 * p.n_chunks + 3.83e-6 * BT * a.d_in * 4.0 + per_step * steps + 2.13e-4 * BT * p.NW * p.NPW * 4.0) +
+           (terms > 1.5e6 ? 0.28e-6 * terms : 0.0);
+}
+
+// The tile: 64 batch rows x 1 term slice, 32 x 2, 16 x 4, or 128 rows with two rows per lane (one 8-byte LDS read feeds
+// two rows, but half the workgroups each staging twice the tile; needs rows long enough for the term loop to matter:
+// slower at fan-in 8).  With nothing forced the library takes the shape with the smallest estimated time; a forced
+// part keeps the rules the other part had before the estimate existed.
 static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
-    const RowlanePlan one = plan_rowlane_with(a, t);
     const bool forced = t && (t->rows_per_lane || t->term_slices);
-    if (forced || !one.ok || one.H != 1 || a.K < kRowlaneTwoRowsMinK) return one;
-    srigl_fwd_tuning two{};
-    if (t) two = *t;
-    two.rows_per_lane = 2;
-    two.term_slices = 1;
-    const RowlanePlan p2 = plan_rowlane_with(a, &two);
-    if (p2.ok && p2.cost < one.cost) return p2;
-    return one;
+    if (forced) return plan_rowlane_with(a, t);
+    RowlanePlan best{};
+    best.ok = false;
+    double best_us = 0.0;
+    // rows per lane, term slices; a later shape must be 5 % ahead of an earlier one (the estimates are good to about that)
+    static const int shapes[4][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}};
+    for (int i = 0; i < 4; ++i) {
+        if (shapes[i][0] == 2 && a.K < kRowlaneTwoRowsMinK) continue;
+        srigl_fwd_tuning shape{};
+        if (t) shape = *t;
+        shape.rows_per_lane = shapes[i][0];
+        shape.term_slices = shapes[i][1];
+        const RowlanePlan p = plan_rowlane_with(a, &shape);
+        if (!p.ok) continue;
+        const double us = rowlane_estimate_us(a, p);
+        if (!best.ok || us < 0.95 * best_us) { best = p; best_us = us; }
+    }
+    return best;
 }
 
 bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t) { return plan_rowlane(a, t).ok; }
@@ -437,20 +463,6 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
     if (!p.ok) return SRIGL_ERR_UNSUPPORTED;
     if (a.idx_u16) return a.x_bf16 ? launch_rowlane_bf16_i16(a, p, st) : launch_rowlane_f32_i16(a, p, st);
     return a.x_bf16 ? launch_rowlane_bf16(a, p, st) : launch_rowlane_f32(a, p, st);
-}
-
-// Estimated time (us) of the batched kernel in launch shape p: a fixed part, and per round of 256 workgroups the chunks
-// of columns it walks (two barriers and a staging burst each), the bytes of x a workgroup stages, the 16-step blocks of
-// terms a wavefront walks (a partly filled block costs a whole one) and the result tile; large layers also the stream of
-// W_c / idx.  A least-squares fit (relative error, mean 8 %) of the mean of cold and cached timings of 13 layer shapes,
-// 512- to 4096-wide, 80-99 % sparse, at batches 2 to 1024.
-static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
-    const int BT = kWave * p.R / p.H;
-    const double rounds = std::max(1.0, (double)p.n_btiles * p.n_groups / 256.0);
-    const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
-    const double terms = (double)a.n_active * a.K;
-    return 1.94 + rounds * (1.59 * p.n_chunks + 5.72e-6 * BT * a.d_in * 4.0 + 0.032 * steps + 1.0e-4 * BT * p.NW * p.NPW * 4.0) +
-           (terms > 1.5e6 ? 0.76e-6 * terms : 0.0);
 }
 
 // The library's own choice of kernel: the smallest of the estimated times of the small-batch kernel (gathered or staged
