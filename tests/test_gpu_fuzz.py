@@ -57,6 +57,21 @@ def test_random_layer_every_algorithm(d_in, d_out, K, B, abl, dtype, seed):
             assert np.array_equal(yh[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (B, 1)).view(np.uint32))
         ran += 1
     assert ran >= 3
+    # the batched kernel in every tile shape and either XCD order (whichever the sizes allow)
+    shapes = 0
+    for rows_per_lane, term_slices in ((1, 1), (1, 2), (1, 4), (2, 1)):
+        for xcd_order in (1, 2):
+            y = torch.full((B, d_out), 3.0e38, dtype=torch.float32, device="cuda")
+            try:
+                B_.srigl_condensed_linear_fwd(dev(xsrc), B, d_in, layer.W_c, layer.idx, layer.active, n, K, layer.bias, d_out, y,
+                                              layer.seg, algo=B_.FWD_ROWLANE,
+                                              tuning=dict(rows_per_lane=rows_per_lane, term_slices=term_slices, xcd_order=xcd_order))
+            except B_.SriglError as e:
+                assert e.status == B_.ERR_UNSUPPORTED
+                continue
+            gate(host(y), y_ref, S, TOL_BF16 if dtype == "bf16" else TOL_F32)
+            shapes += 1
+    assert shapes >= 2 or d_in % 16 != 0
 
 
 @pytest.mark.parametrize("seed", range(24))

@@ -101,3 +101,39 @@ def test_fallbacks():
     assert plan(4, 64, 8, 0)["algo"] == 0 and plan(0, 64, 8, 3)["workgroups"] == 0
     with pytest.raises(B_.SriglError):
         B_.srigl_fwd_plan_query(4, 8, 9, 3, 8)                      # more stored neurons than neurons
+
+
+def test_every_plan_is_one_the_kernels_accept():
+    """Seeded random sizes: whatever the estimates choose is a launch shape inside the kernels' documented limits, and asking
+    for the plan of that algorithm with that shape forced gives the same plan back."""
+    import random
+    rng = random.Random(20230502)
+    for _ in range(400):
+        d_in = rng.choice([16, 48, 64, 100, 256, 768, 1000, 1024, 1536, 2048, 3072, 4096, 8192, 49152])
+        d_out = rng.choice([1, 7, 64, 300, 768, 1024, 3072, 4096, 16384])
+        n_active = max(1, int(d_out * rng.choice([1.0, 1.0, 0.9, 0.7, 0.25])))
+        K = max(1, min(d_in, int(d_in * rng.choice([0.01, 0.05, 0.1, 0.2, 0.5, 1.0]))))
+        B = rng.choice([1, 2, 3, 5, 8, 16, 31, 64, 100, 256, 777, 2048, 5000])
+        dtype = rng.choice([B_.F32, B_.BF16])
+        if B * d_in >= 2 ** 31 or n_active * K >= 2 ** 30:
+            continue
+        p = B_.srigl_fwd_plan_query(B, d_in, n_active, K, d_out, dtype_code=dtype, has_active=(n_active != d_out))
+        assert p["algo"] in (B_.FWD_GENERIC, B_.FWD_KLANE, B_.FWD_ROWLANE), (B, d_in, d_out, n_active, K, p)
+        assert p["workgroups"] >= 1
+        if p["algo"] == B_.FWD_ROWLANE:
+            assert p["rows_per_lane"] in (1, 2) and p["term_slices"] in (1, 2, 4) and 1 <= p["waves"] <= 16
+            assert p["neurons_per_wave"] in (1, 2, 3, 4, 6, 8) and p["chunk_cols"] % 64 == 0 and p["chunk_cols"] >= 64
+            assert p["xcd_order"] in (1, 2) and (p["rows_per_lane"] == 1 or p["term_slices"] == 1)
+            forced = dict(rows_per_lane=p["rows_per_lane"], term_slices=p["term_slices"], waves=p["waves"],
+                          neurons_per_wave=p["neurons_per_wave"], chunk_cols=p["chunk_cols"], xcd_order=p["xcd_order"])
+        elif p["algo"] == B_.FWD_KLANE:
+            L = p["lanes_per_neuron"]
+            assert 4 <= L <= 64 and L & (L - 1) == 0 and p["rows_per_block"] in (1, 2, 4) and p["direct_gather"] in (0, 1)
+            if p["direct_gather"] == 0:
+                assert p["rows_per_block"] * d_in * 4 <= 160 * 1024      # the staged rows fit the LDS
+            forced = dict(lanes_per_neuron=L, rows_per_block=p["rows_per_block"], direct_gather=1 if p["direct_gather"] else 2)
+        else:
+            continue
+        q = B_.srigl_fwd_plan_query(B, d_in, n_active, K, d_out, dtype_code=dtype, has_active=(n_active != d_out), algo=p["algo"],
+                                    tuning=forced)
+        assert q == p, (B, d_in, d_out, n_active, K, p, q)
