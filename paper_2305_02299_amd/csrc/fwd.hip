@@ -404,7 +404,8 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     p.bt_major = by_tiles(p.n_groups) ? 1 : 0;
     // the result tile sits behind the activation tile when both fit (no barrier between the last term and the
     // transposed write), else it reuses the activation tile's space
-    const size_t out_tile = (size_t)BT * (p.NW * npw + 1) * sizeof(float);
+    // (with an active list: plus the column table and the bias of the columns the workgroup writes)
+    const size_t out_tile = (size_t)BT * (p.NW * npw + 1) * sizeof(float) + (a.active ? (size_t)kSpanCap * 8 : 0);
     if (p.lds + out_tile <= 150 * 1024) { p.out_off = (int)(p.lds / sizeof(float)); p.lds += out_tile; }
     else { p.out_off = 0; if (out_tile > p.lds) p.lds = out_tile; }
     if (p.lds > kLdsMax) return p;

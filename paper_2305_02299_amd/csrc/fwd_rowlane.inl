@@ -421,6 +421,44 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     }
     SRIGL_STAMP(13)
     const int n_rows = min(BT, B - b0);
+    if (active) {
+        // The stored columns of this workgroup and the ablated ones between them are one run of consecutive columns of
+        // y, (active[sg0 - 1], active[last slot]]: a table in LDS says which slot, if any, holds a column, and the lanes
+        // write the run left to right (consecutive lanes, consecutive columns) instead of every lane its own column
+        // and the gap in front of it.  Runs longer than the table (very few stored neurons) take the loop below.
+        const int s_last = min(sg0 + NG, n_slots) - 1;
+        const int c0 = sg0 > 0 ? min(active[sg0 - 1] + 1, d_out) : 0;
+        const int c1 = s_last < n_active ? min(active[s_last] + 1, d_out) : d_out;
+        const int span = c1 - c0;
+        if (span > 0 && span <= kSpanCap && c0 >= 0) {
+            int* const tab = reinterpret_cast<int*>(out + BT * OS);
+            float* const bsp = reinterpret_cast<float*>(tab + kSpanCap);
+            for (int c = tid; c < span; c += blockDim.x) {
+                tab[c] = -1;
+                bsp[c] = rl_bias_at(bias, c0 + c);
+            }
+            __syncthreads();
+            if (wv_id == 0) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int i = lane + h * kWave;
+                    const int col = colv[h];
+                    if (col >= c0 && col < c1 && sg0 + i < n_active) tab[col - c0] = i;
+                }
+            }
+            __syncthreads();
+            for (int row = wv_id; row < n_rows; row += nw) {
+                float* yr = y + (size_t)(b0 + row) * d_out + c0;
+                for (int c = lane; c < span; c += kWave) {
+                    const int t = tab[c];
+                    const float v = t >= 0 ? out[row * OS + t] + bsp[c] : bsp[c];
+                    yr[c] = act == SRIGL_ACT_NONE ? v : apply_act(v, act);
+                }
+            }
+            SRIGL_STAMP(14)
+            return;
+        }
+    }
     // the loop exists twice so that the plain forward pass carries no test of the activation code per store
     auto store_rows = [&](auto with_act) {
         for (int row = wv_id; row < n_rows; row += nw) {
