@@ -41,7 +41,7 @@ struct RowlanePlan {
     bool fast;   // x rows allow aligned 4-element loads and d_in is a multiple of 16
     bool ok;
 };
-constexpr int kSpanCap = 512;     // output columns (stored and ablated) a workgroup of the batched kernel writes through its column table
+constexpr int kSpanCap = 1024;     // output columns (stored and ablated) a workgroup of the batched kernel writes through its column table
 constexpr int kStageUnits = 8;   // 16x16 staging units a wavefront holds in registers per chunk
 constexpr int kBlock = 16;       // terms per vector load of W_c / idx (one DPP row)
 constexpr int rowlane_max_threads(int) { return 1024; }

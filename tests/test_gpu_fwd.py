@@ -321,3 +321,13 @@ def test_batched_kernel_either_xcd_order(shape, xcd_order):
     L = si.make_layer(d_in, d_out, K, B, ablate_frac=0.2, seed=d_in + B)
     worst = check_layer(L, B_.FWD_ROWLANE, dict(xcd_order=xcd_order))
     assert worst < 2e-6
+
+
+@pytest.mark.parametrize("abl,B", [(0.3, 70), (0.7, 200), (0.9, 64), (0.97, 300), (0.995, 33)])
+def test_batched_kernel_writes_ablated_columns_between_stored_ones(abl, B):
+    """Runs of output columns per workgroup from a few dozen (30 % ablated) to beyond the column table (99.5 %: the per-lane
+    loop), every ablated column bit-equal to its bias (checked by check_layer)."""
+    L = si.make_layer(512, 4000, 40, B, ablate_frac=abl, seed=int(abl * 1000))
+    for shape in (dict(), dict(term_slices=4), dict(rows_per_lane=2)):
+        worst = check_layer(L, B_.FWD_ROWLANE, shape)
+        assert worst < 2e-6
