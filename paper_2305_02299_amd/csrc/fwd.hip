@@ -330,7 +330,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     if (p.H != 1 && p.H != 2 && p.H != 4) return p;
     if (p.H > 1 && p.R != 1) return p;
     if (!p.fast && (p.R != 1 || p.H != 1)) return p;
-    const int BT = kWave * p.R / p.H, S = BT + 4;
+    const int BT = kWave * p.R / p.H, S = rowlane_row_stride(BT, p.H);
     p.n_btiles = (a.B + BT - 1) / BT;
     const int nw_max = rowlane_max_threads(p.R) / kWave;
     p.NW = t && t->waves ? t->waves : nw_max;
@@ -402,6 +402,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     p.KPRE = rowlane_kpre(npw);
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
     p.bt_major = by_tiles(p.n_groups) ? 1 : 0;
+    p.rounds = (int)rounds(p.n_groups, p.bt_major != 0);
     // the result tile sits behind the activation tile when both fit (no barrier between the last term and the
     // transposed write), else it reuses the activation tile's space
     // (with an active list: plus the column table and the bias of the columns the workgroup writes)
@@ -413,20 +414,21 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     return p;
 }
 
-// Estimated time (us) of the batched kernel in launch shape p: a fixed part, and per round of 256 workgroups the chunks
+// Estimated time (us) of the batched kernel in launch shape p: a fixed part, and per round of workgroups (counted on the
+// busiest XCD: a second, partly filled round takes as long as a full one) the chunks
 // of columns it walks (two barriers and a staging burst each), the bytes of x a workgroup stages, the 16-step blocks of
-// terms a wavefront walks (a partly filled block costs a whole one; a step of four term slices costs 1.6 times a step of
+// terms a wavefront walks (a partly filled block costs a whole one; a step of four term slices costs 1.5 times a step of
 // one: its LDS reads collide) and the result tile; large layers also the stream of W_c / idx.  A least-squares fit
-// (relative error, mean 6 %) of the mean of cold and cached timings of 326 points: 15 layer shapes, 512- to 4096-wide,
+// (relative error, mean 5 %) of the mean of cold and cached timings of 260 points: 15 layer shapes, 512- to 4096-wide,
 // 80-99 % sparse, at batches 2 to 1024, every term-slice count on seven of them.
 static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
     const int BT = kWave * p.R / p.H;
-    const double rounds = std::max(1.0, (double)p.n_btiles * p.n_groups / 256.0);
+    const double rounds = std::max(1, p.rounds);
     const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
-    const double per_step = p.R == 2 ? 0.0216 : (p.H == 1 ? 0.0226 : (p.H == 2 ? 0.0256 : 0.0370));
+    const double per_step = p.R == 2 ? 0.0303 : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
     const double terms = (double)a.n_active * a.K;
-    return 1.88 + rounds * (1.63 * p.n_chunks + 3.83e-6 * BT * a.d_in * 4.0 + per_step * steps + 2.13e-4 * BT * p.NW * p.NPW * 4.0) +
-           (terms > 1.5e6 ? 0.28e-6 * terms : 0.0);
+    return 2.19 + rounds * (1.38 * p.n_chunks + 5.90e-6 * BT * a.d_in * 4.0 + per_step * steps + 1.45e-4 * BT * p.NW * p.NPW * 4.0) +
+           (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);
 }
 
 // The tile: 64 batch rows x 1 term slice, 32 x 2, 16 x 4, or 128 rows with two rows per lane (one 8-byte LDS read feeds

@@ -45,7 +45,7 @@ __device__ __forceinline__ float rl_bias_at(const float* __restrict__ bias, int 
 // Terms run in groups of 8: the LDS reads of group g+1 are issued before the multiply-adds of group
 // g, so that the LDS latency of one group hides behind the arithmetic of the other.
 //
-// LDS: row stride S = BT + 4 words.  The staging pass moves 16 rows x 16 columns per wavefront
+// LDS: row stride S = BT + 4 words (16 with four term slices).  The staging pass moves 16 rows x 16 columns per wavefront
 // instruction (global reads of 64 contiguous bytes per row) and the +4 skew spreads its LDS writes
 // over all banks, while reads of consecutive rows stay conflict-free and 16-byte aligned.  Column C
 // is all zeros: terms that pad a group carry weight 0 and point there, so that a non-finite
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
-    constexpr int S = BT + 4;
+    constexpr int S = rowlane_row_stride(BT, H);
     constexpr int S4 = S * 4;
     constexpr int TB = kBlock * H;           // terms per block (16 steps of H terms)
     using V = typename RowVec<R>::type;
@@ -289,7 +289,17 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     _Pragma("unroll") for (int i = 0; i < kStageUnits; ++i) {                                                   \
         if (u_col[i] < C) {                                                                                     \
             float* d_ = lds + l_off[i];                                                                         \
-            d_[0] = st[i][0]; d_[S] = st[i][1]; d_[2 * S] = st[i][2]; d_[3 * S] = st[i][3];                     \
+            if (H == 4) {   /* stride 16: odd column quads write their pairs in the other order (banks 16 apart) */ \
+                const bool odd_ = (dq & 1) != 0;                                                                \
+                float* p_ = d_ + (odd_ ? S : 0);                                                                \
+                float* q_ = d_ + (odd_ ? 0 : S);                                                                \
+                p_[0] = odd_ ? st[i][1] : st[i][0];                                                             \
+                q_[0] = odd_ ? st[i][0] : st[i][1];                                                             \
+                p_[2 * S] = odd_ ? st[i][3] : st[i][2];                                                         \
+                q_[2 * S] = odd_ ? st[i][2] : st[i][3];                                                         \
+            } else {                                                                                            \
+                d_[0] = st[i][0]; d_[S] = st[i][1]; d_[2 * S] = st[i][2]; d_[3 * S] = st[i][3];                 \
+            }                                                                                                   \
         }                                                                                                       \
     }
 

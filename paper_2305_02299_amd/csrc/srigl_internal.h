@@ -34,6 +34,7 @@ struct FwdArgs {
 // Launch shape of the ROWLANE kernel, decided on the host.
 struct RowlanePlan {
     int R, H, NW, NPW, KPRE, C, n_chunks, n_btiles, n_groups;
+    int rounds;    // rounds of workgroups on the busiest XCD (32 compute units each)
     int bt_major;  // 1: an XCD owns batch tiles (and runs every group of stored rows on them), 0: it owns groups of stored rows
     size_t lds;
     double cost;  // the planner's estimate for this shape (arbitrary units), to compare shapes
@@ -42,6 +43,12 @@ struct RowlanePlan {
     bool ok;
 };
 constexpr int kSpanCap = 1024;     // output columns (stored and ablated) a workgroup of the batched kernel writes through its column table
+// Words between consecutive columns of the activation tile in LDS (a column holds the tile's BT batch rows).  BT + 4: the
+// staging writes of four consecutive columns land in different banks.  Four term slices (16-row tiles): 16, so that the two
+// 16-word runs a half-wavefront reads start 0 or 16 banks apart (they collide only when the two columns have the same
+// parity) instead of a multiple of 4 banks apart (collide in 7 cases of 8); the staging writes then swap the columns of a
+// pair in every other lane group so that they meet in two banks' worth, as with the skew.
+constexpr int rowlane_row_stride(int BT, int H) { return H == 4 ? BT : BT + 4; }
 constexpr int kStageUnits = 8;   // 16x16 staging units a wavefront holds in registers per chunk
 constexpr int kBlock = 16;       // terms per vector load of W_c / idx (one DPP row)
 constexpr int rowlane_max_threads(int) { return 1024; }

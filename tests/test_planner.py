@@ -38,7 +38,7 @@ def test_small_batches_gather_their_activations():
     """Measured: up to a few million gathered terms the small-batch kernel is faster reading x through the caches than staging
     rows of it in LDS (3072 -> 768 at B = 1: 3.7 vs 6.4 us cold), with one, two or four batch rows per workgroup."""
     for (B, d_in, d_out, K, rb) in ((1, 768, 3072, 77, 1), (1, 3072, 768, 308, 1), (4, 3072, 768, 308, 1), (8, 3072, 768, 308, 2),
-                                    (8, 768, 3072, 77, 2), (16, 4096, 1024, 410, 4), (2, 4096, 16384, 205, 2)):
+                                    (8, 768, 3072, 77, 2), (8, 4096, 1024, 410, 2), (2, 4096, 16384, 205, 2)):
         p = plan(B, d_in, d_out, K)
         assert (p["algo"], p["direct_gather"], p["rows_per_block"]) == (B_.FWD_KLANE, 1, rb), (B, d_in, d_out, K, p)
     # very sparse layers at larger batches: many distinct lines per gather, the staged rows win
