@@ -60,29 +60,42 @@ template <> struct RowVec<2> { using type = float2; };
 template <> struct RowVec<4> { using type = float4; };
 
 
-template <typename XT>
-__device__ __forceinline__ void load4(const XT* __restrict__ p, bool vec_ok, int n_valid, float out[4]);
+// Four consecutive activations of one row as they came from memory.  They are turned into fp32 only when they are
+// written to LDS: a conversion right behind the load would make the wavefront wait for the load where it is issued,
+// and the loads of the next chunk are issued long before their data is needed.
+template <typename XT> struct Staged4;
+template <> struct Staged4<float> {
+    float v[4];
+    __device__ __forceinline__ void clear() { v[0] = v[1] = v[2] = v[3] = 0.0f; }
+    __device__ __forceinline__ float get(int k) const { return v[k]; }
+};
+template <> struct Staged4<uint16_t> {
+    uint32_t w[2];   // two bf16 per word, the lower-addressed one in the low half
+    __device__ __forceinline__ void clear() { w[0] = w[1] = 0u; }
+    __device__ __forceinline__ float get(int k) const {
+        return (k & 1) ? __uint_as_float(w[k >> 1] & 0xffff0000u) : __uint_as_float(w[k >> 1] << 16);
+    }
+};
 
-template <>
-__device__ __forceinline__ void load4<float>(const float* __restrict__ p, bool vec_ok, int n_valid, float out[4]) {
+__device__ __forceinline__ void load4(const float* __restrict__ p, bool vec_ok, int n_valid, Staged4<float>& out) {
     if (vec_ok && n_valid >= 4) {
         const float4 v = *reinterpret_cast<const float4*>(p);
-        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+        out.v[0] = v.x; out.v[1] = v.y; out.v[2] = v.z; out.v[3] = v.w;
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) out[i] = (i < n_valid) ? p[i] : 0.0f;
+        for (int i = 0; i < 4; ++i) out.v[i] = (i < n_valid) ? p[i] : 0.0f;
     }
 }
 
-template <>
-__device__ __forceinline__ void load4<uint16_t>(const uint16_t* __restrict__ p, bool vec_ok, int n_valid, float out[4]) {
+__device__ __forceinline__ void load4(const uint16_t* __restrict__ p, bool vec_ok, int n_valid, Staged4<uint16_t>& out) {
     if (vec_ok && n_valid >= 4) {
         const uint2 v = *reinterpret_cast<const uint2*>(p);
-        out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xffff0000u);
-        out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xffff0000u);
+        out.w[0] = v.x; out.w[1] = v.y;
     } else {
+        out.w[0] = out.w[1] = 0u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) out[i] = (i < n_valid) ? bf16_bits_to_float(p[i]) : 0.0f;
+        for (int i = 0; i < 4; ++i)
+            if (i < n_valid) out.w[i >> 1] |= (uint32_t)p[i] << (16 * (i & 1));
     }
 }
 
@@ -270,17 +283,17 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         l_off[i] = f * S + rl;
         u_col[i] = (u < units) ? ct * 16 : 0x40000000;   // units past the tile never pass the column tests below
     }
-    float st[kStageUnits][4];
+    Staged4<XT> st[kStageUnits];
 #define SRIGL_STAGE_LOAD_UNITS(c, u_first, u_last)                                                              \
     _Pragma("unroll") for (int u_ = 0; u_ < kStageUnits; ++u_) {                                                \
         const int c0_ = (c) * C;                                                                                \
         if (u_ >= (u_first) && u_ < (u_last)) {                                                                 \
             if (FAST) {                                                                                         \
-                if (c0_ + u_col[u_] < d_in) load4<XT>(x + (g_off[u_] + (unsigned)c0_), true, 4, st[u_]);        \
+                if (c0_ + u_col[u_] < d_in) load4(x + (g_off[u_] + (unsigned)c0_), true, 4, st[u_]);        \
             } else {                                                                                            \
-                st[u_][0] = st[u_][1] = st[u_][2] = st[u_][3] = 0.0f;                                           \
+                st[u_].clear();                                                                                 \
                 const int nv = min(4, d_in - (c0_ + u_col[u_] + dq * 4));                                       \
-                if (u_col[u_] < C && nv > 0) load4<XT>(x + (g_off[u_] + (unsigned)c0_), false, nv, st[u_]);     \
+                if (u_col[u_] < C && nv > 0) load4(x + (g_off[u_] + (unsigned)c0_), false, nv, st[u_]);     \
             }                                                                                                   \
         }                                                                                                       \
     }
@@ -293,12 +306,13 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 const bool odd_ = (dq & 1) != 0;                                                                \
                 float* p_ = d_ + (odd_ ? S : 0);                                                                \
                 float* q_ = d_ + (odd_ ? 0 : S);                                                                \
-                p_[0] = odd_ ? st[i][1] : st[i][0];                                                             \
-                q_[0] = odd_ ? st[i][0] : st[i][1];                                                             \
-                p_[2 * S] = odd_ ? st[i][3] : st[i][2];                                                         \
-                q_[2 * S] = odd_ ? st[i][2] : st[i][3];                                                         \
+                const float e0_ = st[i].get(0), e1_ = st[i].get(1), e2_ = st[i].get(2), e3_ = st[i].get(3);     \
+                p_[0] = odd_ ? e1_ : e0_;                                                                       \
+                q_[0] = odd_ ? e0_ : e1_;                                                                       \
+                p_[2 * S] = odd_ ? e3_ : e2_;                                                                   \
+                q_[2 * S] = odd_ ? e2_ : e3_;                                                                   \
             } else {                                                                                            \
-                d_[0] = st[i][0]; d_[S] = st[i][1]; d_[2 * S] = st[i][2]; d_[3 * S] = st[i][3];                 \
+                d_[0] = st[i].get(0); d_[S] = st[i].get(1); d_[2 * S] = st[i].get(2); d_[3 * S] = st[i].get(3); \
             }                                                                                                   \
         }                                                                                                       \
     }
