@@ -34,8 +34,15 @@ __global__ __launch_bounds__(256) void k_fwd_csr(const XT* __restrict__ x, int B
 
     if (!GATHER) {
         for (int r = 0; r < RB; ++r) {
-            const int b = min(b0 + r, B - 1);         // rows past B re-read the last row; they are never stored
-            for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = csr_to_f32<XT>(x[(size_t)b * d_in + j]);
+            const XT* xr = x + (size_t)min(b0 + r, B - 1) * d_in;   // rows past B re-read the last row; they are never stored
+            for (int j0 = tid; j0 < d_in; j0 += 4 * (int)blockDim.x) {   // four loads in flight before the first is stored
+                XT v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = xr[min(j0 + u * (int)blockDim.x, d_in - 1)];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (j0 + u * (int)blockDim.x < d_in) xs[r * d_in + j0 + u * (int)blockDim.x] = csr_to_f32<XT>(v[u]);
+            }
         }
         __syncthreads();
     }

@@ -92,9 +92,17 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
 #pragma unroll
     for (int r = 0; r < RB; ++r) xrow[r] = x + (size_t)min(b0 + r, B - 1) * d_in;
     if (!GATHER) {
+        // four loads per thread in flight before the first of them is converted and stored
 #pragma unroll
         for (int r = 0; r < RB; ++r)
-            for (int j = tid; j < d_in; j += blockDim.x) xs[r * d_in + j] = to_f32<XT>(xrow[r][j]);
+            for (int j0 = tid; j0 < d_in; j0 += 4 * (int)blockDim.x) {
+                XT v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = xrow[r][min(j0 + u * (int)blockDim.x, d_in - 1)];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (j0 + u * (int)blockDim.x < d_in) xs[r * d_in + j0 + u * (int)blockDim.x] = to_f32<XT>(v[u]);
+            }
         __syncthreads();
     }
 
