@@ -112,12 +112,8 @@ static srigl_status launch_csr(const void* x, int B, int d_in, const void* value
     const size_t lds = GATHER ? 0 : (size_t)RB * d_in * sizeof(float);
     if (lds > kLdsMax) return SRIGL_ERR_UNSUPPORTED;
     auto kern = k_fwd_csr<RB, GATHER, XT>;
-    static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
-    if (lds > lds_allowed) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
-            return SRIGL_ERR_HIP;
-        lds_allowed = kLdsMax;
-    }
+    static LdsLimit lds_limit;
+    if (lds_limit.ensure(kern, lds) != SRIGL_OK) return SRIGL_ERR_HIP;
     const int groups = 256 >> log2L;
     const int gy = (B + RB - 1) / RB;
     if (gy > 65535) return SRIGL_ERR_UNSUPPORTED;

@@ -229,12 +229,8 @@ static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg,
     const size_t lds = GATHER ? 0 : (size_t)RB * a.d_in * sizeof(float);
     if (lds > kLdsMax) return SRIGL_ERR_UNSUPPORTED;
     auto kern = k_fwd_klane<RB, GATHER, XT, IT>;
-    static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
-    if (lds > lds_allowed) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
-            return SRIGL_ERR_HIP;
-        lds_allowed = kLdsMax;
-    }
+    static LdsLimit lds_limit;
+    if (lds_limit.ensure(kern, lds) != SRIGL_OK) return SRIGL_ERR_HIP;
     const unsigned gx = (unsigned)((n_slots + rows_per_wg - 1) / rows_per_wg);
     const unsigned gy = (unsigned)((a.B + RB - 1) / RB);
     if (gy > 65535u) return SRIGL_ERR_UNSUPPORTED;

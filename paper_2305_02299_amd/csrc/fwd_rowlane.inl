@@ -512,12 +512,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT>
 static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST, IT>;
-    static size_t lds_allowed = 64 * 1024;   // raised once per kernel instance, not per call
-    if (p.lds > lds_allowed) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
-            return SRIGL_ERR_HIP;
-        lds_allowed = kLdsMax;
-    }
+    static LdsLimit lds_limit;
+    if (lds_limit.ensure(kern, p.lds) != SRIGL_OK) return SRIGL_ERR_HIP;
     const long long blocks = p.bt_major ? 8LL * ((p.n_btiles + 7) / 8) * p.n_groups : 8LL * ((p.n_groups + 7) / 8) * p.n_btiles;
     if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,

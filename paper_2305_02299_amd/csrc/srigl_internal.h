@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <stdint.h>
 
@@ -128,6 +129,25 @@ inline double klane_estimate_us(int B, int d_in, int n_active, int K) {
 }
 
 inline srigl_status hip_ok(hipError_t e) { return e == hipSuccess ? SRIGL_OK : SRIGL_ERR_HIP; }
+
+// Kernels that use more than 64 KB of dynamic LDS need the limit raised with hipFuncSetAttribute, which applies to the
+// current device only.  One of these per kernel instance (a function-local static): the attribute is set on the first
+// launch on each device (a bit per device ordinal) and never per call; safe to use from several host threads.
+struct LdsLimit {
+    std::atomic<uint64_t> raised{0};
+    template <typename Kern>
+    srigl_status ensure(Kern kern, size_t bytes) {
+        if (bytes <= 64 * 1024) return SRIGL_OK;
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return SRIGL_ERR_HIP;
+        const uint64_t bit = 1ull << (dev & 63);
+        if (dev < 64 && (raised.load(std::memory_order_acquire) & bit)) return SRIGL_OK;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess)
+            return SRIGL_ERR_HIP;
+        if (dev < 64) raised.fetch_or(bit, std::memory_order_release);
+        return SRIGL_OK;
+    }
+};
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 

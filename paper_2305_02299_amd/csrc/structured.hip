@@ -350,12 +350,8 @@ static srigl_status launch_gemm_r(const void* x, int B, int d_in, const void* Wd
     constexpr size_t ring = (size_t)NS * (BM + BN) * SLAB, epi = EpiLayout<BM, BN, WGM>::BYTES;
     constexpr size_t lds = ring > epi ? ring : epi;
     static_assert(lds <= kLdsMax, "LDS");
-    static bool raised = false;
-    if (lds > 64 * 1024 && !raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return SRIGL_ERR_HIP;
-        raised = true;
-    }
+    static LdsLimit lds_limit;
+    if (lds_limit.ensure(kern, lds) != SRIGL_OK) return SRIGL_ERR_HIP;
     const long long tiles_m = (B + BM - 1) / BM, tiles_n = (n_active + BN - 1) / BN;
     const long long n_wg = ((tiles_m * tiles_n + kXcds - 1) / kXcds) * kXcds;   // 8 equal runs of tiles, one per XCD
     if (n_wg > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
