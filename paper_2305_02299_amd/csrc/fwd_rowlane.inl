@@ -551,6 +551,7 @@ static srigl_status launch_rowlane_x(const FwdArgs& a, const RowlanePlan& p, hip
         case 12: return launch_rowlane_r<1, 2, XT, IT>(a, p, st);
         case 14: return launch_rowlane_r<1, 4, XT, IT>(a, p, st);
         case 21: return launch_rowlane_r<2, 1, XT, IT>(a, p, st);
+        case 22: return launch_rowlane_r<2, 2, XT, IT>(a, p, st);
         default: return SRIGL_ERR_UNSUPPORTED;
     }
 }

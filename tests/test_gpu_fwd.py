@@ -118,6 +118,8 @@ def test_no_bias_and_no_seg(algo):
     {"rows_per_lane": 2, "waves": 8, "neurons_per_wave": 3, "chunk_cols": 128},
     {"rows_per_lane": 2, "waves": 16, "neurons_per_wave": 4, "chunk_cols": 256},
     {"term_slices": 2, "waves": 16, "neurons_per_wave": 3},
+    {"rows_per_lane": 2, "term_slices": 2, "waves": 16, "neurons_per_wave": 3},
+    {"rows_per_lane": 2, "term_slices": 2, "waves": 4, "neurons_per_wave": 4, "chunk_cols": 128},
     {"term_slices": 2, "waves": 8, "neurons_per_wave": 6, "chunk_cols": 192},
     {"term_slices": 4, "waves": 8, "neurons_per_wave": 6},
     {"term_slices": 4, "waves": 16, "neurons_per_wave": 2, "chunk_cols": 128},
@@ -328,6 +330,6 @@ def test_batched_kernel_writes_ablated_columns_between_stored_ones(abl, B):
     """Runs of output columns per workgroup from a few dozen (30 % ablated) to beyond the column table (99.5 %: the per-lane
     loop), every ablated column bit-equal to its bias (checked by check_layer)."""
     L = si.make_layer(512, 4000, 40, B, ablate_frac=abl, seed=int(abl * 1000))
-    for shape in (dict(), dict(term_slices=4), dict(rows_per_lane=2)):
+    for shape in (dict(), dict(term_slices=4), dict(rows_per_lane=2), dict(rows_per_lane=2, term_slices=2)):
         worst = check_layer(L, B_.FWD_ROWLANE, shape)
         assert worst < 2e-6

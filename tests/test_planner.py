@@ -65,6 +65,19 @@ def test_rounds_are_counted_per_xcd():
     assert (p["rows_per_lane"], p["neurons_per_wave"]) == (2, 4)
 
 
+def test_long_rows_take_two_rows_per_lane_in_two_slices():
+    """64-row tiles whose lanes hold two batch rows and work on two terms at once: one 8-byte LDS read per two rows and term.
+    Measured against one row per lane: 768 -> 3072 K = 154 at B = 256 19.9 -> 17.1 us, 1024 -> 4096 K = 102 19.9 -> 16.5,
+    2048 -> 2048 K = 205 at B = 384 35.0 -> 27.6, 4096 -> 1024 K = 410 at B = 1024 69.2 -> 52.4; at K = 77 (B = 256:
+    13.5 vs 13.9) and below the plain 64-row tile stays ahead."""
+    for (B, d_in, d_out, K) in ((256, 768, 3072, 154), (256, 1024, 4096, 102), (384, 2048, 2048, 205), (1024, 4096, 1024, 410)):
+        p = plan(B, d_in, d_out, K)
+        assert (p["algo"], p["rows_per_lane"], p["term_slices"]) == (B_.FWD_ROWLANE, 2, 2), (B, d_in, d_out, K, p)
+    for (B, d_in, d_out, K) in ((256, 768, 3072, 77), (256, 768, 3072, 39)):
+        p = plan(B, d_in, d_out, K)
+        assert (p["rows_per_lane"], p["term_slices"]) == (1, 1), (B, d_in, d_out, K, p)
+
+
 def test_which_workgroups_share_an_xcd():
     """Each of the 8 XCDs has its own L2: either every XCD fetches all of x (and one group's W_c / idx), or its own batch tiles
     of x and all of W_c / idx; the batched kernel takes the order that fetches fewer bytes once an XCD has two tiles."""
@@ -123,7 +136,7 @@ def test_every_plan_is_one_the_kernels_accept():
         if p["algo"] == B_.FWD_ROWLANE:
             assert p["rows_per_lane"] in (1, 2) and p["term_slices"] in (1, 2, 4) and 1 <= p["waves"] <= 16
             assert p["neurons_per_wave"] in (1, 2, 3, 4, 6, 8) and p["chunk_cols"] % 64 == 0 and p["chunk_cols"] >= 64
-            assert p["xcd_order"] in (1, 2) and (p["rows_per_lane"] == 1 or p["term_slices"] == 1)
+            assert p["xcd_order"] in (1, 2) and (p["rows_per_lane"] == 1 or p["term_slices"] in (1, 2))
             forced = dict(rows_per_lane=p["rows_per_lane"], term_slices=p["term_slices"], waves=p["waves"],
                           neurons_per_wave=p["neurons_per_wave"], chunk_cols=p["chunk_cols"], xcd_order=p["xcd_order"])
         elif p["algo"] == B_.FWD_KLANE:
