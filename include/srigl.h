@@ -134,8 +134,7 @@ typedef struct {
     int32_t lanes_per_neuron; /* KLANE: lanes that share one neuron, power of two 1..64                    */
     int32_t rows_per_block;   /* KLANE: batch rows per workgroup, 1, 2, 4 or 8                             */
     int32_t term_slices;      /* ROWLANE: 1, 2 or 4 groups of lanes that work on different terms of a stored
-                                 row at once (batch tile = 64 * rows_per_lane / term_slices rows); with two
-                                 rows per lane: 1 or 2                                                      */
+                                 row at once (batch tile = 64 * rows_per_lane / term_slices rows)           */
     int32_t direct_gather;    /* KLANE: 1 = gather activations from global memory, 2 = stage rows of x in LDS     */
     int32_t xcd_order;        /* ROWLANE: which workgroups share an XCD (one L2): 1 = all batch tiles of a group of
                                  stored rows (W_c / idx fetched once, x by every XCD), 2 = all groups of a batch tile */

@@ -300,6 +300,7 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
 }
 
 constexpr int kRowlaneTwoRowsMinK = 32;
+constexpr int kRowlaneTwoRowsFourSlicesMinK = 100;   // blocks of 64 terms: measured 14 % slower than 32 x 2 tiles at a fan-in of 39
 
 static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t) {
     RowlanePlan p{};
@@ -332,7 +333,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
         }
     }
     if (p.H != 1 && p.H != 2 && p.H != 4) return p;
-    if (p.H > 1 && p.R != 1 && !(p.R == 2 && p.H == 2)) return p;
+    if (p.R == 2 && p.H != 1 && p.H != 2 && p.H != 4) return p;
     if (!p.fast && (p.R != 1 || p.H != 1)) return p;
     const int BT = kWave * p.R / p.H, S = rowlane_row_stride(BT, p.H);
     p.n_btiles = (a.B + BT - 1) / BT;
@@ -367,7 +368,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     // terms held in registers) a tenth more; with term slices the fixed part is about two stored rows' worth.  Fits of
     // the measured ranking of eight launch shapes each at batches 320..768 of three layers.
     // (two rows per lane in two term slices: the 64-row tile of the whole-row shape, a term at three quarters of its cost)
-    const bool r2h2 = p.R == 2 && p.H == 2;
+    const bool r2h2 = p.R == 2 && p.H >= 2;
     const double fixed = r2h2 ? 0.15 * a.d_in : (p.H == 1 ? 0.15 * a.d_in * p.R : 2.0 * a.K);
     const double per_row = (double)a.K * (r2h2 ? 0.75 : (p.H == 1 && p.R == 2 ? 1.3 : 1.0));
     // which workgroups share an XCD: the order that makes the 8 L2s fetch fewer bytes in all (all of x by each XCD, or
@@ -431,16 +432,16 @@ static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
     const int BT = kWave * p.R / p.H;
     const double rounds = std::max(1, p.rounds);
     const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
-    const double per_step = p.R == 2 ? (p.H == 2 ? 0.0356 : 0.0303) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
+    const double per_step = p.R == 2 ? (p.H == 4 ? 0.0440 : (p.H == 2 ? 0.0356 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
     const double terms = (double)a.n_active * a.K;
     return 2.19 + rounds * (1.38 * p.n_chunks + 5.90e-6 * BT * a.d_in * 4.0 + per_step * steps + 1.45e-4 * BT * p.NW * p.NPW * 4.0) +
            (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);
 }
 
 // The tile: 64 batch rows x 1 term slice, 32 x 2, 16 x 4, or two rows per lane: 128 rows (one 8-byte LDS read feeds
-// two rows, but half the workgroups each staging twice the tile) or 64 rows in two term slices (the 64-row tile with
-// half the LDS instructions per term: 10-24 % faster than one row per lane from a fan-in of ~100, slower below; both
-// need rows long enough for the term loop to matter: slower at fan-in 8).  With nothing forced the library takes the shape with the smallest estimated time; a forced
+// two rows, but half the workgroups each staging twice the tile), 64 rows in two term slices or 32 rows in four (the
+// 64- and 32-row tiles with half the LDS instructions per term: 10-24 % faster than one row per lane from a fan-in of
+// ~100, slower below; all need rows long enough for the term loop to matter: slower at fan-in 8).  With nothing forced the library takes the shape with the smallest estimated time; a forced
 // part keeps the rules the other part had before the estimate existed.
 static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     const bool forced = t && (t->rows_per_lane || t->term_slices);
@@ -449,9 +450,10 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     best.ok = false;
     double best_us = 0.0;
     // rows per lane, term slices; a later shape must be 5 % ahead of an earlier one (the estimates are good to about that)
-    static const int shapes[5][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}, {2, 2}};
-    for (int i = 0; i < 5; ++i) {
+    static const int shapes[6][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}, {2, 2}, {2, 4}};
+    for (int i = 0; i < 6; ++i) {
         if (shapes[i][0] == 2 && a.K < kRowlaneTwoRowsMinK) continue;
+        if (shapes[i][0] == 2 && shapes[i][1] == 4 && a.K < kRowlaneTwoRowsFourSlicesMinK) continue;
         srigl_fwd_tuning shape{};
         if (t) shape = *t;
         shape.rows_per_lane = shapes[i][0];

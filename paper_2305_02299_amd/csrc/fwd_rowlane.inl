@@ -302,7 +302,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     _Pragma("unroll") for (int i = 0; i < kStageUnits; ++i) {                                                   \
         if (u_col[i] < C) {                                                                                     \
             float* d_ = lds + l_off[i];                                                                         \
-            if (H == 4) {   /* stride 16: odd column quads write their pairs in the other order (banks 16 apart) */ \
+            if (H == 4 && R == 1) {   /* stride 16: odd column quads write their pairs in the other order (banks 16 apart) */ \
                 const bool odd_ = (dq & 1) != 0;                                                                \
                 float* p_ = d_ + (odd_ ? S : 0);                                                                \
                 float* q_ = d_ + (odd_ ? 0 : S);                                                                \
@@ -552,6 +552,7 @@ static srigl_status launch_rowlane_x(const FwdArgs& a, const RowlanePlan& p, hip
         case 14: return launch_rowlane_r<1, 4, XT, IT>(a, p, st);
         case 21: return launch_rowlane_r<2, 1, XT, IT>(a, p, st);
         case 22: return launch_rowlane_r<2, 2, XT, IT>(a, p, st);
+        case 24: return launch_rowlane_r<2, 4, XT, IT>(a, p, st);
         default: return SRIGL_ERR_UNSUPPORTED;
     }
 }

@@ -49,7 +49,7 @@ constexpr int kSpanCap = 1024;     // output columns (stored and ablated) a work
 // 16-word runs a half-wavefront reads start 0 or 16 banks apart (they collide only when the two columns have the same
 // parity) instead of a multiple of 4 banks apart (collide in 7 cases of 8); the staging writes then swap the columns of a
 // pair in every other lane group so that they meet in two banks' worth, as with the skew.
-constexpr int rowlane_row_stride(int BT, int H) { return H == 4 ? BT : BT + 4; }
+constexpr int rowlane_row_stride(int BT, int H) { return (H == 4 && BT == 16) ? BT : BT + 4; }
 constexpr int kStageUnits = 8;   // 16x16 staging units a wavefront holds in registers per chunk
 constexpr int kBlock = 16;       // terms per vector load of W_c / idx (one DPP row)
 constexpr int rowlane_max_threads(int) { return 1024; }

@@ -59,7 +59,7 @@ def test_random_layer_every_algorithm(d_in, d_out, K, B, abl, dtype, seed):
     assert ran >= 3
     # the batched kernel in every tile shape and either XCD order (whichever the sizes allow)
     shapes = 0
-    for rows_per_lane, term_slices in ((1, 1), (1, 2), (1, 4), (2, 1), (2, 2)):
+    for rows_per_lane, term_slices in ((1, 1), (1, 2), (1, 4), (2, 1), (2, 2), (2, 4)):
         for xcd_order in (1, 2):
             y = torch.full((B, d_out), 3.0e38, dtype=torch.float32, device="cuda")
             try:

@@ -120,6 +120,8 @@ def test_no_bias_and_no_seg(algo):
     {"term_slices": 2, "waves": 16, "neurons_per_wave": 3},
     {"rows_per_lane": 2, "term_slices": 2, "waves": 16, "neurons_per_wave": 3},
     {"rows_per_lane": 2, "term_slices": 2, "waves": 4, "neurons_per_wave": 4, "chunk_cols": 128},
+    {"rows_per_lane": 2, "term_slices": 4, "waves": 16, "neurons_per_wave": 3},
+    {"rows_per_lane": 2, "term_slices": 4, "waves": 8, "neurons_per_wave": 2, "chunk_cols": 192},
     {"term_slices": 2, "waves": 8, "neurons_per_wave": 6, "chunk_cols": 192},
     {"term_slices": 4, "waves": 8, "neurons_per_wave": 6},
     {"term_slices": 4, "waves": 16, "neurons_per_wave": 2, "chunk_cols": 128},
