@@ -406,7 +406,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     if (npw > rowlane_max_npw(p.R)) return p;
     p.NPW = npw;
     p.cost = shape_cost(npw);
-    p.KPRE = rowlane_kpre(npw);
+    p.KPRE = rowlane_kpre_rh(npw, p.R, p.H);
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
     p.bt_major = by_tiles(p.n_groups) ? 1 : 0;
     p.rounds = (int)rounds(p.n_groups, p.bt_major != 0);
@@ -432,7 +432,7 @@ static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
     const int BT = kWave * p.R / p.H;
     const double rounds = std::max(1, p.rounds);
     const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
-    const double per_step = p.R == 2 ? (p.H == 4 ? 0.0440 : (p.H == 2 ? 0.0356 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
+    const double per_step = p.R == 2 ? (p.H == 4 ? 0.0402 : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
     const double terms = (double)a.n_active * a.K;
     return 2.19 + rounds * (1.38 * p.n_chunks + 5.90e-6 * BT * a.d_in * 4.0 + per_step * steps + 1.45e-4 * BT * p.NW * p.NPW * 4.0) +
            (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);

@@ -57,6 +57,10 @@ constexpr int rowlane_max_threads(int) { return 1024; }
 constexpr int rowlane_max_npw(int R) { return R == 1 ? 6 : 4; }
 // blocks of 16 terms per (stored row, chunk) kept in registers, by stored rows per wavefront
 constexpr int rowlane_kpre(int npw) { return npw <= 3 ? 3 : (npw <= 4 ? 2 : 1); }
+// (two rows per lane with term slices: blocks are 32 or 64 terms, so fewer of them cover the same part of a row)
+constexpr int rowlane_kpre_rh(int npw, int R, int H) {
+    return (R == 2 && H >= 2) ? (rowlane_kpre(npw) < 2 ? rowlane_kpre(npw) : 2) : rowlane_kpre(npw);
+}
 srigl_status launch_rowlane_f32(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);
 srigl_status launch_rowlane_bf16(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);
 srigl_status launch_rowlane_f32_i16(const FwdArgs& a, const RowlanePlan& p, hipStream_t st);
