@@ -300,7 +300,8 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
 }
 
 constexpr int kRowlaneTwoRowsMinK = 32;
-constexpr int kRowlaneTwoRowsFourSlicesMinK = 100;   // blocks of 64 terms: measured 14 % slower than 32 x 2 tiles at a fan-in of 39
+constexpr int kRowlaneShortRowK = 200;
+constexpr int kRowlaneTwoRowsFourSlicesMinK = 64;   // blocks of 64 terms: measured 14 % slower than 32 x 2 tiles at a fan-in of 39
 
 static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t) {
     RowlanePlan p{};
@@ -407,6 +408,10 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     p.NPW = npw;
     p.cost = shape_cost(npw);
     p.KPRE = rowlane_kpre_rh(npw, p.R, p.H);
+    // 32-row tiles of two rows per lane: blocks are 64 terms, and rows shorter than ~200 terms run 4-10 % faster with one
+    // block preloaded per stored row and chunk than with two (less fetched beyond the chunk's share of the row), longer
+    // ones 4-8 % slower
+    if (p.R == 2 && p.H == 4 && a.K < kRowlaneShortRowK) p.KPRE = 1;
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
     p.bt_major = by_tiles(p.n_groups) ? 1 : 0;
     p.rounds = (int)rounds(p.n_groups, p.bt_major != 0);
@@ -432,7 +437,7 @@ static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
     const int BT = kWave * p.R / p.H;
     const double rounds = std::max(1, p.rounds);
     const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
-    const double per_step = p.R == 2 ? (p.H == 4 ? 0.0402 : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
+    const double per_step = p.R == 2 ? (p.H == 4 ? (a.K < kRowlaneShortRowK ? 0.0375 : 0.0402) : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
     const double terms = (double)a.n_active * a.K;
     return 2.19 + rounds * (1.38 * p.n_chunks + 5.90e-6 * BT * a.d_in * 4.0 + per_step * steps + 1.45e-4 * BT * p.NW * p.NPW * 4.0) +
            (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);
