@@ -301,6 +301,7 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
 
 constexpr int kRowlaneTwoRowsMinK = 32;
 constexpr int kRowlaneShortRowK = 200;
+constexpr int kRowlaneShortRowOneK = 128;
 constexpr int kRowlaneTwoRowsFourSlicesMinK = 64;   // blocks of 64 terms: measured 14 % slower than 32 x 2 tiles at a fan-in of 39
 
 static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t) {
@@ -412,6 +413,8 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     // block preloaded per stored row and chunk than with two (less fetched beyond the chunk's share of the row), longer
     // ones 4-8 % slower
     if (p.R == 2 && p.H == 4 && a.K < kRowlaneShortRowK) p.KPRE = 1;
+    // one row per lane in two or four slices: one block 3-10 % faster at fan-ins up to ~100, 1-5 % slower from 200
+    if (p.R == 1 && p.H > 1 && a.K < kRowlaneShortRowOneK) p.KPRE = 1;
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
     p.bt_major = by_tiles(p.n_groups) ? 1 : 0;
     p.rounds = (int)rounds(p.n_groups, p.bt_major != 0);

@@ -526,8 +526,8 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
 template <int R, int H, int NPW, typename XT, typename IT>
 static srigl_status launch_rowlane_k(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     constexpr int KPRE = rowlane_kpre_rh(NPW, R, H);
-    if constexpr (R == 2 && H == 4 && KPRE > 1) {
-        // short rows: one preloaded block of 64 terms per stored row and chunk (the host's choice, by fan-in)
+    if constexpr (H > 1 && !(R == 2 && H == 2) && KPRE > 1) {
+        // short rows: one preloaded block of 32 or 64 terms per stored row and chunk (the host's choice, by fan-in)
         if (p.KPRE == 1) return p.fast ? launch_rowlane_f<R, H, NPW, 1, XT, true, IT>(a, p, st) : SRIGL_ERR_UNSUPPORTED;
     }
     if (p.fast) return launch_rowlane_f<R, H, NPW, KPRE, XT, true, IT>(a, p, st);
