@@ -193,10 +193,10 @@ __device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const 
 // n_valid (wave-uniform, may be <= 0) of the block's terms are real; the others become (weight 0, all-zero column).
 template <typename XT, int H>
 __device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, int tofs, int off_mul, int off_add, int zero_off,
-                                             float& wv, int& ov) {
-    if (H > 1) {
-        w_raw = lane_fetch(w_raw, tofs * 4);
-        i_raw = lane_fetch(i_raw, tofs * 4);
+                                             float& wv, int& ov, int fetch_ofs = 0) {
+    if (H > 1) {   // fetch_ofs: first lane of the block when one load brought two blocks (lanes 0-31 and 32-63)
+        w_raw = lane_fetch(w_raw, (tofs + fetch_ofs) * 4);
+        i_raw = lane_fetch(i_raw, (tofs + fetch_ofs) * 4);
     }
     const bool real = tofs < n_valid;
     wv = real ? rl_to_f32<XT>(w_raw) : 0.0f;
@@ -215,6 +215,10 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     constexpr int S = rowlane_row_stride(BT, H);
     constexpr int S4 = S * 4;
     constexpr int TB = kBlock * H;           // terms per block (16 steps of H terms)
+    // Two slices with two preloaded blocks: one 64-lane load brings both blocks (64 consecutive terms, lane l holds term
+    // l) instead of two loads of 32 terms twice over; every vector-memory instruction costs the address unit the same
+    // 16 clocks whatever it returns, and the loads ahead of the first barrier are what that barrier waits for.
+    constexpr bool MERGE = (H == 2 && KPRE == 2);
     using V = typename RowVec<R>::type;
 
     // XCD-aware decode: consecutive workgroup ids go to different XCDs (8 of them), so the id modulo 8 selects the XCD.
@@ -324,8 +328,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #define SRIGL_PRELOAD(i, c)                                                                                     \
     {                                                                                                           \
         const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
-        _Pragma("unroll") for (int p = 0; p < KPRE; ++p)                                                        \
-            request_terms<XT, IT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, lofs, t_last, rw[i][p], ri[i][p]);      \
+        _Pragma("unroll") for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)                                          \
+            request_terms<XT, IT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]); \
     }
 
     float acc[NPW][R];
@@ -341,7 +345,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
-        for (int p = 0; p < KPRE; ++p) request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, lofs, t_last, rw[i][p], ri[i][p]);
+        for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)
+            request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
     SRIGL_STAMP(1)
@@ -372,7 +377,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 int po[KPRE];
 #pragma unroll
                 for (int p = 0; p < KPRE; ++p)
-                    finish_terms<XT, H>(rw[i][p], ri[i][p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p]);
+                    finish_terms<XT, H>(rw[i][MERGE ? 0 : p], ri[i][MERGE ? 0 : p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p],
+                                        MERGE ? p * TB : 0);
                 group_reads<R, 0>(xa, po[0], xb);
                 pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, (n_terms + H - 1) / H, xa, xc);
                 // long ranges: the remaining blocks, one at a time, each requested one block ahead
