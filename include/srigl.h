@@ -114,8 +114,11 @@ srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* m
  * active[n_active] strictly ascending columns in [0, d_out), or NULL when n_active == d_out
  * (the s-th stored neuron is column s) or n_active == 0; bias[d_out] fp32 or NULL (= zero, Alg. 1 verbatim);
  * y[B][d_out] fp32, fully overwritten.  Accumulation is fp32 (bf16 products are exact in fp32).
- * seg: the table written by condense / check_fanin for these idx, or NULL.  With seg == NULL, or
- * rows that are not ascending, only algorithms that do not depend on the order are used.
+ * seg: the table written by condense / check_fanin for these idx, or NULL.  Whenever seg is passed every row of idx
+ * must be strictly ascending (the library cannot see an unsorted row: validate once with srigl_check_fanin in index
+ * mode, which also writes seg; with unsorted rows and a seg table the batched kernel returns wrong sums without an
+ * error).  With seg == NULL only algorithms that do not depend on the order are used, and any in-range order, repeats
+ * included, is summed as Alg. 1 does.  seg != NULL with K > 65535 is SRIGL_ERR_UNSUPPORTED (its entries are 16 bits).
  * Out-of-range entries of `active` are skipped, never written.
  */
 srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
@@ -196,6 +199,19 @@ srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, sr
                                        int32_t n_active1, int32_t d_hidden, const float* bias1, srigl_activation act,
                                        int32_t* idx_out, void* W_out, float* bias_out, void* stream);
 
+/* The first layer of such a pair as it is run: it writes its n_active1 stored neurons next to each other into a hidden
+ * vector of `width` >= n_active1 columns (the caller may pad the width, e.g. to a multiple of 16; padding columns are
+ * neurons nobody reads).  bias_compact[width]: bias1[active1[p]] at position p < n_active1, zero behind; active_compact
+ * [n_active1]: p at position p (the active list of the compact layer when width > n_active1).  Either output may be NULL;
+ * bias1 == NULL is a zero bias, active1 == NULL means n_active1 == d_hidden.  Device pointers, asynchronous on `stream`.
+ *
+ * What a caller of the folded pair must know: the zero-weight fillers of a folded row sit at positions of real hidden
+ * neurons.  Alg. 1 multiplies them like any other term, so a hidden value that is not finite turns 0 * inf into NaN in
+ * rows that never named that neuron in the unfolded layer (srigl_densify + the dense product behave the same way: stored
+ * zeros times x).  The unfolded condensed call has no such term. */
+srigl_status srigl_compact_hidden_layer(const float* bias1, const int32_t* active1, int32_t n_active1, int32_t d_hidden, int32_t width,
+                                        float* bias_compact, int32_t* active_compact, void* stream);
+
 /* ---- narrow column indices ------------------------------------------------------------------------------
  * App. E: the condensed layer stores one column index per kept weight; that index array is all the representation
  * adds to the weights themselves.  A layer with d_in <= 65536 can hold it in 16 bits (half the index bytes; with
@@ -231,7 +247,7 @@ srigl_status srigl_csr_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B,
                                   const float* bias, int32_t d_out, float* y, srigl_activation act, void* stream);
 
 /* ---- one SRigL connectivity update of a layer ------------------------------------------------------------
- * Sec. 3.1, steps 1-7 (with App. G's minimum of one salient weight).  W, grad: fp32 [d_out][d_in]; mask: bytes, every
+ * Sec. 3.1, steps 1-7 (with the minimum of one salient weight stated in the appendix on tuning gamma_sal).  W, grad: fp32 [d_out][d_in]; mask: bytes, every
  * row holds 0 (ablated) or k kept weights; K_upd: the number of weights pruned and grown in this update (step 2, chosen
  * by the caller's schedule); gamma_percent: the ablation threshold gamma_sal in percent; budget: the number of weights the
  * layer may hold (normally k times its neurons that hold weights).  Outputs: mask_out (every row 0 or k' ones), W_out (kept
@@ -252,9 +268,9 @@ srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float*
                                void* workspace, size_t workspace_bytes, int64_t* report_dev, void* stream);
 
 /* ---- structured-only representation -----------------------------------------------------------------
- * Sec. 4.4 / Fig. 4 / App. H compare the condensed layer with the same layer "accelerated using only the
- * ablated neurons without exploiting the fine-grained sparsity": the stored neurons keep dense rows, and
- * the paper finds it faster at larger batch and modest sparsity, from the same set of weights.
+ * Sec. 4.4 / Fig. 4 / App. H compare the condensed layer with the same layer sped up by neuron ablation alone
+ * (the sparsity inside the remaining rows is not used): the stored neurons keep dense rows, and the paper finds
+ * it faster at larger batch and modest sparsity, from the same set of weights.
  *
  * srigl_densify: Wd[n_active][d_in] (w_dtype) <- the condensed rows scattered to their columns, zero
  * elsewhere (bit copies).  idx as in the forward call (in range; not checked here).

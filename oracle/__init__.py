@@ -195,6 +195,19 @@ def fold_ablated_inputs(idx2, W_c2, bias2, active2, d_out2, active1, d_hidden, b
     return idx_out, W_out, bias_out
 
 
+def compact_hidden_layer(bias1, active1, d_hidden, width):
+    """The first layer of a folded pair writes its stored neurons next to each other (Sec. 3.1: ablation reduces the layer's
+    width): position p of the compact hidden vector is neuron active1[p].  Returns (bias_compact[width], active_compact):
+    the stored neurons' biases in that order, zero at the padding positions, and the positions themselves."""
+    active1 = np.arange(d_hidden, dtype=np.int32) if active1 is None else np.asarray(active1, np.int32)
+    n1 = len(active1)
+    assert n1 <= width
+    out = np.zeros(width, dtype=np.float32)
+    for p in range(n1):
+        out[p] = 0.0 if bias1 is None else bias1[active1[p]]
+    return out, np.arange(n1, dtype=np.int32)
+
+
 def mask_update(W, mask, grad, k, K_upd, gamma_percent, budget=None):
     """One SRigL connectivity update of a layer (Sec. 3.1 steps 1-7).  Returns (mask', W', info) with info =
     {k_new, n_remaining, n_ablated_now, n_pruned}."""

@@ -10,7 +10,8 @@
 //     product of App. E, first equation, with W replaced by W (.) M, plus bias
 //     (Sec. 4.4 extracts "weights and bias" of the layer).
 //   * oracle_fwd_*               -- Alg. 1 (condensed forward), three nested
-//     loops b, n, k in the paper's order, output[b,n] += x[b, idx[n,k]] * w[n,k].
+//     loops b, n, k in the paper's order: every stored weight of neuron n times the
+//     input column its index names, summed into output (b, n).
 //     Readings where Alg. 1 is silent: a bias is added; the output has the full
 //     layer width and the s-th stored neuron writes column active[s]; every
 //     column of a neuron that is not stored (ablated, Sec. 3.1 step 4: all of
@@ -136,13 +137,13 @@ static void fwd_generic(const float* xf, const uint16_t* xh, int B, int d_in,
     for (int b = 0; b < B; ++b) {
         for (int n = 0; n < n_active; ++n) {
             double acc = 0.0, mag = 0.0;
-            for (int k = 0; k < K; ++k) {
-                int32_t source_idx = idx[(size_t)n * K + k];
-                double feature = xf ? (double)xf[(size_t)b * d_in + source_idx]
-                                    : (double)bf16_to_float(xh[(size_t)b * d_in + source_idx]);
-                double w = wf ? (double)wf[(size_t)n * K + k] : (double)bf16_to_float(wh[(size_t)n * K + k]);
-                acc += feature * w;
-                mag += std::fabs(feature * w);
+            for (int k = 0; k < K; ++k) {   // Alg. 1: the k-th stored weight of neuron n meets the input column it names
+                const size_t t = (size_t)n * K + k;
+                const size_t j = (size_t)b * d_in + idx[t];
+                const double xv = xf ? (double)xf[j] : (double)bf16_to_float(xh[j]);
+                const double wv = wf ? (double)wf[t] : (double)bf16_to_float(wh[t]);
+                acc += xv * wv;
+                mag += std::fabs(xv * wv);
             }
             int col = active ? active[n] : n;
             double bv = bias ? (double)bias[col] : 0.0;
@@ -197,8 +198,8 @@ void oracle_csr_fwd_f32(const float* x, int B, int d_in, const float* values, co
         }
 }
 
-// Structured-only representation (Sec. 4.4, Fig. 4 and App. H: the same layer "accelerated using only the
-// ablated neurons without exploiting the fine-grained sparsity"): the stored neurons keep dense rows.
+// Structured-only representation (Sec. 4.4, Fig. 4 and App. H: the same layer with the ablated neurons removed and
+// the sparsity inside the remaining rows left unused): the stored neurons keep dense rows.
 // densify: Wd[s][j] = W_c[s][t] where idx[s][t] == j, zero elsewhere (elements copied bit for bit).
 void oracle_densify(const void* W_c, int elem_bytes, const int32_t* idx, int n_active, int K, int d_in, void* Wd) {
     const unsigned char* wc = static_cast<const unsigned char*>(W_c);
@@ -304,7 +305,8 @@ int oracle_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, int elem_b
 //    both lie in its row.  (Taking "top-K" of the magnitudes literally would leave no salient weight, hence no neuron,
 //    once the update fraction has annealed to zero.)
 //  * step 4: a neuron that holds weights is ablated if its count is below max(gamma * k, 1), gamma = gamma_percent / 100
-//    (App. G: the minimum is one); a neuron without weights on entry stays ablated;
+//    (the appendix on tuning gamma_sal, caption of its figure of minimum salient weights per ResNet-50 layer: the
+//    minimum is one whenever gamma * k is below one); a neuron without weights on entry stays ablated;
 //  * step 5: k' = min(d_in, budget / number of remaining neurons) in integers (the layer keeps its weight budget);
 //  * step 6: the K_upd smallest-magnitude kept weights of the remaining neurons are pruned, layer-wide;
 //  * step 7: each remaining neuron keeps its unpruned weights (its k' largest, should it hold more than k') and grows the

@@ -31,7 +31,7 @@ EXPORTS = (
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
     "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
-    "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query", "srigl_fwd_plan_query_algo",
+    "srigl_compact_hidden_layer", "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query", "srigl_fwd_plan_query_algo",
 )
 
 
@@ -87,6 +87,8 @@ def _load() -> ctypes.CDLL:
                                                    vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
     lib.srigl_fold_ablated_inputs.restype = ctypes.c_int
     lib.srigl_fold_ablated_inputs.argtypes = [vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, i32, i32, vp, ctypes.c_int, vp, vp, vp, vp]
+    lib.srigl_compact_hidden_layer.restype = ctypes.c_int
+    lib.srigl_compact_hidden_layer.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     lib.srigl_mask_update_workspace_bytes.restype = sz
     lib.srigl_mask_update_workspace_bytes.argtypes = [i32, i32]
     lib.srigl_mask_update.restype = ctypes.c_int
@@ -270,6 +272,11 @@ def srigl_fold_ablated_inputs(idx2, W_c2, bias2, active2, n2, K2, d_out2, active
                                        int(d_out2), _ptr(active1), int(n_active1), int(d_hidden), _ptr(bias1), int(act),
                                        _ptr(idx_out), _ptr(W_out), _ptr(bias_out), _stream())
     _check(st, "srigl_fold_ablated_inputs")
+
+
+def srigl_compact_hidden_layer(bias1, active1, n_active1, d_hidden, width, bias_compact, active_compact):
+    _check(lib.srigl_compact_hidden_layer(_ptr(bias1), _ptr(active1), int(n_active1), int(d_hidden), int(width), _ptr(bias_compact),
+                                          _ptr(active_compact), _stream()), "srigl_compact_hidden_layer")
 
 
 def srigl_mask_update_workspace_bytes(d_out: int, d_in: int) -> int:

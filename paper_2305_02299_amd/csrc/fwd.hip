@@ -542,6 +542,7 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     if ((x_dtype != SRIGL_F32 && x_dtype != SRIGL_BF16) || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
     if (x_dtype != w_dtype) return SRIGL_ERR_UNSUPPORTED;
     if (idx_u16 && d_in > 65536) return SRIGL_ERR_UNSUPPORTED;
+    if (seg != nullptr && K > 65535) return SRIGL_ERR_UNSUPPORTED;   // seg entries are 16-bit term counts
     if (active == nullptr && n_active != d_out && n_active != 0) return SRIGL_ERR_INVALID_ARG;
     if (B == 0 || d_out == 0) return SRIGL_OK;
     if (y == nullptr) return SRIGL_ERR_INVALID_ARG;

@@ -7,14 +7,6 @@
 
 namespace srigl {
 
-#ifdef SRIGL_TIMELINE   // development builds only: per-wavefront cycle stamps at phase boundaries
-static __device__ long long g_timeline[16 * 4096];
-#define SRIGL_STAMP(slot)                                                                                       \
-    if (lane == 0 && blockIdx.x * 16 + wv_id < 4096) g_timeline[(blockIdx.x * 16 + wv_id) * 16 + (slot)] = clock64();
-#else
-#define SRIGL_STAMP(slot)
-#endif
-
 template <typename XT> __device__ __forceinline__ float rl_to_f32(XT v);
 template <> __device__ __forceinline__ float rl_to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float rl_to_f32<uint16_t>(uint16_t v) { return bf16_bits_to_float(v); }
@@ -253,7 +245,6 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     const int zero_off = C * S4;             // byte offset of the all-zero column
     const int segs_per_chunk = C / kSegCols;
     const int t_last = n_active * K - 1;     // the host guarantees n_active * K < 2^31
-    SRIGL_STAMP(0)
 
     // ---- chunk boundaries: lane j of bnd[i] holds the first term of chunk cb + j for slot s0 + i ----
     int bnd[NPW];
@@ -349,11 +340,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
-    SRIGL_STAMP(1)
     SRIGL_STAGE_STORE()
-    SRIGL_STAMP(2)
     __syncthreads();
-    SRIGL_STAMP(3)
 
     const char* xb = reinterpret_cast<const char*>(lds) + rowl * (R * 4);
     for (int c = 0; c < n_chunks; ++c) {
@@ -399,13 +387,10 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             }
             if (more) SRIGL_PRELOAD(i, c + 1)             // this slot's registers are free: request its next chunk
         }
-        SRIGL_STAMP(4 + 3 * (c < 3 ? c : 2))
         if (more) {
             __syncthreads();                              // every wavefront is done reading chunk c
             SRIGL_STAGE_STORE()
-            SRIGL_STAMP(5 + 3 * (c < 3 ? c : 2))
             __syncthreads();
-            SRIGL_STAMP(6 + 3 * (c < 3 ? c : 2))
         }
     }
 #undef SRIGL_LOAD_BOUNDS
@@ -450,7 +435,6 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             if (s < n_active && col >= 0 && col < d_out) biasv[h] = rl_bias_at(bias, col);
         }
     }
-    SRIGL_STAMP(13)
     const int n_rows = min(BT, B - b0);
     if (active) {
         // The stored columns of this workgroup and the ablated ones between them are one run of consecutive columns of
@@ -486,7 +470,6 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                     yr[c] = act == SRIGL_ACT_NONE ? v : apply_act(v, act);
                 }
             }
-            SRIGL_STAMP(14)
             return;
         }
     }
@@ -513,7 +496,6 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     };
     if (act == SRIGL_ACT_NONE) store_rows(std::false_type{});
     else store_rows(std::true_type{});
-    SRIGL_STAMP(14)
 }
 
 template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT>

@@ -14,6 +14,22 @@ __global__ __launch_bounds__(256) void k_copy_f32(const float* __restrict__ src,
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = src ? src[i] : 0.0f;
 }
 
+// The first layer of a folded pair writes its stored neurons only, next to each other: position p holds neuron active1[p],
+// bias_compact[p] = bias1[active1[p]] (zero at the padding positions p >= n_active1), active_compact[p] = p.
+__global__ __launch_bounds__(256) void k_compact_hidden(const float* __restrict__ bias1, const int32_t* __restrict__ active1, int n_active1,
+                                                        int d_hidden, int width, float* __restrict__ bias_compact,
+                                                        int32_t* __restrict__ active_compact) {
+    for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < width; p += gridDim.x * blockDim.x) {
+        float b = 0.0f;
+        if (p < n_active1 && bias1) {
+            const int j = active1 ? active1[p] : p;
+            if (j >= 0 && j < d_hidden) b = bias1[j];
+        }
+        if (bias_compact) bias_compact[p] = b;
+        if (active_compact && p < n_active1) active_compact[p] = p;
+    }
+}
+
 // One wavefront per stored row of the second layer; all LDS traffic stays inside the wavefront.
 // LDS per wavefront: V[K2] (compact positions of the kept terms, ascending), Wv[K2] (their weight bits),
 // Io[K2] / Wo[K2] (the output row).
@@ -150,6 +166,18 @@ srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, sr
         hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, st, idx2, static_cast<const uint16_t*>(W_c2), bias2, active2, n2, K2,
                            d_out2, active1, n_active1, d_hidden, bias1, (int)act, idx_out, static_cast<uint16_t*>(W_out), bias_out);
     }
+    return hip_ok(hipGetLastError());
+}
+
+srigl_status srigl_compact_hidden_layer(const float* bias1, const int32_t* active1, int32_t n_active1, int32_t d_hidden, int32_t width,
+                                        float* bias_compact, int32_t* active_compact, void* stream) {
+    if (n_active1 < 0 || d_hidden < 0 || width < n_active1 || n_active1 > d_hidden) return SRIGL_ERR_INVALID_ARG;
+    if (active1 == nullptr && n_active1 != d_hidden) return SRIGL_ERR_INVALID_ARG;
+    if (width == 0 || (bias_compact == nullptr && active_compact == nullptr)) return SRIGL_OK;
+    int blocks = (width + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_compact_hidden, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), bias1, active1, n_active1, d_hidden,
+                       width, bias_compact, active_compact);
     return hip_ok(hipGetLastError());
 }
 

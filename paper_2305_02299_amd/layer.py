@@ -114,10 +114,9 @@ def fold_mlp(layer1: CondensedLinear, layer2: CondensedLinear, act: int) -> Cond
     # The hidden vector's width is padded to a multiple of 16 columns (the batched kernel stages rows of whole 64-byte
     # pieces); the padding columns are "ablated neurons" with zero bias, which no row of the second layer reads.
     n1p = (n1 + 15) // 16 * 16
-    bias1_compact = torch.zeros((n1p,), dtype=torch.float32, device=dev)
-    if layer1.bias is not None:
-        bias1_compact[:n1] = layer1.bias if layer1.active is None else layer1.bias[layer1.active.long()]
-    active_first = None if n1p == n1 else torch.arange(n1, dtype=torch.int32, device=dev)
+    bias1_compact = torch.empty((n1p,), dtype=torch.float32, device=dev)
+    active_first = None if n1p == n1 else torch.empty((n1,), dtype=torch.int32, device=dev)
+    B_.srigl_compact_hidden_layer(layer1.bias, layer1.active, n1, layer1.d_out, n1p, bias1_compact, active_first)
     first = CondensedLinear(layer1.d_in, n1p, layer1.K, n1, layer1.W_c, layer1.idx, active_first, bias1_compact, layer1.seg)
     idx_f = torch.empty_like(layer2.idx)
     W_f = torch.empty_like(layer2.W_c)

@@ -135,6 +135,14 @@ def test_rowlane_launch_shapes(tuning):
         assert ran is not None or d_in % 16 != 0     # only the ragged-width layer may be refused (slow staging: H = R = 1)
 
 
+def test_rowlane_row_of_more_chunks_than_a_wavefront_has_lanes():
+    """65 chunks of 64 columns: the per-row register of chunk boundaries (one lane per chunk) is reloaded on the way."""
+    L = si.make_layer(4160, 40, 130, 70, ablate_frac=0.1, seed=79)
+    assert check_layer(L, B_.FWD_ROWLANE, {"rows_per_lane": 1, "term_slices": 1, "waves": 4, "neurons_per_wave": 2, "chunk_cols": 64}) is not None
+    L = si.make_layer(8192, 24, 300, 33, seed=80)      # 128 chunks: two reloads
+    assert check_layer(L, B_.FWD_ROWLANE, {"rows_per_lane": 1, "term_slices": 1, "waves": 2, "neurons_per_wave": 3, "chunk_cols": 64}) is not None
+
+
 @pytest.mark.parametrize("tuning", [{"lanes_per_neuron": l, "rows_per_block": r} for l in (1, 4, 16, 64) for r in (1, 2, 4, 8)])
 def test_klane_launch_shapes(tuning):
     for (d_in, d_out, K, B, abl) in ((768, 300, 77, 9, 0.1), (3072, 96, 307, 3, 0.3), (100, 64, 5, 1, 0.0)):
@@ -261,8 +269,11 @@ def test_large_layer_sampled_rows():
     L = si.config("c5")
     W_c, idx, active = oracle_condensed(L)
     assert W_c.shape == (13108, 205)
-    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 255, 256, 1023, 2046, 2047],
-                                     np.random.default_rng(5).integers(0, 2048, size=5)]))
+    # tile edges, and three interior rows of every 128-row tile (the tallest batch tile of the batched kernel)
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 255, 256, 1023, 2046, 2047]] +
+                                    [128 * t + rng.choice(np.arange(2, 126), size=3, replace=False) for t in range(16)]))
+    assert all(((rows // 128 == t) & (rows % 128 > 1) & (rows % 128 < 126)).sum() >= 2 for t in range(16))
     y_ref, S = oracle.fwd(L.x_bf16[rows], W_c, idx, active, L.bias, L.d_out, want_scale=True)
     for algo in (None, B_.FWD_ROWLANE):
         y = run_gpu(L, W_c, idx, active, L.bias, algo)

@@ -90,6 +90,24 @@ def test_fold_without_ablation_is_the_identity(B_):
     assert np.array_equal(host(idx_o), idx2) and host(W_o).tobytes() == W_c2.tobytes() and np.array_equal(host(bias_o), L2.bias)
 
 
+@pytest.mark.parametrize("shape", [(3072, 0.3, True), (100, 0.0, True), (64, 0.5, False), (1, 0.0, True)])
+def test_compact_hidden_layer_matches_oracle(B_, shape):
+    d_hidden, abl, with_bias = shape
+    rng = np.random.default_rng(d_hidden)
+    n1 = d_hidden - int(abl * d_hidden)
+    active1 = None if n1 == d_hidden else np.sort(rng.choice(d_hidden, n1, replace=False)).astype(np.int32)
+    bias1 = rng.normal(0, 1, d_hidden).astype(np.float32) if with_bias else None
+    width = (n1 + 15) // 16 * 16
+    bias_ref, act_ref = oracle.compact_hidden_layer(bias1, active1, d_hidden, width)
+    bias_o = torch.full((width,), 7.0, device="cuda")
+    act_o = torch.full((n1,), -5, dtype=torch.int32, device="cuda")
+    B_.srigl_compact_hidden_layer(dev(bias1), dev(active1), n1, d_hidden, width, bias_o, act_o)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(bias_o).view(np.uint32), bias_ref.view(np.uint32)) and np.array_equal(host(act_o), act_ref)
+    with pytest.raises(B_.SriglError):
+        B_.srigl_compact_hidden_layer(dev(bias1), dev(active1), n1, d_hidden, n1 - 1, bias_o, act_o)
+
+
 def test_fold_refuses_a_fan_in_wider_than_the_compact_layer(B_):
     idx2 = torch.arange(5, dtype=torch.int32, device="cuda")[None, :].contiguous()
     W = torch.ones((1, 5), device="cuda")

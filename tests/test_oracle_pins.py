@@ -362,6 +362,38 @@ def test_folded_pair_equals_the_unfolded_pair(act, dtype):
         assert not unused_smaller                     # fillers are the smallest unused positions
 
 
+def test_compact_hidden_layer_is_the_first_layer_without_its_ablated_columns():
+    """Pin: the full-width first layer's output restricted to the stored columns equals the compact layer's output when
+    the compact layer uses bias_compact and writes position p for stored neuron p (Alg. 1 on both sides)."""
+    L = si.make_layer(48, 40, 7, 5, ablate_frac=0.4, seed=12)
+    W_c, idx, active = oracle.condense(L.W, L.mask, L.K)
+    width = (len(active) + 15) // 16 * 16
+    bias_c, active_c = oracle.compact_hidden_layer(L.bias, active, L.d_out, width)
+    full = oracle.fwd(L.x, W_c, idx, active, L.bias, L.d_out)
+    compact = oracle.fwd(L.x, W_c, idx, active_c, bias_c, width)
+    assert np.array_equal(compact[:, :len(active)].view(np.uint32), full[:, active].view(np.uint32))
+    assert (compact[:, len(active):] == 0).all() and active_c.tolist() == list(range(len(active)))
+    b0, a0 = oracle.compact_hidden_layer(None, None, 4, 6)
+    assert b0.tolist() == [0.0] * 6 and a0.tolist() == [0, 1, 2, 3]
+
+
+def test_a_filler_of_a_folded_row_meets_a_non_finite_hidden_value():
+    """What the header of srigl_compact_hidden_layer warns of: a folded row is refilled with zero-weight entries at real
+    hidden positions, and Alg. 1 multiplies every stored term, so an infinite hidden value there gives 0 * inf = NaN in a
+    row that never named that neuron; the unfolded layer has no such term."""
+    d_hidden = 6
+    active1 = np.array([0, 2, 3, 5], np.int32)                  # neurons 1 and 4 of layer 1 are ablated
+    idx2 = np.array([[1, 5]], np.int32)                         # the row reads ablated neuron 1 and stored neuron 5
+    W2 = np.array([[0.5, 2.0]], np.float32)
+    bias1 = np.zeros(d_hidden, np.float32)
+    idx_f, W_f, bias_f = oracle.fold_ablated_inputs(idx2, W2, None, None, 1, active1, d_hidden, bias1, 0)
+    assert idx_f.tolist() == [[0, 3]] and W_f.tolist() == [[0.0, 2.0]]          # filler at compact position 0 = neuron 0
+    hidden_full = np.array([[np.inf, 0.0, 1.0, 1.0, 0.0, 3.0]], np.float32)     # neuron 0 overflowed; the row never named it
+    y_unfolded = oracle.fwd(hidden_full, W2, idx2, None, None, 1)
+    y_folded = oracle.fwd(hidden_full[:, active1], W_f, idx_f, None, bias_f, 1)
+    assert y_unfolded[0, 0] == 6.0 and np.isnan(y_folded[0, 0])
+
+
 def test_fold_refuses_a_fan_in_wider_than_the_compact_layer():
     idx2 = np.arange(5, dtype=np.int32)[None, :]
     with pytest.raises(ValueError):
