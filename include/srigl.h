@@ -100,11 +100,32 @@ srigl_status srigl_check_fanin(const uint8_t* mask, const int32_t* idx, int32_t 
  * reported (status = SRIGL_ERR_FANIN); the other outputs are then not meaningful.
  * seg (optional, may be NULL): [cap_rows][srigl_seg_stride(d_in)] uint16 as in check_fanin.
  * K > 65535 with seg != NULL is SRIGL_ERR_UNSUPPORTED.
+ * packed (optional, may be NULL): receives the streaming copy of the first min(n_active, cap_rows) stored rows (see
+ * srigl_packed_bytes); 16-byte aligned, packed_bytes >= srigl_packed_bytes(cap_rows, K, d_in, w_dtype), else
+ * SRIGL_ERR_INVALID_ARG / SRIGL_ERR_CAPACITY.  W_c and idx stay the result that defines the layer; the copy is derived.
  */
 srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* mask, int32_t d_out,
                             int32_t d_in, int32_t K, int32_t cap_rows, void* W_c, int32_t* idx,
-                            int32_t* active, uint16_t* seg, void* workspace, size_t workspace_bytes,
-                            srigl_report* report_dev, void* stream);
+                            int32_t* active, uint16_t* seg, void* packed, size_t packed_bytes, void* workspace,
+                            size_t workspace_bytes, srigl_report* report_dev, void* stream);
+
+/* The streaming copy of a condensed layer.  App. E's representation is the two n x k arrays; how they lie in memory
+ * for the forward pass is free, and W_c / idx as separate row-major arrays of K = 77, 205, 307 ... words per row leave
+ * every row at another alignment, so a lane can fetch only one 4-byte (2-byte) word per load.  The copy holds the same
+ * terms neuron-major in units of four consecutive terms of a row, the four weights of a unit next to its four column
+ * indices (rows padded to whole units with weight 0 / index 0; 16-bit indices beside bf16 weights when d_in <= 65536),
+ * so that one or two 16-byte loads bring a lane its four terms and a lane group reads consecutive units.  The layout
+ * belongs to the library: callers size the buffer with srigl_packed_bytes, have srigl_condense or srigl_pack_terms fill
+ * it, and hand it to the forward call together with W_c / idx.  It must describe the same rows as W_c / idx.
+ *
+ * srigl_packed_bytes: bytes for n_rows stored rows (0 when any size is not positive).
+ * srigl_pack_terms: the copy from W_c[n_rows][K] / idx[n_rows][K] (for layers that did not come out of srigl_condense,
+ * e.g. the folded second layer of an MLP block).  Index values are copied as they are (the 16-bit form keeps their low
+ * 16 bits: validate with srigl_check_fanin first).  Device pointers, `packed` 16-byte aligned, asynchronous on `stream`. */
+size_t srigl_packed_bytes(int32_t n_rows, int32_t K, int32_t d_in, srigl_dtype w_dtype);
+
+srigl_status srigl_pack_terms(const void* W_c, srigl_dtype w_dtype, const int32_t* idx, int32_t n_rows, int32_t K, int32_t d_in,
+                              void* packed, size_t packed_bytes, void* stream);
 
 /* srigl_condensed_linear_fwd -- Alg. 1 (condensed linear layer forward) plus bias and the scatter of
  * stored neurons to their columns.

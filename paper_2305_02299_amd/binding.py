@@ -27,6 +27,7 @@ TILES = {"256x256": TILE_256x256, "256x256_h": TILE_256x256_H, "256x128_w4": TIL
 
 EXPORTS = (
     "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense",
+    "srigl_packed_bytes", "srigl_pack_terms",
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
@@ -67,7 +68,11 @@ def _load() -> ctypes.CDLL:
     lib.srigl_check_fanin.restype = ctypes.c_int
     lib.srigl_check_fanin.argtypes = [vp, vp, i32, i32, i32, vp, vp, sz, vp, vp]
     lib.srigl_condense.restype = ctypes.c_int
-    lib.srigl_condense.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.srigl_condense.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, sz, vp, vp]
+    lib.srigl_packed_bytes.restype = sz
+    lib.srigl_packed_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
+    lib.srigl_pack_terms.restype = ctypes.c_int
+    lib.srigl_pack_terms.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, vp, sz, vp]
     lib.srigl_condensed_linear_fwd.restype = ctypes.c_int
     lib.srigl_condensed_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.srigl_condensed_linear_fwd_algo.restype = ctypes.c_int
@@ -173,11 +178,24 @@ def srigl_check_fanin(mask, idx, n_rows, d_in, K_expected, seg, workspace, repor
     _check(st, "srigl_check_fanin")
 
 
-def srigl_condense(W, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, workspace, report):
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def srigl_condense(W, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, workspace, report, packed=None):
     st = lib.srigl_condense(_ptr(W), _dtype_code(W), _ptr(mask), int(d_out), int(d_in), int(K), int(cap_rows), _ptr(W_c),
-                            _ptr(idx), _ptr(active), _ptr(seg), _ptr(workspace),
-                            0 if workspace is None else workspace.numel() * workspace.element_size(), _ptr(report), _stream())
+                            _ptr(idx), _ptr(active), _ptr(seg), _ptr(packed), _nbytes(packed), _ptr(workspace), _nbytes(workspace),
+                            _ptr(report), _stream())
     _check(st, "srigl_condense")
+
+
+def srigl_packed_bytes(n_rows: int, K: int, d_in: int, dtype_code: int) -> int:
+    return int(lib.srigl_packed_bytes(int(n_rows), int(K), int(d_in), int(dtype_code)))
+
+
+def srigl_pack_terms(W_c, idx, n_rows, K, d_in, packed):
+    _check(lib.srigl_pack_terms(_ptr(W_c), _dtype_code(W_c), _ptr(idx), int(n_rows), int(K), int(d_in), _ptr(packed), _nbytes(packed),
+                                _stream()), "srigl_pack_terms")
 
 
 def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, d_out, y, seg=None, algo=None, tuning=None, act=None):

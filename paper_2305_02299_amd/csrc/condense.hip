@@ -159,12 +159,14 @@ __global__ __launch_bounds__(1024) void k_scan_rows(const int32_t* __restrict__ 
 
 // One wavefront per row: ordered stream compaction of the kept columns.
 // T = bit container of one weight (uint32_t for fp32, uint16_t for bf16).
+// With `packed` the same pass also writes the streaming copy (see PackedLayout): term `pos` of stored row s goes to unit
+// pos / 4, place pos % 4, and the places behind the K-th term of the last unit get weight bits 0 and index 0.
 template <typename T>
 __global__ __launch_bounds__(kRowsPerBlock* kWave) void k_compact_rows(const T* __restrict__ W, const uint8_t* __restrict__ mask,
                                                                      int d_out, int d_in, int K, int cap_rows,
                                                                      const int32_t* __restrict__ slot, T* __restrict__ W_c,
                                                                      int32_t* __restrict__ idx, uint16_t* __restrict__ seg,
-                                                                     int seg_stride) {
+                                                                     int seg_stride, unsigned char* __restrict__ packed, PackedLayout pl) {
     const int lane = threadIdx.x & (kWave - 1);
     const int r = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     if (r >= d_out) return;
@@ -176,6 +178,7 @@ __global__ __launch_bounds__(kRowsPerBlock* kWave) void k_compact_rows(const T* 
     T* wc = W_c + (size_t)s * K;
     int32_t* ix = idx + (size_t)s * K;
     uint16_t* sg = seg ? seg + (size_t)s * seg_stride : nullptr;
+    unsigned char* pk = packed ? packed + (size_t)s * pl.row_bytes() : nullptr;
 
     int base = 0;   // kept columns seen in earlier iterations (same in every lane)
     int chunk = 0;  // index of the next seg entry; one iteration covers 256 columns = 4 entries
@@ -202,7 +205,12 @@ __global__ __launch_bounds__(kRowsPerBlock* kWave) void k_compact_rows(const T* 
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             if ((nz >> (8 * p + 7)) & 1u) {
-                if (pos < K) { ix[pos] = col + p; wc[pos] = w[col + p]; }
+                if (pos < K) {
+                    const T wbits = w[col + p];
+                    ix[pos] = col + p;
+                    wc[pos] = wbits;
+                    if (pk) pl.store(pk, pos, (uint32_t)wbits, col + p);
+                }
                 ++pos;
             }
         }
@@ -210,6 +218,25 @@ __global__ __launch_bounds__(kRowsPerBlock* kWave) void k_compact_rows(const T* 
     }
     if (sg)
         for (int c = chunk + lane; c < seg_stride; c += kWave) sg[c] = (uint16_t)base;
+    if (pk)
+        for (int t = K + lane; t < pl.units * 4; t += kWave) pl.store(pk, t, 0u, 0);
+}
+
+// The streaming copy from the canonical arrays: one thread per place of a unit, padding included.
+__global__ __launch_bounds__(256) void k_pack_terms(const void* __restrict__ W_c, const int32_t* __restrict__ idx, int n_rows, int K,
+                                                    unsigned char* __restrict__ packed, PackedLayout pl) {
+    const long long places = (long long)n_rows * pl.units * 4;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < places; i += (long long)gridDim.x * blockDim.x) {
+        const int s = (int)(i / (pl.units * 4)), t = (int)(i - (long long)s * pl.units * 4);
+        uint32_t wbits = 0u;
+        int col = 0;
+        if (t < K) {
+            const size_t e = (size_t)s * K + t;
+            wbits = pl.w_bytes == 4 ? static_cast<const uint32_t*>(W_c)[e] : (uint32_t)static_cast<const uint16_t*>(W_c)[e];
+            col = idx[e];
+        }
+        pl.store(packed + (size_t)s * pl.row_bytes(), t, wbits, col);
+    }
 }
 
 __global__ void k_empty() {}
@@ -258,18 +285,20 @@ srigl_status srigl_check_fanin(const uint8_t* mask, const int32_t* idx, int32_t 
     return hip_ok(hipGetLastError());
 }
 
-srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* mask, int32_t d_out,
-                            int32_t d_in, int32_t K, int32_t cap_rows, void* W_c, int32_t* idx,
-                            int32_t* active, uint16_t* seg, void* workspace, size_t workspace_bytes,
-                            srigl_report* report_dev, void* stream) {
-    hipStream_t st = static_cast<hipStream_t>(stream);
+static srigl_status condense_core(const void* W, srigl_dtype w_dtype, const uint8_t* mask, int32_t d_out, int32_t d_in, int32_t K,
+                                  int32_t cap_rows, void* W_c, int32_t* idx, int32_t* active, uint16_t* seg, void* packed,
+                                  size_t packed_bytes, void* workspace, srigl_report* report_dev, hipStream_t st) {
     if (d_out < 0 || d_in < 0 || K < 0 || K > d_in || cap_rows < 0 || report_dev == nullptr) return SRIGL_ERR_INVALID_ARG;
     if (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16) return SRIGL_ERR_INVALID_ARG;
     if (d_out > 0 && d_in > 0 && (W == nullptr || mask == nullptr)) return SRIGL_ERR_INVALID_ARG;
     if (cap_rows > 0 && (active == nullptr || (K > 0 && (W_c == nullptr || idx == nullptr)))) return SRIGL_ERR_INVALID_ARG;
     if (seg && K > 65535) return SRIGL_ERR_UNSUPPORTED;
     if (d_out > 0 && workspace == nullptr) return SRIGL_ERR_INVALID_ARG;
-    if (workspace_bytes < srigl_workspace_bytes(d_out)) return SRIGL_ERR_CAPACITY;
+    const PackedLayout pl = packed_layout(K, d_in, w_dtype == SRIGL_BF16);
+    if (packed) {
+        if (reinterpret_cast<uintptr_t>(packed) % 16 != 0) return SRIGL_ERR_INVALID_ARG;
+        if (packed_bytes < srigl_packed_bytes(cap_rows, K, d_in, w_dtype)) return SRIGL_ERR_CAPACITY;
+    }
     int32_t* counts = static_cast<int32_t*>(workspace);
     int32_t* slot = counts + d_out;
     const int blocks = (d_out + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -280,12 +309,40 @@ srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* m
         if (w_dtype == SRIGL_F32)
             hipLaunchKernelGGL(k_compact_rows<uint32_t>, dim3(blocks), dim3(kRowsPerBlock * kWave), 0, st,
                                static_cast<const uint32_t*>(W), mask, d_out, d_in, K, cap_rows, slot,
-                               static_cast<uint32_t*>(W_c), idx, seg, ss);
+                               static_cast<uint32_t*>(W_c), idx, seg, ss, static_cast<unsigned char*>(packed), pl);
         else
             hipLaunchKernelGGL(k_compact_rows<uint16_t>, dim3(blocks), dim3(kRowsPerBlock * kWave), 0, st,
                                static_cast<const uint16_t*>(W), mask, d_out, d_in, K, cap_rows, slot,
-                               static_cast<uint16_t*>(W_c), idx, seg, ss);
+                               static_cast<uint16_t*>(W_c), idx, seg, ss, static_cast<unsigned char*>(packed), pl);
     }
+    return hip_ok(hipGetLastError());
+}
+
+srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* mask, int32_t d_out,
+                            int32_t d_in, int32_t K, int32_t cap_rows, void* W_c, int32_t* idx,
+                            int32_t* active, uint16_t* seg, void* packed, size_t packed_bytes, void* workspace,
+                            size_t workspace_bytes, srigl_report* report_dev, void* stream) {
+    if (d_out >= 0 && workspace_bytes < srigl_workspace_bytes(d_out)) return SRIGL_ERR_CAPACITY;
+    return condense_core(W, w_dtype, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, packed, packed_bytes, workspace,
+                         report_dev, static_cast<hipStream_t>(stream));
+}
+
+size_t srigl_packed_bytes(int32_t n_rows, int32_t K, int32_t d_in, srigl_dtype w_dtype) {
+    if (n_rows <= 0 || K <= 0 || d_in <= 0 || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return 0;
+    return (size_t)n_rows * packed_layout(K, d_in, w_dtype == SRIGL_BF16).row_bytes();
+}
+
+srigl_status srigl_pack_terms(const void* W_c, srigl_dtype w_dtype, const int32_t* idx, int32_t n_rows, int32_t K, int32_t d_in,
+                              void* packed, size_t packed_bytes, void* stream) {
+    if (n_rows < 0 || K < 0 || d_in < 0 || K > d_in || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
+    if (n_rows == 0 || K == 0) return SRIGL_OK;
+    if (W_c == nullptr || idx == nullptr || packed == nullptr || reinterpret_cast<uintptr_t>(packed) % 16 != 0) return SRIGL_ERR_INVALID_ARG;
+    if (packed_bytes < srigl_packed_bytes(n_rows, K, d_in, w_dtype)) return SRIGL_ERR_CAPACITY;
+    const PackedLayout pl = packed_layout(K, d_in, w_dtype == SRIGL_BF16);
+    long long blocks = ((long long)n_rows * pl.units * 4 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_pack_terms, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), W_c, idx, n_rows, K,
+                       static_cast<unsigned char*>(packed), pl);
     return hip_ok(hipGetLastError());
 }
 

@@ -15,6 +15,41 @@ constexpr int kWave = 64;              // CDNA wavefront width
 constexpr int kSegCols = 64;           // columns per entry of the seg table
 constexpr size_t kLdsMax = 160 * 1024; // LDS per workgroup on gfx950
 
+// The streaming copy of the condensed arrays (App. E: values and column indices, n x k each) that srigl_condense and
+// srigl_pack_terms write and the forward kernels may read instead of W_c / idx.  Neuron-major; a row is ceil(K / 4) units
+// of four consecutive terms; a unit holds the four weights, then the four indices, so that the terms a lane works on come
+// with one or two 16-byte loads from one 32-byte piece and a lane group reads consecutive units:
+//   fp32 weights:                       unit = w[4] fp32, idx[4] int32                      (32 bytes)
+//   bf16 weights, d_in <= 65536:        unit = w[4] bf16, idx[4] uint16                     (16 bytes: one load)
+//   bf16 weights, wider inputs:         unit = w[4] bf16, 8 bytes of zeros, idx[4] int32    (32 bytes)
+// Places behind the K-th term carry weight bits 0 and index 0.
+struct PackedLayout {
+    int units;        // units per row
+    int unit_bytes;   // 16 or 32
+    int w_bytes;      // 4 or 2
+    int i_bytes;      // 4 or 2
+    int i_off;        // byte offset of the indices inside a unit
+    __host__ __device__ size_t row_bytes() const { return (size_t)units * unit_bytes; }
+    // term t of a row whose packed copy starts at `row`: weight bits and column
+    __device__ void store(unsigned char* row, int t, uint32_t wbits, int col) const {
+        unsigned char* u = row + (size_t)(t >> 2) * unit_bytes;
+        const int p = t & 3;
+        if (w_bytes == 4) reinterpret_cast<uint32_t*>(u)[p] = wbits; else reinterpret_cast<uint16_t*>(u)[p] = (uint16_t)wbits;
+        if (i_bytes == 4) reinterpret_cast<int32_t*>(u + i_off)[p] = col; else reinterpret_cast<uint16_t*>(u + i_off)[p] = (uint16_t)col;
+        if (unit_bytes == 32 && w_bytes == 2) reinterpret_cast<uint16_t*>(u + 8)[p] = 0;
+    }
+};
+inline PackedLayout packed_layout(int K, int d_in, bool bf16) {
+    PackedLayout pl;
+    pl.units = (K + 3) / 4;
+    pl.w_bytes = bf16 ? 2 : 4;
+    const bool narrow = bf16 && d_in <= 65536;
+    pl.i_bytes = narrow ? 2 : 4;
+    pl.unit_bytes = narrow ? 16 : 32;
+    pl.i_off = narrow ? 8 : 16;
+    return pl;
+}
+
 struct FwdArgs {
     const void* x;
     int32_t x_bf16;
@@ -29,6 +64,7 @@ struct FwdArgs {
     float* y;
     const uint16_t* seg;
     int32_t seg_stride;
+    const void* packed;  // the streaming copy of W_c / idx (PackedLayout), or nullptr
     int32_t act;   // srigl_activation applied to every written value (stored and ablated columns alike)
 };
 

@@ -69,6 +69,40 @@ def test_condense_bit_exact(d_in, d_out, K, abl, dtype):
     assert _gpu_check_mask(L.mask) == oracle.check_fanin_mask(L.mask)
 
 
+@pytest.mark.parametrize("d_in,d_out,K,abl,dtype", SHAPES + [(70000, 6, 9, 0.0, "bf16")])
+def test_packed_copy_bit_exact(d_in, d_out, K, abl, dtype):
+    """The streaming copy written by srigl_condense, and by srigl_pack_terms from the canonical arrays, against the oracle's
+    bytes; rows past n_active stay untouched."""
+    L = si.make_layer(d_in, d_out, K, 1, ablate_frac=abl, dtype=dtype, seed=100 + d_in)
+    Wsrc = L.W_bf16 if dtype == "bf16" else L.W
+    W_c_o, idx_o, act_o = oracle.condense(Wsrc, L.mask, K)
+    n = len(act_o)
+    ref = oracle.pack_terms(W_c_o, idx_o, d_in)
+    code = B_.BF16 if dtype == "bf16" else B_.F32
+    nbytes = B_.srigl_packed_bytes(d_out, K, d_in, code)
+    assert nbytes == d_out * ref.shape[1] and B_.srigl_packed_bytes(n, K, d_in, code) == ref.size
+    W, m = dev(Wsrc), dev(L.mask)
+    W_c = torch.empty((d_out, K), dtype=W.dtype, device="cuda")
+    idx = torch.empty((d_out, K), dtype=torch.int32, device="cuda")
+    active = torch.empty((d_out,), dtype=torch.int32, device="cuda")
+    packed = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws, rep = B_.new_workspace(d_out), B_.new_report()
+    B_.srigl_condense(W, m, d_out, d_in, K, d_out, W_c, idx, active, None, ws, rep, packed=packed)
+    torch.cuda.synchronize()
+    assert B_.read_report(rep)["status"] == 0
+    got = host(packed).reshape(d_out, -1)
+    assert np.array_equal(got[:n], ref) and (got[n:] == 0xA5).all()
+    assert np.array_equal(host(idx)[:n], idx_o)
+    packed2 = torch.full((ref.size,), 0x5A, dtype=torch.uint8, device="cuda")
+    B_.srigl_pack_terms(dev(W_c_o), dev(idx_o), n, K, d_in, packed2)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(packed2).reshape(n, -1), ref)
+    # too small a buffer is refused on the host
+    with pytest.raises(B_.SriglError) as e:
+        B_.srigl_condense(W, m, d_out, d_in, K, d_out, W_c, idx, active, None, ws, rep, packed=packed[:nbytes - 16])
+    assert e.value.status == B_.ERR_CAPACITY
+
+
 def test_condense_special_values_are_bit_copied():
     L = si.make_layer(64, 6, 4, 1, seed=7)
     specials = np.array([0x80000000, 0x00000000, 0x7FC00123, 0xFF800000], np.uint32).view(np.float32)
