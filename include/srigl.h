@@ -127,6 +127,19 @@ size_t srigl_packed_bytes(int32_t n_rows, int32_t K, int32_t d_in, srigl_dtype w
 srigl_status srigl_pack_terms(const void* W_c, srigl_dtype w_dtype, const int32_t* idx, int32_t n_rows, int32_t K, int32_t d_in,
                               void* packed, size_t packed_bytes, void* stream);
 
+/* srigl_condense for callers that cannot allocate device memory or pass scratch of their own: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as srigl_condense
+ * without `workspace`: the per-row counts and slots live in an array inside the library (8 bytes per row of W,
+ * SRIGL_STATIC_MAX_ROWS rows: 512 KiB per GPU, held until the process ends).  d_out > SRIGL_STATIC_MAX_ROWS returns
+ * SRIGL_ERR_CAPACITY and launches nothing.  The call allocates and frees nothing (the first call on a device looks the
+ * array's address up, which is not an allocation).  Every call on a GPU uses that GPU's one array: calls that may
+ * overlap on one GPU (different streams without an order between them) race and must be ordered by the caller; calls
+ * in order need no clearing in between (each call writes what it reads). */
+#define SRIGL_STATIC_MAX_ROWS 65536
+srigl_status srigl_condense_static(const void* W, srigl_dtype w_dtype, const uint8_t* mask, int32_t d_out, int32_t d_in, int32_t K,
+                                   int32_t cap_rows, void* W_c, int32_t* idx, int32_t* active, uint16_t* seg, void* packed,
+                                   size_t packed_bytes, srigl_report* report_dev, void* stream);
+
 /* srigl_condensed_linear_fwd -- Alg. 1 (condensed linear layer forward) plus bias and the scatter of
  * stored neurons to their columns.
  *

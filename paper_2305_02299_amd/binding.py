@@ -26,7 +26,7 @@ TILES = {"256x256": TILE_256x256, "256x256_h": TILE_256x256_H, "256x128_w4": TIL
          "128x128": TILE_128x128, "64x64": TILE_64x64}
 
 EXPORTS = (
-    "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense",
+    "srigl_workspace_bytes", "srigl_seg_stride", "srigl_check_fanin", "srigl_condense", "srigl_condense_static",
     "srigl_packed_bytes", "srigl_pack_terms",
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
@@ -69,6 +69,8 @@ def _load() -> ctypes.CDLL:
     lib.srigl_check_fanin.argtypes = [vp, vp, i32, i32, i32, vp, vp, sz, vp, vp]
     lib.srigl_condense.restype = ctypes.c_int
     lib.srigl_condense.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, sz, vp, vp]
+    lib.srigl_condense_static.restype = ctypes.c_int
+    lib.srigl_condense_static.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.srigl_packed_bytes.restype = sz
     lib.srigl_packed_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
     lib.srigl_pack_terms.restype = ctypes.c_int
@@ -187,6 +189,13 @@ def srigl_condense(W, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, wor
                             _ptr(idx), _ptr(active), _ptr(seg), _ptr(packed), _nbytes(packed), _ptr(workspace), _nbytes(workspace),
                             _ptr(report), _stream())
     _check(st, "srigl_condense")
+
+
+def srigl_condense_static(W, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, report, packed=None):
+    """srigl_condense with the library's built-in scratch in place of a workspace (no allocation on either side)."""
+    st = lib.srigl_condense_static(_ptr(W), _dtype_code(W), _ptr(mask), int(d_out), int(d_in), int(K), int(cap_rows), _ptr(W_c),
+                                   _ptr(idx), _ptr(active), _ptr(seg), _ptr(packed), _nbytes(packed), _ptr(report), _stream())
+    _check(st, "srigl_condense_static")
 
 
 def srigl_packed_bytes(n_rows: int, K: int, d_in: int, dtype_code: int) -> int:

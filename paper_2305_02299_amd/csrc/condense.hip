@@ -10,6 +10,13 @@
 // ballots and prefix popcounts (no LDS, no atomics).
 #include "srigl_internal.h"
 
+#include <mutex>
+
+// Scratch of srigl_condense_static (the condense call for callers that cannot allocate): the per-row counts and slots that
+// srigl_condense takes from its workspace argument.  One copy per GPU, held until the process ends.  The name is a host-side
+// stand-in: kernels get the device address that hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[2 * sizeof(int32_t) * (size_t)SRIGL_STATIC_MAX_ROWS + 256];
+
 namespace srigl {
 
 constexpr int kRowsPerBlock = 4;   // 4 wavefronts of 64 lanes, one row each
@@ -325,6 +332,37 @@ srigl_status srigl_condense(const void* W, srigl_dtype w_dtype, const uint8_t* m
     if (d_out >= 0 && workspace_bytes < srigl_workspace_bytes(d_out)) return SRIGL_ERR_CAPACITY;
     return condense_core(W, w_dtype, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, packed, packed_bytes, workspace,
                          report_dev, static_cast<hipStream_t>(stream));
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static srigl_status scratch_on_current_device(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptr[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SRIGL_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return SRIGL_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SRIGL_ERR_HIP;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return SRIGL_OK;
+}
+
+srigl_status srigl_condense_static(const void* W, srigl_dtype w_dtype, const uint8_t* mask, int32_t d_out, int32_t d_in, int32_t K,
+                                   int32_t cap_rows, void* W_c, int32_t* idx, int32_t* active, uint16_t* seg, void* packed,
+                                   size_t packed_bytes, srigl_report* report_dev, void* stream) {
+    if (d_out > SRIGL_STATIC_MAX_ROWS) return SRIGL_ERR_CAPACITY;   // more rows than the built-in scratch holds
+    void* ws = nullptr;
+    const srigl_status st = scratch_on_current_device(&ws);
+    if (st != SRIGL_OK) return st;
+    // every count and slot of rows [0, d_out) is written by the first two kernels before anything reads it, so what an
+    // earlier call left in the scratch is never seen and nothing has to be cleared
+    return condense_core(W, w_dtype, mask, d_out, d_in, K, cap_rows, W_c, idx, active, seg, packed, packed_bytes, ws, report_dev,
+                         static_cast<hipStream_t>(stream));
 }
 
 size_t srigl_packed_bytes(int32_t n_rows, int32_t K, int32_t d_in, srigl_dtype w_dtype) {
