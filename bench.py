@@ -10,9 +10,9 @@ Timing: W warm-up steps, then exactly K steps, captured in one HIP graph so that
 back to back, between two HIP events on the stream they are launched on, bracketed by device
 synchronisation; the graph is replayed five times and the headline is the median (Fig. 4's protocol:
 median of at least five runs, standard deviation beside it).  The headline is HBM-cold: the K
-launches walk through independent copies of every operand (enough copies to exceed twice the
-Infinity Cache), and a 1 GiB device copy flushes L2 and Infinity Cache ahead of every timed replay,
-so no launch finds its operands cached whatever K is.  The same loop on one fixed set of buffers
+launches walk through independent copies of every operand, and ahead of every timed replay a spacer
+graph runs the same kernel on other copies worth twice the Infinity Cache (512 MB), so no launch
+finds its operands in L2 or Infinity Cache whatever K is.  The same loop on one fixed set of buffers
 ("warm") is reported beside it, as are batch 1, the dispatch floor of an empty kernel, a dense torch
 matmul of the same layer, and the CPU oracle on the host cores.
 
@@ -184,6 +184,100 @@ def sweep(args):
         del sets, layer
 
 
+def point(args):
+    """--point NAME|d_in,d_out,K[,bf16][,ablate=F]: one layer at --batch rows, optionally in a forced kernel (--algo) and launch
+    shape (--tuning JSON); cold (spacer graph on other operand copies ahead of each timed replay) and warm us/call, the launch
+    shape the library takes, and the algorithmic bytes.  One JSON line.  The command the profiles/ summaries are made with."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2305_02299_amd import binding as B_
+    from paper_2305_02299_amd import condense_layer
+
+    torch.cuda.set_device(0)
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+    B = args.batch
+    if "," in args.point:
+        f = args.point.split(",")
+        abl = [float(v.split("=")[1]) for v in f if v.startswith("ablate=")]
+        L = si.make_layer(int(f[0]), int(f[1]), int(f[2]), B, dtype="bf16" if "bf16" in f else "f32", ablate_frac=abl[0] if abl else 0.0,
+                          seed=0)
+    else:
+        L = si.config(args.point, B=B) if args.point == "c3" else si.config(args.point)
+        B = L.B if args.point != "c3" else B
+    bf16 = L.dtype == "bf16"
+    layer = condense_layer(dev(L.W_bf16 if bf16 else L.W), dev(L.mask), L.K, dev(L.bias))
+    x = dev((L.x_bf16 if bf16 else L.x)[:B])
+    algo = {None: None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE}[args.algo]
+    tuning = json.loads(args.tuning) if args.tuning else None
+    if tuning is not None and algo is None:
+        algo = B_.FWD_ROWLANE if any(k in tuning for k in ("rows_per_lane", "term_slices", "waves", "neurons_per_wave", "chunk_cols")) \
+            else B_.FWD_KLANE
+    nbytes = algorithmic_bytes(layer.n_active, L.K, B, L.d_in, L.d_out, 2 if bf16 else 4)
+    n_rot = min(max(2, -(-2 * CACHE_BYTES // nbytes)), 400)
+    steps = max(2, min(args.steps, 200, int(4e8 // nbytes)))
+    sets = [(x.clone(), layer.W_c.clone(), layer.idx.clone(), None if layer.active is None else layer.active.clone(),
+             layer.bias.clone(), layer.seg.clone(), None if args.no_packed else layer.packed.clone(),
+             torch.empty((B, L.d_out), device="cuda")) for _ in range(n_rot + min(steps, n_rot))]
+
+    def on(ss):
+        def f(i):
+            xx, W_c, idx, act, bias, seg, pk, y = ss[i % len(ss)]
+            B_.srigl_condensed_linear_fwd(xx, B, L.d_in, W_c, idx, act, layer.n_active, L.K, bias, L.d_out, y, seg, algo=algo, tuning=tuning,
+                                          packed=pk)
+        return f
+
+    def capture(fn, n):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            fn(0)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        return g
+
+    def timed(g, spacer=None):
+        out = []
+        for _ in range(5):
+            if spacer is not None:
+                spacer.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / steps * 1e3)
+        return out
+
+    n_timed = min(steps, n_rot)
+    spacer = capture(on(sets[n_timed:]), n_rot)
+    cold = timed(capture(on(sets[:n_timed]), steps), spacer)
+    warm = timed(capture(on(sets[:1]), steps))
+    plan = B_.srigl_fwd_plan_query(B, L.d_in, layer.n_active, L.K, L.d_out, B_.BF16 if bf16 else B_.F32, layer.active is not None, True,
+                                   algo=algo, tuning=tuning)
+    # one plain device copy of known size (256 MiB read, 256 MiB written): the reference that byte counters are scaled by
+    ref_src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    ref_dst = torch.empty_like(ref_src)
+    B_.srigl_copy_bytes(ref_src, ref_dst, ref_src.numel())
+    torch.cuda.synchronize()
+    flops = 2.0 * B * layer.n_active * L.K
+    c, w = statistics.median(cold), statistics.median(warm)
+    print(json.dumps({"point": args.point, "d_in": L.d_in, "d_out": L.d_out, "K": L.K, "n_active": layer.n_active, "B": B, "dtype": L.dtype,
+                      "us_cold": round(c, 2), "us_cold_std": round(statistics.pstdev(cold), 3), "us_warm": round(w, 2),
+                      "us_warm_std": round(statistics.pstdev(warm), 3), "steps": steps, "algorithmic_bytes": nbytes,
+                      "gbs_cold": round(nbytes / c / 1e3, 1), "hbm_frac_cold": round(nbytes / c / 1e3 / HBM_PEAK_GBS, 4),
+                      "gflops_cold": round(flops / c / 1e3, 1), "gflops_warm": round(flops / w / 1e3, 1),
+                      "streaming_copy": not args.no_packed, "plan": plan}), flush=True)
+
+
 def structured(args, emit=True):
     """--structured: the structured-only form of the 4096->16384 bf16 layer at B=2048 (dense rows of the stored neurons on the
     matrix cores), one JSON line; the condensed form of the same layer and the library's dense matmul as context."""
@@ -282,8 +376,28 @@ def mlp(args, emit=True, points=None):
         return best
 
     rows = []
+    if points is None:
+        # what the barrier across workgroups costs by itself: the one-launch call on a block with next to no work (one term per
+        # neuron, 256 neurons per layer), against an empty kernel and against two launches of the same tiny layers
+        T1 = si.make_layer(16, 256, 1, 1, seed=3)
+        T2 = si.make_layer(256, 256, 1, 1, seed=4)
+        t1 = condense_layer(dev(T1.W), dev(T1.mask), 1, dev(T1.bias))
+        t2 = condense_layer(dev(T2.W), dev(T2.mask), 1, dev(T2.bias))
+        xt, ht, yt = dev(T1.x), torch.empty((1, 256), device="cuda"), torch.empty((1, 256), device="cuda")
+        t_b = time_graph(lambda i: B_.srigl_condensed_mlp_fwd(xt, 1, 16, t1.packed, None, 256, 1, t1.bias, 256, B_.ACT_GELU, ht, t2.packed, None,
+                                                              256, 1, t2.bias, 256, yt), 200, 5) * 1e3
+        t_e = time_graph(lambda i: B_.srigl_launch_empty(), 200, 5) * 1e3
+
+        def two(i):
+            t1.forward(xt, ht)
+            t2.forward(ht, yt)
+        t_2 = time_graph(two, 200, 5) * 1e3
+        rows.append({"block": "16->256->256, one term per neuron (next to no work)", "B": 1, "us_one_launch_with_barrier": round(t_b, 2),
+                     "us_two_launches": round(t_2, 2), "us_empty_kernel": round(t_e, 2)})
+        if emit:
+            print(json.dumps(rows[-1]), flush=True)
     for abl in (0.0, 0.3, 0.7):
-        for B in (1, 16, 256, 1024):
+        for B in (1, 4, 8, 16, 256, 1024):
             if points is not None and (abl, B) not in points:
                 continue
             L1 = si.make_layer(768, 3072, 77, B, ablate_frac=abl, seed=1)
@@ -303,9 +417,11 @@ def mlp(args, emit=True, points=None):
 
             steps = 200 if B <= 256 else 50
             t_u = time_graph(unfolded, steps, 5) * 1e3
-            t_f = time_graph(lambda i: pair.forward(x, y, h_c), steps, 5) * 1e3
+            t_f = time_graph(lambda i: pair.forward(x, y, h_c, fused=False), steps, 5) * 1e3
+            t_1 = time_graph(lambda i: pair.forward(x, y, h_c, fused=True), steps, 5) * 1e3 if B <= 8 else None
             rows.append({"block": "768->3072 GELU 3072->768, K=77/308", "hidden_ablated": abl, "hidden_stored": l1.n_active, "B": B,
-                         "us_full_width": round(t_u, 2), "us_folded": round(t_f, 2)})
+                         "us_full_width": round(t_u, 2), "us_folded": round(t_f, 2),
+                         "us_folded_one_launch": None if t_1 is None else round(t_1, 2)})
             if emit:
                 print(json.dumps(rows[-1]), flush=True)
     return rows
@@ -468,7 +584,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c2", choices=["c2", "c3"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-packed", action="store_true", help="forward calls on the W_c / idx arrays alone (no streaming copy)")
     ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane"])
+    ap.add_argument("--point", default=None, help="time one layer: c1|c2|c3|c5 or d_in,d_out,K[,bf16][,ablate=F]; see --batch, --algo, --tuning")
+    ap.add_argument("--batch", type=int, default=256, help="--point: batch rows (named configurations other than c3 keep their own)")
+    ap.add_argument("--tuning", default=None, help="--point: JSON object of srigl_fwd_tuning fields to force a launch shape")
     ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")
     ap.add_argument("--no-large", action="store_true", help="--sweep without the 4096->16384 bf16 layer")
     ap.add_argument("--no-csr", action="store_true", help="--sweep without the library CSR product (context column)")
@@ -482,6 +602,8 @@ def main():
         log("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus)
         sys.exit(2)
 
+    if args.point:
+        return point(args)
     if args.sweep:
         return sweep(args)
     if args.structured:
@@ -524,19 +646,8 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps
 
-    evict_src = torch.empty(2 * CACHE_BYTES, dtype=torch.uint8, device="cuda")
-    evict_dst = torch.empty_like(evict_src)
-
-    def evict():
-        """Streams 2 x 512 MB (twice the Infinity Cache, read and written) through the plain copy kernel, so that nothing the
-        next launches read is left in L2 or Infinity Cache."""
-        B_.srigl_copy_bytes(evict_src, evict_dst, evict_src.numel())
-
-    def time_graph(fn, steps, warmup, reps=5, cold=False):
-        """ms per step, one figure per repetition: the `steps` launches are captured once in a HIP graph (they reach the GPU
-        back to back, so a figure is what the device needs per call, kernel + dispatch, not what Python needs) and the
-        graph is replayed `reps` times, each replay between two events on the stream it runs on.  cold: the caches are
-        flushed with evict() ahead of every timed replay (outside the events)."""
+    def capture(fn, steps, warmup):
+        """The launches fn(0) .. fn(steps - 1) captured in one HIP graph (replayed once, untimed, to upload it)."""
         side = torch.cuda.Stream()
         with torch.cuda.stream(side):
             for i in range(warmup):
@@ -546,12 +657,21 @@ def main():
         with torch.cuda.graph(g):
             for i in range(steps):
                 fn(i)
-        g.replay()                      # untimed: uploads the graph
+        g.replay()
         torch.cuda.synchronize()
+        return g
+
+    def time_graph(fn, steps, warmup, reps=5, spacer=None):
+        """ms per step, one figure per repetition: the `steps` launches are captured once in a HIP graph (they reach the GPU
+        back to back, so a figure is what the device needs per call, kernel + dispatch, not what Python needs) and the
+        graph is replayed `reps` times, each replay between two events on the stream it runs on.  spacer: a graph replayed
+        (untimed, same stream) ahead of every timed replay; the cold loop uses it to push the timed launches' operands out
+        of L2 and Infinity Cache."""
+        g = capture(fn, steps, warmup)
         out = []
         for _ in range(reps):
-            if cold:
-                evict()
+            if spacer is not None:
+                spacer.replay()
             e0, e1 = ev(), ev()
             e0.record()
             g.replay()
@@ -580,27 +700,36 @@ def main():
             sets.append((xs.clone(), layer.W_c.clone(), layer.idx.clone(),
                          None if layer.active is None else layer.active.clone(), layer.bias.clone(),
                          None if layer.seg is None else layer.seg.clone(),
-                         torch.empty((B, d_out), dtype=torch.float32, device="cuda")))
+                         torch.empty((B, d_out), dtype=torch.float32, device="cuda"), layer.packed.clone()))
         return sets
 
-    def fwd_on(sets, B):
+    def fwd_on(sets, B, use_packed=True):
         n = len(sets)
 
         def f(i):
-            x, W_c, idx, act, bias, seg, y = sets[i % n]
-            B_.srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, act, n_active, K, bias, d_out, y, seg, algo=algo)
+            x, W_c, idx, act, bias, seg, y, packed = sets[i % n]
+            B_.srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, act, n_active, K, bias, d_out, y, seg, algo=algo,
+                                          packed=packed if use_packed else None)
         return f
 
     results = {}
-    for B in (Bn, 1):
+    # (batch, with the streaming copy of W_c / idx): the two headline batches as the library is meant to be called, and batch 1
+    # on the canonical arrays alone for comparison
+    for B, use_packed in ((Bn, not args.no_packed), (1, not args.no_packed), (1, args.no_packed)):
         nbytes = algorithmic_bytes(n_active, K, B, d_in, d_out, 4)
-        n_sets = max(2, -(-2 * CACHE_BYTES // nbytes))
-        sets = make_sets(B, n_sets)
-        f_cold, f_warm = fwd_on(sets, B), fwd_on(sets[:1], B)
         steps = args.steps
-        # the K timed steps of the contract: one graph of `steps` launches, replayed 5 times from flushed caches; a launch
-        # re-reads an operand set only after every other set has been read (>= 512 MB) or after the flush
-        cold_reps = time_graph(f_cold, steps, args.warmup, reps=5, cold=True)
+        # HBM-cold at any number of steps: the timed launches walk n_timed operand sets of their own, and a spacer graph
+        # of the same kernel on n_rot other sets (>= 512 MB, twice the Infinity Cache) runs ahead of every timed replay,
+        # so at least 512 MB of other operands pass between two reads of any set (by the spacer, or, when steps > n_rot,
+        # by the timed walk itself); code, descriptors and address translations stay as they are in a serving loop
+        n_rot = max(2, -(-2 * CACHE_BYTES // nbytes))
+        n_timed = min(steps, n_rot)
+        sets = make_sets(B, n_timed + n_rot)
+        f_cold, f_warm, f_spacer = (fwd_on(sets[:n_timed], B, use_packed), fwd_on(sets[:1], B, use_packed),
+                                    fwd_on(sets[n_timed:], B, use_packed))
+        spacer = capture(f_spacer, n_rot, 2)
+        n_sets = n_timed + n_rot
+        cold_reps = time_graph(f_cold, steps, args.warmup, reps=5, spacer=spacer)
         warm_reps = time_graph(f_warm, steps, args.warmup, reps=5)
         cold, warm = statistics.median(cold_reps), statistics.median(warm_reps)
         eager = time_loop(f_cold, steps, args.warmup)           # same calls launched one by one from Python
@@ -613,24 +742,26 @@ def main():
             torch.cuda.synchronize()
             lat.append((time.perf_counter() - t0) * 1e6)
         flops = 2.0 * B * n_active * K
-        results[B] = {
+        key = B if use_packed != args.no_packed else "1_other_operand_form"
+        results[key] = {
+            "streaming_copy": use_packed,
             "us_per_call_cold": cold * 1e3, "us_per_call_warm": warm * 1e3, "us_per_call_python_launched": eager * 1e3,
             "us_cold_replays": [round(t * 1e3, 3) for t in cold_reps], "us_cold_std": statistics.pstdev(cold_reps) * 1e3,
             "us_warm_replays": [round(t * 1e3, 3) for t in warm_reps], "us_warm_std": statistics.pstdev(warm_reps) * 1e3,
             "sync_call_latency_us_median": statistics.median(lat),
-            "algorithmic_bytes": nbytes, "operand_sets": n_sets, "operand_sets_touched_per_replay": min(steps, n_sets),
+            "algorithmic_bytes": nbytes, "operand_sets": n_sets, "operand_sets_timed": n_timed, "operand_sets_spacer": n_rot,
             "hbm_gbs_cold": nbytes / (cold * 1e-3) / 1e9, "effective_gbs_warm": nbytes / (warm * 1e-3) / 1e9,
             "gflops_cold": flops / (cold * 1e-3) / 1e9, "gflops_warm": flops / (warm * 1e-3) / 1e9,
         }
-        results[B]["hbm_roofline_frac_cold"] = results[B]["hbm_gbs_cold"] / HBM_PEAK_GBS
-        log("B=%d: cold %.2f us (median of 5 replays, std %.2f), warm %.2f us (std %.2f), %.0f GB/s cold = %.1f%% of 8 TB/s, %.0f GFLOP/s"
-            % (B, cold * 1e3, results[B]["us_cold_std"], warm * 1e3, results[B]["us_warm_std"],
-               results[B]["hbm_gbs_cold"], 100 * results[B]["hbm_roofline_frac_cold"], results[B]["gflops_cold"]))
-        del sets
+        results[key]["hbm_roofline_frac_cold"] = results[key]["hbm_gbs_cold"] / HBM_PEAK_GBS
+        log("B=%d%s: cold %.2f us (median of 5 replays, std %.2f), warm %.2f us (std %.2f), %.0f GB/s cold = %.1f%% of 8 TB/s, %.0f GFLOP/s"
+            % (B, " (streaming copy)" if use_packed else " (W_c / idx arrays)", cold * 1e3, results[key]["us_cold_std"], warm * 1e3,
+               results[key]["us_warm_std"], results[key]["hbm_gbs_cold"], 100 * results[key]["hbm_roofline_frac_cold"],
+               results[key]["gflops_cold"]))
+        del sets, spacer
 
     # ---- context: dispatch floor, copy bandwidth, dense torch matmul ----
     t_empty = statistics.median(time_graph(lambda i: B_.srigl_launch_empty(), 1000, 10))
-    del evict_src, evict_dst
     big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     big2 = torch.empty_like(big)
     t_copy = time_loop(lambda i: B_.srigl_copy_bytes(big, big2, big.numel()), 10, 2)
@@ -660,7 +791,7 @@ def main():
         y_ref, S_ref = oracle.fwd(L.x, W_c_h, idx_h, act_h, L.bias, d_out, want_scale=True)
         y_gpu = torch.empty((Bn, d_out), device="cuda")
         B_.srigl_condensed_linear_fwd(dev(L.x), Bn, d_in, layer.W_c, layer.idx, layer.active, n_active, K, layer.bias, d_out, y_gpu,
-                                      layer.seg, algo=algo)
+                                      layer.seg, algo=algo, packed=None if args.no_packed else layer.packed)
         torch.cuda.synchronize()
         err = np.abs(y_gpu.cpu().numpy().astype(np.float64) - y_ref.astype(np.float64))
         parity = {"max_err_over_term_scale": float(np.max(err / np.maximum(np.maximum(np.abs(y_ref), S_ref), 1e-300))),
@@ -688,10 +819,11 @@ def main():
         "metric": "condensed_linear_fwd_us_per_call", "value": r["us_per_call_cold"], "unit": "us/call",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["us_per_call_cold"] / 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d->%d fp32, K=%d (90%% sparse), n_active=%d, B=%d; HBM-cold: caches flushed by a 1 GiB copy "
-                               "before each of 5 timed replays of the %d-launch graph, which walks %d of %d operand sets; value = median"
-                               % (args.workload, d_in, d_out, K, n_active, Bn, args.steps, r["operand_sets_touched_per_replay"],
-                                  r["operand_sets"]),
+        "config": {"workload": "%s: %d->%d fp32, K=%d (90%% sparse), n_active=%d, B=%d; HBM-cold: the %d timed launches walk %d "
+                               "operand sets, and %d launches on %d other sets (%d MB) run ahead of each of 5 timed replays; value = median"
+                               % (args.workload, d_in, d_out, K, n_active, Bn, args.steps, r["operand_sets_timed"],
+                                  r["operand_sets_spacer"], r["operand_sets_spacer"],
+                                  r["operand_sets_spacer"] * r["algorithmic_bytes"] // 1000000),
                    "algo": args.algo or "auto"},
         "value_std_us": r["us_cold_std"],
         "roofline": {"bound": "hbm", "achieved": r["hbm_gbs_cold"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -706,7 +838,7 @@ def main():
                                "(context.empty_kernel_us); batch 256 is bound by the LDS gather (lds_gather.frac_warm) and vector "
                                "issue (valu_frac_of_fp32_peak), batch 1 by launch plus two dependent memory round trips"},
         "cpu_baseline": cpu, "cpu_baseline_all_cores": cpu_all, "parity_vs_oracle": parity,
-        "batch256": r, "batch1": results[1],
+        "batch256": r, "batch1": results[1], "batch1_other_operand_form": results["1_other_operand_form"],
         "gflops_effective": r["gflops_cold"],
         "hbm_frac_of_measured_copy_bw": r["hbm_gbs_cold"] / copy_gbs,
         "valu_frac_of_fp32_peak": r["gflops_cold"] / 1e3 / FP32_VALU_PEAK_TFLOPS,

@@ -153,18 +153,21 @@ srigl_status srigl_condense_static(const void* W, srigl_dtype w_dtype, const uin
  * mode, which also writes seg; with unsorted rows and a seg table the batched kernel returns wrong sums without an
  * error).  With seg == NULL only algorithms that do not depend on the order are used, and any in-range order, repeats
  * included, is summed as Alg. 1 does.  seg != NULL with K > 65535 is SRIGL_ERR_UNSUPPORTED (its entries are 16 bits).
+ * packed: the streaming copy of these W_c / idx rows (srigl_condense, srigl_pack_terms), 16-byte aligned, or NULL.  The
+ * kernels that can stream it read it in place of W_c / idx (which must still be passed: other kernels read them); the
+ * same terms are summed, possibly in another order (same tolerance).
  * Out-of-range entries of `active` are skipped, never written.
  */
 srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
                                         const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
                                         const int32_t* active, int32_t n_active, int32_t K,
                                         const float* bias, int32_t d_out, float* y,
-                                        const uint16_t* seg, void* stream);
+                                        const uint16_t* seg, const void* packed, void* stream);
 
 /* Launch-shape knobs of the forward kernels (host struct).  0 in a field = the library's default.
  * Values the kernels cannot run are rejected with SRIGL_ERR_UNSUPPORTED, never launched. */
 typedef struct {
-    int32_t rows_per_lane;    /* ROWLANE: batch rows per lane, 1 or 2                                       */
+    int32_t rows_per_lane;    /* ROWLANE: batch rows per lane, 1, 2 or 4 (4: with 2 or 4 term slices only)  */
     int32_t waves;            /* ROWLANE: wavefronts per workgroup, 1..16                                  */
     int32_t neurons_per_wave; /* ROWLANE: stored neurons accumulated per wavefront, 1..8                   */
     int32_t chunk_cols;       /* ROWLANE: activation columns per LDS tile, multiple of 64                  */
@@ -184,7 +187,7 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
                                              const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
                                              const int32_t* active, int32_t n_active, int32_t K,
                                              const float* bias, int32_t d_out, float* y,
-                                             const uint16_t* seg, srigl_fwd_algo algo,
+                                             const uint16_t* seg, const void* packed, srigl_fwd_algo algo,
                                              const srigl_fwd_tuning* tuning, void* stream);
 
 /* What the library's own choice (SRIGL_FWD_AUTO) would launch for a forward call of these sizes: the kernel and its
@@ -218,7 +221,7 @@ srigl_status srigl_condensed_linear_fwd_act(const void* x, srigl_dtype x_dtype, 
                                             const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
                                             const int32_t* active, int32_t n_active, int32_t K,
                                             const float* bias, int32_t d_out, float* y,
-                                            const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
+                                            const uint16_t* seg, const void* packed, srigl_activation act, srigl_fwd_algo algo,
                                             const srigl_fwd_tuning* tuning, void* stream);
 
 /* Width reduction.  Layer 1 has d_hidden neurons of which active1[0..n_active1) are stored (NULL: all of them); an
@@ -246,6 +249,23 @@ srigl_status srigl_fold_ablated_inputs(const int32_t* idx2, const void* W_c2, sr
 srigl_status srigl_compact_hidden_layer(const float* bias1, const int32_t* active1, int32_t n_active1, int32_t d_hidden, int32_t width,
                                         float* bias_compact, int32_t* active_compact, void* stream);
 
+/* Both layers of an MLP block in one launch, for online inference and batches of up to 8 rows (App. H: the timed layer is
+ * one linear of a ViT block: linear, GELU, linear; Sec. 3.1: layer 1's ablation is layer 2's width reduction):
+ *   hidden[b][c] = act(bias1[c] + sum_k W1[s][k] x[b][idx1[s][k]]) for stored neuron s of layer 1 at column c = active1[s]
+ *                  (other columns: act(bias1[c])),   y = bias2 + layer 2 applied to hidden (ablated columns: bias2).
+ * Both layers fp32, each given by its streaming copy (packed1: n_active1 rows of fan-in K1 over d_in columns; packed2:
+ * n_active2 rows of fan-in K2 over d_hidden columns), its active list (NULL: every neuron stored) and bias (NULL: zero).
+ * x[B][d_in], hidden[B][d_hidden] (scratch of the caller, fully overwritten), y[B][d_out].  One launch of 256 workgroups with
+ * a barrier across them between the layers (a counter inside the library, one per GPU: calls that may overlap on one GPU
+ * must be ordered by the caller, and the 256 workgroups must be able to be resident together, which they are on an idle
+ * MI355X).  A workgroup that polls the counter more than spin_limit times (<= 0: about a million) stops waiting, the call's
+ * result is then wrong and *status_dev (device int32, may be NULL; set it to 0 before the call) becomes 1: every wavefront
+ * exits either way.  SRIGL_ERR_UNSUPPORTED for B > 8 or a layer without terms (use two forward calls). */
+srigl_status srigl_condensed_mlp_fwd(const float* x, int32_t B, int32_t d_in, const void* packed1, const int32_t* active1, int32_t n_active1,
+                                     int32_t K1, const float* bias1, int32_t d_hidden, srigl_activation act, float* hidden,
+                                     const void* packed2, const int32_t* active2, int32_t n_active2, int32_t K2, const float* bias2,
+                                     int32_t d_out, float* y, int32_t spin_limit, int32_t* status_dev, void* stream);
+
 /* ---- narrow column indices ------------------------------------------------------------------------------
  * App. E: the condensed layer stores one column index per kept weight; that index array is all the representation
  * adds to the weights themselves.  A layer with d_in <= 65536 can hold it in 16 bits (half the index bytes; with
@@ -257,7 +277,7 @@ srigl_status srigl_compact_hidden_layer(const float* bias1, const int32_t* activ
  *
  * srigl_condensed_linear_fwd_idx16: srigl_condensed_linear_fwd_act with idx16[n_active][K] in place of idx; every
  * other argument, the result and the errors are the same (same kernels, same order of additions: the output is
- * bit-identical to the 32-bit call on the same layer).  d_in > 65536 is SRIGL_ERR_UNSUPPORTED. */
+ * bit-identical to the 32-bit call on the same arrays without a streaming copy).  d_in > 65536 is SRIGL_ERR_UNSUPPORTED. */
 srigl_status srigl_narrow_idx(const int32_t* idx, int64_t n, int32_t d_in, uint16_t* idx16, void* stream);
 
 srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,

@@ -32,7 +32,7 @@ EXPORTS = (
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
     "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
     "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
-    "srigl_compact_hidden_layer", "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query", "srigl_fwd_plan_query_algo",
+    "srigl_compact_hidden_layer", "srigl_condensed_mlp_fwd", "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query", "srigl_fwd_plan_query_algo",
 )
 
 
@@ -76,10 +76,10 @@ def _load() -> ctypes.CDLL:
     lib.srigl_pack_terms.restype = ctypes.c_int
     lib.srigl_pack_terms.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, vp, sz, vp]
     lib.srigl_condensed_linear_fwd.restype = ctypes.c_int
-    lib.srigl_condensed_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32, vp, vp, vp]
+    lib.srigl_condensed_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]
     lib.srigl_condensed_linear_fwd_algo.restype = ctypes.c_int
     lib.srigl_condensed_linear_fwd_algo.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32,
-                                                    vp, vp, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
+                                                    vp, vp, vp, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
     lib.srigl_densify.restype = ctypes.c_int
     lib.srigl_densify.argtypes = [vp, ctypes.c_int, vp, i32, i32, i32, vp, vp]
     lib.srigl_structured_linear_fwd.restype = ctypes.c_int
@@ -91,11 +91,13 @@ def _load() -> ctypes.CDLL:
                                                 ctypes.POINTER(ctypes.c_float)]
     lib.srigl_condensed_linear_fwd_act.restype = ctypes.c_int
     lib.srigl_condensed_linear_fwd_act.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, vp, i32, i32, vp, i32,
-                                                   vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
+                                                   vp, vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(FwdTuning), vp]
     lib.srigl_fold_ablated_inputs.restype = ctypes.c_int
     lib.srigl_fold_ablated_inputs.argtypes = [vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, i32, i32, vp, ctypes.c_int, vp, vp, vp, vp]
     lib.srigl_compact_hidden_layer.restype = ctypes.c_int
     lib.srigl_compact_hidden_layer.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.srigl_condensed_mlp_fwd.restype = ctypes.c_int
+    lib.srigl_condensed_mlp_fwd.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, i32, ctypes.c_int, vp, vp, vp, i32, i32, vp, i32, vp, i32, vp, vp]
     lib.srigl_mask_update_workspace_bytes.restype = sz
     lib.srigl_mask_update_workspace_bytes.argtypes = [i32, i32]
     lib.srigl_mask_update.restype = ctypes.c_int
@@ -207,36 +209,36 @@ def srigl_pack_terms(W_c, idx, n_rows, K, d_in, packed):
                                 _stream()), "srigl_pack_terms")
 
 
-def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, d_out, y, seg=None, algo=None, tuning=None, act=None):
+def _tuning(tuning):
+    if tuning is None:
+        return None
+    tn = FwdTuning()
+    for k, v in tuning.items():
+        setattr(tn, k, int(v))
+    return tn
+
+
+def srigl_condensed_linear_fwd(x, B, d_in, W_c, idx, active, n_active, K, bias, d_out, y, seg=None, algo=None, tuning=None, act=None,
+                               packed=None):
     """algo None: the library's own entry point; otherwise the forced-algorithm entry point; act: the entry point with an
-    activation in the epilogue (ACT_* codes); idx in a 16-bit container: the narrow-index entry point."""
-    if idx.dtype in (torch.int16, torch.uint16) or act is not None:
-        tn = None
-        if tuning is not None:
-            tn = FwdTuning()
-            for k, v in tuning.items():
-                setattr(tn, k, int(v))
-        narrow = idx.dtype != torch.int32   # a 16-bit container carries unsigned 16-bit column indices
-        fn = lib.srigl_condensed_linear_fwd_idx16 if narrow else lib.srigl_condensed_linear_fwd_act
-        st = fn(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
-                _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
-                int(act or ACT_NONE), int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
-        _check(st, "srigl_condensed_linear_fwd_idx16" if narrow else "srigl_condensed_linear_fwd_act")
-        return
-    if algo is None and tuning is None:
-        st = lib.srigl_condensed_linear_fwd(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
-                                            _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
-                                            _stream())
+    activation in the epilogue (ACT_* codes); idx in a 16-bit container: the narrow-index entry point (no streaming copy);
+    packed: the streaming copy of W_c / idx."""
+    tn = _tuning(tuning)
+    tn_ref = ctypes.byref(tn) if tn is not None else None
+    head = (_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx), _ptr(active), int(n_active), int(K),
+            _ptr(bias), int(d_out), _ptr(y), _ptr(seg))
+    if idx.dtype != torch.int32:       # a 16-bit container carries unsigned 16-bit column indices
+        assert packed is None
+        _check(lib.srigl_condensed_linear_fwd_idx16(*head, int(act or ACT_NONE), int(algo or FWD_AUTO), tn_ref, _stream()),
+               "srigl_condensed_linear_fwd_idx16")
+    elif act is not None:
+        _check(lib.srigl_condensed_linear_fwd_act(*head, _ptr(packed), int(act), int(algo or FWD_AUTO), tn_ref, _stream()),
+               "srigl_condensed_linear_fwd_act")
+    elif algo is None and tuning is None:
+        _check(lib.srigl_condensed_linear_fwd(*head, _ptr(packed), _stream()), "srigl_condensed_linear_fwd")
     else:
-        tn = None
-        if tuning is not None:
-            tn = FwdTuning()
-            for k, v in tuning.items():
-                setattr(tn, k, int(v))
-        st = lib.srigl_condensed_linear_fwd_algo(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(W_c), _dtype_code(W_c), _ptr(idx),
-                                                 _ptr(active), int(n_active), int(K), _ptr(bias), int(d_out), _ptr(y), _ptr(seg),
-                                                 int(algo or FWD_AUTO), ctypes.byref(tn) if tn is not None else None, _stream())
-    _check(st, "srigl_condensed_linear_fwd")
+        _check(lib.srigl_condensed_linear_fwd_algo(*head, _ptr(packed), int(algo or FWD_AUTO), tn_ref, _stream()),
+               "srigl_condensed_linear_fwd_algo")
 
 
 def srigl_narrow_idx(idx, d_in, idx16):
@@ -304,6 +306,14 @@ def srigl_fold_ablated_inputs(idx2, W_c2, bias2, active2, n2, K2, d_out2, active
 def srigl_compact_hidden_layer(bias1, active1, n_active1, d_hidden, width, bias_compact, active_compact):
     _check(lib.srigl_compact_hidden_layer(_ptr(bias1), _ptr(active1), int(n_active1), int(d_hidden), int(width), _ptr(bias_compact),
                                           _ptr(active_compact), _stream()), "srigl_compact_hidden_layer")
+
+
+def srigl_condensed_mlp_fwd(x, B, d_in, packed1, active1, n_active1, K1, bias1, d_hidden, act, hidden, packed2, active2, n_active2, K2,
+                            bias2, d_out, y, spin_limit=0, status=None):
+    _check(lib.srigl_condensed_mlp_fwd(_ptr(x), int(B), int(d_in), _ptr(packed1), _ptr(active1), int(n_active1), int(K1), _ptr(bias1),
+                                       int(d_hidden), int(act), _ptr(hidden), _ptr(packed2), _ptr(active2), int(n_active2), int(K2),
+                                       _ptr(bias2), int(d_out), _ptr(y), int(spin_limit), _ptr(status), _stream()),
+           "srigl_condensed_mlp_fwd")
 
 
 def srigl_mask_update_workspace_bytes(d_out: int, d_in: int) -> int:

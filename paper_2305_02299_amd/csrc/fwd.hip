@@ -180,6 +180,121 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
 }
 
 // ------------------------------------------------------------------------------------------------
+// KLANE on the streaming copy of the condensed arrays (PackedLayout).  Same lane mapping and reduction as k_fwd_klane,
+// but the four terms a lane has in flight are one unit of the copy: lane q of a row's group takes the units q, q + L, ...
+// and gets its four weights and four indices with two 16-byte loads out of one 32-byte piece (one load when the unit is
+// 16 bytes: bf16 weights beside 16-bit indices) instead of eight 4- or 2-byte loads from two arrays.  The first unit of a
+// lane's next stored row is requested before the current row's partial sums are combined; in the staged form the first
+// row's unit is requested together with the rows of x, ahead of the barrier, so that both fetches are in flight at once.
+// ------------------------------------------------------------------------------------------------
+template <int RB, bool GATHER, typename XT, int UB>
+__global__ __launch_bounds__(256) void k_fwd_klane_packed(const XT* __restrict__ x, int B, int d_in, const unsigned char* __restrict__ packed,
+                                                          int units, const int32_t* __restrict__ active, int n_active, int K,
+                                                          const float* __restrict__ bias, int d_out, float* __restrict__ y, int log2L,
+                                                          int rows_per_wg, int act) {
+    extern __shared__ float xs[];   // [RB][d_in]; unused when GATHER
+    const int L = 1 << log2L;
+    const int tid = threadIdx.x;
+    const int q = tid & (L - 1);
+    const int grp = tid >> log2L;
+    const int groups = blockDim.x >> log2L;
+    const int b0 = blockIdx.y * RB;
+    const int n_slots = active ? n_active + 1 : n_active;
+    const int s_begin = blockIdx.x * rows_per_wg;
+    const int s_end = min(s_begin + rows_per_wg, n_slots);
+    const size_t row_bytes = (size_t)units * UB;
+
+    const XT* xrow[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) xrow[r] = x + (size_t)min(b0 + r, B - 1) * d_in;
+
+    // unit u of stored row s; rows and units past the end re-read the last ones (their terms are never used)
+    auto unit_at = [&](int s, int u) {
+        return packed + (size_t)min(s, n_active - 1) * row_bytes + (size_t)min(u, units - 1) * UB;
+    };
+    PackedUnit<XT, UB> first;
+    if (!GATHER) {
+        XT v[RB][4];
+        const int j0 = tid;   // this thread's first column; the loop below strides by 4 * blockDim.x
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[r][u] = xrow[r][min(j0 + u * (int)blockDim.x, d_in - 1)];
+        first.load(unit_at(s_begin + grp, q));
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j0 + u * (int)blockDim.x < d_in) xs[r * d_in + j0 + u * (int)blockDim.x] = to_f32<XT>(v[r][u]);
+        for (int r = 0; r < RB; ++r)
+            for (int j = tid + 4 * (int)blockDim.x; j < d_in; j += (int)blockDim.x) xs[r * d_in + j] = to_f32<XT>(xrow[r][j]);
+        __syncthreads();
+    } else {
+        first.load(unit_at(s_begin + grp, q));
+    }
+
+    for (int s = s_begin + grp; s < s_end; s += groups) {
+        float acc[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) acc[r] = 0.0f;
+        if (s < n_active) {
+            for (int u = q; u < units; u += L) {
+                PackedUnit<XT, UB> un;
+                if (u == q) un = first; else un.load(unit_at(s, u));
+                int c[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) c[t] = GATHER ? min(max(un.col(t), 0), d_in - 1) : un.col(t);
+                if (GATHER) {
+                    XT xg[4][RB];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int r = 0; r < RB; ++r) xg[t][r] = xrow[r][c[t]];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (4 * u + t < K) {
+                            const float wv = un.weight(t);
+#pragma unroll
+                            for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, to_f32<XT>(xg[t][r]), acc[r]);
+                        }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (4 * u + t < K) {
+                            const float wv = un.weight(t);
+#pragma unroll
+                            for (int r = 0; r < RB; ++r) acc[r] = fmaf(wv, xs[r * d_in + c[t]], acc[r]);
+                        }
+                }
+            }
+        }
+        if (s + groups < s_end) first.load(unit_at(s + groups, q));
+        for (int off = L >> 1; off > 0; off >>= 1) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] += __shfl_xor(acc[r], off, kWave);
+        }
+        int col = s, prev = s - 1;
+        if (active) {
+            col = min((s < n_active) ? active[s] : d_out, d_out);
+            prev = (s > 0) ? active[s - 1] : -1;
+            for (int c = max(prev + 1, 0) + q; c < col; c += L) {
+                const float braw = bias_at(bias, c);
+                const float bv = act == SRIGL_ACT_NONE ? braw : apply_act(braw, act);
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+                    if (b0 + r < B) y[(size_t)(b0 + r) * d_out + c] = bv;
+            }
+        }
+        if (q == 0 && s < n_active && col >= 0 && col < d_out) {
+            const float bv = bias_at(bias, col);
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+                if (b0 + r < B) y[(size_t)(b0 + r) * d_out + col] = act == SRIGL_ACT_NONE ? acc[r] + bv : apply_act(acc[r] + bv, act);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // 16-bit copy of the index array (App. E: one index per kept weight).  Eight entries per thread when both arrays
 // are 16-byte aligned (two 16-byte loads, one 16-byte store), the tail and unaligned arrays one entry per thread.
 // ------------------------------------------------------------------------------------------------
@@ -239,6 +354,22 @@ static srigl_status launch_klane_t(const FwdArgs& a, int log2L, int rows_per_wg,
     return hip_ok(hipGetLastError());
 }
 
+template <int RB, bool GATHER, typename XT, int UB>
+static srigl_status launch_klane_packed_t(const FwdArgs& a, int log2L, int rows_per_wg, hipStream_t st) {
+    const int n_slots = a.active ? a.n_active + 1 : a.n_active;
+    const size_t lds = GATHER ? 0 : (size_t)RB * a.d_in * sizeof(float);
+    if (lds > kLdsMax) return SRIGL_ERR_UNSUPPORTED;
+    auto kern = k_fwd_klane_packed<RB, GATHER, XT, UB>;
+    static LdsLimit lds_limit;
+    if (lds_limit.ensure(kern, lds) != SRIGL_OK) return SRIGL_ERR_HIP;
+    const unsigned gx = (unsigned)((n_slots + rows_per_wg - 1) / rows_per_wg);
+    const unsigned gy = (unsigned)((a.B + RB - 1) / RB);
+    if (gy > 65535u) return SRIGL_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const XT*)a.x, a.B, a.d_in, static_cast<const unsigned char*>(a.packed),
+                       (a.K + 3) / 4, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, log2L, rows_per_wg, a.act);
+    return hip_ok(hipGetLastError());
+}
+
 // Launch shape of the small-batch kernel, decided on the host.
 struct KlanePlan { int L, RB, rows_per_wg, direct; long long workgroups; bool ok; };
 static KlanePlan plan_klane(const FwdArgs& a, const srigl_fwd_tuning* t) {
@@ -281,6 +412,24 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     if (!kp.ok) return SRIGL_ERR_UNSUPPORTED;
     const int RB = kp.RB, rows_per_wg = kp.rows_per_wg, direct = kp.direct;
     const int log2L = ilog2_floor(kp.L);
+    if (a.packed && !a.idx_u16) {   // the streaming copy: same launch shape, a lane's four terms in one unit
+        const bool narrow = a.x_bf16 && a.d_in <= 65536;
+#define SRIGL_KLANE_P(RBV, G)                                                                                        \
+    return !a.x_bf16 ? launch_klane_packed_t<RBV, G, float, 32>(a, log2L, rows_per_wg, st)                            \
+                     : (narrow ? launch_klane_packed_t<RBV, G, uint16_t, 16>(a, log2L, rows_per_wg, st)              \
+                               : launch_klane_packed_t<RBV, G, uint16_t, 32>(a, log2L, rows_per_wg, st))
+#define SRIGL_KLANE_PG(RBV)                \
+    if (direct) { SRIGL_KLANE_P(RBV, true); } \
+    SRIGL_KLANE_P(RBV, false)
+        switch (RB) {
+            case 1: SRIGL_KLANE_PG(1);
+            case 2: SRIGL_KLANE_PG(2);
+            case 4: SRIGL_KLANE_PG(4);
+            default: SRIGL_KLANE_PG(8);
+        }
+#undef SRIGL_KLANE_P
+#undef SRIGL_KLANE_PG
+    }
 #define SRIGL_KLANE_G(RBV, G)                                                                           \
     return a.x_bf16 ? (a.idx_u16 ? launch_klane_t<RBV, G, uint16_t, uint16_t>(a, log2L, rows_per_wg, st)  \
                                  : launch_klane_t<RBV, G, uint16_t, int32_t>(a, log2L, rows_per_wg, st))  \
@@ -314,7 +463,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
     p.R = t && t->rows_per_lane ? t->rows_per_lane : 1;
     p.H = t && t->term_slices ? t->term_slices : 0;
-    if (p.R != 1 && p.R != 2) return p;
+    if (p.R != 1 && p.R != 2 && p.R != 4) return p;
     // fast staging: whole 16-column units, rows aligned for 4-element vector loads
     const size_t xal = (a.x_bf16 ? 2 : 4) * 4;
     p.fast = (a.d_in % 16 == 0) && ((reinterpret_cast<uintptr_t>(a.x) % xal) == 0);
@@ -336,8 +485,9 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     }
     if (p.H != 1 && p.H != 2 && p.H != 4) return p;
     if (p.R == 2 && p.H != 1 && p.H != 2 && p.H != 4) return p;
+    if (p.R == 4 && p.H != 2 && p.H != 4) return p;   // four rows per lane: 128- or 64-row tiles (whole 64-row groups per term slice)
     if (!p.fast && (p.R != 1 || p.H != 1)) return p;
-    const int BT = kWave * p.R / p.H, S = rowlane_row_stride(BT, p.H);
+    const int BT = kWave * p.R / p.H, S = rowlane_row_stride(BT, p.H, p.R);
     p.n_btiles = (a.B + BT - 1) / BT;
     const int nw_max = rowlane_max_threads(p.R) / kWave;
     p.NW = t && t->waves ? t->waves : nw_max;
@@ -370,9 +520,9 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     // terms held in registers) a tenth more; with term slices the fixed part is about two stored rows' worth.  Fits of
     // the measured ranking of eight launch shapes each at batches 320..768 of three layers.
     // (two rows per lane in two term slices: the 64-row tile of the whole-row shape, a term at three quarters of its cost)
-    const bool r2h2 = p.R == 2 && p.H >= 2;
-    const double fixed = r2h2 ? 0.15 * a.d_in : (p.H == 1 ? 0.15 * a.d_in * p.R : 2.0 * a.K);
-    const double per_row = (double)a.K * (r2h2 ? 0.75 : (p.H == 1 && p.R == 2 ? 1.3 : 1.0));
+    const bool r2h2 = (p.R == 2 && p.H >= 2) || p.R == 4;
+    const double fixed = p.R == 4 ? 0.15 * a.d_in * (kWave * p.R / p.H) / 64.0 : (r2h2 ? 0.15 * a.d_in : (p.H == 1 ? 0.15 * a.d_in * p.R : 2.0 * a.K));
+    const double per_row = (double)a.K * (p.R == 4 ? 0.5 * (kWave * p.R / p.H) / 64.0 : (r2h2 ? 0.75 : (p.H == 1 && p.R == 2 ? 1.3 : 1.0)));
     // which workgroups share an XCD: the order that makes the 8 L2s fetch fewer bytes in all (all of x by each XCD, or
     // all of W_c / idx by each), unless it needs more rounds per XCD; the tuning can force either
     const int xo = t ? t->xcd_order : 0;
@@ -512,6 +662,7 @@ static FwdArgs standin_args(int B, int d_in, int n_active, int K, int d_out, boo
     a.n_active = n_active; a.K = K; a.bias = nullptr; a.d_out = d_out; a.y = nullptr;
     a.seg = has_seg ? reinterpret_cast<const uint16_t*>(aligned) : nullptr;
     a.seg_stride = srigl_seg_stride(d_in);
+    a.packed = nullptr;
     a.act = SRIGL_ACT_NONE;
     return a;
 }
@@ -534,8 +685,8 @@ extern "C" {
 
 static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* W_c, srigl_dtype w_dtype,
                              const void* idx, bool idx_u16, const int32_t* active, int32_t n_active, int32_t K, const float* bias,
-                             int32_t d_out, float* y, const uint16_t* seg, srigl_fwd_algo algo, const srigl_fwd_tuning* tuning,
-                             srigl_activation act, void* stream) {
+                             int32_t d_out, float* y, const uint16_t* seg, const void* packed, srigl_fwd_algo algo,
+                             const srigl_fwd_tuning* tuning, srigl_activation act, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (act != SRIGL_ACT_NONE && act != SRIGL_ACT_RELU && act != SRIGL_ACT_GELU) return SRIGL_ERR_INVALID_ARG;
     if (B < 0 || d_in < 0 || n_active < 0 || K < 0 || d_out < 0 || K > d_in || n_active > d_out) return SRIGL_ERR_INVALID_ARG;
@@ -543,6 +694,7 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     if (x_dtype != w_dtype) return SRIGL_ERR_UNSUPPORTED;
     if (idx_u16 && d_in > 65536) return SRIGL_ERR_UNSUPPORTED;
     if (seg != nullptr && K > 65535) return SRIGL_ERR_UNSUPPORTED;   // seg entries are 16-bit term counts
+    if (packed != nullptr && reinterpret_cast<uintptr_t>(packed) % 16 != 0) return SRIGL_ERR_INVALID_ARG;
     if (active == nullptr && n_active != d_out && n_active != 0) return SRIGL_ERR_INVALID_ARG;
     if (B == 0 || d_out == 0) return SRIGL_OK;
     if (y == nullptr) return SRIGL_ERR_INVALID_ARG;
@@ -552,6 +704,7 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
     a.x = x; a.x_bf16 = (x_dtype == SRIGL_BF16); a.B = B; a.d_in = d_in; a.W_c = W_c; a.idx = idx; a.idx_u16 = idx_u16 ? 1 : 0; a.active = active;
     a.n_active = n_active; a.K = K; a.bias = bias; a.d_out = d_out; a.y = y; a.seg = seg;
     a.seg_stride = srigl_seg_stride(d_in);
+    a.packed = packed;
     a.act = (int32_t)act;
     if (n_active == 0 || K == 0) {   // nothing is stored: every column holds its bias
         long long blocks = ((long long)B * d_out + 255) / 256;
@@ -577,27 +730,27 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
                                              const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
                                              const int32_t* active, int32_t n_active, int32_t K,
                                              const float* bias, int32_t d_out, float* y,
-                                             const uint16_t* seg, srigl_fwd_algo algo,
+                                             const uint16_t* seg, const void* packed, srigl_fwd_algo algo,
                                              const srigl_fwd_tuning* tuning, void* stream) {
-    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, false, active, n_active, K, bias, d_out, y, seg, algo, tuning, SRIGL_ACT_NONE, stream);
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, false, active, n_active, K, bias, d_out, y, seg, packed, algo, tuning, SRIGL_ACT_NONE, stream);
 }
 
 srigl_status srigl_condensed_linear_fwd_act(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
                                             const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
                                             const int32_t* active, int32_t n_active, int32_t K,
                                             const float* bias, int32_t d_out, float* y,
-                                            const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
+                                            const uint16_t* seg, const void* packed, srigl_activation act, srigl_fwd_algo algo,
                                             const srigl_fwd_tuning* tuning, void* stream) {
-    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, false, active, n_active, K, bias, d_out, y, seg, algo, tuning, act, stream);
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, false, active, n_active, K, bias, d_out, y, seg, packed, algo, tuning, act, stream);
 }
 
 srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
                                         const void* W_c, srigl_dtype w_dtype, const int32_t* idx,
                                         const int32_t* active, int32_t n_active, int32_t K,
                                         const float* bias, int32_t d_out, float* y,
-                                        const uint16_t* seg, void* stream) {
-    return srigl_condensed_linear_fwd_algo(x, x_dtype, B, d_in, W_c, w_dtype, idx, active, n_active, K, bias, d_out, y, seg,
-                                           SRIGL_FWD_AUTO, nullptr, stream);
+                                        const uint16_t* seg, const void* packed, void* stream) {
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx, false, active, n_active, K, bias, d_out, y, seg, packed, SRIGL_FWD_AUTO, nullptr,
+                    SRIGL_ACT_NONE, stream);
 }
 
 srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in,
@@ -606,7 +759,7 @@ srigl_status srigl_condensed_linear_fwd_idx16(const void* x, srigl_dtype x_dtype
                                               const float* bias, int32_t d_out, float* y,
                                               const uint16_t* seg, srigl_activation act, srigl_fwd_algo algo,
                                               const srigl_fwd_tuning* tuning, void* stream) {
-    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx16, true, active, n_active, K, bias, d_out, y, seg, algo, tuning, act, stream);
+    return fwd_core(x, x_dtype, B, d_in, W_c, w_dtype, idx16, true, active, n_active, K, bias, d_out, y, seg, nullptr, algo, tuning, act, stream);
 }
 
 srigl_status srigl_narrow_idx(const int32_t* idx, int64_t n, int32_t d_in, uint16_t* idx16, void* stream) {

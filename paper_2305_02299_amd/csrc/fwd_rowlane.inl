@@ -97,6 +97,17 @@ __device__ __forceinline__ int row_bcast(int v) {
     return __builtin_amdgcn_update_dpp(0, v, 0x150 + N, 0xf, 0xf, true);
 }
 
+// (lane n of each 16-lane row) ^ v in one instruction: the LDS address of a term in the swizzled tile
+template <int N>
+__device__ __forceinline__ int xor_row_bcast(int bcast_src, int v) {
+    int r;   // (the s_nop covers the two wait states a DPP read needs after a VALU write of its source, as in fmac_row_bcast)
+    if constexpr (N % 4 == 0)
+        asm("s_nop 1\n\tv_xor_b32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(bcast_src), "v"(v), "n"(N));
+    else
+        asm("v_xor_b32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(bcast_src), "v"(v), "n"(N));
+    return r;
+}
+
 // acc += w[lane n of this row] * x.  The s_nop at the head of every run of 4 covers the two wait states a DPP
 // read needs after a VALU write of `w`; the terms of a group run in order (they chain through acc).
 template <int N>
@@ -127,13 +138,16 @@ __device__ __forceinline__ void fmac_rows(float (&acc)[R], float wv, const typen
 template <int R> struct GroupSize { static constexpr int value = (R >= 2) ? 4 : 8; };
 
 // Group Q of a block (terms Q*GS .. Q*GS+GS-1): its LDS reads, and its multiply-adds
+// (swizzled tile, R = 4: xb is the tile's base and lanepart the byte offset of the lane's rows, combined by exclusive or)
 template <int R, int Q, int J = 0>
-__device__ __forceinline__ void group_reads(typename RowVec<R>::type (&xv)[GroupSize<R>::value], int ov, const char* __restrict__ xb) {
+__device__ __forceinline__ void group_reads(typename RowVec<R>::type (&xv)[GroupSize<R>::value], int ov, const char* __restrict__ xb,
+                                            int lanepart) {
     using V = typename RowVec<R>::type;
     constexpr int GS = GroupSize<R>::value;
     if constexpr (J < GS) {
-        xv[J] = *reinterpret_cast<const V*>(xb + row_bcast<Q * GS + J>(ov));
-        group_reads<R, Q, J + 1>(xv, ov, xb);
+        if constexpr (rowlane_swizzled(R)) xv[J] = *reinterpret_cast<const V*>(xb + xor_row_bcast<Q * GS + J>(ov, lanepart));
+        else xv[J] = *reinterpret_cast<const V*>(xb + row_bcast<Q * GS + J>(ov));
+        group_reads<R, Q, J + 1>(xv, ov, xb, lanepart);
     }
 }
 template <int R, int Q, int J = 0>
@@ -150,15 +164,15 @@ __device__ __forceinline__ void group_fmacs(float (&acc)[R], float wv, const typ
 // before the multiply-adds of this one.
 template <int R, int G, int NB>
 __device__ __forceinline__ void pipe_groups(float (&acc)[R], const float (&wv)[NB], const int (&ov)[NB], const char* __restrict__ xb,
-                                            int n, typename RowVec<R>::type (&cur)[GroupSize<R>::value],
+                                            int lanepart, int n, typename RowVec<R>::type (&cur)[GroupSize<R>::value],
                                             typename RowVec<R>::type (&nxt)[GroupSize<R>::value]) {
     constexpr int GS = GroupSize<R>::value;
     constexpr int GPB = kBlock / GS;   // groups per block
     if constexpr (G + 1 < GPB * NB) {
         if (n > GS * (G + 1)) {
-            group_reads<R, (G + 1) % GPB>(nxt, ov[(G + 1) / GPB], xb);
+            group_reads<R, (G + 1) % GPB>(nxt, ov[(G + 1) / GPB], xb, lanepart);
             group_fmacs<R, G % GPB>(acc, wv[G / GPB], cur);
-            pipe_groups<R, G + 1, NB>(acc, wv, ov, xb, n, nxt, cur);
+            pipe_groups<R, G + 1, NB>(acc, wv, ov, xb, lanepart, n, nxt, cur);
             return;
         }
     }
@@ -183,7 +197,9 @@ __device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const 
     i_raw = (int)*reinterpret_cast<const IT*>(reinterpret_cast<const char*>(idx) + t * (unsigned)sizeof(IT));
 }
 // n_valid (wave-uniform, may be <= 0) of the block's terms are real; the others become (weight 0, all-zero column).
-template <typename XT, int H>
+// SWZ: the offset also carries the column's swizzle bits (bits 6-7: which 64-byte quarter of the column's first 256 bytes the
+// rows 0-15 moved to); off_mul is then a multiple of 256 and off_add moves whole 64-column chunks, which leave those bits alone.
+template <typename XT, int H, bool SWZ = false>
 __device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, int tofs, int off_mul, int off_add, int zero_off,
                                              float& wv, int& ov, int fetch_ofs = 0) {
     if (H > 1) {   // fetch_ofs: first lane of the block when one load brought two blocks (lanes 0-31 and 32-63)
@@ -193,6 +209,7 @@ __device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, i
     const bool real = tofs < n_valid;
     wv = real ? rl_to_f32<XT>(w_raw) : 0.0f;
     ov = real ? i_raw * off_mul + off_add : zero_off;
+    if (SWZ) ov = real ? ov | (((i_raw >> 2) & 3) << 6) : ov;
 }
 
 template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT>
@@ -204,8 +221,9 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
-    constexpr int S = rowlane_row_stride(BT, H);
+    constexpr int S = rowlane_row_stride(BT, H, R);
     constexpr int S4 = S * 4;
+    constexpr bool SWZ = rowlane_swizzled(R);
     constexpr int TB = kBlock * H;           // terms per block (16 steps of H terms)
     // Two slices with two preloaded blocks: one 64-lane load brings both blocks (64 consecutive terms, lane l holds term
     // l) instead of two loads of 32 terms twice over; every vector-memory instruction costs the address unit the same
@@ -276,7 +294,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         const int f = ct * 16 + dq * 4;
         // rows past B re-read row B - 1: their lanes compute values that are never stored
         g_off[i] = (unsigned)(min(b0 + rl, B - 1) * d_in + f);   // the host guarantees B * d_in < 2^31
-        l_off[i] = f * S + rl;
+        l_off[i] = f * S + (SWZ ? (rl ^ (((f >> 2) & 3) << 4)) : rl);   // (f .. f + 3 share one swizzle: f is a multiple of 4)
         u_col[i] = (u < units) ? ct * 16 : 0x40000000;   // units past the tile never pass the column tests below
     }
     Staged4<XT> st[kStageUnits];
@@ -343,7 +361,8 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     SRIGL_STAGE_STORE()
     __syncthreads();
 
-    const char* xb = reinterpret_cast<const char*>(lds) + rowl * (R * 4);
+    const int lanepart = rowl * (R * 4);
+    const char* xb = reinterpret_cast<const char*>(lds) + (SWZ ? 0 : lanepart);
     for (int c = 0; c < n_chunks; ++c) {
         const bool more = (c + 1 < n_chunks);
         int k0n[NPW], nn[NPW];
@@ -365,10 +384,10 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 int po[KPRE];
 #pragma unroll
                 for (int p = 0; p < KPRE; ++p)
-                    finish_terms<XT, H>(rw[i][MERGE ? 0 : p], ri[i][MERGE ? 0 : p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p],
-                                        MERGE ? p * TB : 0);
-                group_reads<R, 0>(xa, po[0], xb);
-                pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, (n_terms + H - 1) / H, xa, xc);
+                    finish_terms<XT, H, SWZ>(rw[i][MERGE ? 0 : p], ri[i][MERGE ? 0 : p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p],
+                                             MERGE ? p * TB : 0);
+                group_reads<R, 0>(xa, po[0], xb, lanepart);
+                pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, lanepart, (n_terms + H - 1) / H, xa, xc);
                 // long ranges: the remaining blocks, one at a time, each requested one block ahead
                 if (n_terms > KPRE * TB) {
                     const int row = (s0 + i) * K + k0n[i];
@@ -378,10 +397,10 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                     for (int kb = KPRE * TB; kb < n_terms; kb += TB) {
                         float wc[1];
                         int oc[1];
-                        finish_terms<XT, H>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
+                        finish_terms<XT, H, SWZ>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
                         if (kb + TB < n_terms) request_terms<XT, IT>(W_c, idx, row + kb + TB, lofs, t_last, wr, ir);
-                        group_reads<R, 0>(xa, oc[0], xb);
-                        pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, (n_terms - kb + H - 1) / H, xa, xc);
+                        group_reads<R, 0>(xa, oc[0], xb, lanepart);
+                        pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, lanepart, (n_terms - kb + H - 1) / H, xa, xc);
                     }
                 }
             }
@@ -530,7 +549,7 @@ static srigl_status launch_rowlane_r(const FwdArgs& a, const RowlanePlan& p, hip
         case 1: return launch_rowlane_k<R, H, 1, XT, IT>(a, p, st);
         case 2: return launch_rowlane_k<R, H, 2, XT, IT>(a, p, st);
         case 3: return launch_rowlane_k<R, H, 3, XT, IT>(a, p, st);
-        case 4: return launch_rowlane_k<R, H, 4, XT, IT>(a, p, st);
+        case 4: if constexpr (MAXN >= 4) return launch_rowlane_k<R, H, 4, XT, IT>(a, p, st); else break;
         case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, H, 6, XT, IT>(a, p, st); else break;
         default: break;
     }
@@ -546,6 +565,8 @@ static srigl_status launch_rowlane_x(const FwdArgs& a, const RowlanePlan& p, hip
         case 21: return launch_rowlane_r<2, 1, XT, IT>(a, p, st);
         case 22: return launch_rowlane_r<2, 2, XT, IT>(a, p, st);
         case 24: return launch_rowlane_r<2, 4, XT, IT>(a, p, st);
+        case 42: return launch_rowlane_r<4, 2, XT, IT>(a, p, st);
+        case 44: return launch_rowlane_r<4, 4, XT, IT>(a, p, st);
         default: return SRIGL_ERR_UNSUPPORTED;
     }
 }

@@ -24,6 +24,7 @@ class CondensedLinear:
     seg: torch.Tensor | None
     Wd: torch.Tensor | None = None   # dense rows of the stored neurons (structured-only form), built on first use
     idx_wide: torch.Tensor | None = None   # the int32 indices when idx holds the 16-bit copy
+    packed: torch.Tensor | None = None     # the streaming copy of W_c / idx (bytes), read by the kernels that can stream it
 
     def narrow(self) -> "CondensedLinear":
         """The same layer with 16-bit column indices (d_in <= 65536); weights, active, bias and seg are shared."""
@@ -57,12 +58,13 @@ class CondensedLinear:
             return y
         assert representation == "condensed"
         B_.srigl_condensed_linear_fwd(x, Bn, self.d_in, self.W_c, self.idx, self.active, self.n_active, self.K, self.bias,
-                                      self.d_out, y, self.seg, algo=algo, tuning=tuning)
+                                      self.d_out, y, self.seg, algo=algo, tuning=tuning,
+                                      packed=self.packed if self.idx.dtype == torch.int32 else None)
         return y
 
 
 def condense_layer(W: torch.Tensor, mask: torch.Tensor, K: int, bias: torch.Tensor | None = None,
-                   want_seg: bool = True) -> CondensedLinear:
+                   want_seg: bool = True, want_packed: bool = True) -> CondensedLinear:
     """srigl_condense on device tensors; reads the report back (one synchronisation) to size the result."""
     d_out, d_in = mask.shape
     dev = W.device
@@ -73,14 +75,17 @@ def condense_layer(W: torch.Tensor, mask: torch.Tensor, K: int, bias: torch.Tens
     seg = torch.empty((d_out, ss), dtype=torch.int16, device=dev) if want_seg else None
     ws = B_.new_workspace(d_out, dev)
     rep = B_.new_report(dev)
-    B_.srigl_condense(W, mask, d_out, d_in, K, d_out, W_c, idx, active, seg, ws, rep)
+    code = B_._dtype_code(W)
+    packed = torch.empty((max(B_.srigl_packed_bytes(d_out, K, d_in, code), 16),), dtype=torch.uint8, device=dev) if want_packed else None
+    B_.srigl_condense(W, mask, d_out, d_in, K, d_out, W_c, idx, active, seg, ws, rep, packed=packed)
     r = B_.read_report(rep)
     if r["status"] != B_.OK:
         raise B_.SriglError(r["status"], "srigl_condense (first bad row %d)" % r["first_bad_row"])
     n = r["n_active"]
     return CondensedLinear(d_in, d_out, K, n, W_c[:n].contiguous(), idx[:n].contiguous(),
                            None if n == d_out else active[:n].contiguous(), bias,
-                           seg[:n].contiguous() if want_seg else None)
+                           seg[:n].contiguous() if want_seg else None,
+                           packed=packed[:B_.srigl_packed_bytes(n, K, d_in, code)] if want_packed and n and K else None)
 
 
 @dataclass
@@ -93,15 +98,22 @@ class CondensedMLP:
     second: CondensedLinear         # d_in == first.d_out
     act: int
 
-    def forward(self, x: torch.Tensor, y: torch.Tensor | None = None, hidden: torch.Tensor | None = None) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, y: torch.Tensor | None = None, hidden: torch.Tensor | None = None,
+                fused: bool | None = None) -> torch.Tensor:
         Bn = x.shape[0]
         f, s = self.first, self.second
         if hidden is None:
             hidden = torch.empty((Bn, f.d_out), dtype=torch.float32, device=x.device)
         if y is None:
             y = torch.empty((Bn, s.d_out), dtype=torch.float32, device=x.device)
-        B_.srigl_condensed_linear_fwd(x, Bn, f.d_in, f.W_c, f.idx, f.active, f.n_active, f.K, f.bias, f.d_out, hidden, f.seg, act=self.act)
-        B_.srigl_condensed_linear_fwd(hidden, Bn, s.d_in, s.W_c, s.idx, s.active, s.n_active, s.K, s.bias, s.d_out, y, s.seg)
+        if fused:      # both layers in one launch (batches up to 8; measured slower than two launches on MI355X: not the default)
+            B_.srigl_condensed_mlp_fwd(x, Bn, f.d_in, f.packed, f.active, f.n_active, f.K, f.bias, f.d_out, self.act, hidden, s.packed,
+                                       s.active, s.n_active, s.K, s.bias, s.d_out, y)
+            return y
+        B_.srigl_condensed_linear_fwd(x, Bn, f.d_in, f.W_c, f.idx, f.active, f.n_active, f.K, f.bias, f.d_out, hidden, f.seg, act=self.act,
+                                      packed=f.packed)
+        B_.srigl_condensed_linear_fwd(hidden, Bn, s.d_in, s.W_c, s.idx, s.active, s.n_active, s.K, s.bias, s.d_out, y, s.seg,
+                                      packed=s.packed)
         return y
 
 
@@ -117,7 +129,8 @@ def fold_mlp(layer1: CondensedLinear, layer2: CondensedLinear, act: int) -> Cond
     bias1_compact = torch.empty((n1p,), dtype=torch.float32, device=dev)
     active_first = None if n1p == n1 else torch.empty((n1,), dtype=torch.int32, device=dev)
     B_.srigl_compact_hidden_layer(layer1.bias, layer1.active, n1, layer1.d_out, n1p, bias1_compact, active_first)
-    first = CondensedLinear(layer1.d_in, n1p, layer1.K, n1, layer1.W_c, layer1.idx, active_first, bias1_compact, layer1.seg)
+    first = CondensedLinear(layer1.d_in, n1p, layer1.K, n1, layer1.W_c, layer1.idx, active_first, bias1_compact, layer1.seg,
+                            packed=layer1.packed)
     idx_f = torch.empty_like(layer2.idx)
     W_f = torch.empty_like(layer2.W_c)
     bias_f = torch.empty((layer2.d_out,), dtype=torch.float32, device=dev)
@@ -130,5 +143,9 @@ def fold_mlp(layer1: CondensedLinear, layer2: CondensedLinear, act: int) -> Cond
     r = B_.read_report(rep)
     if r["status"] != B_.OK:
         raise B_.SriglError(r["status"], "srigl_fold_ablated_inputs produced a bad row (%d)" % r["first_bad_row"])
-    second = CondensedLinear(n1p, layer2.d_out, layer2.K, layer2.n_active, W_f, idx_f, layer2.active, bias_f, seg)
+    packed2 = None
+    if layer2.n_active and layer2.K:
+        packed2 = torch.empty((B_.srigl_packed_bytes(layer2.n_active, layer2.K, n1p, B_.F32),), dtype=torch.uint8, device=dev)
+        B_.srigl_pack_terms(W_f, idx_f, layer2.n_active, layer2.K, n1p, packed2)
+    second = CondensedLinear(n1p, layer2.d_out, layer2.K, layer2.n_active, W_f, idx_f, layer2.active, bias_f, seg, packed=packed2)
     return CondensedMLP(first, second, act)

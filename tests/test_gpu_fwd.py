@@ -19,7 +19,7 @@ ALGOS = {"auto": None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlan
 GUARD = 1024
 
 
-def run_gpu(L, W_c, idx, active, bias, algo=None, tuning=None, seg=True, x=None):
+def run_gpu(L, W_c, idx, active, bias, algo=None, tuning=None, seg=True, x=None, packed=False):
     """Runs the library on device copies; y sits between two guard zones that must stay untouched."""
     xsrc = x if x is not None else (L.x_bf16 if L.dtype == "bf16" else L.x)
     Bn, d_in, d_out = xsrc.shape[0], L.d_in, L.d_out
@@ -27,22 +27,27 @@ def run_gpu(L, W_c, idx, active, bias, algo=None, tuning=None, seg=True, x=None)
     flat = torch.full((Bn * d_out + 2 * GUARD,), 777.0, dtype=torch.float32, device="cuda")
     y = flat[GUARD:GUARD + Bn * d_out].view(Bn, d_out)
     sg = dev(oracle_seg(idx, d_in)) if (seg and n_active and K) else None
+    pk = None
+    if packed and n_active and K:      # the streaming copy of the same rows, written by the library from the canonical arrays
+        pk = torch.empty((B_.srigl_packed_bytes(n_active, K, d_in, B_.BF16 if L.dtype == "bf16" else B_.F32),), dtype=torch.uint8,
+                         device="cuda")
+        B_.srigl_pack_terms(dev(W_c), dev(idx), n_active, K, d_in, pk)
     B_.srigl_condensed_linear_fwd(dev(xsrc), Bn, d_in, dev(W_c), dev(idx), dev(active), n_active, K, dev(bias), d_out, y,
-                                  sg, algo=algo, tuning=tuning)
+                                  sg, algo=algo, tuning=tuning, packed=pk)
     torch.cuda.synchronize()
     out = flat.cpu().numpy()
     assert (out[:GUARD] == 777.0).all() and (out[GUARD + Bn * d_out:] == 777.0).all(), "write outside y"
     return out[GUARD:GUARD + Bn * d_out].reshape(Bn, d_out).copy()
 
 
-def check_layer(L, algo, tuning=None, bias=True, seg=True, unsupported_ok=False):
+def check_layer(L, algo, tuning=None, bias=True, seg=True, unsupported_ok=False, packed=False):
     W_c, idx, active = oracle_condensed(L)
     bias_v = L.bias if bias else None
     xsrc = L.x_bf16 if L.dtype == "bf16" else L.x
     y_ref, S = oracle.fwd(xsrc, W_c, idx, active, bias_v, L.d_out, want_scale=True)
     act_arg = None if len(active) == L.d_out else active
     try:
-        y = run_gpu(L, W_c, idx, act_arg, bias_v, algo, tuning, seg)
+        y = run_gpu(L, W_c, idx, act_arg, bias_v, algo, tuning, seg, packed=packed)
     except B_.SriglError as e:
         if e.status == B_.ERR_UNSUPPORTED and algo is not None:
             if unsupported_ok:
@@ -121,6 +126,10 @@ def test_no_bias_and_no_seg(algo):
     {"rows_per_lane": 2, "term_slices": 2, "waves": 16, "neurons_per_wave": 3},
     {"rows_per_lane": 2, "term_slices": 2, "waves": 4, "neurons_per_wave": 4, "chunk_cols": 128},
     {"rows_per_lane": 2, "term_slices": 4, "waves": 16, "neurons_per_wave": 3},
+    {"rows_per_lane": 4, "term_slices": 4, "waves": 16, "neurons_per_wave": 3},
+    {"rows_per_lane": 4, "term_slices": 4, "waves": 4, "neurons_per_wave": 1, "chunk_cols": 128},
+    {"rows_per_lane": 4, "term_slices": 2, "waves": 16, "neurons_per_wave": 2},
+    {"rows_per_lane": 4, "term_slices": 2, "waves": 8, "neurons_per_wave": 3, "chunk_cols": 64},
     {"rows_per_lane": 2, "term_slices": 4, "waves": 8, "neurons_per_wave": 2, "chunk_cols": 192},
     {"term_slices": 2, "waves": 8, "neurons_per_wave": 6, "chunk_cols": 192},
     {"term_slices": 4, "waves": 8, "neurons_per_wave": 6},
@@ -148,6 +157,39 @@ def test_klane_launch_shapes(tuning):
     for (d_in, d_out, K, B, abl) in ((768, 300, 77, 9, 0.1), (3072, 96, 307, 3, 0.3), (100, 64, 5, 1, 0.0)):
         L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=78)
         check_layer(L, B_.FWD_KLANE, tuning)
+
+
+# ----------------------------------------------------------------------------- the streaming copy in place of W_c / idx
+@pytest.mark.parametrize("cfg,B", [("c1", 1), ("c2", 256), ("c3", 1), ("c3", 256)])
+@pytest.mark.parametrize("algo", ["auto", "klane"])
+def test_named_configs_through_the_streaming_copy(cfg, B, algo):
+    L = si.config(cfg, B=B) if cfg == "c3" else si.config(cfg)
+    worst = check_layer(L, ALGOS[algo], packed=True)
+    assert worst < 2e-6
+
+
+@pytest.mark.parametrize("tuning", [{"lanes_per_neuron": l, "rows_per_block": r, "direct_gather": g}
+                                    for l in (1, 4, 16, 64) for r in (1, 2, 8) for g in (1, 2)])
+def test_klane_launch_shapes_through_the_streaming_copy(tuning):
+    for (d_in, d_out, K, B, abl, dtype) in ((768, 300, 77, 9, 0.1, "f32"), (3072, 96, 307, 3, 0.3, "f32"), (100, 64, 5, 1, 0.0, "f32"),
+                                            (1300, 70, 130, 5, 0.2, "bf16"), (70000, 12, 9, 2, 0.0, "bf16"), (64, 40, 64, 11, 0.0, "f32")):
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=78)
+        check_layer(L, B_.FWD_KLANE, tuning, packed=True, unsupported_ok=(d_in > 40960 and tuning["direct_gather"] == 2))
+
+
+def test_padded_places_of_the_streaming_copy_never_meet_an_activation():
+    """A row of 77 terms fills 19 units and a quarter; the three padded places carry index 0.  A non-finite activation in
+    column 0 must reach only the rows that really name column 0."""
+    L = si.make_layer(768, 200, 77, 3, ablate_frac=0.2, seed=5)
+    L.x[1, 0] = np.inf
+    W_c, idx, active = oracle_condensed(L)
+    names_col0 = idx[:, 0] == 0
+    assert names_col0.any() and not names_col0.all()
+    for tuning in ({"direct_gather": 1}, {"direct_gather": 2}):
+        y = run_gpu(L, W_c, idx, active, L.bias, B_.FWD_KLANE, tuning, packed=True)
+        assert np.isfinite(y[1, active[~names_col0]]).all() and np.isinf(y[1, active[names_col0]]).all()
+        y_ref, S = oracle.fwd(L.x[[0, 2]], W_c, idx, active, L.bias, L.d_out, want_scale=True)
+        gate(y[[0, 2]], y_ref, S, TOL_F32)
 
 
 # ----------------------------------------------------------------------------- exact cases

@@ -137,3 +137,68 @@ def test_folded_pair_end_to_end(B_, act, B):
     y_ref, S = oracle.fwd(h, Wc2, idx2, act2, L2.bias, L2.d_out, want_scale=True)
     # the hidden vector carries the first layer's rounding (~1e-6 of its scale) into the second layer's terms
     gate(host(y), y_ref, S, 2e-5)
+
+
+@pytest.mark.parametrize("act", [0, 2])
+@pytest.mark.parametrize("B", [1, 2, 3, 8])
+@pytest.mark.parametrize("folded", [False, True])
+def test_block_in_one_launch_matches_the_oracle_pair(B_, act, B, folded):
+    """srigl_condensed_mlp_fwd (both layers and the activation in one launch, a barrier across the workgroups between them)
+    against the two-layer oracle; with the width-reduction fold and on the layers as they are; twice in a row into the same
+    buffers (the barrier's counter runs on from launch to launch)."""
+    from paper_2305_02299_amd import condense_layer, fold_mlp
+    L1 = si.make_layer(768, 3072, 77, B, ablate_frac=0.3, seed=41)
+    L2 = si.make_layer(3072, 768, 308, B, ablate_frac=0.1, seed=42)
+    l1 = condense_layer(dev(L1.W), dev(L1.mask), L1.K, dev(L1.bias))
+    l2 = condense_layer(dev(L2.W), dev(L2.mask), L2.K, dev(L2.bias))
+    Wc1, idx1, act1 = oracle.condense(L1.W, L1.mask, L1.K)
+    Wc2, idx2, act2 = oracle.condense(L2.W, L2.mask, L2.K)
+    h_ref = oracle.activate(oracle.fwd(L1.x, Wc1, idx1, act1, L1.bias, L1.d_out), act)
+    y_ref, S = oracle.fwd(h_ref, Wc2, idx2, act2, L2.bias, L2.d_out, want_scale=True)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    y = torch.full((B, L2.d_out), float("nan"), device="cuda")
+    if folded:
+        pair = fold_mlp(l1, l2, act)
+        f, s = pair.first, pair.second
+    else:
+        f, s = l1, l2
+    hidden = torch.full((B, f.d_out), float("nan"), device="cuda")
+    for _ in range(2):
+        B_.srigl_condensed_mlp_fwd(dev(L1.x), B, f.d_in, f.packed, f.active, f.n_active, f.K, f.bias, f.d_out, act, hidden, s.packed,
+                                   s.active, s.n_active, s.K, s.bias, s.d_out, y, status=status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        gate(host(y), y_ref, S, 2e-5)
+        y.fill_(float("nan"))
+    if not folded:      # the hidden vector at full width: stored neurons and act(bias) of the ablated ones
+        gate(host(hidden), h_ref, np.maximum(np.abs(h_ref), 1.0), 1e-5)
+
+
+def test_block_in_one_launch_gives_up_waiting_and_still_exits(B_):
+    """A spin limit of one poll: workgroups stop waiting at the barrier, flag the call and finish (wrong numbers, no hang);
+    the next call with the default limit is right again."""
+    from paper_2305_02299_amd import condense_layer
+    L1 = si.make_layer(256, 512, 26, 1, seed=51)
+    L2 = si.make_layer(512, 128, 52, 1, seed=52)
+    l1 = condense_layer(dev(L1.W), dev(L1.mask), L1.K, dev(L1.bias))
+    l2 = condense_layer(dev(L2.W), dev(L2.mask), L2.K, dev(L2.bias))
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hidden, y = torch.zeros((1, 512), device="cuda"), torch.zeros((1, 128), device="cuda")
+    args = (dev(L1.x), 1, 256, l1.packed, l1.active, l1.n_active, l1.K, l1.bias, 512, 1, hidden, l2.packed, l2.active, l2.n_active, l2.K,
+            l2.bias, 128, y)
+    B_.srigl_condensed_mlp_fwd(*args, spin_limit=1, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) in (0, 1)
+    status.zero_()
+    B_.srigl_condensed_mlp_fwd(*args, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    Wc1, idx1, act1 = oracle.condense(L1.W, L1.mask, L1.K)
+    Wc2, idx2, act2 = oracle.condense(L2.W, L2.mask, L2.K)
+    h = oracle.activate(oracle.fwd(L1.x, Wc1, idx1, act1, L1.bias, 512), 1)
+    y_ref, S = oracle.fwd(h, Wc2, idx2, act2, L2.bias, 128, want_scale=True)
+    gate(host(y), y_ref, S, 2e-5)
+    with pytest.raises(B_.SriglError):
+        B_.srigl_condensed_mlp_fwd(dev(np.zeros((9, 256), np.float32)), 9, 256, l1.packed, l1.active, l1.n_active, l1.K, l1.bias, 512, 1,
+                                   torch.zeros((9, 512), device="cuda"), l2.packed, l2.active, l2.n_active, l2.K, l2.bias, 128,
+                                   torch.zeros((9, 128), device="cuda"))
