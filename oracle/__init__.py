@@ -196,33 +196,22 @@ def fold_ablated_inputs(idx2, W_c2, bias2, active2, d_out2, active1, d_hidden, b
 
 
 def pack_terms(W_c: np.ndarray, idx: np.ndarray, d_in: int) -> np.ndarray:
-    """The streaming copy of App. E's two n x k arrays as bytes, [n][row_bytes]: a row is ceil(K / 4) units of four
-    consecutive terms, a unit holds its four weights and then its four column indices (fp32 weights: 16 + 16 bytes with
-    32-bit indices; bf16 weights: 8 + 8 bytes with 16-bit indices when d_in <= 65536, else 8 bytes, 8 zero bytes and
-    16 bytes of 32-bit indices); places behind the K-th term hold weight bits 0 and index 0.  Little-endian words."""
+    """The streaming copy of App. E's two n x k arrays as bytes, [n][row_bytes]: the terms of a row in order, each weight next
+    to its column index, rows padded to a multiple of four terms with weight bits 0 and index 0.  A term is 8 bytes (fp32
+    weight, 32-bit index), 4 bytes for bf16 weights when d_in <= 65536 (weight in the low half-word, 16-bit index in the high
+    one), else 8 bytes (bf16 weight, 16 zero bits, 32-bit index).  Little-endian words."""
     assert W_c.dtype in (np.float32, np.uint16) and W_c.shape == idx.shape
     n, K = idx.shape
     bf16 = W_c.dtype == np.uint16
-    narrow = bf16 and d_in <= 65536
-    unit_bytes = 16 if narrow else 32
-    units = (K + 3) // 4
-    out = np.zeros((n, units * unit_bytes), dtype=np.uint8)
+    term_bytes = 4 if (bf16 and d_in <= 65536) else 8
+    terms = (K + 3) // 4 * 4
+    out = np.zeros((n, terms * term_bytes), dtype=np.uint8)
     wbits = W_c.view(np.uint16 if bf16 else np.uint32)
     for s in range(n):
-        for u in range(units):
-            base = u * unit_bytes
-            for p in range(4):
-                t = 4 * u + p
-                w = int(wbits[s, t]) if t < K else 0
-                col = int(idx[s, t]) if t < K else 0
-                if bf16:
-                    out[s, base + 2 * p: base + 2 * p + 2] = [w & 0xFF, w >> 8]
-                else:
-                    out[s, base + 4 * p: base + 4 * p + 4] = [(w >> (8 * b)) & 0xFF for b in range(4)]
-                if narrow:
-                    out[s, base + 8 + 2 * p: base + 8 + 2 * p + 2] = [col & 0xFF, (col >> 8) & 0xFF]
-                else:
-                    out[s, base + 16 + 4 * p: base + 16 + 4 * p + 4] = [(col >> (8 * b)) & 0xFF for b in range(4)]
+        for t in range(K):
+            w, col = int(wbits[s, t]), int(idx[s, t])
+            word = (w | (col << 16)) if term_bytes == 4 else (w | (col << 32))
+            out[s, t * term_bytes:(t + 1) * term_bytes] = [(word >> (8 * b)) & 0xFF for b in range(term_bytes)]
     return out
 
 

@@ -166,8 +166,8 @@ __global__ __launch_bounds__(1024) void k_scan_rows(const int32_t* __restrict__ 
 
 // One wavefront per row: ordered stream compaction of the kept columns.
 // T = bit container of one weight (uint32_t for fp32, uint16_t for bf16).
-// With `packed` the same pass also writes the streaming copy (see PackedLayout): term `pos` of stored row s goes to unit
-// pos / 4, place pos % 4, and the places behind the K-th term of the last unit get weight bits 0 and index 0.
+// With `packed` the same pass also writes the streaming copy (see PackedLayout): term `pos` of stored row s next to its
+// index, and the places behind the K-th term up to the next multiple of four get weight bits 0 and index 0.
 template <typename T>
 __global__ __launch_bounds__(kRowsPerBlock* kWave) void k_compact_rows(const T* __restrict__ W, const uint8_t* __restrict__ mask,
                                                                      int d_out, int d_in, int K, int cap_rows,
@@ -226,15 +226,15 @@ __global__ __launch_bounds__(kRowsPerBlock* kWave) void k_compact_rows(const T* 
     if (sg)
         for (int c = chunk + lane; c < seg_stride; c += kWave) sg[c] = (uint16_t)base;
     if (pk)
-        for (int t = K + lane; t < pl.units * 4; t += kWave) pl.store(pk, t, 0u, 0);
+        for (int t = K + lane; t < pl.terms; t += kWave) pl.store(pk, t, 0u, 0);
 }
 
-// The streaming copy from the canonical arrays: one thread per place of a unit, padding included.
+// The streaming copy from the canonical arrays: one thread per term, padding included.
 __global__ __launch_bounds__(256) void k_pack_terms(const void* __restrict__ W_c, const int32_t* __restrict__ idx, int n_rows, int K,
                                                     unsigned char* __restrict__ packed, PackedLayout pl) {
-    const long long places = (long long)n_rows * pl.units * 4;
+    const long long places = (long long)n_rows * pl.terms;
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < places; i += (long long)gridDim.x * blockDim.x) {
-        const int s = (int)(i / (pl.units * 4)), t = (int)(i - (long long)s * pl.units * 4);
+        const int s = (int)(i / pl.terms), t = (int)(i - (long long)s * pl.terms);
         uint32_t wbits = 0u;
         int col = 0;
         if (t < K) {
@@ -377,7 +377,7 @@ srigl_status srigl_pack_terms(const void* W_c, srigl_dtype w_dtype, const int32_
     if (W_c == nullptr || idx == nullptr || packed == nullptr || reinterpret_cast<uintptr_t>(packed) % 16 != 0) return SRIGL_ERR_INVALID_ARG;
     if (packed_bytes < srigl_packed_bytes(n_rows, K, d_in, w_dtype)) return SRIGL_ERR_CAPACITY;
     const PackedLayout pl = packed_layout(K, d_in, w_dtype == SRIGL_BF16);
-    long long blocks = ((long long)n_rows * pl.units * 4 + 255) / 256;
+    long long blocks = ((long long)n_rows * pl.terms + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(k_pack_terms, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), W_c, idx, n_rows, K,
                        static_cast<unsigned char*>(packed), pl);

@@ -182,8 +182,8 @@ __global__ __launch_bounds__(256) void k_fwd_klane(const XT* __restrict__ x, int
 // ------------------------------------------------------------------------------------------------
 // KLANE on the streaming copy of the condensed arrays (PackedLayout).  Same lane mapping and reduction as k_fwd_klane,
 // but the four terms a lane has in flight are one unit of the copy: lane q of a row's group takes the units q, q + L, ...
-// and gets its four weights and four indices with two 16-byte loads out of one 32-byte piece (one load when the unit is
-// 16 bytes: bf16 weights beside 16-bit indices) instead of eight 4- or 2-byte loads from two arrays.  The first unit of a
+// and gets its four (weight, index) pairs with two 16-byte loads out of one 32-byte piece (one load when a term is 4 bytes:
+// bf16 weights beside 16-bit indices) instead of eight 4- or 2-byte loads from two arrays.  The first unit of a
 // lane's next stored row is requested before the current row's partial sums are combined; in the staged form the first
 // row's unit is requested together with the rows of x, ahead of the barrier, so that both fetches are in flight at once.
 // ------------------------------------------------------------------------------------------------
@@ -461,6 +461,8 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     if ((long long)a.B * a.d_in >= (1LL << 31) || ((long long)a.n_active + 256) * a.K + 4096 >= (1LL << 31) ||
         (long long)a.n_active * a.seg_stride >= (1LL << 31)) return p;
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
+    p.pk = t && t->terms_from_copy == 1 && a.packed != nullptr;
+    if (t && (t->terms_from_copy < 0 || t->terms_from_copy > 1)) return p;
     p.R = t && t->rows_per_lane ? t->rows_per_lane : 1;
     p.H = t && t->term_slices ? t->term_slices : 0;
     if (p.R != 1 && p.R != 2 && p.R != 4) return p;

@@ -188,13 +188,25 @@ __device__ __forceinline__ void pipe_groups(float (&acc)[R], const float (&wv)[N
 // finish_terms() fetches the lane's own term from lane tofs with one cross-lane read per array.  The loads are
 // unconditional (the term index is clamped into the arrays) and nothing here consumes their result, so that they stay
 // in flight; finish_terms() turns the raw words into a weight and an LDS byte offset when the block is about to be used.
-template <typename XT, typename IT>
-__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const IT* __restrict__ idx, int t0, int lofs, int t_last,
-                                              XT& w_raw, int& i_raw) {
+// PKB != 0: the terms come from the streaming copy instead (PKB bytes per term, weight and index side by side): one load per
+// block in place of two, t0 then counts terms of the copy's padded rows.
+template <typename XT, typename IT, int PKB>
+__device__ __forceinline__ void request_terms(const XT* __restrict__ W_c, const IT* __restrict__ idx, const unsigned char* __restrict__ pk,
+                                              int t0, int lofs, int t_last, XT& w_raw, int& i_raw) {
     // 32-bit unsigned byte offsets from the (wave-uniform) array bases: one address instruction per load
     const unsigned t = (unsigned)min(t0 + lofs, t_last);
-    w_raw = *reinterpret_cast<const XT*>(reinterpret_cast<const char*>(W_c) + t * (unsigned)sizeof(XT));
-    i_raw = (int)*reinterpret_cast<const IT*>(reinterpret_cast<const char*>(idx) + t * (unsigned)sizeof(IT));
+    if constexpr (PKB == 8) {
+        const uint2 v = *reinterpret_cast<const uint2*>(pk + t * 8u);
+        if constexpr (sizeof(XT) == 4) w_raw = __uint_as_float(v.x); else w_raw = (XT)v.x;
+        i_raw = (int)v.y;
+    } else if constexpr (PKB == 4) {
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(pk + t * 4u);
+        w_raw = (XT)(v & 0xffffu);
+        i_raw = (int)(v >> 16);
+    } else {
+        w_raw = *reinterpret_cast<const XT*>(reinterpret_cast<const char*>(W_c) + t * (unsigned)sizeof(XT));
+        i_raw = (int)*reinterpret_cast<const IT*>(reinterpret_cast<const char*>(idx) + t * (unsigned)sizeof(IT));
+    }
 }
 // n_valid (wave-uniform, may be <= 0) of the block's terms are real; the others become (weight 0, all-zero column).
 // SWZ: the offset also carries the column's swizzle bits (bits 6-7: which 64-byte quarter of the column's first 256 bytes the
@@ -212,12 +224,13 @@ __device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, i
     if (SWZ) ov = real ? ov | (((i_raw >> 2) & 3) << 6) : ov;
 }
 
-template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT>
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT, int PKB = 0>
 __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                       const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
-                                                      int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act, int bt_major) {
+                                                      int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act, int bt_major,
+                                                      const unsigned char* __restrict__ pk, int KS) {
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
@@ -262,7 +275,9 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     const int s0 = sg0 + wv_id * NPW;        // first slot of this wavefront
     const int zero_off = C * S4;             // byte offset of the all-zero column
     const int segs_per_chunk = C / kSegCols;
-    const int t_last = n_active * K - 1;     // the host guarantees n_active * K < 2^31
+    // KS: terms between the starts of consecutive stored rows in the arrays the terms are read from (K, or the padded row of
+    // the streaming copy)
+    const int t_last = n_active * KS - 1;    // the host guarantees n_active * KS < 2^31 (times the bytes of a term: < 2^32)
 
     // ---- chunk boundaries: lane j of bnd[i] holds the first term of chunk cb + j for slot s0 + i ----
     int bnd[NPW];
@@ -338,7 +353,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     {                                                                                                           \
         const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
         _Pragma("unroll") for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)                                          \
-            request_terms<XT, IT>(W_c, idx, (s0 + (i)) * K + k0_ + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]); \
+            request_terms<XT, IT, PKB>(W_c, idx, pk, (s0 + (i)) * KS + k0_ + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]); \
     }
 
     float acc[NPW][R];
@@ -355,7 +370,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
         for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)
-            request_terms<XT, IT>(W_c, idx, (s0 + i) * K + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]);
+            request_terms<XT, IT, PKB>(W_c, idx, pk, (s0 + i) * KS + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
     SRIGL_STAGE_STORE()
@@ -390,15 +405,15 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, lanepart, (n_terms + H - 1) / H, xa, xc);
                 // long ranges: the remaining blocks, one at a time, each requested one block ahead
                 if (n_terms > KPRE * TB) {
-                    const int row = (s0 + i) * K + k0n[i];
+                    const int row = (s0 + i) * KS + k0n[i];
                     XT wr;
                     int ir;
-                    request_terms<XT, IT>(W_c, idx, row + KPRE * TB, lofs, t_last, wr, ir);
+                    request_terms<XT, IT, PKB>(W_c, idx, pk, row + KPRE * TB, lofs, t_last, wr, ir);
                     for (int kb = KPRE * TB; kb < n_terms; kb += TB) {
                         float wc[1];
                         int oc[1];
                         finish_terms<XT, H, SWZ>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
-                        if (kb + TB < n_terms) request_terms<XT, IT>(W_c, idx, row + kb + TB, lofs, t_last, wr, ir);
+                        if (kb + TB < n_terms) request_terms<XT, IT, PKB>(W_c, idx, pk, row + kb + TB, lofs, t_last, wr, ir);
                         group_reads<R, 0>(xa, oc[0], xb, lanepart);
                         pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, lanepart, (n_terms - kb + H - 1) / H, xa, xc);
                     }
@@ -517,26 +532,44 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     else store_rows(std::true_type{});
 }
 
-template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT>
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT, int PKB = 0>
 static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
-    auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST, IT>;
+    auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST, IT, PKB>;
     static LdsLimit lds_limit;
     if (lds_limit.ensure(kern, p.lds) != SRIGL_OK) return SRIGL_ERR_HIP;
     const long long blocks = p.bt_major ? 8LL * ((p.n_btiles + 7) / 8) * p.n_groups : 8LL * ((p.n_groups + 7) / 8) * p.n_btiles;
     if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
                        (const IT*)a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
-                       p.n_groups, p.out_off, a.act, p.bt_major);
+                       p.n_groups, p.out_off, a.act, p.bt_major, static_cast<const unsigned char*>(a.packed), PKB ? (a.K + 3) / 4 * 4 : a.K);
     return hip_ok(hipGetLastError());
+}
+
+// The streaming copy is read when the call brings one whose terms this element type can take in one load (fp32: 8 bytes;
+// bf16 beside 16-bit indices: 4 bytes) and its byte offsets fit 32 bits.
+template <typename XT, typename IT> constexpr int rowlane_packed_term_bytes() { return sizeof(IT) != 4 ? 0 : (sizeof(XT) == 4 ? 8 : 4); }
+template <typename XT, typename IT>
+static bool rowlane_reads_packed(const FwdArgs& a) {
+    constexpr int PKB = rowlane_packed_term_bytes<XT, IT>();
+    if (PKB == 0 || a.packed == nullptr) return false;
+    if (PKB == 4 && a.d_in > 65536) return false;    // bf16 weights beside 32-bit indices: 8-byte terms, read from the arrays instead
+    return ((long long)a.n_active + 256) * ((a.K + 3) / 4 * 4) * PKB + 4096 < (1LL << 32);
 }
 
 template <int R, int H, int NPW, typename XT, typename IT>
 static srigl_status launch_rowlane_k(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     constexpr int KPRE = rowlane_kpre_rh(NPW, R, H);
+    constexpr int PKB = rowlane_packed_term_bytes<XT, IT>();
+    const bool pk = p.pk && p.fast && rowlane_reads_packed<XT, IT>(a);
     if constexpr (H > 1 && !(R == 2 && H == 2) && KPRE > 1) {
         // short rows: one preloaded block of 32 or 64 terms per stored row and chunk (the host's choice, by fan-in)
-        if (p.KPRE == 1) return p.fast ? launch_rowlane_f<R, H, NPW, 1, XT, true, IT>(a, p, st) : SRIGL_ERR_UNSUPPORTED;
+        if (p.KPRE == 1) {
+            if (!p.fast) return SRIGL_ERR_UNSUPPORTED;
+            if constexpr (PKB != 0) { if (pk) return launch_rowlane_f<R, H, NPW, 1, XT, true, IT, PKB>(a, p, st); }
+            return launch_rowlane_f<R, H, NPW, 1, XT, true, IT>(a, p, st);
+        }
     }
+    if constexpr (PKB != 0) { if (pk) return launch_rowlane_f<R, H, NPW, KPRE, XT, true, IT, PKB>(a, p, st); }
     if (p.fast) return launch_rowlane_f<R, H, NPW, KPRE, XT, true, IT>(a, p, st);
     if constexpr (R == 1 && H == 1) return launch_rowlane_f<R, H, NPW, KPRE, XT, false, IT>(a, p, st);
     return SRIGL_ERR_UNSUPPORTED;   // the planner keeps R = 1, H = 1 when the fast staging does not apply

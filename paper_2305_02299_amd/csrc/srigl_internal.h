@@ -16,74 +16,62 @@ constexpr int kSegCols = 64;           // columns per entry of the seg table
 constexpr size_t kLdsMax = 160 * 1024; // LDS per workgroup on gfx950
 
 // The streaming copy of the condensed arrays (App. E: values and column indices, n x k each) that srigl_condense and
-// srigl_pack_terms write and the forward kernels may read instead of W_c / idx.  Neuron-major; a row is ceil(K / 4) units
-// of four consecutive terms; a unit holds the four weights, then the four indices, so that the terms a lane works on come
-// with one or two 16-byte loads from one 32-byte piece and a lane group reads consecutive units:
-//   fp32 weights:                       unit = w[4] fp32, idx[4] int32                      (32 bytes)
-//   bf16 weights, d_in <= 65536:        unit = w[4] bf16, idx[4] uint16                     (16 bytes: one load)
-//   bf16 weights, wider inputs:         unit = w[4] bf16, 8 bytes of zeros, idx[4] int32    (32 bytes)
-// Places behind the K-th term carry weight bits 0 and index 0.
+// srigl_pack_terms write and the forward kernels may read instead of W_c / idx.  Neuron-major and K-interleaved: the weight
+// and the column index of a term sit next to each other, terms in row order, rows padded to a multiple of four terms
+// (weight bits 0, index 0), so that rows start 16-byte aligned, a lane's four consecutive terms come with one or two
+// 16-byte loads, and one 4- or 8-byte load brings both halves of a term:
+//   fp32 weights:                  term = w fp32, idx int32                     (8 bytes)
+//   bf16 weights, d_in <= 65536:   term = w bf16 (low half), idx uint16 (high)  (4 bytes)
+//   bf16 weights, wider inputs:    term = w bf16, 16 zero bits, idx int32       (8 bytes)
 struct PackedLayout {
-    int units;        // units per row
-    int unit_bytes;   // 16 or 32
+    int terms;        // terms per row, padding included (a multiple of 4)
+    int term_bytes;   // 4 or 8
     int w_bytes;      // 4 or 2
-    int i_bytes;      // 4 or 2
-    int i_off;        // byte offset of the indices inside a unit
-    __host__ __device__ size_t row_bytes() const { return (size_t)units * unit_bytes; }
+    __host__ __device__ size_t row_bytes() const { return (size_t)terms * term_bytes; }
     // term t of a row whose packed copy starts at `row`: weight bits and column
     __device__ void store(unsigned char* row, int t, uint32_t wbits, int col) const {
-        unsigned char* u = row + (size_t)(t >> 2) * unit_bytes;
-        const int p = t & 3;
-        if (w_bytes == 4) reinterpret_cast<uint32_t*>(u)[p] = wbits; else reinterpret_cast<uint16_t*>(u)[p] = (uint16_t)wbits;
-        if (i_bytes == 4) reinterpret_cast<int32_t*>(u + i_off)[p] = col; else reinterpret_cast<uint16_t*>(u + i_off)[p] = (uint16_t)col;
-        if (unit_bytes == 32 && w_bytes == 2) reinterpret_cast<uint16_t*>(u + 8)[p] = 0;
+        if (term_bytes == 4) {
+            reinterpret_cast<uint32_t*>(row)[t] = (wbits & 0xffffu) | ((uint32_t)col << 16);
+        } else {
+            reinterpret_cast<uint2*>(row)[t] = make_uint2(w_bytes == 4 ? wbits : (wbits & 0xffffu), (uint32_t)col);
+        }
     }
 };
 inline PackedLayout packed_layout(int K, int d_in, bool bf16) {
     PackedLayout pl;
-    pl.units = (K + 3) / 4;
+    pl.terms = (K + 3) / 4 * 4;
     pl.w_bytes = bf16 ? 2 : 4;
-    const bool narrow = bf16 && d_in <= 65536;
-    pl.i_bytes = narrow ? 2 : 4;
-    pl.unit_bytes = narrow ? 16 : 32;
-    pl.i_off = narrow ? 8 : 16;
+    pl.term_bytes = (bf16 && d_in <= 65536) ? 4 : 8;
     return pl;
 }
 
 // One unit of the streaming copy in registers (device side).
+// (four consecutive terms; UB = bytes of the four terms: 32, or 16 for bf16 weights beside 16-bit indices)
 template <typename XT, int UB> struct PackedUnit;
 template <> struct PackedUnit<float, 32> {
-    float4 w; int4 c;
+    uint4 a, b;   // (w0, i0, w1, i1), (w2, i2, w3, i3)
     __device__ __forceinline__ void load(const unsigned char* __restrict__ u) {
-        w = *reinterpret_cast<const float4*>(u);
-        c = *reinterpret_cast<const int4*>(u + 16);
+        a = *reinterpret_cast<const uint4*>(u);
+        b = *reinterpret_cast<const uint4*>(u + 16);
     }
-    __device__ __forceinline__ float weight(int t) const { return t == 0 ? w.x : (t == 1 ? w.y : (t == 2 ? w.z : w.w)); }
-    __device__ __forceinline__ int col(int t) const { return t == 0 ? c.x : (t == 1 ? c.y : (t == 2 ? c.z : c.w)); }
+    __device__ __forceinline__ float weight(int t) const { return __uint_as_float(t == 0 ? a.x : (t == 1 ? a.z : (t == 2 ? b.x : b.z))); }
+    __device__ __forceinline__ int col(int t) const { return (int)(t == 0 ? a.y : (t == 1 ? a.w : (t == 2 ? b.y : b.w))); }
 };
 template <> struct PackedUnit<uint16_t, 16> {
-    uint4 v;   // x, y: four bf16 weights; z, w: four 16-bit indices
+    uint4 v;   // four terms: bf16 weight in the low half, 16-bit index in the high half
     __device__ __forceinline__ void load(const unsigned char* __restrict__ u) { v = *reinterpret_cast<const uint4*>(u); }
-    __device__ __forceinline__ float weight(int t) const {
-        const uint32_t pair = t < 2 ? v.x : v.y;
-        return (t & 1) ? __uint_as_float(pair & 0xffff0000u) : __uint_as_float(pair << 16);
-    }
-    __device__ __forceinline__ int col(int t) const {
-        const uint32_t pair = t < 2 ? v.z : v.w;
-        return (int)((t & 1) ? (pair >> 16) : (pair & 0xffffu));
-    }
+    __device__ __forceinline__ uint32_t word(int t) const { return t == 0 ? v.x : (t == 1 ? v.y : (t == 2 ? v.z : v.w)); }
+    __device__ __forceinline__ float weight(int t) const { return __uint_as_float(word(t) << 16); }
+    __device__ __forceinline__ int col(int t) const { return (int)(word(t) >> 16); }
 };
 template <> struct PackedUnit<uint16_t, 32> {
-    uint2 w; int4 c;
+    uint4 a, b;   // (w0, i0, w1, i1), (w2, i2, w3, i3), weights as bf16 bits in the low half of their word
     __device__ __forceinline__ void load(const unsigned char* __restrict__ u) {
-        w = *reinterpret_cast<const uint2*>(u);
-        c = *reinterpret_cast<const int4*>(u + 16);
+        a = *reinterpret_cast<const uint4*>(u);
+        b = *reinterpret_cast<const uint4*>(u + 16);
     }
-    __device__ __forceinline__ float weight(int t) const {
-        const uint32_t pair = t < 2 ? w.x : w.y;
-        return (t & 1) ? __uint_as_float(pair & 0xffff0000u) : __uint_as_float(pair << 16);
-    }
-    __device__ __forceinline__ int col(int t) const { return t == 0 ? c.x : (t == 1 ? c.y : (t == 2 ? c.z : c.w)); }
+    __device__ __forceinline__ float weight(int t) const { return __uint_as_float((t == 0 ? a.x : (t == 1 ? a.z : (t == 2 ? b.x : b.z))) << 16); }
+    __device__ __forceinline__ int col(int t) const { return (int)(t == 0 ? a.y : (t == 1 ? a.w : (t == 2 ? b.y : b.w))); }
 };
 
 struct FwdArgs {
@@ -113,6 +101,7 @@ struct RowlanePlan {
     double cost;  // the planner's estimate for this shape (arbitrary units), to compare shapes
     int out_off;  // word offset of the result tile in LDS (0: it reuses the activation tile after a barrier)
     bool fast;   // x rows allow aligned 4-element loads and d_in is a multiple of 16
+    bool pk;     // the terms are read from the streaming copy (forced through the tuning; the default reads W_c / idx)
     bool ok;
 };
 constexpr int kSpanCap = 1024;     // output columns (stored and ablated) a workgroup of the batched kernel writes through its column table

@@ -161,10 +161,10 @@ def test_klane_launch_shapes(tuning):
 
 # ----------------------------------------------------------------------------- the streaming copy in place of W_c / idx
 @pytest.mark.parametrize("cfg,B", [("c1", 1), ("c2", 256), ("c3", 1), ("c3", 256)])
-@pytest.mark.parametrize("algo", ["auto", "klane"])
+@pytest.mark.parametrize("algo", ["auto", "klane", "rowlane"])
 def test_named_configs_through_the_streaming_copy(cfg, B, algo):
     L = si.config(cfg, B=B) if cfg == "c3" else si.config(cfg)
-    worst = check_layer(L, ALGOS[algo], packed=True)
+    worst = check_layer(L, ALGOS[algo], {"terms_from_copy": 1} if algo == "rowlane" else None, packed=True)
     assert worst < 2e-6
 
 
@@ -175,6 +175,27 @@ def test_klane_launch_shapes_through_the_streaming_copy(tuning):
                                             (1300, 70, 130, 5, 0.2, "bf16"), (70000, 12, 9, 2, 0.0, "bf16"), (64, 40, 64, 11, 0.0, "f32")):
         L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=78)
         check_layer(L, B_.FWD_KLANE, tuning, packed=True, unsupported_ok=(d_in > 40960 and tuning["direct_gather"] == 2))
+
+
+@pytest.mark.parametrize("tuning", [
+    {"rows_per_lane": 1, "waves": 4, "neurons_per_wave": 1, "chunk_cols": 64},
+    {"rows_per_lane": 1, "waves": 16, "neurons_per_wave": 6, "chunk_cols": 256},
+    {"rows_per_lane": 2, "waves": 16, "neurons_per_wave": 4, "chunk_cols": 256},
+    {"rows_per_lane": 2, "term_slices": 2, "waves": 16, "neurons_per_wave": 3},
+    {"rows_per_lane": 2, "term_slices": 4, "waves": 8, "neurons_per_wave": 2, "chunk_cols": 192},
+    {"rows_per_lane": 4, "term_slices": 4, "waves": 16, "neurons_per_wave": 3},
+    {"term_slices": 2, "waves": 8, "neurons_per_wave": 6, "chunk_cols": 192},
+    {"term_slices": 4, "waves": 16, "neurons_per_wave": 2, "chunk_cols": 128},
+])
+def test_rowlane_launch_shapes_through_the_streaming_copy(tuning):
+    """The batched kernel with its terms read from the streaming copy (one load per block of terms): every tile shape, fp32
+    and bf16 storage, rows whose padded length differs from K, and a bf16 layer too wide for 16-bit indices (which the
+    kernel reads from the arrays)."""
+    for (d_in, d_out, K, B, abl, dtype) in ((768, 300, 77, 300, 0.1, "f32"), (3072, 96, 307, 70, 0.3, "f32"), (768, 40, 8, 17, 0.0, "f32"),
+                                            (1024, 50, 615, 33, 0.2, "f32"), (1024, 200, 102, 130, 0.2, "bf16"),
+                                            (4096, 64, 205, 70, 0.0, "bf16"), (65552, 20, 9, 40, 0.0, "bf16")):
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=79)
+        assert check_layer(L, B_.FWD_ROWLANE, dict(tuning, terms_from_copy=1), packed=True, unsupported_ok=True) is not None
 
 
 def test_padded_places_of_the_streaming_copy_never_meet_an_activation():
@@ -317,8 +338,8 @@ def test_large_layer_sampled_rows():
                                     [128 * t + rng.choice(np.arange(2, 126), size=3, replace=False) for t in range(16)]))
     assert all(((rows // 128 == t) & (rows % 128 > 1) & (rows % 128 < 126)).sum() >= 2 for t in range(16))
     y_ref, S = oracle.fwd(L.x_bf16[rows], W_c, idx, active, L.bias, L.d_out, want_scale=True)
-    for algo in (None, B_.FWD_ROWLANE):
-        y = run_gpu(L, W_c, idx, active, L.bias, algo)
+    for algo, packed in ((None, False), (B_.FWD_ROWLANE, False), (B_.FWD_ROWLANE, True)):
+        y = run_gpu(L, W_c, idx, active, L.bias, algo, {"terms_from_copy": 1} if packed else None, packed=packed)
         gate(y[rows], y_ref, S, TOL_BF16)
         ablated = np.setdiff1d(np.arange(L.d_out), active)
         assert np.array_equal(y[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (2048, 1)).view(np.uint32))

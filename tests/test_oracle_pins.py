@@ -373,25 +373,27 @@ def test_packed_copy_handworked_fixture():
 
 def test_packed_copy_holds_every_term_once_and_wide_indices_when_needed():
     """Reading the bytes back with plain struct unpacking returns the canonical arrays; a bf16 layer wider than 65536
-    columns keeps 32-bit indices behind 8 zero bytes."""
+    columns keeps 32-bit indices behind the weight's half-word and 16 zero bits."""
     import struct
     rng = np.random.default_rng(3)
     for (n, K, d_in, bf16) in ((5, 77, 768, False), (3, 9, 70000, True), (4, 12, 4096, True)):
         idx = np.sort(np.stack([rng.choice(d_in, K, replace=False) for _ in range(n)]), axis=1).astype(np.int32)
         W = rng.integers(1, 65535, size=(n, K)).astype(np.uint16) if bf16 else rng.normal(size=(n, K)).astype(np.float32)
         raw = oracle.pack_terms(W, idx, d_in)
-        narrow = bf16 and d_in <= 65536
-        ub = 16 if narrow else 32
-        assert raw.shape == (n, (K + 3) // 4 * ub)
+        tb = 4 if (bf16 and d_in <= 65536) else 8
+        terms = (K + 3) // 4 * 4
+        assert raw.shape == (n, terms * tb)
         for s in range(n):
             b = raw[s].tobytes()
-            for t in range((K + 3) // 4 * 4):
-                u, p = divmod(t, 4)
-                w = struct.unpack_from("<H" if bf16 else "<f", b, u * ub + (2 if bf16 else 4) * p)[0]
-                col = struct.unpack_from("<H" if narrow else "<i", b, u * ub + (8 + 2 * p if narrow else 16 + 4 * p))[0]
+            for t in range(terms):
+                if tb == 4:
+                    w, col = struct.unpack_from("<HH", b, 4 * t)
+                elif bf16:
+                    w, zero, col = struct.unpack_from("<HHi", b, 8 * t)
+                    assert zero == 0
+                else:
+                    w, col = struct.unpack_from("<fi", b, 8 * t)
                 assert (w, col) == ((W[s, t], idx[s, t]) if t < K else (0, 0))
-            if bf16 and not narrow:
-                assert all(b[u * 32 + 8: u * 32 + 16] == bytes(8) for u in range((K + 3) // 4))
 
 
 def test_compact_hidden_layer_is_the_first_layer_without_its_ablated_columns():
