@@ -128,12 +128,13 @@ def sweep(args):
         n_sets = min(max(2, -(-2 * CACHE_BYTES // nbytes)), 300)
         xs = dev(xsrc)
         sets = [(xs.clone(), layer.W_c.clone(), layer.idx.clone(), None if layer.active is None else layer.active.clone(),
-                 layer.bias.clone(), layer.seg.clone(), torch.empty((B, L.d_out), device="cuda")) for _ in range(n_sets)]
+                 layer.bias.clone(), layer.seg.clone(), torch.empty((B, L.d_out), device="cuda"), layer.packed.clone())
+                for _ in range(n_sets)]
 
         def f_on(ss):
             def f(i):
-                x, W_c, idx, act, bias, seg, y = ss[i % len(ss)]
-                B_.srigl_condensed_linear_fwd(x, B, L.d_in, W_c, idx, act, layer.n_active, L.K, bias, L.d_out, y, seg)
+                x, W_c, idx, act, bias, seg, y, packed = ss[i % len(ss)]
+                B_.srigl_condensed_linear_fwd(x, B, L.d_in, W_c, idx, act, layer.n_active, L.K, bias, L.d_out, y, seg, packed=packed)
             return f
         steps = max(20, min(400, int(20000 / max(1.0, nbytes / 4e5))))
         cold = time_graph(f_on(sets), max(steps, n_sets), 10) * 1e3

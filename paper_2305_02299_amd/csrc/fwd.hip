@@ -490,6 +490,7 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     if (p.R == 4 && p.H != 2 && p.H != 4) return p;   // four rows per lane: 128- or 64-row tiles (whole 64-row groups per term slice)
     if (!p.fast && (p.R != 1 || p.H != 1)) return p;
     const int BT = kWave * p.R / p.H, S = rowlane_row_stride(BT, p.H, p.R);
+    if ((long long)(BT + 1) * a.d_in * 4 >= (1LL << 32)) return p;   // a lane's byte offset inside its batch tile is 32-bit
     p.n_btiles = (a.B + BT - 1) / BT;
     const int nw_max = rowlane_max_threads(p.R) / kWave;
     p.NW = t && t->waves ? t->waves : nw_max;

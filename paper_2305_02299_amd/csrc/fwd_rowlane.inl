@@ -230,7 +230,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
                                                       int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act, int bt_major,
-                                                      const unsigned char* __restrict__ pk, int KS) {
+                                                      const unsigned char* __restrict__ pk, int KS, unsigned div_magic) {
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
@@ -250,14 +250,18 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     // only its own rows of x and every XCD all of W_c / idx.  The host picks the order that fetches fewer bytes.
     const int wg = blockIdx.x;
     const int xcd = wg & 7, inx = wg >> 3;
+    // (the quotient by the host's multiplier, ceil(2^32 / divisor), exact for this launch's ids; 0: plain division)
+    const int dec_d = bt_major ? n_groups : n_btiles;
+    const int dec_q = dec_d == 1 ? inx : (div_magic ? (int)__umulhi((unsigned)inx, div_magic) : inx / dec_d);
+    const int dec_r = inx - dec_q * dec_d;
     int bt, g;
     if (bt_major) {
-        g = inx % n_groups;
-        bt = (inx / n_groups) * 8 + xcd;
+        g = dec_r;
+        bt = dec_q * 8 + xcd;
         if (bt >= n_btiles) return;
     } else {
-        bt = inx % n_btiles;
-        g = (inx / n_btiles) * 8 + xcd;
+        bt = dec_r;
+        g = dec_q * 8 + xcd;
         if (g >= n_groups) return;
     }
 
@@ -291,26 +295,27 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         bnd[i] = v;                                                                                             \
     }
 
-    // ---- staging: 16 rows x 16 columns per unit; unit u = wv_id + i * nw -> (row tile, column tile) ----
+    // ---- staging: 16 rows x 16 columns per unit; unit u = wv_id + i * nw -> row tile u % (BT / 16), column tile u / (BT / 16)
+    // (BT / 16 is a power of two: the units a wavefront takes walk along its rows, and the split costs a shift) ----
     const int dq = lane & 3, db = lane >> 2;             // 4 column quads x 16 rows per wavefront pass
     const int col_tiles = C >> 4;                         // C is a multiple of 64
-    const float inv_col_tiles = 1.0f / (float)col_tiles;
-    const int units = (BT / 16) * col_tiles;              // <= kStageUnits * nw (checked by the host)
-    unsigned g_off[kStageUnits];                          // element offset into x of this lane's 4 columns (chunk 0)
+    constexpr int RT = BT / 16, RT_LOG2 = RT == 1 ? 0 : (RT == 2 ? 1 : (RT == 4 ? 2 : 3));
+    static_assert(RT == 1 || RT == 2 || RT == 4 || RT == 8, "batch tile of 16 .. 128 rows");
+    // this lane's bytes are addressed from the tile's first row (a wave-uniform base) with 32-bit offsets: BT rows of x
+    const char* const xtile = reinterpret_cast<const char*>(x + (size_t)b0 * d_in);
+    unsigned g_off[kStageUnits];                          // byte offset from xtile of this lane's 4 columns (chunk 0)
     int l_off[kStageUnits];                               // word offset into the LDS tile
     int u_col[kStageUnits];                               // first column of the unit (wave-uniform)
 #pragma unroll
     for (int i = 0; i < kStageUnits; ++i) {
         const int u = wv_id + i * nw;
-        // u / col_tiles without an integer division (exact: u and col_tiles are below 2^11, the half keeps the quotient
-        // at least 0.5 / col_tiles away from the next integer)
-        const int rt = (int)(((float)u + 0.5f) * inv_col_tiles), ct = u - rt * col_tiles;
+        const int rt = u & (RT - 1), ct = u >> RT_LOG2;
         const int rl = rt * 16 + db;
         const int f = ct * 16 + dq * 4;
         // rows past B re-read row B - 1: their lanes compute values that are never stored
-        g_off[i] = (unsigned)(min(b0 + rl, B - 1) * d_in + f);   // the host guarantees B * d_in < 2^31
+        g_off[i] = (unsigned)(min(rl, B - 1 - b0) * d_in + f) * (unsigned)sizeof(XT);   // BT * d_in * 4 < 2^32 (host)
         l_off[i] = f * S + (SWZ ? (rl ^ (((f >> 2) & 3) << 4)) : rl);   // (f .. f + 3 share one swizzle: f is a multiple of 4)
-        u_col[i] = (u < units) ? ct * 16 : 0x40000000;   // units past the tile never pass the column tests below
+        u_col[i] = (ct < col_tiles) ? ct * 16 : 0x40000000;   // units past the tile never pass the column tests below
     }
     Staged4<XT> st[kStageUnits];
 #define SRIGL_STAGE_LOAD_UNITS(c, u_first, u_last)                                                              \
@@ -318,11 +323,11 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         const int c0_ = (c) * C;                                                                                \
         if (u_ >= (u_first) && u_ < (u_last)) {                                                                 \
             if (FAST) {                                                                                         \
-                if (c0_ + u_col[u_] < d_in) load4(x + (g_off[u_] + (unsigned)c0_), true, 4, st[u_]);        \
+                if (c0_ + u_col[u_] < d_in) load4(reinterpret_cast<const XT*>(xtile + (g_off[u_] + (unsigned)c0_ * (unsigned)sizeof(XT))), true, 4, st[u_]); \
             } else {                                                                                            \
                 st[u_].clear();                                                                                 \
                 const int nv = min(4, d_in - (c0_ + u_col[u_] + dq * 4));                                       \
-                if (u_col[u_] < C && nv > 0) load4(x + (g_off[u_] + (unsigned)c0_), false, nv, st[u_]);     \
+                if (u_col[u_] < C && nv > 0) load4(reinterpret_cast<const XT*>(xtile + (g_off[u_] + (unsigned)c0_ * (unsigned)sizeof(XT))), false, nv, st[u_]); \
             }                                                                                                   \
         }                                                                                                       \
     }
@@ -532,6 +537,12 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     else store_rows(std::true_type{});
 }
 
+// ceil(2^32 / d): workgroup id / 8 divided by d is then one multiply-high, exact while (id / 8) * d < 2^32; 0 = divide
+static inline unsigned rowlane_decode_multiplier(long long blocks, int d) {
+    if (d <= 1 || (blocks / 8 + 1) * (long long)d >= (1LL << 32)) return 0u;
+    return (unsigned)(((1ULL << 32) + (unsigned)d - 1) / (unsigned)d);
+}
+
 template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT, int PKB = 0>
 static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
     auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST, IT, PKB>;
@@ -541,7 +552,8 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
     if (blocks > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
                        (const IT*)a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
-                       p.n_groups, p.out_off, a.act, p.bt_major, static_cast<const unsigned char*>(a.packed), PKB ? (a.K + 3) / 4 * 4 : a.K);
+                       p.n_groups, p.out_off, a.act, p.bt_major, static_cast<const unsigned char*>(a.packed), PKB ? (a.K + 3) / 4 * 4 : a.K,
+                       rowlane_decode_multiplier(blocks, p.bt_major ? p.n_groups : p.n_btiles));
     return hip_ok(hipGetLastError());
 }
 
