@@ -328,6 +328,26 @@ def structured(args, emit=True):
     t_d = time_graph(lambda i: torch.matmul(xt, Wt.t()), steps, warmup)
     flops = 2.0 * L.B * layer.n_active * L.d_in
     tf = flops / (t_s * 1e-3) / 1e12
+
+    def few_tiles(name, Bn):
+        """An fp32 layer whose output tiles reach a fraction of the compute units: one part against the library's choice of parts."""
+        Ls = si.config(name, B=Bn)
+        ly = condense_layer(dev(Ls.W), dev(Ls.mask), Ls.K, dev(Ls.bias))
+        xd, yd, Wdd = dev(Ls.x), torch.empty((Bn, Ls.d_out), device="cuda"), ly.dense_rows()
+        parts, need = B_.srigl_structured_split_plan(Bn, Ls.d_in, ly.n_active, Ls.d_out, B_.F32)
+        ws = torch.empty((max(need, 4),), dtype=torch.uint8, device="cuda")
+        one = time_graph(lambda i: B_.srigl_structured_linear_fwd(xd, Bn, Ls.d_in, Wdd, ly.active, ly.n_active, ly.bias, Ls.d_out, yd),
+                         steps, warmup)
+        cut = time_graph(lambda i: B_.srigl_structured_linear_fwd_split(xd, Bn, Ls.d_in, Wdd, ly.active, ly.n_active, ly.bias, Ls.d_out, yd,
+                                                                        ws), steps, warmup)
+        cond = time_graph(lambda i: ly.forward(xd, yd), steps, warmup)
+        Wfull = dev((Ls.W * Ls.mask).astype(np.float32))
+        lib = time_graph(lambda i: torch.matmul(xd, Wfull.t()), steps, warmup)
+        return {"layer": "%s %d->%d fp32, n_active=%d, B=%d" % (name, Ls.d_in, Ls.d_out, ly.n_active, Bn), "parts": parts,
+                "structured_one_part_us": round(one * 1e3, 2), "structured_parts_us": round(cut * 1e3, 2),
+                "condensed_us": round(cond * 1e3, 2), "library_dense_f32_matmul_us": round(lib * 1e3, 2)}
+
+    few = [few_tiles("c3", 256), few_tiles("c3", 64), few_tiles("c2", 64)]
     out = ({
         "metric": "structured_linear_fwd_us_per_call", "value": t_s * 1e3, "unit": "us/call", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": t_s, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
@@ -335,7 +355,8 @@ def structured(args, emit=True):
         "config": {"workload": "c5 structured-only: %d->%d bf16, n_active=%d dense rows, B=%d" % (L.d_in, L.d_out, layer.n_active, L.B)},
         "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None},
         "context": {"condensed_same_layer_us": t_c * 1e3, "library_dense_bf16_matmul_us": t_d * 1e3,
-                    "library_dense_tflops": 2.0 * L.B * L.d_out * L.d_in / (t_d * 1e-3) / 1e12}})
+                    "library_dense_tflops": 2.0 * L.B * L.d_out * L.d_in / (t_d * 1e-3) / 1e12,
+                    "fp32_layers_of_few_tiles": few}})
     if emit:
         print(json.dumps(out), flush=True)
     return out

@@ -358,6 +358,26 @@ srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype
                                               srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
                                               const float* bias, int32_t d_out, float* y, srigl_gemm_tile tile, void* stream);
 
+/* The same product with d_in cut into parts (Sec. 4.4 / Fig. 4, structured-only form at small batch or few stored neurons:
+ * the output tiles alone then reach a fraction of the compute units).  Every part's tiles run side by side and write
+ * partial sums to workspace[part][B][n_active] (fp32); a second launch adds the parts in ascending order, adds the bias
+ * and writes every column of y (deterministic: no atomics).  The sums differ from the one-part call's in rounding order only.
+ *
+ * srigl_structured_split_plan: the library's choice of parts for these sizes (1 = do not split) and the workspace
+ * bytes that choice needs (parts * B * n_active * 4; 0 for one part).  Host-only.
+ * srigl_structured_linear_fwd_split: splits = 0 takes that choice (with tile = SRIGL_TILE_AUTO; a forced tile with
+ * splits = 0 keeps one part), splits = 1..16 forces it; every part must hold at least one LDS stage of the tile
+ * (SRIGL_ERR_INVALID_ARG otherwise).  workspace (device, 4-byte aligned, owned by the caller, contents undefined
+ * afterwards) smaller than parts * B * n_active * 4 bytes: SRIGL_ERR_CAPACITY.  Calls that share a workspace must not
+ * overlap. */
+srigl_status srigl_structured_split_plan(int32_t B, int32_t d_in, int32_t n_active, int32_t d_out, srigl_dtype dtype, int32_t* splits,
+                                         size_t* workspace_bytes);
+
+srigl_status srigl_structured_linear_fwd_split(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
+                                               srigl_dtype w_dtype, const int32_t* active, int32_t n_active, const float* bias,
+                                               int32_t d_out, float* y, srigl_gemm_tile tile, int32_t splits, void* workspace,
+                                               size_t workspace_bytes, void* stream);
+
 /* Which of the two representations of a layer is expected to run its forward pass faster for a batch of B rows
  * (Sec. 4.4 / Fig. 4: the condensed form wins at small batch and high sparsity, the structured-only form at large batch
  * and modest sparsity).  Host-only arithmetic on the sizes, from timings of both kernels on MI355X; the two estimates

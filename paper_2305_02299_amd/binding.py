@@ -30,7 +30,7 @@ EXPORTS = (
     "srigl_packed_bytes", "srigl_pack_terms",
     "srigl_condensed_linear_fwd", "srigl_condensed_linear_fwd_algo", "srigl_launch_empty",
     "srigl_copy_bytes", "srigl_status_str", "srigl_densify", "srigl_structured_linear_fwd",
-    "srigl_structured_linear_fwd_tile", "srigl_choose_representation",
+    "srigl_structured_linear_fwd_tile", "srigl_structured_split_plan", "srigl_structured_linear_fwd_split", "srigl_choose_representation",
     "srigl_condensed_linear_fwd_act", "srigl_fold_ablated_inputs", "srigl_mask_update_workspace_bytes", "srigl_mask_update",
     "srigl_compact_hidden_layer", "srigl_condensed_mlp_fwd", "srigl_narrow_idx", "srigl_condensed_linear_fwd_idx16", "srigl_csr_linear_fwd", "srigl_fwd_plan_query", "srigl_fwd_plan_query_algo",
 )
@@ -87,6 +87,11 @@ def _load() -> ctypes.CDLL:
     lib.srigl_structured_linear_fwd.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, vp]
     lib.srigl_structured_linear_fwd_tile.restype = ctypes.c_int
     lib.srigl_structured_linear_fwd_tile.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, ctypes.c_int, vp]
+    lib.srigl_structured_split_plan.restype = ctypes.c_int
+    lib.srigl_structured_split_plan.argtypes = [i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_size_t)]
+    lib.srigl_structured_linear_fwd_split.restype = ctypes.c_int
+    lib.srigl_structured_linear_fwd_split.argtypes = [vp, ctypes.c_int, i32, i32, vp, ctypes.c_int, vp, i32, vp, i32, vp, ctypes.c_int, i32,
+                                                      vp, ctypes.c_size_t, vp]
     lib.srigl_choose_representation.restype = ctypes.c_int
     lib.srigl_choose_representation.argtypes = [i32, i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
                                                 ctypes.POINTER(ctypes.c_float)]
@@ -286,6 +291,23 @@ def srigl_structured_linear_fwd(x, B, d_in, Wd, active, n_active, bias, d_out, y
         st = lib.srigl_structured_linear_fwd_tile(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(Wd), wcode, _ptr(active),
                                                   int(n_active), _ptr(bias), int(d_out), _ptr(y), int(tile), _stream())
     _check(st, "srigl_structured_linear_fwd")
+
+
+def srigl_structured_split_plan(B, d_in, n_active, d_out, dtype_code):
+    """Returns (parts of d_in the library would take, workspace bytes that needs)."""
+    n, b = ctypes.c_int32(0), ctypes.c_size_t(0)
+    _check(lib.srigl_structured_split_plan(int(B), int(d_in), int(n_active), int(d_out), int(dtype_code), ctypes.byref(n), ctypes.byref(b)),
+           "srigl_structured_split_plan")
+    return int(n.value), int(b.value)
+
+
+def srigl_structured_linear_fwd_split(x, B, d_in, Wd, active, n_active, bias, d_out, y, workspace, splits=0, tile=None):
+    """splits 0: the library's choice (srigl_structured_split_plan); workspace: a device byte tensor (or None for one part)."""
+    wcode = _dtype_code(Wd if Wd is not None else x)
+    st = lib.srigl_structured_linear_fwd_split(_ptr(x), _dtype_code(x), int(B), int(d_in), _ptr(Wd), wcode, _ptr(active), int(n_active),
+                                               _ptr(bias), int(d_out), _ptr(y), int(tile or 0), int(splits), _ptr(workspace),
+                                               _nbytes(workspace), _stream())
+    _check(st, "srigl_structured_linear_fwd_split")
 
 
 def srigl_choose_representation(B, d_in, n_active, K, d_out, dtype_code):

@@ -100,6 +100,39 @@ __global__ __launch_bounds__(256) void k_fill_ablated(const int32_t* __restrict_
     }
 }
 
+// y[r][c] = bias[c] + sum over the parts z (ascending) of part[z][r][s] when column c is stored neuron s, else bias[c].
+// One thread per (row r, slot s <= n_active): slot s writes its neuron's column and the ablated columns between the previous
+// stored neuron and its own; slot n_active writes the ablated columns after the last stored neuron.  The parts' values are
+// requested together (up to kMaxSplits independent loads), so a thread waits for memory twice: the list, then the values.
+constexpr int kMaxSplits = 16;
+__global__ __launch_bounds__(256) void k_sum_parts(const float* __restrict__ part, int splits, int B, int n_active,
+                                                   const int32_t* __restrict__ active, const float* __restrict__ bias, int d_out,
+                                                   float* __restrict__ y) {
+    const int s = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.y;
+    if (s > n_active) return;
+    float v[kMaxSplits];
+    const size_t plane = (size_t)B * n_active;
+    const float* p = part + (size_t)r * n_active + (s < n_active ? s : 0);
+#pragma unroll
+    for (int z = 0; z < kMaxSplits; ++z) v[z] = (z < splits && s < n_active) ? p[z * plane] : 0.0f;
+    int lo, hi;   // ablated columns lo .. hi - 1, then the stored neuron's column hi (none for the last slot)
+    if (active == nullptr) {
+        lo = hi = s;   // every neuron stored: n_active == d_out
+    } else {
+        lo = s > 0 ? active[s - 1] + 1 : 0;
+        hi = s < n_active ? active[s] : d_out;
+    }
+    float* yr = y + (size_t)r * d_out;
+    for (int c = lo; c < hi; ++c) __builtin_nontemporal_store(bias ? bias[c] : 0.0f, &yr[c]);
+    if (s < n_active) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int z = 0; z < kMaxSplits; ++z) sum += v[z];   // parts past `splits` hold zeros
+        __builtin_nontemporal_store(sum + (bias ? bias[hi] : 0.0f), &yr[hi]);
+    }
+}
+
 template <typename T> struct Frag;
 template <> struct Frag<uint16_t> { using type = bf16x8_t; };
 template <> struct Frag<float> { using type = float4; };
@@ -140,7 +173,8 @@ struct EpiLayout {
 template <typename T, int BM, int BN, int WGM, int WGN, int NS, int SLAB, bool RAGGED>
 __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __restrict__ x, int B, int d_in, const T* __restrict__ Wd,
                                                                    const int32_t* __restrict__ active, int n_active,
-                                                                   const float* __restrict__ bias, int d_out, float* __restrict__ y) {
+                                                                   const float* __restrict__ bias, int d_out, float* __restrict__ y,
+                                                                   int splits, float* __restrict__ part) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];   // [NS][BM + BN rows][SLAB bytes]
     using F = typename Frag<T>::type;
     constexpr int NWAVES = WGM * WGN;
@@ -196,12 +230,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
     }
     const unsigned char* xbase = reinterpret_cast<const unsigned char*>(x + (size_t)m0 * d_in);
     const unsigned char* wbase = reinterpret_cast<const unsigned char*>(Wd + (size_t)n0 * d_in);
-    const int n_st = (d_in + EPS - 1) / EPS;
+    // Part blockIdx.y of d_in (splits parts of whole stages, sizes one stage apart at most): stages h_first .. h_first + n_st - 1
+    // of the row.  With one part the tile's sums are complete and go to y; with several they go to part[blockIdx.y][B][n_active].
+    const int n_st_row = (d_in + EPS - 1) / EPS;
+    const int h_first = (int)(((long long)blockIdx.y * n_st_row) / splits);
+    const int n_st = (int)(((long long)(blockIdx.y + 1) * n_st_row) / splits) - h_first;
     // RAGGED: d_in is not a multiple of EPS; the pieces of the last stage that lie past the end of the rows come from zeros.
     // A stage index past the end re-issues the last stage (into a slot nobody reads again): the loop body has no branches
     // and the number of loads in flight at each wait is fixed.
     auto issue_stage = [&](int h_unclamped) {
-        const int h = min(h_unclamped, n_st - 1);
+        const int h = h_first + min(h_unclamped, n_st - 1);
         unsigned char* stage = smem + (h_unclamped % NS) * STAGE + 1024 * wv;
         const unsigned char* xs = xbase + (size_t)h * SLAB;
         const unsigned char* ws = wbase + (size_t)h * SLAB;
@@ -268,6 +306,26 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
 #pragma unroll
                 for (int j = 0; j < TN; ++j) mma_block(acc[i][j], a[kk & 1][i], b[kk & 1][j]);
         }
+    }
+
+    // One part of several: the partial sums of the tile, stored neuron s in column s of this part's [B][n_active] array
+    // (bias, ablated columns and the sum over the parts belong to k_sum_parts).
+    if (part != nullptr) {
+        float* pz = part + (size_t)blockIdx.y * B * n_active;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+            if (col >= n_active) continue;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                    if (m < B) pz[(size_t)m * n_active + col] = acc[i][j][e];
+                }
+            }
+        }
+        return;
     }
 
     // Epilogue without an active list: stored neuron s is column s; every lane writes its accumulators where they belong
@@ -345,7 +403,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_structured_gemm(const T* __r
 
 template <typename T, int BM, int BN, int WGM, int WGN, int NS, int SLAB, bool RAGGED>
 static srigl_status launch_gemm_r(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active, const float* bias,
-                                int d_out, float* y, hipStream_t st) {
+                                int d_out, float* y, int splits, float* part, hipStream_t st) {
     auto kern = k_structured_gemm<T, BM, BN, WGM, WGN, NS, SLAB, RAGGED>;
     constexpr size_t ring = (size_t)NS * (BM + BN) * SLAB, epi = EpiLayout<BM, BN, WGM>::BYTES;
     constexpr size_t lds = ring > epi ? ring : epi;
@@ -355,19 +413,28 @@ static srigl_status launch_gemm_r(const void* x, int B, int d_in, const void* Wd
     const long long tiles_m = (B + BM - 1) / BM, tiles_n = (n_active + BN - 1) / BN;
     const long long n_wg = ((tiles_m * tiles_n + kXcds - 1) / kXcds) * kXcds;   // 8 equal runs of tiles, one per XCD
     if (n_wg > 0x7fffffffLL) return SRIGL_ERR_UNSUPPORTED;
-    const dim3 grid((unsigned)n_wg);
+    // every part holds at least one stage
+    if (splits < 1 || splits > 65535 || (splits > 1 && (part == nullptr || splits > (d_in * (int)sizeof(T) + SLAB - 1) / SLAB)))
+        return SRIGL_ERR_INVALID_ARG;
+    if (splits > 1 && B > 65535) return SRIGL_ERR_UNSUPPORTED;   // the sum's grid has one row of workgroups per batch row
+    const dim3 grid((unsigned)n_wg, (unsigned)splits);
     // a lane addresses its rows with 32-bit byte offsets from the tile's first row
     if ((long long)(BM > BN ? BM : BN) * d_in * (long long)sizeof(T) >= (1ll << 31)) return SRIGL_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), lds, st, (const T*)x, B, d_in, (const T*)Wd, active, n_active, bias, d_out, y);
+    hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), lds, st, (const T*)x, B, d_in, (const T*)Wd, active, n_active, bias, d_out, y,
+                       splits, splits > 1 ? part : nullptr);
+    if (splits > 1) {
+        hipLaunchKernelGGL(k_sum_parts, dim3((unsigned)(n_active / 256 + 1), (unsigned)B), dim3(256), 0, st, part, splits, B, n_active, active,
+                           bias, d_out, y);
+    }
     return hip_ok(hipGetLastError());
 }
 
 template <typename T, int BM, int BN, int WGM, int WGN, int NS, int SLAB>
 static srigl_status launch_gemm(const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active, const float* bias,
-                                int d_out, float* y, hipStream_t st) {
+                                int d_out, float* y, int splits, float* part, hipStream_t st) {
     if (d_in % (SLAB / (int)sizeof(T)) == 0)
-        return launch_gemm_r<T, BM, BN, WGM, WGN, NS, SLAB, false>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-    return launch_gemm_r<T, BM, BN, WGM, WGN, NS, SLAB, true>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        return launch_gemm_r<T, BM, BN, WGM, WGN, NS, SLAB, false>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+    return launch_gemm_r<T, BM, BN, WGM, WGN, NS, SLAB, true>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
 }
 
 // Tile choice and time estimate: a workgroup needs about ns_per_k nanoseconds per element of d_in for its tile (measured on
@@ -395,17 +462,56 @@ static srigl_gemm_tile choose_tile(int B, int n_active, bool f32, double* ns_per
     return best;
 }
 
+// The same choice with d_in cut into parts (the parts' tiles run side by side; their partial sums pass through a workspace
+// and a second launch adds them): worth it when the tiles alone reach a fraction of the 256 compute units.  Parts: as many
+// as keep the workgroups (8 runs of tiles, padded) within 256, or within 480 for 64x64 tiles, two of which share a compute
+// unit and then run about 1.6 times longer each; at most 16, at least 4 stages of 128 bytes each.  Measured on MI355X
+// (3072 -> 768 fp32, 538 stored neurons): batch 256 88 us in one part, 21 us in 12; batch 64 69 us and 12 us in 16.
+static void choose_tile_and_split(int B, int n_active, int d_in, int d_out, bool f32, srigl_gemm_tile* tile_out, int* splits_out,
+                                  double* est_us_out) {
+    const int stages = (d_in * (f32 ? 4 : 2) + kSlabBytes - 1) / kSlabBytes;
+    srigl_gemm_tile best = SRIGL_TILE_64x64;
+    int best_s = 1;
+    double best_us = 0.0;
+    for (const TileModel& m : kTileModels) {
+        const long long tiles = (long long)((B + m.bm - 1) / m.bm) * ((n_active + m.bn - 1) / m.bn);
+        const long long padded = (tiles + kXcds - 1) / kXcds * kXcds;
+        const long long wg_cap = m.bm == 64 ? 480 : 256;
+        int cap = stages / 4 < kMaxSplits ? stages / 4 : kMaxSplits;
+        if (cap < 1) cap = 1;
+        int s = padded >= wg_cap ? 1 : (int)(wg_cap / padded);
+        s = s > cap ? cap : s;
+        for (int pass = 0; pass < 2; ++pass) {   // one part, then several
+            if (pass == 1 && s == 1) break;
+            double us;
+            if (pass == 0) {
+                const long long rounds = (tiles + 255) / 256;
+                const double ns_k = f32 ? (rounds == 1 ? m.ns_per_k_f32_single_round : m.ns_per_k_f32) : m.ns_per_k_bf16;
+                us = (double)rounds * ns_k * d_in * 1e-3;
+            } else {
+                const double ns_k = f32 ? m.ns_per_k_f32 : m.ns_per_k_bf16;
+                const double crowd = (m.bm == 64 && padded * s > 256) ? 1.6 : 1.0;
+                us = 7.0 + ns_k * crowd * d_in / s * 1e-3;   // 7.0: the second launch and a second pipeline fill
+            }
+            if (best_us == 0.0 || us < best_us) { best_us = us; best = m.tile; best_s = pass == 0 ? 1 : s; }
+        }
+    }
+    if (tile_out) *tile_out = best;
+    if (splits_out) *splits_out = best_s;
+    if (est_us_out) *est_us_out = 3.5 + best_us + 4.0 * (double)B * d_out / 4.5e6;
+}
+
 template <typename T>
 static srigl_status launch_structured(int tile, const void* x, int B, int d_in, const void* Wd, const int32_t* active, int n_active,
-                                      const float* bias, int d_out, float* y, hipStream_t st) {
+                                      const float* bias, int d_out, float* y, int splits, float* part, hipStream_t st) {
     if (tile == SRIGL_TILE_AUTO) tile = choose_tile(B, n_active, sizeof(T) == 4);
     switch (tile) {
-        case SRIGL_TILE_256x256: return launch_gemm<T, 256, 256, 2, 4, 2, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_256x256_H: return launch_gemm<T, 256, 256, 2, 4, 5, 64>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_256x128_W4: return launch_gemm<T, 256, 128, 2, 2, 3, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_256x128: return launch_gemm<T, 256, 128, 4, 2, 3, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_128x128: return launch_gemm<T, 128, 128, 2, 2, 4, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-        case SRIGL_TILE_64x64: return launch_gemm<T, 64, 64, 2, 2, 4, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+        case SRIGL_TILE_256x256: return launch_gemm<T, 256, 256, 2, 4, 2, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+        case SRIGL_TILE_256x256_H: return launch_gemm<T, 256, 256, 2, 4, 5, 64>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+        case SRIGL_TILE_256x128_W4: return launch_gemm<T, 256, 128, 2, 2, 3, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+        case SRIGL_TILE_256x128: return launch_gemm<T, 256, 128, 4, 2, 3, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+        case SRIGL_TILE_128x128: return launch_gemm<T, 128, 128, 2, 2, 4, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+        case SRIGL_TILE_64x64: return launch_gemm<T, 64, 64, 2, 2, 4, 128>(x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
         default: return SRIGL_ERR_INVALID_ARG;
     }
 }
@@ -450,31 +556,31 @@ srigl_status srigl_densify(const void* W_c, srigl_dtype w_dtype, const int32_t* 
 // Estimates in microseconds, calibrated on MI355X measurements of both forms (fp32 and bf16 storage, batches 1..2048,
 // 512- to 4096-wide layers, 80-99 % sparsity):
 //   condensed  = the estimate of the forward kernel the library's own choice takes for these sizes (condensed_estimate_us)
-//   structured ~ 3.5 + d_in x (rounds of tiles x nanoseconds per element of d_in of the chosen tile) / 1000
+//   structured ~ 3.5 + d_in x (rounds of tiles x nanoseconds per element of d_in of the chosen tile) / 1000 / parts of d_in
+//                  + the second launch when d_in is cut into parts (srigl_structured_linear_fwd_split)
 //                  + 4 B d_out / 4.5e6              (writing the result at HBM speed)
 srigl_representation srigl_choose_representation(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out,
                                                  srigl_dtype dtype, float* est_condensed_us, float* est_structured_us) {
-    const double b = B > 0 ? B : 0;
     const double cond = condensed_estimate_us(B, d_in, n_active, K, d_out, dtype == SRIGL_BF16, n_active < d_out);
-    double ns_per_k = 0.0;
     const bool f32 = dtype == SRIGL_F32;
-    choose_tile(B > 0 ? B : 1, n_active > 0 ? n_active : 1, f32, &ns_per_k);
     const int elem = f32 ? 4 : 2;
-    double stru = 3.5 + ns_per_k * d_in * 1e-3 + 4.0 * b * d_out / 4.5e6;
+    double stru = 0.0;
+    choose_tile_and_split(B > 0 ? B : 1, n_active > 0 ? n_active : 1, d_in, d_out, f32, nullptr, nullptr, &stru);
     if ((d_in * elem) % 16 != 0) stru = 1e30;   // the matrix-core kernel needs rows of whole 16-byte pieces
     if (est_condensed_us) *est_condensed_us = (float)cond;
     if (est_structured_us) *est_structured_us = (float)stru;
     return stru < cond ? SRIGL_REPR_STRUCTURED : SRIGL_REPR_CONDENSED;
 }
 
-srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
-                                              srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
-                                              const float* bias, int32_t d_out, float* y, srigl_gemm_tile tile, void* stream) {
+static srigl_status structured_core(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd, srigl_dtype w_dtype,
+                                    const int32_t* active, int32_t n_active, const float* bias, int32_t d_out, float* y, int tile,
+                                    int splits, void* workspace, size_t workspace_bytes, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (B < 0 || d_in < 0 || n_active < 0 || d_out < 0 || n_active > d_out) return SRIGL_ERR_INVALID_ARG;
     if ((x_dtype != SRIGL_F32 && x_dtype != SRIGL_BF16) || (w_dtype != SRIGL_F32 && w_dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
     if (x_dtype != w_dtype) return SRIGL_ERR_UNSUPPORTED;
     if (active == nullptr && n_active != d_out && n_active != 0) return SRIGL_ERR_INVALID_ARG;
+    if (splits < 0 || splits > kMaxSplits) return SRIGL_ERR_INVALID_ARG;
     if (B == 0 || d_out == 0) return SRIGL_OK;
     if (y == nullptr) return SRIGL_ERR_INVALID_ARG;
     if (n_active > 0 && d_in > 0 && (x == nullptr || Wd == nullptr)) return SRIGL_ERR_INVALID_ARG;
@@ -489,14 +595,48 @@ srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype
         hipLaunchKernelGGL(k_fill_ablated, grid, dim3(256), 0, st, active, n_active, bias, B, d_out, y);
         return hip_ok(hipGetLastError());
     }
-    if (x_dtype == SRIGL_F32) return launch_structured<float>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
-    return launch_structured<uint16_t>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, st);
+    if (splits == 0) {   // the library's choice of parts (and of the tile, unless forced)
+        srigl_gemm_tile t = SRIGL_TILE_AUTO;
+        choose_tile_and_split(B, n_active, d_in, d_out, x_dtype == SRIGL_F32, &t, &splits, nullptr);
+        if (tile != SRIGL_TILE_AUTO) splits = 1;   // a forced tile keeps the whole of d_in unless the parts are forced too
+        else tile = t;
+    }
+    if (splits > 1) {
+        const size_t need = (size_t)splits * B * n_active * sizeof(float);
+        if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 3) != 0) return SRIGL_ERR_CAPACITY;
+    }
+    float* part = static_cast<float*>(workspace);
+    if (x_dtype == SRIGL_F32) return launch_structured<float>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+    return launch_structured<uint16_t>(tile, x, B, d_in, Wd, active, n_active, bias, d_out, y, splits, part, st);
+}
+
+srigl_status srigl_structured_linear_fwd_tile(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
+                                              srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
+                                              const float* bias, int32_t d_out, float* y, srigl_gemm_tile tile, void* stream) {
+    return structured_core(x, x_dtype, B, d_in, Wd, w_dtype, active, n_active, bias, d_out, y, tile, 1, nullptr, 0, stream);
 }
 
 srigl_status srigl_structured_linear_fwd(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
                                          srigl_dtype w_dtype, const int32_t* active, int32_t n_active,
                                          const float* bias, int32_t d_out, float* y, void* stream) {
-    return srigl_structured_linear_fwd_tile(x, x_dtype, B, d_in, Wd, w_dtype, active, n_active, bias, d_out, y, SRIGL_TILE_AUTO, stream);
+    return structured_core(x, x_dtype, B, d_in, Wd, w_dtype, active, n_active, bias, d_out, y, SRIGL_TILE_AUTO, 1, nullptr, 0, stream);
+}
+
+srigl_status srigl_structured_split_plan(int32_t B, int32_t d_in, int32_t n_active, int32_t d_out, srigl_dtype dtype, int32_t* splits,
+                                         size_t* workspace_bytes) {
+    if (B < 0 || d_in < 0 || n_active < 0 || d_out < 0 || (dtype != SRIGL_F32 && dtype != SRIGL_BF16)) return SRIGL_ERR_INVALID_ARG;
+    int s = 1;
+    if (B > 0 && d_in > 0 && n_active > 0) choose_tile_and_split(B, n_active, d_in, d_out, dtype == SRIGL_F32, nullptr, &s, nullptr);
+    if (splits) *splits = s;
+    if (workspace_bytes) *workspace_bytes = s > 1 ? (size_t)s * B * n_active * sizeof(float) : 0;
+    return SRIGL_OK;
+}
+
+srigl_status srigl_structured_linear_fwd_split(const void* x, srigl_dtype x_dtype, int32_t B, int32_t d_in, const void* Wd,
+                                               srigl_dtype w_dtype, const int32_t* active, int32_t n_active, const float* bias,
+                                               int32_t d_out, float* y, srigl_gemm_tile tile, int32_t splits, void* workspace,
+                                               size_t workspace_bytes, void* stream) {
+    return structured_core(x, x_dtype, B, d_in, Wd, w_dtype, active, n_active, bias, d_out, y, tile, splits, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

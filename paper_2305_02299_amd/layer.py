@@ -25,6 +25,7 @@ class CondensedLinear:
     Wd: torch.Tensor | None = None   # dense rows of the stored neurons (structured-only form), built on first use
     idx_wide: torch.Tensor | None = None   # the int32 indices when idx holds the 16-bit copy
     packed: torch.Tensor | None = None     # the streaming copy of W_c / idx (bytes), read by the kernels that can stream it
+    split_ws: torch.Tensor | None = None   # partial sums of the structured-only product when it cuts d_in into parts (grown on demand)
 
     def narrow(self) -> "CondensedLinear":
         """The same layer with 16-bit column indices (d_in <= 65536); weights, active, bias and seg are shared."""
@@ -54,7 +55,11 @@ class CondensedLinear:
         if representation == "auto":
             representation = "structured" if self.choose(Bn) == B_.REPR_STRUCTURED else "condensed"
         if representation == "structured":
-            B_.srigl_structured_linear_fwd(x, Bn, self.d_in, self.dense_rows(), self.active, self.n_active, self.bias, self.d_out, y)
+            _, need = B_.srigl_structured_split_plan(Bn, self.d_in, self.n_active, self.d_out, B_._dtype_code(self.W_c))
+            if need and (self.split_ws is None or self.split_ws.numel() < need):
+                self.split_ws = torch.empty((need,), dtype=torch.uint8, device=x.device)
+            B_.srigl_structured_linear_fwd_split(x, Bn, self.d_in, self.dense_rows(), self.active, self.n_active, self.bias, self.d_out, y,
+                                                 self.split_ws if need else None)
             return y
         assert representation == "condensed"
         B_.srigl_condensed_linear_fwd(x, Bn, self.d_in, self.W_c, self.idx, self.active, self.n_active, self.K, self.bias,

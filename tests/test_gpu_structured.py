@@ -17,7 +17,7 @@ def B_():
     return binding
 
 
-def run_case(B_, L, tol, tile=None):
+def run_case(B_, L, tol, tile=None, splits=None):
     W_c, idx, active = oracle_condensed(L)
     n, K = W_c.shape
     x = L.x_bf16 if L.dtype == "bf16" else L.x
@@ -31,7 +31,12 @@ def run_case(B_, L, tol, tile=None):
     assert np.array_equal(got_Wd.view(np.uint16 if L.dtype == "bf16" else np.uint32),
                           Wd_ref.view(np.uint16 if L.dtype == "bf16" else np.uint32))
     y = torch.full((L.B, L.d_out), float("nan"), device="cuda")
-    B_.srigl_structured_linear_fwd(dev(x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y, tile=tile)
+    if splits is None:
+        B_.srigl_structured_linear_fwd(dev(x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y, tile=tile)
+    else:   # d_in cut into parts (0: as many as the library would take); the partial sums start as NaN
+        parts = splits or B_.srigl_structured_split_plan(L.B, L.d_in, n, L.d_out, B_.BF16 if L.dtype == "bf16" else B_.F32)[0]
+        ws = torch.full((max(parts * L.B * n, 1),), float("nan"), device="cuda") if parts > 1 else None
+        B_.srigl_structured_linear_fwd_split(dev(x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y, ws, splits=splits, tile=tile)
     torch.cuda.synchronize()
     y_ref = oracle.structured_fwd(x, Wd_ref, active, L.bias, L.d_out)
     _, S = oracle.fwd(x, W_c, idx, active, L.bias, L.d_out, want_scale=True)
@@ -74,6 +79,53 @@ def test_every_tile_shape(B_, tile, dtype):
     for (d_in, d_out, K, B, abl) in [(520, 700, 52, 300, 0.2), (40, 97, 4, 33, 0.0), (136, 513, 14, 257, 0.4)]:
         L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=d_in + 3 * B)
         run_case(B_, L, tol, tile=B_.TILES[tile])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("splits", [2, 3, 7, 16])
+def test_d_in_cut_into_parts(B_, dtype, splits):
+    """Forced numbers of parts on the smallest and one larger tile: ragged edges in all three dimensions, parts of unequal
+    numbers of stages, a last stage that is cut short by the row end, with and without ablated neurons."""
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    for (d_in, d_out, K, B, abl) in [(1040, 300, 52, 130, 0.2), (2048, 97, 64, 33, 0.0), (1096, 513, 14, 70, 0.4)]:
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, dtype=dtype, seed=d_in + 3 * B + splits)
+        run_case(B_, L, tol, tile=B_.TILES["64x64"], splits=splits)
+        run_case(B_, L, tol, tile=B_.TILES["128x128"], splits=splits)
+
+
+@pytest.mark.parametrize("name,B", [("c3", 256), ("c3", 64), ("c2", 16), ("c1", 1)])
+def test_library_choice_of_parts(B_, name, B):
+    """The plan's own number of parts on the named layers (the wide layer with few stored neurons is the case it exists for)."""
+    L = si.config(name, B=B)
+    W_c, _, _ = oracle_condensed(L)
+    parts, need = B_.srigl_structured_split_plan(B, L.d_in, W_c.shape[0], L.d_out, B_.F32)
+    assert (parts > 1) == (need > 0) and need == (parts * B * W_c.shape[0] * 4 if parts > 1 else 0)
+    if name == "c3":
+        assert parts > 1
+    run_case(B_, L, TOL_F32, splits=0)
+
+
+def test_parts_argument_errors(B_):
+    from paper_2305_02299_amd.binding import SriglError
+    L = si.make_layer(256, 64, 8, 16, seed=3)
+    W_c, idx, active = oracle.condense(L.W, L.mask, L.K)
+    n = len(active)
+    Wd = dev(oracle.densify(W_c, idx, L.d_in))
+    y = torch.empty((L.B, L.d_out), device="cuda")
+    args = (dev(L.x), L.B, L.d_in, Wd, dev(active), n, dev(L.bias), L.d_out, y)
+    ws = torch.empty((4 * L.B * n,), device="cuda")
+    with pytest.raises(SriglError) as e:     # workspace of 4 parts offered for 8
+        B_.srigl_structured_linear_fwd_split(*args, ws, splits=8, tile=B_.TILES["64x64"])
+    assert e.value.status == B_.ERR_CAPACITY
+    with pytest.raises(SriglError) as e:     # no workspace at all
+        B_.srigl_structured_linear_fwd_split(*args, None, splits=2, tile=B_.TILES["64x64"])
+    assert e.value.status == B_.ERR_CAPACITY
+    with pytest.raises(SriglError) as e:     # 256 fp32 columns are 8 stages of 128 bytes: 16 parts would leave empty ones
+        B_.srigl_structured_linear_fwd_split(*args, torch.empty((16 * L.B * n,), device="cuda"), splits=16, tile=B_.TILES["64x64"])
+    assert e.value.status == B_.ERR_INVALID_ARG
+    with pytest.raises(SriglError):
+        B_.srigl_structured_linear_fwd_split(*args, ws, splits=17)
+    B_.srigl_structured_linear_fwd_split(*args, ws, splits=4, tile=B_.TILES["64x64"])   # the same call with a workspace that fits
 
 
 def test_integer_inputs_bit_exact(B_):

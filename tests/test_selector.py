@@ -53,3 +53,23 @@ def test_rows_that_are_not_whole_16_byte_pieces_stay_condensed(B_):
     assert r == B_.REPR_CONDENSED
     r, c, s = B_.srigl_choose_representation(4096, 772, 3072, 385, 3072, B_.BF16)
     assert r == B_.REPR_CONDENSED
+
+
+def test_parts_of_d_in_for_the_structured_only_product(B_):
+    """Host-only plan: a wide fp32 layer with few stored neurons at a modest batch is cut into parts (its tiles alone reach a
+    fraction of the compute units); a product with thousands of tiles is not; the workspace is parts x B x n_active floats."""
+    L = si.config("c3", B=256)
+    n = 538
+    parts, need = B_.srigl_structured_split_plan(256, L.d_in, n, L.d_out, B_.F32)
+    assert 2 <= parts <= 16 and need == parts * 256 * n * 4
+    L5 = si.config("c5")
+    assert B_.srigl_structured_split_plan(L5.B, L5.d_in, 13108, L5.d_out, B_.BF16) == (1, 0)
+    # every part keeps at least four stages of 128 bytes: 64 fp32 columns are two stages, so one part
+    assert B_.srigl_structured_split_plan(16, 64, 64, 64, B_.F32) == (1, 0)
+    for (B, d_in, n_active) in [(1, 768, 3072), (64, 3072, 538), (300, 1024, 96), (2048, 4096, 100)]:
+        for dt in (B_.F32, B_.BF16):
+            parts, need = B_.srigl_structured_split_plan(B, d_in, n_active, n_active, dt)
+            stages = (d_in * (4 if dt == B_.F32 else 2) + 127) // 128
+            assert 1 <= parts <= max(1, min(16, stages // 4))
+            assert need == (parts * B * n_active * 4 if parts > 1 else 0)
+    assert B_.srigl_structured_split_plan(0, 768, 0, 3072, B_.F32) == (1, 0)
