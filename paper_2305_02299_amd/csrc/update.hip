@@ -29,16 +29,17 @@ struct SelState {
 // 2 = smallest kept weights of the remaining neurons.  Pass p of a walk adds into hist[sel][p]; the launch of pass p + 1
 // reads it (every workgroup picks the byte of pass p for itself), so no launch reads and clears the same counters, and no
 // device-wide fence is needed (on this multi-die GPU such a fence costs about 0.1 ms per launch).
-// slot[sel][p & 1] = the walk's state before pass p (written by workgroup 0 of the launch of pass p, read by the next launch);
-// fin[sel] = the finished selection: select key >= fin.prefix.
+// slot[sel][p & 1] = the walk's state before pass p (written by workgroup 0 of the launch of pass p, read by the next launch).
+// The launch after a walk's eighth pass takes the last digit for itself (finished_walk): select key >= its prefix.
 // Copies of every layer-wide histogram: a pass ends with one atomic per non-empty digit and workgroup, and 2048 workgroups
-// adding to the same 256 counters took longer than reading a 2.4-million-element layer (43 us of a 167 us update).
-constexpr int kHistCopies = 8;
+// adding to the same 256 counters took longer than reading a 2.4-million-element layer (43 us of a 167 us update).  Every
+// workgroup of the next pass reads all copies, which costs too: 4 copies measured best (1, 2, 8: 2-5 % slower; 32: 50 %).
+constexpr int kHistCopies = 4;
 struct UpdateScratch {
     unsigned int hist[3][8][kHistCopies][256];   // workgroup w adds into copy w % kHistCopies
     SelState slot[3][2];
-    SelState fin[3];
-    long long k_new, n_remaining, n_ablated_now, n_pruned;
+    SelState fin[2];                    // the finished selections of step 3 (written by k_row_salient for the launches after it)
+    unsigned int cnt_remaining[kHistCopies], cnt_ablated[kHistCopies];   // steps 4-5: neurons that stay / are ablated now (sums of the copies)
     unsigned long long cand_count[3];   // keys in the selection's candidate list; above the capacity: the list is not valid
 };
 
@@ -69,9 +70,10 @@ __global__ __launch_bounds__(256) void k_update_init(UpdateScratch* s, long long
         z.prefix = 0; z.k_rem = (unsigned long long)K_upd; z.total = 0; z.done = 0; z.pad = 0;
         s->slot[t][0] = z;
         s->slot[t][1] = z;
-        s->fin[t] = z;
+        if (t < 2) s->fin[t] = z;
         s->cand_count[t] = 0;
     }
+    if (blockIdx.x == 0 && t < kHistCopies) { s->cnt_remaining[t] = 0; s->cnt_ablated[t] = 0; }
 }
 
 // From a 256-bin histogram (lane l reads bins 4l .. 4l + 3), for one wavefront: the byte d with suffix(d) >= want >
@@ -111,24 +113,31 @@ __device__ __forceinline__ void pick_from(const unsigned long long (&v)[4], unsi
 // turn of kCopyTurn puts equal digits of different copies in different banks)
 constexpr int kCopyTurn = 16;
 template <int COPIES, int TURN>
-__device__ __forceinline__ void pick_byte_copies(const unsigned int (*h)[256], unsigned long long want, int lane, unsigned long long& digit,
-                                                 unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
-    unsigned long long v[4] = {0, 0, 0, 0};
+__device__ __forceinline__ void sum_byte_copies(const unsigned int (*h)[256], int lane, unsigned long long (&v)[4]) {
+    v[0] = v[1] = v[2] = v[3] = 0;
 #pragma unroll
     for (int c = 0; c < COPIES; ++c) {
         const uint4 q = *reinterpret_cast<const uint4*>(&h[c][(4 * lane + TURN * c) & 255]);
         v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
     }
+}
+template <int COPIES, int TURN>
+__device__ __forceinline__ void pick_byte_copies(const unsigned int (*h)[256], unsigned long long want, int lane, unsigned long long& digit,
+                                                 unsigned long long& above, unsigned long long& in_bin, unsigned long long& total) {
+    unsigned long long v[4];
+    sum_byte_copies<COPIES, TURN>(h, lane, v);
     pick_from(v, want, lane, digit, above, in_bin, total);
 }
 
 // The state of a layer-wide walk before pass `pass` (1..8), from the state before pass - 1 and the histogram of pass - 1.
 // Called by one whole wavefront; the result is the same on every lane.
-__device__ SelState advance(const SelState& before, const unsigned int (*hist_prev)[256], int pass, int lane) {
+// advance_from: with the counters of pass - 1 already summed (lane l holds digits 4l .. 4l + 3); advance requests them
+// before the state is looked at, so that the two reads from memory do not wait for each other.
+__device__ SelState advance_from(const SelState& before, const unsigned long long (&v)[4], int pass, int lane) {
     SelState st = before;
     if (st.done) return st;
     unsigned long long digit, above, in_bin, total;
-    pick_byte_copies<kHistCopies, 0>(hist_prev, st.k_rem == 0 ? 1 : st.k_rem, lane, digit, above, in_bin, total);
+    pick_from(v, st.k_rem == 0 ? 1 : st.k_rem, lane, digit, above, in_bin, total);
     if (pass == 1) {
         st.total = total;
         if (st.k_rem == 0 || total < st.k_rem) {
@@ -147,6 +156,23 @@ __device__ SelState advance(const SelState& before, const unsigned int (*hist_pr
     }
     return st;
 }
+__device__ SelState advance(const SelState& before, const unsigned int (*hist_prev)[256], int pass, int lane) {
+    unsigned long long v[4];
+    sum_byte_copies<kHistCopies, 0>(hist_prev, lane, v);
+    return advance_from(before, v, pass, lane);
+}
+
+// The finished selection `sel` for the launch that follows its eighth pass: the last digit from that pass's counters.
+// Called by one whole wavefront; the result is the same on every lane.
+__device__ __forceinline__ SelState finished_walk(const UpdateScratch* __restrict__ s, int sel, int lane) {
+    return advance(s->slot[sel][1], s->hist[sel][7], 8, lane);
+}
+__device__ __forceinline__ unsigned int sum_copies(const unsigned int (&c)[kHistCopies]) {
+    unsigned int n = 0;
+#pragma unroll
+    for (int i = 0; i < kHistCopies; ++i) n += c[i];
+    return n;
+}
 
 // One pass of the walk.  PAIR: selections 0 (kept weights, smallest first) and 1 (pruned positions, largest gradient first)
 // together: every element belongs to exactly one of them, so one read of the layer serves both.  Otherwise selection 2
@@ -158,8 +184,9 @@ __device__ SelState advance(const SelState& before, const unsigned int (*hist_pr
 // and two 16-byte loads that do not wait for each other (a line of W or grad is fetched for almost every run of 32 elements
 // anyway, so reading both arrays in full costs no extra traffic).
 constexpr int kCopies = 8;
+constexpr int kPassThreads = 256;   // threads per workgroup of a layer-wide pass (512 and 1024 measured no faster)
 template <bool PAIR, bool COMPACT, bool VEC>
-__global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W, const uint8_t* __restrict__ mask,
+__global__ __launch_bounds__(kPassThreads) void k_layer_hist(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, const int* __restrict__ remains, unsigned int N,
                                                     int d_in, int pass, UpdateScratch* __restrict__ s,
                                                     unsigned long long* __restrict__ candA, unsigned long long* __restrict__ candB,
@@ -171,16 +198,17 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
     __shared__ unsigned long long keep_base[2];
     const int t = threadIdx.x;
     const int selA = PAIR ? 0 : 2;
-    // walks that had ended before the previous pass: nothing to count (every thread reads the two flags for itself)
-    if (pass > 0 && s->slot[selA][(pass + 1) & 1].done != 0 && (!PAIR || s->slot[1][(pass + 1) & 1].done != 0)) {
+    const SelState before_a = s->slot[selA][(pass + 1) & 1], before_b = s->slot[1][(pass + 1) & 1];
+    // walks that had ended before the previous pass: nothing to count
+    if (pass > 0 && before_a.done != 0 && (!PAIR || before_b.done != 0)) {
         if (blockIdx.x == 0 && t == 0) {
-            s->slot[selA][pass & 1] = s->slot[selA][(pass + 1) & 1];
-            if (PAIR) s->slot[1][pass & 1] = s->slot[1][(pass + 1) & 1];
+            s->slot[selA][pass & 1] = before_a;
+            if (PAIR) s->slot[1][pass & 1] = before_b;
         }
         return;
     }
     if (t < 64) {
-        SelState a = s->slot[selA][(pass + 1) & 1], b = s->slot[1][(pass + 1) & 1];   // the states before pass - 1
+        SelState a = before_a, b = before_b;
         if (pass > 0) {
             a = advance(a, s->hist[selA][pass - 1], pass, t);
             if (PAIR) b = advance(b, s->hist[1][pass - 1], pass, t);
@@ -191,10 +219,15 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
         } else {
             a = s->slot[selA][0];
             b = s->slot[1][0];
+            // step 6 with no neuron ablated in step 4: same candidates, same count, so step 3's walk already has the answer
+            if (!PAIR && sum_copies(s->cnt_ablated) == 0) {
+                a = s->fin[0];
+                if (blockIdx.x == 0 && t == 0) s->slot[2][0] = a;
+            }
         }
         if (t == 0) { cur[0] = a; cur[1] = b; }
     }
-    for (int i = t; i < 2 * kCopies * 256; i += 256) (&h[0][0][0])[i] = 0;
+    for (int i = t; i < 2 * kCopies * 256; i += kPassThreads) (&h[0][0][0])[i] = 0;
     if (t < 2) keep_n[t] = 0;
     __syncthreads();
     const bool doneA = cur[0].done != 0, doneB = PAIR ? cur[1].done != 0 : true;
@@ -231,7 +264,7 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
     };
     if ((scanA || scanB) && VEC) {
         const unsigned int N4 = N / 4;   // d_in is a multiple of 4, so N is, and a run of 4 stays inside one row
-        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < N4; i += (unsigned long long)gridDim.x * 256) {
+        for (unsigned long long i = (unsigned long long)blockIdx.x * kPassThreads + t; i < N4; i += (unsigned long long)gridDim.x * kPassThreads) {
             const unsigned int base = 4u * (unsigned int)i;
             const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + base);
             float4 w4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), g4 = w4;
@@ -244,7 +277,7 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
             element(base + 3, m4 >> 24, w4.w, g4.w, rem);
         }
     } else if (scanA || scanB) {
-        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < N; i += (unsigned long long)gridDim.x * 256) {
+        for (unsigned long long i = (unsigned long long)blockIdx.x * kPassThreads + t; i < N; i += (unsigned long long)gridDim.x * kPassThreads) {
             const unsigned int ii = (unsigned int)i;
             const unsigned int m = mask[ii];
             if (m != 0) {
@@ -255,23 +288,25 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
         }
     }
     if (!doneA && listA) {
-        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < countA; i += (unsigned long long)gridDim.x * 256) {
+        for (unsigned long long i = (unsigned long long)blockIdx.x * kPassThreads + t; i < countA; i += (unsigned long long)gridDim.x * kPassThreads) {
             const unsigned long long key = candA[i];
             if ((key >> pshift) == prefixA) atomicAdd(&h[0][copy][(unsigned int)(key >> shift) & dmask], 1u);
         }
     }
     if (PAIR && !doneB && listB) {
-        for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + t; i < countB; i += (unsigned long long)gridDim.x * 256) {
+        for (unsigned long long i = (unsigned long long)blockIdx.x * kPassThreads + t; i < countB; i += (unsigned long long)gridDim.x * kPassThreads) {
             const unsigned long long key = candB[i];
             if ((key >> pshift) == prefixB) atomicAdd(&h[1][copy][(unsigned int)(key >> shift) & dmask], 1u);
         }
     }
     __syncthreads();
     unsigned int a = 0, b = 0;
+    if (t < 256) {
 #pragma unroll
-    for (int c = 0; c < kCopies; ++c) { a += h[0][c][t]; b += h[1][c][t]; }
-    if (a) atomicAdd(&s->hist[selA][pass][blockIdx.x % kHistCopies][t], a);
-    if (PAIR && b) atomicAdd(&s->hist[1][pass][blockIdx.x % kHistCopies][t], b);
+        for (int c = 0; c < kCopies; ++c) { a += h[0][c][t]; b += h[1][c][t]; }
+        if (a) atomicAdd(&s->hist[selA][pass][blockIdx.x % kHistCopies][t], a);
+        if (PAIR && b) atomicAdd(&s->hist[1][pass][blockIdx.x % kHistCopies][t], b);
+    }
     if (COMPACT) {
         if (t < 2) {
             const unsigned int n = keep_n[t];
@@ -284,34 +319,41 @@ __global__ __launch_bounds__(256) void k_layer_hist(const float* __restrict__ W,
             const unsigned int n = keep_n[q];
             unsigned long long* __restrict__ dst = q == 0 ? candA : candB;
             if (n == 0 || n > (unsigned)kBlockList || keep_base[q] + n > cap) continue;
-            for (unsigned int e = t; e < n; e += 256) dst[keep_base[q] + e] = keep[q][e];
+            for (unsigned int e = t; e < n; e += kPassThreads) dst[keep_base[q] + e] = keep[q][e];
         }
     }
 }
 
-// After the eighth pass: the last digit, and the finished selection.  One wavefront.
-template <bool PAIR>
-__global__ __launch_bounds__(64) void k_layer_finish(UpdateScratch* __restrict__ s) {
-    const int t = threadIdx.x;
-    const int selA = PAIR ? 0 : 2;
-    const SelState a = advance(s->slot[selA][1], s->hist[selA][7], 8, t);
-    if (t == 0) s->fin[selA] = a;
-    if (PAIR) {
-        const SelState b = advance(s->slot[1][1], s->hist[1][7], 8, t);
-        if (t == 0) s->fin[1] = b;
-    }
-}
-
-// Steps 3 and the start of 4: per neuron, how many weights it holds and how many salient ones.  One wavefront per row.
+// Steps 3 to 5 up to the counts: per neuron, how many weights it holds and how many salient ones, whether it stays
+// (remains[r]; a neuron without weights stays ablated), and the layer's numbers of staying and newly ablated neurons (one
+// atomic per workgroup and counter, spread over copies; read by the launches after this one).  One wavefront per row.
 // VEC as in k_layer_hist: a lane takes runs of 4 columns.
 template <bool VEC>
 __global__ __launch_bounds__(256) void k_row_salient(const float* __restrict__ W, const uint8_t* __restrict__ mask,
-                                                     const float* __restrict__ grad, int d_out, int d_in,
-                                                     const UpdateScratch* __restrict__ s, int* __restrict__ held, int* __restrict__ salient) {
+                                                     const float* __restrict__ grad, int d_out, int d_in, int k, int gamma_percent,
+                                                     UpdateScratch* __restrict__ s, int* __restrict__ remains) {
+    __shared__ int wg_stay, wg_ablated;
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= d_out) return;
-    const unsigned long long t_small = s->fin[0].prefix, t_grad = s->fin[1].prefix;
+    if (threadIdx.x == 0) { wg_stay = 0; wg_ablated = 0; }
+    // the row's first kAhead steps are requested before the thresholds are (they do not depend on them)
+    constexpr int kAhead = 4;
+    uint32_t pm[kAhead];
+    float4 pw[kAhead], pg[kAhead];
+    if (VEC && r < d_out) {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int c = 4 * lane + 256 * u;
+            const unsigned int i = (unsigned int)r * d_in + (c < d_in ? c : 0);
+            pm[u] = *reinterpret_cast<const uint32_t*>(mask + i);
+            pw[u] = *reinterpret_cast<const float4*>(W + i);
+            pg[u] = *reinterpret_cast<const float4*>(grad + i);
+        }
+    }
+    const SelState fa = finished_walk(s, 0, lane), fb = finished_walk(s, 1, lane);
+    if (blockIdx.x == 0 && threadIdx.x == 0) { s->fin[0] = fa; s->fin[1] = fb; }
+    __syncthreads();
+    const unsigned long long t_small = fa.prefix, t_grad = fb.prefix;
     int h = 0, sal = 0;
     auto element = [&](unsigned int i, unsigned int m, float w, float g) {
         if (m) {
@@ -321,58 +363,49 @@ __global__ __launch_bounds__(256) void k_row_salient(const float* __restrict__ W
             ++sal;                                                    // would be grown
         }
     };
-    if (VEC) {
-        for (int c = 4 * lane; c < d_in; c += 256) {
-            const unsigned int i = (unsigned int)r * d_in + c;
-            const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + i);
-            const float4 w4 = *reinterpret_cast<const float4*>(W + i);
-            const float4 g4 = *reinterpret_cast<const float4*>(grad + i);
-            element(i + 0, m4 & 0xffu, w4.x, g4.x);
-            element(i + 1, (m4 >> 8) & 0xffu, w4.y, g4.y);
-            element(i + 2, (m4 >> 16) & 0xffu, w4.z, g4.z);
-            element(i + 3, m4 >> 24, w4.w, g4.w);
+    if (r < d_out) {
+        if (VEC) {
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int c = 4 * lane + 256 * u;
+                if (c >= d_in) break;
+                const unsigned int i = (unsigned int)r * d_in + c;
+                element(i + 0, pm[u] & 0xffu, pw[u].x, pg[u].x);
+                element(i + 1, (pm[u] >> 8) & 0xffu, pw[u].y, pg[u].y);
+                element(i + 2, (pm[u] >> 16) & 0xffu, pw[u].z, pg[u].z);
+                element(i + 3, pm[u] >> 24, pw[u].w, pg[u].w);
+            }
+            for (int c = 4 * lane + 256 * kAhead; c < d_in; c += 256) {
+                const unsigned int i = (unsigned int)r * d_in + c;
+                const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + i);
+                const float4 w4 = *reinterpret_cast<const float4*>(W + i);
+                const float4 g4 = *reinterpret_cast<const float4*>(grad + i);
+                element(i + 0, m4 & 0xffu, w4.x, g4.x);
+                element(i + 1, (m4 >> 8) & 0xffu, w4.y, g4.y);
+                element(i + 2, (m4 >> 16) & 0xffu, w4.z, g4.z);
+                element(i + 3, m4 >> 24, w4.w, g4.w);
+            }
+        } else {
+            for (int c = lane; c < d_in; c += 64) {
+                const unsigned int i = (unsigned int)r * d_in + c;
+                const unsigned int m = mask[i];
+                element(i, m, m ? W[i] : 0.0f, m ? 0.0f : grad[i]);
+            }
         }
-    } else {
-        for (int c = lane; c < d_in; c += 64) {
-            const unsigned int i = (unsigned int)r * d_in + c;
-            const unsigned int m = mask[i];
-            element(i, m, m ? W[i] : 0.0f, m ? 0.0f : grad[i]);
+        for (int off = 32; off > 0; off >>= 1) { h += __shfl_xor(h, off, 64); sal += __shfl_xor(sal, off, 64); }
+        if (lane == 0) {
+            int stays = 0;
+            if (h > 0) {
+                const bool too_few = sal < 1 || (long long)sal * 100 < (long long)gamma_percent * k;
+                if (too_few) atomicAdd(&wg_ablated, 1); else { stays = 1; atomicAdd(&wg_stay, 1); }
+            }
+            remains[r] = stays;
         }
     }
-    for (int off = 32; off > 0; off >>= 1) { h += __shfl_xor(h, off, 64); sal += __shfl_xor(sal, off, 64); }
-    if (lane == 0) { held[r] = h; salient[r] = sal; }
-}
-
-// Steps 4 and 5.  One workgroup.
-__global__ __launch_bounds__(1024) void k_decide(const int* __restrict__ held, const int* __restrict__ salient, int d_out, int d_in, int k,
-                                                 int gamma_percent, long long budget, int* __restrict__ remains,
-                                                 UpdateScratch* __restrict__ s) {
-    __shared__ int n_rem, n_abl;
-    if (threadIdx.x == 0) { n_rem = 0; n_abl = 0; }
-    __syncthreads();
-    int rem = 0, abl = 0;
-    for (int r = threadIdx.x; r < d_out; r += blockDim.x) {
-        int stays = 0;
-        if (held[r] > 0) {
-            const long long sal = salient[r];
-            const bool too_few = sal < 1 || sal * 100 < (long long)gamma_percent * k;
-            if (too_few) ++abl; else { stays = 1; ++rem; }
-        }
-        remains[r] = stays;
-    }
-    if (rem) atomicAdd(&n_rem, rem);
-    if (abl) atomicAdd(&n_abl, abl);
     __syncthreads();
     if (threadIdx.x == 0) {
-        long long k_new = n_rem > 0 ? budget / n_rem : 0;
-        if (k_new > d_in) k_new = d_in;
-        s->k_new = k_new;
-        s->n_remaining = n_rem;
-        s->n_ablated_now = n_abl;
-        if (n_abl == 0) {   // same candidates, same count: the walk of step 3 already has the answer
-            s->slot[2][0] = s->fin[0];
-            s->slot[2][1] = s->fin[0];
-        }
+        if (wg_stay) atomicAdd(&s->cnt_remaining[blockIdx.x % kHistCopies], (unsigned int)wg_stay);
+        if (wg_ablated) atomicAdd(&s->cnt_ablated[blockIdx.x % kHistCopies], (unsigned int)wg_ablated);
     }
 }
 
@@ -423,12 +456,44 @@ __device__ unsigned long long row_select(unsigned long long want, KeyOf key_of, 
 template <int CPT, bool VEC>
 __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const float* __restrict__ W, const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ grad, int d_in, const int* __restrict__ remains,
-                                                    const UpdateScratch* __restrict__ s, uint8_t* __restrict__ mask_out,
-                                                    float* __restrict__ W_out) {
+                                                    const UpdateScratch* __restrict__ s, long long K_upd, long long budget,
+                                                    uint8_t* __restrict__ mask_out, float* __restrict__ W_out,
+                                                    long long* __restrict__ report) {
     __shared__ __align__(16) unsigned int h[3][kRowCopies][256];
     __shared__ int n_kept;
+    __shared__ unsigned long long prune_threshold;
     const int r = blockIdx.x, t = threadIdx.x;
     const unsigned int row0 = (unsigned int)r * d_in;
+    // rows of up to 4096 columns: the thread's columns are requested before the selection's state is (neither waits for the other)
+    constexpr bool kEarly = VEC && CPT <= 16;
+    float4 pw[kEarly ? CPT / 4 : 1], pg[kEarly ? CPT / 4 : 1];
+    uint32_t pm[kEarly ? CPT / 4 : 1];
+    if (kEarly) {
+#pragma unroll
+        for (int q = 0; q < CPT / 4; ++q) {
+            const int c0 = 4 * (t + 256 * q);
+            const unsigned int i = row0 + (c0 < d_in ? c0 : 0);
+            pw[q] = *reinterpret_cast<const float4*>(W + i);
+            pg[q] = *reinterpret_cast<const float4*>(grad + i);
+            pm[q] = *reinterpret_cast<const uint32_t*>(mask + i);
+        }
+    }
+    // step 5: the new fan-in from the count of staying neurons; step 6's finished selection (its last digit is taken here)
+    const long long n_remaining = sum_copies(s->cnt_remaining);
+    long long k_new = n_remaining > 0 ? budget / n_remaining : 0;
+    if (k_new > d_in) k_new = d_in;
+    if (t < 64) {
+        const SelState f2 = finished_walk(s, 2, t);
+        if (t == 0) {
+            prune_threshold = f2.prefix;
+            if (r == 0) {
+                report[0] = k_new;
+                report[1] = n_remaining;
+                report[2] = sum_copies(s->cnt_ablated);
+                report[3] = (long long)((unsigned long long)K_upd < f2.total ? (unsigned long long)K_upd : f2.total);
+            }
+        }
+    }
     // column of the thread's j-th element
     auto col_of = [&](int j) { return VEC ? 4 * (t + 256 * (j >> 2)) + (j & 3) : t + 256 * j; };
     if (!remains[r]) {
@@ -442,12 +507,11 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
         }
         return;
     }
-    const unsigned long long t_prune = s->fin[2].prefix;
-    const long long k_new = s->k_new;
     unsigned long long key[CPT];
     unsigned int survives = 0, valid = 0;   // bit j: the thread's j-th column
     if (t == 0) n_kept = 0;
     __syncthreads();
+    const unsigned long long t_prune = prune_threshold;
     auto take = [&](int j, int c, float w, float g, uint8_t m) {
         valid |= 1u << j;
         const unsigned int i = row0 + c;
@@ -466,9 +530,9 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
             const int c0 = 4 * (t + 256 * q);
             if (c0 < d_in) {
                 // all three loads go out at once (the lines are fetched either way)
-                const float4 w4 = *reinterpret_cast<const float4*>(W + row0 + c0);
-                const float4 g4 = *reinterpret_cast<const float4*>(grad + row0 + c0);
-                const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + row0 + c0);
+                const float4 w4 = kEarly ? pw[kEarly ? q : 0] : *reinterpret_cast<const float4*>(W + row0 + c0);
+                const float4 g4 = kEarly ? pg[kEarly ? q : 0] : *reinterpret_cast<const float4*>(grad + row0 + c0);
+                const uint32_t m4 = kEarly ? pm[kEarly ? q : 0] : *reinterpret_cast<const uint32_t*>(mask + row0 + c0);
                 take(4 * q + 0, c0 + 0, w4.x, g4.x, (uint8_t)(m4 & 0xffu));
                 take(4 * q + 1, c0 + 1, w4.y, g4.y, (uint8_t)((m4 >> 8) & 0xffu));
                 take(4 * q + 2, c0 + 2, w4.z, g4.z, (uint8_t)((m4 >> 16) & 0xffu));
@@ -532,14 +596,9 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
     }
 }
 
-__global__ void k_update_report(const UpdateScratch* __restrict__ s, long long K_upd, long long* __restrict__ report) {
-    if (threadIdx.x == 0) {
-        report[0] = s->k_new;
-        report[1] = s->n_remaining;
-        report[2] = s->n_ablated_now;
-        const unsigned long long cand = s->fin[2].total;
-        report[3] = (long long)((unsigned long long)K_upd < cand ? (unsigned long long)K_upd : cand);
-    }
+// A layer without elements: nothing stays, nothing is pruned.
+__global__ void k_update_report_empty(long long* __restrict__ report) {
+    if (threadIdx.x < 4) report[threadIdx.x] = 0;
 }
 
 template <bool PAIR>
@@ -549,19 +608,18 @@ static void layer_select(const float* W, const uint8_t* mask, const float* grad,
                      reinterpret_cast<uintptr_t>(mask) % 4 == 0;
     // a thread takes 1 or 4 elements per step and at least 8 steps (every workgroup ends with up to 512 atomics), at most
     // four workgroups per compute unit
-    const unsigned int per_step = vec ? 1024u : 256u;
+    const unsigned int per_step = (vec ? 4u : 1u) * kPassThreads;
     unsigned int blocks = (N / 8 + per_step - 1) / per_step;
     if (blocks > 1024) blocks = 1024;
     if (blocks == 0) blocks = 1;
 #define SRIGL_HIST(COMPACT, VEC)                                                                                                   \
-    hipLaunchKernelGGL((k_layer_hist<PAIR, COMPACT, VEC>), dim3(blocks), dim3(256), 0, st, W, mask, grad, remains, N, d_in, pass, s, \
+    hipLaunchKernelGGL((k_layer_hist<PAIR, COMPACT, VEC>), dim3(blocks), dim3(kPassThreads), 0, st, W, mask, grad, remains, N, d_in, pass, s, \
                        candA, candB, cap)
     for (int pass = 0; pass < 8; ++pass) {
         if (pass == kCompactPass && cap > 0) { if (vec) SRIGL_HIST(true, true); else SRIGL_HIST(true, false); }
         else { if (vec) SRIGL_HIST(false, true); else SRIGL_HIST(false, false); }
     }
 #undef SRIGL_HIST
-    hipLaunchKernelGGL(k_layer_finish<PAIR>, dim3(1), dim3(64), 0, st, s);
 }
 
 // Keys per candidate list: a sixteenth of the layer, at least 4096 (a list holds the keys that share 16 leading bits with
@@ -573,7 +631,7 @@ static size_t cand_capacity(int32_t d_out, int32_t d_in) {
 }
 static size_t update_head_bytes(int32_t d_out) {
     const size_t rows = d_out > 0 ? (size_t)d_out : 0;
-    return ((sizeof(UpdateScratch) + 3 * rows * sizeof(int32_t) + 255) / 256) * 256;
+    return ((sizeof(UpdateScratch) + rows * sizeof(int32_t) + 255) / 256) * 256;
 }
 
 }  // namespace srigl
@@ -599,36 +657,35 @@ srigl_status srigl_mask_update(const float* W, const uint8_t* mask, const float*
     const unsigned int N = (unsigned int)((long long)d_out * d_in);
     if (N > 0 && (W == nullptr || mask == nullptr || grad == nullptr || mask_out == nullptr || W_out == nullptr)) return SRIGL_ERR_INVALID_ARG;
     UpdateScratch* s = static_cast<UpdateScratch*>(workspace);
-    int* held = reinterpret_cast<int*>(static_cast<unsigned char*>(workspace) + sizeof(UpdateScratch));
-    int* salient = held + d_out;
-    int* remains = salient + d_out;
+    int* remains = reinterpret_cast<int*>(static_cast<unsigned char*>(workspace) + sizeof(UpdateScratch));
     const unsigned long long cap = cand_capacity(d_out, d_in);
     unsigned long long* candA = reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(workspace) + update_head_bytes(d_out));
     unsigned long long* candB = candA + cap;
+    long long* report = reinterpret_cast<long long*>(report_dev);
+    if (N == 0) {
+        hipLaunchKernelGGL(k_update_report_empty, dim3(1), dim3(64), 0, st, report);
+        return hip_ok(hipGetLastError());
+    }
+    // 19 launches, each reading what the one before it counted: the state, 8 passes of steps 1-3, the per-neuron counts of
+    // steps 3-5, 8 passes of step 6, and step 7 (which also writes the report)
     hipLaunchKernelGGL(k_update_init, dim3(48), dim3(256), 0, st, s, (long long)K_upd);
-    if (N > 0) {
-        layer_select<true>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
-        const bool vec_in = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
-                            reinterpret_cast<uintptr_t>(mask) % 4 == 0;
-        if (vec_in) hipLaunchKernelGGL(k_row_salient<true>, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, s, held, salient);
-        else hipLaunchKernelGGL(k_row_salient<false>, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, s, held, salient);
-    }
-    hipLaunchKernelGGL(k_decide, dim3(1), dim3(1024), 0, st, held, salient, d_out, d_in, k, gamma_percent, (long long)budget, remains, s);
-    if (N > 0) {
-        layer_select<false>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
-        // 16-byte moves need rows that start on 16-byte (mask: 4-byte) boundaries
-        const bool vec = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
-                         reinterpret_cast<uintptr_t>(W_out) % 16 == 0 && reinterpret_cast<uintptr_t>(mask) % 4 == 0 &&
-                         reinterpret_cast<uintptr_t>(mask_out) % 4 == 0;
+    layer_select<true>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
+    const bool vec_in = d_in % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(grad) % 16 == 0 &&
+                        reinterpret_cast<uintptr_t>(mask) % 4 == 0;
+    if (vec_in) hipLaunchKernelGGL(k_row_salient<true>, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, k, gamma_percent, s, remains);
+    else hipLaunchKernelGGL(k_row_salient<false>, dim3((d_out + 3) / 4), dim3(256), 0, st, W, mask, grad, d_out, d_in, k, gamma_percent, s, remains);
+    layer_select<false>(W, mask, grad, remains, N, d_in, s, candA, candB, cap, st);
+    // 16-byte moves need rows that start on 16-byte (mask: 4-byte) boundaries
+    const bool vec = vec_in && reinterpret_cast<uintptr_t>(W_out) % 16 == 0 && reinterpret_cast<uintptr_t>(mask_out) % 4 == 0;
 #define SRIGL_ROW_UPDATE(CPT)                                                                                                      \
-    if (vec) hipLaunchKernelGGL((k_row_update<CPT, true>), dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out); \
-    else hipLaunchKernelGGL((k_row_update<CPT, false>), dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s, mask_out, W_out)
-        if (d_in <= 1024) { SRIGL_ROW_UPDATE(4); }
-        else if (d_in <= 4096) { SRIGL_ROW_UPDATE(16); }
-        else { SRIGL_ROW_UPDATE(32); }
+    if (vec) hipLaunchKernelGGL((k_row_update<CPT, true>), dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s,         \
+                                (long long)K_upd, (long long)budget, mask_out, W_out, report);                                     \
+    else hipLaunchKernelGGL((k_row_update<CPT, false>), dim3(d_out), dim3(256), 0, st, W, mask, grad, d_in, remains, s,            \
+                            (long long)K_upd, (long long)budget, mask_out, W_out, report)
+    if (d_in <= 1024) { SRIGL_ROW_UPDATE(4); }
+    else if (d_in <= 4096) { SRIGL_ROW_UPDATE(16); }
+    else { SRIGL_ROW_UPDATE(32); }
 #undef SRIGL_ROW_UPDATE
-    }
-    hipLaunchKernelGGL(k_update_report, dim3(1), dim3(64), 0, st, s, (long long)K_upd, reinterpret_cast<long long*>(report_dev));
     return hip_ok(hipGetLastError());
 }
 
