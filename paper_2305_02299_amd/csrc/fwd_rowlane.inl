@@ -506,7 +506,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 for (int c = lane; c < span; c += kWave) {
                     const int t = tab[c];
                     const float v = t >= 0 ? out[row * OS + t] + bsp[c] : bsp[c];
-                    yr[c] = act == SRIGL_ACT_NONE ? v : apply_act(v, act);
+                    __builtin_nontemporal_store(act == SRIGL_ACT_NONE ? v : apply_act(v, act), &yr[c]);
                 }
             }
             return;
@@ -524,11 +524,11 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 if (active)
                     for (int cc = prevv[h]; cc < col; ++cc) {
                         const float bv = rl_bias_at(bias, cc);
-                        yr[cc] = decltype(with_act)::value ? apply_act(bv, act) : bv;
+                        __builtin_nontemporal_store(decltype(with_act)::value ? apply_act(bv, act) : bv, &yr[cc]);
                     }
                 if (sg0 + i < n_active && col < d_out) {
                     const float v = out[row * OS + i] + biasv[h];
-                    yr[col] = decltype(with_act)::value ? apply_act(v, act) : v;
+                    __builtin_nontemporal_store(decltype(with_act)::value ? apply_act(v, act) : v, &yr[col]);
                 }
             }
         }
