@@ -103,3 +103,13 @@ def test_structured_random_shapes(seed):
         B_.srigl_structured_linear_fwd(dev(x), B, d_in, Wd, dev(active), n, dev(L.bias), d_out, y, tile=tile)
         torch.cuda.synchronize()
         gate(host(y), y_ref, S, TOL_BF16 if dtype == "bf16" else TOL_F32)
+    # the same product with d_in cut into parts: the library's own choice, and a forced number that the rows allow
+    stages = (d_in * (2 if dtype == "bf16" else 4) + 127) // 128
+    for splits in (0, int(rng.integers(1, min(stages, 16) + 1))):
+        parts = splits or B_.srigl_structured_split_plan(B, d_in, n, d_out, B_.BF16 if dtype == "bf16" else B_.F32)[0]
+        ws = torch.full((max(parts * B * n, 1),), float("nan"), device="cuda") if parts > 1 else None
+        y = torch.full((B, d_out), float("nan"), device="cuda")
+        B_.srigl_structured_linear_fwd_split(dev(x), B, d_in, Wd, dev(active), n, dev(L.bias), d_out, y, ws, splits=splits,
+                                             tile=B_.TILES["64x64"] if splits else None)
+        torch.cuda.synchronize()
+        gate(host(y), y_ref, S, TOL_BF16 if dtype == "bf16" else TOL_F32)

@@ -27,32 +27,38 @@ def test_forward_pair_and_structured_in_a_graph():
     y_struct = torch.empty((48, 512), device="cuda")
     y_cond = torch.empty((48, 512), device="cuda")
 
+    y_parts = torch.empty((48, 512), device="cuda")
+    parts_ws = torch.empty((3 * 48 * l1.n_active,), device="cuda")
+
     def work():
         pair.forward(x, y_pair, hidden)
         B_.srigl_structured_linear_fwd(x, 48, 192, Wd, l1.active, l1.n_active, l1.bias, 512, y_struct)
+        B_.srigl_structured_linear_fwd_split(x, 48, 192, Wd, l1.active, l1.n_active, l1.bias, 512, y_parts, parts_ws, splits=3,
+                                             tile=B_.TILES["64x64"])
         B_.srigl_condensed_linear_fwd(x, 48, 192, l1.W_c, l1.idx, l1.active, l1.n_active, l1.K, l1.bias, 512, y_cond, l1.seg)
 
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
         work()                                    # eager, on a side stream
     side.synchronize()
-    eager = [t.clone() for t in (y_pair, y_struct, y_cond)]
+    eager = [t.clone() for t in (y_pair, y_struct, y_cond, y_parts)]
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         work()
     for rep in range(4):
-        for t in (y_pair, y_struct, y_cond, hidden):
+        for t in (y_pair, y_struct, y_cond, y_parts, parts_ws, hidden):
             t.fill_(float("nan"))                 # eager work between replays
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        for got, want in zip((y_pair, y_struct, y_cond), eager):
+        for got, want in zip((y_pair, y_struct, y_cond, y_parts), eager):
             assert torch.equal(got, want), "replay %d differs from the eager run" % rep
     # and the eager result is the oracle's
     W_c, idx, active = oracle_condensed(L1)
     y_ref, S = oracle.fwd(L1.x, W_c, idx, active, L1.bias, 512, want_scale=True)
     gate(host(y_cond), y_ref, S, TOL_F32)
     gate(host(y_struct), y_ref, S, TOL_F32)
+    gate(host(y_parts), y_ref, S, TOL_F32)
 
 
 def test_condense_and_update_in_a_graph():
