@@ -178,8 +178,10 @@ typedef struct {
     int32_t direct_gather;    /* KLANE: 1 = gather activations from global memory, 2 = stage rows of x in LDS     */
     int32_t xcd_order;        /* ROWLANE: which workgroups share an XCD (one L2): 1 = all batch tiles of a group of
                                  stored rows (W_c / idx fetched once, x by every XCD), 2 = all groups of a batch tile */
-    int32_t terms_from_copy;  /* ROWLANE: 1 = read the terms from the streaming copy when the call brings one (one load per
-                                 block of terms instead of two; measured no faster, so the default, 0, reads W_c / idx)  */
+    int32_t terms_from_copy;  /* 1 = read the terms from the streaming copy wherever the call brings one.  The default, 0:
+                                 ROWLANE reads W_c / idx (one load per block of terms instead of two measured no faster);
+                                 KLANE reads the copy when a workgroup holds one batch row and W_c / idx when it holds
+                                 more (measured faster that way round)                                              */
 } srigl_fwd_tuning;
 
 /* Same, with the algorithm and launch shape forced (for tests and measurements).  tuning may be

@@ -409,10 +409,14 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
     if (a.B == 0 || n_slots == 0) return SRIGL_OK;
     const KlanePlan kp = plan_klane(a, t);
-    if (!kp.ok) return SRIGL_ERR_UNSUPPORTED;
+    if (!kp.ok || (t && (t->terms_from_copy < 0 || t->terms_from_copy > 1))) return SRIGL_ERR_UNSUPPORTED;
     const int RB = kp.RB, rows_per_wg = kp.rows_per_wg, direct = kp.direct;
     const int log2L = ilog2_floor(kp.L);
-    if (a.packed && !a.idx_u16) {   // the streaming copy: same launch shape, a lane's four terms in one unit
+    // The streaming copy (same launch shape, a lane's four terms in one unit) when a workgroup holds one batch row: there it
+    // is ahead on operands that come from HBM (768->3072: 3.73 against 3.83 us at B = 1; 4096->16384 bf16: 9.5 against 10.6)
+    // and level on cached ones.  With two or more rows per workgroup the array kernel is faster (3072->768 at B = 16: 6.4
+    // against 9.1 us), so there the copy is read only when the tuning asks for it.
+    if (a.packed && !a.idx_u16 && (RB == 1 || (t && t->terms_from_copy == 1))) {
         const bool narrow = a.x_bf16 && a.d_in <= 65536;
 #define SRIGL_KLANE_P(RBV, G)                                                                                        \
     return !a.x_bf16 ? launch_klane_packed_t<RBV, G, float, 32>(a, log2L, rows_per_wg, st)                            \
