@@ -149,8 +149,11 @@ def sweep(args):
             Wrows = torch.empty((max(layer.n_active, 1), L.d_in), dtype=layer.W_c.dtype, device="cuda")
             B_.srigl_densify(layer.W_c, layer.idx, layer.n_active, L.K, L.d_in, Wrows)
             ys = torch.empty((B, L.d_out), device="cuda")
-            structured = time_graph(lambda i: B_.srigl_structured_linear_fwd(xs, B, L.d_in, Wrows, layer.active, layer.n_active,
-                                                                            layer.bias, L.d_out, ys), min(steps, 100), 5) * 1e3
+            # (d_in cut into as many parts as the library's plan takes for these sizes: the call the selector's estimate is about)
+            parts, need = B_.srigl_structured_split_plan(B, L.d_in, layer.n_active, L.d_out, B_.BF16 if bf16 else B_.F32)
+            part_ws = torch.empty((need,), dtype=torch.uint8, device="cuda") if need else None
+            structured = time_graph(lambda i: B_.srigl_structured_linear_fwd_split(xs, B, L.d_in, Wrows, layer.active, layer.n_active,
+                                                                                  layer.bias, L.d_out, ys, part_ws), min(steps, 100), 5) * 1e3
         # unstructured context (Fig. 4's CSR line): the same masked weight as a CSR matrix through the library's sparse product
         csr = None
         if not bf16 and not args.no_csr:
@@ -178,6 +181,7 @@ def sweep(args):
                           "gflops_cold": round(flops / cold / 1e3, 1), "gflops_warm": round(flops / warm / 1e3, 1),
                           "algorithmic_bytes": nbytes, "torch_dense_matmul_us": round(dense, 2),
                           "structured_only_us_warm": None if structured is None else round(structured, 2),
+                          "structured_only_parts": None if structured is None else parts,
                           "library_csr_spmm_us": None if csr is None else round(csr, 2),
                           "own_csr_us_warm": None if own_csr is None else round(own_csr, 2),
                           "selected": "structured" if sel == B_.REPR_STRUCTURED else "condensed",

@@ -491,7 +491,8 @@ static void choose_tile_and_split(int B, int n_active, int d_in, int d_out, bool
             } else {
                 const double ns_k = f32 ? m.ns_per_k_f32 : m.ns_per_k_bf16;
                 const double crowd = (m.bm == 64 && padded * s > 256) ? 1.6 : 1.0;
-                us = 7.0 + ns_k * crowd * d_in / s * 1e-3;   // 7.0: the second launch and a second pipeline fill
+                // 7.0: the second launch and a second pipeline fill; the partial sums are written once and read once
+                us = 7.0 + ns_k * crowd * d_in / s * 1e-3 + 8.0 * s * (double)B * n_active / 4.5e6;
             }
             if (best_us == 0.0 || us < best_us) { best_us = us; best = m.tile; best_s = pass == 0 ? 1 : s; }
         }
