@@ -119,29 +119,41 @@ __global__ __launch_bounds__(1024) void k_scan_rows(const int32_t* __restrict__ 
         __syncthreads();
     }
 
+    // Every thread takes a run of consecutive rows: it counts its stored rows, the workgroup turns the counts into each thread's
+    // first slot (one scan inside every wavefront, one over the 16 wavefront totals), and the thread numbers its rows from there.
     int n_bad = 0, first_bad = 0x7fffffff;
-    for (int base = 0; base < n_rows; base += nthreads) {
-        const int r = base + tid;
-        int c = (r < n_rows) ? counts[r] : 0;
+    const int per_thread = (n_rows + nthreads - 1) / nthreads;
+    const int r0 = tid * per_thread, r1 = min(n_rows, r0 + per_thread);
+    auto classify = [&](int r, bool& stored, bool& bad) {
+        const int c = counts[r];
+        if (index_mode) { stored = (c == K); bad = (c != K); }
+        else            { stored = (c == K) && (c > 0); bad = (c != 0) && (c != K); }
+    };
+    int mine = 0;
+    for (int r = r0; r < r1; ++r) {
         bool stored, bad;
-        if (index_mode) { stored = (r < n_rows) && (c == K); bad = (r < n_rows) && (c != K); }
-        else            { stored = (c == K) && (c > 0);      bad = (c != 0) && (c != K); }
+        classify(r, stored, bad);
+        mine += stored ? 1 : 0;
         if (bad) { ++n_bad; first_bad = min(first_bad, r); }
-        const uint64_t b = __ballot(stored);
-        const int in_wave = (int)lanes_below(b);
-        if (lane == 0) s_wave[wv] = __popcll(b);
-        __syncthreads();
-        int before = s_base;
-        for (int w = 0; w < wv; ++w) before += s_wave[w];
-        const int my = before + in_wave;
-        if (r < n_rows) {
-            if (slot) slot[r] = stored ? my : -1;
-            if (stored && active && my < cap_rows) active[my] = r;
-        }
-        __syncthreads();
-        if (tid == 0) { int t = 0; for (int w = 0; w < nwaves; ++w) t += s_wave[w]; s_base += t; }
-        __syncthreads();
     }
+    int incl = mine;   // inclusive scan over the lanes of this wavefront
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    int my = incl - mine;
+    for (int w = 0; w < wv; ++w) my += s_wave[w];
+    if (tid == nthreads - 1) s_base = my + mine;   // the last thread's end is the number of stored rows
+    for (int r = r0; r < r1; ++r) {
+        bool stored, bad;
+        classify(r, stored, bad);
+        if (slot) slot[r] = stored ? my : -1;
+        if (stored && active && my < cap_rows) active[my] = r;
+        my += stored ? 1 : 0;
+    }
+    __syncthreads();
     for (int off = 32; off > 0; off >>= 1) {
         n_bad += __shfl_xor(n_bad, off, kWave);
         first_bad = min(first_bad, __shfl_xor(first_bad, off, kWave));
