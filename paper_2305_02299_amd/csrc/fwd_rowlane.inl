@@ -179,6 +179,48 @@ __device__ __forceinline__ void pipe_groups(float (&acc)[R], const float (&wv)[N
     group_fmacs<R, G % GPB>(acc, wv[G / GPB], cur);
 }
 
+// The same walk with the reads two groups ahead of the multiply-adds (three buffers in rotation): a wavefront's reads then have
+// two groups' worth of its own and the other wavefronts' arithmetic to return in, where one group's worth left every
+// wavefront of a full compute unit waiting on the LDS queue.  On entry the reads of group G are in flight in `a`, and those
+// of group G + 1 in `b` if that group exists.
+template <int R, int G, int NB>
+__device__ __forceinline__ void pipe_groups2(float (&acc)[R], const float (&wv)[NB], const int (&ov)[NB], const char* __restrict__ xb,
+                                             int lanepart, int n, typename RowVec<R>::type (&a)[GroupSize<R>::value],
+                                             typename RowVec<R>::type (&b)[GroupSize<R>::value],
+                                             typename RowVec<R>::type (&c)[GroupSize<R>::value]) {
+    constexpr int GS = GroupSize<R>::value;
+    constexpr int GPB = kBlock / GS;
+    if constexpr (G + 2 < GPB * NB) {
+        if (n > GS * (G + 2)) {
+            group_reads<R, (G + 2) % GPB>(c, ov[(G + 2) / GPB], xb, lanepart);
+            group_fmacs<R, G % GPB>(acc, wv[G / GPB], a);
+            pipe_groups2<R, G + 1, NB>(acc, wv, ov, xb, lanepart, n, b, c, a);
+            return;
+        }
+    }
+    group_fmacs<R, G % GPB>(acc, wv[G / GPB], a);
+    if constexpr (G + 1 < GPB * NB) {
+        if (n > GS * (G + 1)) group_fmacs<R, (G + 1) % GPB>(acc, wv[(G + 1) / GPB], b);
+    }
+}
+// Reads of the first group (and of the second, two ahead), then the walk.  DEPTH = 1 keeps the two-buffer form.
+template <int R, int NB, int DEPTH>
+__device__ __forceinline__ void walk_groups(float (&acc)[R], const float (&wv)[NB], const int (&ov)[NB], const char* __restrict__ xb,
+                                            int lanepart, int n) {
+    using V = typename RowVec<R>::type;
+    constexpr int GS = GroupSize<R>::value;
+    constexpr int GPB = kBlock / GS;
+    V a[GS], b[GS];
+    group_reads<R, 0>(a, ov[0], xb, lanepart);
+    if constexpr (DEPTH == 2 && GPB * NB > 1) {
+        V c[GS];
+        if (n > GS) group_reads<R, 1 % GPB>(b, ov[1 / GPB], xb, lanepart);
+        pipe_groups2<R, 0, NB>(acc, wv, ov, xb, lanepart, n, a, b, c);
+    } else {
+        pipe_groups<R, 0, NB>(acc, wv, ov, xb, lanepart, n, a, b);
+    }
+}
+
 // One block of terms of stored-row data starting at term index t0 (wave-uniform): 16 * H consecutive terms, one vector
 // load per array.  The lane at position l16 of slice p works on term t0 + tofs, tofs = H * l16 + p (so that a partly
 // filled block ends after ceil(n / H) of its 16 steps).  With one slice the lanes load their own terms (16 consecutive
@@ -242,6 +284,10 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     // l) instead of two loads of 32 terms twice over; every vector-memory instruction costs the address unit the same
     // 16 clocks whatever it returns, and the loads ahead of the first barrier are what that barrier waits for.
     constexpr bool MERGE = (H == 2 && KPRE == 2);
+    // Groups of LDS reads in flight ahead of the multiply-adds: two for 128-row tiles in one slice (measured 5 % faster on the
+    // 4096 -> 16384 bf16 layer at B = 2048, 1 % on 768 -> 3072 at B = 1024), one elsewhere (two measured equal on the 64-row
+    // two-slice tile and 3 % slower on 16-row tiles; with 16-byte reads a third buffer does not fit the registers)
+    constexpr int kReadAhead = (R == 2 && H == 1) ? 2 : 1;
     using V = typename RowVec<R>::type;
 
     // XCD-aware decode: consecutive workgroup ids go to different XCDs (8 of them), so the id modulo 8 selects the XCD.
@@ -398,7 +444,6 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             // so that the vector-memory queue never takes the whole burst at once
             if (more) { SRIGL_STAGE_LOAD_UNITS(c + 1, (i * kStageUnits) / NPW, ((i + 1) * kStageUnits) / NPW) }
             const int n_terms = nn[i];
-            V xa[GroupSize<R>::value], xc[GroupSize<R>::value];
             if (n_terms > 0) {
                 float pw[KPRE];
                 int po[KPRE];
@@ -406,8 +451,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 for (int p = 0; p < KPRE; ++p)
                     finish_terms<XT, H, SWZ>(rw[i][MERGE ? 0 : p], ri[i][MERGE ? 0 : p], n_terms - p * TB, tofs, S4, -c * C * S4, zero_off, pw[p], po[p],
                                              MERGE ? p * TB : 0);
-                group_reads<R, 0>(xa, po[0], xb, lanepart);
-                pipe_groups<R, 0, KPRE>(acc[i], pw, po, xb, lanepart, (n_terms + H - 1) / H, xa, xc);
+                walk_groups<R, KPRE, kReadAhead>(acc[i], pw, po, xb, lanepart, (n_terms + H - 1) / H);
                 // long ranges: the remaining blocks, one at a time, each requested one block ahead
                 if (n_terms > KPRE * TB) {
                     const int row = (s0 + i) * KS + k0n[i];
@@ -419,8 +463,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                         int oc[1];
                         finish_terms<XT, H, SWZ>(wr, ir, n_terms - kb, tofs, S4, -c * C * S4, zero_off, wc[0], oc[0]);
                         if (kb + TB < n_terms) request_terms<XT, IT, PKB>(W_c, idx, pk, row + kb + TB, lofs, t_last, wr, ir);
-                        group_reads<R, 0>(xa, oc[0], xb, lanepart);
-                        pipe_groups<R, 0, 1>(acc[i], wc, oc, xb, lanepart, (n_terms - kb + H - 1) / H, xa, xc);
+                        walk_groups<R, 1, kReadAhead>(acc[i], wc, oc, xb, lanepart, (n_terms - kb + H - 1) / H);
                     }
                 }
             }
