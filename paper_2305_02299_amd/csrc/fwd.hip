@@ -457,7 +457,8 @@ constexpr int kRowlaneShortRowK = 200;
 constexpr int kRowlaneShortRowOneK = 128;
 constexpr int kRowlaneTwoRowsFourSlicesMinK = 64;   // blocks of 64 terms: measured 14 % slower than 32 x 2 tiles at a fan-in of 39
 
-static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t) {
+// npw_cap: the most stored rows per wavefront the choice may take (0: whatever the tile allows)
+static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t, int npw_cap = 0) {
     RowlanePlan p{};
     p.ok = false;
     // the kernel indexes x, W_c / idx and seg with 32-bit offsets
@@ -556,13 +557,14 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
         double best = -1.0;
         for (int ci = 0; ci < 6; ++ci) {
             const int c = cand[ci];
-            if (c > rowlane_max_npw(p.R)) break;
+            if (c > rowlane_max_npw(p.R, p.H) || (c == 8 && !a.x_bf16)) break;   // (eight rows of fp32 terms spill registers)
+            if (npw_cap && c > npw_cap) break;
             const double cost = shape_cost(c);
             if (best < 0 || cost < best) { best = cost; npw = c; }
         }
     }
     if (npw != 1 && npw != 2 && npw != 3 && npw != 4 && npw != 6 && npw != 8) return p;
-    if (npw > rowlane_max_npw(p.R)) return p;
+    if (npw > rowlane_max_npw(p.R, p.H) || (npw == 8 && !a.x_bf16)) return p;
     p.NPW = npw;
     p.cost = shape_cost(npw);
     p.KPRE = rowlane_kpre_rh(npw, p.R, p.H);
@@ -597,7 +599,9 @@ static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
     const int BT = kWave * p.R / p.H;
     const double rounds = std::max(1, p.rounds);
     const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
-    const double per_step = p.R == 2 ? (p.H == 4 ? (a.K < kRowlaneShortRowK ? 0.0375 : 0.0402) : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368));
+    // (six or eight rows per wavefront keep one block of terms per row: the steps measured 0-40 % slower, longest on long segments)
+    const double many_rows = (p.R == 2 && p.H == 1 && p.NPW >= 6) ? 1.15 : 1.0;
+    const double per_step = many_rows * (p.R == 2 ? (p.H == 4 ? (a.K < kRowlaneShortRowK ? 0.0375 : 0.0402) : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368)));
     const double terms = (double)a.n_active * a.K;
     return 2.19 + rounds * (1.38 * p.n_chunks + 5.90e-6 * BT * a.d_in * 4.0 + per_step * steps + 1.45e-4 * BT * p.NW * p.NPW * 4.0) +
            (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);
@@ -615,16 +619,18 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     best.ok = false;
     double best_us = 0.0;
     // rows per lane, term slices; a later shape must be 5 % ahead of an earlier one (the estimates are good to about that)
-    static const int shapes[6][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}, {2, 2}, {2, 4}};
-    for (int i = 0; i < 6; ++i) {
+    // (the last entry: 128-row tiles with six or eight stored rows per wavefront, half the workgroups of the four-row form;
+    // ahead at 1024 rows and more, where it saves a round of workgroups: 768 -> 3072 at B = 1024 36.4 -> 33.0 us)
+    static const int shapes[7][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}, {2, 2}, {2, 4}, {2, 1}};
+    for (int i = 0; i < 7; ++i) {
         if (shapes[i][0] == 2 && a.K < kRowlaneTwoRowsMinK) continue;
         if (shapes[i][0] == 2 && shapes[i][1] == 4 && a.K < kRowlaneTwoRowsFourSlicesMinK) continue;
         srigl_fwd_tuning shape{};
         if (t) shape = *t;
         shape.rows_per_lane = shapes[i][0];
         shape.term_slices = shapes[i][1];
-        const RowlanePlan p = plan_rowlane_with(a, &shape);
-        if (!p.ok) continue;
+        const RowlanePlan p = plan_rowlane_with(a, &shape, i == 1 ? 4 : 0);
+        if (!p.ok || (i == 6 && p.NPW <= 4)) continue;
         const double us = rowlane_estimate_us(a, p);
         if (!best.ok || us < 0.95 * best_us) { best = p; best_us = us; }
     }

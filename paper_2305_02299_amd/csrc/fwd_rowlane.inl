@@ -632,13 +632,14 @@ static srigl_status launch_rowlane_k(const FwdArgs& a, const RowlanePlan& p, hip
 
 template <int R, int H, typename XT, typename IT>
 static srigl_status launch_rowlane_r(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
-    constexpr int MAXN = rowlane_max_npw(R);
+    constexpr int MAXN = rowlane_max_npw(R, H);
     switch (p.NPW) {
         case 1: return launch_rowlane_k<R, H, 1, XT, IT>(a, p, st);
         case 2: return launch_rowlane_k<R, H, 2, XT, IT>(a, p, st);
         case 3: return launch_rowlane_k<R, H, 3, XT, IT>(a, p, st);
         case 4: if constexpr (MAXN >= 4) return launch_rowlane_k<R, H, 4, XT, IT>(a, p, st); else break;
         case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, H, 6, XT, IT>(a, p, st); else break;
+        case 8: if constexpr (MAXN >= 8 && sizeof(XT) == 2) return launch_rowlane_k<R, H, 8, XT, IT>(a, p, st); else break;
         default: break;
     }
     return SRIGL_ERR_UNSUPPORTED;
