@@ -459,6 +459,23 @@ constexpr int kRowlaneTwoRowsFourSlicesMinK = 64;   // blocks of 64 terms: measu
 
 // npw_cap: the most stored rows per wavefront the choice may take (0: whatever the tile allows)
 static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t, int npw_cap = 0) {
+    // Wavefronts per workgroup, when the tuning leaves them open: 16, or 12 (three per SIMD instead of four) when that takes no
+    // more rounds of workgroups, chunks or stored rows per wavefront: the same rows spread over more workgroups, each with a
+    // quarter less to do (3072 -> 768 with 538 stored rows at B = 256: 192 workgroups of 16 wavefronts 14.9 us, 240 of 12
+    // 13.2 us; 13 or 14 wavefronts load one SIMD like 16 and measured 14.6).
+    if (!t || t->waves == 0) {
+        srigl_fwd_tuning tw{};
+        if (t) tw = *t;
+        tw.waves = rowlane_max_threads(tw.rows_per_lane ? tw.rows_per_lane : 1) / kWave;
+        const RowlanePlan full = plan_rowlane_with(a, &tw, npw_cap);
+        tw.waves = tw.waves * 3 / 4;
+        const RowlanePlan fewer = plan_rowlane_with(a, &tw, npw_cap);
+        // (with one stored row per wavefront the workgroups are too small for that to pay: 5.4 -> 6.0 us on 768 -> 3072 at B = 32)
+        if (full.ok && fewer.ok && full.NPW >= 2 && fewer.rounds <= full.rounds && fewer.NPW <= full.NPW && fewer.n_chunks <= full.n_chunks &&
+            fewer.n_groups > full.n_groups)
+            return fewer;
+        return full.ok ? full : fewer;
+    }
     RowlanePlan p{};
     p.ok = false;
     // the kernel indexes x, W_c / idx and seg with 32-bit offsets
