@@ -35,11 +35,14 @@ struct SelState {
 // adding to the same 256 counters took longer than reading a 2.4-million-element layer (43 us of a 167 us update).  Every
 // workgroup of the next pass reads all copies, which costs too: 4 copies measured best (1, 2, 8: 2-5 % slower; 32: 50 %).
 constexpr int kHistCopies = 4;
+constexpr int kCountCopies = 64;
 struct UpdateScratch {
     unsigned int hist[3][8][kHistCopies][256];   // workgroup w adds into copy w % kHistCopies
     SelState slot[3][2];
     SelState fin[2];                    // the finished selections of step 3 (written by k_row_salient for the launches after it)
-    unsigned int cnt_remaining[kHistCopies], cnt_ablated[kHistCopies];   // steps 4-5: neurons that stay / are ablated now (sums of the copies)
+    // steps 4-5: neurons that stay / are ablated now (sums of the copies: one per lane of the wavefront that reads them; a
+    // workgroup of the per-neuron kernel adds into copy w % 64, so a 16384-row layer sends 64 atomics to an address, not 1024)
+    unsigned int cnt_remaining[kCountCopies], cnt_ablated[kCountCopies];
     unsigned long long cand_count[3];   // keys in the selection's candidate list; above the capacity: the list is not valid
 };
 
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(256) void k_update_init(UpdateScratch* s, long long
         if (t < 2) s->fin[t] = z;
         s->cand_count[t] = 0;
     }
-    if (blockIdx.x == 0 && t < kHistCopies) { s->cnt_remaining[t] = 0; s->cnt_ablated[t] = 0; }
+    if (blockIdx.x == 0 && t < kCountCopies) { s->cnt_remaining[t] = 0; s->cnt_ablated[t] = 0; }
 }
 
 // From a 256-bin histogram (lane l reads bins 4l .. 4l + 3), for one wavefront: the byte d with suffix(d) >= want >
@@ -167,10 +170,10 @@ __device__ SelState advance(const SelState& before, const unsigned int (*hist_pr
 __device__ __forceinline__ SelState finished_walk(const UpdateScratch* __restrict__ s, int sel, int lane) {
     return advance(s->slot[sel][1], s->hist[sel][7], 8, lane);
 }
-__device__ __forceinline__ unsigned int sum_copies(const unsigned int (&c)[kHistCopies]) {
-    unsigned int n = 0;
-#pragma unroll
-    for (int i = 0; i < kHistCopies; ++i) n += c[i];
+// Sum of the 64 copies of a neuron counter.  Called by one whole wavefront; the result is the same on every lane.
+__device__ __forceinline__ unsigned int sum_copies(const unsigned int (&c)[kCountCopies], int lane) {
+    unsigned int n = c[lane];
+    for (int off = 32; off > 0; off >>= 1) n += __shfl_xor(n, off, 64);
     return n;
 }
 
@@ -220,7 +223,7 @@ __global__ __launch_bounds__(kPassThreads) void k_layer_hist(const float* __rest
             a = s->slot[selA][0];
             b = s->slot[1][0];
             // step 6 with no neuron ablated in step 4: same candidates, same count, so step 3's walk already has the answer
-            if (!PAIR && sum_copies(s->cnt_ablated) == 0) {
+            if (!PAIR && sum_copies(s->cnt_ablated, t) == 0) {
                 a = s->fin[0];
                 if (blockIdx.x == 0 && t == 0) s->slot[2][0] = a;
             }
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(256) void k_row_salient(const float* __restrict__ W
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (threadIdx.x == 0) { wg_stay = 0; wg_ablated = 0; }
     // the row's first kAhead steps are requested before the thresholds are (they do not depend on them)
-    constexpr int kAhead = 4;
+    constexpr int kAhead = 2;
     uint32_t pm[kAhead];
     float4 pw[kAhead], pg[kAhead];
     if (VEC && r < d_out) {
@@ -404,8 +407,8 @@ __global__ __launch_bounds__(256) void k_row_salient(const float* __restrict__ W
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (wg_stay) atomicAdd(&s->cnt_remaining[blockIdx.x % kHistCopies], (unsigned int)wg_stay);
-        if (wg_ablated) atomicAdd(&s->cnt_ablated[blockIdx.x % kHistCopies], (unsigned int)wg_ablated);
+        if (wg_stay) atomicAdd(&s->cnt_remaining[blockIdx.x % kCountCopies], (unsigned int)wg_stay);
+        if (wg_ablated) atomicAdd(&s->cnt_ablated[blockIdx.x % kCountCopies], (unsigned int)wg_ablated);
     }
 }
 
@@ -462,6 +465,7 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
     __shared__ __align__(16) unsigned int h[3][kRowCopies][256];
     __shared__ int n_kept;
     __shared__ unsigned long long prune_threshold;
+    __shared__ long long new_fan_in;
     const int r = blockIdx.x, t = threadIdx.x;
     const unsigned int row0 = (unsigned int)r * d_in;
     // rows of up to 4096 columns: the thread's columns are requested before the selection's state is (neither waits for the other)
@@ -479,17 +483,19 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
         }
     }
     // step 5: the new fan-in from the count of staying neurons; step 6's finished selection (its last digit is taken here)
-    const long long n_remaining = sum_copies(s->cnt_remaining);
-    long long k_new = n_remaining > 0 ? budget / n_remaining : 0;
-    if (k_new > d_in) k_new = d_in;
     if (t < 64) {
+        const long long n_remaining = sum_copies(s->cnt_remaining, t);
+        const long long n_ablated = sum_copies(s->cnt_ablated, t);
+        long long k = n_remaining > 0 ? budget / n_remaining : 0;
+        if (k > d_in) k = d_in;
         const SelState f2 = finished_walk(s, 2, t);
         if (t == 0) {
             prune_threshold = f2.prefix;
+            new_fan_in = k;
             if (r == 0) {
-                report[0] = k_new;
+                report[0] = k;
                 report[1] = n_remaining;
-                report[2] = sum_copies(s->cnt_ablated);
+                report[2] = n_ablated;
                 report[3] = (long long)((unsigned long long)K_upd < f2.total ? (unsigned long long)K_upd : f2.total);
             }
         }
@@ -512,6 +518,7 @@ __global__ __launch_bounds__(256, CPT <= 16 ? 5 : 2) void k_row_update(const flo
     if (t == 0) n_kept = 0;
     __syncthreads();
     const unsigned long long t_prune = prune_threshold;
+    const long long k_new = new_fan_in;
     auto take = [&](int j, int c, float w, float g, uint8_t m) {
         valid |= 1u << j;
         const unsigned int i = row0 + c;
