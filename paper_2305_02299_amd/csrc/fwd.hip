@@ -378,14 +378,20 @@ static KlanePlan plan_klane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     const int n_slots = a.active ? a.n_active + 1 : a.n_active;
     // lanes per stored row: enough that a lane has at most ~4 terms, at least 4, at most 64
     int L = t && t->lanes_per_neuron ? t->lanes_per_neuron : 0;
+    // nothing forced: the staged shape with few lanes per stored row where it is ahead
+    int few_L = 0, few_RB = 0;
+    const bool open_shape = !t || (t->lanes_per_neuron == 0 && t->rows_per_block == 0 && t->direct_gather == 0);
+    const bool few = open_shape && klane_few_lanes_staged(a.B, a.d_in, a.n_active, a.K, &few_L, &few_RB) &&
+                     (size_t)few_RB * a.d_in * sizeof(float) <= kLdsMax / 2;
+    if (few) L = few_L;
     if (L == 0) L = klane_lanes(a.K);
     if (L < 1 || L > 64 || (L & (L - 1)) != 0) return p;
     // activations: gathered from global memory, or staged in LDS (the tuning can force either: 1 = gather, 2 = stage);
     // an input row too long for the LDS is always gathered
     const int dg = t ? t->direct_gather : 0;
     if (dg < 0 || dg > 2) return p;
-    p.direct = dg == 1 || (dg == 0 && klane_gathers(a.B, a.d_in, a.n_active, a.K)) ? 1 : 0;
-    int RB = t && t->rows_per_block ? t->rows_per_block : 0;
+    p.direct = dg == 1 || (dg == 0 && !few && klane_gathers(a.B, a.d_in, a.n_active, a.K)) ? 1 : 0;
+    int RB = t && t->rows_per_block ? t->rows_per_block : (few ? few_RB : 0);
     if (RB != 0 && RB != 1 && RB != 2 && RB != 4 && RB != 8) return p;
     if (RB == 0) RB = p.direct ? klane_gather_rows(a.B, a.n_active, a.K) : klane_stage_rows(a.B, a.d_in);
     if (!p.direct) {
@@ -415,8 +421,9 @@ srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipSt
     // The streaming copy (same launch shape, a lane's four terms in one unit) when a workgroup holds one batch row: there it
     // is ahead on operands that come from HBM (768->3072: 3.73 against 3.83 us at B = 1; 4096->16384 bf16: 9.5 against 10.6)
     // and level on cached ones.  With two or more rows per workgroup the array kernel is faster (3072->768 at B = 16: 6.4
-    // against 9.1 us), so there the copy is read only when the tuning asks for it.
-    if (a.packed && !a.idx_u16 && (RB == 1 || (t && t->terms_from_copy == 1))) {
+    // against 9.1 us), so there the copy is read only when the tuning asks for it.  The staged form reads the copy with any
+    // number of rows (768 -> 3072 K = 39 at B = 32, two rows per workgroup: 5.3 / 4.5 us against 6.4 / 4.6 on the arrays).
+    if (a.packed && !a.idx_u16 && (RB == 1 || !direct || (t && t->terms_from_copy == 1))) {
         const bool narrow = a.x_bf16 && a.d_in <= 65536;
 #define SRIGL_KLANE_P(RBV, G)                                                                                        \
     return !a.x_bf16 ? launch_klane_packed_t<RBV, G, float, 32>(a, log2L, rows_per_wg, st)                            \
@@ -670,6 +677,10 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
 // kernel, above 2048 rows the batched kernel always wins.
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
     const int B = a.B, d_in = a.d_in, n_active = a.n_active, K = a.K;
+    {   // the staged few-lanes shape of the small-batch kernel where it measured ahead of both estimates' kernels
+        int few_L = 0, few_RB = 0;
+        if (klane_few_lanes_staged(B, d_in, n_active, K, &few_L, &few_RB) && plan_klane(a, nullptr).ok) return SRIGL_FWD_KLANE;
+    }
     bool batched = B > 16;
     if (B > 1 && B <= 2048 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");

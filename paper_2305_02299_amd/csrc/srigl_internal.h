@@ -199,6 +199,22 @@ inline double klane_estimate_us(int B, int d_in, int n_active, int K) {
     return klane_gathers(B, d_in, n_active, K) ? klane_gather_estimate_us(B, d_in, n_active, K) : klane_stage_estimate_us(B, d_in, n_active, K);
 }
 
+// Batches of 8 to 32 rows on inputs up to 1024 wide with moderate fan-in and at least 2048 stored rows: the small-batch
+// kernel with the rows of x staged in LDS and few lanes per stored row (16 or 32 stored rows per workgroup share one staged
+// tile) runs ahead of both the gathering form and the batched kernel, cold and cached: 768 -> 3072 K = 77 at B = 8 / 16 /
+// 32: 5.1 / 5.8 / 6.6 us cold against 5.6 / 6.1 / 7.7; K = 39 at B = 16 / 32: 4.8 / 5.6 against 5.6 / 7.0; with 30 % of the
+// neurons ablated at B = 32: 7.0 against 9.1; 1024 -> 4096 bf16 K = 102 at B = 8: 5.1 against 6.0.  Not taken where it
+// measured behind on operands from HBM: wider inputs (3072 -> 768 at B = 8: 9.1 against 6.1 us; 2048 -> 2048 K = 102: 6.2
+// against 5.5), layers of 1024 stored rows (a quarter of the workgroups: 4.7 against 4.1), fan-ins above 128 from B = 16,
+// and B x K above ~2500, where the batched kernel is level or ahead.
+inline bool klane_few_lanes_staged(int B, int d_in, int n_active, int K, int* L, int* RB) {
+    if (d_in > 1024 || d_in % 4 != 0 || n_active < 2048 || B < 8 || B > 32 || K < 32 || (long long)B * K > 2560 || (K > 128 && B > 8))
+        return false;
+    *L = B >= 16 ? 8 : 16;
+    *RB = 2;
+    return true;
+}
+
 inline srigl_status hip_ok(hipError_t e) { return e == hipSuccess ? SRIGL_OK : SRIGL_ERR_HIP; }
 
 // Kernels that use more than 64 KB of dynamic LDS need the limit raised with hipFuncSetAttribute, which applies to the

@@ -40,9 +40,23 @@ def test_small_batches_gather_their_activations():
     """Measured: up to a few million gathered terms the small-batch kernel is faster reading x through the caches than staging
     rows of it in LDS (3072 -> 768 at B = 1: 3.7 vs 6.4 us cold), with one, two or four batch rows per workgroup."""
     for (B, d_in, d_out, K, rb) in ((1, 768, 3072, 77, 1), (1, 3072, 768, 308, 1), (4, 3072, 768, 308, 1), (8, 3072, 768, 308, 2),
-                                    (8, 768, 3072, 77, 2), (8, 4096, 1024, 410, 2), (2, 4096, 16384, 205, 2)):
+                                    (4, 768, 3072, 77, 1), (8, 4096, 1024, 410, 2), (2, 4096, 16384, 205, 2)):
         p = plan(B, d_in, d_out, K)
         assert (p["algo"], p["direct_gather"], p["rows_per_block"]) == (B_.FWD_KLANE, 1, rb), (B, d_in, d_out, K, p)
+    # 8 to 32 rows on inputs up to 1024 wide with moderate fan-in and 2048 stored rows or more: rows of x staged, few lanes per
+    # stored row (measured ahead of the gathering form and of the batched kernel: 768 -> 3072 at B = 8 / 16 / 32 5.1 / 5.8 / 6.6 us
+    # cold against 5.6 / 6.1 / 7.7)
+    for (B, d_in, d_out, K, lanes, rb) in ((8, 768, 3072, 77, 16, 2), (16, 768, 3072, 77, 8, 2), (32, 768, 3072, 77, 8, 2),
+                                           (32, 768, 3072, 39, 8, 2), (8, 1024, 4096, 102, 16, 2), (8, 768, 3072, 154, 16, 2)):
+        p = plan(B, d_in, d_out, K)
+        assert (p["algo"], p["direct_gather"], p["lanes_per_neuron"], p["rows_per_block"]) == (B_.FWD_KLANE, 0, lanes, rb), (B, d_in, K, p)
+    # not beyond B x K of about 2500, nor on wide inputs, few stored rows, long rows from 16 batch rows on, or very short rows
+    assert plan(8, 2048, 2048, 204)["direct_gather"] == 1
+    assert plan(8, 1024, 1024, 102)["direct_gather"] == 1
+    assert plan(16, 768, 3072, 154)["algo"] == B_.FWD_ROWLANE
+    assert plan(32, 768, 3072, 154)["algo"] == B_.FWD_ROWLANE
+    assert plan(8, 3072, 768, 308)["direct_gather"] == 1
+    assert plan(16, 768, 3072, 8)["direct_gather"] == 1
     # very sparse layers at larger batches: many distinct lines per gather, the staged rows win
     p = plan(256, 768, 3072, 8)                                        # 8.9 / 7.3 us staged, 10.9 / 9.4 gathered, 9.4 / 8.4 batched
     assert (p["algo"], p["direct_gather"], p["rows_per_block"]) == (B_.FWD_KLANE, 0, 2)
@@ -104,7 +118,8 @@ def test_very_sparse_layers_stay_on_the_small_batch_kernel_at_larger_batches():
 
 def test_mid_batches_follow_the_estimates():
     assert plan(8, 768, 3072, 77)["algo"] == B_.FWD_KLANE
-    assert plan(32, 768, 3072, 77)["algo"] == B_.FWD_ROWLANE
+    assert plan(32, 768, 3072, 77)["algo"] == B_.FWD_KLANE            # staged, 8 lanes per stored row: 6.3 / 4.9 us vs 7.4 / 5.3 batched
+    assert plan(64, 768, 3072, 77)["algo"] == B_.FWD_ROWLANE
     assert plan(32, 2048, 512, 205)["algo"] == B_.FWD_KLANE         # few stored rows: the batched kernel cannot fill the GPU
     assert plan(96, 2048, 512, 205)["algo"] == B_.FWD_ROWLANE
     assert plan(16, 2560, 2560, 256)["algo"] == B_.FWD_ROWLANE        # wide input, many stored rows: 9.6 vs 13.7 us measured
