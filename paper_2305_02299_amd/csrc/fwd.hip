@@ -625,7 +625,7 @@ static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
     const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
     // (six or eight rows per wavefront keep one block of terms per row: the steps measured 0-40 % slower, longest on long segments)
     const double many_rows = (p.R == 2 && p.H == 1 && p.NPW >= 6) ? 1.15 : 1.0;
-    const double per_step = many_rows * (p.R == 2 ? (p.H == 4 ? (a.K < kRowlaneShortRowK ? 0.0375 : 0.0402) : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368)));
+    const double per_step = many_rows * (p.R == 2 ? (p.H == 4 ? (a.K < kRowlaneShortRowK ? 0.0345 : 0.0375) : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368)));
     const double terms = (double)a.n_active * a.K;
     return 2.19 + rounds * (1.38 * p.n_chunks + 5.90e-6 * BT * a.d_in * 4.0 + per_step * steps + 1.45e-4 * BT * p.NW * p.NPW * 4.0) +
            (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);
