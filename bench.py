@@ -190,7 +190,7 @@ def sweep(args):
 
 
 def point(args):
-    """--point NAME|d_in,d_out,K[,bf16][,ablate=F]: one layer at --batch rows, optionally in a forced kernel (--algo) and launch
+    """--point NAME|d_in,d_out,K[,bf16][,ablate=F][,clustered]: one layer at --batch rows, optionally in a forced kernel (--algo) and launch
     shape (--tuning JSON); cold (spacer graph on other operand copies ahead of each timed replay) and warm us/call, the launch
     shape the library takes, and the algorithmic bytes.  One JSON line.  The command the profiles/ summaries are made with."""
     import torch
@@ -210,7 +210,7 @@ def point(args):
         f = args.point.split(",")
         abl = [float(v.split("=")[1]) for v in f if v.startswith("ablate=")]
         L = si.make_layer(int(f[0]), int(f[1]), int(f[2]), B, dtype="bf16" if "bf16" in f else "f32", ablate_frac=abl[0] if abl else 0.0,
-                          seed=0)
+                          idx_dist="clustered" if "clustered" in f else "uniform", seed=0)
     else:
         L = si.config(args.point, B=B) if args.point == "c3" else si.config(args.point)
         B = L.B if args.point != "c3" else B
@@ -612,7 +612,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-packed", action="store_true", help="forward calls on the W_c / idx arrays alone (no streaming copy)")
     ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane"])
-    ap.add_argument("--point", default=None, help="time one layer: c1|c2|c3|c5 or d_in,d_out,K[,bf16][,ablate=F]; see --batch, --algo, --tuning")
+    ap.add_argument("--point", default=None, help="time one layer: c1|c2|c3|c5 or d_in,d_out,K[,bf16][,ablate=F][,clustered]; see --batch, --algo, --tuning")
     ap.add_argument("--batch", type=int, default=256, help="--point: batch rows (named configurations other than c3 keep their own)")
     ap.add_argument("--tuning", default=None, help="--point: JSON object of srigl_fwd_tuning fields to force a launch shape")
     ap.add_argument("--sweep", action="store_true", help="time every named configuration and the sparsity x batch grid")

@@ -182,6 +182,12 @@ typedef struct {
                                  ROWLANE reads W_c / idx (one load per block of terms instead of two measured no faster);
                                  KLANE reads the copy when a workgroup holds one batch row and W_c / idx when it holds
                                  more (measured faster that way round)                                              */
+    int32_t spread_rows;      /* ROWLANE: how a workgroup's stored rows are shared out among its wavefronts: 1 = consecutive
+                                 rows to a wavefront, 2 = dealt out in the order of their median input column, so that rows
+                                 whose indices cluster in the same columns do not meet in one wavefront (every column chunk
+                                 ends in a barrier and costs what its busiest wavefront costs), 3 = dealt out in the
+                                 workgroups whose rows' medians lie far apart, consecutive in the others; 0 = the library's
+                                 choice (3 from four chunks per row on, else 1)                                          */
 } srigl_fwd_tuning;
 
 /* Same, with the algorithm and launch shape forced (for tests and measurements).  tuning may be
@@ -205,6 +211,7 @@ typedef struct {
     int64_t workgroups;       /* workgroups that do work                                                    */
     int32_t direct_gather;    /* KLANE: 1 = activations gathered from global memory, 0 = rows of x staged in LDS */
     int32_t xcd_order;        /* ROWLANE: 1 or 2 as in srigl_fwd_tuning                                     */
+    int32_t spread_rows;      /* ROWLANE: 1, 2 or 3 as in srigl_fwd_tuning                                  */
 } srigl_fwd_plan;
 srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
                                   int32_t has_active, int32_t has_seg, srigl_fwd_plan* plan);

@@ -46,14 +46,14 @@ class FwdTuning(ctypes.Structure):
     _fields_ = [("rows_per_lane", ctypes.c_int32), ("waves", ctypes.c_int32), ("neurons_per_wave", ctypes.c_int32),
                 ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32), ("rows_per_block", ctypes.c_int32),
                 ("term_slices", ctypes.c_int32), ("direct_gather", ctypes.c_int32), ("xcd_order", ctypes.c_int32),
-                ("terms_from_copy", ctypes.c_int32)]
+                ("terms_from_copy", ctypes.c_int32), ("spread_rows", ctypes.c_int32)]
 
 
 class FwdPlan(ctypes.Structure):
     _fields_ = [("algo", ctypes.c_int32), ("rows_per_lane", ctypes.c_int32), ("term_slices", ctypes.c_int32), ("waves", ctypes.c_int32),
                 ("neurons_per_wave", ctypes.c_int32), ("chunk_cols", ctypes.c_int32), ("lanes_per_neuron", ctypes.c_int32),
                 ("rows_per_block", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("direct_gather", ctypes.c_int32),
-                ("xcd_order", ctypes.c_int32)]
+                ("xcd_order", ctypes.c_int32), ("spread_rows", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:

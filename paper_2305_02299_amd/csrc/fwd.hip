@@ -8,6 +8,7 @@
 // of column active[s], and a virtual row s == n_active fills the tail.
 #include "srigl_internal.h"
 #include <algorithm>
+#include <cmath>
 
 namespace srigl {
 
@@ -465,6 +466,7 @@ constexpr int kRowlaneShortRowOneK = 128;
 constexpr int kRowlaneTwoRowsFourSlicesMinK = 64;   // blocks of 64 terms: measured 14 % slower than 32 x 2 tiles at a fan-in of 39
 
 // npw_cap: the most stored rows per wavefront the choice may take (0: whatever the tile allows)
+static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p);
 static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t, int npw_cap = 0) {
     // Wavefronts per workgroup, when the tuning leaves them open: 16, or 12 (three per SIMD instead of four) when that takes no
     // more rounds of workgroups, chunks or stored rows per wavefront: the same rows spread over more workgroups, each with a
@@ -601,6 +603,21 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
     p.n_groups = (n_slots + p.NW * npw - 1) / (p.NW * npw);
     p.bt_major = by_tiles(p.n_groups) ? 1 : 0;
     p.rounds = (int)rounds(p.n_groups, p.bt_major != 0);
+    // Rows dealt out by median column: 10-16 % faster on layers whose rows cluster around different columns (4096-wide
+    // inputs in 8 or 16 chunks, 2048- and 3072-wide ones at 1024 rows; nothing on 768-wide ones), 0.5-1.5 us per workgroup
+    // otherwise (the keys' latency ahead of the first terms, and the barriers of the test).  The library's choice: from four
+    // chunks on, where a workgroup is estimated to run for 45 us or more (the test then costs under 2 %), and only in
+    // workgroups whose medians lie further apart than those of rows drawn evenly from all columns would (eight standard
+    // deviations of such a median).
+    const int sp = t ? t->spread_rows : 0;
+    if (sp < 0 || sp > 3) return p;
+    const int apart = 2 + (int)(4.0 * a.d_in / std::sqrt((double)std::max(a.K, 1)));
+    // (rows can be dealt out where the kernel reads W_c / idx with aligned loads and a wavefront holds at least two rows)
+    const bool can_spread = npw >= 2 && p.fast && !p.pk && reinterpret_cast<uintptr_t>(a.idx) % 4 == 0;
+    const bool long_groups = (rowlane_estimate_us(a, p) - 2.19) / std::max(1, p.rounds) >= 45.0;
+    if (sp == 0) p.spread = (p.n_chunks >= 4 && can_spread && a.seg != nullptr && long_groups) ? apart : 0;
+    else p.spread = sp == 1 ? 0 : (sp == 2 ? 1 : apart);
+    if (p.spread && !can_spread) return p;
     // the result tile sits behind the activation tile when both fit (no barrier between the last term and the
     // transposed write), else it reuses the activation tile's space
     // (with an active list: plus the column table and the bias of the columns the workgroup writes)
@@ -850,6 +867,7 @@ srigl_status srigl_fwd_plan_query_algo(int32_t B, int32_t d_in, int32_t n_active
         if (!p.ok) return SRIGL_ERR_UNSUPPORTED;
         plan->rows_per_lane = p.R; plan->term_slices = p.H; plan->waves = p.NW; plan->neurons_per_wave = p.NPW;
         plan->chunk_cols = p.C; plan->workgroups = (int64_t)p.n_groups * p.n_btiles; plan->xcd_order = p.bt_major ? 2 : 1;
+        plan->spread_rows = p.spread == 0 ? 1 : (p.spread == 1 ? 2 : 3);
     } else if (algo == SRIGL_FWD_KLANE) {
         const KlanePlan p = plan_klane(a, tuning);
         if (!p.ok) return SRIGL_ERR_UNSUPPORTED;

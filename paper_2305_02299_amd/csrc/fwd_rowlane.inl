@@ -266,13 +266,16 @@ __device__ __forceinline__ void finish_terms(XT w_raw, int i_raw, int n_valid, i
     if (SWZ) ov = real ? ov | (((i_raw >> 2) & 3) << 6) : ov;
 }
 
-template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT, int PKB = 0>
+// Workgroup barrier that orders LDS accesses only: outstanding vector-memory loads stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT, int PKB = 0, bool SPREAD = false>
 __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT* __restrict__ x, int B, int d_in, const XT* __restrict__ W_c,
                                                       const IT* __restrict__ idx, const int32_t* __restrict__ active,
                                                       int n_active, int K, const float* __restrict__ bias, int d_out,
                                                       float* __restrict__ y, const uint16_t* __restrict__ seg, int seg_stride,
                                                       int C, int n_chunks, int n_btiles, int n_groups, int out_off, int act, int bt_major,
-                                                      const unsigned char* __restrict__ pk, int KS, unsigned div_magic) {
+                                                      const unsigned char* __restrict__ pk, int KS, unsigned div_magic, int spread) {
     extern __shared__ float lds[];   // x tile [C + 1][S]; afterwards out tile [BT][NG + 1]
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
@@ -329,12 +332,36 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     // the streaming copy)
     const int t_last = n_active * KS - 1;    // the host guarantees n_active * KS < 2^31 (times the bytes of a term: < 2^32)
 
-    // ---- chunk boundaries: lane j of bnd[i] holds the first term of chunk cb + j for slot s0 + i ----
+    // ---- which stored rows this wavefront takes: NPW consecutive ones, or (spread) every nw-th of the workgroup's rows in
+    // the order of their median input column.  Every chunk ends in a barrier, so a chunk costs what its busiest wavefront
+    // costs; rows whose columns cluster around the same place are heavy in the same chunks, and dealing them out one
+    // to a wavefront evens the chunks out.  Any assignment gives the same sums: a row's terms are still added in order. ----
+    // (dealt out: the rows' positions in the workgroup, a byte each, packed four to a scalar register and unpacked at every
+    // use behind an empty asm statement that keeps the compiler from unpacking them once for the whole kernel: NPW more
+    // live scalar registers spill, and their spill lanes then push vector registers out to scratch)
+    constexpr int PW = (NPW + 3) / 4;
+    unsigned slot_pack[PW];
+#pragma unroll
+    for (int j = 0; j < PW; ++j) {
+        slot_pack[j] = 0u;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) slot_pack[j] |= (unsigned)((wv_id * NPW + 4 * j + b) & 0xff) << (8 * b);
+    }
+    auto slot_of = [&](int i) -> int {
+        if constexpr (SPREAD) {
+            unsigned v = slot_pack[i >> 2];
+            asm volatile("" : "+s"(v));
+            return sg0 + (int)((v >> (8 * (i & 3))) & 0xffu);
+        } else {
+            return s0 + i;
+        }
+    };
+    // ---- chunk boundaries: lane j of bnd[i] holds the first term of chunk cb + j for the i-th row ----
     int bnd[NPW];
     int cb = 0;
 #define SRIGL_LOAD_BOUNDS()                                                                                     \
     _Pragma("unroll") for (int i = 0; i < NPW; ++i) {                                                           \
-        const int s = min(s0 + i, n_active - 1);                                                                \
+        const int s = min(slot_of(i), n_active - 1);                                                              \
         const int j = min(cb + lane, n_chunks);                                                                 \
         int v = (j == 0) ? 0 : K;                                                                               \
         if (seg) v = seg[(unsigned)(s * seg_stride + min(j * segs_per_chunk, seg_stride - 1))];                 \
@@ -404,7 +431,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     {                                                                                                           \
         const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
         _Pragma("unroll") for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)                                          \
-            request_terms<XT, IT, PKB>(W_c, idx, pk, (s0 + (i)) * KS + k0_ + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]); \
+            request_terms<XT, IT, PKB>(W_c, idx, pk, slot_of(i) * KS + k0_ + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]); \
     }
 
     float acc[NPW][R];
@@ -417,11 +444,78 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     // waits for these only, while the term blocks and the boundaries requested behind them are still in flight.
     // Chunk 0 starts at term 0 of every row, so its blocks are requested before the boundaries are known.
     SRIGL_STAGE_LOAD(0)
+    // The keys are read behind the tile's requests, with wave-uniform addresses (scalar loads: they leave the vector-memory
+    // counter alone, which the compiler waits to zero once loads sit behind branches, as the tile's do): a wavefront reads
+    // those of its NPW consecutive rows, lane i keeps the i-th, and the ranking runs while the tile is on its way.
+    if constexpr (SPREAD) {
+        int spread_key = 0x7fffffff;                           // rows past the last stored one sort last
+        int w_lo = 0x7fffffff, w_hi = -1;                      // smallest and largest key of this wavefront's rows
+        const uint32_t* const idx_words = reinterpret_cast<const uint32_t*>(idx);   // (4-byte aligned: the host checks)
+#pragma unroll
+        for (int i = 0; i < NPW; ++i) {
+            if (s0 + i < n_active) {
+                const unsigned e = (unsigned)(s0 + i) * (unsigned)K + (unsigned)(K >> 1);   // n_active * K < 2^31 (host)
+                int k;
+                if constexpr (sizeof(IT) == 4) k = (int)idx_words[e];
+                else k = (int)((idx_words[e >> 1] >> ((e & 1u) * 16u)) & 0xffffu);
+                if (lane == i) spread_key = k;
+                w_lo = min(w_lo, k);
+                w_hi = max(w_hi, k);
+            }
+        }
+        // (barriers that wait for this wavefront's LDS traffic only: a __syncthreads would also wait for the tile's loads,
+        // and the terms could then be requested only after the tile has arrived)
+        // NG <= 128 keys; the NG x NG comparisons of the ranking are split over all threads (part p of the workgroup's
+        // 128-thread parts takes every n_parts-th row to compare with)
+        int* const keys = reinterpret_cast<int*>(lds);
+        int* const ranks = keys + 128;
+        unsigned* const place_words = reinterpret_cast<unsigned*>(keys + 256);   // [nw][PW]: the rows of a wavefront, a byte each
+        int* const wave_lo = keys + 384;
+        int* const wave_hi = keys + 400;
+        const int t = tid & 127, part = tid >> 7, n_parts = max((int)blockDim.x >> 7, 1);
+        if (lane < NPW) keys[wv_id * NPW + lane] = spread_key;
+        if (tid < 128) ranks[tid] = 0;
+        if (lane == 0) { wave_lo[wv_id] = w_lo; wave_hi[wv_id] = w_hi; }
+        lds_barrier();
+        // spread >= 2: only where the medians of this workgroup's rows lie more than spread - 2 columns apart (rows drawn
+        // evenly from all columns have their medians close together, and nothing to gain); every wavefront takes the
+        // same decision from the same numbers
+        bool deal = true;
+        if (spread >= 2) {
+            int lo = 0x7fffffff, hi = -1;
+            for (int w = 0; w < nw; ++w) {
+                lo = min(lo, wave_lo[w]);
+                hi = max(hi, wave_hi[w]);
+            }
+            deal = hi >= 0 && hi - lo > spread - 2;
+        }
+        if (deal) {
+            if (t < NG && part < n_parts) {
+                const int mine = keys[t];
+                int below = 0;
+#pragma unroll 8
+                for (int u = part; u < NG; u += n_parts) {
+                    const int ku = keys[u];
+                    below += (ku < mine || (ku == mine && u < t)) ? 1 : 0;
+                }
+                atomicAdd(&ranks[t], below);
+            }
+            lds_barrier();
+            if (tid < NG) {
+                const int rank = ranks[tid];                   // -> wavefront rank % nw, its (rank / nw)-th row
+                reinterpret_cast<unsigned char*>(place_words)[(rank % nw) * (PW * 4) + rank / nw] = (unsigned char)tid;
+            }
+            lds_barrier();
+#pragma unroll
+            for (int j = 0; j < PW; ++j) slot_pack[j] = (unsigned)__builtin_amdgcn_readfirstlane((int)place_words[wv_id * PW + j]);
+        }
+        lds_barrier();                                         // the tile is written over this space next
+    }
 #pragma unroll
     for (int i = 0; i < NPW; ++i)
 #pragma unroll
         for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)
-            request_terms<XT, IT, PKB>(W_c, idx, pk, (s0 + i) * KS + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]);
+            request_terms<XT, IT, PKB>(W_c, idx, pk, slot_of(i) * KS + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]);
     SRIGL_LOAD_BOUNDS()
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column
     SRIGL_STAGE_STORE()
@@ -435,7 +529,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
 #pragma unroll
         for (int i = 0; i < NPW; ++i) {
             k0n[i] = __builtin_amdgcn_readlane(bnd[i], c - cb);
-            nn[i] = (s0 + i < n_active) ? __builtin_amdgcn_readlane(bnd[i], c - cb + 1) - k0n[i] : 0;
+            nn[i] = (slot_of(i) < n_active) ? __builtin_amdgcn_readlane(bnd[i], c - cb + 1) - k0n[i] : 0;
         }
         if (more && c + 2 - cb > kWave - 1) { cb = c + 1; SRIGL_LOAD_BOUNDS() }   // boundaries c+1, c+2 stay in the register
 #pragma unroll
@@ -454,7 +548,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                 walk_groups<R, KPRE, kReadAhead>(acc[i], pw, po, xb, lanepart, (n_terms + H - 1) / H);
                 // long ranges: the remaining blocks, one at a time, each requested one block ahead
                 if (n_terms > KPRE * TB) {
-                    const int row = (s0 + i) * KS + k0n[i];
+                    const int row = slot_of(i) * KS + k0n[i];
                     XT wr;
                     int ir;
                     request_terms<XT, IT, PKB>(W_c, idx, pk, row + KPRE * TB, lofs, t_last, wr, ir);
@@ -492,7 +586,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             float v = acc[i][r];
             if constexpr (H >= 2) v += __shfl_xor(v, LR, kWave);        // the slices hold partial sums of the same rows
             if constexpr (H >= 4) v += __shfl_xor(v, 2 * LR, kWave);
-            if (lane < LR) out[(rowl * R + r) * OS + wv_id * NPW + i] = v;
+            if (lane < LR) out[(rowl * R + r) * OS + (slot_of(i) - sg0)] = v;
         }
     __syncthreads();
 
@@ -586,9 +680,15 @@ static inline unsigned rowlane_decode_multiplier(long long blocks, int d) {
     return (unsigned)(((1ULL << 32) + (unsigned)d - 1) / (unsigned)d);
 }
 
-template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT, int PKB = 0>
+template <int R, int H, int NPW, int KPRE, typename XT, bool FAST, typename IT, int PKB = 0, bool SPREAD = false>
 static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hipStream_t st) {
-    auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST, IT, PKB>;
+    // (the kernel that deals the rows out is a second instance: with the assignment in registers that the compiler cannot
+    // fold into addresses, the consecutive case measured 3-8 % slower inside one kernel that can do both)
+    if constexpr (!SPREAD && FAST && PKB == 0 && NPW >= 2) {
+        if (p.spread) return launch_rowlane_f<R, H, NPW, KPRE, XT, FAST, IT, PKB, true>(a, p, st);
+    }
+    if (!SPREAD && p.spread) return SRIGL_ERR_UNSUPPORTED;
+    auto kern = k_fwd_rowlane<R, H, NPW, KPRE, XT, FAST, IT, PKB, SPREAD>;
     static LdsLimit lds_limit;
     if (lds_limit.ensure(kern, p.lds) != SRIGL_OK) return SRIGL_ERR_HIP;
     const long long blocks = p.bt_major ? 8LL * ((p.n_btiles + 7) / 8) * p.n_groups : 8LL * ((p.n_groups + 7) / 8) * p.n_btiles;
@@ -596,7 +696,7 @@ static srigl_status launch_rowlane_f(const FwdArgs& a, const RowlanePlan& p, hip
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(p.NW * kWave), p.lds, st, (const XT*)a.x, a.B, a.d_in, (const XT*)a.W_c,
                        (const IT*)a.idx, a.active, a.n_active, a.K, a.bias, a.d_out, a.y, a.seg, a.seg_stride, p.C, p.n_chunks, p.n_btiles,
                        p.n_groups, p.out_off, a.act, p.bt_major, static_cast<const unsigned char*>(a.packed), PKB ? (a.K + 3) / 4 * 4 : a.K,
-                       rowlane_decode_multiplier(blocks, p.bt_major ? p.n_groups : p.n_btiles));
+                       rowlane_decode_multiplier(blocks, p.bt_major ? p.n_groups : p.n_btiles), p.spread);
     return hip_ok(hipGetLastError());
 }
 

@@ -102,6 +102,8 @@ struct RowlanePlan {
     int out_off;  // word offset of the result tile in LDS (0: it reuses the activation tile after a barrier)
     bool fast;   // x rows allow aligned 4-element loads and d_in is a multiple of 16
     bool pk;     // the terms are read from the streaming copy (forced through the tuning; the default reads W_c / idx)
+    int spread;  // 0: a wavefront takes consecutive stored rows; 1: every NW-th of the workgroup's rows in the order of their median
+                 // columns; 2 + t: the same in workgroups whose rows' medians lie more than t columns apart
     bool ok;
 };
 constexpr int kSpanCap = 1024;     // output columns (stored and ablated) a workgroup of the batched kernel writes through its column table

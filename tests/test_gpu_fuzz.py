@@ -71,6 +71,21 @@ def test_random_layer_every_algorithm(d_in, d_out, K, B, abl, dtype, seed):
                 continue
             gate(host(y), y_ref, S, TOL_BF16 if dtype == "bf16" else TOL_F32)
             shapes += 1
+        # the same tile with a workgroup's stored rows dealt out among its wavefronts (always; where their medians lie apart)
+        for spread_rows in (2, 3):
+            y = torch.full((B, d_out), 3.0e38, dtype=torch.float32, device="cuda")
+            try:
+                B_.srigl_condensed_linear_fwd(dev(xsrc), B, d_in, layer.W_c, layer.idx, layer.active, n, K, layer.bias, d_out, y,
+                                              layer.seg, algo=B_.FWD_ROWLANE,
+                                              tuning=dict(rows_per_lane=rows_per_lane, term_slices=term_slices, neurons_per_wave=2 + seed % 2,
+                                                          waves=(4, 7, 16)[seed % 3], spread_rows=spread_rows))
+            except B_.SriglError as e:
+                assert e.status == B_.ERR_UNSUPPORTED
+                continue
+            yh = host(y)
+            gate(yh, y_ref, S, TOL_BF16 if dtype == "bf16" else TOL_F32)
+            if len(ablated):
+                assert np.array_equal(yh[:, ablated].view(np.uint32), np.tile(L.bias[ablated], (B, 1)).view(np.uint32))
     assert shapes >= 2 or d_in % 16 != 0
 
 

@@ -403,6 +403,39 @@ def test_batched_kernel_either_xcd_order(shape, xcd_order):
     assert worst < 2e-6
 
 
+@pytest.mark.parametrize("dist", ["uniform", "clustered"])
+@pytest.mark.parametrize("shape", [(768, 300, 77, 300, dict(neurons_per_wave=3)), (2048, 1000, 205, 200, dict(rows_per_lane=2, term_slices=1, neurons_per_wave=6)),
+                                   (4096, 530, 64, 130, dict(rows_per_lane=1, term_slices=2, waves=12, neurons_per_wave=2)),
+                                   (1024, 96, 64, 530, dict(chunk_cols=256, neurons_per_wave=2)),
+                                   (320, 130, 40, 70, dict(rows_per_lane=4, term_slices=4, neurons_per_wave=2, chunk_cols=64))])
+@pytest.mark.parametrize("mode", [2, 3])
+def test_batched_kernel_rows_dealt_out_by_median_column(shape, dist, mode):
+    """A workgroup's stored rows shared out among its wavefronts in the order of their median column instead of in runs of
+    consecutive rows: same sums (a row's terms are added in the same order), with a last workgroup that holds fewer rows
+    than places, ablated columns between the stored ones, one to six rows per wavefront and several chunks per row."""
+    d_in, d_out, K, B, tn = shape
+    L = si.make_layer(d_in, d_out, K, B, ablate_frac=0.2, seed=d_in + B, idx_dist=dist)
+    tuning = dict(tn or {}, spread_rows=mode)
+    assert B_.srigl_fwd_plan_query(B, d_in, int(L.mask.any(1).sum()), K, d_out, B_.F32, True, True, algo=B_.FWD_ROWLANE, tuning=tuning)["spread_rows"] == mode
+    worst = check_layer(L, B_.FWD_ROWLANE, tuning)
+    assert worst < 2e-6
+
+
+def test_rows_are_not_dealt_out_one_to_a_wavefront_or_from_the_copy():
+    """One stored row per wavefront leaves nothing to deal out, and the kernel that reads the streaming copy keeps consecutive
+    rows: both refuse the forced setting; the library's own choice deals rows out from four chunks per row on where a workgroup
+    runs long enough for the test of the medians not to show."""
+    L = si.make_layer(320, 130, 40, 70, ablate_frac=0.2, seed=1)
+    assert check_layer(L, B_.FWD_ROWLANE, dict(neurons_per_wave=1, spread_rows=2), unsupported_ok=True) is None
+    assert check_layer(L, B_.FWD_ROWLANE, dict(terms_from_copy=1, spread_rows=2), unsupported_ok=True, packed=True) is None
+    q = lambda B, d_in, n, K, **kw: B_.srigl_fwd_plan_query(B, d_in, n, K, n, kw.pop("dtype", B_.F32), False, True, algo=B_.FWD_ROWLANE, **kw)
+    assert q(2048, 4096, 16384, 205, dtype=B_.BF16)["spread_rows"] == 3      # 16 chunks of 256 columns
+    assert q(1024, 4096, 4096, 205)["spread_rows"] == 3                      # 16 chunks, ~65 us per workgroup
+    assert q(256, 4096, 4096, 205)["spread_rows"] == 1                       # 8 chunks of 512, but ~35 us per workgroup
+    assert q(256, 768, 3072, 77)["spread_rows"] == 1                         # 2 chunks
+    assert q(1024, 768, 3072, 77)["spread_rows"] == 1                        # 3 chunks
+
+
 @pytest.mark.parametrize("abl,B", [(0.3, 70), (0.7, 200), (0.9, 64), (0.97, 300), (0.995, 33)])
 def test_batched_kernel_writes_ablated_columns_between_stored_ones(abl, B):
     """Runs of output columns per workgroup from a few dozen (30 % ablated) to beyond the column table (99.5 %: the per-lane
