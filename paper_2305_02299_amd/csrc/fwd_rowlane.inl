@@ -336,22 +336,21 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     // the order of their median input column.  Every chunk ends in a barrier, so a chunk costs what its busiest wavefront
     // costs; rows whose columns cluster around the same place are heavy in the same chunks, and dealing them out one
     // to a wavefront evens the chunks out.  Any assignment gives the same sums: a row's terms are still added in order. ----
-    // (dealt out: the rows' positions in the workgroup, a byte each, packed four to a scalar register and unpacked at every
-    // use behind an empty asm statement that keeps the compiler from unpacking them once for the whole kernel: NPW more
-    // live scalar registers spill, and their spill lanes then push vector registers out to scratch)
-    constexpr int PW = (NPW + 3) / 4;
-    unsigned slot_pack[PW];
+    // (with six or eight rows per wavefront every use reads the row through an empty asm statement, which keeps the compiler
+    // from deriving each row's offsets once for the whole kernel: those live scalar registers spill, and their spill lanes
+    // then push vector registers out to scratch; 2-5 % on the shapes that take six or eight rows)
+    int slot[NPW];
 #pragma unroll
-    for (int j = 0; j < PW; ++j) {
-        slot_pack[j] = 0u;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) slot_pack[j] |= (unsigned)((wv_id * NPW + 4 * j + b) & 0xff) << (8 * b);
-    }
+    for (int i = 0; i < NPW; ++i) slot[i] = s0 + i;
     auto slot_of = [&](int i) -> int {
         if constexpr (SPREAD) {
-            unsigned v = slot_pack[i >> 2];
+            int v = slot[i];
+            if constexpr (NPW >= 6) asm volatile("" : "+s"(v));
+            return v;
+        } else if constexpr (NPW >= 6) {
+            int v = s0;
             asm volatile("" : "+s"(v));
-            return sg0 + (int)((v >> (8 * (i & 3))) & 0xffu);
+            return v + i;
         } else {
             return s0 + i;
         }
@@ -361,7 +360,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     int cb = 0;
 #define SRIGL_LOAD_BOUNDS()                                                                                     \
     _Pragma("unroll") for (int i = 0; i < NPW; ++i) {                                                           \
-        const int s = min(slot_of(i), n_active - 1);                                                              \
+        const int s = min(slot_of(i), n_active - 1);                                                            \
         const int j = min(cb + lane, n_chunks);                                                                 \
         int v = (j == 0) ? 0 : K;                                                                               \
         if (seg) v = seg[(unsigned)(s * seg_stride + min(j * segs_per_chunk, seg_stride - 1))];                 \
@@ -469,13 +468,14 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         // 128-thread parts takes every n_parts-th row to compare with)
         int* const keys = reinterpret_cast<int*>(lds);
         int* const ranks = keys + 128;
-        unsigned* const place_words = reinterpret_cast<unsigned*>(keys + 256);   // [nw][PW]: the rows of a wavefront, a byte each
+        int* const place_row = keys + 256;                     // row of the workgroup per place (wavefront, its i-th row)
         int* const wave_lo = keys + 384;
         int* const wave_hi = keys + 400;
         const int t = tid & 127, part = tid >> 7, n_parts = max((int)blockDim.x >> 7, 1);
         if (lane < NPW) keys[wv_id * NPW + lane] = spread_key;
         if (tid < 128) ranks[tid] = 0;
         if (lane == 0) { wave_lo[wv_id] = w_lo; wave_hi[wv_id] = w_hi; }
+        if (tid >= nw && tid < 16) { wave_lo[tid] = 0x7fffffff; wave_hi[tid] = -1; }   // (all 16 entries are read below)
         lds_barrier();
         // spread >= 2: only where the medians of this workgroup's rows lie more than spread - 2 columns apart (rows drawn
         // evenly from all columns have their medians close together, and nothing to gain); every wavefront takes the
@@ -483,9 +483,12 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         bool deal = true;
         if (spread >= 2) {
             int lo = 0x7fffffff, hi = -1;
-            for (int w = 0; w < nw; ++w) {
-                lo = min(lo, wave_lo[w]);
-                hi = max(hi, wave_hi[w]);
+#pragma unroll
+            for (int w = 0; w < 16; w += 4) {                  // four 16-byte reads per array, all in flight together
+                const int4 l4 = *reinterpret_cast<const int4*>(wave_lo + w);
+                const int4 h4 = *reinterpret_cast<const int4*>(wave_hi + w);
+                lo = min(min(lo, min(l4.x, l4.y)), min(l4.z, l4.w));
+                hi = max(max(hi, max(h4.x, h4.y)), max(h4.z, h4.w));
             }
             deal = hi >= 0 && hi - lo > spread - 2;
         }
@@ -503,11 +506,11 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
             lds_barrier();
             if (tid < NG) {
                 const int rank = ranks[tid];                   // -> wavefront rank % nw, its (rank / nw)-th row
-                reinterpret_cast<unsigned char*>(place_words)[(rank % nw) * (PW * 4) + rank / nw] = (unsigned char)tid;
+                place_row[(rank % nw) * NPW + rank / nw] = tid;
             }
             lds_barrier();
 #pragma unroll
-            for (int j = 0; j < PW; ++j) slot_pack[j] = (unsigned)__builtin_amdgcn_readfirstlane((int)place_words[wv_id * PW + j]);
+            for (int i = 0; i < NPW; ++i) slot[i] = sg0 + __builtin_amdgcn_readfirstlane(place_row[wv_id * NPW + i]);
         }
         lds_barrier();                                         // the tile is written over this space next
     }
