@@ -220,7 +220,7 @@ def point(args):
     algo = {None: None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE}[args.algo]
     tuning = json.loads(args.tuning) if args.tuning else None
     if tuning is not None and algo is None:
-        algo = B_.FWD_ROWLANE if any(k in tuning for k in ("rows_per_lane", "term_slices", "waves", "neurons_per_wave", "chunk_cols", "terms_from_copy")) \
+        algo = B_.FWD_ROWLANE if any(k in tuning for k in ("rows_per_lane", "term_slices", "waves", "neurons_per_wave", "chunk_cols", "terms_from_copy", "xcd_order", "spread_rows")) \
             else B_.FWD_KLANE
     nbytes = algorithmic_bytes(layer.n_active, L.K, B, L.d_in, L.d_out, 2 if bf16 else 4)
     n_rot = min(max(2, -(-2 * CACHE_BYTES // nbytes)), 400)

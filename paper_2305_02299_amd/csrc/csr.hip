@@ -119,7 +119,8 @@ static srigl_status launch_csr(const void* x, int B, int d_in, const void* value
     if (gy > 65535) return SRIGL_ERR_UNSUPPORTED;
     // rows per workgroup: one pass of all groups, more when that still leaves > 8 (gathering: 32) workgroups per CU
     int rows_per_wg = groups;
-    while ((long long)((d_out + rows_per_wg - 1) / rows_per_wg) * gy > 256 * (GATHER ? 32 : 8)) rows_per_wg += groups;
+    // (a batch of more row blocks than that keeps the limit out of reach: one pass over all rows per workgroup then)
+    while (rows_per_wg < d_out && (long long)((d_out + rows_per_wg - 1) / rows_per_wg) * gy > 256 * (GATHER ? 32 : 8)) rows_per_wg += groups;
     const unsigned gx = (unsigned)((d_out + rows_per_wg - 1) / rows_per_wg);
     hipLaunchKernelGGL(kern, dim3(gx, (unsigned)gy), dim3(256), lds, st, (const XT*)x, B, d_in, (const XT*)values, col_idx, row_ptr,
                        bias, d_out, y, log2L, rows_per_wg, act);

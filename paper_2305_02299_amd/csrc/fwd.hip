@@ -405,7 +405,8 @@ static KlanePlan plan_klane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     int rows_per_wg = groups;
     // (the gathering form has no staging to share between passes: it takes more of them only beyond 32 workgroups per CU)
     const long long max_wgs = p.direct ? 256 * 32 : 256 * 8;
-    while ((long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB) > max_wgs) rows_per_wg += groups;
+    // (a batch of more row blocks than that limit keeps it out of reach: one pass over all stored rows per workgroup then)
+    while (rows_per_wg < n_slots && (long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB) > max_wgs) rows_per_wg += groups;
     p.L = L; p.RB = RB; p.rows_per_wg = rows_per_wg;
     p.workgroups = (long long)((n_slots + rows_per_wg - 1) / rows_per_wg) * ((a.B + RB - 1) / RB);
     p.ok = true;
@@ -583,14 +584,14 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
         double best = -1.0;
         for (int ci = 0; ci < 6; ++ci) {
             const int c = cand[ci];
-            if (c > rowlane_max_npw(p.R, p.H) || (c == 8 && !a.x_bf16)) break;   // (eight rows of fp32 terms spill registers)
+            if (c > rowlane_max_npw(p.R, p.H)) break;
             if (npw_cap && c > npw_cap) break;
             const double cost = shape_cost(c);
             if (best < 0 || cost < best) { best = cost; npw = c; }
         }
     }
     if (npw != 1 && npw != 2 && npw != 3 && npw != 4 && npw != 6 && npw != 8) return p;
-    if (npw > rowlane_max_npw(p.R, p.H) || (npw == 8 && !a.x_bf16)) return p;
+    if (npw > rowlane_max_npw(p.R, p.H)) return p;
     p.NPW = npw;
     p.cost = shape_cost(npw);
     p.KPRE = rowlane_kpre_rh(npw, p.R, p.H);

@@ -742,7 +742,7 @@ static srigl_status launch_rowlane_r(const FwdArgs& a, const RowlanePlan& p, hip
         case 3: return launch_rowlane_k<R, H, 3, XT, IT>(a, p, st);
         case 4: if constexpr (MAXN >= 4) return launch_rowlane_k<R, H, 4, XT, IT>(a, p, st); else break;
         case 6: if constexpr (MAXN >= 6) return launch_rowlane_k<R, H, 6, XT, IT>(a, p, st); else break;
-        case 8: if constexpr (MAXN >= 8 && sizeof(XT) == 2) return launch_rowlane_k<R, H, 8, XT, IT>(a, p, st); else break;
+        case 8: if constexpr (MAXN >= 8) return launch_rowlane_k<R, H, 8, XT, IT>(a, p, st); else break;
         default: break;
     }
     return SRIGL_ERR_UNSUPPORTED;

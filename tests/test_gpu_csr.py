@@ -50,6 +50,23 @@ def test_unstructured_masks(B_, shape, act):
     gate(host(y), oracle.activate(pre, act), 1.2 * S, TOL_F32)
 
 
+def test_batch_of_more_row_blocks_than_the_workgroup_limit(B_):
+    """2100 rows of a 2048-wide input are staged one row per workgroup: more row blocks than the 2048 workgroups the launch
+    is held to, so every workgroup walks all rows of the matrix."""
+    d_in, d_out, B = 2048, 24, 2100
+    rng = np.random.default_rng(9)
+    W = rng.normal(0, 0.1, (d_out, d_in)).astype(np.float32)
+    mask = (rng.random((d_out, d_in)) < 0.02).astype(np.uint8)
+    x = rng.normal(size=(B, d_in)).astype(np.float32)
+    bias = rng.normal(0, 0.1, d_out).astype(np.float32)
+    vals, cols, ptr = csr_of(W, mask)
+    y = torch.full((B, d_out), float("nan"), device="cuda")
+    B_.srigl_csr_linear_fwd(dev(x), B, d_in, dev(vals), dev(cols), dev(ptr), dev(bias), d_out, y)
+    torch.cuda.synchronize()
+    ref, S = oracle.csr_fwd(x, vals, cols, ptr, bias, want_scale=True)
+    gate(host(y), ref, 1.2 * S, TOL_F32)
+
+
 @pytest.mark.parametrize("B", [1, 16, 256])
 def test_constant_fan_in_mask_agrees_with_the_condensed_forward(B_, B):
     L = si.make_layer(768, 512, 77, B, ablate_frac=0.1, seed=3)

@@ -392,6 +392,16 @@ def test_small_batch_kernel_gathered_and_staged_activations(B, rb, gather, dtype
     assert worst < (TOL_BF16 if dtype == "bf16" else 2e-6)
 
 
+@pytest.mark.parametrize("gather", [1, 2])
+def test_small_batch_kernel_forced_at_a_batch_beyond_its_workgroup_limit(gather):
+    """More row blocks than the 2048 (staged) or 8192 (gathered) workgroups the launch is held to: one workgroup per row block
+    that walks all stored rows."""
+    B = 2100 if gather == 2 else 8300
+    L = si.make_layer(2048, 24, 40, B, ablate_frac=0.2, seed=B)
+    worst = check_layer(L, B_.FWD_KLANE, dict(direct_gather=gather, rows_per_block=1))
+    assert worst < 2e-6
+
+
 @pytest.mark.parametrize("xcd_order", [1, 2])
 @pytest.mark.parametrize("shape", [(768, 300, 77, 300), (3072, 200, 307, 200), (320, 130, 40, 1100), (2048, 96, 64, 530)])
 def test_batched_kernel_either_xcd_order(shape, xcd_order):

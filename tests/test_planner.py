@@ -138,6 +138,18 @@ def test_fallbacks():
         B_.srigl_fwd_plan_query(4, 8, 9, 3, 8)                      # more stored neurons than neurons
 
 
+def test_forced_small_batch_kernel_at_batches_beyond_its_workgroup_limit():
+    """The small-batch kernel gives a workgroup more stored rows until the launch has at most 2048 (staged) or 8192 (gathered)
+    workgroups; a batch with more row blocks than that takes one workgroup per row block, every stored row in it."""
+    for B, d_in, rb in ((2049, 2048, 1), (4096, 2048, 1), (65535, 2048, 1), (4100, 768, 2), (20000, 768, 2)):
+        p = plan(B, d_in, 300, 40, algo=B_.FWD_KLANE, tuning=dict(direct_gather=2))
+        assert p["rows_per_block"] == rb and p["workgroups"] == -(-B // rb), (B, d_in, p)
+    p = plan(9000, 2048, 300, 40, algo=B_.FWD_KLANE, tuning=dict(direct_gather=1, rows_per_block=1))
+    assert p["workgroups"] == 9000
+    with pytest.raises(B_.SriglError):
+        plan(65536, 2048, 300, 40, algo=B_.FWD_KLANE, tuning=dict(rows_per_block=1))   # the batch is the grid's second dimension
+
+
 def test_every_plan_is_one_the_kernels_accept():
     """Seeded random sizes: whatever the estimates choose is a launch shape inside the kernels' documented limits, and asking
     for the plan of that algorithm with that shape forced gives the same plan back."""
