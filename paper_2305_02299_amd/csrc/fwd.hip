@@ -584,7 +584,8 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
         double best = -1.0;
         for (int ci = 0; ci < 6; ++ci) {
             const int c = cand[ci];
-            if (c > rowlane_max_npw(p.R, p.H)) break;
+            // (six or eight rows with term slices, eight with one row per lane: only as the planner's last shapes)
+            if (c > rowlane_max_npw(p.R, p.H) || (npw_cap < 8 && ((p.R == 2 && p.H >= 2 && c > 4) || (p.R == 1 && c > 6)))) break;
             if (npw_cap && c > npw_cap) break;
             const double cost = shape_cost(c);
             if (best < 0 || cost < best) { best = cost; npw = c; }
@@ -642,7 +643,8 @@ static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
     const double rounds = std::max(1, p.rounds);
     const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
     // (six or eight rows per wavefront keep one block of terms per row: the steps measured 0-40 % slower, longest on long segments)
-    const double many_rows = (p.R == 2 && p.H == 1 && p.NPW >= 6) ? 1.15 : 1.0;
+    // (the same in two slices: 4096 -> 4096 at B = 512 measured 63.5 us with eight rows, 73.1 with four)
+    const double many_rows = (p.R == 2 && p.NPW >= 6) ? (p.H == 1 ? 1.15 : 1.2) : 1.0;
     const double per_step = many_rows * (p.R == 2 ? (p.H == 4 ? (a.K < kRowlaneShortRowK ? 0.0345 : 0.0375) : (p.H == 2 ? 0.0337 : 0.0303)) : (p.H == 1 ? 0.0240 : (p.H == 2 ? 0.0279 : 0.0368)));
     const double terms = (double)a.n_active * a.K;
     return 2.19 + rounds * (1.38 * p.n_chunks + 5.90e-6 * BT * a.d_in * 4.0 + per_step * steps + 1.45e-4 * BT * p.NW * p.NPW * 4.0) +
@@ -663,16 +665,20 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     // rows per lane, term slices; a later shape must be 5 % ahead of an earlier one (the estimates are good to about that)
     // (the last entry: 128-row tiles with six or eight stored rows per wavefront, half the workgroups of the four-row form;
     // ahead at 1024 rows and more, where it saves a round of workgroups: 768 -> 3072 at B = 1024 36.4 -> 33.0 us)
-    static const int shapes[7][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}, {2, 2}, {2, 4}, {2, 1}};
-    for (int i = 0; i < 7; ++i) {
-        if (shapes[i][0] == 2 && a.K < kRowlaneTwoRowsMinK) continue;
+    // (and the 64-row two-slice tile with six or eight: ahead where that still fills the compute units, 4096 -> 4096 at
+    // B = 384 / 512 68.3 / 69.4 -> 62.2 / 63.5 us, 1024 -> 4096 at B = 512 28.8 -> 26.5)
+    static const int shapes[8][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}, {2, 2}, {2, 4}, {2, 1}, {2, 2}};
+    for (int i = 0; i < 8; ++i) {
+        // (two rows per lane need rows long enough for the term loop to matter; with six or eight rows per wavefront they are
+        // ahead from shorter ones: 1024 -> 4096 K = 26 at B = 1024 39.6 -> 28.8 us, 768 -> 3072 K = 16 22.3 -> 18.3)
+        if (shapes[i][0] == 2 && a.K < (i >= 6 ? 16 : kRowlaneTwoRowsMinK)) continue;
         if (shapes[i][0] == 2 && shapes[i][1] == 4 && a.K < kRowlaneTwoRowsFourSlicesMinK) continue;
         srigl_fwd_tuning shape{};
         if (t) shape = *t;
         shape.rows_per_lane = shapes[i][0];
         shape.term_slices = shapes[i][1];
-        const RowlanePlan p = plan_rowlane_with(a, &shape, i == 1 ? 4 : 0);
-        if (!p.ok || (i == 6 && p.NPW <= 4)) continue;
+        const RowlanePlan p = plan_rowlane_with(a, &shape, i == 1 ? 4 : (i >= 6 ? 8 : 0));
+        if (!p.ok || (i >= 6 && p.NPW <= 4)) continue;
         const double us = rowlane_estimate_us(a, p);
         if (!best.ok || us < 0.95 * best_us) { best = p; best_us = us; }
     }

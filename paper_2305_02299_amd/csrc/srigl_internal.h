@@ -121,9 +121,9 @@ constexpr bool rowlane_swizzled(int R) { return R == 4; }
 constexpr int kStageUnits = 8;   // 16x16 staging units a wavefront holds in registers per chunk
 constexpr int kBlock = 16;       // terms per vector load of W_c / idx (one DPP row)
 constexpr int rowlane_max_threads(int) { return 1024; }
-// stored rows per wavefront the register budget allows without spilling (one-slice tiles of two rows per lane keep one
-// block of terms per row in registers and take up to 8 rows: half the workgroups stage the same x)
-constexpr int rowlane_max_npw(int R, int H = 2) { return R == 1 ? 6 : (R == 2 ? (H == 1 ? 8 : 4) : 3); }
+// stored rows per wavefront the register budget allows without spilling (from six rows on a wavefront keeps one block of
+// terms per row in registers; with four rows per lane the 16-byte reads leave room for three)
+constexpr int rowlane_max_npw(int R, int H = 2) { return R == 4 ? 3 : 8; }
 // blocks of 16 terms per (stored row, chunk) kept in registers, by stored rows per wavefront
 constexpr int rowlane_kpre(int npw) { return npw <= 3 ? 3 : (npw <= 4 ? 2 : 1); }
 // (two rows per lane with term slices: blocks are 32 or 64 terms, so fewer of them cover the same part of a row)
