@@ -135,6 +135,15 @@ def test_no_bias_and_no_seg(algo):
     {"term_slices": 4, "waves": 8, "neurons_per_wave": 6},
     {"term_slices": 4, "waves": 16, "neurons_per_wave": 2, "chunk_cols": 128},
     {"term_slices": 4, "waves": 2, "neurons_per_wave": 1, "chunk_cols": 64},
+    {"rows_per_lane": 1, "term_slices": 1, "waves": 16, "neurons_per_wave": 8, "chunk_cols": 128},
+    {"rows_per_lane": 1, "term_slices": 2, "waves": 3, "neurons_per_wave": 8},
+    {"rows_per_lane": 1, "term_slices": 4, "waves": 16, "neurons_per_wave": 8, "chunk_cols": 256},
+    {"rows_per_lane": 2, "term_slices": 1, "waves": 16, "neurons_per_wave": 8, "chunk_cols": 128},
+    {"rows_per_lane": 2, "term_slices": 1, "waves": 5, "neurons_per_wave": 6, "chunk_cols": 64},
+    {"rows_per_lane": 2, "term_slices": 2, "waves": 16, "neurons_per_wave": 8},
+    {"rows_per_lane": 2, "term_slices": 2, "waves": 7, "neurons_per_wave": 6, "chunk_cols": 128},
+    {"rows_per_lane": 2, "term_slices": 4, "waves": 16, "neurons_per_wave": 6},
+    {"rows_per_lane": 2, "term_slices": 4, "waves": 12, "neurons_per_wave": 8, "chunk_cols": 192},
 ])
 def test_rowlane_launch_shapes(tuning):
     for (d_in, d_out, K, B, abl) in ((768, 300, 77, 300, 0.1), (3072, 96, 307, 70, 0.3), (1001, 64, 100, 257, 0.0),
@@ -188,6 +197,10 @@ def test_klane_launch_shapes_through_the_streaming_copy(tuning):
     {"rows_per_lane": 4, "term_slices": 4, "waves": 16, "neurons_per_wave": 3},
     {"term_slices": 2, "waves": 8, "neurons_per_wave": 6, "chunk_cols": 192},
     {"term_slices": 4, "waves": 16, "neurons_per_wave": 2, "chunk_cols": 128},
+    {"rows_per_lane": 1, "term_slices": 1, "waves": 16, "neurons_per_wave": 8, "chunk_cols": 128},
+    {"rows_per_lane": 2, "term_slices": 1, "waves": 16, "neurons_per_wave": 8, "chunk_cols": 128},
+    {"rows_per_lane": 2, "term_slices": 2, "waves": 7, "neurons_per_wave": 6, "chunk_cols": 128},
+    {"rows_per_lane": 2, "term_slices": 4, "waves": 12, "neurons_per_wave": 8, "chunk_cols": 192},
 ])
 def test_rowlane_launch_shapes_through_the_streaming_copy(tuning):
     """The batched kernel with its terms read from the streaming copy (one load per block of terms): every tile shape, fp32
@@ -429,6 +442,17 @@ def test_batched_kernel_rows_dealt_out_by_median_column(shape, dist, mode):
     assert B_.srigl_fwd_plan_query(B, d_in, int(L.mask.any(1).sum()), K, d_out, B_.F32, True, True, algo=B_.FWD_ROWLANE, tuning=tuning)["spread_rows"] == mode
     worst = check_layer(L, B_.FWD_ROWLANE, tuning)
     assert worst < 2e-6
+
+
+@pytest.mark.parametrize("tuning", [dict(rows_per_lane=2, term_slices=1, neurons_per_wave=8), dict(rows_per_lane=2, term_slices=2, neurons_per_wave=8),
+                                    dict(rows_per_lane=1, term_slices=1, neurons_per_wave=8), dict(rows_per_lane=2, term_slices=4, neurons_per_wave=6)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_six_and_eight_rows_per_wavefront_with_and_without_dealing(tuning, dtype):
+    """Clustered rows in several chunks, a last workgroup that holds fewer rows than places, both storage types."""
+    L = si.make_layer(2048, 700, 102, 150, ablate_frac=0.25, seed=12, dtype=dtype, idx_dist="clustered")
+    for mode in (1, 2, 3):
+        worst = check_layer(L, B_.FWD_ROWLANE, dict(tuning, chunk_cols=256, spread_rows=mode))
+        assert worst < (TOL_BF16 if dtype == "bf16" else 2e-6)
 
 
 def test_rows_are_not_dealt_out_one_to_a_wavefront_or_from_the_copy():
