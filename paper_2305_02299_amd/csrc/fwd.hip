@@ -670,8 +670,8 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     static const int shapes[8][2] = {{1, 1}, {2, 1}, {1, 2}, {1, 4}, {2, 2}, {2, 4}, {2, 1}, {2, 2}};
     for (int i = 0; i < 8; ++i) {
         // (two rows per lane need rows long enough for the term loop to matter; with six or eight rows per wavefront they are
-        // ahead from shorter ones: 1024 -> 4096 K = 26 at B = 1024 39.6 -> 28.8 us, 768 -> 3072 K = 16 22.3 -> 18.3)
-        if (shapes[i][0] == 2 && a.K < (i >= 6 ? 16 : kRowlaneTwoRowsMinK)) continue;
+        // ahead at any fan-in: 1024 -> 4096 K = 26 at B = 1024 39.6 -> 28.8 us, 768 -> 3072 K = 16 22.3 -> 18.3, K = 8 20.3 -> 17.6)
+        if (shapes[i][0] == 2 && i < 6 && a.K < kRowlaneTwoRowsMinK) continue;
         if (shapes[i][0] == 2 && shapes[i][1] == 4 && a.K < kRowlaneTwoRowsFourSlicesMinK) continue;
         srigl_fwd_tuning shape{};
         if (t) shape = *t;
@@ -679,6 +679,10 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
         shape.term_slices = shapes[i][1];
         const RowlanePlan p = plan_rowlane_with(a, &shape, i == 1 ? 4 : (i >= 6 ? 8 : 0));
         if (!p.ok || (i >= 6 && p.NPW <= 4)) continue;
+        // (inputs wider than 1024 with less than a term per 256 columns: the estimate counts blocks of terms, not the near-empty block every
+        // chunk still costs a row, and ranks these shapes ahead of the small-batch kernel where they measured 50-80 % behind
+        // it: 4096 -> 4096 K = 12 at B = 512..2048)
+        if (i >= 6 && a.K < kRowlaneTwoRowsMinK && a.d_in > 1024 && (long long)a.K * 256 < a.d_in) continue;
         const double us = rowlane_estimate_us(a, p);
         if (!best.ok || us < 0.95 * best_us) { best = p; best_us = us; }
     }
