@@ -467,7 +467,7 @@ constexpr int kRowlaneShortRowOneK = 128;
 constexpr int kRowlaneTwoRowsFourSlicesMinK = 64;   // blocks of 64 terms: measured 14 % slower than 32 x 2 tiles at a fan-in of 39
 
 // npw_cap: the most stored rows per wavefront the choice may take (0: whatever the tile allows)
-static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p);
+static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p, bool whole_blocks = false);
 static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t, int npw_cap = 0) {
     // Wavefronts per workgroup, when the tuning leaves them open: 16, or 12 (three per SIMD instead of four) when that takes no
     // more rounds of workgroups, chunks or stored rows per wavefront: the same rows spread over more workgroups, each with a
@@ -638,10 +638,16 @@ static RowlanePlan plan_rowlane_with(const FwdArgs& a, const srigl_fwd_tuning* t
 // one: its LDS reads collide) and the result tile; large layers also the stream of W_c / idx.  A least-squares fit
 // (relative error, mean 5 %) of the mean of cold and cached timings of 260 points: 15 layer shapes, 512- to 4096-wide,
 // 80-99 % sparse, at batches 2 to 1024, every term-slice count on seven of them.
-static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p) {
+// whole_blocks: every row counted in whole blocks of terms, as the comparison with the small-batch kernel was fitted
+static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p, bool whole_blocks) {
     const int BT = kWave * p.R / p.H;
     const double rounds = std::max(1, p.rounds);
-    const double steps = (double)p.NPW * ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock;
+    // (a row that fits one block of terms is walked in groups of 4 or 8 steps up to its own length, not the whole block:
+    // counted so between tile shapes, where whole blocks ranked the sliced tiles 20 % too slow on rows of 16-26 terms:
+    // 768 -> 3072 K = 16 at B = 256 9.2 -> 7.7 us, 1024 -> 4096 K = 26 at B = 64 7.3 -> 6.1)
+    const int group = p.R >= 2 ? 4 : 8;
+    const int short_steps = std::max(group, ((a.K + p.H - 1) / p.H + group - 1) / group * group);
+    const double steps = (double)p.NPW * (a.K <= kBlock * p.H && !whole_blocks ? short_steps : ((a.K + kBlock * p.H - 1) / (kBlock * p.H)) * kBlock);
     // (six or eight rows per wavefront keep one block of terms per row: the steps measured 0-40 % slower, longest on long segments)
     // (the same in two slices: 4096 -> 4096 at B = 512 measured 63.5 us with eight rows, 73.1 with four)
     const double many_rows = (p.R == 2 && p.NPW >= 6) ? (p.H == 1 ? 1.15 : 1.2) : 1.0;
@@ -713,7 +719,7 @@ srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
     if (B > 1 && B <= 2048 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
         const RowlanePlan rp = plan_rowlane(a, nullptr);
-        batched = rp.ok && rowlane_estimate_us(a, rp) < klane_estimate_us(B, d_in, n_active, K);
+        batched = rp.ok && rowlane_estimate_us(a, rp, true) < klane_estimate_us(B, d_in, n_active, K);
     }
     const bool can_batch = rowlane_supported(a, nullptr);
     if (batched && can_batch) return SRIGL_FWD_ROWLANE;
@@ -740,7 +746,7 @@ double condensed_estimate_us(int B, int d_in, int n_active, int K, int d_out, bo
     if (B <= 0 || n_active <= 0 || K <= 0 || d_in <= 0) return 2.0;
     const FwdArgs a = standin_args(B, d_in, n_active, K, d_out, bf16, has_active, true);
     const RowlanePlan rp = plan_rowlane(a, nullptr);
-    const double batched = rp.ok ? rowlane_estimate_us(a, rp) : 1e30;
+    const double batched = rp.ok ? rowlane_estimate_us(a, rp, true) : 1e30;
     if (B > 2048 && rp.ok) return batched;
     return std::min(batched, klane_estimate_us(B, d_in, n_active, K));
 }
