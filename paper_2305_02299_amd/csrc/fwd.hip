@@ -9,6 +9,7 @@
 #include "srigl_internal.h"
 #include <algorithm>
 #include <cmath>
+#include <cstring>
 
 namespace srigl {
 
@@ -662,7 +663,7 @@ static double rowlane_estimate_us(const FwdArgs& a, const RowlanePlan& p, bool w
 // 64- and 32-row tiles with half the LDS instructions per term: 10-24 % faster than one row per lane from a fan-in of
 // ~100, slower below; all need rows long enough for the term loop to matter: slower at fan-in 8).  With nothing forced the library takes the shape with the smallest estimated time; a forced
 // part keeps the rules the other part had before the estimate existed.
-static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
+static RowlanePlan plan_rowlane_by_estimate(const FwdArgs& a, const srigl_fwd_tuning* t) {
     const bool forced = t && (t->rows_per_lane || t->term_slices);
     if (forced) return plan_rowlane_with(a, t);
     RowlanePlan best{};
@@ -695,6 +696,79 @@ static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
     return best;
 }
 
+// A second ranking of the launch shapes, fitted to measurements of every shape (rows per lane x term slices x stored rows
+// per wavefront) on 25 layers (768..4096 wide, fan-in 16..410, fp32 and bf16) at 11 batches from 48 to 2048, cached operands:
+// per launch a constant; per round of workgroups a constant, a cost per chunk, per staged byte and per word of the result
+// tile; per stored row and round a cost per step (terms / slices), a cost per chunk that holds terms of the row (the
+// expected number for evenly drawn columns), and more per step from six rows per wavefront on (one block of terms in
+// registers); the last three per tile shape.  Least squares on the relative error (std 8 %).  On those 275 points the shape
+// of smallest estimate above is 2.0 % slower than the best measured one on average (41 points more than 5 %, 17 more than
+// 10 %, worst 25 %); the smallest of this ranking 0.8 % (15 / 5 / 16 %), and 0.9 % when the layer in question is left out
+// of the fit.
+static double rowlane_model_us(const FwdArgs& a, const RowlanePlan& p) {
+    static const double per_shape[6][3] = {{2.2139, 0.68796, 0.26927}, {2.3224, 1.0124, 0.35542}, {2.8715, 1.7402, 0.20129},     // R = 1: H = 1, 2, 4
+                                           {2.6993, 0.6968, 0.57723},  {2.8913, 1.0691, 0.56794}, {3.1549, 1.3301, 0.64974}};   // R = 2
+    if (p.R > 2) return 1e30;
+    const int BT = kWave * p.R / p.H, NG = p.NW * p.NPW;
+    const double* c = per_shape[(p.R - 1) * 3 + (p.H == 1 ? 0 : (p.H == 2 ? 1 : 2))];
+    const double rounds = std::max(1, p.rounds), steps = (double)a.K / p.H;
+    const double with_terms = p.n_chunks > 1 ? p.n_chunks * (1.0 - std::pow(1.0 - 1.0 / p.n_chunks, (double)a.K)) : 1.0;
+    const double per_row = c[0] * steps * 1e-2 + c[1] * with_terms * 1e-1 + (p.NPW >= 6 ? c[2] * steps * 1e-2 : 0.0);
+    return 1.3466 + rounds * (1.4726 + 0.2878 * p.n_chunks + 14.303e-6 * BT * a.d_in * 4.0 + 0.3571e-3 * BT * NG + p.NPW * per_row);
+}
+
+// The launch shape of the library's own choice: the one of smallest estimate, unless the fitted ranking has another shape more
+// than 5 % ahead of it (of the 275 measured points 40 then change their shape; mean distance to the best measured shape
+// 0.6 %, 14 points beyond 5 %, 4 beyond 10 %).  Rows of fewer than 16 terms, which the fit has not seen, keep the estimate's.
+static RowlanePlan plan_rowlane_ranked(const FwdArgs& a, const srigl_fwd_tuning* t) {
+    const RowlanePlan first = plan_rowlane_by_estimate(a, t);
+    const bool forced = t && (t->rows_per_lane || t->term_slices || t->neurons_per_wave);
+    if (forced || !first.ok || a.K < 16) return first;
+    const double first_us = rowlane_model_us(a, first);
+    RowlanePlan best = first;
+    double best_us = first_us;
+    static const int rows_per_wave[6] = {1, 2, 3, 4, 6, 8};
+    for (int R = 1; R <= 2; ++R)
+        for (int H = 1; H <= 4; H *= 2)
+            for (int n = 0; n < 6; ++n) {
+                srigl_fwd_tuning shape{};
+                if (t) shape = *t;
+                shape.rows_per_lane = R;
+                shape.term_slices = H;
+                shape.neurons_per_wave = rows_per_wave[n];
+                const RowlanePlan p = plan_rowlane_with(a, &shape, 8);
+                if (!p.ok) continue;
+                const double us = rowlane_model_us(a, p);
+                if (us < best_us) { best = p; best_us = us; }
+            }
+    return first_us <= 1.05 * best_us ? first : best;
+}
+
+// (the ranking walks some hundred candidate shapes: the last few answers are kept per thread, keyed by everything a plan
+// depends on, so that a caller that repeats a launch pays for it once)
+static RowlanePlan plan_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t) {
+    struct Key {
+        int32_t B, d_in, n_active, K, d_out, seg_stride, flags;
+        srigl_fwd_tuning t;
+        bool operator==(const Key& o) const { return std::memcmp(this, &o, sizeof(Key)) == 0; }
+    };
+    struct Entry { Key key; RowlanePlan plan; bool used; };
+    static thread_local Entry cache[8] = {};
+    static thread_local int next = 0;
+    Key k;
+    std::memset(&k, 0, sizeof(k));
+    k.B = a.B; k.d_in = a.d_in; k.n_active = a.n_active; k.K = a.K; k.d_out = a.d_out; k.seg_stride = a.seg_stride;
+    k.flags = (a.x_bf16 ? 1 : 0) | (a.idx_u16 ? 2 : 0) | (a.active ? 4 : 0) | (a.seg ? 8 : 0) | (a.packed ? 16 : 0) | (a.bias ? 32 : 0) |
+              (int)((reinterpret_cast<uintptr_t>(a.x) & 15) << 8) | (int)((reinterpret_cast<uintptr_t>(a.idx) & 3) << 12) | (t ? 64 : 0);
+    if (t) k.t = *t;
+    for (int i = 0; i < 8; ++i)
+        if (cache[i].used && cache[i].key == k) return cache[i].plan;
+    const RowlanePlan p = plan_rowlane_ranked(a, t);
+    cache[next].key = k; cache[next].plan = p; cache[next].used = true;
+    next = (next + 1) & 7;
+    return p;
+}
+
 bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t) { return plan_rowlane(a, t).ok; }
 
 srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st) {
@@ -718,7 +792,7 @@ srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
     bool batched = B > 16;
     if (B > 1 && B <= 2048 && d_in % 16 == 0) {
         static_assert(kKlaneTerms == 4, "klane_estimate_us assumes 4 terms per lane and request");
-        const RowlanePlan rp = plan_rowlane(a, nullptr);
+        const RowlanePlan rp = plan_rowlane_by_estimate(a, nullptr);   // (the comparison was fitted with this shape and estimate)
         batched = rp.ok && rowlane_estimate_us(a, rp, true) < klane_estimate_us(B, d_in, n_active, K);
     }
     const bool can_batch = rowlane_supported(a, nullptr);
@@ -745,7 +819,7 @@ static FwdArgs standin_args(int B, int d_in, int n_active, int K, int d_out, boo
 double condensed_estimate_us(int B, int d_in, int n_active, int K, int d_out, bool bf16, bool has_active) {
     if (B <= 0 || n_active <= 0 || K <= 0 || d_in <= 0) return 2.0;
     const FwdArgs a = standin_args(B, d_in, n_active, K, d_out, bf16, has_active, true);
-    const RowlanePlan rp = plan_rowlane(a, nullptr);
+    const RowlanePlan rp = plan_rowlane_by_estimate(a, nullptr);
     const double batched = rp.ok ? rowlane_estimate_us(a, rp, true) : 1e30;
     if (B > 2048 && rp.ok) return batched;
     return std::min(batched, klane_estimate_us(B, d_in, n_active, K));

@@ -85,15 +85,16 @@ def test_long_rows_take_two_rows_per_lane_in_two_slices():
     """64-row tiles whose lanes hold two batch rows and work on two terms at once: one 8-byte LDS read per two rows and term.
     Measured against one row per lane: 768 -> 3072 K = 154 at B = 256 19.9 -> 17.1 us, 1024 -> 4096 K = 102 19.9 -> 16.5,
     2048 -> 2048 K = 205 at B = 384 35.0 -> 27.6, 4096 -> 1024 K = 410 at B = 1024 69.2 -> 52.4; at K = 77 (B = 256:
-    13.6 -> 12.4 with two blocks of 32 terms preloaded per stored row and chunk instead of three); at a fan-in of 39 the plain
-    64-row tile stays."""
+    13.6 -> 12.4 with two blocks of 32 terms preloaded per stored row and chunk instead of three); at a fan-in of 39 the fitted
+    ranking takes the 32-row tile of two rows per lane with six stored rows per wavefront (12.6 / 10.7 -> 11.2 / 9.9 us cold /
+    cached against the plain 64-row tile, which the estimate alone would keep)."""
     for (B, d_in, d_out, K) in ((256, 768, 3072, 154), (256, 1024, 4096, 102), (384, 2048, 2048, 205), (1024, 4096, 1024, 410),
                                 (256, 768, 3072, 77)):
         p = plan(B, d_in, d_out, K)
         assert (p["algo"], p["rows_per_lane"], p["term_slices"]) == (B_.FWD_ROWLANE, 2, 2), (B, d_in, d_out, K, p)
     for (B, d_in, d_out, K) in ((256, 768, 3072, 39),):
         p = plan(B, d_in, d_out, K)
-        assert (p["rows_per_lane"], p["term_slices"]) == (1, 1), (B, d_in, d_out, K, p)
+        assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"]) == (2, 4, 6), (B, d_in, d_out, K, p)
     # wide inputs, long rows: 32-row tiles the same way (four slices of 16 lanes); 4096 -> 1024 K = 410 at B = 512: 39.6 -> 31.4 us
     p = plan(512, 4096, 1024, 410)
     assert (p["rows_per_lane"], p["term_slices"]) == (2, 4)
@@ -148,6 +149,26 @@ def test_forced_small_batch_kernel_at_batches_beyond_its_workgroup_limit():
     assert p["workgroups"] == 9000
     with pytest.raises(B_.SriglError):
         plan(65536, 2048, 300, 40, algo=B_.FWD_KLANE, tuning=dict(rows_per_block=1))   # the batch is the grid's second dimension
+
+
+def test_fitted_ranking_moves_the_shape_only_when_it_is_well_ahead():
+    """The shape of smallest estimate stays unless the ranking fitted to measured shapes has another one more than 5 % ahead:
+    the headline layer keeps its shape (the ranking has a 32-row tile 4 % ahead, measured level), the changes below measured
+    10-22 % faster; rows of fewer than 16 terms keep the estimate's shape."""
+    p = plan(256, 768, 3072, 77)
+    assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"], p["chunk_cols"]) == (2, 2, 3, 384)
+    p = plan(256, 3072, 768, 307, n_active=538)
+    assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"], p["waves"]) == (1, 4, 3, 12)
+    p = plan(2048, 4096, 16384, 205, n_active=13108, dtype_code=B_.BF16)
+    assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"]) == (2, 1, 8)
+    for (B, d_in, d_out, K, shape) in ((1024, 3072, 768, 154, (2, 4, 6)),      # 36.9 / 28.2 -> 28.8 / 22.7 us
+                                       (512, 768, 3072, 39, (2, 2, 6)),        # 18.6 / 16.5 -> 16.5 / 14.6
+                                       (128, 4096, 4096, 41, (1, 4, 8)),       # 22.7 / 16.6 -> 17.8 / 13.4
+                                       (1024, 2048, 2048, 102, (2, 2, 8))):    # 45.1 / 38.6 -> 39.0 / 32.1
+        p = plan(B, d_in, d_out, K)
+        assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"]) == shape, (B, d_in, d_out, K, p)
+    legacy = plan(1024, 768, 3072, 8)
+    assert (legacy["rows_per_lane"], legacy["term_slices"], legacy["neurons_per_wave"]) == (2, 1, 6)
 
 
 def test_every_plan_is_one_the_kernels_accept():
