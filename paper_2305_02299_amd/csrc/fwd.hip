@@ -697,33 +697,36 @@ static RowlanePlan plan_rowlane_by_estimate(const FwdArgs& a, const srigl_fwd_tu
 }
 
 // A second ranking of the launch shapes, fitted to measurements of every shape (rows per lane x term slices x stored rows
-// per wavefront) on 25 layers (768..4096 wide, fan-in 16..410, fp32 and bf16) at 11 batches from 48 to 2048, cached operands:
+// per wavefront) on 39 layers (768..4096 wide, fan-in 8..410, fp32 and bf16) at up to 14 batches from 48 to 4096, cached operands:
 // per launch a constant; per round of workgroups a constant, a cost per chunk, per staged byte and per word of the result
 // tile; per stored row and round a cost per step (terms / slices), a cost per chunk that holds terms of the row (the
 // expected number for evenly drawn columns), and more per step from six rows per wavefront on (one block of terms in
-// registers); the last three per tile shape.  Least squares on the relative error (std 8 %).  On those 275 points the shape
-// of smallest estimate above is 2.0 % slower than the best measured one on average (41 points more than 5 %, 17 more than
-// 10 %, worst 25 %); the smallest of this ranking 0.8 % (15 / 5 / 16 %), and 0.9 % when the layer in question is left out
-// of the fit.
+// registers), the last three per tile shape; and a cost per stored term of layers beyond the L2.  Least squares on the
+// relative error (std 8 %) of 17600 launches.  On the first 275 points (fan-in 16 and more, up to 2048 rows) the shape of
+// smallest estimate above is 2.0 % slower than the best measured one on average (41 points more than 5 %, 17 more than
+// 10 %, worst 25 %), on rows of fewer than 16 terms 4.9 %; the smallest of this ranking 0.9 % on all 489 points (27 beyond
+// 5 %, 10 beyond 10 %, worst 22 %), and 1.0 % when the layer in question is left out of the fit.
 static double rowlane_model_us(const FwdArgs& a, const RowlanePlan& p) {
-    static const double per_shape[6][3] = {{2.2139, 0.68796, 0.26927}, {2.3224, 1.0124, 0.35542}, {2.8715, 1.7402, 0.20129},     // R = 1: H = 1, 2, 4
-                                           {2.6993, 0.6968, 0.57723},  {2.8913, 1.0691, 0.56794}, {3.1549, 1.3301, 0.64974}};   // R = 2
+    static const double per_shape[6][3] = {{2.1716, 0.93914, 0.27754}, {2.2649, 1.2646, 0.38936}, {2.8034, 2.1405, 0.20622},     // R = 1: H = 1, 2, 4
+                                           {2.6393, 0.89263, 0.55438}, {2.8239, 1.3094, 0.56102}, {3.0297, 1.627, 0.67318}};    // R = 2
     if (p.R > 2) return 1e30;
     const int BT = kWave * p.R / p.H, NG = p.NW * p.NPW;
     const double* c = per_shape[(p.R - 1) * 3 + (p.H == 1 ? 0 : (p.H == 2 ? 1 : 2))];
     const double rounds = std::max(1, p.rounds), steps = (double)a.K / p.H;
     const double with_terms = p.n_chunks > 1 ? p.n_chunks * (1.0 - std::pow(1.0 - 1.0 / p.n_chunks, (double)a.K)) : 1.0;
     const double per_row = c[0] * steps * 1e-2 + c[1] * with_terms * 1e-1 + (p.NPW >= 6 ? c[2] * steps * 1e-2 : 0.0);
-    return 1.3466 + rounds * (1.4726 + 0.2878 * p.n_chunks + 14.303e-6 * BT * a.d_in * 4.0 + 0.3571e-3 * BT * NG + p.NPW * per_row);
+    const double terms = (double)a.n_active * a.K;
+    return 1.4497 + rounds * (1.3486 + 0.39696 * p.n_chunks + 13.5e-6 * BT * a.d_in * 4.0 + 0.38181e-3 * BT * NG + p.NPW * per_row) +
+           (terms > 1.5e6 ? 0.89109e-6 * terms : 0.0);
 }
 
 // The launch shape of the library's own choice: the one of smallest estimate, unless the fitted ranking has another shape more
-// than 5 % ahead of it (of the 275 measured points 40 then change their shape; mean distance to the best measured shape
-// 0.6 %, 14 points beyond 5 %, 4 beyond 10 %).  Rows of fewer than 16 terms, which the fit has not seen, keep the estimate's.
+// than 5 % ahead of it (mean distance to the best measured shape over the 489 measured points then 0.7 %, 24 points beyond
+// 5 %, 8 beyond 10 %).
 static RowlanePlan plan_rowlane_ranked(const FwdArgs& a, const srigl_fwd_tuning* t) {
     const RowlanePlan first = plan_rowlane_by_estimate(a, t);
     const bool forced = t && (t->rows_per_lane || t->term_slices || t->neurons_per_wave);
-    if (forced || !first.ok || a.K < 16) return first;
+    if (forced || !first.ok) return first;
     const double first_us = rowlane_model_us(a, first);
     RowlanePlan best = first;
     double best_us = first_us;
