@@ -217,7 +217,7 @@ def point(args):
     bf16 = L.dtype == "bf16"
     layer = condense_layer(dev(L.W_bf16 if bf16 else L.W), dev(L.mask), L.K, dev(L.bias))
     x = dev((L.x_bf16 if bf16 else L.x)[:B])
-    algo = {None: None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE}[args.algo]
+    algo = {None: None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE, "rowloop": B_.FWD_ROWLOOP}[args.algo]
     tuning = json.loads(args.tuning) if args.tuning else None
     if tuning is not None and algo is None:
         algo = B_.FWD_ROWLANE if any(k in tuning for k in ("rows_per_lane", "term_slices", "waves", "neurons_per_wave", "chunk_cols", "terms_from_copy", "xcd_order", "spread_rows")) \
@@ -611,7 +611,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-packed", action="store_true", help="forward calls on the W_c / idx arrays alone (no streaming copy)")
-    ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane"])
+    ap.add_argument("--algo", default=None, choices=[None, "generic", "klane", "rowlane", "rowloop"])
     ap.add_argument("--point", default=None, help="time one layer: c1|c2|c3|c5 or d_in,d_out,K[,bf16][,ablate=F][,clustered]; see --batch, --algo, --tuning")
     ap.add_argument("--batch", type=int, default=256, help="--point: batch rows (named configurations other than c3 keep their own)")
     ap.add_argument("--tuning", default=None, help="--point: JSON object of srigl_fwd_tuning fields to force a launch shape")
@@ -649,7 +649,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
-    algo = {None: None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE}[args.algo]
+    algo = {None: None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE, "rowloop": B_.FWD_ROWLOOP}[args.algo]
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
 
     L = si.config(args.workload)                      # B = 256

@@ -51,7 +51,9 @@ typedef enum {
     SRIGL_FWD_AUTO = 0,
     SRIGL_FWD_GENERIC = 1,  /* one thread per output, activations read from global memory; any index order */
     SRIGL_FWD_KLANE = 2,    /* small batch: lanes split one neuron's K terms, cross-lane reduction          */
-    SRIGL_FWD_ROWLANE = 3   /* batched: lanes are batch rows, activation tile transposed in LDS             */
+    SRIGL_FWD_ROWLANE = 3,  /* batched: lanes are batch rows, activation tile transposed in LDS             */
+    SRIGL_FWD_ROWLOOP = 4   /* batched, inputs narrow enough that a 32-row tile holds every column of x: a wavefront
+                               walks any number of stored rows, so a workgroup owns hundreds of them per staged tile */
 } srigl_fwd_algo;
 
 /* 32 bytes, lives in device memory, written by check_fanin / condense. */

@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_FANIN, ERR_CAPACITY, ERR_INDEX_RANGE, ERR_UNSUPPORTED, 
 F32, BF16 = 0, 1
 REPR_CONDENSED, REPR_STRUCTURED = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
-FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE = range(4)
+FWD_AUTO, FWD_GENERIC, FWD_KLANE, FWD_ROWLANE, FWD_ROWLOOP = range(5)
 TILE_AUTO, TILE_256x256, TILE_256x256_H, TILE_256x128_W4, TILE_256x128, TILE_128x128, TILE_64x64 = range(7)
 TILES = {"256x256": TILE_256x256, "256x256_h": TILE_256x256_H, "256x128_w4": TILE_256x128_W4, "256x128": TILE_256x128,
          "128x128": TILE_128x128, "64x64": TILE_64x64}

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsrigl.so")
-SOURCES = ["condense.hip", "fwd.hip", "fwd_rowlane_f32.hip", "fwd_rowlane_bf16.hip", "fwd_rowlane_f32_i16.hip", "fwd_rowlane_bf16_i16.hip", "structured.hip", "mlp.hip", "update.hip", "csr.hip"]
+SOURCES = ["condense.hip", "fwd.hip", "fwd_rowlane_f32.hip", "fwd_rowlane_bf16.hip", "fwd_rowlane_f32_i16.hip", "fwd_rowlane_bf16_i16.hip", "fwd_rowloop.hip", "structured.hip", "mlp.hip", "update.hip", "csr.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -786,7 +786,8 @@ srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hip
 // The library's own choice of kernel: the smallest of the estimated times of the small-batch kernel (gathered or staged
 // activations) and of the batched kernel in the launch shape it would take.  A single row always takes the small-batch
 // kernel, above 2048 rows the batched kernel always wins.
-srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
+// The choice between the small-batch kernel, the chunked batched kernel and the fallback.
+static srigl_fwd_algo choose_chunked_or_small(const FwdArgs& a) {
     const int B = a.B, d_in = a.d_in, n_active = a.n_active, K = a.K;
     {   // the staged few-lanes shape of the small-batch kernel where it measured ahead of both estimates' kernels
         int few_L = 0, few_RB = 0;
@@ -802,6 +803,27 @@ srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
     if (batched && can_batch) return SRIGL_FWD_ROWLANE;
     if (plan_klane(a, nullptr).ok) return SRIGL_FWD_KLANE;
     return can_batch ? SRIGL_FWD_ROWLANE : SRIGL_FWD_GENERIC;
+}
+
+// Estimate (us) of the faster of the small-batch and the chunked batched kernel (above 2048 rows: of the batched one).
+static double chunked_or_small_estimate_us(const FwdArgs& a) {
+    const RowlanePlan rp = plan_rowlane_by_estimate(a, nullptr);
+    const double batched = rp.ok ? rowlane_estimate_us(a, rp, true) : 1e30;
+    if (a.B > 2048 && rp.ok) return batched;
+    return std::min(batched, klane_estimate_us(a.B, a.d_in, a.n_active, a.K));
+}
+// The whole-input batched kernel is taken where its estimate is ahead of that one's (5 % behind still counts: over the
+// 238 launches its estimate was fitted to, that threshold left the least time on the table, 0.9 % against 7.5 % without
+// this kernel); never against the staged few-lanes shape of the small-batch kernel, which was placed by measurement.
+constexpr double kRowloopMargin = 0.95;
+srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
+    const srigl_fwd_algo base = choose_chunked_or_small(a);
+    if (base == SRIGL_FWD_GENERIC || a.B < 2) return base;
+    int few_L = 0, few_RB = 0;
+    if (base == SRIGL_FWD_KLANE && klane_few_lanes_staged(a.B, a.d_in, a.n_active, a.K, &few_L, &few_RB)) return base;
+    const double rl = rowloop_estimate_us(a);
+    if (rl >= 1e29) return base;
+    return rl * kRowloopMargin < chunked_or_small_estimate_us(a) ? SRIGL_FWD_ROWLOOP : base;
 }
 
 // stand-ins for the device arrays of a call of these sizes: the planner looks at their alignment and at which ones are
@@ -822,10 +844,8 @@ static FwdArgs standin_args(int B, int d_in, int n_active, int K, int d_out, boo
 double condensed_estimate_us(int B, int d_in, int n_active, int K, int d_out, bool bf16, bool has_active) {
     if (B <= 0 || n_active <= 0 || K <= 0 || d_in <= 0) return 2.0;
     const FwdArgs a = standin_args(B, d_in, n_active, K, d_out, bf16, has_active, true);
-    const RowlanePlan rp = plan_rowlane_by_estimate(a, nullptr);
-    const double batched = rp.ok ? rowlane_estimate_us(a, rp, true) : 1e30;
-    if (B > 2048 && rp.ok) return batched;
-    return std::min(batched, klane_estimate_us(B, d_in, n_active, K));
+    const double other = chunked_or_small_estimate_us(a), rl = rowloop_estimate_us(a);
+    return rl * kRowloopMargin < other ? rl : other;
 }
 
 }  // namespace srigl
@@ -868,11 +888,13 @@ static srigl_status fwd_core(const void* x, srigl_dtype x_dtype, int32_t B, int3
         case SRIGL_FWD_GENERIC: return launch_fwd_generic(a, st);
         case SRIGL_FWD_KLANE: return launch_fwd_klane(a, tuning, st);
         case SRIGL_FWD_ROWLANE: return launch_fwd_rowlane(a, tuning, st);
+        case SRIGL_FWD_ROWLOOP: return launch_fwd_rowloop(a, tuning, st);
         case SRIGL_FWD_AUTO: break;
         default: return SRIGL_ERR_INVALID_ARG;
     }
     switch (choose_fwd_algo(a)) {
         case SRIGL_FWD_ROWLANE: return launch_fwd_rowlane(a, nullptr, st);
+        case SRIGL_FWD_ROWLOOP: return launch_fwd_rowloop(a, nullptr, st);
         case SRIGL_FWD_KLANE: return launch_fwd_klane(a, nullptr, st);
         default: return launch_fwd_generic(a, st);
     }
@@ -946,7 +968,8 @@ srigl_status srigl_fwd_plan_query(int32_t B, int32_t d_in, int32_t n_active, int
 srigl_status srigl_fwd_plan_query_algo(int32_t B, int32_t d_in, int32_t n_active, int32_t K, int32_t d_out, srigl_dtype dtype,
                                        int32_t has_active, int32_t has_seg, srigl_fwd_algo forced, const srigl_fwd_tuning* tuning,
                                        srigl_fwd_plan* plan) {
-    if (forced != SRIGL_FWD_AUTO && forced != SRIGL_FWD_GENERIC && forced != SRIGL_FWD_KLANE && forced != SRIGL_FWD_ROWLANE)
+    if (forced != SRIGL_FWD_AUTO && forced != SRIGL_FWD_GENERIC && forced != SRIGL_FWD_KLANE && forced != SRIGL_FWD_ROWLANE &&
+        forced != SRIGL_FWD_ROWLOOP)
         return SRIGL_ERR_INVALID_ARG;
     if (plan == nullptr || B < 0 || d_in < 0 || n_active < 0 || K < 0 || d_out < 0 || K > d_in || n_active > d_out)
         return SRIGL_ERR_INVALID_ARG;
@@ -962,6 +985,8 @@ srigl_status srigl_fwd_plan_query_algo(int32_t B, int32_t d_in, int32_t n_active
         plan->rows_per_lane = p.R; plan->term_slices = p.H; plan->waves = p.NW; plan->neurons_per_wave = p.NPW;
         plan->chunk_cols = p.C; plan->workgroups = (int64_t)p.n_groups * p.n_btiles; plan->xcd_order = p.bt_major ? 2 : 1;
         plan->spread_rows = p.spread == 0 ? 1 : (p.spread == 1 ? 2 : 3);
+    } else if (algo == SRIGL_FWD_ROWLOOP) {
+        if (!rowloop_plan_query(a, tuning, plan)) return SRIGL_ERR_UNSUPPORTED;
     } else if (algo == SRIGL_FWD_KLANE) {
         const KlanePlan p = plan_klane(a, tuning);
         if (!p.ok) return SRIGL_ERR_UNSUPPORTED;

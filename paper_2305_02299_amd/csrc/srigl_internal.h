@@ -140,6 +140,12 @@ srigl_status launch_fwd_generic(const FwdArgs& a, hipStream_t st);
 srigl_status launch_fwd_klane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
 srigl_status launch_fwd_rowlane(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
 bool rowlane_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
+// ROWLOOP (fwd_rowloop.hip): the launch, whether these sizes can run it, its estimated time (us; 1e30 if they cannot) and
+// the launch shape for srigl_fwd_plan_query
+srigl_status launch_fwd_rowloop(const FwdArgs& a, const srigl_fwd_tuning* t, hipStream_t st);
+bool rowloop_supported(const FwdArgs& a, const srigl_fwd_tuning* t);
+double rowloop_estimate_us(const FwdArgs& a);
+bool rowloop_plan_query(const FwdArgs& a, const srigl_fwd_tuning* t, srigl_fwd_plan* plan);
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a);
 // Estimated time (us) of the condensed forward call of these sizes in the kernel the library's own choice takes.
 double condensed_estimate_us(int B, int d_in, int n_active, int K, int d_out, bool bf16, bool has_active);

@@ -43,7 +43,7 @@ def test_random_layer_every_algorithm(d_in, d_out, K, B, abl, dtype, seed):
     y_ref, S = oracle.fwd(xsrc, W_c, idx, active, L.bias, d_out, want_scale=True)
     ablated = np.setdiff1d(np.arange(d_out), active)
     ran = 0
-    for algo in (None, B_.FWD_GENERIC, B_.FWD_KLANE, B_.FWD_ROWLANE):
+    for algo in (None, B_.FWD_GENERIC, B_.FWD_KLANE, B_.FWD_ROWLANE, B_.FWD_ROWLOOP):
         y = torch.full((B, d_out), 3.0e38, dtype=torch.float32, device="cuda")
         try:
             B_.srigl_condensed_linear_fwd(dev(xsrc), B, d_in, layer.W_c, layer.idx, layer.active, n, K, layer.bias, d_out, y,

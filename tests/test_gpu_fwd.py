@@ -15,7 +15,7 @@ from paper_2305_02299_amd import binding as B_
 
 pytestmark = pytest.mark.gpu
 
-ALGOS = {"auto": None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE}
+ALGOS = {"auto": None, "generic": B_.FWD_GENERIC, "klane": B_.FWD_KLANE, "rowlane": B_.FWD_ROWLANE, "rowloop": B_.FWD_ROWLOOP}
 GUARD = 1024
 
 
@@ -153,6 +153,48 @@ def test_rowlane_launch_shapes(tuning):
         assert ran is not None or d_in % 16 != 0     # only the ragged-width layer may be refused (slow staging: H = R = 1)
 
 
+@pytest.mark.parametrize("tuning", [
+    None,
+    {"term_slices": 4, "waves": 16, "neurons_per_wave": 1},
+    {"term_slices": 4, "waves": 3, "neurons_per_wave": 7},
+    {"term_slices": 4, "waves": 16, "neurons_per_wave": 5, "xcd_order": 2},
+    {"term_slices": 4, "waves": 8, "neurons_per_wave": 2, "xcd_order": 1},
+    {"term_slices": 2, "waves": 16, "neurons_per_wave": 2},
+    {"term_slices": 2, "waves": 5, "neurons_per_wave": 3, "xcd_order": 2},
+    {"term_slices": 2, "waves": 1, "neurons_per_wave": 40},
+])
+def test_whole_input_batched_kernel_launch_shapes(tuning):
+    """ROWLOOP: every column of x in one LDS tile, a wavefront walks its stored rows one after the other.  Rows of one block of
+    terms per slice up to rows longer than the four preloaded blocks (K = 300 in four slices: 75 steps, K = 500 in two: 250),
+    batches with a ragged last tile, stored columns with and without ablated ones between them, fp32 and bf16."""
+    for (d_in, d_out, K, B, abl, dtype) in ((768, 300, 77, 300, 0.1, "f32"), (512, 333, 300, 70, 0.0, "f32"), (512, 90, 500, 33, 0.3, "f32"),
+                                            (256, 1000, 8, 257, 0.0, "bf16"), (1024, 130, 1, 65, 0.5, "f32"), (16, 40, 16, 100, 0.2, "f32"),
+                                            (640, 2100, 39, 95, 0.6, "bf16")):
+        L = si.make_layer(d_in, d_out, K, B, dtype=dtype, ablate_frac=abl, seed=91)
+        ran = check_layer(L, B_.FWD_ROWLOOP, tuning, unsupported_ok=True)
+        # the 64-row tile of two term slices holds inputs up to 600 columns wide, the 32-row one up to 1100
+        assert (ran is not None) == (d_in <= 512 or tuning is None or tuning["term_slices"] == 4), (d_in, tuning)
+
+
+def test_whole_input_batched_kernel_few_stored_neurons_among_many_ablated():
+    """Runs of output columns longer than the workgroup's column table: the lanes write their stored column and the ablated ones
+    in front of it."""
+    for (d_in, d_out, K, B, abl) in ((128, 30000, 9, 40, 0.97), (1024, 40000, 40, 33, 0.998), (64, 5000, 3, 70, 0.9)):
+        L = si.make_layer(d_in, d_out, K, B, ablate_frac=abl, seed=92)
+        for tuning in (None, {"waves": 2, "neurons_per_wave": 1}, {"term_slices": 2, "waves": 16, "neurons_per_wave": 1}):
+            ran = check_layer(L, B_.FWD_ROWLOOP, tuning, unsupported_ok=True)
+            assert ran is not None or (d_in == 1024 and tuning and tuning.get("term_slices") == 2)
+
+
+def test_whole_input_batched_kernel_refuses_what_it_cannot_hold():
+    for (d_in, K) in ((3072, 77), (1200, 30), (100, 7)):     # wider than the LDS tile; not a multiple of 16 columns
+        L = si.make_layer(d_in, 64, K, 40, seed=93)
+        assert check_layer(L, B_.FWD_ROWLOOP, None, unsupported_ok=True) is None
+    L = si.make_layer(256, 64, 20, 40, seed=93)
+    for tuning in ({"rows_per_lane": 1}, {"term_slices": 1}, {"waves": 17}, {"xcd_order": 3}, {"neurons_per_wave": 4096}):
+        assert check_layer(L, B_.FWD_ROWLOOP, tuning, unsupported_ok=True) is None, tuning
+
+
 def test_rowlane_row_of_more_chunks_than_a_wavefront_has_lanes():
     """65 chunks of 64 columns: the per-row register of chunk boundaries (one lane per chunk) is reloaded on the way."""
     L = si.make_layer(4160, 40, 130, 70, ablate_frac=0.1, seed=79)
@@ -261,10 +303,10 @@ def test_one_hot_rows_are_bit_exact(algo):
     assert np.array_equal(y.view(np.uint32), exp.view(np.uint32))
 
 
-@pytest.mark.parametrize("algo", ["auto", "generic", "klane"])
+@pytest.mark.parametrize("algo", ["auto", "generic", "klane", "rowloop"])
 def test_unsorted_and_duplicate_indices(algo):
     """Alg. 1 is a plain sum over k: without seg the library must accept any in-range index order."""
-    L = si.make_layer(300, 50, 21, 40, seed=43)
+    L = si.make_layer(304 if algo == "rowloop" else 300, 50, 21, 40, seed=43)    # (ROWLOOP: whole 16-column units)
     W_c, idx, active = oracle_condensed(L)
     rng = np.random.default_rng(43)
     perm = np.stack([rng.permutation(21) for _ in range(50)])

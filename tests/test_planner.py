@@ -20,8 +20,13 @@ def test_single_row_takes_the_small_batch_kernel():
 
 
 def test_headline_batch_is_one_workgroup_per_compute_unit():
+    # the whole 768-wide input fits one 32-row tile in LDS: wavefronts walk six stored rows each, 11.6 / 10.1 us cold / cached
     p = plan(256, 768, 3072, 77)
-    assert p["algo"] == B_.FWD_ROWLANE
+    assert p["algo"] == B_.FWD_ROWLOOP
+    assert (p["rows_per_lane"], p["term_slices"], p["waves"], p["neurons_per_wave"]) == (2, 4, 16, 6)
+    assert p["workgroups"] == 256 and p["chunk_cols"] == 768
+    # the chunked batched kernel on the same layer (12.8 / 11.9 us):
+    p = plan(256, 768, 3072, 77, algo=B_.FWD_ROWLANE)
     # 64-row tiles (two rows per lane in two term slices), 16 wavefronts of three stored rows: 12.9 / 11.8 us cold / cached
     # against 14.2 / 12.9 with one row per lane
     assert (p["rows_per_lane"], p["term_slices"], p["waves"], p["neurons_per_wave"]) == (2, 2, 16, 3)
@@ -58,7 +63,7 @@ def test_small_batches_gather_their_activations():
     assert plan(8, 3072, 768, 308)["direct_gather"] == 1
     assert plan(16, 768, 3072, 8)["direct_gather"] == 1
     # very sparse layers at larger batches: many distinct lines per gather, the staged rows win
-    p = plan(256, 768, 3072, 8)                                        # 8.9 / 7.3 us staged, 10.9 / 9.4 gathered, 9.4 / 8.4 batched
+    p = plan(256, 768, 3072, 8, algo=B_.FWD_KLANE)                     # 8.9 / 7.3 us staged, 10.9 / 9.4 gathered, 9.4 / 8.4 batched
     assert (p["algo"], p["direct_gather"], p["rows_per_block"]) == (B_.FWD_KLANE, 0, 2)
     # 4096 -> 4096 at 99 % and 64 rows: the batched kernel (16.0 / 11.8 us) is ahead of staged (17.9 / 14.4) and gathered
     assert plan(64, 4096, 4096, 41)["algo"] == B_.FWD_ROWLANE
@@ -75,9 +80,9 @@ def test_rounds_are_counted_per_xcd():
     p = plan(320, 3072, 768, 308)
     assert p["algo"] == B_.FWD_ROWLANE and p["neurons_per_wave"] in (2, 6)
     # 768 -> 3072 at B = 384: 128-row tiles with three rows per wavefront are one round of 192 workgroups
-    p = plan(384, 768, 3072, 77)
+    p = plan(384, 768, 3072, 77, algo=B_.FWD_ROWLANE)
     assert (p["rows_per_lane"], p["neurons_per_wave"], p["workgroups"]) == (2, 3, 192)
-    p = plan(640, 768, 3072, 77)
+    p = plan(640, 768, 3072, 77, algo=B_.FWD_ROWLANE)
     assert (p["rows_per_lane"], p["neurons_per_wave"]) == (2, 4)
 
 
@@ -90,10 +95,10 @@ def test_long_rows_take_two_rows_per_lane_in_two_slices():
     cached against the plain 64-row tile, which the estimate alone would keep)."""
     for (B, d_in, d_out, K) in ((256, 768, 3072, 154), (256, 1024, 4096, 102), (384, 2048, 2048, 205), (1024, 4096, 1024, 410),
                                 (256, 768, 3072, 77)):
-        p = plan(B, d_in, d_out, K)
+        p = plan(B, d_in, d_out, K, algo=B_.FWD_ROWLANE)
         assert (p["algo"], p["rows_per_lane"], p["term_slices"]) == (B_.FWD_ROWLANE, 2, 2), (B, d_in, d_out, K, p)
     for (B, d_in, d_out, K) in ((256, 768, 3072, 39),):
-        p = plan(B, d_in, d_out, K)
+        p = plan(B, d_in, d_out, K, algo=B_.FWD_ROWLANE)
         assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"]) == (2, 4, 6), (B, d_in, d_out, K, p)
     # wide inputs, long rows: 32-row tiles the same way (four slices of 16 lanes); 4096 -> 1024 K = 410 at B = 512: 39.6 -> 31.4 us
     p = plan(512, 4096, 1024, 410)
@@ -103,8 +108,8 @@ def test_long_rows_take_two_rows_per_lane_in_two_slices():
 def test_which_workgroups_share_an_xcd():
     """Each of the 8 XCDs has its own L2: either every XCD fetches all of x (and one group's W_c / idx), or its own batch tiles
     of x and all of W_c / idx; the batched kernel takes the order that fetches fewer bytes once an XCD has two tiles."""
-    assert plan(256, 768, 3072, 77)["xcd_order"] == 1          # x 0.8 MB < W_c + idx 1.9 MB; only four batch tiles
-    assert plan(2048, 768, 3072, 77)["xcd_order"] == 2         # x 6.3 MB; 65.9 -> 62.0 us
+    assert plan(256, 768, 3072, 77, algo=B_.FWD_ROWLANE)["xcd_order"] == 1          # x 0.8 MB < W_c + idx 1.9 MB; only four batch tiles
+    assert plan(2048, 768, 3072, 77, algo=B_.FWD_ROWLANE)["xcd_order"] == 2         # x 6.3 MB; 65.9 -> 62.0 us
     assert plan(256, 3072, 768, 307, n_active=538)["xcd_order"] == 2   # 16 tiles of 16 rows; x 3.1 MB > 1.3 MB
     assert plan(128, 2048, 512, 205, algo=B_.FWD_ROWLANE)["xcd_order"] == 1   # one tile per XCD: 9.6 vs 10.4 us
 
@@ -112,8 +117,8 @@ def test_which_workgroups_share_an_xcd():
 def test_very_sparse_layers_stay_on_the_small_batch_kernel_at_larger_batches():
     assert plan(96, 3072, 768, 31)["algo"] == B_.FWD_KLANE            # 5.9 / 4.8 us (cold / cached) vs 11.9 / 10.7
     assert plan(96, 768, 3072, 8)["algo"] == B_.FWD_KLANE             # 6.0 / 5.0 vs 8.1 / 7.4
-    assert plan(256, 768, 3072, 8)["algo"] == B_.FWD_KLANE
-    assert plan(256, 768, 3072, 39)["algo"] == B_.FWD_ROWLANE
+    assert plan(256, 768, 3072, 8)["algo"] in (B_.FWD_KLANE, B_.FWD_ROWLOOP)   # 8.8 / 8.1 us against 9.1 / 7.1
+    assert plan(256, 768, 3072, 39)["algo"] == B_.FWD_ROWLOOP
     assert plan(4096, 3072, 768, 31)["algo"] == B_.FWD_ROWLANE      # above 2048 rows always the batched kernel
 
 
@@ -155,7 +160,7 @@ def test_fitted_ranking_moves_the_shape_only_when_it_is_well_ahead():
     """The shape of smallest estimate stays unless the ranking fitted to measured shapes has another one more than 5 % ahead:
     the headline layer keeps its shape (the ranking has a 32-row tile 4 % ahead, measured level), the changes below measured
     10-22 % faster; rows of fewer than 16 terms keep the estimate's shape."""
-    p = plan(256, 768, 3072, 77)
+    p = plan(256, 768, 3072, 77, algo=B_.FWD_ROWLANE)
     assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"], p["chunk_cols"]) == (2, 2, 3, 384)
     p = plan(256, 3072, 768, 307, n_active=538)
     assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"], p["waves"]) == (1, 4, 3, 12)
@@ -165,9 +170,9 @@ def test_fitted_ranking_moves_the_shape_only_when_it_is_well_ahead():
                                        (512, 768, 3072, 39, (2, 2, 6)),        # 18.6 / 16.5 -> 16.5 / 14.6
                                        (128, 4096, 4096, 41, (1, 4, 8)),       # 22.7 / 16.6 -> 17.8 / 13.4
                                        (1024, 2048, 2048, 102, (2, 2, 8))):    # 45.1 / 38.6 -> 39.0 / 32.1
-        p = plan(B, d_in, d_out, K)
+        p = plan(B, d_in, d_out, K, algo=B_.FWD_ROWLANE)
         assert (p["rows_per_lane"], p["term_slices"], p["neurons_per_wave"]) == shape, (B, d_in, d_out, K, p)
-    legacy = plan(1024, 768, 3072, 8)
+    legacy = plan(1024, 768, 3072, 8, algo=B_.FWD_ROWLANE)
     assert (legacy["rows_per_lane"], legacy["term_slices"], legacy["neurons_per_wave"]) == (2, 1, 6)
 
 
@@ -186,7 +191,7 @@ def test_every_plan_is_one_the_kernels_accept():
         if B * d_in >= 2 ** 31 or n_active * K >= 2 ** 30:
             continue
         p = B_.srigl_fwd_plan_query(B, d_in, n_active, K, d_out, dtype_code=dtype, has_active=(n_active != d_out))
-        assert p["algo"] in (B_.FWD_GENERIC, B_.FWD_KLANE, B_.FWD_ROWLANE), (B, d_in, d_out, n_active, K, p)
+        assert p["algo"] in (B_.FWD_GENERIC, B_.FWD_KLANE, B_.FWD_ROWLANE, B_.FWD_ROWLOOP), (B, d_in, d_out, n_active, K, p)
         assert p["workgroups"] >= 1
         if p["algo"] == B_.FWD_ROWLANE:
             assert p["rows_per_lane"] in (1, 2) and p["term_slices"] in (1, 2, 4) and 1 <= p["waves"] <= 16
@@ -194,6 +199,13 @@ def test_every_plan_is_one_the_kernels_accept():
             assert p["xcd_order"] in (1, 2)
             forced = dict(rows_per_lane=p["rows_per_lane"], term_slices=p["term_slices"], waves=p["waves"],
                           neurons_per_wave=p["neurons_per_wave"], chunk_cols=p["chunk_cols"], xcd_order=p["xcd_order"])
+        elif p["algo"] == B_.FWD_ROWLOOP:
+            assert p["rows_per_lane"] == 2 and p["term_slices"] in (2, 4) and p["waves"] == 16 and p["neurons_per_wave"] >= 1
+            tile_rows = 128 // p["term_slices"]
+            assert d_in % 16 == 0 and p["chunk_cols"] == d_in and p["xcd_order"] in (1, 2)
+            # the tile of x, the all-zero column and the result tile fit the LDS
+            assert ((d_in + 1) * (tile_rows + 4) + tile_rows * (p["neurons_per_wave"] * 16 + 1)) * 4 <= 160 * 1024
+            forced = dict(term_slices=p["term_slices"], waves=p["waves"], neurons_per_wave=p["neurons_per_wave"], xcd_order=p["xcd_order"])
         elif p["algo"] == B_.FWD_KLANE:
             L = p["lanes_per_neuron"]
             assert 4 <= L <= 64 and L & (L - 1) == 0 and p["rows_per_block"] in (1, 2, 4) and p["direct_gather"] in (0, 1)
