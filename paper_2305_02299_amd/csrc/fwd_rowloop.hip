@@ -300,13 +300,16 @@ static RowloopPlan plan_rowloop(const FwdArgs& a, const srigl_fwd_tuning* t) {
     p.n_btiles = (a.B + BT - 1) / BT;
     const int xo = t ? t->xcd_order : 0;
     if (xo < 0 || xo > 2) return p;
+    const double x_bytes = (double)a.B * a.d_in * (a.x_bf16 ? 2 : 4);
+    const double term_bytes = (double)a.n_active * a.K * ((a.x_bf16 ? 2 : 4) + (a.idx_u16 ? 2 : 4));
     auto shape = [&](int NG) {
         RowloopPlan q = p;
         q.NG = NG;
         q.n_groups = (a.n_active + NG - 1) / NG;
         const long long by_groups = (long long)((q.n_groups + 7) / 8) * q.n_btiles, by_tiles = (long long)((q.n_btiles + 7) / 8) * q.n_groups;
-        // batch tiles to XCDs when that takes no more rounds and every XCD gets a tile (else groups of stored rows)
-        q.bt_major = xo ? (xo == 2) : (q.n_btiles >= 8 && by_tiles <= by_groups);
+        // batch tiles to XCDs when that takes no more rounds, every XCD gets a tile and x is the larger operand: an XCD's L2
+        // then fetches its own rows of x and all of W_c / idx; else groups of stored rows (all of x, its groups' W_c / idx)
+        q.bt_major = xo ? (xo == 2) : (q.n_btiles >= 8 && by_tiles <= by_groups && x_bytes >= term_bytes);
         q.rounds = (int)(((q.bt_major ? by_tiles : by_groups) + 31) / 32);
         return q;
     };
