@@ -162,11 +162,15 @@ def test_rowlane_launch_shapes(tuning):
     {"term_slices": 2, "waves": 16, "neurons_per_wave": 2},
     {"term_slices": 2, "waves": 5, "neurons_per_wave": 3, "xcd_order": 2},
     {"term_slices": 2, "waves": 1, "neurons_per_wave": 40},
+    {"term_slices": 4, "waves": 4, "neurons_per_wave": 24},     # 96 stored rows per workgroup, 24 to a wavefront
+    {"term_slices": 2, "waves": 2, "neurons_per_wave": 30},
+    {"term_slices": 4, "waves": 16, "neurons_per_wave": 7},     # 112 rows: a last group that is not full on every layer below
 ])
 def test_whole_input_batched_kernel_launch_shapes(tuning):
     """ROWLOOP: every column of x in one LDS tile, a wavefront walks its stored rows one after the other.  Rows of one block of
     terms per slice up to rows longer than the four preloaded blocks (K = 300 in four slices: 75 steps, K = 500 in two: 250),
-    batches with a ragged last tile, stored columns with and without ablated ones between them, fp32 and bf16."""
+    batches with a ragged last tile, stored columns with and without ablated ones between them, fp32 and bf16; few and many stored rows per
+    wavefront, with a last group that is not full."""
     for (d_in, d_out, K, B, abl, dtype) in ((768, 300, 77, 300, 0.1, "f32"), (512, 333, 300, 70, 0.0, "f32"), (512, 90, 500, 33, 0.3, "f32"),
                                             (256, 1000, 8, 257, 0.0, "bf16"), (1024, 130, 1, 65, 0.5, "f32"), (16, 40, 16, 100, 0.2, "f32"),
                                             (640, 2100, 39, 95, 0.6, "bf16")):
