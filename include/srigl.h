@@ -167,7 +167,10 @@ srigl_status srigl_condensed_linear_fwd(const void* x, srigl_dtype x_dtype, int3
                                         const uint16_t* seg, const void* packed, void* stream);
 
 /* Launch-shape knobs of the forward kernels (host struct).  0 in a field = the library's default.
- * Values the kernels cannot run are rejected with SRIGL_ERR_UNSUPPORTED, never launched. */
+ * Values the kernels cannot run are rejected with SRIGL_ERR_UNSUPPORTED, never launched.
+ * SRIGL_FWD_ROWLOOP reads rows_per_lane (2 only), term_slices (4: 32-row tile, inputs up to about 1100 columns wide;
+ * 2: 64-row tile, up to about 600), waves (1..16), neurons_per_wave (stored rows a wavefront walks, any number the result
+ * tile in LDS has room for) and xcd_order; d_in must be a multiple of 16; the index order within a row is free. */
 typedef struct {
     int32_t rows_per_lane;    /* ROWLANE: batch rows per lane, 1, 2 or 4 (4: with 2 or 4 term slices only)  */
     int32_t waves;            /* ROWLANE: wavefronts per workgroup, 1..16                                  */
@@ -207,8 +210,8 @@ srigl_status srigl_condensed_linear_fwd_algo(const void* x, srigl_dtype x_dtype,
  * pass an active list / a seg table; arrays are taken to be 16-byte aligned).  All fields are 0 when no forward kernel
  * would run (B, d_out, n_active or K zero).  For tests of the planner and for users who want to know. */
 typedef struct {
-    int32_t algo;             /* srigl_fwd_algo: SRIGL_FWD_GENERIC, _KLANE or _ROWLANE                       */
-    int32_t rows_per_lane, term_slices, waves, neurons_per_wave, chunk_cols;   /* ROWLANE, else 0          */
+    int32_t algo;             /* srigl_fwd_algo: SRIGL_FWD_GENERIC, _KLANE, _ROWLANE or _ROWLOOP             */
+    int32_t rows_per_lane, term_slices, waves, neurons_per_wave, chunk_cols;   /* ROWLANE, ROWLOOP (chunk_cols = d_in), else 0 */
     int32_t lanes_per_neuron, rows_per_block;                                 /* KLANE, else 0            */
     int64_t workgroups;       /* workgroups that do work                                                    */
     int32_t direct_gather;    /* KLANE: 1 = activations gathered from global memory, 0 = rows of x staged in LDS */
