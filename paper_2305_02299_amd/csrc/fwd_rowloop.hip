@@ -13,6 +13,7 @@
 // Terms: a term slice takes a run of ceil(K / H) consecutive terms of the row, 16 to a block, one vector load per array and
 // block, requested two rows ahead; the group walk (LDS reads one group ahead of the multiply-adds) is the chunked kernel's.
 #include "fwd_rowlane.inl"
+#include <type_traits>
 
 namespace srigl {
 
@@ -31,7 +32,7 @@ __global__ __launch_bounds__(1024) void k_fwd_rowloop(const XT* __restrict__ x, 
                                                       const IT* __restrict__ idx, const int32_t* __restrict__ active, int n_active,
                                                       int K, const float* __restrict__ bias, int d_out, float* __restrict__ y,
                                                       int NG, int n_btiles, int n_groups, int out_off, int span_cap, int act, int bt_major) {
-    extern __shared__ float lds[];   // x tile [d_in + 1][S]; result tile [BT][NG | 1]; column table [span_cap]
+    extern __shared__ float lds[];   // x tile [d_in + 1][S]; result tile [BT][NG | 1]; bias [NG], or bias and column table [span_cap] each
     constexpr int LR = kWave / H;            // lanes per term slice
     constexpr int BT = LR * R;               // batch rows per tile
     constexpr int S = rowlane_row_stride(BT, H, R);
@@ -96,46 +97,100 @@ __global__ __launch_bounds__(1024) void k_fwd_rowloop(const XT* __restrict__ x, 
         ov = real ? i_raw * S4 : zero_off;
     };
 
-    for (int ub = 0; ub < n_units; ub += kStageUnits * nw) {
+    // What the stores at the end need besides the sums is requested behind the tile and parked in LDS before the first barrier,
+    // so that the epilogue reads LDS only (its loads used to cost it two dependent trips to the L2, about a microsecond):
+    // without an active list the bias of the workgroup's columns; with one, the run of consecutive columns [c0, c1) that the
+    // workgroup writes (the columns behind the previous group's last stored one up to this group's last; the last group also
+    // takes the ablated columns up to d_out), the bias of that run and, per column of it, which row of the result tile holds
+    // it, if any.  TP entries per thread wait in registers behind the tile's requests; what is beyond goes through a loop.
+    constexpr int TP = 4;
+    const int nthreads = blockDim.x;
+    float* const out = lds + out_off;
+    const int OS = NG | 1;                    // odd stride: conflict-free transposed writes
+    float* const bsp = out + BT * OS;         // bias of the workgroup's columns
+    int* const tab = reinterpret_cast<int*>(bsp + (active ? span_cap : NG));
+    int c0 = 0, c1 = 0, span = 0;
+    bool tabled = false;
+    if (active != nullptr) {
+        c0 = sg0 > 0 ? min(max(active[sg0 - 1] + 1, 0), d_out) : 0;
+        c1 = (g == n_groups - 1) ? d_out : min(max(active[sg0 + ng - 1] + 1, c0), d_out);
+        span = c1 - c0;
+        tabled = span <= span_cap;
+    }
+    const int n_bias = active ? (tabled ? span : 0) : ng;      // bias entries parked, counted from column (active ? c0 : sg0)
+    const int bias0 = active ? c0 : sg0;
+    float e_bias[TP];
+    int e_col[TP];
+
+    // A pass stages kStageUnits units per wavefront.  Every load of a pass is unconditional (a unit, row or entry past the
+    // end re-reads the last one and is dropped afterwards) and the first pass, which is the only one with 16 wavefronts, is
+    // straight-line code: with loads under branches, or in a loop whose registers a load of the last turn may still own, the
+    // compiler waits for every load in flight before the next one is issued (measured on the staging of this kernel: the
+    // six tile loads of a wavefront went out one round trip after the other).
+    const float* const bias_src = bias ? bias : reinterpret_cast<const float*>(x);   // never used: entries are 0 without a bias
+    auto stage_pass = [&](int ub, auto first) {
         Staged4<XT> st[kStageUnits];
         int l_off[kStageUnits];
 #pragma unroll
         for (int i = 0; i < kStageUnits; ++i) {
-            const int u = ub + wv_id + i * nw;
-            if (u < n_units) {
-                const int rt = u & (RT - 1), ct = u >> RT_LOG2;
-                const int rl = rt * 16 + db;
-                const int f = ct * 16 + dq * 4;
-                // rows past B re-read row B - 1: their lanes compute values that are never stored
-                const unsigned off = (unsigned)(min(rl, B - 1 - b0) * d_in + f) * (unsigned)sizeof(XT);   // BT * d_in * 4 < 2^32 (host)
-                load4(reinterpret_cast<const XT*>(xtile + off), true, 4, st[i]);
-                l_off[i] = f * S + rl;
-            }
+            const int u = min(ub + wv_id + i * nw, n_units - 1);
+            const int rt = u & (RT - 1), ct = u >> RT_LOG2;
+            const int rl = rt * 16 + db;
+            const int f = ct * 16 + dq * 4;
+            // rows past B re-read row B - 1: their lanes compute values that are never stored
+            const unsigned off = (unsigned)(min(rl, B - 1 - b0) * d_in + f) * (unsigned)sizeof(XT);   // BT * d_in * 4 < 2^32 (host)
+            load4(reinterpret_cast<const XT*>(xtile + off), true, 4, st[i]);
+            l_off[i] = f * S + rl;
         }
-        // behind the tile's first requests: the first row's terms (vector loads return in order, and the barrier below waits
-        // for the tile only)
-        if (ub == 0) {
+        if constexpr (decltype(first)::value) {
+            // behind the tile's first requests: the first rows' terms (vector loads return in order, and the tile's stores
+            // into LDS wait for the tile only), and, behind those, what the epilogue needs
 #pragma unroll
-            for (int d = 0; d < D; ++d)
-                if (wv_id + d * nw < ng) request_row(wv_id + d * nw, rw[d], ri[d]);
+            for (int d = 0; d < D; ++d) request_row(min(wv_id + d * nw, ng - 1), rw[d], ri[d]);
+#pragma unroll
+            for (int q = 0; q < TP; ++q) {
+                const int e = tid + q * nthreads;
+                // (raw values: whether an entry counts is decided where it is written to LDS, so that nothing here waits)
+                e_bias[q] = bias_src[bias ? min(bias0 + min(e, max(n_bias - 1, 0)), d_out - 1) : 0];
+                e_col[q] = active != nullptr ? active[sg0 + min(e, ng - 1)] : -1;
+            }
+            if (tabled)
+                for (int c = tid; c < span; c += nthreads) tab[c] = -1;
         }
 #pragma unroll
         for (int i = 0; i < kStageUnits; ++i) {
-            const int u = ub + wv_id + i * nw;
-            if (u < n_units) {
+            if (ub + wv_id + i * nw < n_units) {
                 float* d = lds + l_off[i];
                 d[0] = st[i].get(0); d[S] = st[i].get(1); d[2 * S] = st[i].get(2); d[3 * S] = st[i].get(3);
             }
         }
-    }
+    };
+    stage_pass(0, std::true_type{});
+    for (int ub = kStageUnits * nw; ub < n_units; ub += kStageUnits * nw) stage_pass(ub, std::false_type{});
     for (int t = tid; t < S; t += blockDim.x) lds[C * S + t] = 0.0f;   // the all-zero column that padding terms point at
+#pragma unroll
+    for (int q = 0; q < TP; ++q) {
+        const int e = tid + q * nthreads;
+        if (e < n_bias) bsp[e] = bias ? e_bias[q] : 0.0f;
+    }
+    for (int e = tid + TP * nthreads; e < n_bias; e += nthreads) bsp[e] = rl_bias_at(bias, bias0 + e);
+    if (tabled) {
+        lds_barrier();   // every thread's part of the table is cleared (LDS only: the tile's loads stay in flight)
+#pragma unroll
+        for (int q = 0; q < TP; ++q) {
+            const int col = e_col[q];
+            if (tid + q * nthreads < ng && col >= c0 && col < c1) tab[col - c0] = tid + q * nthreads;
+        }
+        for (int e = tid + TP * nthreads; e < ng; e += nthreads) {
+            const int col = active[sg0 + e];
+            if (col >= c0 && col < c1) tab[col - c0] = e;
+        }
+    }
     __syncthreads();
 
     // ---- the rows of this wavefront, one after the other ----
     const int lanepart = rowl * (R * 4);
     const char* const xb = reinterpret_cast<const char*>(lds) + lanepart;
-    float* const out = lds + out_off;
-    const int OS = NG | 1;                    // odd stride: conflict-free transposed writes
     auto walk_row = [&](int j, XT (&w)[KPRE], int (&i)[KPRE]) {
         float acc[R];
 #pragma unroll
@@ -189,33 +244,19 @@ __global__ __launch_bounds__(1024) void k_fwd_rowloop(const XT* __restrict__ x, 
         for (int row = wv_id; row < n_rows; row += nw) {
             float* yr = y + (size_t)(b0 + row) * d_out + sg0;
             for (int c = lane; c < ng; c += kWave) {
-                const float v = out[row * OS + c] + rl_bias_at(bias, sg0 + c);
+                const float v = out[row * OS + c] + bsp[c];
                 __builtin_nontemporal_store(act == SRIGL_ACT_NONE ? v : apply_act(v, act), &yr[c]);
             }
         }
         return;
     }
-    // With an active list the stored columns of the workgroup and the ablated ones between them are one run of consecutive
-    // columns of y, [c0, c1): the columns behind the previous group's last stored one up to this group's last (the last group
-    // also takes the ablated columns up to d_out).
-    const int c0 = sg0 > 0 ? min(max(active[sg0 - 1] + 1, 0), d_out) : 0;
-    const int c1 = (g == n_groups - 1) ? d_out : min(max(active[sg0 + ng - 1] + 1, c0), d_out);
-    const int span = c1 - c0;
-    if (span <= span_cap) {
-        // a table says which row of the result tile, if any, holds a column; lanes write the run left to right
-        int* const tab = reinterpret_cast<int*>(out + BT * OS);
-        for (int c = tid; c < span; c += blockDim.x) tab[c] = -1;
-        __syncthreads();
-        for (int j = tid; j < ng; j += blockDim.x) {
-            const int col = active[sg0 + j];
-            if (col >= c0 && col < c1) tab[col - c0] = j;
-        }
-        __syncthreads();
+    if (tabled) {
+        // lanes write the run left to right
         for (int row = wv_id; row < n_rows; row += nw) {
             float* yr = y + (size_t)(b0 + row) * d_out + c0;
             for (int c = lane; c < span; c += kWave) {
                 const int t = tab[c];
-                const float bv = rl_bias_at(bias, c0 + c);
+                const float bv = bsp[c];
                 const float v = t >= 0 ? out[row * OS + t] + bv : bv;
                 __builtin_nontemporal_store(act == SRIGL_ACT_NONE ? v : apply_act(v, act), &yr[c]);
             }
@@ -293,7 +334,7 @@ static RowloopPlan plan_rowloop(const FwdArgs& a, const srigl_fwd_tuning* t) {
     if (tile + (size_t)BT * (p.NW + 1) * sizeof(float) > kLdsMax) return p;
     const size_t rem = kLdsMax - tile;
     // rows per workgroup the result tile (and, with an active list, a column table of twice as many columns) has room for
-    const size_t per_row = (size_t)BT * sizeof(float) + (a.active ? 2 * sizeof(int) : 0);
+    const size_t per_row = (size_t)BT * sizeof(float) + (a.active ? 2 * (sizeof(int) + sizeof(float)) : sizeof(float));
     long long ng_max = (long long)(rem / per_row) - 2;
     if (ng_max < p.NW) return p;
     if (ng_max > 4096) ng_max = 4096;
@@ -335,10 +376,12 @@ static RowloopPlan plan_rowloop(const FwdArgs& a, const srigl_fwd_tuning* t) {
     }
     const int OS = p.NG | 1;
     p.out_off = (a.d_in + 1) * S;
-    const size_t used = tile + (size_t)BT * OS * sizeof(float);
+    // behind the result tile: the bias of the workgroup's columns; with an active list the bias and the column table of a run
+    // of up to span_cap columns
+    const size_t used = tile + (size_t)BT * OS * sizeof(float) + (a.active ? 0 : (size_t)p.NG * sizeof(float));
     if (used > kLdsMax) return p;
-    p.span_cap = a.active ? (int)std::min<size_t>((kLdsMax - used) / sizeof(int), 1u << 20) : 0;
-    p.lds = used + (size_t)p.span_cap * sizeof(int);
+    p.span_cap = a.active ? (int)std::min<size_t>((kLdsMax - used) / (sizeof(int) + sizeof(float)), 1u << 20) : 0;
+    p.lds = used + (size_t)p.span_cap * (sizeof(int) + sizeof(float));
     if (8LL * ((p.n_groups + 7) / 8) * ((p.n_btiles + 7) / 8 * 8) > 0x7fffffffLL) return p;
     p.ok = true;
     return p;
