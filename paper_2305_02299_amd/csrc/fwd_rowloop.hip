@@ -72,7 +72,8 @@ __global__ __launch_bounds__(1024) void k_fwd_rowloop(const XT* __restrict__ x, 
     // Terms.  Slice p of the lanes takes the p-th run of Q = ceil(K / H) consecutive terms of a row, 16 steps to a block: the
     // lane at position l16 of its 16-lane DPP row loads term p * Q + 16 * block + l16 (16 consecutive words per slice and
     // block) and that is also the term its DPP row broadcasts at step l16 of the block, so no cross-lane fetch is needed.
-    // D = 2 rows are in flight ahead of the one being walked (D buffers in turn; four measured no faster, from HBM or cached).
+    // D = 2 rows are in flight ahead of the one being walked (D buffers in turn; three and four measured 1-4 % slower, from HBM
+    // and cached, also once the waits for a row's terms were counted ones).
     const int Q = (K + H - 1) / H;
     const int slice = lane / LR, l16 = lane & (kBlock - 1);
     const int t_lane = slice * Q + l16;       // this lane's term of block 0, counted from the row's first term
@@ -199,8 +200,10 @@ __global__ __launch_bounds__(1024) void k_fwd_rowloop(const XT* __restrict__ x, 
         int po[KPRE];
 #pragma unroll
         for (int p = 0; p < KPRE; ++p) finish(w[p], i[p], p, pw[p], po[p]);
-        // the buffer is free: the row D rows on goes out now, with the arithmetic of D rows to return in
-        if (j + D * nw < ng) request_row(j + D * nw, w, i);
+        // the buffer is free: the row D rows on goes out now, with the arithmetic of D rows to return in (unconditional, as in
+        // the prologue: past the workgroup's last row the last one is read again and never walked; under a branch the wait
+        // for the next row's terms would become a wait for everything in flight, these included)
+        request_row(min(j + D * nw, ng - 1), w, i);
         walk_groups<R, KPRE, ROWLOOP_DEPTH>(acc, pw, po, xb, lanepart, Q);
         if (Q > KPRE * kBlock) {   // long rows: the remaining blocks, each requested one block ahead
             const unsigned base = (unsigned)(sg0 + j) * (unsigned)K + (unsigned)t_lane;
@@ -231,11 +234,14 @@ __global__ __launch_bounds__(1024) void k_fwd_rowloop(const XT* __restrict__ x, 
         }
         if (H == 2 || (lane & 16) == 0) out[(rowl * R + (lane >> 5)) * OS + j] = v;
     };
-    for (int j = wv_id; j < ng; j += D * nw) {
+    int j = wv_id;
+    for (; j + (D - 1) * nw < ng; j += D * nw) {   // whole turns of the D buffers: straight-line
 #pragma unroll
-        for (int d = 0; d < D; ++d)
-            if (j + d * nw < ng) walk_row(j + d * nw, rw[d], ri[d]);
+        for (int d = 0; d < D; ++d) walk_row(j + d * nw, rw[d], ri[d]);
     }
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d)                 // the rows of a last, partial turn
+        if (j + d * nw < ng) walk_row(j + d * nw, rw[d], ri[d]);
     __syncthreads();
 
     // ---- results: row-contiguous stores of the workgroup's run of columns ----
