@@ -390,20 +390,31 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         u_col[i] = (ct < col_tiles) ? ct * 16 : 0x40000000;   // units past the tile never pass the column tests below
     }
     Staged4<XT> st[kStageUnits];
-#define SRIGL_STAGE_LOAD_UNITS(c, u_first, u_last)                                                              \
+    // live: the chunk exists.  With six or eight stored rows per wavefront (UNC) the aligned form loads unconditionally: a
+    // unit past the tile, past d_in, or of a chunk that does not exist reads the tile's first 16 bytes instead and is never
+    // used, and the terms behind a row's last chunk are read (clamped into the arrays) and never used.  With loads under
+    // branches the compiler waits for every vector-memory operation in flight wherever it needs one of them: a stored row's
+    // terms, requested a chunk earlier, then also wait for the next chunk's activations requested a moment ago, six or eight
+    // times per chunk.  Measured (cold / cached): 4096->16384 bf16 at batch 2048 887 -> 806 us, 4096->4096 K = 41 at 1024
+    // 104 / 88 -> 85 / 74, K = 205 139 / 119 -> 120 / 110; with four rows per wavefront or fewer the spare loads cost more than
+    // the counted waits save (3072->768 at batch 64 11.9 -> 12.8), so those shapes keep the branches.
+    constexpr bool UNC = NPW >= 6;
+#define SRIGL_STAGE_LOAD_UNITS(live, c, u_first, u_last)                                                        \
     _Pragma("unroll") for (int u_ = 0; u_ < kStageUnits; ++u_) {                                                \
         const int c0_ = (c) * C;                                                                                \
         if (u_ >= (u_first) && u_ < (u_last)) {                                                                 \
             if (FAST) {                                                                                         \
-                if (c0_ + u_col[u_] < d_in) load4(reinterpret_cast<const XT*>(xtile + (g_off[u_] + (unsigned)c0_ * (unsigned)sizeof(XT))), true, 4, st[u_]); \
-            } else {                                                                                            \
+                const bool in_ = (live) && c0_ + u_col[u_] < d_in;                                              \
+                if (UNC) load4(reinterpret_cast<const XT*>(xtile + (in_ ? g_off[u_] + (unsigned)c0_ * (unsigned)sizeof(XT) : 0u)), true, 4, st[u_]); \
+                else if (in_) load4(reinterpret_cast<const XT*>(xtile + (g_off[u_] + (unsigned)c0_ * (unsigned)sizeof(XT))), true, 4, st[u_]); \
+            } else if (live) {                                                                                            \
                 st[u_].clear();                                                                                 \
                 const int nv = min(4, d_in - (c0_ + u_col[u_] + dq * 4));                                       \
                 if (u_col[u_] < C && nv > 0) load4(reinterpret_cast<const XT*>(xtile + (g_off[u_] + (unsigned)c0_ * (unsigned)sizeof(XT))), false, nv, st[u_]); \
             }                                                                                                   \
         }                                                                                                       \
     }
-#define SRIGL_STAGE_LOAD(c) SRIGL_STAGE_LOAD_UNITS(c, 0, kStageUnits)
+#define SRIGL_STAGE_LOAD(c) SRIGL_STAGE_LOAD_UNITS(true, c, 0, kStageUnits)
 #define SRIGL_STAGE_STORE()                                                                                     \
     _Pragma("unroll") for (int i = 0; i < kStageUnits; ++i) {                                                   \
         if (u_col[i] < C) {                                                                                     \
@@ -426,11 +437,13 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
     // ---- terms: the first KPRE blocks of every slot for one chunk live in registers ----
     XT rw[NPW][KPRE];    // raw words as loaded; finished into (weight, offset) right before use
     int ri[NPW][KPRE];
-#define SRIGL_PRELOAD(i, c)                                                                                     \
+#define SRIGL_PRELOAD(live, i, c)                                                                               \
     {                                                                                                           \
         const int k0_ = __builtin_amdgcn_readlane(bnd[i], (c) - cb);                                            \
-        _Pragma("unroll") for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)                                          \
-            request_terms<XT, IT, PKB>(W_c, idx, pk, slot_of(i) * KS + k0_ + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]); \
+        if (UNC || (live)) {                                                                                    \
+            _Pragma("unroll") for (int p = 0; p < (MERGE ? 1 : KPRE); ++p)                                      \
+                request_terms<XT, IT, PKB>(W_c, idx, pk, slot_of(i) * KS + k0_ + p * TB, MERGE ? lane : lofs, t_last, rw[i][p], ri[i][p]); \
+        }                                                                                                       \
     }
 
     float acc[NPW][R];
@@ -539,7 +552,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
         for (int i = 0; i < NPW; ++i) {
             // the next chunk's activations: a share of the staging loads goes out before each stored row's arithmetic,
             // so that the vector-memory queue never takes the whole burst at once
-            if (more) { SRIGL_STAGE_LOAD_UNITS(c + 1, (i * kStageUnits) / NPW, ((i + 1) * kStageUnits) / NPW) }
+            SRIGL_STAGE_LOAD_UNITS(more, c + 1, (i * kStageUnits) / NPW, ((i + 1) * kStageUnits) / NPW)
             const int n_terms = nn[i];
             if (n_terms > 0) {
                 float pw[KPRE];
@@ -564,7 +577,7 @@ __global__ __launch_bounds__(rowlane_max_threads(R)) void k_fwd_rowlane(const XT
                     }
                 }
             }
-            if (more) SRIGL_PRELOAD(i, c + 1)             // this slot's registers are free: request its next chunk
+            SRIGL_PRELOAD(more, i, c + 1)                 // this slot's registers are free: request its next chunk
         }
         if (more) {
             __syncthreads();                              // every wavefront is done reading chunk c
