@@ -814,13 +814,14 @@ static double chunked_or_small_estimate_us(const FwdArgs& a) {
 }
 // The whole-input batched kernel is taken where its estimate is ahead of that one's (5 % behind still counts: over the
 // 238 launches its estimate was fitted to, that threshold left the least time on the table, 0.9 % against 7.5 % without
-// this kernel); never against the staged few-lanes shape of the small-batch kernel, which was placed by measurement.
+// this kernel); below 32 batch rows never against the staged few-lanes shape of the small-batch kernel, which was placed by
+// measurement (at 32 rows this kernel measured ahead of it on rows of 77 terms, 6.1 / 5.4 against 7.5 / 6.4 us, and level on shorter ones).
 constexpr double kRowloopMargin = 0.95;
 srigl_fwd_algo choose_fwd_algo(const FwdArgs& a) {
     const srigl_fwd_algo base = choose_chunked_or_small(a);
     if (base == SRIGL_FWD_GENERIC || a.B < 2) return base;
     int few_L = 0, few_RB = 0;
-    if (base == SRIGL_FWD_KLANE && klane_few_lanes_staged(a.B, a.d_in, a.n_active, a.K, &few_L, &few_RB)) return base;
+    if (base == SRIGL_FWD_KLANE && a.B < 32 && klane_few_lanes_staged(a.B, a.d_in, a.n_active, a.K, &few_L, &few_RB)) return base;
     const double rl = rowloop_estimate_us(a);
     if (rl >= 1e29) return base;
     return rl * kRowloopMargin < chunked_or_small_estimate_us(a) ? SRIGL_FWD_ROWLOOP : base;

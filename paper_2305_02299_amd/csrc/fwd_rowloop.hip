@@ -308,17 +308,17 @@ static double rowloop_shape_us(const FwdArgs& a, const RowloopPlan& p) {
 }
 
 // Estimated time (us) of the shape the ranking above has taken, to compare this kernel with the others: the same terms,
-// with an extra one for the bytes of y, fitted (least squares of the relative error, standard deviation 5.4 %) to the mean of the
+// with an extra one for the bytes of y, fitted (least squares of the relative error, standard deviation 5.7 %) to the mean of the
 // cold and cached timings of 238 launches: 17 layers 256 to 1024 wide, fan-ins 8 to 231, up to 70 % of the neurons ablated,
 // at 14 batches from 16 to 4096.
 static double rowloop_compare_us(const FwdArgs& a, const RowloopPlan& p) {
     const int BT = kWave * 2 / p.H;
     const double rows_per_wave = (double)((p.NG + p.NW - 1) / p.NW);
     const double steps = (double)((a.K + p.H - 1) / p.H);
-    const double per_step = 0.0326 * p.NW / 16.0;
+    const double per_step = 0.0336 * p.NW / 16.0;
     const double terms = (double)a.n_active * a.K;
-    return 1.75 + p.rounds * (1.78 + 1.74e-5 * BT * a.d_in * 4.0 + rows_per_wave * (steps * per_step + 0.176) + 3.8e-5 * BT * p.NG) +
-           1.59e-6 * a.B * a.d_out + (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);
+    return 1.86 + p.rounds * (2.41 + 7.3e-6 * BT * a.d_in * 4.0 + rows_per_wave * (steps * per_step + 0.059)) +
+           1.75e-6 * a.B * a.d_out + (terms > 1.5e6 ? 0.29e-6 * terms : 0.0);
 }
 
 static RowloopPlan plan_rowloop(const FwdArgs& a, const srigl_fwd_tuning* t) {
