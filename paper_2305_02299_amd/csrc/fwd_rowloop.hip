@@ -17,9 +17,7 @@
 
 namespace srigl {
 
-#ifndef ROWLOOP_DEPTH
-#define ROWLOOP_DEPTH 2
-#endif
+constexpr int kRowloopReadAhead = 2;   // groups of LDS reads in flight ahead of the multiply-adds (walk_groups)
 struct RowloopPlan {
     int H, NW, NG, KPRE, n_btiles, n_groups, out_off, span_cap, bt_major;
     int rounds;
@@ -204,7 +202,7 @@ __global__ __launch_bounds__(1024) void k_fwd_rowloop(const XT* __restrict__ x, 
         // the prologue: past the workgroup's last row the last one is read again and never walked; under a branch the wait
         // for the next row's terms would become a wait for everything in flight, these included)
         request_row(min(j + D * nw, ng - 1), w, i);
-        walk_groups<R, KPRE, ROWLOOP_DEPTH>(acc, pw, po, xb, lanepart, Q);
+        walk_groups<R, KPRE, kRowloopReadAhead>(acc, pw, po, xb, lanepart, Q);
         if (Q > KPRE * kBlock) {   // long rows: the remaining blocks, each requested one block ahead
             const unsigned base = (unsigned)(sg0 + j) * (unsigned)K + (unsigned)t_lane;
             auto fetch = [&](int blk, XT& wr, int& ir) {
